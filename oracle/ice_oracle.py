@@ -1,0 +1,202 @@
+"""ctypes wrapper around the C oracle (oracle/ice_oracle.c).
+
+TEST INFRASTRUCTURE ONLY.  Imported by tests/, the smoke check and the benchmark's
+cpu_baseline leg; never by the product package.  It holds no arithmetic of its own:
+it allocates numpy arrays, passes their pointers to the C functions and hands the
+arrays back.  All state arrays carry a leading unit dimension U = batch * n_kv_heads.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+import subprocess
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "ice_oracle.c")
+_LIB = os.path.join(_HERE, "libice_oracle.so")
+
+
+def build(force: bool = False) -> str:
+    """Compile the oracle with gcc (no fused multiply-add, OpenMP over units)."""
+    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
+        subprocess.check_call(["gcc", "-O2", "-ffp-contract=off", "-fopenmp", "-fPIC", "-shared",
+                               "-o", _LIB, _SRC, "-lm"])
+    return _LIB
+
+
+class _State(C.Structure):
+    _fields_ = [(n, C.c_int32) for n in ("U", "d", "s", "C", "G", "max_pages", "max_tokens")] + \
+               [(n, C.c_void_p) for n in ("n_tokens", "n_pages", "Kp", "Vp", "page_cluster", "page_fill",
+                                          "page_pos", "cluster_tail", "cluster_cnt", "cluster_sum",
+                                          "centroid", "page_sum", "rep")]
+
+
+_lib = None
+
+
+def lib():
+    global _lib
+    if _lib is None:
+        _lib = C.CDLL(build())
+        _lib.orc_num_threads.restype = C.c_int
+        _lib.orc_insert.restype = C.c_int
+    return _lib
+
+
+def _p(a):
+    return None if a is None else a.ctypes.data_as(C.c_void_p)
+
+
+def num_threads() -> int:
+    return lib().orc_num_threads()
+
+
+def set_num_threads(t: int) -> None:
+    lib().orc_set_num_threads(C.c_int(t))
+
+
+def assign(K: np.ndarray, mu_bf16: np.ndarray):
+    """Exhaustive nearest centroid for one unit.  K uint16 [n,d], mu_bf16 uint16 [C,d].
+    Returns (a int32 [n], best float64 [n], second float64 [n])."""
+    n, d = K.shape
+    Cn = mu_bf16.shape[0]
+    K = np.ascontiguousarray(K, np.uint16)
+    mu_bf16 = np.ascontiguousarray(mu_bf16, np.uint16)
+    a = np.empty(n, np.int32)
+    best = np.empty(n, np.float64)
+    second = np.empty(n, np.float64)
+    lib().orc_assign(_p(K), _p(mu_bf16), C.c_int(n), C.c_int(Cn), C.c_int(d), _p(a), _p(best), _p(second))
+    return a, best, second
+
+
+def means(K: np.ndarray, a: np.ndarray, n_clusters: int, mu_prev: np.ndarray):
+    """Means of the members for one unit; empty clusters keep mu_prev.  Returns (mu, sum, cnt)."""
+    n, d = K.shape
+    K = np.ascontiguousarray(K, np.uint16)
+    a = np.ascontiguousarray(a, np.int32)
+    mu = np.array(mu_prev, np.float32, copy=True, order="C")
+    ssum = np.zeros((n_clusters, d), np.float32)
+    cnt = np.zeros(n_clusters, np.int32)
+    lib().orc_means(_p(K), _p(a), C.c_int(n), C.c_int(n_clusters), C.c_int(d), _p(mu), _p(ssum), _p(cnt))
+    return mu, ssum, cnt
+
+
+def lloyd(K: np.ndarray, init_idx: np.ndarray, T: int):
+    """T Lloyd rounds for one unit from the promoted keys.  Returns (a, mu, sum, cnt, inertia[T])."""
+    n, d = K.shape
+    Cn = init_idx.shape[0]
+    K = np.ascontiguousarray(K, np.uint16)
+    init_idx = np.ascontiguousarray(init_idx, np.int32)
+    a = np.empty(n, np.int32)
+    mu = np.empty((Cn, d), np.float32)
+    ssum = np.empty((Cn, d), np.float32)
+    cnt = np.empty(Cn, np.int32)
+    inertia = np.empty(T, np.float64)
+    lib().orc_lloyd(_p(K), C.c_int(n), C.c_int(Cn), C.c_int(d), _p(init_idx), C.c_int(T),
+                    _p(a), _p(mu), _p(ssum), _p(cnt), _p(inertia))
+    return a, mu, ssum, cnt, inertia
+
+
+class OracleIndex:
+    """One layer's index for U units, as plain numpy arrays filled by the C oracle."""
+
+    ARRAYS = ("n_tokens", "n_pages", "Kp", "Vp", "page_cluster", "page_fill", "page_pos",
+              "cluster_tail", "cluster_cnt", "cluster_sum", "centroid", "page_sum", "rep")
+
+    def __init__(self, U: int, group_size: int, page_size: int, n_clusters: int, max_tokens: int, d: int = 128):
+        self.U, self.G, self.s, self.C, self.d = U, group_size, page_size, n_clusters, d
+        self.max_tokens = max_tokens
+        self.max_pages = MP = max_tokens // page_size + n_clusters
+        s, Cn = page_size, n_clusters
+        self.n_tokens = np.zeros(U, np.int32)
+        self.n_pages = np.zeros(U, np.int32)
+        self.Kp = np.zeros((U, MP, s, d), np.uint16)
+        self.Vp = np.zeros((U, MP, s, d), np.uint16)
+        self.page_cluster = np.full((U, MP), -1, np.int32)
+        self.page_fill = np.zeros((U, MP), np.int32)
+        self.page_pos = np.full((U, MP, s), -1, np.int32)
+        self.cluster_tail = np.full((U, Cn), -1, np.int32)
+        self.cluster_cnt = np.zeros((U, Cn), np.int32)
+        self.cluster_sum = np.zeros((U, Cn, d), np.float32)
+        self.centroid = np.zeros((U, Cn, d), np.float32)
+        self.page_sum = np.zeros((U, MP, d), np.float32)
+        self.rep = np.zeros((U, MP, d), np.uint16)
+        self.assign = None
+
+    def _state(self) -> _State:
+        st = _State()
+        st.U, st.d, st.s, st.C, st.G = self.U, self.d, self.s, self.C, self.G
+        st.max_pages, st.max_tokens = self.max_pages, self.max_tokens
+        for name in self.ARRAYS:
+            arr = getattr(self, name)
+            assert arr.flags["C_CONTIGUOUS"]
+            setattr(st, name, arr.ctypes.data)
+        return st
+
+    def _units(self, x: np.ndarray, tail: tuple, dtype) -> np.ndarray:
+        x = np.ascontiguousarray(x, dtype).reshape((self.U,) + tail)
+        return x
+
+    def build(self, K: np.ndarray, V: np.ndarray, init_idx: np.ndarray, T: int):
+        """K, V uint16 [..., n, d] (leading dims flatten to U); init_idx int32 [..., C]."""
+        n = K.shape[-2]
+        K = self._units(K, (n, self.d), np.uint16)
+        V = self._units(V, (n, self.d), np.uint16)
+        init_idx = self._units(init_idx, (self.C,), np.int32)
+        self.assign = np.empty((self.U, n), np.int32)
+        inertia = np.empty((self.U, T), np.float64)
+        st = self._state()
+        lib().orc_build(C.byref(st), _p(K), _p(V), C.c_int(n), _p(init_idx), C.c_int(T),
+                        _p(self.assign), _p(inertia))
+        return inertia
+
+    def paginate(self, K: np.ndarray, V: np.ndarray, assign: np.ndarray):
+        """Lay pages out for a given assignment (int32 [U, n]); cluster means are not touched."""
+        n = K.shape[-2]
+        K = self._units(K, (n, self.d), np.uint16)
+        V = self._units(V, (n, self.d), np.uint16)
+        assign = self._units(assign, (n,), np.int32)
+        self.assign = assign.copy()
+        st = self._state()
+        lib().orc_paginate(C.byref(st), _p(K), _p(V), _p(assign), C.c_int(n))
+
+    def insert(self, k: np.ndarray, v: np.ndarray, force: np.ndarray | None = None):
+        """k, v uint16 [..., d].  Returns (chosen int32 [U], best float64 [U], second float64 [U])."""
+        k = self._units(k, (self.d,), np.uint16)
+        v = self._units(v, (self.d,), np.uint16)
+        if force is not None:
+            force = self._units(force, (), np.int32)
+        chosen = np.empty(self.U, np.int32)
+        best = np.empty(self.U, np.float64)
+        second = np.empty(self.U, np.float64)
+        st = self._state()
+        rc = lib().orc_insert(C.byref(st), _p(k), _p(v), _p(force), _p(chosen), _p(best), _p(second))
+        if rc != 0:
+            raise OverflowError("oracle insert: token capacity exceeded")
+        return chosen, best, second
+
+    def select(self, q: np.ndarray, token_budget: int):
+        """q uint16 [..., G, d] -> (ids int32 [U,P] ascending, -1 padded; n_sel [U]; scores [U,P];
+        S_all float32 [U, max_pages])."""
+        q = self._units(q, (self.G, self.d), np.uint16)
+        P = token_budget // self.s
+        ids = np.full((self.U, max(P, 1)), -1, np.int32)[:, :P].copy()
+        n_sel = np.zeros(self.U, np.int32)
+        scores = np.zeros((self.U, P), np.float32)
+        S_all = np.full((self.U, self.max_pages), -np.inf, np.float32)
+        st = self._state()
+        lib().orc_select(C.byref(st), _p(q), C.c_int(token_budget), _p(ids), _p(n_sel), _p(scores), _p(S_all))
+        return ids, n_sel, scores, S_all
+
+    def attend(self, q: np.ndarray, ids: np.ndarray, n_sel: np.ndarray) -> np.ndarray:
+        """Sparse attention over the listed pages: float32 [U, G, d]."""
+        q = self._units(q, (self.G, self.d), np.uint16)
+        P = ids.shape[-1]
+        ids = self._units(ids, (P,), np.int32)
+        n_sel = self._units(n_sel, (), np.int32)
+        out = np.zeros((self.U, self.G, self.d), np.float32)
+        st = self._state()
+        lib().orc_attend(C.byref(st), _p(q), _p(ids), _p(n_sel), C.c_int(P), _p(out))
+        return out

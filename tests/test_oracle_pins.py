@@ -1,0 +1,499 @@
+"""Pins for the CPU oracle: each test ties one oracle step to something that is not the oracle —
+numpy brute force over the direct definition, a hand-written example, a closed form, an
+invariant, or a library routine (torch SDPA).  CPU only."""
+import math
+
+import numpy as np
+import pytest
+
+import datagen
+from datagen import bf16_bits_to_f32 as widen, f32_to_bf16_bits as narrow
+from oracle import ice_oracle as orc
+
+D = 128
+
+
+def _rand_bits(rng, shape, scale=1.0):
+    return narrow((scale * rng.standard_normal(shape)).astype(np.float32))
+
+
+# ----------------------------------------------------------------------------- assign (Sec. 4.2)
+@pytest.mark.parametrize("n,C,seed", [(64, 8, 0), (37, 5, 1), (500, 24, 2), (1, 1, 3)])
+def test_assign_is_exhaustive_nearest_centroid(n, C, seed):
+    """argmin over the full n x C matrix of ||k - mu||^2 computed directly (not the expanded form)."""
+    rng = np.random.default_rng(seed)
+    K = _rand_bits(rng, (n, D))
+    mu = _rand_bits(rng, (C, D))
+    a, best, second = orc.assign(K, mu)
+    kf, mf = widen(K).astype(np.float64), widen(mu).astype(np.float64)
+    dist = ((kf[:, None, :] - mf[None, :, :]) ** 2).sum(-1)
+    assert np.array_equal(a, dist.argmin(1).astype(np.int32))
+    # the objective drops the key's own norm: best + ||k||^2 is the true squared distance
+    np.testing.assert_allclose(best + (kf ** 2).sum(1), dist.min(1), rtol=0, atol=1e-9)
+    if C > 1:
+        np.testing.assert_allclose(second + (kf ** 2).sum(1), np.sort(dist, 1)[:, 1], rtol=0, atol=1e-9)
+
+
+def test_assign_ties_take_lowest_index():
+    rng = np.random.default_rng(5)
+    K = _rand_bits(rng, (40, D))
+    mu = _rand_bits(rng, (3, D))
+    mu6 = np.concatenate([mu, mu])            # centroid c+3 duplicates centroid c
+    a, _, _ = orc.assign(K, mu6)
+    assert a.max() <= 2
+    a3, _, _ = orc.assign(K, mu)
+    assert np.array_equal(a, a3)
+
+
+def test_assign_key_equal_to_centroid_picks_it():
+    rng = np.random.default_rng(6)
+    mu = _rand_bits(rng, (16, D))
+    a, best, _ = orc.assign(mu.copy(), mu)
+    assert np.array_equal(a, np.arange(16))
+    np.testing.assert_allclose(best + (widen(mu).astype(np.float64) ** 2).sum(1), 0.0, atol=1e-9)
+
+
+# ----------------------------------------------------------------------------- means (Lloyd step)
+def test_means_match_numpy_scatter_add_and_empty_cluster_keeps_centroid():
+    rng = np.random.default_rng(7)
+    n, C = 300, 9
+    K = _rand_bits(rng, (n, D))
+    a = rng.integers(0, C - 1, n).astype(np.int32)      # cluster C-1 stays empty
+    prev = rng.standard_normal((C, D)).astype(np.float32)
+    mu, ssum, cnt = orc.means(K, a, C, prev)
+    acc = np.zeros((C, D))
+    np.add.at(acc, a, widen(K).astype(np.float64))
+    ref_cnt = np.bincount(a, minlength=C)
+    assert np.array_equal(cnt, ref_cnt)
+    np.testing.assert_allclose(ssum, acc, rtol=1e-6, atol=1e-6)
+    np.testing.assert_allclose(mu[:-1], acc[:-1] / ref_cnt[:-1, None], rtol=1e-6, atol=1e-6)
+    assert np.array_equal(mu[-1], prev[-1])
+
+
+# ----------------------------------------------------------------------------- Lloyd rounds
+def _inertia(K, mu, a):
+    kf = widen(K).astype(np.float64)
+    return float(((kf - mu.astype(np.float64)[a]) ** 2).sum())
+
+
+def test_lloyd_round1_is_nearest_promoted_key():
+    """Round 1 is the paper's two-level parent assignment: parent = nearest promoted key (Alg. 2)."""
+    w = datagen.small(n_tokens=400, n_clusters=12)
+    K, _ = datagen.keys_values(w)
+    idx = datagen.init_indices(w)
+    a, mu, ssum, cnt, _ = orc.lloyd(K[0, 0], idx[0, 0], 1)
+    kf = widen(K[0, 0]).astype(np.float64)
+    dist = ((kf[:, None, :] - kf[idx[0, 0]][None, :, :]) ** 2).sum(-1)
+    assert np.array_equal(a, dist.argmin(1))
+    assert np.array_equal(a[idx[0, 0]], np.arange(12))     # a promoted key is its own parent
+
+
+def test_lloyd_final_state_invariants_and_monotone_inertia():
+    w = datagen.small(n_tokens=800, n_clusters=20, n_components=10)
+    K, _ = datagen.keys_values(w)
+    idx = datagen.init_indices(w)
+    T = 6
+    a, mu, ssum, cnt, inertia = orc.lloyd(K[0, 1], idx[0, 1], T)
+    kf = widen(K[0, 1]).astype(np.float64)
+    # centroids are the means of the final assignment
+    for c in range(20):
+        m = a == c
+        assert cnt[c] == m.sum()
+        if m.any():
+            np.testing.assert_allclose(mu[c], kf[m].mean(0), rtol=1e-6, atol=1e-6)
+            np.testing.assert_allclose(ssum[c], kf[m].sum(0), rtol=1e-6, atol=1e-5)
+    assert cnt.sum() == 800
+    # k-means never increases the objective (up to the bf16 rounding of the centroids)
+    assert np.all(np.diff(inertia) <= 1e-3 * inertia[:-1])
+    assert inertia[-1] < inertia[0]
+    # the reported inertia is the objective seen by that round's assignment
+    a1, mu1, *_ = orc.lloyd(K[0, 1], idx[0, 1], 1)
+    mu0 = widen(narrow(widen(K[0, 1][idx[0, 1]])))
+    np.testing.assert_allclose(inertia[0], _inertia(K[0, 1], mu0, a1), rtol=1e-9)
+
+
+def test_lloyd_recovers_well_separated_components():
+    """Special case with a known answer: one promoted key per far-apart component."""
+    rng = np.random.default_rng(11)
+    M, per = 6, 30
+    cen = 20.0 * np.eye(M, D, dtype=np.float32)
+    lab = np.repeat(np.arange(M), per)
+    x = cen[lab] + 0.1 * rng.standard_normal((M * per, D)).astype(np.float32)
+    K = narrow(x)
+    init = np.arange(M, dtype=np.int32) * per
+    a, mu, _, cnt, _ = orc.lloyd(K, init, 3)
+    assert np.array_equal(a, lab)
+    assert np.all(cnt == per)
+    np.testing.assert_allclose(mu, cen, atol=0.1)
+
+
+def test_lloyd_equals_composed_steps():
+    w = datagen.small(n_tokens=300, n_clusters=7)
+    K, _ = datagen.keys_values(w)
+    idx = datagen.init_indices(w)
+    a, mu, ssum, cnt, _ = orc.lloyd(K[0, 0], idx[0, 0], 3)
+    m = widen(K[0, 0][idx[0, 0]]).copy()
+    for _ in range(3):
+        aa, _, _ = orc.assign(K[0, 0], narrow(m))
+        m, ss, cc = orc.means(K[0, 0], aa, 7, m)
+    assert np.array_equal(a, aa) and np.array_equal(mu, m) and np.array_equal(cnt, cc)
+
+
+# ----------------------------------------------------------------------------- pages (Sec. 4.1)
+def test_paginate_hand_example():
+    """n = 10, s = 4, C = 3, written out by hand."""
+    rng = np.random.default_rng(13)
+    K = _rand_bits(rng, (1, 10, D))
+    V = _rand_bits(rng, (1, 10, D))
+    a = np.array([[2, 0, 2, 2, 0, 2, 2, 0, 2, 2]], np.int32)   # cluster 1 is empty
+    ix = orc.OracleIndex(1, 1, 4, 3, max_tokens=16)
+    ix.paginate(K, V, a)
+    # cluster 0: tokens 1,4,7 -> page 0; cluster 2: tokens 0,2,3,5 -> page 1; 6,8,9 -> page 2
+    assert ix.n_pages[0] == 3 and ix.n_tokens[0] == 10
+    assert ix.page_cluster[0, :4].tolist() == [0, 2, 2, -1]
+    assert ix.page_fill[0, :4].tolist() == [3, 4, 3, 0]
+    assert ix.page_pos[0, :3].tolist() == [[1, 4, 7, -1], [0, 2, 3, 5], [6, 8, 9, -1]]
+    assert ix.cluster_tail[0].tolist() == [0, -1, 2]
+    assert np.array_equal(ix.Kp[0, 1, 2], K[0, 3]) and np.array_equal(ix.Vp[0, 2, 0], V[0, 6])
+    # representative of page 0 = mean of keys 1,4,7 up to bf16 rounding
+    mean = widen(K[0, [1, 4, 7]]).astype(np.float64).mean(0)
+    got = widen(ix.rep[0, 0]).astype(np.float64)
+    assert np.all(np.abs(got - mean) <= np.abs(mean) * 2.0 ** -8 + 1e-30)
+    s3 = widen(K[0, 1]) + widen(K[0, 4])
+    s3 = s3 + widen(K[0, 7])
+    assert np.array_equal(ix.page_sum[0, 0], s3)               # slot order, fp32
+
+
+def _check_invariants(ix, K_all, V_all, assign_all):
+    """I1-I4, I6 on an OracleIndex; K_all/V_all [U, n, d], assign_all [U, n]."""
+    for u in range(ix.U):
+        n, npg = int(ix.n_tokens[u]), int(ix.n_pages[u])
+        fill = ix.page_fill[u, :npg]
+        assert fill.sum() == n and fill.min() >= 1 and fill.max() <= ix.s            # I2
+        pos = ix.page_pos[u, :npg]
+        valid = np.arange(ix.s)[None, :] < fill[:, None]
+        assert np.array_equal(np.sort(pos[valid]), np.arange(n))                      # I1
+        assert np.all(pos[~valid] == -1)
+        for c in range(ix.C):
+            pages = np.nonzero(ix.page_cluster[u, :npg] == c)[0]
+            partial = pages[fill[pages] < ix.s]
+            assert len(partial) <= 1                                                  # I3
+            if len(pages):
+                assert ix.cluster_tail[u, c] == pages.max()
+                if len(partial):
+                    assert partial[0] == pages.max()
+            else:
+                assert ix.cluster_tail[u, c] == -1
+        pc = np.repeat(ix.page_cluster[u, :npg], ix.s).reshape(npg, ix.s)
+        assert np.array_equal(assign_all[u][pos[valid]], pc[valid])                   # I4
+        assert np.array_equal(ix.Kp[u, :npg][valid], K_all[u][pos[valid]])            # I6
+        assert np.array_equal(ix.Vp[u, :npg][valid], V_all[u][pos[valid]])
+
+
+def test_paginate_invariants_random():
+    w = datagen.small(n_tokens=777, n_clusters=19, n_kv_heads=3)
+    K, V = datagen.keys_values(w)
+    rng = np.random.default_rng(17)
+    a = rng.integers(0, 19, (3, 777)).astype(np.int32)
+    ix = orc.OracleIndex(3, 4, 16, 19, max_tokens=800)
+    ix.paginate(K[0], V[0], a)
+    _check_invariants(ix, K[0], V[0], a)
+    # within a cluster tokens appear in ascending position and pages are consecutive
+    for u in range(3):
+        npg = ix.n_pages[u]
+        assert np.all(np.diff(ix.page_cluster[u, :npg]) >= 0)
+        for c in range(19):
+            pages = np.nonzero(ix.page_cluster[u, :npg] == c)[0]
+            seq = [p for pg in pages for p in ix.page_pos[u, pg] if p >= 0]
+            assert seq == sorted(seq) and seq == np.nonzero(a[u] == c)[0].tolist()
+
+
+def test_representative_of_identical_keys_is_the_key():
+    """fill copies of one bf16 vector: the fp32 sum and the divide are exact, so rep == key bits."""
+    rng = np.random.default_rng(19)
+    key = _rand_bits(rng, (D,))
+    for fill in (1, 2, 5, 16):
+        K = np.tile(key, (1, fill, 1))
+        ix = orc.OracleIndex(1, 1, 16, 1, max_tokens=16)
+        ix.paginate(K, K, np.zeros((1, fill), np.int32))
+        assert np.array_equal(ix.rep[0, 0], key)
+        np.testing.assert_array_equal(ix.page_sum[0, 0], fill * widen(key))
+
+
+def test_representative_is_rounded_mean():
+    rng = np.random.default_rng(23)
+    K = _rand_bits(rng, (1, 16 * 5, D))
+    ix = orc.OracleIndex(1, 1, 16, 1, max_tokens=80)
+    ix.paginate(K, K, np.zeros((1, 80), np.int32))
+    mean = widen(K[0]).astype(np.float64).reshape(5, 16, D).mean(1)
+    got = widen(ix.rep[0, :5]).astype(np.float64)
+    # fp32 sum of 16 terms then one bf16 rounding: half a bf16 ulp (<= 2^-8 relative) plus the sum error
+    assert np.all(np.abs(got - mean) <= np.abs(mean) * 2.0 ** -8 + 1e-5)
+
+
+# ----------------------------------------------------------------------------- insert (Alg. 1, Sec. 4.2)
+def test_insert_follows_nearest_centroid_and_keeps_invariants():
+    w = datagen.small(n_tokens=640, n_clusters=10, n_kv_heads=2, n_components=8)
+    K, V = datagen.keys_values(w, n_tokens=700)
+    idx = datagen.init_indices(w, n_tokens=600)
+    ix = orc.OracleIndex(2, 4, 16, 10, max_tokens=700)
+    ix.build(K[0, :, :600], V[0, :, :600], idx[0], 4)
+    assign = [ix.assign[u].tolist() for u in range(2)]
+    for t in range(600, 700):
+        mub = narrow(ix.centroid)                         # centroids as seen by this insertion
+        pages_before = ix.n_pages.copy()
+        tails = ix.cluster_tail.copy()
+        fills = ix.page_fill.copy()
+        chosen, best, second = ix.insert(K[0, :, t], V[0, :, t])
+        for u in range(2):
+            kf = widen(K[0, u, t]).astype(np.float64)
+            dist = ((kf[None, :] - widen(mub[u]).astype(np.float64)) ** 2).sum(-1)
+            assert chosen[u] == dist.argmin()
+            c = int(chosen[u])
+            assign[u].append(c)
+            old_tail = tails[u, c]
+            if old_tail < 0 or fills[u, old_tail] == 16:   # node outgrew its page: a new page
+                assert ix.n_pages[u] == pages_before[u] + 1
+                assert ix.cluster_tail[u, c] == pages_before[u]
+                assert ix.page_fill[u, pages_before[u]] == 1
+            else:
+                assert ix.n_pages[u] == pages_before[u]
+                assert ix.page_fill[u, old_tail] == fills[u, old_tail] + 1
+    a = np.array(assign, np.int32)
+    _check_invariants(ix, K[0], V[0], a)
+    kf = widen(K[0]).astype(np.float64)
+    for u in range(2):
+        for c in range(10):
+            m = a[u] == c
+            assert ix.cluster_cnt[u, c] == m.sum()
+            if m.any():                                    # running mean == true mean (I5)
+                np.testing.assert_allclose(ix.centroid[u, c], kf[u][m].mean(0), rtol=1e-5, atol=1e-5)
+    # representatives stay the rounded mean of their page
+    for u in range(2):
+        for p in range(ix.n_pages[u]):
+            f = ix.page_fill[u, p]
+            mean = widen(ix.Kp[u, p, :f]).astype(np.float64).mean(0)
+            got = widen(ix.rep[u, p]).astype(np.float64)
+            assert np.all(np.abs(got - mean) <= np.abs(mean) * 2.0 ** -8 + 1e-5)
+
+
+def test_insert_into_empty_cluster_and_capacity():
+    rng = np.random.default_rng(29)
+    K = _rand_bits(rng, (1, 8, D))
+    ix = orc.OracleIndex(1, 1, 4, 2, max_tokens=9)
+    ix.paginate(K, K, np.zeros((1, 8), np.int32))          # cluster 1 owns nothing
+    ix.centroid[0, 0] = widen(K[0]).mean(0)
+    ix.cluster_cnt[0] = [8, 0]
+    far = narrow(np.full(D, 50.0, np.float32))
+    ix.centroid[0, 1] = widen(far)
+    chosen, _, _ = ix.insert(far[None], far[None])
+    assert chosen[0] == 1 and ix.n_pages[0] == 3 and ix.cluster_tail[0, 1] == 2
+    assert ix.page_pos[0, 2, 0] == 8 and ix.page_fill[0, 2] == 1
+    assert np.array_equal(ix.rep[0, 2], far) and ix.cluster_cnt[0, 1] == 1
+    with pytest.raises(OverflowError):
+        ix.insert(far[None], far[None])
+
+
+def test_insert_force_overrides_choice():
+    rng = np.random.default_rng(31)
+    K = _rand_bits(rng, (1, 8, D))
+    ix = orc.OracleIndex(1, 1, 4, 2, max_tokens=16)
+    ix.paginate(K, K, (np.arange(8) % 2)[None].astype(np.int32))
+    ix.centroid[0] = 0
+    chosen, _, _ = ix.insert(K[0, :1], K[0, :1], force=np.array([1], np.int32))
+    assert chosen[0] == 1 and ix.page_cluster[0, ix.n_pages[0] - 1] == 1
+
+
+# ----------------------------------------------------------------------------- select (Sec. 4.4, Alg. 3)
+def _built(w, T=3, max_extra=0):
+    K, V = datagen.keys_values(w)
+    idx = datagen.init_indices(w)
+    U = w.batch * w.n_kv_heads
+    ix = orc.OracleIndex(U, w.group_size, w.page_size, w.n_clusters, max_tokens=w.n_tokens + max_extra)
+    ix.build(K, V, idx, T)
+    return ix, K.reshape(U, w.n_tokens, D), V.reshape(U, w.n_tokens, D)
+
+
+def _scores_numpy(ix, q):
+    qf = widen(q).astype(np.float64)                       # [U, G, d]
+    out = []
+    for u in range(ix.U):
+        r = widen(ix.rep[u, :ix.n_pages[u]]).astype(np.float64)
+        sc = (r @ qf[u].T) / np.linalg.norm(qf[u], axis=1)[None, :]
+        out.append(sc.max(1).astype(np.float32))
+    return out
+
+
+@pytest.mark.parametrize("budget", [16, 128, 256])
+def test_select_is_full_sort(budget):
+    w = datagen.small(n_tokens=1500, n_clusters=24, n_kv_heads=3)
+    ix, _, _ = _built(w)
+    q = datagen.queries(w).reshape(ix.U, w.group_size, D)
+    ids, n_sel, scores, S_all = ix.select(q, budget)
+    P = budget // 16
+    S = _scores_numpy(ix, q)
+    for u in range(ix.U):
+        npg = int(ix.n_pages[u])
+        np.testing.assert_allclose(S_all[u, :npg], S[u], rtol=2e-7, atol=1e-7)
+        order = sorted(range(npg), key=lambda p: (-S_all[u, p], p))
+        want = sorted(order[:min(P, npg)])
+        assert n_sel[u] == len(want)
+        assert ids[u, :len(want)].tolist() == want
+        assert np.all(ids[u, len(want):] == -1)
+        assert np.array_equal(scores[u, :len(want)], S_all[u, want])
+        assert ix.page_fill[u, want].sum() <= budget       # loaded keys <= pages x page size
+
+
+def test_select_budget_covering_everything_returns_every_page():
+    w = datagen.small(n_tokens=300, n_clusters=6)
+    ix, _, _ = _built(w)
+    q = datagen.queries(w).reshape(ix.U, w.group_size, D)
+    ids, n_sel, _, _ = ix.select(q, 16 * 64)
+    for u in range(ix.U):
+        assert n_sel[u] == ix.n_pages[u]
+        assert ids[u, :n_sel[u]].tolist() == list(range(ix.n_pages[u]))
+
+
+def test_select_ties_take_lowest_page_id():
+    rng = np.random.default_rng(37)
+    key = _rand_bits(rng, (D,))
+    K = np.tile(key, (1, 64, 1))                           # 4 identical pages
+    ix = orc.OracleIndex(1, 2, 16, 1, max_tokens=64)
+    ix.paginate(K, K, np.zeros((1, 64), np.int32))
+    q = _rand_bits(rng, (1, 2, D))
+    ids, n_sel, _, _ = ix.select(q, 32)
+    assert n_sel[0] == 2 and ids[0].tolist() == [0, 1]
+
+
+def test_select_single_token_pages_rank_like_the_transformed_euclidean_search():
+    """With one key per page the representative is the key, and ranking by q.k/||q|| must equal
+    ranking by Euclidean distance between T_K(k) and T_Q(q) (Eqs. 2-3):
+    ||T_K(k) - T_Q(q)||^2 = 2 - 2 q.k / (c ||q||)."""
+    rng = np.random.default_rng(41)
+    n = 48
+    K = _rand_bits(rng, (1, n, D))
+    ix = orc.OracleIndex(1, 1, 16, n, max_tokens=n)
+    ix.paginate(K, K, np.arange(n, dtype=np.int32)[None])  # every token its own node
+    q = _rand_bits(rng, (1, 1, D))
+    ids, n_sel, _, _ = ix.select(q, 16 * 5)
+    kf, qf = widen(K[0]).astype(np.float64), widen(q[0, 0]).astype(np.float64)
+    c = np.linalg.norm(kf, axis=1).max() * 1.01
+    TK = np.concatenate([kf / c, np.sqrt(1 - (kf ** 2).sum(1) / c ** 2)[:, None]], 1)
+    TQ = np.concatenate([qf / np.linalg.norm(qf), [0.0]])
+    dist = ((TK - TQ[None]) ** 2).sum(1)
+    np.testing.assert_allclose(dist, 2 - 2 * (kf @ qf) / (c * np.linalg.norm(qf)), atol=1e-12)
+    assert ids[0].tolist() == sorted(np.argsort(dist)[:5].tolist())
+
+
+def test_select_group_score_is_max_over_heads():
+    """A page that only one query head of the group likes is still selected (GQA sharing, Sec. 4.3)."""
+    e = np.zeros((3, D), np.float32)
+    e[0, 0] = e[1, 1] = e[2, 2] = 4.0
+    K = narrow(np.repeat(e, 16, axis=0))[None]             # three pages along three axes
+    ix = orc.OracleIndex(1, 2, 16, 3, max_tokens=48)
+    ix.paginate(K, K, np.repeat(np.arange(3), 16)[None].astype(np.int32))
+    qv = np.zeros((1, 2, D), np.float32)
+    qv[0, 0, 0] = 1.0
+    qv[0, 0, 2] = 0.5
+    qv[0, 1, 1] = 100.0                                    # a long query must not dominate: scores are normalised
+    qv[0, 1, 2] = 60.0
+    ids, n_sel, scores, S_all = ix.select(narrow(qv), 32)
+    # head 0 scores (4/|q0|, 0, 2/|q0|) = (3.578, 0, 1.789); head 1 scores (0, 3.43, 2.058)
+    assert ids[0].tolist() == [0, 1]
+    np.testing.assert_allclose(S_all[0, :3], [4 / math.hypot(1, .5), 400 / math.hypot(100, 60),
+                                              240 / math.hypot(100, 60)], rtol=1e-6)
+
+
+# ----------------------------------------------------------------------------- attend (Eq. 1)
+def _dense_attention(q, K, V):
+    """Textbook softmax attention, fp64: q [G,d], K,V [n,d]."""
+    z = (q @ K.T) / math.sqrt(q.shape[-1])
+    z = z - z.max(1, keepdims=True)
+    p = np.exp(z)
+    return (p / p.sum(1, keepdims=True)) @ V
+
+
+def test_attend_with_every_page_equals_dense_attention():
+    w = datagen.small(n_tokens=900, n_clusters=12, n_kv_heads=2)
+    ix, K, V = _built(w)
+    q = datagen.queries(w).reshape(ix.U, w.group_size, D)
+    ids, n_sel, _, _ = ix.select(q, 16 * 128)
+    out = ix.attend(q, ids, n_sel)
+    import torch
+    for u in range(ix.U):
+        ref = _dense_attention(widen(q[u]).astype(np.float64), widen(K[u]).astype(np.float64),
+                               widen(V[u]).astype(np.float64))
+        np.testing.assert_allclose(out[u], ref, rtol=0, atol=2e-7 * max(1.0, np.abs(ref).max()))
+        tq = torch.from_numpy(widen(q[u]).copy())[None]
+        sd = torch.nn.functional.scaled_dot_product_attention(
+            tq, torch.from_numpy(widen(K[u]).copy())[None], torch.from_numpy(widen(V[u]).copy())[None])
+        np.testing.assert_allclose(out[u], sd[0].numpy(), rtol=0, atol=2e-5)
+
+
+def test_attend_subset_equals_dense_attention_over_that_subset():
+    w = datagen.small(n_tokens=900, n_clusters=12, n_kv_heads=2)
+    ix, K, V = _built(w)
+    q = datagen.queries(w).reshape(ix.U, w.group_size, D)
+    ids, n_sel, _, _ = ix.select(q, 64)
+    out = ix.attend(q, ids, n_sel)
+    for u in range(ix.U):
+        pos = np.concatenate([ix.page_pos[u, p, :ix.page_fill[u, p]] for p in ids[u, :n_sel[u]]])
+        ref = _dense_attention(widen(q[u]).astype(np.float64), widen(K[u][pos]).astype(np.float64),
+                               widen(V[u][pos]).astype(np.float64))
+        np.testing.assert_allclose(out[u], ref, rtol=0, atol=2e-7 * max(1.0, np.abs(ref).max()))
+        # the order in which the pages are listed does not matter
+        perm = ids[u, :n_sel[u]][::-1].copy()
+        ids2 = ids.copy()
+        ids2[u, :n_sel[u]] = perm
+        np.testing.assert_allclose(ix.attend(q, ids2, n_sel)[u], out[u], rtol=0, atol=1e-6)
+
+
+def test_attend_closed_forms():
+    rng = np.random.default_rng(43)
+    key = _rand_bits(rng, (D,))
+    V = _rand_bits(rng, (1, 40, D))
+    K = np.tile(key, (1, 40, 1))
+    ix = orc.OracleIndex(1, 3, 16, 1, max_tokens=40)
+    ix.paginate(K, V, np.zeros((1, 40), np.int32))
+    q = _rand_bits(rng, (1, 3, D))
+    # all keys equal -> uniform weights -> mean of the values
+    out = ix.attend(q, np.array([[0, 1, 2]], np.int32), np.array([3], np.int32))
+    np.testing.assert_allclose(out[0], np.tile(widen(V[0]).astype(np.float64).mean(0), (3, 1)), atol=1e-6)
+    # one page holding the ragged tail (8 tokens)
+    out = ix.attend(q, np.array([[2, -1, -1]], np.int32), np.array([1], np.int32))
+    np.testing.assert_allclose(out[0], np.tile(widen(V[0, 32:]).astype(np.float64).mean(0), (3, 1)), atol=1e-6)
+    # nothing selected -> zeros
+    out = ix.attend(q, np.array([[-1, -1, -1]], np.int32), np.array([0], np.int32))
+    assert np.all(out == 0)
+    # one page with one token -> that token's value
+    ix1 = orc.OracleIndex(1, 3, 16, 1, max_tokens=16)
+    ix1.paginate(K[:, :1], V[:, :1], np.zeros((1, 1), np.int32))
+    out = ix1.attend(q, np.array([[0]], np.int32), np.array([1], np.int32))
+    np.testing.assert_array_equal(out[0], np.tile(widen(V[0, 0]), (3, 1)))
+
+
+def test_attend_two_tokens_is_a_sigmoid_of_the_scaled_logit_gap():
+    """Pins the 1/sqrt(d) scale: weights of two keys are sigmoid(+-(q.k1 - q.k2)/sqrt(d))."""
+    k = np.zeros((2, D), np.float32)
+    k[0, 0], k[1, 0] = 3.0, -1.0
+    v = np.zeros((2, D), np.float32)
+    v[0, 5], v[1, 5] = 1.0, 0.0
+    ix = orc.OracleIndex(1, 1, 16, 1, max_tokens=16)
+    ix.paginate(narrow(k)[None], narrow(v)[None], np.zeros((1, 2), np.int32))
+    q = np.zeros((1, 1, D), np.float32)
+    q[0, 0, 0] = 2.0
+    out = ix.attend(narrow(q), np.array([[0]], np.int32), np.array([1], np.int32))
+    gap = (2.0 * 3.0 - 2.0 * (-1.0)) / math.sqrt(D)
+    assert abs(out[0, 0, 5] - 1.0 / (1.0 + math.exp(-gap))) < 1e-7
+
+
+# ----------------------------------------------------------------------------- input recipe sanity
+def test_bf16_rounding_is_nearest_even():
+    x = np.array([1.0, 1.00390625, 1.01171875, 1.0 + 2.0 ** -9, -2.5, 3.0e38], np.float32)
+    got = widen(narrow(x))
+    # 1 + 2^-8 lies halfway between 1 and 1 + 2^-7 -> even (1.0); 1 + 3*2^-8 -> 1 + 2^-6 (even)
+    assert got.tolist()[:5] == [1.0, 1.0, 1.015625, 1.0, -2.5]
+    import torch
+    y = np.random.default_rng(1).standard_normal(10000).astype(np.float32)
+    ref = torch.from_numpy(y).to(torch.bfloat16).float().numpy()
+    assert np.array_equal(widen(narrow(y)), ref)
