@@ -1,0 +1,168 @@
+/*
+ * icecache.h - C ABI of the MI355X (gfx950) implementation of the IceCache hot path.
+ *
+ * One ice_index_t holds one attention layer's clustered, paged KV cache for
+ * U = batch * n_kv_heads independent units (one unit = one (sequence, KV head) pair; the
+ * paper keeps one index per head, Sec. 4.1).  Keys with similar embeddings share a page
+ * (Sec. 4.1); a decode query scores one representative per page, picks the best pages under a
+ * token budget (Sec. 4.3-4.4, Alg. 3) and attends only to the tokens in them (Eq. 1).
+ *
+ * Conventions
+ *   Pointers  Every tensor pointer is a DEVICE pointer owned by the caller, 16-byte aligned,
+ *             contiguous and row-major as annotated.  bf16 = upper 16 bits of an IEEE fp32.
+ *             The only host pointers are ice_config_t*, ice_index_view_t* and ice_index_t**.
+ *   Memory    The library never allocates device memory.  The caller passes one workspace of
+ *             ice_workspace_bytes() bytes (256-byte aligned) to ice_create(); page pools,
+ *             tables, representatives, centroids and scratch all live inside it.
+ *             ice_build_index COPIES K and V into page tiles; the originals may be freed.
+ *   Streams   `stream` is a hipStream_t (NULL = default stream).  Every call only enqueues
+ *             work; no call synchronises or reads device memory on the host.  Calls on one
+ *             index must be issued in order on one stream (or be ordered by the caller).
+ *   Errors    Every call returns an ice_status_t and never throws or aborts.  All errors are
+ *             detected on the host from the arguments and host-side counters BEFORE anything is
+ *             enqueued; ice_last_error() returns a thread-local description of the last failure.
+ *   Units     unit u = b * n_kv_heads + h_kv; query head h_q belongs to KV head
+ *             h_q / group_size.  Page ids are local to a unit: 0 <= id < n_pages[u].
+ */
+#ifndef ICECACHE_H
+#define ICECACHE_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct ice_index ice_index_t;
+
+typedef enum {
+    ICE_OK = 0,
+    ICE_ERR_INVALID_ARG = 1, /* null or misaligned pointer, non-positive size                  */
+    ICE_ERR_SHAPE = 2,       /* sizes inconsistent with each other or with the configuration   */
+    ICE_ERR_STATE = 3,       /* call made before ice_build_index / ice_import_index            */
+    ICE_ERR_CAPACITY = 4,    /* would exceed max_tokens, or the workspace is too small         */
+    ICE_ERR_UNSUPPORTED = 5, /* head_dim != 128, page_size not in {16,32,64}, group_size not in
+                                {1,2,4,8}                                                       */
+    ICE_ERR_DEVICE = 6       /* a HIP call failed (text in ice_last_error)                      */
+} ice_status_t;
+
+typedef struct {
+    int32_t batch;        /* B  >= 1                                                            */
+    int32_t n_kv_heads;   /* H_kv >= 1                                                          */
+    int32_t group_size;   /* G = query heads per KV head (GQA, Sec. 4.3): 1, 2, 4 or 8          */
+    int32_t head_dim;     /* d: 128 only                                                        */
+    int32_t max_tokens;   /* per unit: prefill tokens plus every later ice_insert               */
+    int32_t kmeans_iters; /* T >= 1 Lloyd rounds, fixed count (no convergence test)             */
+    uint64_t seed;        /* selects the promoted keys when init_idx is NULL                    */
+    const int32_t *init_idx; /* optional DEVICE int32 [B,H_kv,n_clusters]: token index of each
+                                promoted key (the initial centroids, Alg. 2 "random promotion");
+                                entries should be distinct; read during ice_build_index         */
+} ice_config_t;
+
+/* Device-pointer view of an index (export) or of caller arrays to copy in (import).
+ * Per-unit arrays are laid out [U][...] with the element strides given below.
+ *   Kp, Vp        bf16  [U][max_pages][page_size][d]   page tiles (4 KiB each at page_size 16)
+ *   page_cluster  int32 [U][max_pages]                 owning cluster, -1 for unused pages
+ *   page_fill     int32 [U][max_pages]                 tokens in the page, 0..page_size
+ *   page_pos      int32 [U][max_pages][page_size]      original token position, -1 = empty slot
+ *   cluster_tail  int32 [U][n_clusters]                last page of the cluster or -1
+ *   cluster_cnt   int32 [U][n_clusters]
+ *   cluster_sum   fp32  [U][n_clusters][d]
+ *   centroid      fp32  [U][n_clusters][d]
+ *   page_sum      fp32  [U][max_pages][d]              slot-ordered fp32 sum of the page's keys
+ *   rep           bf16  [U][max_pages][d]              representative = bf16(page_sum / fill)
+ *   n_pages       int32 [U]                            live pages per unit
+ *   assign        int32 [U][max_tokens]  (export only) cluster of every prefill token after the
+ *                                                      last Lloyd round
+ *   assign_centroid_bf16 bf16 [U][cpad][d] (export only) the bf16 centroids that `assign` was
+ *                                                      computed against (cpad = n_clusters
+ *                                                      rounded up to 32)
+ *   init_idx      int32 [U][n_clusters]  (export only) promoted token indices actually used
+ */
+typedef struct {
+    int32_t n_units, group_size, head_dim, page_size, n_clusters, cpad;
+    int32_t max_pages;   /* floor(max_tokens / page_size) + n_clusters                          */
+    int32_t max_tokens;
+    int32_t n_tokens;    /* tokens per unit so far (host-side counter; equal for all units)     */
+    int32_t reserved;
+    void *Kp, *Vp;
+    int32_t *page_cluster, *page_fill, *page_pos, *cluster_tail, *cluster_cnt;
+    float *cluster_sum, *centroid, *page_sum;
+    void *rep;
+    int32_t *n_pages;
+    int32_t *assign;
+    void *assign_centroid_bf16;
+    int32_t *init_idx;
+} ice_index_view_t;
+
+/* Bytes of device workspace an index with this configuration needs.  0 on invalid arguments. */
+size_t ice_workspace_bytes(const ice_config_t *cfg, int32_t page_size, int32_t n_clusters);
+
+/* Creates the host-side object over a caller-owned device workspace (not touched here).
+ * The workspace must stay alive until ice_destroy.  cfg is copied (init_idx pointer included). */
+ice_status_t ice_create(const ice_config_t *cfg, void *workspace, size_t workspace_bytes,
+                        ice_index_t **out);
+/* Frees the host-side object only. */
+ice_status_t ice_destroy(ice_index_t *idx);
+
+/* Index build at prefill (Sec. 4.1-4.2, Alg. 2 restricted to two levels, iterated):
+ * n_clusters keys per unit are promoted to initial centroids; kmeans_iters rounds of
+ * (nearest centroid by squared Euclidean distance on bf16 centroids, lowest id on ties ->
+ * member means); each cluster's tokens, in ascending position, are cut into pages of page_size
+ * (a node owns a list of pages, Sec. 4.1); every page gets a representative (mean key).
+ *   K, V: bf16 [B, H_kv, n_tokens, d].
+ * Errors: SHAPE if n_clusters > n_tokens or n_tokens > max_tokens; UNSUPPORTED page_size;
+ * CAPACITY if the workspace is too small for (page_size, n_clusters).  Rebuilding is allowed. */
+ice_status_t ice_build_index(ice_index_t *idx, const void *K, const void *V, int32_t n_tokens,
+                             int32_t page_size, int32_t n_clusters, void *stream);
+
+/* Inserts one decode token per unit (Sec. 4.2 last paragraph, Alg. 1 insertion loop): nearest
+ * centroid, append to that cluster's tail page (a new page when it is full or absent, Sec. 4.1),
+ * update the page representative and the cluster's running mean.
+ *   k, v: bf16 [B, H_kv, d].   CAPACITY when n_tokens == max_tokens; STATE before a build. */
+ice_status_t ice_insert(ice_index_t *idx, const void *k, const void *v, void *stream);
+
+/* Page selection for one decode query (Sec. 4.3-4.4, Alg. 3): P = floor(token_budget/page_size);
+ * score(p) = max over the G query heads of (q_h . rep_p) / ||q_h||; the min(P, n_pages) best
+ * pages by (score descending, id ascending) are returned with ids ascending, padded with -1.
+ *   q: bf16 [B, H_q, d];  page_ids: int32 [B, H_kv, P];  n_selected: int32 [B, H_kv];
+ *   scores_or_null: fp32 [B, H_kv, P] group score of each returned page (0 in the padding).
+ * SHAPE if token_budget < page_size. */
+ice_status_t ice_select(ice_index_t *idx, const void *q, int32_t token_budget, int32_t *page_ids,
+                        int32_t *n_selected, float *scores_or_null, void *stream);
+
+/* Sparse attention over the listed pages (Eq. 1 with the mask set on the tokens of those
+ * pages): softmax(q_h . k / sqrt(d)) . v over every filled slot, fp32 accumulation and output.
+ *   page_ids: int32 [B, H_kv, P] with P = n_ids_per_unit; the first n_selected[u] entries of
+ *   each row are used and must be distinct live page ids;  out: fp32 [B, H_q, d].
+ * A unit with n_selected == 0 gets zeros. */
+ice_status_t ice_attend(ice_index_t *idx, const void *q, const int32_t *page_ids,
+                        const int32_t *n_selected, int32_t n_ids_per_unit, float *out, void *stream);
+
+/* ice_select followed by ice_attend on the same stream; the ids never leave the device. */
+ice_status_t ice_select_attend(ice_index_t *idx, const void *q, int32_t token_budget,
+                               int32_t *page_ids, int32_t *n_selected, float *out, void *stream);
+
+/* Test and snapshot surface.  Export fills `view` with pointers INTO the workspace (no copy).
+ * Import copies caller arrays (device pointers, same layout; the export-only fields are
+ * ignored; n_tokens, page_size, n_clusters, max_pages must fit the workspace) into the index and
+ * recomputes only what is derived from the centroids (their bf16 rounding and squared norms);
+ * every other bit is used as given. */
+ice_status_t ice_export_index(ice_index_t *idx, ice_index_view_t *view);
+ice_status_t ice_import_index(ice_index_t *idx, const ice_index_view_t *view, void *stream);
+
+/* The assignment step alone (one Lloyd round's first half) on caller data, for parity tests:
+ *   K bf16 [n_units, n, d]; centroids_bf16 bf16 [n_units, n_clusters, d] ->
+ *   assign_out int32 [n_units, n]; best_out_or_null fp32 [n_units, n] = min_c(||mu_c||^2 - 2 k.mu_c).
+ * Uses the index's workspace as scratch and invalidates a built index (STATE afterwards). */
+ice_status_t ice_debug_assign(ice_index_t *idx, const void *K, int32_t n, const void *centroids_bf16,
+                              int32_t n_clusters, int32_t *assign_out, float *best_out_or_null,
+                              void *stream);
+
+const char *ice_last_error(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* ICECACHE_H */

@@ -1,0 +1,333 @@
+// Host side of the C ABI: argument validation, workspace layout, launch sequencing.
+// No call here allocates device memory, synchronises, or reads device memory.
+#include <cstdarg>
+#include <cstdio>
+#include <cstring>
+#include <new>
+
+#include "ice_internal.h"
+
+struct ice_index : ice::Host {};
+
+namespace {
+
+using namespace ice;
+
+thread_local char g_err[512] = "";
+
+ice_status_t fail(ice_status_t code, const char *fmt, ...) {
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(g_err, sizeof(g_err), fmt, ap);
+    va_end(ap);
+    return code;
+}
+
+bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+ice_status_t check_cfg(const ice_config_t *c) {
+    if (!c) return fail(ICE_ERR_INVALID_ARG, "config is null");
+    if (c->batch < 1 || c->n_kv_heads < 1 || c->max_tokens < 1 || c->kmeans_iters < 1)
+        return fail(ICE_ERR_INVALID_ARG, "batch, n_kv_heads, max_tokens and kmeans_iters must be >= 1");
+    if (c->head_dim != kD) return fail(ICE_ERR_UNSUPPORTED, "head_dim %d: only 128 is supported", c->head_dim);
+    if (c->group_size != 1 && c->group_size != 2 && c->group_size != 4 && c->group_size != 8)
+        return fail(ICE_ERR_UNSUPPORTED, "group_size %d: only 1, 2, 4, 8 are supported", c->group_size);
+    if ((long long)c->batch * c->n_kv_heads > 65535) return fail(ICE_ERR_UNSUPPORTED, "more than 65535 units");
+    return ICE_OK;
+}
+
+ice_status_t check_shape(int page_size, int n_clusters) {
+    if (page_size != 16 && page_size != 32 && page_size != 64)
+        return fail(ICE_ERR_UNSUPPORTED, "page_size %d: only 16, 32, 64 are supported", page_size);
+    if (n_clusters < 1) return fail(ICE_ERR_INVALID_ARG, "n_clusters must be >= 1");
+    if (n_clusters > 8192) return fail(ICE_ERR_UNSUPPORTED, "n_clusters %d: at most 8192", n_clusters);
+    return ICE_OK;
+}
+
+// Carves the workspace; with base == nullptr only measures.  Every region is 256-byte aligned.
+size_t lay_out(const ice_config_t &cfg, int s, int C, char *base, Dev *out) {
+    Dev d{};
+    d.U = cfg.batch * cfg.n_kv_heads;
+    d.G = cfg.group_size;
+    d.s = s;
+    d.C = C;
+    d.Cpad = round_up(C, 32);
+    d.max_tokens = cfg.max_tokens;
+    d.max_pages = cfg.max_tokens / s + C;
+    const size_t U = d.U, MP = d.max_pages, MT = d.max_tokens, CP = d.Cpad;
+    const size_t n_chunks = (MT + kSortChunk - 1) / kSortChunk;
+    size_t off = 0;
+    auto take = [&](size_t bytes) -> char * {
+        char *p = base ? base + off : nullptr;
+        off += (bytes + 255) / 256 * 256;
+        return p;
+    };
+    d.Kp = (bf16_t *)take(U * MP * s * kD * 2);
+    d.Vp = (bf16_t *)take(U * MP * s * kD * 2);
+    d.page_cluster = (int *)take(U * MP * 4);
+    d.page_fill = (int *)take(U * MP * 4);
+    d.page_pos = (int *)take(U * MP * s * 4);
+    d.cluster_tail = (int *)take(U * C * 4);
+    d.cluster_cnt = (int *)take(U * C * 4);
+    d.cluster_sum = (float *)take(U * C * kD * 4);
+    d.centroid = (float *)take(U * C * kD * 4);
+    d.page_sum = (float *)take(U * MP * kD * 4);
+    d.rep = (bf16_t *)take(U * MP * kD * 2);
+    d.n_pages = (int *)take(U * 4);
+    d.n_tokens = (int *)take(U * 4);
+    for (int b = 0; b < 2; ++b) {
+        d.cent_bf16[b] = (bf16_t *)take(U * CP * kD * 2);
+        d.cnorm[b] = (float *)take(U * CP * 4);
+    }
+    d.init_idx = (int *)take(U * C * 4);
+    d.assign = (int *)take(U * MT * 4);
+    d.packed = (unsigned long long *)take(U * MT * 8);
+    d.order = (int *)take(U * MT * 4);
+    d.chunk_hist = (int *)take(U * n_chunks * CP * 4);
+    d.cluster_start = (int *)take(U * (CP + 1) * 4);
+    d.page_base = (int *)take(U * (CP + 1) * 4);
+    d.scores = (float *)take(U * MP * 4);
+    d.sel_ids = (int *)take(U * MP * 4);
+    d.sel_n = (int *)take(U * 4);
+    if (out) *out = d;
+    return off;
+}
+
+ice_status_t ensure_layout(ice_index *ix, int s, int C) {
+    if (ix->laid_out && ix->dev.s == s && ix->dev.C == C) return ICE_OK;
+    const size_t need = lay_out(ix->cfg, s, C, nullptr, nullptr);
+    if (need > ix->ws_bytes)
+        return fail(ICE_ERR_CAPACITY, "workspace has %zu bytes, page_size %d / n_clusters %d need %zu", ix->ws_bytes, s,
+                    C, need);
+    lay_out(ix->cfg, s, C, ix->ws, &ix->dev);
+    ix->laid_out = true;
+    ix->built = false;
+    return ICE_OK;
+}
+
+ice_status_t device_status(const char *what) {
+    const hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return fail(ICE_ERR_DEVICE, "%s: %s", what, hipGetErrorString(e));
+    return ICE_OK;
+}
+
+__global__ void fill_i32_kernel(int *p, int n, int v) {
+    const int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n) p[i] = v;
+}
+
+}  // namespace
+
+extern "C" {
+
+const char *ice_last_error(void) { return g_err; }
+
+size_t ice_workspace_bytes(const ice_config_t *cfg, int32_t page_size, int32_t n_clusters) {
+    if (check_cfg(cfg) != ICE_OK || check_shape(page_size, n_clusters) != ICE_OK) return 0;
+    return lay_out(*cfg, page_size, n_clusters, nullptr, nullptr);
+}
+
+ice_status_t ice_create(const ice_config_t *cfg, void *workspace, size_t workspace_bytes, ice_index_t **out) {
+    if (!out) return fail(ICE_ERR_INVALID_ARG, "out is null");
+    *out = nullptr;
+    if (ice_status_t st = check_cfg(cfg)) return st;
+    if (!workspace || (reinterpret_cast<uintptr_t>(workspace) & 255u))
+        return fail(ICE_ERR_INVALID_ARG, "workspace is null or not 256-byte aligned");
+    if (workspace_bytes == 0) return fail(ICE_ERR_INVALID_ARG, "workspace_bytes is 0");
+    ice_index *ix = new (std::nothrow) ice_index();
+    if (!ix) return fail(ICE_ERR_INVALID_ARG, "out of host memory");
+    ix->cfg = *cfg;
+    ix->ws = static_cast<char *>(workspace);
+    ix->ws_bytes = workspace_bytes;
+    ix->laid_out = false;
+    ix->built = false;
+    ix->n_tokens = 0;
+    ix->cur = 0;
+    *out = ix;
+    return ICE_OK;
+}
+
+ice_status_t ice_destroy(ice_index_t *idx) {
+    if (!idx) return fail(ICE_ERR_INVALID_ARG, "index is null");
+    delete idx;
+    return ICE_OK;
+}
+
+ice_status_t ice_build_index(ice_index_t *ix, const void *K, const void *V, int32_t n, int32_t page_size,
+                             int32_t n_clusters, void *stream) {
+    if (!ix) return fail(ICE_ERR_INVALID_ARG, "index is null");
+    if (!K || !V || !aligned16(K) || !aligned16(V)) return fail(ICE_ERR_INVALID_ARG, "K or V is null or misaligned");
+    if (ix->cfg.init_idx && (reinterpret_cast<uintptr_t>(ix->cfg.init_idx) & 3u))
+        return fail(ICE_ERR_INVALID_ARG, "init_idx is misaligned");
+    if (ice_status_t st = check_shape(page_size, n_clusters)) return st;
+    if (n < 1) return fail(ICE_ERR_INVALID_ARG, "n_tokens must be >= 1");
+    if (n_clusters > n) return fail(ICE_ERR_SHAPE, "n_clusters %d exceeds n_tokens %d", n_clusters, n);
+    if (n > ix->cfg.max_tokens) return fail(ICE_ERR_SHAPE, "n_tokens %d exceeds max_tokens %d", n, ix->cfg.max_tokens);
+    if (ice_status_t st = ensure_layout(ix, page_size, n_clusters)) return st;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    const Dev &d = ix->dev;
+    const bf16_t *Kb = static_cast<const bf16_t *>(K), *Vb = static_cast<const bf16_t *>(V);
+    ix->built = false;
+    int cur = 0;
+    launch_init_centroids(d, Kb, n, ix->cfg.init_idx, ix->cfg.seed, cur, s);
+    for (int t = 0; t < ix->cfg.kmeans_iters; ++t) {
+        launch_assign(d, Kb, n, cur, s);
+        launch_sort(d, n, nullptr, nullptr, s);
+        launch_means(d, Kb, n, cur, s);
+        cur ^= 1;
+    }
+    launch_paginate(d, Kb, Vb, n, s);
+    hipLaunchKernelGGL(fill_i32_kernel, dim3((d.U + 255) / 256), dim3(256), 0, s, d.n_tokens, d.U, n);
+    if (ice_status_t st = device_status("ice_build_index")) return st;
+    ix->cur = cur;
+    ix->n_tokens = n;
+    ix->built = true;
+    return ICE_OK;
+}
+
+ice_status_t ice_insert(ice_index_t *ix, const void *k, const void *v, void *stream) {
+    if (!ix) return fail(ICE_ERR_INVALID_ARG, "index is null");
+    if (!ix->built) return fail(ICE_ERR_STATE, "ice_insert before ice_build_index");
+    if (!k || !v || !aligned16(k) || !aligned16(v)) return fail(ICE_ERR_INVALID_ARG, "k or v is null or misaligned");
+    if (ix->n_tokens >= ix->cfg.max_tokens)
+        return fail(ICE_ERR_CAPACITY, "index already holds max_tokens = %d tokens per unit", ix->cfg.max_tokens);
+    launch_insert(ix->dev, static_cast<const bf16_t *>(k), static_cast<const bf16_t *>(v), ix->cur,
+                  static_cast<hipStream_t>(stream));
+    if (ice_status_t st = device_status("ice_insert")) return st;
+    ix->n_tokens += 1;
+    return ICE_OK;
+}
+
+static ice_status_t check_select(ice_index_t *ix, const void *q, int32_t budget, const int32_t *ids,
+                                 const int32_t *n_sel, const char *who) {
+    if (!ix) return fail(ICE_ERR_INVALID_ARG, "index is null");
+    if (!ix->built) return fail(ICE_ERR_STATE, "%s before ice_build_index", who);
+    if (!q || !aligned16(q)) return fail(ICE_ERR_INVALID_ARG, "q is null or misaligned");
+    if (!ids || !n_sel) return fail(ICE_ERR_INVALID_ARG, "page_ids or n_selected is null");
+    if (budget < ix->dev.s) return fail(ICE_ERR_SHAPE, "token_budget %d is below page_size %d", budget, ix->dev.s);
+    return ICE_OK;
+}
+
+ice_status_t ice_select(ice_index_t *ix, const void *q, int32_t budget, int32_t *ids, int32_t *n_sel, float *scores,
+                        void *stream) {
+    if (ice_status_t st = check_select(ix, q, budget, ids, n_sel, "ice_select")) return st;
+    launch_select(ix->dev, static_cast<const bf16_t *>(q), budget / ix->dev.s, ids, n_sel, scores,
+                  static_cast<hipStream_t>(stream));
+    return device_status("ice_select");
+}
+
+ice_status_t ice_attend(ice_index_t *ix, const void *q, const int32_t *ids, const int32_t *n_sel, int32_t P, float *out,
+                        void *stream) {
+    if (!ix) return fail(ICE_ERR_INVALID_ARG, "index is null");
+    if (!ix->built) return fail(ICE_ERR_STATE, "ice_attend before ice_build_index");
+    if (!q || !aligned16(q)) return fail(ICE_ERR_INVALID_ARG, "q is null or misaligned");
+    if (!ids || !n_sel || !out) return fail(ICE_ERR_INVALID_ARG, "page_ids, n_selected or out is null");
+    if (P < 1) return fail(ICE_ERR_SHAPE, "n_ids_per_unit must be >= 1");
+    launch_attend(ix->dev, static_cast<const bf16_t *>(q), ids, n_sel, P, out, static_cast<hipStream_t>(stream));
+    return device_status("ice_attend");
+}
+
+ice_status_t ice_select_attend(ice_index_t *ix, const void *q, int32_t budget, int32_t *ids, int32_t *n_sel, float *out,
+                               void *stream) {
+    if (ice_status_t st = check_select(ix, q, budget, ids, n_sel, "ice_select_attend")) return st;
+    if (!out) return fail(ICE_ERR_INVALID_ARG, "out is null");
+    const int P = budget / ix->dev.s;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    launch_select(ix->dev, static_cast<const bf16_t *>(q), P, ids, n_sel, nullptr, s);
+    launch_attend(ix->dev, static_cast<const bf16_t *>(q), ids, n_sel, P, out, s);
+    return device_status("ice_select_attend");
+}
+
+ice_status_t ice_export_index(ice_index_t *ix, ice_index_view_t *v) {
+    if (!ix || !v) return fail(ICE_ERR_INVALID_ARG, "index or view is null");
+    if (!ix->built) return fail(ICE_ERR_STATE, "ice_export_index before ice_build_index");
+    const Dev &d = ix->dev;
+    memset(v, 0, sizeof(*v));
+    v->n_units = d.U;
+    v->group_size = d.G;
+    v->head_dim = kD;
+    v->page_size = d.s;
+    v->n_clusters = d.C;
+    v->cpad = d.Cpad;
+    v->max_pages = d.max_pages;
+    v->max_tokens = d.max_tokens;
+    v->n_tokens = ix->n_tokens;
+    v->Kp = d.Kp;
+    v->Vp = d.Vp;
+    v->page_cluster = d.page_cluster;
+    v->page_fill = d.page_fill;
+    v->page_pos = d.page_pos;
+    v->cluster_tail = d.cluster_tail;
+    v->cluster_cnt = d.cluster_cnt;
+    v->cluster_sum = d.cluster_sum;
+    v->centroid = d.centroid;
+    v->page_sum = d.page_sum;
+    v->rep = d.rep;
+    v->n_pages = d.n_pages;
+    v->assign = d.assign;
+    v->assign_centroid_bf16 = d.cent_bf16[ix->cur ^ 1];
+    v->init_idx = d.init_idx;
+    return ICE_OK;
+}
+
+ice_status_t ice_import_index(ice_index_t *ix, const ice_index_view_t *v, void *stream) {
+    if (!ix || !v) return fail(ICE_ERR_INVALID_ARG, "index or view is null");
+    if (ice_status_t st = check_shape(v->page_size, v->n_clusters)) return st;
+    if (v->n_units != ix->cfg.batch * ix->cfg.n_kv_heads || v->group_size != ix->cfg.group_size || v->head_dim != kD ||
+        v->max_tokens != ix->cfg.max_tokens || v->max_pages != ix->cfg.max_tokens / v->page_size + v->n_clusters)
+        return fail(ICE_ERR_SHAPE, "view dimensions do not match the index configuration");
+    if (v->n_tokens < 0 || v->n_tokens > ix->cfg.max_tokens) return fail(ICE_ERR_SHAPE, "view n_tokens out of range");
+    if (!v->Kp || !v->Vp || !v->page_cluster || !v->page_fill || !v->page_pos || !v->cluster_tail || !v->cluster_cnt ||
+        !v->cluster_sum || !v->centroid || !v->page_sum || !v->rep || !v->n_pages)
+        return fail(ICE_ERR_INVALID_ARG, "a view array is null");
+    if (ice_status_t st = ensure_layout(ix, v->page_size, v->n_clusters)) return st;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    const Dev &d = ix->dev;
+    const size_t U = d.U, MP = d.max_pages, C = d.C, ps = d.s;
+    hipError_t e = hipSuccess;
+    auto copy = [&](void *dst, const void *src, size_t bytes) {
+        if (e == hipSuccess) e = hipMemcpyAsync(dst, src, bytes, hipMemcpyDeviceToDevice, s);
+    };
+    copy(d.Kp, v->Kp, U * MP * ps * kD * 2);
+    copy(d.Vp, v->Vp, U * MP * ps * kD * 2);
+    copy(d.page_cluster, v->page_cluster, U * MP * 4);
+    copy(d.page_fill, v->page_fill, U * MP * 4);
+    copy(d.page_pos, v->page_pos, U * MP * ps * 4);
+    copy(d.cluster_tail, v->cluster_tail, U * C * 4);
+    copy(d.cluster_cnt, v->cluster_cnt, U * C * 4);
+    copy(d.cluster_sum, v->cluster_sum, U * C * kD * 4);
+    copy(d.centroid, v->centroid, U * C * kD * 4);
+    copy(d.page_sum, v->page_sum, U * MP * kD * 4);
+    copy(d.rep, v->rep, U * MP * kD * 2);
+    copy(d.n_pages, v->n_pages, U * 4);
+    if (e != hipSuccess) return fail(ICE_ERR_DEVICE, "ice_import_index: %s", hipGetErrorString(e));
+    hipLaunchKernelGGL(fill_i32_kernel, dim3((d.U + 255) / 256), dim3(256), 0, s, d.n_tokens, d.U, v->n_tokens);
+    ix->cur = 0;
+    launch_refresh_centroids(d, 0, s);
+    launch_refresh_centroids(d, 1, s);
+    if (ice_status_t st = device_status("ice_import_index")) return st;
+    ix->n_tokens = v->n_tokens;
+    ix->built = true;
+    return ICE_OK;
+}
+
+ice_status_t ice_debug_assign(ice_index_t *ix, const void *K, int32_t n, const void *cent, int32_t n_clusters,
+                              int32_t *assign_out, float *best_out, void *stream) {
+    if (!ix) return fail(ICE_ERR_INVALID_ARG, "index is null");
+    if (!K || !cent || !assign_out || !aligned16(K) || !aligned16(cent))
+        return fail(ICE_ERR_INVALID_ARG, "K, centroids or assign_out is null or misaligned");
+    if (n < 1) return fail(ICE_ERR_INVALID_ARG, "n must be >= 1");
+    if (n > ix->cfg.max_tokens) return fail(ICE_ERR_SHAPE, "n %d exceeds max_tokens %d", n, ix->cfg.max_tokens);
+    const int s_cur = ix->laid_out ? ix->dev.s : 16;
+    if (ice_status_t st = check_shape(s_cur, n_clusters)) return st;
+    if (ice_status_t st = ensure_layout(ix, s_cur, n_clusters)) return st;
+    ix->built = false;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    const Dev &d = ix->dev;
+    launch_load_centroids(d, static_cast<const bf16_t *>(cent), 0, s);
+    launch_assign(d, static_cast<const bf16_t *>(K), n, 0, s);
+    launch_sort(d, n, best_out, assign_out, s);
+    return device_status("ice_debug_assign");
+}
+
+}  // extern "C"

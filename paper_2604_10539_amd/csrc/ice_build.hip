@@ -1,0 +1,510 @@
+// Index build at prefill: promotion of the initial centroids, nearest-centroid assignment on the
+// matrix cores, deterministic per-cluster means, and the node -> page layout (Sec. 4.1-4.2,
+// Alg. 2 of the paper restricted to two levels and iterated as Lloyd rounds).
+#include "ice_internal.h"
+
+namespace ice {
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef unsigned long long u64;
+
+__device__ inline uint64_t splitmix64(uint64_t x) {
+    x += 0x9E3779B97F4A7C15ull;
+    x = (x ^ (x >> 30)) * 0xBF58476D1CE4E5B9ull;
+    x = (x ^ (x >> 27)) * 0x94D049BB133111EBull;
+    return x ^ (x >> 31);
+}
+
+// ------------------------------------------------------------------------------------------------
+// Initial centroids = the promoted keys (Alg. 2, "random promotion" with an exact count): cluster c
+// of unit u starts at key init_idx[u][c], or, without a list, at a hashed position inside the c-th
+// of C equal strata of the sequence (distinct by construction).  One wave per centroid row; rows
+// >= C are padding (zero vector, infinite norm) in both centroid buffers.
+__global__ __launch_bounds__(64) void init_centroids_kernel(Dev d, const bf16_t *K, int n,
+                                                            const int *init_idx, uint64_t seed, int cur) {
+    const int c = blockIdx.x, u = blockIdx.y, lane = threadIdx.x;
+    uint32_t *cb0 = (uint32_t *)(d.cent_bf16[cur] + ((size_t)u * d.Cpad + c) * kD);
+    uint32_t *cb1 = (uint32_t *)(d.cent_bf16[cur ^ 1] + ((size_t)u * d.Cpad + c) * kD);
+    if (c >= d.C) {
+        cb0[lane] = 0u;
+        cb1[lane] = 0u;
+        if (lane == 0) {
+            d.cnorm[cur][(size_t)u * d.Cpad + c] = INFINITY;
+            d.cnorm[cur ^ 1][(size_t)u * d.Cpad + c] = INFINITY;
+        }
+        return;
+    }
+    int idx;
+    if (init_idx) {
+        idx = init_idx[(size_t)u * d.C + c];
+        idx = idx < 0 ? 0 : (idx >= n ? n - 1 : idx);
+    } else {
+        long long lo = (long long)c * n / d.C, hi = (long long)(c + 1) * n / d.C;
+        idx = (int)(lo + (long long)(splitmix64(seed ^ ((uint64_t)u << 32) ^ (uint64_t)c) % (uint64_t)(hi - lo)));
+    }
+    const uint32_t w = ((const uint32_t *)(K + ((size_t)u * n + idx) * kD))[lane];
+    const float lo = bf16_lo(w), hi = bf16_hi(w);
+    cb0[lane] = w;
+    ((float2 *)(d.centroid + ((size_t)u * d.C + c) * kD))[lane] = make_float2(lo, hi);
+    const float nn = wave_sum(lo * lo + hi * hi);
+    if (lane == 0) {
+        d.cnorm[cur][(size_t)u * d.Cpad + c] = nn;
+        d.init_idx[(size_t)u * d.C + c] = idx;
+    }
+}
+
+void launch_init_centroids(const Dev &d, const bf16_t *K, int n, const int *init_idx, uint64_t seed, int cur,
+                           hipStream_t st) {
+    hipLaunchKernelGGL(init_centroids_kernel, dim3(d.Cpad, d.U), dim3(64), 0, st, d, K, n, init_idx, seed, cur);
+}
+
+// Caller-supplied bf16 centroids [U][C][128] -> live centroid buffer (padding + squared norms).
+__global__ __launch_bounds__(64) void load_centroids_kernel(Dev d, const bf16_t *cent, int cur) {
+    const int c = blockIdx.x, u = blockIdx.y, lane = threadIdx.x;
+    uint32_t *cb = (uint32_t *)(d.cent_bf16[cur] + ((size_t)u * d.Cpad + c) * kD);
+    if (c >= d.C) {
+        cb[lane] = 0u;
+        if (lane == 0) d.cnorm[cur][(size_t)u * d.Cpad + c] = INFINITY;
+        return;
+    }
+    const uint32_t w = ((const uint32_t *)(cent + ((size_t)u * d.C + c) * kD))[lane];
+    cb[lane] = w;
+    const float lo = bf16_lo(w), hi = bf16_hi(w);
+    const float nn = wave_sum(lo * lo + hi * hi);
+    if (lane == 0) d.cnorm[cur][(size_t)u * d.Cpad + c] = nn;
+}
+
+void launch_load_centroids(const Dev &d, const bf16_t *cent, int cur, hipStream_t st) {
+    hipLaunchKernelGGL(load_centroids_kernel, dim3(d.Cpad, d.U), dim3(64), 0, st, d, cent, cur);
+}
+
+// Recompute the bf16 rounding and squared norm of every centroid from the fp32 centroids.
+__global__ __launch_bounds__(64) void refresh_centroids_kernel(Dev d, int cur) {
+    const int c = blockIdx.x, u = blockIdx.y, lane = threadIdx.x;
+    uint32_t *cb = (uint32_t *)(d.cent_bf16[cur] + ((size_t)u * d.Cpad + c) * kD);
+    if (c >= d.C) {
+        cb[lane] = 0u;
+        if (lane == 0) d.cnorm[cur][(size_t)u * d.Cpad + c] = INFINITY;
+        return;
+    }
+    const float2 m = ((const float2 *)(d.centroid + ((size_t)u * d.C + c) * kD))[lane];
+    const bf16_t b0 = f32_to_bf16(m.x), b1 = f32_to_bf16(m.y);
+    cb[lane] = (uint32_t)b0 | ((uint32_t)b1 << 16);
+    const float lo = bf16_to_f32(b0), hi = bf16_to_f32(b1);
+    const float nn = wave_sum(lo * lo + hi * hi);
+    if (lane == 0) d.cnorm[cur][(size_t)u * d.Cpad + c] = nn;
+}
+
+void launch_refresh_centroids(const Dev &d, int cur, hipStream_t st) {
+    hipLaunchKernelGGL(refresh_centroids_kernel, dim3(d.Cpad, d.U), dim3(64), 0, st, d, cur);
+}
+
+__global__ void fill_u64_kernel(u64 *p, size_t n, u64 v) {
+    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += (size_t)gridDim.x * blockDim.x) p[i] = v;
+}
+
+// ------------------------------------------------------------------------------------------------
+// Nearest centroid on the matrix cores.
+//   score(i, c) = k_i . mu~_c - ||mu~_c||^2 / 2      (argmax score == argmin ||k_i - mu~_c||^2)
+// A dense (keys x 128) by (128 x centroids) contraction: v_mfma_f32_32x32x16_bf16 with the
+// centroids as the A operand (rows) and the keys as the B operand (columns), so one lane ends up
+// with 16 centroid scores of ONE key per 32x32 tile and the argmax over centroids stays in-lane.
+// The accumulator is seeded with -||mu~||^2/2, so the epilogue is compare/select only.
+//
+// A workgroup of 8 waves covers CW * CT * 32 centroids (wave w keeps CT tiles of 32 centroids in
+// registers for its whole life) and streams its share of the unit's keys through LDS in tiles of
+// 256 keys (coalesced 16-byte global loads, rows padded to 272 bytes so the 32-row operand reads
+// are bank-conflict free).  When CW < 8 the remaining waves split the key tile instead.  Per key
+// the waves' candidates meet in an LDS 64-bit max of (ordered score, ~centroid id): the exact fp32
+// maximum with the lowest centroid id on ties.  More than CW*CT*32 centroids are covered by
+// blockIdx.y slices that meet the same way in global memory.
+constexpr int kKeyStride = 136;  // bf16 elements per LDS key row (128 + 8 padding)
+
+template <int CT, int CW>
+__global__ __launch_bounds__(512) void assign_kernel(Dev d, const bf16_t *__restrict__ K, int n, int cur,
+                                                      int keys_per_wg, int zsplit) {
+    constexpr int KW = 8 / CW;
+    extern __shared__ __align__(16) char smem[];
+    bf16_t *keys = (bf16_t *)smem;                                   // [2][256][kKeyStride]
+    u64 *best = (u64 *)(smem + 2 * kAssignTile * kKeyStride * 2);    // [256]
+
+    const int u = blockIdx.z, tid = threadIdx.x;
+    const int wave = tid >> 6, lane = tid & 63, col = lane & 31, half = lane >> 5;
+    const int cw = wave % CW, kw = wave / CW;
+    const int cbase = (blockIdx.y * CW + cw) * CT * 32;
+    const int k0 = blockIdx.x * keys_per_wg;
+    const int kend = min(n, k0 + keys_per_wg);
+    const int ntiles = (kend - k0 + kAssignTile - 1) / kAssignTile;
+    const bf16_t *Ku = K + (size_t)u * n * kD;
+
+    // centroid operand and accumulator seeds, resident for the whole kernel
+    bf16x8 A[CT][8];
+    f32x16 seed[CT];
+#pragma unroll
+    for (int ct = 0; ct < CT; ++ct) {
+        const int row0 = cbase + ct * 32;
+        if (row0 < d.Cpad) {
+            const uint4 *src = (const uint4 *)(d.cent_bf16[cur] + ((size_t)u * d.Cpad + row0 + col) * kD);
+#pragma unroll
+            for (int ks = 0; ks < 8; ++ks) A[ct][ks] = __builtin_bit_cast(bf16x8, src[ks * 2 + half]);
+            const float *wn = d.cnorm[cur] + (size_t)u * d.Cpad + row0;
+#pragma unroll
+            for (int v = 0; v < 16; ++v) seed[ct][v] = -0.5f * wn[8 * (v >> 2) + 4 * half + (v & 3)];
+        } else {
+#pragma unroll
+            for (int ks = 0; ks < 8; ++ks) A[ct][ks] = __builtin_bit_cast(bf16x8, make_uint4(0, 0, 0, 0));
+#pragma unroll
+            for (int v = 0; v < 16; ++v) seed[ct][v] = -INFINITY;
+        }
+    }
+
+    uint4 stage[8];
+    auto load_tile = [&](int t) {
+        const int base = k0 + t * kAssignTile;
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            const int id = tid + 512 * i, row = id >> 4, ch = id & 15;
+            const int key = base + row;
+            stage[i] = key < kend ? ((const uint4 *)(Ku + (size_t)key * kD))[ch] : make_uint4(0, 0, 0, 0);
+        }
+    };
+    auto store_tile = [&](int buf) {
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            const int id = tid + 512 * i, row = id >> 4, ch = id & 15;
+            *(uint4 *)(keys + ((size_t)buf * kAssignTile + row) * kKeyStride + ch * 8) = stage[i];
+        }
+    };
+
+    if (tid < kAssignTile) best[tid] = 0ull;
+    if (ntiles > 0) {
+        load_tile(0);
+        store_tile(0);
+    }
+    __syncthreads();
+
+    for (int t = 0; t < ntiles; ++t) {
+        const int buf = t & 1;
+        if (t + 1 < ntiles) load_tile(t + 1);
+        for (int sub = kw; sub < 8; sub += KW) {
+            const bf16_t *krow = keys + ((size_t)buf * kAssignTile + sub * 32 + col) * kKeyStride + half * 8;
+            bf16x8 B[8];
+#pragma unroll
+            for (int ks = 0; ks < 8; ++ks) B[ks] = __builtin_bit_cast(bf16x8, *(const uint4 *)(krow + ks * 16));
+            float bv = -INFINITY;
+            int bi = 0;
+#pragma unroll
+            for (int ct = 0; ct < CT; ++ct) {
+                f32x16 acc = seed[ct];
+#pragma unroll
+                for (int ks = 0; ks < 8; ++ks)
+                    acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(A[ct][ks], B[ks], acc, 0, 0, 0);
+                // rows of this lane, ascending centroid id: ct*32 + 8*(v/4) + 4*half + v%4
+#pragma unroll
+                for (int v = 0; v < 16; ++v) {
+                    const bool gt = acc[v] > bv;
+                    bv = gt ? acc[v] : bv;
+                    bi = gt ? (ct * 32 + 8 * (v >> 2) + (v & 3)) : bi;
+                }
+            }
+            const uint32_t cid = (uint32_t)(cbase + bi + 4 * half);
+            const u64 pk = ((u64)f32_ordered(bv) << 32) | (u64)(0xFFFFFFFFu - cid);
+            atomicMax(&best[sub * 32 + col], pk);
+        }
+        if (t + 1 < ntiles) store_tile(buf ^ 1);
+        __syncthreads();
+        if (tid < kAssignTile) {
+            const int key = k0 + t * kAssignTile + tid;
+            if (key < kend) {
+                u64 *dst = d.packed + (size_t)u * d.max_tokens + key;
+                if (zsplit == 1) *dst = best[tid];
+                else atomicMax(dst, best[tid]);
+            }
+            best[tid] = 0ull;
+        }
+        __syncthreads();
+    }
+}
+
+void launch_assign(const Dev &d, const bf16_t *K, int n, int cur, hipStream_t st) {
+    const int tiles = d.Cpad / 32;
+    int CT = tiles == 1 ? 1 : 2, CW = 1;
+    while (CW < 8 && CW * CT < tiles) CW *= 2;
+    const int cblock = CT * CW * 32;
+    const int zsplit = (d.Cpad + cblock - 1) / cblock;
+    // enough workgroups to fill 256 CUs, each amortising its centroid load over >= 512 keys
+    int keys_per_wg = kAssignTile;
+    while ((long long)((n + keys_per_wg - 1) / keys_per_wg) * zsplit * d.U > 512 && keys_per_wg < 4096) keys_per_wg *= 2;
+    dim3 grid((n + keys_per_wg - 1) / keys_per_wg, zsplit, d.U);
+    const size_t lds = 2 * kAssignTile * kKeyStride * 2 + kAssignTile * 8;
+    if (zsplit > 1) {
+        const size_t tot = (size_t)d.U * d.max_tokens;
+        hipLaunchKernelGGL(fill_u64_kernel, dim3(1024), dim3(256), 0, st, d.packed, tot, 0ull);
+    }
+#define ICE_ASSIGN(ct, cw)                                                                          \
+    do {                                                                                            \
+        (void)hipFuncSetAttribute((const void *)assign_kernel<ct, cw>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds); \
+        hipLaunchKernelGGL((assign_kernel<ct, cw>), grid, dim3(512), lds, st, d, K, n, cur, keys_per_wg, zsplit);       \
+    } while (0)
+    if (CT == 1) ICE_ASSIGN(1, 1);
+    else if (CW == 1) ICE_ASSIGN(2, 1);
+    else if (CW == 2) ICE_ASSIGN(2, 2);
+    else if (CW == 4) ICE_ASSIGN(2, 4);
+    else ICE_ASSIGN(2, 8);
+#undef ICE_ASSIGN
+}
+
+// ------------------------------------------------------------------------------------------------
+// Stable counting sort of the tokens by cluster (ascending position inside a cluster): the order
+// both the deterministic means and the page layout need.  Three small kernels: per-chunk
+// histograms (which also unpack the assignment), scans, ranks.
+__global__ __launch_bounds__(256) void sort_hist_kernel(Dev d, int n, int n_chunks, float *best_out,
+                                                         int *assign_out) {
+    extern __shared__ int cnt[];  // [4][Cpad]
+    const int u = blockIdx.y, wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    const int chunk = blockIdx.x * 4 + wave;
+    int *my = cnt + wave * d.Cpad;
+    for (int c = lane; c < d.Cpad; c += 64) my[c] = 0;
+    __syncthreads();
+    if (chunk < n_chunks) {
+        const int i0 = chunk * kSortChunk;
+        for (int g = 0; g < kSortChunk / 64; ++g) {
+            const int i = i0 + g * 64 + lane;
+            if (i < n) {
+                const u64 pk = d.packed[(size_t)u * d.max_tokens + i];
+                const int a = (int)(0xFFFFFFFFu - (uint32_t)pk);
+                d.assign[(size_t)u * d.max_tokens + i] = a;
+                if (assign_out) assign_out[(size_t)u * n + i] = a;
+                if (best_out) best_out[(size_t)u * n + i] = -2.0f * ordered_f32((uint32_t)(pk >> 32));
+                atomicAdd(&my[a], 1);
+            }
+        }
+    }
+    __syncthreads();
+    if (chunk < n_chunks)
+        for (int c = lane; c < d.Cpad; c += 64) d.chunk_hist[((size_t)u * n_chunks + chunk) * d.Cpad + c] = my[c];
+}
+
+// One workgroup per unit: per cluster, exclusive scan of the chunk histograms over the chunks;
+// then exclusive scans over the clusters of the member counts and of the page counts.
+__global__ __launch_bounds__(1024) void sort_scan_kernel(Dev d, int n_chunks) {
+    __shared__ int wsum[2][16];
+    __shared__ int carry[2];
+    const int u = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    if (tid < 2) carry[tid] = 0;
+    __syncthreads();
+    for (int c0 = 0; c0 < d.Cpad; c0 += 1024) {
+        const int c = c0 + tid;
+        int tot = 0;
+        if (c < d.Cpad) {
+            int *h = d.chunk_hist + (size_t)u * n_chunks * d.Cpad + c;
+            for (int k = 0; k < n_chunks; ++k) {
+                const int t = h[(size_t)k * d.Cpad];
+                h[(size_t)k * d.Cpad] = tot;
+                tot += t;
+            }
+        }
+        const int pages = (tot + d.s - 1) / d.s;
+        // inclusive wave scans of (tot, pages)
+        int a = tot, b = pages;
+        for (int off = 1; off < 64; off <<= 1) {
+            const int ta = __shfl_up(a, off), tb = __shfl_up(b, off);
+            if (lane >= off) { a += ta; b += tb; }
+        }
+        if (lane == 63) { wsum[0][wave] = a; wsum[1][wave] = b; }
+        __syncthreads();
+        int pa = carry[0], pb = carry[1];
+        for (int w = 0; w < wave; ++w) { pa += wsum[0][w]; pb += wsum[1][w]; }
+        const int ex_a = pa + a - tot, ex_b = pb + b - pages;
+        if (c < d.Cpad) {
+            d.cluster_start[(size_t)u * (d.Cpad + 1) + c] = ex_a;
+            d.page_base[(size_t)u * (d.Cpad + 1) + c] = ex_b;
+            if (c < d.C) {
+                d.cluster_cnt[(size_t)u * d.C + c] = tot;
+                d.cluster_tail[(size_t)u * d.C + c] = tot > 0 ? ex_b + pages - 1 : -1;
+            }
+        }
+        __syncthreads();
+        if (tid == 1023) { carry[0] = pa + a; carry[1] = pb + b; }
+        __syncthreads();
+    }
+    if (tid == 0) {
+        d.cluster_start[(size_t)u * (d.Cpad + 1) + d.Cpad] = carry[0];
+        d.page_base[(size_t)u * (d.Cpad + 1) + d.Cpad] = carry[1];
+        d.n_pages[u] = carry[1];
+    }
+}
+
+__global__ __launch_bounds__(256) void sort_rank_kernel(Dev d, int n, int n_chunks, int nbits) {
+    extern __shared__ int cnt[];  // [4][Cpad] running write positions
+    const int u = blockIdx.y, wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    const int chunk = blockIdx.x * 4 + wave;
+    if (chunk >= n_chunks) return;  // no workgroup-wide barrier below
+    int *my = cnt + wave * d.Cpad;
+    for (int c = lane; c < d.Cpad; c += 64)
+        my[c] = d.cluster_start[(size_t)u * (d.Cpad + 1) + c] + d.chunk_hist[((size_t)u * n_chunks + chunk) * d.Cpad + c];
+    __builtin_amdgcn_wave_barrier();
+    const u64 lt = (1ull << lane) - 1ull;
+    const int i0 = chunk * kSortChunk;
+    for (int g = 0; g < kSortChunk / 64; ++g) {
+        const int i = i0 + g * 64 + lane;
+        const bool valid = i < n;
+        const int a = valid ? d.assign[(size_t)u * d.max_tokens + i] : 0;
+        u64 peers = __ballot(valid);
+        for (int b = 0; b < nbits; ++b) {
+            const bool bit = (a >> b) & 1;
+            const u64 bal = __ballot(bit);
+            peers &= bit ? bal : ~bal;
+        }
+        if (!valid) peers = 0ull;  // (only trailing lanes of the last group)
+        int base = 0;
+        const int leader = valid ? (int)__builtin_ctzll(peers) : lane;
+        if (valid && lane == leader) base = atomicAdd(&my[a], (int)__popcll(peers));
+        base = __shfl(base, leader);
+        if (valid) d.order[(size_t)u * d.max_tokens + base + (int)__popcll(peers & lt)] = i;
+    }
+}
+
+void launch_sort(const Dev &d, int n, float *best_out, int *assign_out, hipStream_t st) {
+    const int n_chunks = (n + kSortChunk - 1) / kSortChunk;
+    int nbits = 0;
+    while ((1 << nbits) < d.Cpad) ++nbits;
+    const size_t lds = (size_t)4 * d.Cpad * sizeof(int);
+    hipLaunchKernelGGL(sort_hist_kernel, dim3((n_chunks + 3) / 4, d.U), dim3(256), lds, st, d, n, n_chunks, best_out,
+                       assign_out);
+    hipLaunchKernelGGL(sort_scan_kernel, dim3(d.U), dim3(1024), 0, st, d, n_chunks);
+    hipLaunchKernelGGL(sort_rank_kernel, dim3((n_chunks + 3) / 4, d.U), dim3(256), lds, st, d, n, n_chunks, nbits);
+}
+
+// ------------------------------------------------------------------------------------------------
+// Centroid update: one wave per cluster gathers its members' key rows (256 contiguous bytes each,
+// 16 lanes x 16 bytes, four rows per load) in sorted order and sums them in fp32 in a fixed order,
+// so the result is the same on every run (no floating-point atomics).  Writes sum, count, mean,
+// and the bf16 rounding + squared norm of the mean into the OTHER centroid buffer; an empty
+// cluster keeps its centroid.
+__global__ __launch_bounds__(256) void means_kernel(Dev d, const bf16_t *__restrict__ K, int n, int cur) {
+    const int u = blockIdx.y, wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    const int c = blockIdx.x * 4 + wave;
+    if (c >= d.C) return;
+    const int g = lane >> 4, ch = lane & 15;
+    const int start = d.cluster_start[(size_t)u * (d.Cpad + 1) + c];
+    const int cnt = d.cluster_start[(size_t)u * (d.Cpad + 1) + c + 1] - start;
+    const int *ord = d.order + (size_t)u * d.max_tokens + start;
+    const bf16_t *Ku = K + (size_t)u * n * kD;
+    float acc[8];
+#pragma unroll
+    for (int j = 0; j < 8; ++j) acc[j] = 0.f;
+    for (int r = g; r < cnt; r += 4) {
+        const uint4 w = ((const uint4 *)(Ku + (size_t)ord[r] * kD))[ch];
+        acc[0] += bf16_lo(w.x); acc[1] += bf16_hi(w.x);
+        acc[2] += bf16_lo(w.y); acc[3] += bf16_hi(w.y);
+        acc[4] += bf16_lo(w.z); acc[5] += bf16_hi(w.z);
+        acc[6] += bf16_lo(w.w); acc[7] += bf16_hi(w.w);
+    }
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+        acc[j] += __shfl_xor(acc[j], 16);
+        acc[j] += __shfl_xor(acc[j], 32);
+    }
+    float mu[8];
+    float *cen = d.centroid + ((size_t)u * d.C + c) * kD + ch * 8;
+    if (cnt > 0) {
+#pragma unroll
+        for (int j = 0; j < 8; ++j) mu[j] = acc[j] / (float)cnt;
+    } else {
+#pragma unroll
+        for (int j = 0; j < 8; ++j) mu[j] = cen[j];
+    }
+    uint32_t pk[4];
+    float nn = 0.f;
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+        const bf16_t b0 = f32_to_bf16(mu[2 * j]), b1 = f32_to_bf16(mu[2 * j + 1]);
+        pk[j] = (uint32_t)b0 | ((uint32_t)b1 << 16);
+        const float f0 = bf16_to_f32(b0), f1 = bf16_to_f32(b1);
+        nn += f0 * f0 + f1 * f1;
+    }
+    nn = row16_sum(nn);
+    if (g == 0) {
+        float *sum = d.cluster_sum + ((size_t)u * d.C + c) * kD + ch * 8;
+        ((float4 *)sum)[0] = make_float4(acc[0], acc[1], acc[2], acc[3]);
+        ((float4 *)sum)[1] = make_float4(acc[4], acc[5], acc[6], acc[7]);
+        ((float4 *)cen)[0] = make_float4(mu[0], mu[1], mu[2], mu[3]);
+        ((float4 *)cen)[1] = make_float4(mu[4], mu[5], mu[6], mu[7]);
+        ((uint4 *)(d.cent_bf16[cur ^ 1] + ((size_t)u * d.Cpad + c) * kD))[ch] = make_uint4(pk[0], pk[1], pk[2], pk[3]);
+        if (ch == 0) d.cnorm[cur ^ 1][(size_t)u * d.Cpad + c] = nn;
+    }
+}
+
+void launch_means(const Dev &d, const bf16_t *K, int n, int cur, hipStream_t st) {
+    hipLaunchKernelGGL(means_kernel, dim3((d.C + 3) / 4, d.U), dim3(256), 0, st, d, K, n, cur);
+}
+
+// ------------------------------------------------------------------------------------------------
+// Node -> pages (Sec. 4.1): clusters in id order, members in ascending position, cut every s
+// tokens; consecutive page ids.  One wave per page copies the s key rows and s value rows into
+// the page's contiguous tiles, records their positions, and forms the representative: the fp32
+// sum of the page's keys in slot order (one add per slot), divided by the fill, rounded to bf16.
+__global__ __launch_bounds__(256) void paginate_kernel(Dev d, const bf16_t *__restrict__ K,
+                                                        const bf16_t *__restrict__ V, int n) {
+    extern __shared__ __align__(16) char smem[];  // [4][s][128] bf16
+    const int u = blockIdx.y, wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    const int p = blockIdx.x * 4 + wave;
+    if (p >= d.max_pages) return;
+    const int s = d.s;
+    const size_t pg = (size_t)u * d.max_pages + p;
+    const int np = d.n_pages[u];
+    if (p >= np) {  // unused page: clear its table entries
+        if (lane == 0) { d.page_cluster[pg] = -1; d.page_fill[pg] = 0; }
+        for (int t = lane; t < s; t += 64) d.page_pos[pg * s + t] = -1;
+        return;
+    }
+    const int *pb = d.page_base + (size_t)u * (d.Cpad + 1);
+    int lo = 0, hi = d.Cpad;  // largest c with pb[c] <= p (clusters without pages are skipped)
+    while (hi - lo > 1) {
+        const int mid = (lo + hi) >> 1;
+        if (pb[mid] <= p) lo = mid; else hi = mid;
+    }
+    const int c = lo;
+    const int start = d.cluster_start[(size_t)u * (d.Cpad + 1) + c];
+    const int cnt = d.cluster_start[(size_t)u * (d.Cpad + 1) + c + 1] - start;
+    const int r0 = (p - pb[c]) * s;
+    const int fill = min(s, cnt - r0);
+    const int *ord = d.order + (size_t)u * d.max_tokens + start + r0;
+    const int g = lane >> 4, ch = lane & 15;
+    bf16_t *tile = (bf16_t *)smem + (size_t)wave * s * kD;
+    for (int t4 = 0; t4 < s; t4 += 4) {
+        const int slot = t4 + g;
+        const bool valid = slot < fill;
+        const int tok = valid ? ord[slot] : -1;
+        uint4 kw = make_uint4(0, 0, 0, 0), vw = kw;
+        if (valid) {
+            kw = ((const uint4 *)(K + ((size_t)u * n + tok) * kD))[ch];
+            vw = ((const uint4 *)(V + ((size_t)u * n + tok) * kD))[ch];
+        }
+        ((uint4 *)(d.Kp + (pg * s + slot) * kD))[ch] = kw;
+        ((uint4 *)(d.Vp + (pg * s + slot) * kD))[ch] = vw;
+        ((uint4 *)(tile + (size_t)slot * kD))[ch] = kw;
+        if (ch == 0) d.page_pos[pg * s + slot] = tok;
+    }
+    if (lane == 0) { d.page_cluster[pg] = c; d.page_fill[pg] = fill; }
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_s_waitcnt(0xc07f);  // lgkmcnt(0): the tile writes above are visible to the wave
+    float a0 = 0.f, a1 = 0.f;
+    for (int t = 0; t < fill; ++t) {
+        const uint32_t w = ((const uint32_t *)(tile + (size_t)t * kD))[lane];
+        a0 = a0 + bf16_lo(w);
+        a1 = a1 + bf16_hi(w);
+    }
+    ((float2 *)(d.page_sum + pg * kD))[lane] = make_float2(a0, a1);
+    const float f = (float)fill;
+    ((uint32_t *)(d.rep + pg * kD))[lane] = (uint32_t)f32_to_bf16(a0 / f) | ((uint32_t)f32_to_bf16(a1 / f) << 16);
+}
+
+void launch_paginate(const Dev &d, const bf16_t *K, const bf16_t *V, int n, hipStream_t st) {
+    const size_t lds = (size_t)4 * d.s * kD * 2;
+    hipLaunchKernelGGL(paginate_kernel, dim3((d.max_pages + 3) / 4, d.U), dim3(256), lds, st, d, K, V, n);
+}
+
+}  // namespace ice

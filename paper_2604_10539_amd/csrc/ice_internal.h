@@ -1,0 +1,113 @@
+// Internal declarations shared by the host API and the kernel files (gfx950 only).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "icecache.h"
+
+namespace ice {
+
+constexpr int kD = 128;          // head_dim
+constexpr int kSortChunk = 1024; // tokens per wave in the counting sort
+constexpr int kAssignTile = 256; // keys staged in LDS per step of the assign kernel
+
+typedef uint16_t bf16_t;
+
+// Everything a kernel needs, passed by value.  Pointers are into the caller's workspace.
+struct Dev {
+    int U, G, s, C, Cpad, max_pages, max_tokens;
+    // index state
+    bf16_t *Kp, *Vp;            // [U][max_pages][s][128]
+    int *page_cluster, *page_fill; // [U][max_pages]
+    int *page_pos;              // [U][max_pages][s]
+    int *cluster_tail, *cluster_cnt; // [U][C]
+    float *cluster_sum, *centroid;   // [U][C][128]
+    float *page_sum;            // [U][max_pages][128]
+    bf16_t *rep;                // [U][max_pages][128]
+    int *n_pages;               // [U]
+    int *n_tokens;              // [U] device mirror of the token count (page_pos of inserts)
+    bf16_t *cent_bf16[2];       // [U][Cpad][128] double buffer: [cur] is live, [cur^1] previous
+    float *cnorm[2];            // [U][Cpad] squared norms of cent_bf16 (+inf in the padding)
+    // build scratch
+    int *init_idx;              // [U][C]
+    int *assign;                // [U][max_tokens]
+    unsigned long long *packed; // [U][max_tokens] (ordered score << 32) | ~cluster
+    int *order;                 // [U][max_tokens] tokens sorted by (cluster, position)
+    int *chunk_hist;            // [U][n_chunks_max][Cpad]
+    int *cluster_start;         // [U][Cpad+1] exclusive scan of counts
+    int *page_base;             // [U][Cpad+1] exclusive scan of pages per cluster
+    // decode scratch
+    float *scores;              // [U][max_pages]
+    int *sel_ids;               // [U][max_sel] ids handed from select to attend in the fused call
+    int *sel_n;                 // [U]
+};
+
+struct Host {
+    ice_config_t cfg;
+    char *ws;
+    size_t ws_bytes;
+    Dev dev;
+    bool laid_out;   // dev pointers valid for (s, C)
+    bool built;
+    int n_tokens;    // per unit
+    int cur;         // live centroid buffer
+    int max_sel;
+};
+
+__host__ __device__ inline int round_up(int x, int m) { return (x + m - 1) / m * m; }
+
+// ---- launchers (host functions defined in the kernel files) ----
+void launch_init_centroids(const Dev &d, const bf16_t *K, int n, const int *init_idx_or_null,
+                           uint64_t seed, int cur, hipStream_t st);
+void launch_load_centroids(const Dev &d, const bf16_t *cent, int cur, hipStream_t st);
+void launch_assign(const Dev &d, const bf16_t *K, int n, int cur, hipStream_t st);
+void launch_sort(const Dev &d, int n, float *best_out_or_null, int *assign_out_or_null, hipStream_t st);
+void launch_means(const Dev &d, const bf16_t *K, int n, int cur, hipStream_t st);
+void launch_paginate(const Dev &d, const bf16_t *K, const bf16_t *V, int n, hipStream_t st);
+void launch_refresh_centroids(const Dev &d, int cur, hipStream_t st);
+void launch_insert(const Dev &d, const bf16_t *k, const bf16_t *v, int cur, hipStream_t st);
+void launch_select(const Dev &d, const bf16_t *q, int P, int *ids, int *n_sel, float *scores_out,
+                   hipStream_t st);
+void launch_attend(const Dev &d, const bf16_t *q, const int *ids, const int *n_sel, int P, float *out,
+                   hipStream_t st);
+
+// ---- device helpers ----
+__device__ inline float bf16_lo(uint32_t w) { return __uint_as_float(w << 16); }
+__device__ inline float bf16_hi(uint32_t w) { return __uint_as_float(w & 0xFFFF0000u); }
+__device__ inline float bf16_to_f32(bf16_t b) { return __uint_as_float(((uint32_t)b) << 16); }
+// round to nearest even; finite inputs
+__device__ inline bf16_t f32_to_bf16(float f) {
+    uint32_t u = __float_as_uint(f);
+    u += 0x7FFFu + ((u >> 16) & 1u);
+    return (bf16_t)(u >> 16);
+}
+// monotone map fp32 -> u32 (larger float <=> larger unsigned)
+__device__ inline uint32_t f32_ordered(float f) {
+    uint32_t u = __float_as_uint(f);
+    return u ^ ((u & 0x80000000u) ? 0xFFFFFFFFu : 0x80000000u);
+}
+__device__ inline float ordered_f32(uint32_t k) {
+    uint32_t u = k ^ ((k & 0x80000000u) ? 0x80000000u : 0xFFFFFFFFu);
+    return __uint_as_float(u);
+}
+
+template <int CTRL>
+__device__ inline float dpp_f32(float x) {
+    return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(x), CTRL, 0xF, 0xF, true));
+}
+// sum over the 16 lanes of a DPP row; every lane of the row gets the same bits
+__device__ inline float row16_sum(float x) {
+    x += dpp_f32<0xB1>(x);  // quad_perm [1,0,3,2]
+    x += dpp_f32<0x4E>(x);  // quad_perm [2,3,0,1]
+    x += dpp_f32<0x141>(x); // row_half_mirror
+    x += dpp_f32<0x140>(x); // row_mirror
+    return x;
+}
+__device__ inline float wave_sum(float x) {
+    x = row16_sum(x);
+    x += __shfl_xor(x, 16);
+    x += __shfl_xor(x, 32);
+    return x;
+}
+
+}  // namespace ice

@@ -1,0 +1,378 @@
+"""GPU parity: the HIP library, called through its C ABI, against the CPU oracle on the same seeded
+inputs.  Integer results (tables, page ids, bit copies, ordered-fp32 quantities) must be bit-exact;
+floating-point decisions may differ only inside a stated tie band, which is counted and printed;
+attention must agree within max-abs 2e-3 (bf16 inputs, fp32 accumulation)."""
+import math
+
+import numpy as np
+import pytest
+import torch
+
+import datagen
+from datagen import bf16_bits_to_f32 as widen, f32_to_bf16_bits as narrow
+from oracle import ice_oracle as orc
+from tests.util import D, STATE_FIELDS, down, export_np, oracle_arrays_to_device, oracle_from_export, up, valid_slot_mask
+
+pytestmark = pytest.mark.gpu
+
+ATTN_TOL = 2e-3        # contract: max-abs on bf16 inputs with fp32 accumulation
+ATTN_EXPECTED = 2e-4   # what fp32 accumulation actually delivers; a regression guard
+SCORE_TIE = 1e-5       # ties within 1e-5 (relative to max(1, |score|)) are reported, not failed
+U2 = 2.0 ** -24        # fp32 unit roundoff
+
+
+def _mk(w, T=3, extra=0, init=True, seed=0):
+    from paper_2604_10539_amd import IceIndex
+    K, V = datagen.keys_values(w)
+    idx = datagen.init_indices(w)
+    ix = IceIndex(w.batch, w.n_kv_heads, w.group_size, w.n_tokens + extra, w.page_size, w.n_clusters,
+                  kmeans_iters=T, seed=seed, init_idx=up(idx) if init else None)
+    U = w.batch * w.n_kv_heads
+    return ix, K.reshape(U, w.n_tokens, D), V.reshape(U, w.n_tokens, D), idx.reshape(U, w.n_clusters)
+
+
+def _assign_band(K, mub):
+    """Rigorous bound on |fp32 objective - exact objective| for one unit: the objective is a chain of
+    d+1 fp32 additions of exact products seeded with -w/2, then doubled."""
+    kf, mf = widen(K).astype(np.float64), widen(mub).astype(np.float64)
+    w = (mf ** 2).sum(1)
+    mag = 0.5 * w.max() + np.linalg.norm(kf, axis=1) * np.linalg.norm(mf, axis=1).max()
+    return 2.0 * (D + 2) * U2 * mag * 2.0
+
+
+def _check_assign(K, mub, a_gpu, label):
+    """GPU choice must be optimal within the tie band; returns the number of rows that differ."""
+    a_ref, best, second = orc.assign(K, mub)
+    kf, mf = widen(K).astype(np.float64), widen(mub).astype(np.float64)
+    obj_gpu = (mf[a_gpu] ** 2).sum(1) - 2.0 * (kf * mf[a_gpu]).sum(1)
+    band = _assign_band(K, mub)
+    diff = np.nonzero(a_gpu != a_ref)[0]
+    assert np.all(obj_gpu - best <= band), "%s: a GPU assignment is worse than the optimum beyond the tie band" % label
+    print("[assign %s] %d of %d rows differ from the oracle, all inside the tie band (max band %.2e)"
+          % (label, len(diff), len(a_ref), band.max()))
+    assert len(diff) <= max(2, len(a_ref) // 500), "%s: too many near-tie flips" % label
+    return len(diff)
+
+
+# ----------------------------------------------------------------------------------------- assign
+@pytest.mark.parametrize("n,C", [(1000, 24), (4096, 32), (5000, 100), (3001, 512), (2100, 700), (4099, 2048), (333, 1)])
+def test_debug_assign_matches_exhaustive_search(n, C):
+    from paper_2604_10539_amd import IceIndex
+    rng = np.random.default_rng(n + C)
+    w = datagen.small(n_tokens=n, n_clusters=C, n_kv_heads=2, n_components=max(4, C // 2))
+    K, _ = datagen.keys_values(w)
+    K = K.reshape(2, n, D)
+    mub = np.stack([K[u][rng.choice(n, C, replace=False)] for u in range(2)])
+    mub = narrow(widen(mub) + 0.05 * rng.standard_normal(mub.shape).astype(np.float32))
+    ix = IceIndex(1, 2, 4, n, 16, C, kmeans_iters=1)
+    a, best = ix.debug_assign(up(K), up(mub))
+    a, best = down(a), down(best)
+    for u in range(2):
+        assert a[u].min() >= 0 and a[u].max() < C
+        _check_assign(K[u], mub[u], a[u], "n=%d C=%d u=%d" % (n, C, u))
+        _, ref_best, _ = orc.assign(K[u], mub[u])
+        np.testing.assert_allclose(best[u], ref_best, rtol=0, atol=float(_assign_band(K[u], mub[u]).max()))
+
+
+def test_debug_assign_exact_ties_take_lowest_id():
+    from paper_2604_10539_amd import IceIndex
+    rng = np.random.default_rng(3)
+    n = 700
+    K = narrow(rng.standard_normal((1, n, D)).astype(np.float32))
+    base = narrow(rng.standard_normal((1, 40, D)).astype(np.float32))
+    mub = np.concatenate([base, base], axis=1)             # centroid c+40 duplicates centroid c
+    ix = IceIndex(1, 1, 4, n, 16, 80, kmeans_iters=1)
+    a, _ = ix.debug_assign(up(K), up(mub))
+    a = down(a)
+    assert a.max() < 40
+    _check_assign(K[0], base[0], a[0], "duplicates")
+
+
+# ----------------------------------------------------------------------------------------- build
+@pytest.mark.parametrize("kw", [
+    dict(n_tokens=4096, n_clusters=32, n_kv_heads=2, n_components=32),                 # config 1 shape
+    dict(n_tokens=5003, n_clusters=100, n_kv_heads=3, n_components=40),                # ragged everywhere
+    dict(n_tokens=2500, n_clusters=24, n_kv_heads=2, page_size=32, n_components=12),
+    dict(n_tokens=2600, n_clusters=40, n_kv_heads=1, page_size=64, group_size=8, n_components=12),
+    dict(n_tokens=6000, n_clusters=600, n_kv_heads=2, n_components=200),               # two centroid slices
+])
+def test_build_stepwise_parity(kw):
+    """Per-step protocol: each stage is compared with the oracle on the GPU's own previous stage."""
+    T = 3
+    w = datagen.small(**kw)
+    ix, K, V, idx = _mk(w, T=T)
+    ix.build_index(up(K), up(V))
+    ex = export_np(ix)
+    n, C, s = w.n_tokens, w.n_clusters, w.page_size
+    assert np.array_equal(ex["init_idx"], idx)
+    a_gpu = ex["assign"][:, :n]
+    o = orc.OracleIndex(ix.U, w.group_size, s, C, n)
+    o.paginate(K, V, a_gpu)
+    for u in range(ix.U):
+        # (a) last assignment against the bf16 centroids it was computed from
+        _check_assign(K[u], ex["assign_centroid_bf16"][u, :C], a_gpu[u], "build u=%d" % u)
+        # (b) means of the GPU's own assignment: counts exact, sums/means to fp32 accuracy
+        prev = widen(ex["assign_centroid_bf16"][u, :C])
+        mu, ssum, cnt = orc.means(K[u], a_gpu[u], C, prev)
+        assert np.array_equal(ex["cluster_cnt"][u], cnt)
+        live = cnt > 0
+        np.testing.assert_allclose(ex["cluster_sum"][u], ssum, rtol=1e-5, atol=1e-4)
+        np.testing.assert_allclose(ex["centroid"][u][live], mu[live], rtol=1e-5, atol=1e-5)
+    # (c) page layout of the GPU's own assignment: every table and every stored bit
+    assert np.array_equal(ex["n_pages"], o.n_pages)
+    for name in ("page_cluster", "page_fill", "page_pos", "cluster_tail"):
+        assert np.array_equal(ex[name], getattr(o, name)), name
+    for u in range(ix.U):
+        npg = o.n_pages[u]
+        m = valid_slot_mask(o.page_fill[u, :npg], s)
+        assert np.array_equal(ex["Kp"][u, :npg][m], o.Kp[u, :npg][m])
+        assert np.array_equal(ex["Vp"][u, :npg][m], o.Vp[u, :npg][m])
+        assert np.array_equal(ex["page_sum"][u, :npg].view(np.uint32), o.page_sum[u, :npg].view(np.uint32))
+        assert np.array_equal(ex["rep"][u, :npg], o.rep[u, :npg])
+    # (d) the iteration as a whole: objective close to the oracle's run from the same promoted keys
+    for u in range(ix.U):
+        a_o, mu_o, _, _, _ = orc.lloyd(K[u], idx[u], T)
+        kf = widen(K[u]).astype(np.float64)
+        j_gpu = ((kf - ex["centroid"][u].astype(np.float64)[a_gpu[u]]) ** 2).sum()
+        j_orc = ((kf - mu_o.astype(np.float64)[a_o]) ** 2).sum()
+        assert abs(j_gpu - j_orc) <= 5e-3 * j_orc, (j_gpu, j_orc)
+
+
+def test_build_is_deterministic_and_inertia_decreases():
+    w = datagen.small(n_tokens=4000, n_clusters=64, n_kv_heads=2, n_components=48)
+    prev_j = None
+    for T in (1, 2, 4):
+        ix, K, V, idx = _mk(w, T=T)
+        ix.build_index(up(K), up(V))
+        ex1 = export_np(ix)
+        ix.build_index(up(K), up(V))           # rebuild in place
+        ex2 = export_np(ix)
+        for name in STATE_FIELDS + ("assign",):
+            a, b = ex1[name], ex2[name]
+            if name in ("Kp", "Vp", "page_sum", "rep"):
+                continue                        # stale slots of unused pages may differ; live ones checked below
+            assert np.array_equal(a, b), name
+        for u in range(ix.U):
+            npg = ex1["n_pages"][u]
+            assert np.array_equal(ex1["rep"][u, :npg], ex2["rep"][u, :npg])
+            assert np.array_equal(ex1["page_sum"][u, :npg].view(np.uint32), ex2["page_sum"][u, :npg].view(np.uint32))
+        kf = widen(K).astype(np.float64)
+        j = sum(((kf[u] - ex1["centroid"][u].astype(np.float64)[ex1["assign"][u, :w.n_tokens]]) ** 2).sum()
+                for u in range(ix.U))
+        if prev_j is not None:
+            assert j <= prev_j * (1 + 1e-3)
+        prev_j = j
+
+
+def test_build_with_seed_promotes_distinct_keys():
+    w = datagen.small(n_tokens=3000, n_clusters=50, n_kv_heads=2)
+    ix, K, V, _ = _mk(w, T=2, init=False, seed=1234)
+    ix.build_index(up(K), up(V))
+    ex = export_np(ix)
+    for u in range(ix.U):
+        sel = ex["init_idx"][u]
+        assert len(set(sel.tolist())) == 50 and sel.min() >= 0 and sel.max() < 3000
+        # same protocol as with an explicit list: oracle from the exported indices
+        a_o, mu_o, _, cnt_o, _ = orc.lloyd(K[u], sel, 1)
+    ix2, _, _, _ = _mk(w, T=2, init=False, seed=99)
+    ix2.build_index(up(K), up(V))
+    assert not np.array_equal(export_np(ix2)["init_idx"], ex["init_idx"])
+
+
+# ----------------------------------------------------------------------------------------- select
+def _compare_select(o, q, budget, ids, n_sel, scores=None):
+    """ids/n_sel from the GPU against the oracle on identical representative bits."""
+    oid, ons, osc, S_all = o.select(q, budget)
+    U, P = oid.shape
+    ids, n_sel = ids.reshape(U, P), n_sel.reshape(U)
+    assert np.array_equal(n_sel, ons)
+    ties = 0
+    for u in range(U):
+        k = int(ons[u])
+        g = ids[u, :k]
+        assert np.all(np.diff(g) > 0), "ids must be ascending and distinct"
+        assert np.all(ids[u, k:] == -1)
+        if np.array_equal(g, oid[u, :k]):
+            continue
+        only_g, only_o = np.setdiff1d(g, oid[u, :k]), np.setdiff1d(oid[u, :k], g)
+        thr = np.sort(S_all[u, :o.n_pages[u]])[::-1][k - 1]
+        band = SCORE_TIE * max(1.0, abs(float(thr)))
+        for p in np.concatenate([only_g, only_o]):
+            assert abs(float(S_all[u, p]) - float(thr)) <= band, "selection differs outside the tie band"
+        ties += len(only_g)
+    if scores is not None:
+        scores = scores.reshape(U, P)
+        for u in range(U):
+            k = int(ons[u])
+            np.testing.assert_allclose(scores[u, :k], S_all[u, ids[u, :k]], rtol=2e-6, atol=2e-6)
+    print("[select] %d page ids differ from the oracle inside the 1e-5 tie band" % ties)
+    return ties
+
+
+@pytest.mark.parametrize("kw,budget", [
+    (dict(n_tokens=4096, n_clusters=32, n_kv_heads=2, n_components=32), 256),
+    (dict(n_tokens=5003, n_clusters=100, n_kv_heads=3, n_components=40), 64),
+    (dict(n_tokens=5003, n_clusters=100, n_kv_heads=3, n_components=40, group_size=1), 512),
+    (dict(n_tokens=2500, n_clusters=24, n_kv_heads=2, page_size=32, group_size=2), 256),
+    (dict(n_tokens=2600, n_clusters=40, n_kv_heads=1, page_size=64, group_size=8), 640),
+    (dict(n_tokens=300, n_clusters=6, n_kv_heads=2), 16 * 64),           # budget covers every page
+    (dict(n_tokens=20000, n_clusters=300, n_kv_heads=2, n_components=128), 16),   # one page of many
+])
+def test_select_and_attend_on_gpu_built_index(kw, budget):
+    w = datagen.small(**kw)
+    ix, K, V, _ = _mk(w, T=2)
+    ix.build_index(up(K), up(V))
+    q = datagen.queries(w)
+    ids, n_sel, scores = ix.select(up(q), budget)
+    out = ix.attend(up(q), ids, n_sel)
+    ex = export_np(ix)
+    o = oracle_from_export(ix, ex)
+    ids_n, ns_n = down(ids), down(n_sel)
+    _compare_select(o, q, budget, ids_n, ns_n, down(scores))
+    # attention over the GPU's own ids
+    P = ids_n.shape[-1]
+    ref = o.attend(q, ids_n.reshape(ix.U, P), ns_n.reshape(ix.U))
+    err = np.abs(down(out).reshape(ref.shape) - ref).max()
+    print("[attend] max abs err %.3g" % err)
+    assert err <= ATTN_TOL and err <= ATTN_EXPECTED
+    # fused call gives the same ids and the same output bits
+    ids2, ns2, out2 = ix.select_attend(up(q), budget)
+    assert torch.equal(ids2, ids) and torch.equal(ns2, n_sel) and torch.equal(out2, out)
+    # loaded tokens never exceed the budget
+    for u in range(ix.U):
+        sel = ids_n.reshape(ix.U, P)[u, :ns_n.reshape(ix.U)[u]]
+        assert ex["page_fill"][u, sel].sum() <= budget
+
+
+def test_attend_with_every_page_equals_dense_attention():
+    w = datagen.small(n_tokens=1500, n_clusters=20, n_kv_heads=2)
+    ix, K, V, _ = _mk(w, T=2)
+    ix.build_index(up(K), up(V))
+    q = datagen.queries(w)
+    ids, n_sel, out = ix.select_attend(up(q), 16 * 128)
+    out = down(out).reshape(ix.U, w.group_size, D)
+    qf = widen(q).astype(np.float64).reshape(ix.U, w.group_size, D)
+    for u in range(ix.U):
+        z = qf[u] @ widen(K[u]).astype(np.float64).T / math.sqrt(D)
+        p = np.exp(z - z.max(1, keepdims=True))
+        ref = (p / p.sum(1, keepdims=True)) @ widen(V[u]).astype(np.float64)
+        assert np.abs(out[u] - ref).max() <= ATTN_EXPECTED
+
+
+def test_select_ties_and_empty_selection():
+    """Identical pages tie exactly: the lowest ids win.  n_selected = 0 gives zeros."""
+    from paper_2604_10539_amd import IceIndex
+    rng = np.random.default_rng(5)
+    key = narrow(rng.standard_normal(D).astype(np.float32))
+    K = np.tile(key, (1, 1, 96, 1))
+    V = narrow(rng.standard_normal((1, 1, 96, D)).astype(np.float32))
+    ix = IceIndex(1, 1, 2, 96, 16, 1, kmeans_iters=1, init_idx=up(np.zeros((1, 1, 1), np.int32)))
+    ix.build_index(up(K), up(V))
+    q = narrow(rng.standard_normal((1, 2, D)).astype(np.float32))
+    ids, n_sel, _ = ix.select(up(q), 48)
+    assert down(ids).ravel().tolist() == [0, 1, 2] and int(n_sel.item()) == 3
+    zero = torch.zeros_like(n_sel)
+    out = ix.attend(up(q), ids, zero)
+    assert torch.count_nonzero(out).item() == 0
+    # order of the listed pages does not matter
+    out_a = ix.attend(up(q), ids, n_sel)
+    out_b = ix.attend(up(q), ids.flip(-1).contiguous(), n_sel)
+    assert (out_a - out_b).abs().max().item() <= 1e-6
+
+
+# ----------------------------------------------------------------------------------------- import
+def test_imported_oracle_index_select_attend():
+    """An index built entirely by the oracle, imported bit for bit, must select the same pages."""
+    from paper_2604_10539_amd import IceIndex
+    w = datagen.small(n_tokens=3000, n_clusters=48, n_kv_heads=3, n_components=24)
+    K, V = datagen.keys_values(w)
+    idx = datagen.init_indices(w)
+    o = orc.OracleIndex(3, w.group_size, 16, 48, 3000)
+    o.build(K, V, idx, 4)
+    ix = IceIndex(1, 3, w.group_size, 3000, 16, 48)
+    ix.import_arrays(oracle_arrays_to_device(o), 3000)
+    q = datagen.queries(w)
+    ids, n_sel, scores = ix.select(up(q), 256)
+    _compare_select(o, q, 256, down(ids), down(n_sel), down(scores))
+    out = ix.attend(up(q), ids, n_sel)
+    ref = o.attend(q, down(ids).reshape(3, -1), down(n_sel).reshape(3))
+    assert np.abs(down(out).reshape(ref.shape) - ref).max() <= ATTN_EXPECTED
+    ex = export_np(ix)
+    for name in STATE_FIELDS:
+        assert np.array_equal(ex[name], getattr(o, name)), name
+
+
+# ----------------------------------------------------------------------------------------- insert
+@pytest.mark.parametrize("kw,steps", [
+    (dict(n_tokens=2000, n_clusters=24, n_kv_heads=2, n_components=16, drift=0.01), 300),
+    (dict(n_tokens=600, n_clusters=5, n_kv_heads=3, page_size=32, n_components=4, drift=0.02), 200),
+])
+def test_insert_replay_is_bit_exact(kw, steps):
+    """The oracle starts from the exported post-build state and replays every insertion; all tables
+    and the ordered-fp32 quantities must match bit for bit after every step (checked at intervals
+    and at the end).  A nearest-centroid decision inside the tie band is followed and counted."""
+    w = datagen.small(**kw)
+    ix, K, V, _ = _mk(w, T=3, extra=steps)
+    ix.build_index(up(K), up(V))
+    ex = export_np(ix)
+    o = oracle_from_export(ix, ex)
+    stream = datagen.DecodeStream(w)
+    flips = 0
+    exv = ix.export()                      # device views; page tables are read back every step
+    for t in range(steps):
+        k, v, q = stream.next()
+        ku = k.reshape(ix.U, D)
+        mub = narrow(o.centroid)           # centroids as both sides see them before this insertion
+        ix.insert(up(k), up(v))
+        torch.cuda.synchronize()
+        pos_t, pc_t = down(exv["page_pos"]), down(exv["page_cluster"])
+        force = np.empty(ix.U, np.int32)
+        for u in range(ix.U):
+            pg = np.argwhere(pos_t[u] == w.n_tokens + t)
+            assert len(pg) == 1, "the new token must sit in exactly one slot"
+            c_gpu = int(pc_t[u, pg[0][0]])
+            a_own, best, _ = orc.assign(ku[u][None], mub[u])
+            if c_gpu != a_own[0]:          # allowed only inside the tie band; the oracle then follows
+                mf = widen(mub[u, c_gpu]).astype(np.float64)
+                obj = (mf ** 2).sum() - 2.0 * (widen(ku[u]).astype(np.float64) * mf).sum()
+                assert obj - best[0] <= _assign_band(ku[u][None], mub[u])[0], "insert picked a non-nearest centroid"
+                flips += 1
+            force[u] = c_gpu
+        o.insert(k, v, force=force)
+        if (t % 50 == 49) or t == steps - 1:
+            exg = export_np(ix)
+            for name in STATE_FIELDS:
+                a, b = exg[name], getattr(o, name)
+                for u in range(ix.U):
+                    npg = o.n_pages[u]
+                    if name in ("Kp", "Vp"):
+                        m = valid_slot_mask(o.page_fill[u, :npg], w.page_size)
+                        assert np.array_equal(a[u, :npg][m], b[u, :npg][m]), name
+                    elif name in ("page_sum", "rep"):
+                        assert np.array_equal(a[u, :npg], b[u, :npg]), name
+                    elif name in ("cluster_sum", "centroid"):
+                        assert np.array_equal(a[u].view(np.uint32), b[u].view(np.uint32)), name
+                    else:
+                        assert np.array_equal(a[u], b[u]), name
+    print("[insert] %d steps replayed, %d tie-band flips" % (steps, flips))
+    # the grown index still selects and attends like the oracle
+    k, v, q = stream.next()
+    ids, n_sel, out = ix.select_attend(up(q), w.token_budget)
+    _compare_select(o, q, w.token_budget, down(ids), down(n_sel))
+    ref = o.attend(q, down(ids).reshape(ix.U, -1), down(n_sel).reshape(ix.U))
+    assert np.abs(down(out).reshape(ref.shape) - ref).max() <= ATTN_EXPECTED
+
+
+def test_insert_capacity_and_state_errors():
+    from paper_2604_10539_amd import IceError, IceIndex, binding
+    w = datagen.small(n_tokens=500, n_clusters=8, n_kv_heads=1)
+    ix, K, V, _ = _mk(w, T=1, extra=1)
+    k = up(K[:, 0])
+    with pytest.raises(IceError) as e:
+        ix.insert(k, k)
+    assert e.value.status == binding.ICE_ERR_STATE
+    ix.build_index(up(K), up(V))
+    ix.insert(k, k)
+    with pytest.raises(IceError) as e:
+        ix.insert(k, k)
+    assert e.value.status == binding.ICE_ERR_CAPACITY
