@@ -10,8 +10,9 @@ launches) is reported beside it, together with the index build (clustering) and 
 the roofline of the dominant kernel and the CPU oracle timed on the host cores.
 
 All inputs are seeded synthetic data (datagen.py) resident in HBM before the timed region.  Between
-timed steps a 1 GiB buffer is overwritten (untimed) so that no step finds its index in the
-256 MB memory-side cache: every figure labelled "cold" is an HBM figure.
+timed steps a 1 GiB buffer is READ (untimed) so that no step finds its index in L2 or in the 256 MB
+memory-side cache: every figure labelled "cold" is an HBM figure.  (Reading rather than writing the
+buffer leaves clean lines behind; dirty lines would add write-back traffic to the timed kernel.)
 """
 from __future__ import annotations
 
@@ -114,7 +115,7 @@ def main():
     # ---------------------------------------------------------------- algorithmic bytes of one step
     # select: every live representative row (256 B) + the G query rows + the ids written;
     # attend: valid K and V rows of the selected pages + the fp32 outputs.
-    flush = torch.empty(1 << 30, dtype=torch.uint8, device=dev)
+    flush = torch.zeros(1 << 28, dtype=torch.int32, device=dev)       # 1 GiB, read between timed steps
     ids_b = torch.empty((L, H, P), dtype=torch.int32, device=dev)
     ns_b = torch.empty((L, H), dtype=torch.int32, device=dev)
     out_b = torch.empty((L, H * G, D), dtype=torch.float32, device=dev)
@@ -129,22 +130,24 @@ def main():
     bytes_step = bytes_select + bytes_attend
 
     def timed(fn, steps, warmup, cold=True):
+        """ms per step.  All steps are enqueued without host round trips (flush, event, step, event),
+        so the events bracket GPU execution of the step only; one synchronisation at the end."""
         for i in range(warmup):
             if cold:
-                flush.fill_(i & 0xFF)
+                flush.sum()
             fn()
         torch.cuda.synchronize()
-        tot = 0.0
+        evs = []
         for i in range(steps):
             if cold:
-                flush.fill_(i & 0xFF)       # untimed: evicts L2 and the memory-side cache
+                flush.sum()                 # untimed: evicts L2 and the memory-side cache
             a, b = ev(), ev()
             a.record(st)
             fn()
             b.record(st)
-            torch.cuda.synchronize()
-            tot += a.elapsed_time(b)
-        return tot / steps                  # ms per step
+            evs.append((a, b))
+        torch.cuda.synchronize()
+        return sum(a.elapsed_time(b) for a, b in evs) / steps
 
     cold = not args.warm
     # ---------------------------------------------------------------- batched: 256 units per launch set
@@ -231,7 +234,7 @@ def main():
         "effective_GBps": gbps,
         "bytes_per_step": bytes_step,
         "hbm_frac": gbps / HBM_PEAK_GBPS,
-        "roofline": {"bound": "hbm", "kernel": "ice_select (score_kernel + select_kernel), 256 units per launch",
+        "roofline": {"bound": "hbm", "kernel": "decode_step_kernel (score + top-P, no attention), 256 units per launch",
                      "achieved": sel_gbps, "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": sel_gbps / HBM_PEAK_GBPS,
                      "traffic": None, "algorithmic_bytes_per_launch": bytes_select, "us_per_launch": ms_sel * 1e3},
         "attend": {"us_per_launch": ms_att * 1e3, "GBps": bytes_attend / (ms_att * 1e-3) / 1e9,

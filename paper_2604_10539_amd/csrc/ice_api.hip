@@ -86,9 +86,8 @@ size_t lay_out(const ice_config_t &cfg, int s, int C, char *base, Dev *out) {
     d.chunk_hist = (int *)take(U * n_chunks * CP * 4);
     d.cluster_start = (int *)take(U * (CP + 1) * 4);
     d.page_base = (int *)take(U * (CP + 1) * 4);
-    d.scores = (float *)take(U * MP * 4);
-    d.sel_ids = (int *)take(U * MP * 4);
-    d.sel_n = (int *)take(U * 4);
+    d.scores = (uint32_t *)take(U * MP * 4);
+    d.counter = (int *)take(U * 4);
     if (out) *out = d;
     return off;
 }
@@ -114,6 +113,14 @@ ice_status_t device_status(const char *what) {
 __global__ void fill_i32_kernel(int *p, int n, int v) {
     const int i = blockIdx.x * blockDim.x + threadIdx.x;
     if (i < n) p[i] = v;
+}
+
+// token counters, arrival counters and the empty marks of the score slots
+void reset_decode_state(const Dev &d, int n_tokens, hipStream_t s) {
+    hipLaunchKernelGGL(fill_i32_kernel, dim3((d.U + 255) / 256), dim3(256), 0, s, d.n_tokens, d.U, n_tokens);
+    hipLaunchKernelGGL(fill_i32_kernel, dim3((d.U + 255) / 256), dim3(256), 0, s, d.counter, d.U, 0);
+    const int ns = d.U * d.max_pages;
+    hipLaunchKernelGGL(fill_i32_kernel, dim3((ns + 255) / 256), dim3(256), 0, s, (int *)d.scores, ns, -1);
 }
 
 }  // namespace
@@ -177,7 +184,7 @@ ice_status_t ice_build_index(ice_index_t *ix, const void *K, const void *V, int3
         cur ^= 1;
     }
     launch_paginate(d, Kb, Vb, n, s);
-    hipLaunchKernelGGL(fill_i32_kernel, dim3((d.U + 255) / 256), dim3(256), 0, s, d.n_tokens, d.U, n);
+    reset_decode_state(d, n, s);
     if (ice_status_t st = device_status("ice_build_index")) return st;
     ix->cur = cur;
     ix->n_tokens = n;
@@ -205,14 +212,21 @@ static ice_status_t check_select(ice_index_t *ix, const void *q, int32_t budget,
     if (!q || !aligned16(q)) return fail(ICE_ERR_INVALID_ARG, "q is null or misaligned");
     if (!ids || !n_sel) return fail(ICE_ERR_INVALID_ARG, "page_ids or n_selected is null");
     if (budget < ix->dev.s) return fail(ICE_ERR_SHAPE, "token_budget %d is below page_size %d", budget, ix->dev.s);
+    if (ix->dev.max_pages > decode_step_max_pages(ix->dev.G))
+        return fail(ICE_ERR_UNSUPPORTED, "%d pages per unit exceed the selection kernel's limit of %d", ix->dev.max_pages,
+                    decode_step_max_pages(ix->dev.G));
+    if (decode_step_lds_bytes(ix->dev, budget / ix->dev.s) > 160u * 1024u - 64u)
+        return fail(ICE_ERR_UNSUPPORTED, "token_budget %d needs more LDS than a CU has for the candidate list "
+                    "(a budget that covers max_pages is always accepted)", budget);
     return ICE_OK;
 }
 
 ice_status_t ice_select(ice_index_t *ix, const void *q, int32_t budget, int32_t *ids, int32_t *n_sel, float *scores,
                         void *stream) {
     if (ice_status_t st = check_select(ix, q, budget, ids, n_sel, "ice_select")) return st;
-    launch_select(ix->dev, static_cast<const bf16_t *>(q), budget / ix->dev.s, ids, n_sel, scores,
-                  static_cast<hipStream_t>(stream));
+    launch_decode_step(ix->dev, static_cast<const bf16_t *>(q), budget / ix->dev.s, ix->n_tokens / ix->dev.s + ix->dev.C,
+                       ids, n_sel, scores, nullptr,
+                       static_cast<hipStream_t>(stream));
     return device_status("ice_select");
 }
 
@@ -233,8 +247,8 @@ ice_status_t ice_select_attend(ice_index_t *ix, const void *q, int32_t budget, i
     if (!out) return fail(ICE_ERR_INVALID_ARG, "out is null");
     const int P = budget / ix->dev.s;
     hipStream_t s = static_cast<hipStream_t>(stream);
-    launch_select(ix->dev, static_cast<const bf16_t *>(q), P, ids, n_sel, nullptr, s);
-    launch_attend(ix->dev, static_cast<const bf16_t *>(q), ids, n_sel, P, out, s);
+    launch_decode_step(ix->dev, static_cast<const bf16_t *>(q), P, ix->n_tokens / ix->dev.s + ix->dev.C, ids, n_sel, nullptr,
+                       out, s);
     return device_status("ice_select_attend");
 }
 
@@ -301,7 +315,7 @@ ice_status_t ice_import_index(ice_index_t *ix, const ice_index_view_t *v, void *
     copy(d.rep, v->rep, U * MP * kD * 2);
     copy(d.n_pages, v->n_pages, U * 4);
     if (e != hipSuccess) return fail(ICE_ERR_DEVICE, "ice_import_index: %s", hipGetErrorString(e));
-    hipLaunchKernelGGL(fill_i32_kernel, dim3((d.U + 255) / 256), dim3(256), 0, s, d.n_tokens, d.U, v->n_tokens);
+    reset_decode_state(d, v->n_tokens, s);
     ix->cur = 0;
     launch_refresh_centroids(d, 0, s);
     launch_refresh_centroids(d, 1, s);

@@ -5,7 +5,17 @@
 namespace ice {
 
 typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef unsigned v2u __attribute__((ext_vector_type(2)));
 typedef unsigned long long u64;
+#ifdef ICE_PROF
+__device__ long long ice_prof[16];
+#define ICE_STAMP(i) do { if (threadIdx.x == 0 && u == 0) ice_prof[i] = wall_clock64(); } while (0)
+#else
+#define ICE_STAMP(i) do { } while (0)
+#endif
+constexpr uint32_t kScoreEmpty = 0xFFFFFFFFu;  // a NaN pattern no score can take (scores come out of fmaxf)
 
 // a.lo*b.lo + a.hi*b.hi + c on packed bf16 pairs, fp32 accumulate (v_dot2_f32_bf16)
 __device__ inline float dot2(uint32_t a, uint32_t b, float c) {
@@ -95,269 +105,181 @@ void launch_insert(const Dev &d, const bf16_t *k, const bf16_t *v, int cur, hipS
 }
 
 // ------------------------------------------------------------------------------------------------
-// Representative scoring (Sec. 4.3-4.4; query normalisation of Eq. 3): for every live page p
-//   S[p] = max over the G query heads of the group of  (q_h . rep_p) / ||q_h||.
-// The representatives of a unit are one contiguous bf16 stream; a wave reads 1 KiB (four rows)
-// per load instruction, 16 lanes x 16 bytes per row, and reduces each row's partial dot products
-// inside its 16-lane DPP row.  The unit's pages are split over gridDim.x workgroups.
+// Sparse paged attention over a list of pages (Eq. 1 with the mask set on the tokens of the listed
+// pages), for one unit, by the NW waves of the calling workgroup.  Wave w streams pages w, w+NW, ...;
+// a page's key tile and value tile are each s x 256 contiguous bytes.  Per 16-token block:
+//   logits   one v_mfma_f32_16x16x32_bf16 chain, A = the G query rows, B = the 16 key rows (lane
+//            (g, r) reads bytes [64*ks + 16*g, +16) of key row r): lane r of row group 0 gets the
+//            logits of token r for heads 0..3 (group 1: heads 4..7);
+//   softmax  running maximum and denominator per head, shared by the whole wave (DPP row maxima),
+//            fp32; the 16 x G weights and the G rescale factors cross to the value layout via LDS;
+//   values   lane (g, c) holds 8 output dims of every head and reads value rows 4t+g, 16 bytes
+//            each (1 KiB per load instruction), fp32 FMAs.
+// The four row groups are summed at the end, the NW waves merged by the (max, sum, output) rule.
+// `list` may point to LDS or global memory; `red` is LDS scratch of attend_scratch_floats() floats.
+__host__ __device__ constexpr int attend_scratch_floats(int G, int NW) { return NW * (G * (kD + 2) + 16 * 8 + 8); }
+
 template <int G>
-__global__ __launch_bounds__(256) void score_kernel(Dev d, const bf16_t *__restrict__ q) {
-    const int u = blockIdx.y, tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+__device__ inline void load_query_operand(const bf16_t *q, int u, int lane, bf16x8 (&qa)[4], float *sumsq) {
     const int g = lane >> 4, ch = lane & 15;
-    const int np = d.n_pages[u];
-    const int per = round_up((np + gridDim.x - 1) / gridDim.x, 16);
-    const int p0 = blockIdx.x * per, p1 = min(np, p0 + per);
-    if (p0 >= p1) return;
-    uint4 qr[G];
-    float inv[G];
+    float nn = 0.f;
 #pragma unroll
-    for (int h = 0; h < G; ++h) {
-        qr[h] = ((const uint4 *)(q + ((size_t)u * G + h) * kD))[ch];
-        const float nn = row16_sum(dot8(qr[h], qr[h]));
-        inv[h] = 1.0f / fmaxf(sqrtf(nn), 1e-20f);
+    for (int ks = 0; ks < 4; ++ks) {
+        const uint4 w = ch < G ? ((const uint4 *)(q + ((size_t)u * G + ch) * kD))[ks * 4 + g] : make_uint4(0, 0, 0, 0);
+        qa[ks] = __builtin_bit_cast(bf16x8, w);
+        nn += dot8(w, w);
     }
-    const bf16_t *rep = d.rep + (size_t)u * d.max_pages * kD;
-    float *S = d.scores + (size_t)u * d.max_pages;
-    constexpr int UNR = 4;
-    for (int base = p0; base < p1; base += 64 * UNR / 4) {  // 64 pages per workgroup iteration
-        uint4 r[UNR];
-#pragma unroll
-        for (int x = 0; x < UNR; ++x) {
-            const int pp = base + 16 * x + wave * 4 + g;
-            r[x] = pp < p1 ? ((const uint4 *)(rep + (size_t)pp * kD))[ch] : make_uint4(0, 0, 0, 0);
-        }
-#pragma unroll
-        for (int x = 0; x < UNR; ++x) {
-            float sc = -INFINITY;
-#pragma unroll
-            for (int h = 0; h < G; ++h) sc = fmaxf(sc, row16_sum(dot8(r[x], qr[h])) * inv[h]);
-            const int pp = base + 16 * x + wave * 4 + g;
-            if (ch == 0 && pp < p1) S[pp] = sc;
-        }
-    }
+    if (sumsq) *sumsq = nn;
 }
 
-// ------------------------------------------------------------------------------------------------
-// Top-P page selection (Alg. 3 with pages ranked directly): exact radix select on the
-// order-preserving integer image of the fp32 scores finds the P-th largest score; pages above it,
-// plus the lowest-id pages equal to it, are written in ascending id order (ordered compaction).
-// One workgroup per unit; the scores are re-read from L2 in each of the four 8-bit passes.
-__global__ __launch_bounds__(1024) void select_kernel(Dev d, int P, int *__restrict__ ids_out,
-                                                       int *__restrict__ n_sel_out, float *__restrict__ scores_out) {
-    __shared__ int hist[256];
-    __shared__ int wtot[16];
-    __shared__ uint32_t sh_prefix;
-    __shared__ int sh_kk, sh_base_eq, sh_base_out;
-    const int u = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int np = d.n_pages[u];
-    const int k = min(P, np);
-    const float *S = d.scores + (size_t)u * d.max_pages;
-    int *ids = ids_out + (size_t)u * P;
-    float *sco = scores_out ? scores_out + (size_t)u * P : nullptr;
-    for (int x = k + tid; x < P; x += 1024) {
-        ids[x] = -1;
-        if (sco) sco[x] = 0.f;
-    }
-    if (tid == 0) n_sel_out[u] = k;
-    if (k == 0) return;
-
-    uint32_t prefix = 0, mask = 0;
-    int kk = k;
-    for (int shift = 24; shift >= 0; shift -= 8) {
-        if (tid < 256) hist[tid] = 0;
-        __syncthreads();
-        for (int i = tid; i < np; i += 1024) {
-            const uint32_t key = f32_ordered(S[i]);
-            if ((key & mask) == prefix) atomicAdd(&hist[(key >> shift) & 255], 1);
-        }
-        __syncthreads();
-        // bins in descending order: thread t < 256 owns bin 255 - t
-        int h = 0, incl = 0;
-        if (tid < 256) {
-            h = hist[255 - tid];
-            incl = h;
-            for (int off = 1; off < 64; off <<= 1) {
-                const int t = __shfl_up(incl, off);
-                if (lane >= off) incl += t;
-            }
-            if (lane == 63) wtot[wave] = incl;
-        }
-        __syncthreads();
-        if (tid < 256) {
-            for (int w = 0; w < wave; ++w) incl += wtot[w];
-            const int excl = incl - h;
-            if (incl >= kk && excl < kk) {
-                sh_prefix = prefix | ((uint32_t)(255 - tid) << shift);
-                sh_kk = kk - excl;
-            }
-        }
-        __syncthreads();
-        prefix = sh_prefix;
-        kk = sh_kk;
-        mask |= 255u << shift;
-        __syncthreads();
-    }
-    // prefix = key of the k-th largest score; kk = how many pages equal to it are still wanted
-    if (tid == 0) { sh_base_eq = 0; sh_base_out = 0; }
-    __syncthreads();
-    for (int i0 = 0; i0 < np; i0 += 1024) {
-        const int i = i0 + tid;
-        uint32_t key = 0;
-        float sc = 0.f;
-        if (i < np) { sc = S[i]; key = f32_ordered(sc); }
-        const bool gt = i < np && key > prefix, eq = i < np && key == prefix;
-        // exclusive rank among the "equal" pages, in id order
-        const u64 beq = __ballot(eq);
-        if (lane == 0) wtot[wave] = (int)__popcll(beq);
-        __syncthreads();
-        int eqr = sh_base_eq + (int)__popcll(beq & ((1ull << lane) - 1ull));
-        int tot_eq = 0;
-        for (int w = 0; w < 16; ++w) { if (w < wave) eqr += wtot[w]; tot_eq += wtot[w]; }
-        const bool take = gt || (eq && eqr < kk);
-        __syncthreads();
-        const u64 bt = __ballot(take);
-        if (lane == 0) wtot[wave] = (int)__popcll(bt);
-        __syncthreads();
-        int pos = sh_base_out + (int)__popcll(bt & ((1ull << lane) - 1ull));
-        int tot_out = 0;
-        for (int w = 0; w < 16; ++w) { if (w < wave) pos += wtot[w]; tot_out += wtot[w]; }
-        if (take) {
-            ids[pos] = i;
-            if (sco) sco[pos] = sc;
-        }
-        __syncthreads();
-        if (tid == 0) { sh_base_eq += tot_eq; sh_base_out += tot_out; }
-        __syncthreads();
-    }
-}
-
-void launch_select(const Dev &d, const bf16_t *q, int P, int *ids, int *n_sel, float *scores_out, hipStream_t st) {
-    // split each unit's representatives over enough workgroups to occupy the 256 CUs
-    int chunks = (512 + d.U - 1) / d.U;
-    const int max_chunks = (d.max_pages + 63) / 64;
-    if (chunks > max_chunks) chunks = max_chunks;
-    if (chunks < 1) chunks = 1;
-    dim3 grid(chunks, d.U);
-    switch (d.G) {
-        case 1: hipLaunchKernelGGL(score_kernel<1>, grid, dim3(256), 0, st, d, q); break;
-        case 2: hipLaunchKernelGGL(score_kernel<2>, grid, dim3(256), 0, st, d, q); break;
-        case 4: hipLaunchKernelGGL(score_kernel<4>, grid, dim3(256), 0, st, d, q); break;
-        default: hipLaunchKernelGGL(score_kernel<8>, grid, dim3(256), 0, st, d, q); break;
-    }
-    hipLaunchKernelGGL(select_kernel, dim3(d.U), dim3(1024), 0, st, d, P, ids, n_sel, scores_out);
-}
-
-// ------------------------------------------------------------------------------------------------
-// Sparse paged attention (Eq. 1 with the mask set on the tokens of the selected pages).  One
-// workgroup of 16 waves per unit; wave w streams selected pages w, w+16, ...: a page's key tile
-// and value tile are each s x 256 contiguous bytes, read 1 KiB (four token rows) per load.  For
-// every 16-token block the G heads' logits are reduced inside 16-lane DPP rows, so each row group
-// of lanes runs its own online softmax (running max, denominator, 8 output dims per lane) over the
-// tokens it sees; the four row groups, then the 16 waves, are merged with the usual
-// (max, sum, weighted output) rule.  fp32 throughout, bf16 only as the storage format.
 template <int G, int NW>
-__global__ __launch_bounds__(NW * 64) void attend_kernel(Dev d, const bf16_t *__restrict__ q,
-                                                          const int *__restrict__ ids, const int *__restrict__ n_sel,
-                                                          int P, float *__restrict__ out) {
-    extern __shared__ __align__(16) char smem[];
-    float(*wacc)[G][kD] = (float(*)[G][kD])smem;                                  // [NW][G][128]
-    float(*wm)[G] = (float(*)[G])(smem + sizeof(float) * NW * G * kD);            // [NW][G]
-    float(*wl)[G] = (float(*)[G])(smem + sizeof(float) * NW * G * (kD + 1));      // [NW][G]
-    const int u = blockIdx.x, tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+__device__ inline void attend_pages(const Dev &d, int u, const bf16x8 (&qa)[4], const int *list, int ns,
+                                    float *__restrict__ out, float *red) {
+    constexpr int GR = (G + 3) / 4;  // row groups that hold logits
+    float(*wacc)[G][kD] = (float(*)[G][kD])red;                   // [NW][G][128]
+    float(*wm)[G] = (float(*)[G])(red + NW * G * kD);             // [NW][G]
+    float(*wl)[G] = (float(*)[G])(red + NW * G * (kD + 1));       // [NW][G]
+    const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
     const int g = lane >> 4, ch = lane & 15;
-    const int ns = min(n_sel[u], P);
+    float *px = red + NW * G * (kD + 2) + wave * (16 * 8 + 8);    // [16 tokens][8 heads] weights of this wave
+    float *al = px + 16 * 8;                                      // [8] rescale factors
     const float scale = 0.08838834764831845f;  // 1/sqrt(128)
-    uint4 qr[G];
-    float m[G], l[G], acc[G][8];
+    const int s = d.s;
+    float m[4], l[4], acc[G][8];
 #pragma unroll
-    for (int h = 0; h < G; ++h) {
-        qr[h] = ((const uint4 *)(q + ((size_t)u * G + h) * kD))[ch];
-        m[h] = -INFINITY;
-        l[h] = 0.f;
+    for (int v = 0; v < 4; ++v) { m[v] = -INFINITY; l[v] = 0.f; }
+#pragma unroll
+    for (int h = 0; h < G; ++h)
 #pragma unroll
         for (int j = 0; j < 8; ++j) acc[h][j] = 0.f;
-    }
-    const int s = d.s;
     for (int x = wave; x < ns; x += NW) {
-        const int p = ids[(size_t)u * P + x];
+        const int p = list[x];
         if ((unsigned)p >= (unsigned)d.max_pages) continue;  // not a page id: ignored
         const size_t pg = (size_t)u * d.max_pages + p;
-        const int fill = d.page_fill[pg];
-        for (int b0 = 0; b0 < fill; b0 += 16) {  // 16-token blocks of the page
-            uint4 kt[4], vt[4];
+        // the first 16-token block is fetched before the fill count is known (one fewer dependent
+        // round trip); slots >= fill may hold stale bytes and are masked after the load
+        uint4 kb[4], vt[4];
 #pragma unroll
-            for (int t = 0; t < 4; ++t) {
-                const int slot = b0 + 4 * t + g;  // < s; slots >= fill may hold stale bytes: not read
-                const bool valid = slot < fill;
-                kt[t] = valid ? ((const uint4 *)(d.Kp + (pg * s + slot) * kD))[ch] : make_uint4(0, 0, 0, 0);
-                vt[t] = valid ? ((const uint4 *)(d.Vp + (pg * s + slot) * kD))[ch] : make_uint4(0, 0, 0, 0);
+        for (int t = 0; t < 4; ++t) {
+            kb[t] = ((const uint4 *)(d.Kp + (pg * s + ch) * kD))[t * 4 + g];
+            vt[t] = ((const uint4 *)(d.Vp + (pg * s + 4 * t + g) * kD))[ch];
+        }
+        const int fill = d.page_fill[pg];
+        ICE_STAMP(8);
+        for (int b0 = 0; b0 < fill; b0 += 16) {
+            if (b0 > 0) {
+#pragma unroll
+                for (int t = 0; t < 4; ++t) {
+                    kb[t] = ((const uint4 *)(d.Kp + (pg * s + b0 + ch) * kD))[t * 4 + g];
+                    vt[t] = ((const uint4 *)(d.Vp + (pg * s + b0 + 4 * t + g) * kD))[ch];
+                }
             }
-            float z[G][4];
+            f32x4 z = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int ks = 0; ks < 4; ++ks)
+                z = __builtin_amdgcn_mfma_f32_16x16x32_bf16(qa[ks], __builtin_bit_cast(bf16x8, kb[ks]), z, 0, 0, 0);
+#ifdef ICE_PROF
+            if (threadIdx.x == 0 && u == 0 && z[0] != 12345.f) ice_prof[9] = wall_clock64();
+#endif
+            const bool tok_ok = b0 + ch < fill;  // this lane's logits belong to token b0 + ch
+            float pw[4], alpha[4];
+#pragma unroll
+            for (int v = 0; v < 4; ++v) {
+                const float zz = tok_ok ? z[v] * scale : -INFINITY;
+                float mx = zz;
+                mx = fmaxf(mx, dpp_f32<0xB1>(mx));
+                mx = fmaxf(mx, dpp_f32<0x4E>(mx));
+                mx = fmaxf(mx, dpp_f32<0x141>(mx));
+                mx = fmaxf(mx, dpp_f32<0x140>(mx));   // block maximum of head 4g+v on all 16 lanes of the row
+                const float mn = fmaxf(m[v], mx);     // finite: every live page has at least one token
+                alpha[v] = __expf(m[v] - mn);
+                pw[v] = __expf(zz - mn);
+                l[v] = l[v] * alpha[v] + pw[v];
+                m[v] = mn;
+            }
+            if (g < GR) {
+                *(float4 *)(px + ch * 8 + 4 * g) = make_float4(pw[0], pw[1], pw[2], pw[3]);
+                if (ch == 0) *(float4 *)(al + 4 * g) = make_float4(alpha[0], alpha[1], alpha[2], alpha[3]);
+            }
+            __builtin_amdgcn_wave_barrier();
+            float a[G];
+#pragma unroll
+            for (int h4 = 0; h4 < GR; ++h4) {
+                const float4 t4 = *(const float4 *)(al + 4 * h4);
+                a[4 * h4] = t4.x;
+                if (4 * h4 + 1 < G) a[4 * h4 + 1] = t4.y;
+                if (4 * h4 + 2 < G) a[4 * h4 + 2] = t4.z;
+                if (4 * h4 + 3 < G) a[4 * h4 + 3] = t4.w;
+            }
+#pragma unroll
+            for (int h = 0; h < G; ++h)
+#pragma unroll
+                for (int j = 0; j < 8; ++j) acc[h][j] *= a[h];
 #pragma unroll
             for (int t = 0; t < 4; ++t) {
                 const bool valid = b0 + 4 * t + g < fill;
+                const uint4 vv = valid ? vt[t] : make_uint4(0, 0, 0, 0);
+                const float v0 = bf16_lo(vv.x), v1 = bf16_hi(vv.x), v2 = bf16_lo(vv.y), v3 = bf16_hi(vv.y);
+                const float v4 = bf16_lo(vv.z), v5 = bf16_hi(vv.z), v6 = bf16_lo(vv.w), v7 = bf16_hi(vv.w);
+                float pr[G];
+#pragma unroll
+                for (int h4 = 0; h4 < GR; ++h4) {
+                    const float4 t4 = *(const float4 *)(px + (4 * t + g) * 8 + 4 * h4);
+                    pr[4 * h4] = t4.x;
+                    if (4 * h4 + 1 < G) pr[4 * h4 + 1] = t4.y;
+                    if (4 * h4 + 2 < G) pr[4 * h4 + 2] = t4.z;
+                    if (4 * h4 + 3 < G) pr[4 * h4 + 3] = t4.w;
+                }
 #pragma unroll
                 for (int h = 0; h < G; ++h) {
-                    const float dot = row16_sum(dot8(kt[t], qr[h]));
-                    z[h][t] = valid ? dot * scale : -INFINITY;
-                }
-            }
-            float pw[G][4];
-#pragma unroll
-            for (int h = 0; h < G; ++h) {
-                const float mn = fmaxf(fmaxf(fmaxf(z[h][0], z[h][1]), fmaxf(z[h][2], z[h][3])), m[h]);
-                const float mm = mn == -INFINITY ? 0.f : mn;
-                const float alpha = __expf(m[h] - mm);
-                float ps = 0.f;
-#pragma unroll
-                for (int t = 0; t < 4; ++t) {
-                    pw[h][t] = __expf(z[h][t] - mm);
-                    ps += pw[h][t];
-                }
-                l[h] = l[h] * alpha + ps;
-                m[h] = mn;
-#pragma unroll
-                for (int j = 0; j < 8; ++j) acc[h][j] *= alpha;
-            }
-#pragma unroll
-            for (int t = 0; t < 4; ++t) {
-                const float v0 = bf16_lo(vt[t].x), v1 = bf16_hi(vt[t].x), v2 = bf16_lo(vt[t].y), v3 = bf16_hi(vt[t].y);
-                const float v4 = bf16_lo(vt[t].z), v5 = bf16_hi(vt[t].z), v6 = bf16_lo(vt[t].w), v7 = bf16_hi(vt[t].w);
-#pragma unroll
-                for (int h = 0; h < G; ++h) {
-                    const float pp = pw[h][t];
+                    const float pp = pr[h];
                     acc[h][0] = fmaf(pp, v0, acc[h][0]); acc[h][1] = fmaf(pp, v1, acc[h][1]);
                     acc[h][2] = fmaf(pp, v2, acc[h][2]); acc[h][3] = fmaf(pp, v3, acc[h][3]);
                     acc[h][4] = fmaf(pp, v4, acc[h][4]); acc[h][5] = fmaf(pp, v5, acc[h][5]);
                     acc[h][6] = fmaf(pp, v6, acc[h][6]); acc[h][7] = fmaf(pp, v7, acc[h][7]);
                 }
             }
+            __builtin_amdgcn_wave_barrier();  // the next block overwrites px / al
         }
     }
-    // merge the four row groups of the wave
+    ICE_STAMP(10);
+    // sum the four row groups (all share the wave's running maxima) with two rounds of lane-swap
+    // instructions: v_permlane32_swap exchanges the upper half of one register with the lower half
+    // of another, v_permlane16_swap the odd 16-lane rows with the even ones, so each swap+add
+    // folds two registers into one.  Of the N = 8G partial sums per lane, lane row r ends up with
+    // the complete sums number n + (N/4) r, n < N/4.
+    {
+        constexpr int N = 8 * G;
+        float R[N];
 #pragma unroll
-    for (int off = 16; off <= 32; off <<= 1) {
+        for (int h = 0; h < G; ++h)
 #pragma unroll
-        for (int h = 0; h < G; ++h) {
-            const float mo = __shfl_xor(m[h], off), lo = __shfl_xor(l[h], off);
-            const float mn = fmaxf(m[h], mo);
-            const float mm = mn == -INFINITY ? 0.f : mn;
-            const float a = __expf(m[h] - mm), b = __expf(mo - mm);
-            l[h] = l[h] * a + lo * b;
-            m[h] = mn;
+            for (int j = 0; j < 8; ++j) R[h * 8 + j] = acc[h][j];
 #pragma unroll
-            for (int j = 0; j < 8; ++j) acc[h][j] = acc[h][j] * a + __shfl_xor(acc[h][j], off) * b;
+        for (int n = 0; n < N / 2; ++n) {
+            const v2u r = __builtin_amdgcn_permlane32_swap(__float_as_uint(R[n]), __float_as_uint(R[n + N / 2]), false, false);
+            R[n] = __uint_as_float(r[0]) + __uint_as_float(r[1]);
+        }
+#pragma unroll
+        for (int n = 0; n < N / 4; ++n) {
+            const v2u r = __builtin_amdgcn_permlane16_swap(__float_as_uint(R[n]), __float_as_uint(R[n + N / 4]), false, false);
+            R[n] = __uint_as_float(r[0]) + __uint_as_float(r[1]);
+        }
+#pragma unroll
+        for (int n = 0; n < N / 4; ++n) {
+            const int idx = n + (N / 4) * g;
+            wacc[wave][idx >> 3][ch * 8 + (idx & 7)] = R[n];
         }
     }
-    if (g == 0) {
 #pragma unroll
-        for (int h = 0; h < G; ++h) {
-            if (ch == 0) { wm[wave][h] = m[h]; wl[wave][h] = l[h]; }
+    for (int v = 0; v < 4; ++v) l[v] = row16_sum(l[v]);
+    if (g < GR && ch == 0) {
 #pragma unroll
-            for (int j = 0; j < 8; ++j) wacc[wave][h][ch * 8 + j] = acc[h][j];
-        }
+        for (int v = 0; v < 4; ++v)
+            if (4 * g + v < G) { wm[wave][4 * g + v] = m[v]; wl[wave][4 * g + v] = l[v]; }
     }
     __syncthreads();
+    ICE_STAMP(11);
     for (int o = tid; o < G * kD; o += NW * 64) {
         const int h = o / kD, j = o % kD;
         float M = -INFINITY;
@@ -374,11 +296,22 @@ __global__ __launch_bounds__(NW * 64) void attend_kernel(Dev d, const bf16_t *__
     }
 }
 
+template <int G, int NW>
+__global__ __launch_bounds__(NW * 64) void attend_kernel(Dev d, const bf16_t *__restrict__ q,
+                                                          const int *__restrict__ ids, const int *__restrict__ n_sel,
+                                                          int P, float *__restrict__ out) {
+    extern __shared__ __align__(16) char smem[];
+    const int u = blockIdx.x;
+    bf16x8 qa[4];
+    load_query_operand<G>(q, u, threadIdx.x & 63, qa, nullptr);
+    attend_pages<G, NW>(d, u, qa, ids + (size_t)u * P, min(n_sel[u], P), out, (float *)smem);
+}
+
 void launch_attend(const Dev &d, const bf16_t *q, const int *ids, const int *n_sel, int P, float *out,
                    hipStream_t st) {
 #define ICE_ATTEND(g, nw)                                                                              \
-    hipLaunchKernelGGL((attend_kernel<g, nw>), dim3(d.U), dim3(nw * 64), sizeof(float) * nw * g * (kD + 2), st, d, q, \
-                       ids, n_sel, P, out)
+    hipLaunchKernelGGL((attend_kernel<g, nw>), dim3(d.U), dim3(nw * 64), sizeof(float) * attend_scratch_floats(g, nw), st, d, \
+                       q, ids, n_sel, P, out)
     switch (d.G) {
         case 1: ICE_ATTEND(1, 16); break;
         case 2: ICE_ATTEND(2, 16); break;
@@ -386,6 +319,348 @@ void launch_attend(const Dev &d, const bf16_t *q, const int *ids, const int *n_s
         default: ICE_ATTEND(8, 8); break;
     }
 #undef ICE_ATTEND
+}
+
+// ------------------------------------------------------------------------------------------------
+// One decode step for all units in ONE launch: score every page representative, pick the top-P
+// pages, attend over them (Sec. 4.3-4.4, Alg. 3, Eq. 1).
+//
+// Phase A, every workgroup: a unit's representatives are one contiguous bf16 stream, split over
+// `chunks` workgroups.  A wave reads 1 KiB (four rows) per load instruction, 16 lanes x 16 bytes per
+// row, reduces each row's partial dot products inside its 16-lane DPP row, and stores
+//   S[p] = max over the G query heads of (q_h . rep_p) / ||q_h||     (query normalisation of Eq. 3).
+// The workgroup then bumps the unit's arrival counter; the LAST one to arrive carries on alone.
+// Workgroup ids are mapped so that all chunks of a unit share (id mod 8), i.e. the same XCD and L2.
+//
+// Phase B, last workgroup of the unit: exact top-k over the composite key (score, lower id first),
+// all keys distinct.  Each wave finds the k-th largest of the keys it holds in registers with a
+// bitwise radix descent on wave ballots (no atomics, no barriers); the largest of these thresholds
+// cannot exceed the global k-th largest, so only keys at or above it (at most k per wave) go to an
+// LDS candidate list, where every candidate counts how many candidates beat it.  Rank < k wins;
+// winners are placed in ascending id order.
+//
+// Phase C, same workgroup: attention over the winners (attend_pages), ids never leave the chip.
+template <int G, int NW, int EMAX>
+__global__ __launch_bounds__(NW * 64) void decode_step_kernel(Dev d, const bf16_t *__restrict__ q, int P, int chunks, int np_hint,
+                                                               int *__restrict__ ids_out, int *__restrict__ n_sel_out,
+                                                               float *__restrict__ scores_out, float *__restrict__ out) {
+    constexpr int NT = NW * 64;
+    extern __shared__ __align__(16) char smem[];
+    __shared__ int sh_last, sh_M, sh_M2, sh_W;
+    __shared__ uint32_t sh_pre;
+    __shared__ u64 sh_tau;
+    const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+    const int g = lane >> 4, ch = lane & 15;
+    const int xcd = blockIdx.x & 7, r = blockIdx.x >> 3;
+    const int chunk = r % chunks, u = xcd + 8 * (r / chunks);
+    if (u >= d.U) return;
+    const int np = d.n_pages[u];  // first needed after the first loads are in flight
+    const bf16_t *rep = d.rep + (size_t)u * d.max_pages * kD;
+    uint32_t *S = d.scores + (size_t)u * d.max_pages;  // fp32 bits; kScoreEmpty = not written yet
+
+    if (chunk == 0) ICE_STAMP(0);
+    // ---- phase A: scores of this chunk, 16 pages per v_mfma_f32_16x16x32_bf16 chain.
+    // A operand = the G query rows (rows >= G are zero), B operand = 16 representative rows: lane
+    // (g = lane/16, r = lane%16) reads bytes [64*ks + 16*g, +16) of row r for k-step ks, i.e. one
+    // load instruction fetches a 64-byte piece of each of 16 consecutive 256-byte rows.  Lane r of
+    // row group 0 ends up with the dot products of page r with heads 0..3 (group 1: heads 4..7).
+    bf16x8 qa[4];
+    {
+        float nn;
+        load_query_operand<G>(q, u, lane, qa, &nn);
+        nn += __shfl_xor(nn, 16);
+        nn += __shfl_xor(nn, 32);  // ||q_h||^2 on every lane with lane%16 == h
+        const float invn = 1.0f / fmaxf(sqrtf(nn), 1e-20f);
+        float inv[4];
+#pragma unroll
+        for (int v = 0; v < 4; ++v) inv[v] = __shfl(invn, (4 * g + v) & 15);
+        const int per = round_up((np_hint + chunks - 1) / chunks, 16 * NW);
+        const int p0 = chunk * per, pend = min(np_hint, p0 + per);
+        const int nblk = (pend - p0 + 15) >> 4;
+        constexpr int UNR = 4;
+        int lim = pend;  // the first round of loads does not wait for np (np <= np_hint <= max_pages)
+        for (int b0 = wave; b0 < nblk; b0 += NW * UNR) {
+            uint4 bb[UNR][4];
+#pragma unroll
+            for (int x = 0; x < UNR; ++x) {
+                const int page = p0 + 16 * (b0 + NW * x) + ch;
+                const uint4 *src = (const uint4 *)(rep + (size_t)page * kD);
+#pragma unroll
+                for (int ks = 0; ks < 4; ++ks) bb[x][ks] = page < lim ? src[ks * 4 + g] : make_uint4(0, 0, 0, 0);
+            }
+            lim = min(np, pend);
+#pragma unroll
+            for (int x = 0; x < UNR; ++x) {
+                f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+                for (int ks = 0; ks < 4; ++ks)
+                    acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(qa[ks], __builtin_bit_cast(bf16x8, bb[x][ks]), acc, 0, 0, 0);
+                float sc = -INFINITY;
+#pragma unroll
+                for (int v = 0; v < 4; ++v)
+                    if (4 * g + v < G) sc = fmaxf(sc, acc[v] * inv[v]);
+                if (G > 4) sc = fmaxf(sc, __shfl_xor(sc, 16));
+                const int page = p0 + 16 * (b0 + NW * x) + ch;
+                if (g == 0 && page < lim)
+                    __hip_atomic_store(S + page, __float_as_uint(sc), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            }
+        }
+    }
+    // ---- arrival: count, and let the last workgroup of the unit go on.  No device-scope fence is
+    // used (on this chip it writes back / invalidates a whole L2, per workgroup): scores travel as
+    // device-scope atomic words, each slot doubles as its own ready flag (kScoreEmpty until written),
+    // and the reader re-reads a slot until it is filled.  Writers never wait, so the reader only ever
+    // waits for stores that were issued and completed (barrier below) before the counter moved.
+    __syncthreads();
+    if (tid == 0) {
+        const int old = __hip_atomic_fetch_add(d.counter + u, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        const int last = old == chunks - 1;
+        if (last) __hip_atomic_store(d.counter + u, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);  // next launch
+        sh_last = last;
+        sh_M = 0;
+        sh_W = 0;
+        sh_pre = 0u;
+        sh_tau = 0ull;
+    }
+    __syncthreads();
+    if (!sh_last) return;
+    ICE_STAMP(1);
+    auto read_score = [&](int pid) -> uint32_t {
+        uint32_t v = __hip_atomic_load(S + pid, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        for (int spin = 0; v == kScoreEmpty && spin < (1 << 16); ++spin)
+            v = __hip_atomic_load(S + pid, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        if (v == kScoreEmpty) {  // never expected; a fence bounds the wait
+            __threadfence();
+            v = __hip_atomic_load(S + pid, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        }
+        __hip_atomic_store(S + pid, kScoreEmpty, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);  // re-arm the slot
+        return v;
+    };
+
+    // ---- phase B: top-k pages
+    const int k = min(P, np);
+    int *ids = ids_out + (size_t)u * P;
+    float *sco = scores_out ? scores_out + (size_t)u * P : nullptr;
+    for (int x = k + tid; x < P; x += NT) {
+        ids[x] = -1;
+        if (sco) sco[x] = 0.f;
+    }
+    if (tid == 0) n_sel_out[u] = k;
+    const int Pk = min(P, d.max_pages);
+    int *sel_list = (int *)smem;                                  // [Pk] winners, ascending id
+    u64 *sel_comp = (u64 *)(smem + round_up(Pk * 4, 16));         // [Pk] winners by rank
+    char *region = smem + round_up(Pk * 4, 16) + (size_t)Pk * 8;  // candidates, later attention scratch
+    u64 *cand = (u64 *)region;
+    if (k == np) {
+        // budget covers every page
+        for (int x = tid; x < k; x += NT) {
+            const uint32_t v = read_score(x);
+            sel_list[x] = x;
+            ids[x] = x;
+            if (sco) sco[x] = __uint_as_float(v);
+        }
+    } else {
+        // B1: every wave finds the 16-bit prefix of the k-th largest key it holds (bitwise radix
+        // descent on wave ballots; the candidate sets live in scalar registers).  Keys below the
+        // largest such prefix cannot be among the k largest of the unit.
+        uint32_t key[EMAX];
+        u64 cm[EMAX];
+        int nvalid = 0;
+#pragma unroll
+        for (int e = 0; e < EMAX; ++e) {
+            const int pid = e * NT + tid;
+            const bool valid = pid < np;
+            key[e] = valid ? f32_ordered(__uint_as_float(read_score(pid))) : 0u;
+            cm[e] = __ballot(valid);
+            nvalid += (int)__popcll(cm[e]);
+        }
+        ICE_STAMP(2);
+        if (k <= 32) {
+            // the k-th largest of the 64 per-lane maxima is a lower bound of the wave's k-th largest
+            uint32_t lmax = key[0];
+#pragma unroll
+            for (int e = 1; e < EMAX; ++e) lmax = max(lmax, key[e]);
+            u64 m1 = cm[0];
+            if ((int)__popcll(m1) >= k) {  // (wave-uniform)
+                int kk = k;
+                uint32_t pre = 0;
+                for (int bit = 31; bit >= 12; --bit) {
+                    const u64 bm = __ballot((lmax >> bit) & 1u) & m1;
+                    const int cnt = (int)__popcll(bm);
+                    if (cnt >= kk) { pre |= 1u << bit; m1 = bm; }
+                    else { kk -= cnt; m1 ^= bm; }
+                }
+                if (lane == 0) atomicMax(&sh_pre, pre);
+            }
+        } else if (nvalid >= k) {  // (wave-uniform) otherwise every key of this wave stays a candidate
+            int kk = k;
+            uint32_t pre = 0;
+            for (int bit = 31; bit >= 16; --bit) {
+                u64 bm[EMAX];
+                int cnt = 0;
+#pragma unroll
+                for (int e = 0; e < EMAX; ++e) {
+                    bm[e] = __ballot((key[e] >> bit) & 1u) & cm[e];
+                    cnt += (int)__popcll(bm[e]);
+                }
+                if (cnt >= kk) {
+                    pre |= 1u << bit;
+#pragma unroll
+                    for (int e = 0; e < EMAX; ++e) cm[e] = bm[e];
+                } else {
+                    kk -= cnt;
+#pragma unroll
+                    for (int e = 0; e < EMAX; ++e) cm[e] ^= bm[e];
+                }
+            }
+            if (lane == 0) atomicMax(&sh_pre, pre);
+        }
+        __syncthreads();
+        const uint32_t pre = sh_pre;
+        ICE_STAMP(3);
+        // B2: candidates = (score key, ~page id) composites at or above the prefix; all distinct
+#pragma unroll
+        for (int e = 0; e < EMAX; ++e) {
+            const int pid = e * NT + tid;
+            const bool is = pid < np && key[e] >= pre;
+            const u64 bal = __ballot(is);
+            int base = 0;
+            if (lane == 0 && bal) base = atomicAdd(&sh_M, (int)__popcll(bal));
+            base = __shfl(base, 0);
+            if (is) cand[base + (int)__popcll(bal & ((1ull << lane) - 1ull))] = ((u64)key[e] << 32) | (u64)(0xFFFFFFFFu - (uint32_t)pid);
+        }
+        __syncthreads();
+        const int M = sh_M;  // >= k
+        ICE_STAMP(4);
+#ifdef ICE_PROF
+        if (tid == 0 && u == 0) ice_prof[15] = M;
+#endif
+        // B3: the k winners among the M candidates, exactly, into sel_comp[0..k)
+        if (M <= 256) {
+            // every candidate counts the candidates that beat it; `parts` lanes share one candidate
+            int lp = 0;
+            while (lp < 6 && (M << (lp + 1)) <= NT) ++lp;
+            const int parts = 1 << lp, i = tid >> lp, part = tid & (parts - 1), len = (M + parts - 1) >> lp;
+            const u64 mine = i < M ? cand[i] : ~0ull;
+            int rank = 0;
+            for (int j = part * len; j < min(M, (part + 1) * len); ++j) rank += cand[j] > mine;
+            for (int off = 1; off < parts; off <<= 1) rank += __shfl_xor(rank, off);
+            if (part == 0 && i < M && rank < k) sel_comp[rank] = mine;
+        } else {
+            // radix select on LDS histograms, 8 bits a pass, over the (32 + nb)-bit packed composite
+            int nb = 0;
+            while ((1 << nb) < np) ++nb;
+            const u64 idmask = (1ull << nb) - 1ull;
+            int *hist = (int *)(cand + M);          // 256 bins + 4 wave totals, behind the candidates
+            u64 prefix = 0ull, known = 0ull;
+            int kk = k;
+            for (int sft = ((32 + nb - 1) / 8) * 8; sft >= 0; sft -= 8) {
+                if (tid < 256) hist[tid] = 0;
+                __syncthreads();
+                for (int t = tid; t < M; t += NT) {
+                    const u64 cc = cand[t];
+                    const u64 pk = ((cc >> 32) << nb) | (cc & idmask);
+                    if ((pk & known) == prefix) atomicAdd(&hist[(int)((pk >> sft) & 255ull)], 1);
+                }
+                __syncthreads();
+                int h = 0, incl = 0;
+                if (tid < 256) {  // bins in descending order: thread t owns bin 255 - t
+                    h = hist[255 - tid];
+                    incl = h;
+                    for (int off = 1; off < 64; off <<= 1) {
+                        const int t2 = __shfl_up(incl, off);
+                        if (lane >= off) incl += t2;
+                    }
+                    if (lane == 63) hist[256 + wave] = incl;
+                }
+                __syncthreads();
+                if (tid < 256) {
+                    for (int w2 = 0; w2 < wave; ++w2) incl += hist[256 + w2];
+                    const int excl = incl - h;
+                    if (incl >= kk && excl < kk) {
+                        sh_tau = prefix | ((u64)(255 - tid) << sft);
+                        sh_M2 = kk - excl;
+                    }
+                }
+                __syncthreads();
+                prefix = sh_tau;
+                kk = sh_M2;
+                known |= 255ull << sft;
+                __syncthreads();
+            }
+            // prefix = packed composite of the k-th largest candidate; everything at or above it wins
+            for (int t = tid; t < M; t += NT) {
+                const u64 cc = cand[t];
+                const u64 pk = ((cc >> 32) << nb) | (cc & idmask);
+                if (pk >= prefix) sel_comp[atomicAdd(&sh_W, 1)] = cc;
+            }
+        }
+        __syncthreads();
+        ICE_STAMP(5);
+        // B4: the winners' places in ascending id order
+        for (int t = tid; t < k; t += NT) {
+            const u64 mine = sel_comp[t];
+            const uint32_t myid = 0xFFFFFFFFu - (uint32_t)mine;
+            int pos = 0;
+            for (int j = 0; j < k; ++j) pos += (0xFFFFFFFFu - (uint32_t)sel_comp[j]) < myid;
+            sel_list[pos] = (int)myid;
+            ids[pos] = (int)myid;
+            if (sco) sco[pos] = ordered_f32((uint32_t)(mine >> 32));
+        }
+    }
+    if (!out) return;
+    __syncthreads();
+    ICE_STAMP(6);
+    // ---- phase C: attention over the winners
+    attend_pages<G, NW>(d, u, qa, sel_list, k, out, (float *)region);
+    ICE_STAMP(7);
+}
+#ifdef ICE_PROF
+}  // namespace ice
+extern "C" int ice_debug_prof(long long *host16) {
+    return (int)hipMemcpyFromSymbol(host16, HIP_SYMBOL(ice::ice_prof), sizeof(long long) * 16);
+}
+namespace ice {
+#endif
+
+size_t decode_step_lds_bytes(const Dev &d, int P);
+
+void launch_decode_step(const Dev &d, const bf16_t *q, int P, int np_hint, int *ids, int *n_sel, float *scores_out,
+                        float *out, hipStream_t st) {
+    const int NW = d.G == 8 ? 8 : 16;
+    // a workgroup pass scores 16*NW pages per load round; few units -> split each unit over many
+    // workgroups (one round each), many units -> one workgroup per unit and no cross-workgroup step
+    if (np_hint > d.max_pages) np_hint = d.max_pages;
+    if (np_hint < 1) np_hint = 1;
+    int chunks = 256 / d.U;
+    const int max_chunks = (np_hint + 16 * NW - 1) / (16 * NW);
+    if (chunks > max_chunks) chunks = max_chunks;
+    if (chunks < 1) chunks = 1;
+    const size_t lds = decode_step_lds_bytes(d, P);
+    const int grid = round_up(d.U, 8) * chunks;
+    const int E = (d.max_pages + NW * 64 - 1) / (NW * 64);
+#define ICE_STEP(g, nw, e)                                                                                          \
+    do {                                                                                                            \
+        (void)hipFuncSetAttribute((const void *)decode_step_kernel<g, nw, e>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds); \
+        hipLaunchKernelGGL((decode_step_kernel<g, nw, e>), dim3(grid), dim3(nw * 64), lds, st, d, q, P, chunks, np_hint, ids, \
+                           n_sel, scores_out, out);                                                                 \
+    } while (0)
+    if (d.G == 8) { if (E <= 8) ICE_STEP(8, 8, 8); else ICE_STEP(8, 8, 32); }
+    else if (d.G == 4) { if (E <= 4) ICE_STEP(4, 16, 4); else ICE_STEP(4, 16, 16); }
+    else if (d.G == 2) { if (E <= 4) ICE_STEP(2, 16, 4); else ICE_STEP(2, 16, 16); }
+    else { if (E <= 4) ICE_STEP(1, 16, 4); else ICE_STEP(1, 16, 16); }
+#undef ICE_STEP
+}
+
+// largest page count and page budget launch_decode_step can serve (register-resident keys, LDS lists)
+int decode_step_max_pages(int G) { return (G == 8 ? 8 * 64 * 32 : 16 * 64 * 16); }
+size_t decode_step_lds_bytes(const Dev &d, int P) {
+    const int NW = d.G == 8 ? 8 : 16;
+    const int Pk = P < d.max_pages ? P : d.max_pages;
+    // no candidate list is needed when the budget covers every page the index can hold
+    const size_t cand_bytes = P >= d.max_pages ? 0 : (size_t)d.max_pages * 8 + 260 * 4;
+    const size_t red_bytes = sizeof(float) * attend_scratch_floats(d.G, NW);
+    return round_up(Pk * 4, 16) + (size_t)Pk * 8 + (cand_bytes > red_bytes ? cand_bytes : red_bytes);
 }
 
 }  // namespace ice

@@ -37,9 +37,8 @@ struct Dev {
     int *cluster_start;         // [U][Cpad+1] exclusive scan of counts
     int *page_base;             // [U][Cpad+1] exclusive scan of pages per cluster
     // decode scratch
-    float *scores;              // [U][max_pages]
-    int *sel_ids;               // [U][max_sel] ids handed from select to attend in the fused call
-    int *sel_n;                 // [U]
+    uint32_t *scores;           // [U][max_pages] fp32 bits of the page scores; 0xFFFFFFFF = empty slot
+    int *counter;               // [U] arrival counters of the decode-step kernel (zero between launches)
 };
 
 struct Host {
@@ -51,7 +50,6 @@ struct Host {
     bool built;
     int n_tokens;    // per unit
     int cur;         // live centroid buffer
-    int max_sel;
 };
 
 __host__ __device__ inline int round_up(int x, int m) { return (x + m - 1) / m * m; }
@@ -66,8 +64,12 @@ void launch_means(const Dev &d, const bf16_t *K, int n, int cur, hipStream_t st)
 void launch_paginate(const Dev &d, const bf16_t *K, const bf16_t *V, int n, hipStream_t st);
 void launch_refresh_centroids(const Dev &d, int cur, hipStream_t st);
 void launch_insert(const Dev &d, const bf16_t *k, const bf16_t *v, int cur, hipStream_t st);
-void launch_select(const Dev &d, const bf16_t *q, int P, int *ids, int *n_sel, float *scores_out,
-                   hipStream_t st);
+// scores + top-P selection (+ attention when out != nullptr) in one launch
+// np_hint: host-side upper bound of the live pages per unit (tokens / page_size + clusters)
+void launch_decode_step(const Dev &d, const bf16_t *q, int P, int np_hint, int *ids, int *n_sel, float *scores_out,
+                        float *out, hipStream_t st);
+int decode_step_max_pages(int G);
+size_t decode_step_lds_bytes(const Dev &d, int P);
 void launch_attend(const Dev &d, const bf16_t *q, const int *ids, const int *n_sel, int P, float *out,
                    hipStream_t st);
 

@@ -280,6 +280,26 @@ def test_select_ties_and_empty_selection():
     assert (out_a - out_b).abs().max().item() <= 1e-6
 
 
+def test_select_many_exact_ties_uses_lowest_ids():
+    """More tied candidates than the fast ranking path takes (hundreds of identical pages plus a few
+    distinct ones): the radix path must still return the best pages, lowest ids first among ties."""
+    from paper_2604_10539_amd import IceIndex
+    rng = np.random.default_rng(9)
+    n = 16 * 700
+    key = narrow(rng.standard_normal(D).astype(np.float32))
+    K = np.tile(key, (1, 1, n, 1))
+    K[0, 0, 16 * 300:16 * 303] = narrow(3.0 * widen(key))          # three pages that beat the rest
+    K[0, 0, 16 * 10:16 * 12] = narrow(-1.0 * widen(key))           # two pages that lose
+    V = narrow(rng.standard_normal((1, 1, n, D)).astype(np.float32))
+    ix = IceIndex(1, 1, 1, n, 16, 1, kmeans_iters=1, init_idx=up(np.zeros((1, 1, 1), np.int32)))
+    ix.build_index(up(K), up(V))
+    q = narrow(widen(key)[None, None, :].copy())
+    ids, n_sel, scores = ix.select(up(q), 16 * 8)
+    assert down(ids).ravel().tolist() == [0, 1, 2, 3, 4, 300, 301, 302]
+    o = oracle_from_export(ix, export_np(ix))
+    _compare_select(o, q, 16 * 8, down(ids), down(n_sel), down(scores))
+
+
 # ----------------------------------------------------------------------------------------- import
 def test_imported_oracle_index_select_attend():
     """An index built entirely by the oracle, imported bit for bit, must select the same pages."""
