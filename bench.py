@@ -115,7 +115,7 @@ def main():
     # ---------------------------------------------------------------- algorithmic bytes of one step
     # select: every live representative row (256 B) + the G query rows + the ids written;
     # attend: valid K and V rows of the selected pages + the fp32 outputs.
-    flush = torch.zeros(1 << 28, dtype=torch.int32, device=dev)       # 1 GiB, read between timed steps
+    flush = torch.zeros(1 << 28, dtype=torch.float32, device=dev)     # 1 GiB, read between timed steps
     ids_b = torch.empty((L, H, P), dtype=torch.int32, device=dev)
     ns_b = torch.empty((L, H), dtype=torch.int32, device=dev)
     out_b = torch.empty((L, H * G, D), dtype=torch.float32, device=dev)
@@ -150,6 +150,11 @@ def main():
         return sum(a.elapsed_time(b) for a, b in evs) / steps
 
     cold = not args.warm
+    # a plain copy of known size (256 MiB read, 256 MiB written): the reference dispatch against
+    # which the HBM byte counters of a profiler run are scaled
+    calib_src = flush[: 1 << 26]
+    calib_dst = torch.empty_like(calib_src)
+    torch.mul(calib_src, 1.0, out=calib_dst)
     # ---------------------------------------------------------------- batched: 256 units per launch set
     ms_batched = timed(lambda: batched.select_attend(q, budget, ids_b, ns_b, out_b), args.steps, args.warmup, cold)
     ms_sel = timed(lambda: ice_select(batched.handle, q, budget, ids_b, ns_b, None), args.steps, args.warmup, cold)

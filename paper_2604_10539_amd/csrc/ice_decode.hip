@@ -342,7 +342,7 @@ void launch_attend(const Dev &d, const bf16_t *q, const int *ids, const int *n_s
 // Phase C, same workgroup: attention over the winners (attend_pages), ids never leave the chip.
 template <int G, int NW, int EMAX>
 __global__ __launch_bounds__(NW * 64) void decode_step_kernel(Dev d, const bf16_t *__restrict__ q, int P, int chunks, int np_hint,
-                                                               int *__restrict__ ids_out, int *__restrict__ n_sel_out,
+                                                               int lds_scores_off, int *__restrict__ ids_out, int *__restrict__ n_sel_out,
                                                                float *__restrict__ scores_out, float *__restrict__ out) {
     constexpr int NT = NW * 64;
     extern __shared__ __align__(16) char smem[];
@@ -357,6 +357,10 @@ __global__ __launch_bounds__(NW * 64) void decode_step_kernel(Dev d, const bf16_
     const int np = d.n_pages[u];  // first needed after the first loads are in flight
     const bf16_t *rep = d.rep + (size_t)u * d.max_pages * kD;
     uint32_t *S = d.scores + (size_t)u * d.max_pages;  // fp32 bits; kScoreEmpty = not written yet
+
+    // one workgroup per unit: the scores never leave LDS and there is nobody to wait for
+    const bool single = chunks == 1;
+    uint32_t *sc_lds = (uint32_t *)(smem + lds_scores_off);
 
     if (chunk == 0) ICE_STAMP(0);
     // ---- phase A: scores of this chunk, 16 pages per v_mfma_f32_16x16x32_bf16 chain.
@@ -401,8 +405,10 @@ __global__ __launch_bounds__(NW * 64) void decode_step_kernel(Dev d, const bf16_
                     if (4 * g + v < G) sc = fmaxf(sc, acc[v] * inv[v]);
                 if (G > 4) sc = fmaxf(sc, __shfl_xor(sc, 16));
                 const int page = p0 + 16 * (b0 + NW * x) + ch;
-                if (g == 0 && page < lim)
-                    __hip_atomic_store(S + page, __float_as_uint(sc), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                if (g == 0 && page < lim) {
+                    if (single) sc_lds[page] = __float_as_uint(sc);
+                    else __hip_atomic_store(S + page, __float_as_uint(sc), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                }
             }
         }
     }
@@ -413,9 +419,12 @@ __global__ __launch_bounds__(NW * 64) void decode_step_kernel(Dev d, const bf16_
     // waits for stores that were issued and completed (barrier below) before the counter moved.
     __syncthreads();
     if (tid == 0) {
-        const int old = __hip_atomic_fetch_add(d.counter + u, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        const int last = old == chunks - 1;
-        if (last) __hip_atomic_store(d.counter + u, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);  // next launch
+        int last = 1;
+        if (!single) {
+            const int old = __hip_atomic_fetch_add(d.counter + u, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            last = old == chunks - 1;
+            if (last) __hip_atomic_store(d.counter + u, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);  // next launch
+        }
         sh_last = last;
         sh_M = 0;
         sh_W = 0;
@@ -425,8 +434,9 @@ __global__ __launch_bounds__(NW * 64) void decode_step_kernel(Dev d, const bf16_
     __syncthreads();
     if (!sh_last) return;
     ICE_STAMP(1);
-    auto read_score = [&](int pid) -> uint32_t {
-        uint32_t v = __hip_atomic_load(S + pid, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    // all of a thread's score words are requested first, then checked: one round trip, not E
+    auto finish_score = [&](int pid, uint32_t v) -> uint32_t {
+        if (single) return v;
         for (int spin = 0; v == kScoreEmpty && spin < (1 << 16); ++spin)
             v = __hip_atomic_load(S + pid, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         if (v == kScoreEmpty) {  // never expected; a fence bounds the wait
@@ -435,6 +445,9 @@ __global__ __launch_bounds__(NW * 64) void decode_step_kernel(Dev d, const bf16_
         }
         __hip_atomic_store(S + pid, kScoreEmpty, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);  // re-arm the slot
         return v;
+    };
+    auto request_score = [&](int pid) -> uint32_t {
+        return single ? sc_lds[pid] : __hip_atomic_load(S + pid, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     };
 
     // ---- phase B: top-k pages
@@ -454,7 +467,7 @@ __global__ __launch_bounds__(NW * 64) void decode_step_kernel(Dev d, const bf16_
     if (k == np) {
         // budget covers every page
         for (int x = tid; x < k; x += NT) {
-            const uint32_t v = read_score(x);
+            const uint32_t v = finish_score(x, request_score(x));
             sel_list[x] = x;
             ids[x] = x;
             if (sco) sco[x] = __uint_as_float(v);
@@ -467,10 +480,12 @@ __global__ __launch_bounds__(NW * 64) void decode_step_kernel(Dev d, const bf16_
         u64 cm[EMAX];
         int nvalid = 0;
 #pragma unroll
+        for (int e = 0; e < EMAX; ++e) key[e] = e * NT + tid < np ? request_score(e * NT + tid) : 0u;
+#pragma unroll
         for (int e = 0; e < EMAX; ++e) {
             const int pid = e * NT + tid;
             const bool valid = pid < np;
-            key[e] = valid ? f32_ordered(__uint_as_float(read_score(pid))) : 0u;
+            key[e] = valid ? f32_ordered(__uint_as_float(finish_score(pid, key[e]))) : 0u;
             cm[e] = __ballot(valid);
             nvalid += (int)__popcll(cm[e]);
         }
@@ -642,8 +657,8 @@ void launch_decode_step(const Dev &d, const bf16_t *q, int P, int np_hint, int *
 #define ICE_STEP(g, nw, e)                                                                                          \
     do {                                                                                                            \
         (void)hipFuncSetAttribute((const void *)decode_step_kernel<g, nw, e>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds); \
-        hipLaunchKernelGGL((decode_step_kernel<g, nw, e>), dim3(grid), dim3(nw * 64), lds, st, d, q, P, chunks, np_hint, ids, \
-                           n_sel, scores_out, out);                                                                 \
+        hipLaunchKernelGGL((decode_step_kernel<g, nw, e>), dim3(grid), dim3(nw * 64), lds, st, d, q, P, chunks, np_hint, \
+                           (int)(lds - (size_t)d.max_pages * 4), ids, n_sel, scores_out, out);                                                                 \
     } while (0)
     if (d.G == 8) { if (E <= 8) ICE_STEP(8, 8, 8); else ICE_STEP(8, 8, 32); }
     else if (d.G == 4) { if (E <= 4) ICE_STEP(4, 16, 4); else ICE_STEP(4, 16, 16); }
@@ -660,7 +675,9 @@ size_t decode_step_lds_bytes(const Dev &d, int P) {
     // no candidate list is needed when the budget covers every page the index can hold
     const size_t cand_bytes = P >= d.max_pages ? 0 : (size_t)d.max_pages * 8 + 260 * 4;
     const size_t red_bytes = sizeof(float) * attend_scratch_floats(d.G, NW);
-    return round_up(Pk * 4, 16) + (size_t)Pk * 8 + (cand_bytes > red_bytes ? cand_bytes : red_bytes);
+    // winner lists, candidate list / attention scratch (used one after the other), LDS copy of the scores
+    return round_up(Pk * 4, 16) + (size_t)Pk * 8 + round_up((int)(cand_bytes > red_bytes ? cand_bytes : red_bytes), 16) +
+           (size_t)d.max_pages * 4;
 }
 
 }  // namespace ice
