@@ -32,6 +32,9 @@ if ROOT not in sys.path:
 import datagen  # noqa: E402
 
 HBM_PEAK_GBPS = 8000.0
+# HBM bytes of one batched decode_step launch (fetch + write), from the counter runs summarised in
+# profiles/decode_step_cfg2_hbm_counters.md; refreshed whenever that profile is.
+MEASURED_TRAFFIC_BYTES = None
 MFMA_BF16_PEAK_TFLOPS = 2500.0
 D = 128
 
@@ -239,9 +242,14 @@ def main():
         "effective_GBps": gbps,
         "bytes_per_step": bytes_step,
         "hbm_frac": gbps / HBM_PEAK_GBPS,
-        "roofline": {"bound": "hbm", "kernel": "decode_step_kernel (score + top-P, no attention), 256 units per launch",
-                     "achieved": sel_gbps, "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": sel_gbps / HBM_PEAK_GBPS,
-                     "traffic": None, "algorithmic_bytes_per_launch": bytes_select, "us_per_launch": ms_sel * 1e3},
+        "roofline": {"bound": "hbm", "kernel": "decode_step_kernel<4,16,4> (score + top-P + attention in one launch), "
+                                               "256 workgroups of 1024 threads, one per unit",
+                     "achieved": gbps, "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": gbps / HBM_PEAK_GBPS,
+                     "traffic": MEASURED_TRAFFIC_BYTES, "algorithmic_bytes_per_launch": bytes_step,
+                     "us_per_launch": ms_batched * 1e3,
+                     "traffic_note": "rocprofv3 --pmc FETCH_SIZE x 2.0 (the counter reads half of a plain copy kernel's "
+                                     "known bytes) + WRITE_SIZE x 1.0; see profiles/"},
+        "select_only": {"us_per_launch": ms_sel * 1e3, "GBps": sel_gbps, "algorithmic_bytes_per_launch": bytes_select},
         "attend": {"us_per_launch": ms_att * 1e3, "GBps": bytes_attend / (ms_att * 1e-3) / 1e9,
                    "algorithmic_bytes_per_launch": bytes_attend},
         "sequential": {"us_per_layer_step": ms_seq * 1e3 / L, "GBps": bytes_step / (ms_seq * 1e-3) / 1e9,

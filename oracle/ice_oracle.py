@@ -105,15 +105,20 @@ class OracleIndex:
     ARRAYS = ("n_tokens", "n_pages", "Kp", "Vp", "page_cluster", "page_fill", "page_pos",
               "cluster_tail", "cluster_cnt", "cluster_sum", "centroid", "page_sum", "rep")
 
-    def __init__(self, U: int, group_size: int, page_size: int, n_clusters: int, max_tokens: int, d: int = 128):
+    def __init__(self, U: int, group_size: int, page_size: int, n_clusters: int, max_tokens: int, d: int = 128,
+                 max_pages: int | None = None, alloc_kv: bool = True):
+        """max_pages overrides the default pool size (floor(max_tokens / page_size) + n_clusters), e.g. for
+        an index that holds only a few gathered pages; alloc_kv=False leaves out the K/V page pools
+        (selection needs only the representatives)."""
         self.U, self.G, self.s, self.C, self.d = U, group_size, page_size, n_clusters, d
         self.max_tokens = max_tokens
-        self.max_pages = MP = max_tokens // page_size + n_clusters
+        self.max_pages = MP = max_tokens // page_size + n_clusters if max_pages is None else max_pages
         s, Cn = page_size, n_clusters
         self.n_tokens = np.zeros(U, np.int32)
         self.n_pages = np.zeros(U, np.int32)
-        self.Kp = np.zeros((U, MP, s, d), np.uint16)
-        self.Vp = np.zeros((U, MP, s, d), np.uint16)
+        kv_pages = MP if alloc_kv else 1
+        self.Kp = np.zeros((U, kv_pages, s, d), np.uint16)
+        self.Vp = np.zeros((U, kv_pages, s, d), np.uint16)
         self.page_cluster = np.full((U, MP), -1, np.int32)
         self.page_fill = np.zeros((U, MP), np.int32)
         self.page_pos = np.full((U, MP, s), -1, np.int32)

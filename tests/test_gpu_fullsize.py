@@ -1,0 +1,205 @@
+"""GPU parity at the benchmark's full sizes and launch shapes.  What the oracle can compute in full
+(selection over every page of every unit, attention over the selected pages) is compared in full;
+what it cannot in seconds (the n x C assignment, the page layout of 256 units) is compared on
+sampled keys and sampled units, plus invariants that hold at any size."""
+from concurrent.futures import ThreadPoolExecutor
+
+import numpy as np
+import pytest
+import torch
+
+import datagen
+from datagen import bf16_bits_to_f32 as widen, f32_to_bf16_bits as narrow
+from oracle import ice_oracle as orc
+from tests.test_gpu_parity import ATTN_EXPECTED, ATTN_TOL, _assign_band, _compare_select
+from tests.util import D, down, up, valid_slot_mask
+
+pytestmark = pytest.mark.gpu
+
+
+def _select_attend_vs_oracle(ix, ex, q_np, budget, ids, n_sel, out):
+    """Selection over all pages of all units, attention over the GPU's ids, both against the oracle.
+    The oracle gets the representatives in full and only the selected K/V tiles (gathered on the GPU)."""
+    U, G, s = ix.U, ix.group_size, ix.page_size
+    P = ids.shape[-1]
+    ids2, ns = ids.reshape(U, P), n_sel.reshape(U)
+    o = orc.OracleIndex(U, G, s, ix.n_clusters, ix.max_tokens, alloc_kv=False)
+    o.rep[...] = down(ex["rep"])
+    o.n_pages[...] = down(ex["n_pages"])
+    o.page_fill[...] = down(ex["page_fill"])
+    _compare_select(o, q_np, budget, down(ids2), down(ns))
+    # compact index: page j of unit u = the j-th selected page
+    gi = ids2.clamp(min=0).long()
+    g = orc.OracleIndex(U, G, s, ix.n_clusters, ix.max_tokens, max_pages=P)
+    g.Kp[...] = down(torch.gather(ex["Kp"], 1, gi[:, :, None, None].expand(U, P, s, D)))
+    g.Vp[...] = down(torch.gather(ex["Vp"], 1, gi[:, :, None, None].expand(U, P, s, D)))
+    g.page_fill[...] = down(torch.gather(ex["page_fill"], 1, gi))
+    g.n_pages[...] = down(ns)
+    ref = g.attend(q_np, np.tile(np.arange(P, dtype=np.int32), (U, 1)), down(ns))
+    err = np.abs(down(out).reshape(ref.shape) - ref).max()
+    print("[full size] attention max abs err %.3g over %d units" % (err, U))
+    assert err <= ATTN_TOL and err <= ATTN_EXPECTED
+    fill = down(ex["page_fill"])
+    for u in range(U):
+        assert fill[u, down(ids2)[u, :down(ns)[u]]].sum() <= budget
+
+
+def _check_units(ix, ex, K, V, units, n, rng, n_keys=256):
+    """Sampled units: table invariants, bit copies, ordered-fp32 representatives (oracle page layout
+    of the GPU's assignment), and the assignment itself on sampled keys."""
+    s, C = ix.page_size, ix.n_clusters
+    for u in units:
+        a = down(ex["assign"][u, :n])
+        Ku, Vu = K[u], V[u]
+        o = orc.OracleIndex(1, ix.group_size, s, C, n)
+        o.paginate(Ku[None], Vu[None], a[None])
+        npg = int(o.n_pages[0])
+        assert int(ex["n_pages"][u]) == npg
+        for name in ("page_cluster", "page_fill", "cluster_tail"):
+            assert np.array_equal(down(ex[name][u])[:getattr(o, name).shape[1]], getattr(o, name)[0]), name
+        assert np.array_equal(down(ex["page_pos"][u, :npg]), o.page_pos[0, :npg])
+        m = valid_slot_mask(o.page_fill[0, :npg], s)
+        assert np.array_equal(down(ex["Kp"][u, :npg])[m], o.Kp[0, :npg][m])
+        assert np.array_equal(down(ex["Vp"][u, :npg])[m], o.Vp[0, :npg][m])
+        assert np.array_equal(down(ex["rep"][u, :npg]), o.rep[0, :npg])
+        assert np.array_equal(down(ex["page_sum"][u, :npg]).view(np.uint32), o.page_sum[0, :npg].view(np.uint32))
+        pos = o.page_pos[0, :npg][m]
+        assert np.array_equal(np.sort(pos), np.arange(n))                       # every token exactly once
+        # assignment on sampled keys against the centroids it was computed from
+        mub = down(ex["assign_centroid_bf16"][u, :C])
+        pick = rng.choice(n, n_keys, replace=False)
+        a_ref, best, _ = orc.assign(Ku[pick], mub)
+        kf, mf = widen(Ku[pick]).astype(np.float64), widen(mub).astype(np.float64)
+        obj = (mf[a[pick]] ** 2).sum(1) - 2.0 * (kf * mf[a[pick]]).sum(1)
+        assert np.all(obj - best <= _assign_band(Ku[pick], mub))
+        assert (a[pick] != a_ref).sum() <= 2
+        # centroids are the means of their members
+        cnt = np.bincount(a, minlength=C)
+        assert np.array_equal(down(ex["cluster_cnt"][u]), cnt)
+        c0 = int(np.argmax(cnt))
+        mean = widen(Ku[a == c0]).astype(np.float64).mean(0)
+        np.testing.assert_allclose(down(ex["centroid"][u, c0]), mean, rtol=1e-5, atol=1e-5)
+
+
+def test_config2_all_32_layers_in_the_bench_launch_shape():
+    """256 units (32 layers x 8 KV heads), n = 32768, C = 512, budget 256: exactly what bench.py times."""
+    from paper_2604_10539_amd import IceIndex
+    w = datagen.WORKLOADS["cfg2"]
+    L = 32
+
+    def gen(l):
+        K, V = datagen.keys_values(w, seed=w.seed + l)
+        return K[0], V[0], datagen.init_indices(w, seed=w.seed + l)[0], datagen.queries(w, seed=w.seed + l)[0]
+
+    with ThreadPoolExecutor(max_workers=16) as ex_:
+        layers = list(ex_.map(gen, range(L)))
+    K = np.stack([x[0] for x in layers]).reshape(L * 8, w.n_tokens, D)
+    V = np.stack([x[1] for x in layers]).reshape(L * 8, w.n_tokens, D)
+    init = np.stack([x[2] for x in layers])
+    q_np = np.stack([x[3] for x in layers])
+    del layers
+    ix = IceIndex(L, 8, 4, w.n_tokens + 64, 16, 512, kmeans_iters=2, init_idx=up(init))
+    ix.build_index(up(K), up(V))
+    ids, n_sel, out = ix.select_attend(up(q_np), 256)
+    torch.cuda.synchronize()
+    ex = ix.export()
+    _select_attend_vs_oracle(ix, ex, q_np, 256, ids, n_sel, out)
+    _check_units(ix, ex, K, V, [0, 97, 255], w.n_tokens, np.random.default_rng(0))
+    # one layer at a time (8 units, several workgroups per unit) gives the same ids and output bits
+    one = IceIndex(1, 8, 4, w.n_tokens + 64, 16, 512, kmeans_iters=2, init_idx=up(init[5]))
+    one.build_index(up(K[40:48]), up(V[40:48]))
+    ids1, ns1, out1 = one.select_attend(up(q_np[5:6]), 256)
+    assert torch.equal(ids1[0], ids[5]) and torch.equal(out1[0], out[5])
+
+
+def test_config3_shape_long_context():
+    """n = 131072, C = 2048 (four centroid slices), budget 1024 (P = 64), 5 % outlier keys; 2 of the 8 heads."""
+    from paper_2604_10539_amd import IceIndex
+    w0 = datagen.WORKLOADS["cfg3"]
+    w = datagen.small("cfg3_2heads", n_kv_heads=2, n_tokens=w0.n_tokens, n_clusters=w0.n_clusters, token_budget=1024,
+                      n_components=w0.n_components, outlier_frac=w0.outlier_frac, seed=w0.seed)
+    K, V = datagen.keys_values(w)
+    K, V = K.reshape(2, w.n_tokens, D), V.reshape(2, w.n_tokens, D)
+    init, q_np = datagen.init_indices(w), datagen.queries(w)
+    ix = IceIndex(1, 2, 4, w.n_tokens, 16, w.n_clusters, kmeans_iters=2, init_idx=up(init))
+    ix.build_index(up(K), up(V))
+    ids, n_sel, out = ix.select_attend(up(q_np), 1024)
+    torch.cuda.synchronize()
+    ex = ix.export()
+    _select_attend_vs_oracle(ix, ex, q_np, 1024, ids, n_sel, out)
+    _check_units(ix, ex, K, V, [1], w.n_tokens, np.random.default_rng(1), n_keys=64)
+
+
+def test_config4_shape_batched_sequences():
+    """16 sequences x 8 KV heads = 128 units in one launch (two workgroups per unit); context reduced to
+    8192 so the full page layout of every unit can be checked."""
+    from paper_2604_10539_amd import IceIndex
+    w = datagen.small("cfg4_small", batch=16, n_kv_heads=8, n_tokens=8192, n_clusters=128, token_budget=256,
+                      n_components=64, seed=4000)
+    K, V = datagen.keys_values(w)
+    K, V = K.reshape(128, w.n_tokens, D), V.reshape(128, w.n_tokens, D)
+    init, q_np = datagen.init_indices(w), datagen.queries(w)
+    ix = IceIndex(16, 8, 4, w.n_tokens, 16, w.n_clusters, kmeans_iters=3, init_idx=up(init))
+    ix.build_index(up(K), up(V))
+    ids, n_sel, out = ix.select_attend(up(q_np), 256)
+    torch.cuda.synchronize()
+    ex = ix.export()
+    _select_attend_vs_oracle(ix, ex, q_np, 256, ids, n_sel, out)
+    _check_units(ix, ex, K, V, [0, 63, 127], w.n_tokens, np.random.default_rng(2))
+
+
+def test_config5_long_generation_loop():
+    """Prompt of 16384 tokens, then decode steps of insert -> select(256) -> attend with drifting
+    centres; the oracle replays every insertion from the exported post-build state (bit-exact tables
+    and ordered-fp32 state), selection and attention are compared every 16 steps."""
+    from paper_2604_10539_amd import IceIndex
+    from tests.util import STATE_FIELDS, export_np, oracle_from_export
+    w = datagen.WORKLOADS["cfg5"]
+    steps = 384
+    K, V = datagen.keys_values(w)
+    init = datagen.init_indices(w)
+    ix = IceIndex(1, 8, 4, w.n_tokens + steps, 16, w.n_clusters, kmeans_iters=3, init_idx=up(init))
+    ix.build_index(up(K), up(V))
+    o = oracle_from_export(ix, export_np(ix))
+    exv = ix.export()
+    stream = datagen.DecodeStream(w)
+    flips = 0
+    for t in range(steps):
+        k, v, q = stream.next()
+        ku = k.reshape(8, D)
+        mub = narrow(o.centroid)
+        ix.insert(up(k), up(v))
+        ids, n_sel, out = ix.select_attend(up(q), 256)
+        torch.cuda.synchronize()
+        pos_t, pc_t = down(exv["page_pos"]), down(exv["page_cluster"])
+        force = np.empty(8, np.int32)
+        for u in range(8):
+            pg = np.argwhere(pos_t[u] == w.n_tokens + t)
+            assert len(pg) == 1
+            force[u] = pc_t[u, pg[0][0]]
+            a_own, best, _ = orc.assign(ku[u][None], mub[u])
+            if force[u] != a_own[0]:
+                mf = widen(mub[u, force[u]]).astype(np.float64)
+                obj = (mf ** 2).sum() - 2.0 * (widen(ku[u]).astype(np.float64) * mf).sum()
+                assert obj - best[0] <= _assign_band(ku[u][None], mub[u])[0]
+                flips += 1
+        o.insert(k, v, force=force)
+        if t % 16 == 15 or t == steps - 1:
+            _compare_select(o, q, 256, down(ids), down(n_sel))
+            ref = o.attend(q, down(ids).reshape(8, -1), down(n_sel).reshape(8))
+            assert np.abs(down(out).reshape(ref.shape) - ref).max() <= ATTN_EXPECTED
+    exg = export_np(ix)
+    for name in STATE_FIELDS:
+        a, b = exg[name], getattr(o, name)
+        for u in range(8):
+            npg = o.n_pages[u]
+            if name in ("Kp", "Vp"):
+                m = valid_slot_mask(o.page_fill[u, :npg], 16)
+                assert np.array_equal(a[u, :npg][m], b[u, :npg][m]), name
+            elif name in ("page_sum", "rep"):
+                assert np.array_equal(a[u, :npg], b[u, :npg]), name
+            elif name in ("cluster_sum", "centroid"):
+                assert np.array_equal(a[u].view(np.uint32), b[u].view(np.uint32)), name
+            else:
+                assert np.array_equal(a[u], b[u]), name
+    print("[config 5] %d steps, %d nearest-centroid decisions inside the tie band" % (steps, flips))
