@@ -116,7 +116,7 @@ void launch_insert(const Dev &d, const bf16_t *k, const bf16_t *v, int cur, hipS
 //   values   lane (g, c) holds 8 output dims of every head and reads value rows 4t+g, 16 bytes
 //            each (1 KiB per load instruction), fp32 FMAs.
 // The four row groups are summed at the end, the NW waves merged by the (max, sum, output) rule.
-// `list` may point to LDS or global memory; `red` is LDS scratch of attend_scratch_floats() floats.
+// page_of(x) names the x-th listed page; `red` is LDS scratch of attend_scratch_floats() floats.
 __host__ __device__ constexpr int attend_scratch_floats(int G, int NW) { return NW * (G * (kD + 2) + 16 * 8 + 8); }
 
 template <int G>
@@ -132,8 +132,8 @@ __device__ inline void load_query_operand(const bf16_t *q, int u, int lane, bf16
     if (sumsq) *sumsq = nn;
 }
 
-template <int G, int NW>
-__device__ inline void attend_pages(const Dev &d, int u, const bf16x8 (&qa)[4], const int *list, int ns,
+template <int G, int NW, typename PageOf>
+__device__ inline void attend_pages(const Dev &d, int u, const bf16x8 (&qa)[4], PageOf page_of, int ns,
                                     float *__restrict__ out, float *red) {
     constexpr int GR = (G + 3) / 4;  // row groups that hold logits
     float(*wacc)[G][kD] = (float(*)[G][kD])red;                   // [NW][G][128]
@@ -153,7 +153,7 @@ __device__ inline void attend_pages(const Dev &d, int u, const bf16x8 (&qa)[4], 
 #pragma unroll
         for (int j = 0; j < 8; ++j) acc[h][j] = 0.f;
     for (int x = wave; x < ns; x += NW) {
-        const int p = list[x];
+        const int p = page_of(x);
         if ((unsigned)p >= (unsigned)d.max_pages) continue;  // not a page id: ignored
         const size_t pg = (size_t)u * d.max_pages + p;
         // the first 16-token block is fetched before the fill count is known (one fewer dependent
@@ -280,19 +280,24 @@ __device__ inline void attend_pages(const Dev &d, int u, const bf16x8 (&qa)[4], 
     }
     __syncthreads();
     ICE_STAMP(11);
+    if (tid < G) {  // per head: the waves' weights exp(m_w - M) and the reciprocal denominator
+        float M = -INFINITY;
+        for (int w = 0; w < NW; ++w) M = fmaxf(M, wm[w][tid]);
+        float L = 0.f;
+        for (int w = 0; w < NW; ++w) {
+            const float e = M == -INFINITY ? 0.f : __expf(wm[w][tid] - M);
+            L += wl[w][tid] * e;
+            wm[w][tid] = e;
+        }
+        wl[0][tid] = L > 0.f ? 1.0f / L : 0.f;
+    }
+    __syncthreads();
     for (int o = tid; o < G * kD; o += NW * 64) {
         const int h = o / kD, j = o % kD;
-        float M = -INFINITY;
-        for (int w = 0; w < NW; ++w) M = fmaxf(M, wm[w][h]);
-        float L = 0.f, O = 0.f;
-        if (M != -INFINITY) {
-            for (int w = 0; w < NW; ++w) {
-                const float e = __expf(wm[w][h] - M);
-                L += wl[w][h] * e;
-                O += wacc[w][h][j] * e;
-            }
-        }
-        out[((size_t)u * G + h) * kD + j] = L > 0.f ? O / L : 0.f;
+        float O = 0.f;
+#pragma unroll
+        for (int w = 0; w < NW; ++w) O += wacc[w][h][j] * wm[w][h];
+        out[((size_t)u * G + h) * kD + j] = O * wl[0][h];
     }
 }
 
@@ -304,7 +309,8 @@ __global__ __launch_bounds__(NW * 64) void attend_kernel(Dev d, const bf16_t *__
     const int u = blockIdx.x;
     bf16x8 qa[4];
     load_query_operand<G>(q, u, threadIdx.x & 63, qa, nullptr);
-    attend_pages<G, NW>(d, u, qa, ids + (size_t)u * P, min(n_sel[u], P), out, (float *)smem);
+    const int *list = ids + (size_t)u * P;
+    attend_pages<G, NW>(d, u, qa, [=](int x) { return list[x]; }, min(n_sel[u], P), out, (float *)smem);
 }
 
 void launch_attend(const Dev &d, const bf16_t *q, const int *ids, const int *n_sel, int P, float *out,
@@ -460,7 +466,6 @@ __global__ __launch_bounds__(NW * 64) void decode_step_kernel(Dev d, const bf16_
     }
     if (tid == 0) n_sel_out[u] = k;
     const int Pk = min(P, d.max_pages);
-    int *sel_list = (int *)smem;                                  // [Pk] winners, ascending id
     u64 *sel_comp = (u64 *)(smem + round_up(Pk * 4, 16));         // [Pk] winners by rank
     char *region = smem + round_up(Pk * 4, 16) + (size_t)Pk * 8;  // candidates, later attention scratch
     u64 *cand = (u64 *)region;
@@ -468,7 +473,6 @@ __global__ __launch_bounds__(NW * 64) void decode_step_kernel(Dev d, const bf16_
         // budget covers every page
         for (int x = tid; x < k; x += NT) {
             const uint32_t v = finish_score(x, request_score(x));
-            sel_list[x] = x;
             ids[x] = x;
             if (sco) sco[x] = __uint_as_float(v);
         }
@@ -610,25 +614,29 @@ __global__ __launch_bounds__(NW * 64) void decode_step_kernel(Dev d, const bf16_
                 if (pk >= prefix) sel_comp[atomicAdd(&sh_W, 1)] = cc;
             }
         }
-        __syncthreads();
-        ICE_STAMP(5);
+    }
+    __syncthreads();
+    ICE_STAMP(5);
+    // ---- phase C: attention over the winners, in rank order (the ids' ascending order is only an
+    // output format and is produced afterwards, off the critical path)
+    const bool all_pages = k == np;
+    if (out) {
+        ICE_STAMP(6);
+        attend_pages<G, NW>(d, u, qa, [=](int x) { return all_pages ? x : (int)(0xFFFFFFFFu - (uint32_t)sel_comp[x]); }, k,
+                            out, (float *)region);
+        ICE_STAMP(7);
+    }
+    if (!all_pages) {
         // B4: the winners' places in ascending id order
         for (int t = tid; t < k; t += NT) {
             const u64 mine = sel_comp[t];
             const uint32_t myid = 0xFFFFFFFFu - (uint32_t)mine;
             int pos = 0;
             for (int j = 0; j < k; ++j) pos += (0xFFFFFFFFu - (uint32_t)sel_comp[j]) < myid;
-            sel_list[pos] = (int)myid;
             ids[pos] = (int)myid;
             if (sco) sco[pos] = ordered_f32((uint32_t)(mine >> 32));
         }
     }
-    if (!out) return;
-    __syncthreads();
-    ICE_STAMP(6);
-    // ---- phase C: attention over the winners
-    attend_pages<G, NW>(d, u, qa, sel_list, k, out, (float *)region);
-    ICE_STAMP(7);
 }
 #ifdef ICE_PROF
 }  // namespace ice

@@ -235,9 +235,9 @@ def test_select_and_attend_on_gpu_built_index(kw, budget):
     err = np.abs(down(out).reshape(ref.shape) - ref).max()
     print("[attend] max abs err %.3g" % err)
     assert err <= ATTN_TOL and err <= ATTN_EXPECTED
-    # fused call gives the same ids and the same output bits
+    # fused call: same ids; it attends in rank order, so the output may differ in the last bits
     ids2, ns2, out2 = ix.select_attend(up(q), budget)
-    assert torch.equal(ids2, ids) and torch.equal(ns2, n_sel) and torch.equal(out2, out)
+    assert torch.equal(ids2, ids) and torch.equal(ns2, n_sel) and (out2 - out).abs().max().item() <= 5e-6
     # loaded tokens never exceed the budget
     for u in range(ix.U):
         sel = ids_n.reshape(ix.U, P)[u, :ns_n.reshape(ix.U)[u]]
