@@ -1,6 +1,8 @@
 // Index build at prefill: promotion of the initial centroids, nearest-centroid assignment on the
 // matrix cores, deterministic per-cluster means, and the node -> page layout (Sec. 4.1-4.2,
 // Alg. 2 of the paper restricted to two levels and iterated as Lloyd rounds).
+#include <cstdlib>
+
 #include "ice_internal.h"
 
 namespace ice {
@@ -119,6 +121,56 @@ __global__ void fill_u64_kernel(u64 *p, size_t n, u64 v) {
 // the waves' candidates meet in an LDS 64-bit max of (ordered score, ~centroid id): the exact fp32
 // maximum with the lowest centroid id on ties.  More than CW*CT*32 centroids are covered by
 // blockIdx.y slices that meet the same way in global memory.
+//
+// In-lane argmax over the 16 scores of one accumulator tile: a binary tournament in which the
+// right-hand entry wins only when strictly larger (lowest element index on ties).  Each comparison
+// is one v_cmp into a scalar lane mask plus one v_cndmask for the value; the winner's element
+// index is never carried per lane: its four bits are assembled as lane masks on the scalar unit
+// (three scalar operations per 2:1 selection), which runs beside the vector and matrix pipes.
+__device__ inline u64 mask_mux(u64 sel, u64 hi, u64 lo) { return (sel & hi) | (~sel & lo); }
+
+__device__ inline void argmax16(const f32x16 &x, float &m, u64 (&bit)[4]) {
+    float t1[8], t2[4], t3[2];
+    u64 a[8], b[4], c[2], l0[4], h1[2], h0[2];
+#pragma unroll
+    for (int p = 0; p < 8; ++p) {
+        const bool g = x[2 * p + 1] > x[2 * p];
+        a[p] = __builtin_amdgcn_ballot_w64(g);
+        t1[p] = g ? x[2 * p + 1] : x[2 * p];
+    }
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+        const bool g = t1[2 * q + 1] > t1[2 * q];
+        b[q] = __builtin_amdgcn_ballot_w64(g);
+        t2[q] = g ? t1[2 * q + 1] : t1[2 * q];
+        l0[q] = mask_mux(b[q], a[2 * q + 1], a[2 * q]);
+    }
+#pragma unroll
+    for (int h = 0; h < 2; ++h) {
+        const bool g = t2[2 * h + 1] > t2[2 * h];
+        c[h] = __builtin_amdgcn_ballot_w64(g);
+        t3[h] = g ? t2[2 * h + 1] : t2[2 * h];
+        h1[h] = mask_mux(c[h], b[2 * h + 1], b[2 * h]);
+        h0[h] = mask_mux(c[h], l0[2 * h + 1], l0[2 * h]);
+    }
+    const bool g = t3[1] > t3[0];
+    const u64 dm = __builtin_amdgcn_ballot_w64(g);
+    m = g ? t3[1] : t3[0];
+    bit[3] = dm;
+    bit[2] = mask_mux(dm, c[1], c[0]);
+    bit[1] = mask_mux(dm, h1[1], h1[0]);
+    bit[0] = mask_mux(dm, h0[1], h0[0]);
+}
+
+#ifdef ICE_PROF
+__device__ long long ice_prof_b[16];
+__device__ long long ice_prof_w[128];
+#define ICE_BSTAMP(i) do { if (threadIdx.x == 0 && blockIdx.x == 0 && blockIdx.z == 0) ice_prof_b[i] = wall_clock64(); } while (0)
+#define ICE_WSTAMP(t, i) do { if ((t) == 1 && (threadIdx.x & 63) == 0 && blockIdx.x == 0 && blockIdx.z == 0) { ice_prof_w[(threadIdx.x >> 6) * 8 + (i)] = wall_clock64(); ice_prof_w[64 + (threadIdx.x >> 6) * 8 + (i)] = clock64(); } } while (0)
+#else
+#define ICE_BSTAMP(i) do { } while (0)
+#define ICE_WSTAMP(t, i) do { } while (0)
+#endif
 constexpr int kKeyStride = 136;  // bf16 elements per LDS key row (128 + 8 padding)
 
 template <int CT, int CW>
@@ -127,7 +179,7 @@ __global__ __launch_bounds__(512) void assign_kernel(Dev d, const bf16_t *__rest
     constexpr int KW = 8 / CW;
     extern __shared__ __align__(16) char smem[];
     bf16_t *keys = (bf16_t *)smem;                                   // [2][256][kKeyStride]
-    u64 *best = (u64 *)(smem + 2 * kAssignTile * kKeyStride * 2);    // [256]
+    u64 *best = (u64 *)(smem + 2 * kAssignTile * kKeyStride * 2);    // [2][256]
 
     const int u = blockIdx.z, tid = threadIdx.x;
     const int wave = tid >> 6, lane = tid & 63, col = lane & 31, half = lane >> 5;
@@ -138,22 +190,32 @@ __global__ __launch_bounds__(512) void assign_kernel(Dev d, const bf16_t *__rest
     const int ntiles = (kend - k0 + kAssignTile - 1) / kAssignTile;
     const bf16_t *Ku = K + (size_t)u * n * kD;
 
-    // centroid operand and accumulator seeds, resident for the whole kernel
-    bf16x8 A[CT][8];
+    ICE_BSTAMP(0);
+    // Prologue.  The workgroup's block of centroid rows goes to LDS with fully coalesced 16-byte
+    // loads (the staging area is the key buffers, not yet in use) and every wave then picks its
+    // MFMA fragments from there: reading the fragments straight from global memory touches 32
+    // separate rows per load instruction.  The first key tile is in flight meanwhile.
+    constexpr int R = CW * CT * 32;  // centroid rows of this workgroup
+    const int crow0 = blockIdx.y * R;
+    uint4 cst[R / 32];
+    {
+        const bf16_t *csrc = d.cent_bf16[cur] + ((size_t)u * d.Cpad + crow0) * kD;
+#pragma unroll
+        for (int i = 0; i < R / 32; ++i) {
+            const int id = tid + 512 * i, row = id >> 4, ch = id & 15;
+            cst[i] = crow0 + row < d.Cpad ? ((const uint4 *)(csrc + (size_t)row * kD))[ch] : make_uint4(0, 0, 0, 0);
+        }
+    }
+    // accumulator seeds, resident for the whole kernel
     f32x16 seed[CT];
 #pragma unroll
     for (int ct = 0; ct < CT; ++ct) {
         const int row0 = cbase + ct * 32;
         if (row0 < d.Cpad) {
-            const uint4 *src = (const uint4 *)(d.cent_bf16[cur] + ((size_t)u * d.Cpad + row0 + col) * kD);
-#pragma unroll
-            for (int ks = 0; ks < 8; ++ks) A[ct][ks] = __builtin_bit_cast(bf16x8, src[ks * 2 + half]);
             const float *wn = d.cnorm[cur] + (size_t)u * d.Cpad + row0;
 #pragma unroll
             for (int v = 0; v < 16; ++v) seed[ct][v] = -0.5f * wn[8 * (v >> 2) + 4 * half + (v & 3)];
         } else {
-#pragma unroll
-            for (int ks = 0; ks < 8; ++ks) A[ct][ks] = __builtin_bit_cast(bf16x8, make_uint4(0, 0, 0, 0));
 #pragma unroll
             for (int v = 0; v < 16; ++v) seed[ct][v] = -INFINITY;
         }
@@ -177,55 +239,126 @@ __global__ __launch_bounds__(512) void assign_kernel(Dev d, const bf16_t *__rest
         }
     };
 
-    if (tid < kAssignTile) best[tid] = 0ull;
-    if (ntiles > 0) {
-        load_tile(0);
-        store_tile(0);
+    if (ntiles > 0) load_tile(0);
+#pragma unroll
+    for (int i = 0; i < R / 32; ++i) {
+        const int id = tid + 512 * i, row = id >> 4, ch = id & 15;
+        *(uint4 *)(keys + (size_t)row * kKeyStride + ch * 8) = cst[i];
     }
+    if (tid < 2 * kAssignTile) best[tid] = 0ull;
     __syncthreads();
+    // centroid operand, resident for the whole kernel
+    bf16x8 A[CT][8];
+#pragma unroll
+    for (int ct = 0; ct < CT; ++ct) {
+        const bf16_t *crow = keys + (size_t)((cw * CT + ct) * 32 + col) * kKeyStride + half * 8;
+#pragma unroll
+        for (int ks = 0; ks < 8; ++ks) A[ct][ks] = __builtin_bit_cast(bf16x8, *(const uint4 *)(crow + ks * 16));
+    }
+    __syncthreads();  // every wave holds its fragments before the first key tile overwrites them
+    if (ntiles > 0) store_tile(0);
+    __syncthreads();
+    ICE_BSTAMP(1);
 
+    constexpr int NSUB = 8 / KW;  // 32-key sub-tiles of this wave per tile
+    const uint32_t inv_cid0 = 0xFFFFFFFFu - (uint32_t)(cbase + 4 * half);  // low word for local centroid id 0
     for (int t = 0; t < ntiles; ++t) {
         const int buf = t & 1;
+        u64 *bestt = best + buf * kAssignTile;
+        ICE_WSTAMP(t, 0);
         if (t + 1 < ntiles) load_tile(t + 1);
-        for (int sub = kw; sub < 8; sub += KW) {
-            const bf16_t *krow = keys + ((size_t)buf * kAssignTile + sub * 32 + col) * kKeyStride + half * 8;
-            bf16x8 B[8];
+        // Software pipeline over "slots" j = (sub-tile i, centroid tile ct): while the matrix cores
+        // run the 8-MFMA chain of slot j+1 into one accumulator set, the vector and scalar units
+        // reduce slot j's 16 scores per lane from the other set (argmax16).  Only four to five
+        // vector operations fit under one MFMA, which is why the index half of the argmax lives
+        // in scalar lane masks.  The key operand of a sub-tile is read from LDS one sub-tile ahead.
+        constexpr int NSLOT = NSUB * CT;
+        bf16x8 B[2][8];
+        auto load_b = [&](int i, bf16x8 (&dst)[8]) {
+            const bf16_t *krow = keys + ((size_t)buf * kAssignTile + (kw + i * KW) * 32 + col) * kKeyStride + half * 8;
 #pragma unroll
-            for (int ks = 0; ks < 8; ++ks) B[ks] = __builtin_bit_cast(bf16x8, *(const uint4 *)(krow + ks * 16));
-            float bv = -INFINITY;
-            int bi = 0;
+            for (int ks = 0; ks < 8; ++ks) dst[ks] = __builtin_bit_cast(bf16x8, *(const uint4 *)(krow + ks * 16));
+        };
+        f32x16 acc[2];
+        auto chain = [&](int j, f32x16 &dst) {
+            const int i = j / CT, ct = j % CT;
+            dst = seed[ct];
 #pragma unroll
-            for (int ct = 0; ct < CT; ++ct) {
-                f32x16 acc = seed[ct];
+            for (int ks = 0; ks < 8; ++ks)
+                dst = __builtin_amdgcn_mfma_f32_32x32x16_bf16(A[ct][ks], B[i & 1][ks], dst, 0, 0, 0);
+        };
+        load_b(0, B[0]);
+        if (CT == 1 && NSUB > 1) load_b(1, B[1]);
+        chain(0, acc[0]);
+        float sv = 0.f;
+        u64 sbit[5] = {0, 0, 0, 0, 0};
 #pragma unroll
-                for (int ks = 0; ks < 8; ++ks)
-                    acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(A[ct][ks], B[ks], acc, 0, 0, 0);
-                // rows of this lane, ascending centroid id: ct*32 + 8*(v/4) + 4*half + v%4
+        for (int j = 0; j < NSLOT; ++j) {
+            const int i = j / CT, ct = j % CT;
+            // LDS reads for the sub-tile whose first chain is issued in the NEXT iteration
+            if ((j + 2) % CT == 0 && (j + 2) / CT < NSUB && (j + 2) / CT >= 1 && !(CT == 1 && j + 2 == 1))
+                load_b((j + 2) / CT, B[((j + 2) / CT) & 1]);
+            if (j + 1 < NSLOT) chain(j + 1, acc[(j + 1) & 1]);
+            // element v of this lane has local centroid id ct*32 + 8*(v/4) + v%4 (+ 4*half), ascending in v
+            float m;
+            u64 bit[4];
+            argmax16(acc[j & 1], m, bit);
+            if (ct == 0) {
+                sv = m;
 #pragma unroll
-                for (int v = 0; v < 16; ++v) {
-                    const bool gt = acc[v] > bv;
-                    bv = gt ? acc[v] : bv;
-                    bi = gt ? (ct * 32 + 8 * (v >> 2) + (v & 3)) : bi;
-                }
+                for (int b = 0; b < 4; ++b) sbit[b] = bit[b];
+                sbit[4] = 0;
+            } else {
+                const bool gt = m > sv;
+                const u64 e = __builtin_amdgcn_ballot_w64(gt);
+                sv = gt ? m : sv;
+#pragma unroll
+                for (int b = 0; b < 4; ++b) sbit[b] = mask_mux(e, bit[b], sbit[b]);
+                sbit[4] = e;
             }
-            const uint32_t cid = (uint32_t)(cbase + bi + 4 * half);
-            const u64 pk = ((u64)f32_ordered(bv) << 32) | (u64)(0xFFFFFFFFu - cid);
-            atomicMax(&best[sub * 32 + col], pk);
+            if (ct == CT - 1) {
+                const uint32_t local = (__builtin_amdgcn_inverse_ballot_w64(sbit[0]) ? 1u : 0u) |
+                                       (__builtin_amdgcn_inverse_ballot_w64(sbit[1]) ? 2u : 0u) |
+                                       (__builtin_amdgcn_inverse_ballot_w64(sbit[2]) ? 8u : 0u) |
+                                       (__builtin_amdgcn_inverse_ballot_w64(sbit[3]) ? 16u : 0u) |
+                                       (__builtin_amdgcn_inverse_ballot_w64(sbit[4]) ? 32u : 0u);
+                // +0.0f: a score of -0 must pack like +0
+                const u64 pk = ((u64)f32_ordered(sv + 0.0f) << 32) | (u64)(inv_cid0 - local);
+                atomicMax(&bestt[(kw + i * KW) * 32 + col], pk);
+            }
         }
+        ICE_BSTAMP(2 + 2 * (t & 3));
+        ICE_WSTAMP(t, 1);
         if (t + 1 < ntiles) store_tile(buf ^ 1);
+        ICE_WSTAMP(t, 2);
         __syncthreads();
+        ICE_WSTAMP(t, 3);
+        ICE_BSTAMP(3 + 2 * (t & 3));
+        // the per-key winners of this tile leave through the first 256 threads; the other buffer
+        // collects the next tile meanwhile, and this one is not touched again before the barrier
+        // of the next tile
         if (tid < kAssignTile) {
             const int key = k0 + t * kAssignTile + tid;
             if (key < kend) {
                 u64 *dst = d.packed + (size_t)u * d.max_tokens + key;
-                if (zsplit == 1) *dst = best[tid];
-                else atomicMax(dst, best[tid]);
+                if (zsplit == 1) *dst = bestt[tid];
+                else atomicMax(dst, bestt[tid]);
             }
-            best[tid] = 0ull;
+            bestt[tid] = 0ull;
         }
-        __syncthreads();
     }
 }
+
+#ifdef ICE_PROF
+}  // namespace ice
+extern "C" int ice_debug_prof_b(long long *host16) {
+    return (int)hipMemcpyFromSymbol(host16, HIP_SYMBOL(ice::ice_prof_b), sizeof(long long) * 16);
+}
+extern "C" int ice_debug_prof_w(long long *host128) {
+    return (int)hipMemcpyFromSymbol(host128, HIP_SYMBOL(ice::ice_prof_w), sizeof(long long) * 128);
+}
+namespace ice {
+#endif
 
 void launch_assign(const Dev &d, const bf16_t *K, int n, int cur, hipStream_t st) {
     const int tiles = d.Cpad / 32;
@@ -233,11 +366,17 @@ void launch_assign(const Dev &d, const bf16_t *K, int n, int cur, hipStream_t st
     while (CW < 8 && CW * CT < tiles) CW *= 2;
     const int cblock = CT * CW * 32;
     const int zsplit = (d.Cpad + cblock - 1) / cblock;
-    // enough workgroups to fill 256 CUs, each amortising its centroid load over >= 512 keys
+    // One workgroup per CU when the work allows it (a workgroup fills a CU: 140 KB of LDS, 8 waves
+    // of ~230 registers), each amortising its prologue over as many key tiles as possible.
     int keys_per_wg = kAssignTile;
-    while ((long long)((n + keys_per_wg - 1) / keys_per_wg) * zsplit * d.U > 512 && keys_per_wg < 4096) keys_per_wg *= 2;
+    int wg_target = 256, kpw_max = 1 << 30;
+#ifdef ICE_PROF
+    if (const char *e = getenv("ICE_ASSIGN_WGS")) wg_target = atoi(e);
+    if (const char *e = getenv("ICE_ASSIGN_KPW")) kpw_max = atoi(e);
+#endif
+    while ((long long)((n + keys_per_wg - 1) / keys_per_wg) * zsplit * d.U > wg_target && keys_per_wg < kpw_max) keys_per_wg *= 2;
     dim3 grid((n + keys_per_wg - 1) / keys_per_wg, zsplit, d.U);
-    const size_t lds = 2 * kAssignTile * kKeyStride * 2 + kAssignTile * 8;
+    const size_t lds = 2 * kAssignTile * kKeyStride * 2 + 2 * kAssignTile * 8;
     if (zsplit > 1) {
         const size_t tot = (size_t)d.U * d.max_tokens;
         hipLaunchKernelGGL(fill_u64_kernel, dim3(1024), dim3(256), 0, st, d.packed, tot, 0ull);
