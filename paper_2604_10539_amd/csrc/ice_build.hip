@@ -398,31 +398,33 @@ void launch_assign(const Dev &d, const bf16_t *K, int n, int cur, hipStream_t st
 // Stable counting sort of the tokens by cluster (ascending position inside a cluster): the order
 // both the deterministic means and the page layout need.  Three small kernels: per-chunk
 // histograms (which also unpack the assignment), scans, ranks.
-__global__ __launch_bounds__(256) void sort_hist_kernel(Dev d, int n, int n_chunks, float *best_out,
-                                                         int *assign_out) {
-    extern __shared__ int cnt[];  // [4][Cpad]
-    const int u = blockIdx.y, wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
-    const int chunk = blockIdx.x * 4 + wave;
-    int *my = cnt + wave * d.Cpad;
-    for (int c = lane; c < d.Cpad; c += 64) my[c] = 0;
+__global__ __launch_bounds__(64) void sort_hist_kernel(Dev d, int n, int n_chunks, float *best_out,
+                                                        int *assign_out) {
+    extern __shared__ int cnt[];  // [Cpad]
+    const int u = blockIdx.y, lane = threadIdx.x, chunk = blockIdx.x;
+    for (int c = lane; c < d.Cpad; c += 64) cnt[c] = 0;
+    constexpr int NG = kSortChunk / 64;
+    const int i0 = chunk * kSortChunk;
+    u64 pk[NG];  // the whole chunk is in flight before the first counter is touched
+#pragma unroll
+    for (int g = 0; g < NG; ++g) {
+        const int i = i0 + g * 64 + lane;
+        pk[g] = i < n ? d.packed[(size_t)u * d.max_tokens + i] : 0ull;
+    }
     __syncthreads();
-    if (chunk < n_chunks) {
-        const int i0 = chunk * kSortChunk;
-        for (int g = 0; g < kSortChunk / 64; ++g) {
-            const int i = i0 + g * 64 + lane;
-            if (i < n) {
-                const u64 pk = d.packed[(size_t)u * d.max_tokens + i];
-                const int a = (int)(0xFFFFFFFFu - (uint32_t)pk);
-                d.assign[(size_t)u * d.max_tokens + i] = a;
-                if (assign_out) assign_out[(size_t)u * n + i] = a;
-                if (best_out) best_out[(size_t)u * n + i] = -2.0f * ordered_f32((uint32_t)(pk >> 32));
-                atomicAdd(&my[a], 1);
-            }
+#pragma unroll
+    for (int g = 0; g < NG; ++g) {
+        const int i = i0 + g * 64 + lane;
+        if (i < n) {
+            const int a = (int)(0xFFFFFFFFu - (uint32_t)pk[g]);
+            d.assign[(size_t)u * d.max_tokens + i] = a;
+            if (assign_out) assign_out[(size_t)u * n + i] = a;
+            if (best_out) best_out[(size_t)u * n + i] = -2.0f * ordered_f32((uint32_t)(pk[g] >> 32));
+            atomicAdd(&cnt[a], 1);
         }
     }
     __syncthreads();
-    if (chunk < n_chunks)
-        for (int c = lane; c < d.Cpad; c += 64) d.chunk_hist[((size_t)u * n_chunks + chunk) * d.Cpad + c] = my[c];
+    for (int c = lane; c < d.Cpad; c += 64) d.chunk_hist[((size_t)u * n_chunks + chunk) * d.Cpad + c] = cnt[c];
 }
 
 // One workgroup per unit: per cluster, exclusive scan of the chunk histograms over the chunks;
@@ -438,10 +440,15 @@ __global__ __launch_bounds__(1024) void sort_scan_kernel(Dev d, int n_chunks) {
         int tot = 0;
         if (c < d.Cpad) {
             int *h = d.chunk_hist + (size_t)u * n_chunks * d.Cpad + c;
-            for (int k = 0; k < n_chunks; ++k) {
-                const int t = h[(size_t)k * d.Cpad];
-                h[(size_t)k * d.Cpad] = tot;
-                tot += t;
+            for (int k0 = 0; k0 < n_chunks; k0 += 16) {  // 16 counts in flight per round trip
+                int v[16];
+#pragma unroll
+                for (int j = 0; j < 16; ++j) v[j] = k0 + j < n_chunks ? h[(size_t)(k0 + j) * d.Cpad] : 0;
+#pragma unroll
+                for (int j = 0; j < 16; ++j) {
+                    if (k0 + j < n_chunks) h[(size_t)(k0 + j) * d.Cpad] = tot;
+                    tot += v[j];
+                }
             }
         }
         const int pages = (tot + d.s - 1) / d.s;
@@ -475,21 +482,26 @@ __global__ __launch_bounds__(1024) void sort_scan_kernel(Dev d, int n_chunks) {
     }
 }
 
-__global__ __launch_bounds__(256) void sort_rank_kernel(Dev d, int n, int n_chunks, int nbits) {
-    extern __shared__ int cnt[];  // [4][Cpad] running write positions
-    const int u = blockIdx.y, wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
-    const int chunk = blockIdx.x * 4 + wave;
-    if (chunk >= n_chunks) return;  // no workgroup-wide barrier below
-    int *my = cnt + wave * d.Cpad;
-    for (int c = lane; c < d.Cpad; c += 64)
-        my[c] = d.cluster_start[(size_t)u * (d.Cpad + 1) + c] + d.chunk_hist[((size_t)u * n_chunks + chunk) * d.Cpad + c];
-    __builtin_amdgcn_wave_barrier();
-    const u64 lt = (1ull << lane) - 1ull;
+__global__ __launch_bounds__(64) void sort_rank_kernel(Dev d, int n, int n_chunks, int nbits) {
+    extern __shared__ int cnt[];  // [Cpad] running write positions
+    const int u = blockIdx.y, lane = threadIdx.x, chunk = blockIdx.x;
+    constexpr int NG = kSortChunk / 64;
     const int i0 = chunk * kSortChunk;
-    for (int g = 0; g < kSortChunk / 64; ++g) {
+    int av[NG];
+#pragma unroll
+    for (int g = 0; g < NG; ++g) {
+        const int i = i0 + g * 64 + lane;
+        av[g] = i < n ? d.assign[(size_t)u * d.max_tokens + i] : 0;
+    }
+    for (int c = lane; c < d.Cpad; c += 64)
+        cnt[c] = d.cluster_start[(size_t)u * (d.Cpad + 1) + c] + d.chunk_hist[((size_t)u * n_chunks + chunk) * d.Cpad + c];
+    __syncthreads();
+    const u64 lt = (1ull << lane) - 1ull;
+#pragma unroll
+    for (int g = 0; g < NG; ++g) {
         const int i = i0 + g * 64 + lane;
         const bool valid = i < n;
-        const int a = valid ? d.assign[(size_t)u * d.max_tokens + i] : 0;
+        const int a = av[g];
         u64 peers = __ballot(valid);
         for (int b = 0; b < nbits; ++b) {
             const bool bit = (a >> b) & 1;
@@ -499,7 +511,7 @@ __global__ __launch_bounds__(256) void sort_rank_kernel(Dev d, int n, int n_chun
         if (!valid) peers = 0ull;  // (only trailing lanes of the last group)
         int base = 0;
         const int leader = valid ? (int)__builtin_ctzll(peers) : lane;
-        if (valid && lane == leader) base = atomicAdd(&my[a], (int)__popcll(peers));
+        if (valid && lane == leader) base = atomicAdd(&cnt[a], (int)__popcll(peers));
         base = __shfl(base, leader);
         if (valid) d.order[(size_t)u * d.max_tokens + base + (int)__popcll(peers & lt)] = i;
     }
@@ -509,11 +521,10 @@ void launch_sort(const Dev &d, int n, float *best_out, int *assign_out, hipStrea
     const int n_chunks = (n + kSortChunk - 1) / kSortChunk;
     int nbits = 0;
     while ((1 << nbits) < d.Cpad) ++nbits;
-    const size_t lds = (size_t)4 * d.Cpad * sizeof(int);
-    hipLaunchKernelGGL(sort_hist_kernel, dim3((n_chunks + 3) / 4, d.U), dim3(256), lds, st, d, n, n_chunks, best_out,
-                       assign_out);
+    const size_t lds = (size_t)d.Cpad * sizeof(int);
+    hipLaunchKernelGGL(sort_hist_kernel, dim3(n_chunks, d.U), dim3(64), lds, st, d, n, n_chunks, best_out, assign_out);
     hipLaunchKernelGGL(sort_scan_kernel, dim3(d.U), dim3(1024), 0, st, d, n_chunks);
-    hipLaunchKernelGGL(sort_rank_kernel, dim3((n_chunks + 3) / 4, d.U), dim3(256), lds, st, d, n, n_chunks, nbits);
+    hipLaunchKernelGGL(sort_rank_kernel, dim3(n_chunks, d.U), dim3(64), lds, st, d, n, n_chunks, nbits);
 }
 
 // ------------------------------------------------------------------------------------------------
@@ -534,12 +545,29 @@ __global__ __launch_bounds__(256) void means_kernel(Dev d, const bf16_t *__restr
     float acc[8];
 #pragma unroll
     for (int j = 0; j < 8; ++j) acc[j] = 0.f;
-    for (int r = g; r < cnt; r += 4) {
-        const uint4 w = ((const uint4 *)(Ku + (size_t)ord[r] * kD))[ch];
-        acc[0] += bf16_lo(w.x); acc[1] += bf16_hi(w.x);
-        acc[2] += bf16_lo(w.y); acc[3] += bf16_hi(w.y);
-        acc[4] += bf16_lo(w.z); acc[5] += bf16_hi(w.z);
-        acc[6] += bf16_lo(w.w); acc[7] += bf16_hi(w.w);
+    // Group g sums rows g, g+4, g+8, ... in that order.  The member list is read 64 entries at a
+    // time (one per lane) and the rows are fetched eight per group at once, so a wave keeps 8 KB
+    // of key rows in flight instead of one dependent load pair per step.
+    for (int base = 0; base < cnt; base += 64) {
+        const int mine = base + lane < cnt ? ord[base + lane] : -1;
+        const int rows = min(64, cnt - base);
+#pragma unroll
+        for (int h = 0; h < 2; ++h) {
+            if (h * 32 >= rows) break;
+            uint4 w[8];
+#pragma unroll
+            for (int k = 0; k < 8; ++k) {
+                const int tok = __shfl(mine, 4 * (h * 8 + k) + g);
+                w[k] = tok >= 0 ? ((const uint4 *)(Ku + (size_t)tok * kD))[ch] : make_uint4(0, 0, 0, 0);
+            }
+#pragma unroll
+            for (int k = 0; k < 8; ++k) {  // rows past the end add +0
+                acc[0] += bf16_lo(w[k].x); acc[1] += bf16_hi(w[k].x);
+                acc[2] += bf16_lo(w[k].y); acc[3] += bf16_hi(w[k].y);
+                acc[4] += bf16_lo(w[k].z); acc[5] += bf16_hi(w[k].z);
+                acc[6] += bf16_lo(w[k].w); acc[7] += bf16_hi(w[k].w);
+            }
+        }
     }
 #pragma unroll
     for (int j = 0; j < 8; ++j) {
