@@ -160,6 +160,17 @@ ice_status_t ice_debug_assign(ice_index_t *idx, const void *K, int32_t n, const 
                               int32_t n_clusters, int32_t *assign_out, float *best_out_or_null,
                               void *stream);
 
+/* Measured-peak microbenchmarks for the benchmark's roofline context (no method arithmetic):
+ *   ice_debug_peak_read  streams `bytes` (multiple of 16, 16-byte aligned device pointer) once with
+ *                        16-byte loads; achieved bytes/s = bytes / kernel time.
+ *   ice_debug_peak_mfma  runs `iters` rounds of four independent v_mfma_f32_32x32x16_bf16 chains per
+ *                        wave on register operands and writes the flop count of the launch to the
+ *                        HOST double *flops_out (may be null).
+ * `sink` is a device buffer of at least 524288 floats that keeps the results alive.  Both only
+ * enqueue on `stream`.  INVALID_ARG for null / misaligned pointers or iters < 1. */
+ice_status_t ice_debug_peak_read(const void *buf, size_t bytes, float *sink, void *stream);
+ice_status_t ice_debug_peak_mfma(float *sink, int32_t iters, double *flops_out, void *stream);
+
 const char *ice_last_error(void);
 
 #ifdef __cplusplus

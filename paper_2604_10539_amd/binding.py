@@ -18,7 +18,7 @@ STATUS_NAMES = ["ICE_OK", "ICE_ERR_INVALID_ARG", "ICE_ERR_SHAPE", "ICE_ERR_STATE
                 "ICE_ERR_UNSUPPORTED", "ICE_ERR_DEVICE"]
 SYMBOLS = ["ice_workspace_bytes", "ice_create", "ice_destroy", "ice_build_index", "ice_insert", "ice_select",
            "ice_attend", "ice_select_attend", "ice_export_index", "ice_import_index", "ice_debug_assign",
-           "ice_last_error"]
+           "ice_debug_peak_read", "ice_debug_peak_mfma", "ice_last_error"]
 
 
 class IceConfig(C.Structure):
@@ -67,6 +67,8 @@ def lib() -> C.CDLL:
         L.ice_import_index.argtypes = [C.c_void_p, C.POINTER(IceIndexView), C.c_void_p]
         L.ice_debug_assign.argtypes = [C.c_void_p, C.c_void_p, C.c_int32, C.c_void_p, C.c_int32, C.c_void_p,
                                        C.c_void_p, C.c_void_p]
+        L.ice_debug_peak_read.argtypes = [C.c_void_p, C.c_size_t, C.c_void_p, C.c_void_p]
+        L.ice_debug_peak_mfma.argtypes = [C.c_void_p, C.c_int32, C.POINTER(C.c_double), C.c_void_p]
         for name in SYMBOLS:
             if name not in ("ice_last_error", "ice_workspace_bytes"):
                 getattr(L, name).restype = C.c_int
@@ -153,6 +155,17 @@ def ice_import_index(idx, view: IceIndexView, stream=None) -> None:
 def ice_debug_assign(idx, K, n, centroids_bf16, n_clusters, assign_out, best_out=None, stream=None) -> None:
     _check(lib().ice_debug_assign(idx, _ptr(K), n, _ptr(centroids_bf16), n_clusters, _ptr(assign_out),
                                   _ptr(best_out), _stream(stream)))
+
+
+def ice_debug_peak_read(buf, nbytes, sink, stream=None) -> None:
+    _check(lib().ice_debug_peak_read(_ptr(buf), nbytes, _ptr(sink), _stream(stream)))
+
+
+def ice_debug_peak_mfma(sink, iters, stream=None) -> float:
+    """Enqueues the MFMA loop; returns the flop count of the launch."""
+    flops = C.c_double(0.0)
+    _check(lib().ice_debug_peak_mfma(_ptr(sink), iters, C.byref(flops), _stream(stream)))
+    return flops.value
 
 
 # ------------------------------------------------------------------------------------------------

@@ -1,0 +1,76 @@
+// Two microbenchmarks of what the chip reaches on the two resources the hot path is bound by:
+// a streaming read (HBM) and a register-resident MFMA loop (matrix cores).  They run in the same
+// process as the benchmark so that its roofline fractions can be quoted against measured peaks
+// as well as against the nominal ones.  No part of the method's arithmetic is here.
+#include <hip/hip_runtime.h>
+
+#include "ice_internal.h"
+#include "icecache.h"
+
+namespace ice {
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+
+constexpr int kPeakBlocks = 2048;  // 8 workgroups of 4 waves per CU
+
+// every lane reads 16 bytes per load, four loads in flight, grid-stride; the xor keeps the loads alive
+__global__ __launch_bounds__(256) void peak_read_kernel(const uint4 *__restrict__ p, size_t n16, float *sink) {
+    size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    const size_t stride = (size_t)gridDim.x * blockDim.x;
+    uint4 acc = make_uint4(0, 0, 0, 0);
+    for (; i + 3 * stride < n16; i += 4 * stride) {
+        const uint4 a = p[i], b = p[i + stride], c = p[i + 2 * stride], e = p[i + 3 * stride];
+        acc.x ^= a.x ^ b.x ^ c.x ^ e.x;
+        acc.y ^= a.y ^ b.y ^ c.y ^ e.y;
+        acc.z ^= a.z ^ b.z ^ c.z ^ e.z;
+        acc.w ^= a.w ^ b.w ^ c.w ^ e.w;
+    }
+    for (; i < n16; i += stride) {
+        const uint4 a = p[i];
+        acc.x ^= a.x; acc.y ^= a.y; acc.z ^= a.z; acc.w ^= a.w;
+    }
+    if ((acc.x ^ acc.y ^ acc.z ^ acc.w) == 0x9E3779B9u) sink[0] = 1.f;  // practically never
+}
+
+// four independent v_mfma_f32_32x32x16_bf16 accumulator chains per wave, operands in registers
+__global__ __launch_bounds__(256) void peak_mfma_kernel(float *sink, int iters) {
+    bf16x8 a, b;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+        a[i] = (__bf16)(float)((threadIdx.x + i) & 7);
+        b[i] = (__bf16)(float)(i + 1);
+    }
+    f32x16 acc[4];
+#pragma unroll
+    for (int k = 0; k < 4; ++k)
+#pragma unroll
+        for (int i = 0; i < 16; ++i) acc[k][i] = 0.f;
+    for (int it = 0; it < iters; ++it) {
+#pragma unroll
+        for (int k = 0; k < 4; ++k) acc[k] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, acc[k], 0, 0, 0);
+    }
+    float s = 0.f;
+#pragma unroll
+    for (int k = 0; k < 4; ++k)
+#pragma unroll
+        for (int i = 0; i < 16; ++i) s += acc[k][i];
+    sink[(size_t)blockIdx.x * blockDim.x + threadIdx.x] = s;
+}
+
+}  // namespace ice
+
+extern "C" ice_status_t ice_debug_peak_read(const void *buf, size_t bytes, float *sink, void *stream) {
+    if (!buf || !sink || bytes < 16 || (reinterpret_cast<uintptr_t>(buf) & 15u)) return ICE_ERR_INVALID_ARG;
+    hipLaunchKernelGGL(ice::peak_read_kernel, dim3(ice::kPeakBlocks), dim3(256), 0, (hipStream_t)stream,
+                       (const uint4 *)buf, bytes / 16, sink);
+    return hipGetLastError() == hipSuccess ? ICE_OK : ICE_ERR_DEVICE;
+}
+
+extern "C" ice_status_t ice_debug_peak_mfma(float *sink, int32_t iters, double *flops_out, void *stream) {
+    if (!sink || iters < 1) return ICE_ERR_INVALID_ARG;
+    hipLaunchKernelGGL(ice::peak_mfma_kernel, dim3(ice::kPeakBlocks), dim3(256), 0, (hipStream_t)stream, sink, iters);
+    // waves x iterations x 4 chains x (2 * 32 * 32 * 16) flops
+    if (flops_out) *flops_out = (double)ice::kPeakBlocks * 4.0 * iters * 4.0 * 32768.0;
+    return hipGetLastError() == hipSuccess ? ICE_OK : ICE_ERR_DEVICE;
+}

@@ -62,6 +62,18 @@ def test_host_side_argument_errors():
     assert status(p.ice_destroy, 0) == b.ICE_ERR_INVALID_ARG
 
 
+def test_peak_microbenchmarks_reject_bad_arguments():
+    import paper_2604_10539_amd as p
+    from paper_2604_10539_amd import binding as b
+    fake = 0x10000000
+    for call in (lambda: b.lib().ice_debug_peak_read(None, 1 << 20, fake, None),
+                 lambda: b.lib().ice_debug_peak_read(fake + 4, 1 << 20, fake, None),
+                 lambda: b.lib().ice_debug_peak_read(fake, 8, fake, None),
+                 lambda: b.lib().ice_debug_peak_mfma(None, 16, None, None),
+                 lambda: b.lib().ice_debug_peak_mfma(fake, 0, None, None)):
+        assert call() == b.ICE_ERR_INVALID_ARG
+
+
 def test_product_package_never_touches_the_oracle():
     pkg = os.path.join(ROOT, "paper_2604_10539_amd")
     for dirpath, _, files in os.walk(pkg):
