@@ -339,11 +339,13 @@ void launch_attend(const Dev &d, const bf16_t *q, const int *ids, const int *n_s
 // Workgroup ids are mapped so that all chunks of a unit share (id mod 8), i.e. the same XCD and L2.
 //
 // Phase B, last workgroup of the unit: exact top-k over the composite key (score, lower id first),
-// all keys distinct.  Each wave finds the k-th largest of the keys it holds in registers with a
-// bitwise radix descent on wave ballots (no atomics, no barriers); the largest of these thresholds
-// cannot exceed the global k-th largest, so only keys at or above it (at most k per wave) go to an
-// LDS candidate list, where every candidate counts how many candidates beat it.  Rank < k wins;
-// winners are placed in ascending id order.
+// all keys distinct.  A threshold that at least k keys reach comes first: the keys sit in registers,
+// every 16-lane row takes the maximum of its keys, and the k-th largest of these row maxima is
+// such a threshold (k different rows hold a key at or above it); with 64 rows and k = 16 it lets
+// through barely more than k keys.  (Budgets above the row count use a bitwise radix descent on
+// wave ballots instead.)  Keys at or above the threshold go to an LDS candidate list, where every
+// candidate counts how many candidates beat it.  Rank < k wins; winners are placed in ascending id
+// order.
 //
 // Phase C, same workgroup: attention over the winners (attend_pages), ids never leave the chip.
 template <int G, int NW, int EMAX>
@@ -354,6 +356,7 @@ __global__ __launch_bounds__(NW * 64) void decode_step_kernel(Dev d, const bf16_
     extern __shared__ __align__(16) char smem[];
     __shared__ int sh_last, sh_M, sh_M2, sh_W;
     __shared__ uint32_t sh_pre;
+    __shared__ uint32_t sh_rowmax[4 * NW];
     __shared__ u64 sh_tau;
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
     const int g = lane >> 4, ch = lane & 15;
@@ -369,6 +372,12 @@ __global__ __launch_bounds__(NW * 64) void decode_step_kernel(Dev d, const bf16_
     uint32_t *sc_lds = (uint32_t *)(smem + lds_scores_off);
 
     if (chunk == 0) ICE_STAMP(0);
+    if (tid == 0) {  // (visible to the workgroup after the barrier that ends phase A)
+        sh_M = 0;
+        sh_W = 0;
+        sh_pre = 0u;
+        sh_tau = 0ull;
+    }
     // ---- phase A: scores of this chunk, 16 pages per v_mfma_f32_16x16x32_bf16 chain.
     // A operand = the G query rows (rows >= G are zero), B operand = 16 representative rows: lane
     // (g = lane/16, r = lane%16) reads bytes [64*ks + 16*g, +16) of row r for k-step ks, i.e. one
@@ -424,21 +433,16 @@ __global__ __launch_bounds__(NW * 64) void decode_step_kernel(Dev d, const bf16_
     // and the reader re-reads a slot until it is filled.  Writers never wait, so the reader only ever
     // waits for stores that were issued and completed (barrier below) before the counter moved.
     __syncthreads();
-    if (tid == 0) {
-        int last = 1;
-        if (!single) {
+    if (!single) {
+        if (tid == 0) {
             const int old = __hip_atomic_fetch_add(d.counter + u, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            last = old == chunks - 1;
+            const int last = old == chunks - 1;
             if (last) __hip_atomic_store(d.counter + u, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);  // next launch
+            sh_last = last;
         }
-        sh_last = last;
-        sh_M = 0;
-        sh_W = 0;
-        sh_pre = 0u;
-        sh_tau = 0ull;
+        __syncthreads();
+        if (!sh_last) return;
     }
-    __syncthreads();
-    if (!sh_last) return;
     ICE_STAMP(1);
     // all of a thread's score words are requested first, then checked: one round trip, not E
     auto finish_score = [&](int pid, uint32_t v) -> uint32_t {
@@ -477,9 +481,9 @@ __global__ __launch_bounds__(NW * 64) void decode_step_kernel(Dev d, const bf16_
             if (sco) sco[x] = __uint_as_float(v);
         }
     } else {
-        // B1: every wave finds the 16-bit prefix of the k-th largest key it holds (bitwise radix
-        // descent on wave ballots; the candidate sets live in scalar registers).  Keys below the
-        // largest such prefix cannot be among the k largest of the unit.
+        // (budgets above the row count: every wave finds the 16-bit prefix of the k-th largest key it
+        // holds by a bitwise radix descent on wave ballots, the candidate sets in scalar registers;
+        // keys below the largest such prefix cannot be among the k largest of the unit)
         uint32_t key[EMAX];
         u64 cm[EMAX];
         int nvalid = 0;
@@ -494,23 +498,27 @@ __global__ __launch_bounds__(NW * 64) void decode_step_kernel(Dev d, const bf16_
             nvalid += (int)__popcll(cm[e]);
         }
         ICE_STAMP(2);
-        if (k <= 32) {
-            // the k-th largest of the 64 per-lane maxima is a lower bound of the wave's k-th largest
+        constexpr int NR = 4 * NW;  // 16-lane rows in the workgroup
+        if (k <= NR) {
+            // B1: the k-th largest row maximum (rows without keys count as 0, the smallest key)
             uint32_t lmax = key[0];
 #pragma unroll
             for (int e = 1; e < EMAX; ++e) lmax = max(lmax, key[e]);
-            u64 m1 = cm[0];
-            if ((int)__popcll(m1) >= k) {  // (wave-uniform)
-                int kk = k;
-                uint32_t pre = 0;
-                for (int bit = 31; bit >= 12; --bit) {
-                    const u64 bm = __ballot((lmax >> bit) & 1u) & m1;
-                    const int cnt = (int)__popcll(bm);
-                    if (cnt >= kk) { pre |= 1u << bit; m1 = bm; }
-                    else { kk -= cnt; m1 ^= bm; }
-                }
-                if (lane == 0) atomicMax(&sh_pre, pre);
+            lmax = row16_max_u32(lmax);
+            if (ch == 0) sh_rowmax[wave * 4 + g] = lmax;
+            __syncthreads();
+            // rank of row maximum i among the NR (equal values: lower row first); 16 lanes share the work
+            const int i = tid >> 4, part = tid & 15;
+            const uint32_t v = sh_rowmax[i];
+            uint32_t c = 0;
+#pragma unroll
+            for (int jj = 0; jj < NR / 16; ++jj) {
+                const int j = part * (NR / 16) + jj;
+                const uint32_t o = sh_rowmax[j];
+                c += (o > v || (o == v && j < i)) ? 1u : 0u;
             }
+            c = row16_sum_u32(c);
+            if (part == 0 && (int)c == k - 1) sh_pre = v;
         } else if (nvalid >= k) {  // (wave-uniform) otherwise every key of this wave stays a candidate
             int kk = k;
             uint32_t pre = 0;
@@ -537,16 +545,26 @@ __global__ __launch_bounds__(NW * 64) void decode_step_kernel(Dev d, const bf16_
         __syncthreads();
         const uint32_t pre = sh_pre;
         ICE_STAMP(3);
-        // B2: candidates = (score key, ~page id) composites at or above the prefix; all distinct
+        // B2: candidates = (score key, ~page id) composites at or above the threshold; all distinct.
+        // One LDS counter bump per wave reserves the slots of all its candidates.
+        {
+            u64 bal[EMAX];
+            int tot = 0;
 #pragma unroll
-        for (int e = 0; e < EMAX; ++e) {
-            const int pid = e * NT + tid;
-            const bool is = pid < np && key[e] >= pre;
-            const u64 bal = __ballot(is);
+            for (int e = 0; e < EMAX; ++e) {
+                bal[e] = __ballot(e * NT + tid < np && key[e] >= pre);
+                tot += (int)__popcll(bal[e]);
+            }
             int base = 0;
-            if (lane == 0 && bal) base = atomicAdd(&sh_M, (int)__popcll(bal));
+            if (lane == 0 && tot) base = atomicAdd(&sh_M, tot);
             base = __shfl(base, 0);
-            if (is) cand[base + (int)__popcll(bal & ((1ull << lane) - 1ull))] = ((u64)key[e] << 32) | (u64)(0xFFFFFFFFu - (uint32_t)pid);
+#pragma unroll
+            for (int e = 0; e < EMAX; ++e) {
+                const int pid = e * NT + tid;
+                if ((bal[e] >> lane) & 1ull)
+                    cand[base + (int)__popcll(bal[e] & ((1ull << lane) - 1ull))] = ((u64)key[e] << 32) | (u64)(0xFFFFFFFFu - (uint32_t)pid);
+                base += (int)__popcll(bal[e]);
+            }
         }
         __syncthreads();
         const int M = sh_M;  // >= k
@@ -562,8 +580,15 @@ __global__ __launch_bounds__(NW * 64) void decode_step_kernel(Dev d, const bf16_
             const int parts = 1 << lp, i = tid >> lp, part = tid & (parts - 1), len = (M + parts - 1) >> lp;
             const u64 mine = i < M ? cand[i] : ~0ull;
             int rank = 0;
+#pragma unroll 4
             for (int j = part * len; j < min(M, (part + 1) * len); ++j) rank += cand[j] > mine;
-            for (int off = 1; off < parts; off <<= 1) rank += __shfl_xor(rank, off);
+            // sum over the `parts` lanes of a candidate: DPP inside a 16-lane row, shuffles beyond
+            if (parts >= 2) rank += (int)dpp_u32<0xB1>((uint32_t)rank);
+            if (parts >= 4) rank += (int)dpp_u32<0x4E>((uint32_t)rank);
+            if (parts >= 8) rank += (int)dpp_u32<0x141>((uint32_t)rank);
+            if (parts >= 16) rank += (int)dpp_u32<0x140>((uint32_t)rank);
+            if (parts >= 32) rank += __shfl_xor(rank, 16);
+            if (parts >= 64) rank += __shfl_xor(rank, 32);
             if (part == 0 && i < M && rank < k) sel_comp[rank] = mine;
         } else {
             // radix select on LDS histograms, 8 bits a pass, over the (32 + nb)-bit packed composite

@@ -105,6 +105,25 @@ __device__ inline float row16_sum(float x) {
     x += dpp_f32<0x140>(x); // row_mirror
     return x;
 }
+template <int CTRL>
+__device__ inline uint32_t dpp_u32(uint32_t x) {
+    return (uint32_t)__builtin_amdgcn_update_dpp(0, (int)x, CTRL, 0xF, 0xF, true);
+}
+// maximum / sum over the 16 lanes of a DPP row (every lane of the row gets the result)
+__device__ inline uint32_t row16_max_u32(uint32_t x) {
+    x = max(x, dpp_u32<0xB1>(x));
+    x = max(x, dpp_u32<0x4E>(x));
+    x = max(x, dpp_u32<0x141>(x));
+    x = max(x, dpp_u32<0x140>(x));
+    return x;
+}
+__device__ inline uint32_t row16_sum_u32(uint32_t x) {
+    x += dpp_u32<0xB1>(x);
+    x += dpp_u32<0x4E>(x);
+    x += dpp_u32<0x141>(x);
+    x += dpp_u32<0x140>(x);
+    return x;
+}
 __device__ inline float wave_sum(float x) {
     x = row16_sum(x);
     x += __shfl_xor(x, 16);
