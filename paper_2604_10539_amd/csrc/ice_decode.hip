@@ -6,6 +6,7 @@ namespace ice {
 
 typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef short bf16x4s __attribute__((ext_vector_type(4)));  // operand type of the 16x16x16 bf16 MFMA builtin
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef unsigned v2u __attribute__((ext_vector_type(2)));
 typedef unsigned long long u64;
@@ -112,12 +113,17 @@ void launch_insert(const Dev &d, const bf16_t *k, const bf16_t *v, int cur, hipS
 //            (g, r) reads bytes [64*ks + 16*g, +16) of key row r): lane r of row group 0 gets the
 //            logits of token r for heads 0..3 (group 1: heads 4..7);
 //   softmax  running maximum and denominator per head, shared by the whole wave (DPP row maxima),
-//            fp32; the 16 x G weights and the G rescale factors cross to the value layout via LDS;
-//   values   lane (g, c) holds 8 output dims of every head and reads value rows 4t+g, 16 bytes
-//            each (1 KiB per load instruction), fp32 FMAs.
-// The four row groups are summed at the end, the NW waves merged by the (max, sum, output) rule.
-// page_of(x) names the x-th listed page; `red` is LDS scratch of attend_scratch_floats() floats.
-__host__ __device__ constexpr int attend_scratch_floats(int G, int NW) { return NW * (G * (kD + 2) + 16 * 8 + 8); }
+//            fp32; the 16 x G weights cross to the matrix-operand layout via LDS;
+//   values   also on the matrix cores: out[head][dim] += sum_token p[head][token] v[token][dim] as
+//            v_mfma_f32_16x16x16_bf16 with A = the weights, split into two bf16 terms (p = hi + lo,
+//            relative error 2^-16, so the fp32 softmax survives), and B = the value rows.  Lane
+//            (g, c) loads value rows 4t+g, 16 bytes each (1 KiB per load instruction): it holds
+//            tokens {g, 4+g, 8+g, 12+g} x dims 8c..8c+7, which is exactly the B operand of eight
+//            column tiles if tile j is made of dims {8c + j} and contraction slot 4g+i stands for
+//            token 4i+g (a permutation of the sum); two byte-permutes per tile pack it.
+// The NW waves are merged by the (max, sum, output) rule.  page_of(x) names the x-th listed page;
+// `red` is LDS scratch of attend_scratch_floats() floats.
+__host__ __device__ constexpr int attend_scratch_floats(int G, int NW) { return NW * (G * (kD + 2) + 16 * 8); }
 
 template <int G>
 __device__ inline void load_query_operand(const bf16_t *q, int u, int lane, bf16x8 (&qa)[4], float *sumsq) {
@@ -135,23 +141,24 @@ __device__ inline void load_query_operand(const bf16_t *q, int u, int lane, bf16
 template <int G, int NW, typename PageOf>
 __device__ inline void attend_pages(const Dev &d, int u, const bf16x8 (&qa)[4], PageOf page_of, int ns,
                                     float *__restrict__ out, float *red) {
-    constexpr int GR = (G + 3) / 4;  // row groups that hold logits
+    constexpr int GR = (G + 3) / 4;  // row groups that hold logits and outputs
     float(*wacc)[G][kD] = (float(*)[G][kD])red;                   // [NW][G][128]
     float(*wm)[G] = (float(*)[G])(red + NW * G * kD);             // [NW][G]
     float(*wl)[G] = (float(*)[G])(red + NW * G * (kD + 1));       // [NW][G]
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
     const int g = lane >> 4, ch = lane & 15;
-    float *px = red + NW * G * (kD + 2) + wave * (16 * 8 + 8);    // [16 tokens][8 heads] weights of this wave
-    float *al = px + 16 * 8;                                      // [8] rescale factors
+    float *px = red + NW * G * (kD + 2) + wave * (16 * 8);        // [16 tokens][8 heads] weights of this wave
     const float scale = 0.08838834764831845f;  // 1/sqrt(128)
     const int s = d.s;
-    float m[4], l[4], acc[G][8];
+    // lane (g, r): m, l of heads 4g..4g+3 (wave-wide maxima, own-token denominators);
+    // acc[j][v] = output of head 4g+v, dim 8r+j
+    float m[4], l[4];
+    f32x4 acc[8];
 #pragma unroll
     for (int v = 0; v < 4; ++v) { m[v] = -INFINITY; l[v] = 0.f; }
 #pragma unroll
-    for (int h = 0; h < G; ++h)
-#pragma unroll
-        for (int j = 0; j < 8; ++j) acc[h][j] = 0.f;
+    for (int j = 0; j < 8; ++j) acc[j] = f32x4{0.f, 0.f, 0.f, 0.f};
+    bool first = true;
     for (int x = wave; x < ns; x += NW) {
         const int p = page_of(x);
         if ((unsigned)p >= (unsigned)d.max_pages) continue;  // not a page id: ignored
@@ -197,78 +204,56 @@ __device__ inline void attend_pages(const Dev &d, int u, const bf16x8 (&qa)[4], 
                 l[v] = l[v] * alpha[v] + pw[v];
                 m[v] = mn;
             }
-            if (g < GR) {
-                *(float4 *)(px + ch * 8 + 4 * g) = make_float4(pw[0], pw[1], pw[2], pw[3]);
-                if (ch == 0) *(float4 *)(al + 4 * g) = make_float4(alpha[0], alpha[1], alpha[2], alpha[3]);
-            }
+            if (g < GR) *(float4 *)(px + ch * 8 + 4 * g) = make_float4(pw[0], pw[1], pw[2], pw[3]);
             __builtin_amdgcn_wave_barrier();
-            float a[G];
+            // A operand: lane (g, h) holds p[head h][token 4i+g], i = 0..3, as hi + lo bf16 terms
+            float pa[4];
 #pragma unroll
-            for (int h4 = 0; h4 < GR; ++h4) {
-                const float4 t4 = *(const float4 *)(al + 4 * h4);
-                a[4 * h4] = t4.x;
-                if (4 * h4 + 1 < G) a[4 * h4 + 1] = t4.y;
-                if (4 * h4 + 2 < G) a[4 * h4 + 2] = t4.z;
-                if (4 * h4 + 3 < G) a[4 * h4 + 3] = t4.w;
+            for (int i = 0; i < 4; ++i) pa[i] = ch < G ? px[(4 * i + g) * 8 + ch] : 0.f;
+            uint32_t hi[4], lo[4];
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                hi[i] = __float_as_uint(pa[i]) & 0xFFFF0000u;
+                lo[i] = __float_as_uint(pa[i] - __uint_as_float(hi[i]));
+            }
+            const v2u ahi = {__builtin_amdgcn_perm(hi[1], hi[0], 0x07060302u), __builtin_amdgcn_perm(hi[3], hi[2], 0x07060302u)};
+            const v2u alo = {__builtin_amdgcn_perm(lo[1], lo[0], 0x07060302u), __builtin_amdgcn_perm(lo[3], lo[2], 0x07060302u)};
+            if (!first) {  // rescale what earlier blocks left (same lanes hold the factors)
+#pragma unroll
+                for (int j = 0; j < 8; ++j)
+#pragma unroll
+                    for (int v = 0; v < 4; ++v) acc[j][v] *= alpha[v];
+            }
+            first = false;
+            if (fill - b0 < 16) {  // a partly filled block: rows past the end must not reach the matrix core
+#pragma unroll
+                for (int t = 0; t < 4; ++t)
+                    if (b0 + 4 * t + g >= fill) vt[t] = make_uint4(0, 0, 0, 0);
             }
 #pragma unroll
-            for (int h = 0; h < G; ++h)
-#pragma unroll
-                for (int j = 0; j < 8; ++j) acc[h][j] *= a[h];
-#pragma unroll
-            for (int t = 0; t < 4; ++t) {
-                const bool valid = b0 + 4 * t + g < fill;
-                const uint4 vv = valid ? vt[t] : make_uint4(0, 0, 0, 0);
-                const float v0 = bf16_lo(vv.x), v1 = bf16_hi(vv.x), v2 = bf16_lo(vv.y), v3 = bf16_hi(vv.y);
-                const float v4 = bf16_lo(vv.z), v5 = bf16_hi(vv.z), v6 = bf16_lo(vv.w), v7 = bf16_hi(vv.w);
-                float pr[G];
-#pragma unroll
-                for (int h4 = 0; h4 < GR; ++h4) {
-                    const float4 t4 = *(const float4 *)(px + (4 * t + g) * 8 + 4 * h4);
-                    pr[4 * h4] = t4.x;
-                    if (4 * h4 + 1 < G) pr[4 * h4 + 1] = t4.y;
-                    if (4 * h4 + 2 < G) pr[4 * h4 + 2] = t4.z;
-                    if (4 * h4 + 3 < G) pr[4 * h4 + 3] = t4.w;
-                }
-#pragma unroll
-                for (int h = 0; h < G; ++h) {
-                    const float pp = pr[h];
-                    acc[h][0] = fmaf(pp, v0, acc[h][0]); acc[h][1] = fmaf(pp, v1, acc[h][1]);
-                    acc[h][2] = fmaf(pp, v2, acc[h][2]); acc[h][3] = fmaf(pp, v3, acc[h][3]);
-                    acc[h][4] = fmaf(pp, v4, acc[h][4]); acc[h][5] = fmaf(pp, v5, acc[h][5]);
-                    acc[h][6] = fmaf(pp, v6, acc[h][6]); acc[h][7] = fmaf(pp, v7, acc[h][7]);
-                }
+            for (int j = 0; j < 8; ++j) {
+                // column tile j: dims {8c + j}; contraction slot 4g+i = token 4i+g
+                const uint32_t sel = (j & 1) ? 0x07060302u : 0x05040100u;
+                const uint32_t w0 = j < 2 ? vt[0].x : j < 4 ? vt[0].y : j < 6 ? vt[0].z : vt[0].w;
+                const uint32_t w1 = j < 2 ? vt[1].x : j < 4 ? vt[1].y : j < 6 ? vt[1].z : vt[1].w;
+                const uint32_t w2 = j < 2 ? vt[2].x : j < 4 ? vt[2].y : j < 6 ? vt[2].z : vt[2].w;
+                const uint32_t w3 = j < 2 ? vt[3].x : j < 4 ? vt[3].y : j < 6 ? vt[3].z : vt[3].w;
+                const v2u bv = {__builtin_amdgcn_perm(w1, w0, sel), __builtin_amdgcn_perm(w3, w2, sel)};
+                acc[j] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(__builtin_bit_cast(bf16x4s, ahi), __builtin_bit_cast(bf16x4s, bv), acc[j], 0, 0, 0);
+                acc[j] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(__builtin_bit_cast(bf16x4s, alo), __builtin_bit_cast(bf16x4s, bv), acc[j], 0, 0, 0);
             }
-            __builtin_amdgcn_wave_barrier();  // the next block overwrites px / al
+            __builtin_amdgcn_wave_barrier();  // the next block overwrites px
         }
     }
     ICE_STAMP(10);
-    // sum the four row groups (all share the wave's running maxima) with two rounds of lane-swap
-    // instructions: v_permlane32_swap exchanges the upper half of one register with the lower half
-    // of another, v_permlane16_swap the odd 16-lane rows with the even ones, so each swap+add
-    // folds two registers into one.  Of the N = 8G partial sums per lane, lane row r ends up with
-    // the complete sums number n + (N/4) r, n < N/4.
-    {
-        constexpr int N = 8 * G;
-        float R[N];
+    if (g < GR) {
 #pragma unroll
-        for (int h = 0; h < G; ++h)
-#pragma unroll
-            for (int j = 0; j < 8; ++j) R[h * 8 + j] = acc[h][j];
-#pragma unroll
-        for (int n = 0; n < N / 2; ++n) {
-            const v2u r = __builtin_amdgcn_permlane32_swap(__float_as_uint(R[n]), __float_as_uint(R[n + N / 2]), false, false);
-            R[n] = __uint_as_float(r[0]) + __uint_as_float(r[1]);
-        }
-#pragma unroll
-        for (int n = 0; n < N / 4; ++n) {
-            const v2u r = __builtin_amdgcn_permlane16_swap(__float_as_uint(R[n]), __float_as_uint(R[n + N / 4]), false, false);
-            R[n] = __uint_as_float(r[0]) + __uint_as_float(r[1]);
-        }
-#pragma unroll
-        for (int n = 0; n < N / 4; ++n) {
-            const int idx = n + (N / 4) * g;
-            wacc[wave][idx >> 3][ch * 8 + (idx & 7)] = R[n];
+        for (int v = 0; v < 4; ++v) {
+            if (4 * g + v < G) {
+                float *dst = &wacc[wave][4 * g + v][ch * 8];
+                *(float4 *)dst = make_float4(acc[0][v], acc[1][v], acc[2][v], acc[3][v]);
+                *(float4 *)(dst + 4) = make_float4(acc[4][v], acc[5][v], acc[6][v], acc[7][v]);
+            }
         }
     }
 #pragma unroll
