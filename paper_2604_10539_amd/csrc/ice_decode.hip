@@ -12,9 +12,12 @@ typedef unsigned v2u __attribute__((ext_vector_type(2)));
 typedef unsigned long long u64;
 #ifdef ICE_PROF
 __device__ long long ice_prof[16];
+__device__ long long ice_prof_u[4 * 1024];  // per unit: start, end of scoring, end of selection, end
 #define ICE_STAMP(i) do { if (threadIdx.x == 0 && u == 0) ice_prof[i] = wall_clock64(); } while (0)
+#define ICE_USTAMP(i) do { if (threadIdx.x == 0 && u < 1024) ice_prof_u[4 * u + (i)] = wall_clock64(); } while (0)
 #else
 #define ICE_STAMP(i) do { } while (0)
+#define ICE_USTAMP(i) do { } while (0)
 #endif
 constexpr uint32_t kScoreEmpty = 0xFFFFFFFFu;  // a NaN pattern no score can take (scores come out of fmaxf)
 
@@ -122,7 +125,8 @@ void launch_insert(const Dev &d, const bf16_t *k, const bf16_t *v, int cur, hipS
 //            column tiles if tile j is made of dims {8c + j} and contraction slot 4g+i stands for
 //            token 4i+g (a permutation of the sum); two byte-permutes per tile pack it.
 // The NW waves are merged by the (max, sum, output) rule.  page_of(x) names the x-th listed page;
-// `red` is LDS scratch of attend_scratch_floats() floats.
+// `red` is LDS scratch of attend_scratch_floats() floats; aside() is work of the caller that needs
+// no barrier and runs where a wave would otherwise wait for the slowest wave's pages.
 __host__ __device__ constexpr int attend_scratch_floats(int G, int NW) { return NW * (G * (kD + 2) + 16 * 8); }
 
 template <int G>
@@ -138,9 +142,9 @@ __device__ inline void load_query_operand(const bf16_t *q, int u, int lane, bf16
     if (sumsq) *sumsq = nn;
 }
 
-template <int G, int NW, typename PageOf>
+template <int G, int NW, typename PageOf, typename Aside>
 __device__ inline void attend_pages(const Dev &d, int u, const bf16x8 (&qa)[4], PageOf page_of, int ns,
-                                    float *__restrict__ out, float *red) {
+                                    float *__restrict__ out, float *red, Aside aside) {
     constexpr int GR = (G + 3) / 4;  // row groups that hold logits and outputs
     float(*wacc)[G][kD] = (float(*)[G][kD])red;                   // [NW][G][128]
     float(*wm)[G] = (float(*)[G])(red + NW * G * kD);             // [NW][G]
@@ -209,7 +213,10 @@ __device__ inline void attend_pages(const Dev &d, int u, const bf16x8 (&qa)[4], 
             // A operand: lane (g, h) holds p[head h][token 4i+g], i = 0..3, as hi + lo bf16 terms
             float pa[4];
 #pragma unroll
-            for (int i = 0; i < 4; ++i) pa[i] = ch < G ? px[(4 * i + g) * 8 + ch] : 0.f;
+            for (int i = 0; i < 4; ++i) {
+                const float t = px[(4 * i + g) * 8 + (ch & 7)];  // (unconditional read, then select: no branch)
+                pa[i] = ch < G ? t : 0.f;
+            }
             uint32_t hi[4], lo[4];
 #pragma unroll
             for (int i = 0; i < 4; ++i) {
@@ -263,18 +270,22 @@ __device__ inline void attend_pages(const Dev &d, int u, const bf16x8 (&qa)[4], 
         for (int v = 0; v < 4; ++v)
             if (4 * g + v < G) { wm[wave][4 * g + v] = m[v]; wl[wave][4 * g + v] = l[v]; }
     }
+    aside();
     __syncthreads();
     ICE_STAMP(11);
-    if (tid < G) {  // per head: the waves' weights exp(m_w - M) and the reciprocal denominator
-        float M = -INFINITY;
-        for (int w = 0; w < NW; ++w) M = fmaxf(M, wm[w][tid]);
-        float L = 0.f;
-        for (int w = 0; w < NW; ++w) {
-            const float e = M == -INFINITY ? 0.f : __expf(wm[w][tid] - M);
-            L += wl[w][tid] * e;
-            wm[w][tid] = e;
-        }
-        wl[0][tid] = L > 0.f ? 1.0f / L : 0.f;
+    // per head: the waves' merge weights exp(m_w - M) / L, one 16-lane row per head, one lane per wave
+    static_assert(NW <= 16, "one DPP row holds the waves of a head");
+    if (tid < 16 * G) {
+        const int h = tid >> 4, w = tid & 15;
+        const float mw = w < NW ? wm[w][h] : -INFINITY, lw = w < NW ? wl[w][h] : 0.f;
+        float M = mw;
+        M = fmaxf(M, dpp_f32<0xB1>(M));
+        M = fmaxf(M, dpp_f32<0x4E>(M));
+        M = fmaxf(M, dpp_f32<0x141>(M));
+        M = fmaxf(M, dpp_f32<0x140>(M));
+        const float e = M == -INFINITY ? 0.f : __expf(mw - M);
+        const float L = row16_sum(lw * e);
+        if (w < NW) wm[w][h] = L > 0.f ? e / L : 0.f;
     }
     __syncthreads();
     for (int o = tid; o < G * kD; o += NW * 64) {
@@ -282,7 +293,7 @@ __device__ inline void attend_pages(const Dev &d, int u, const bf16x8 (&qa)[4], 
         float O = 0.f;
 #pragma unroll
         for (int w = 0; w < NW; ++w) O += wacc[w][h][j] * wm[w][h];
-        out[((size_t)u * G + h) * kD + j] = O * wl[0][h];
+        out[((size_t)u * G + h) * kD + j] = O;
     }
 }
 
@@ -295,7 +306,7 @@ __global__ __launch_bounds__(NW * 64) void attend_kernel(Dev d, const bf16_t *__
     bf16x8 qa[4];
     load_query_operand<G>(q, u, threadIdx.x & 63, qa, nullptr);
     const int *list = ids + (size_t)u * P;
-    attend_pages<G, NW>(d, u, qa, [=](int x) { return list[x]; }, min(n_sel[u], P), out, (float *)smem);
+    attend_pages<G, NW>(d, u, qa, [=](int x) { return list[x]; }, min(n_sel[u], P), out, (float *)smem, [] {});
 }
 
 void launch_attend(const Dev &d, const bf16_t *q, const int *ids, const int *n_sel, int P, float *out,
@@ -357,6 +368,7 @@ __global__ __launch_bounds__(NW * 64) void decode_step_kernel(Dev d, const bf16_
     uint32_t *sc_lds = (uint32_t *)(smem + lds_scores_off);
 
     if (chunk == 0) ICE_STAMP(0);
+    if (chunk == 0) ICE_USTAMP(0);
     if (tid == 0) {  // (visible to the workgroup after the barrier that ends phase A)
         sh_M = 0;
         sh_W = 0;
@@ -429,6 +441,7 @@ __global__ __launch_bounds__(NW * 64) void decode_step_kernel(Dev d, const bf16_
         if (!sh_last) return;
     }
     ICE_STAMP(1);
+    ICE_USTAMP(1);
     // all of a thread's score words are requested first, then checked: one round trip, not E
     auto finish_score = [&](int pid, uint32_t v) -> uint32_t {
         if (single) return v;
@@ -627,17 +640,14 @@ __global__ __launch_bounds__(NW * 64) void decode_step_kernel(Dev d, const bf16_
     }
     __syncthreads();
     ICE_STAMP(5);
+    ICE_USTAMP(2);
     // ---- phase C: attention over the winners, in rank order (the ids' ascending order is only an
     // output format and is produced afterwards, off the critical path)
     const bool all_pages = k == np;
-    if (out) {
-        ICE_STAMP(6);
-        attend_pages<G, NW>(d, u, qa, [=](int x) { return all_pages ? x : (int)(0xFFFFFFFFu - (uint32_t)sel_comp[x]); }, k,
-                            out, (float *)region);
-        ICE_STAMP(7);
-    }
-    if (!all_pages) {
-        // B4: the winners' places in ascending id order
+    // B4: the winners' places in ascending id order; during the attention it runs where the first
+    // waves would wait for the last ones
+    auto order_ids = [&] {
+        if (all_pages) return;
         for (int t = tid; t < k; t += NT) {
             const u64 mine = sel_comp[t];
             const uint32_t myid = 0xFFFFFFFFu - (uint32_t)mine;
@@ -646,10 +656,22 @@ __global__ __launch_bounds__(NW * 64) void decode_step_kernel(Dev d, const bf16_
             ids[pos] = (int)myid;
             if (sco) sco[pos] = ordered_f32((uint32_t)(mine >> 32));
         }
+    };
+    if (out) {
+        ICE_STAMP(6);
+        attend_pages<G, NW>(d, u, qa, [=](int x) { return all_pages ? x : (int)(0xFFFFFFFFu - (uint32_t)sel_comp[x]); }, k,
+                            out, (float *)region, order_ids);
+        ICE_STAMP(7);
+    } else {
+        order_ids();
     }
+    ICE_USTAMP(3);
 }
 #ifdef ICE_PROF
 }  // namespace ice
+extern "C" int ice_debug_prof_u(long long *host4096) {
+    return (int)hipMemcpyFromSymbol(host4096, HIP_SYMBOL(ice::ice_prof_u), sizeof(long long) * 4096);
+}
 extern "C" int ice_debug_prof(long long *host16) {
     return (int)hipMemcpyFromSymbol(host16, HIP_SYMBOL(ice::ice_prof), sizeof(long long) * 16);
 }
