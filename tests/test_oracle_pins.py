@@ -497,3 +497,23 @@ def test_bf16_rounding_is_nearest_even():
     y = np.random.default_rng(1).standard_normal(10000).astype(np.float32)
     ref = torch.from_numpy(y).to(torch.bfloat16).float().numpy()
     assert np.array_equal(widen(narrow(y)), ref)
+
+
+# ----------------------------------------------------------------------------- change detector
+def test_oracle_still_gives_the_stored_small_case():
+    """tests/golden/oracle_small_case.json was written by tests/golden/write_oracle_fixture.py from the
+    oracle alone; the oracle's answer on that seeded case must not drift unnoticed."""
+    import importlib.util
+    import json
+    import os
+    here = os.path.join(os.path.dirname(os.path.abspath(__file__)), "golden")
+    spec = importlib.util.spec_from_file_location("write_oracle_fixture", os.path.join(here, "write_oracle_fixture.py"))
+    mod = importlib.util.module_from_spec(spec)
+    spec.loader.exec_module(mod)
+    now = json.loads(json.dumps(mod.compute()))
+    with open(os.path.join(here, "oracle_small_case.json")) as f:
+        stored = json.load(f)
+    for key in ("n_pages", "cluster_cnt", "insert_clusters", "page_ids", "n_selected", "sha256_16"):
+        assert now[key] == stored[key], key
+    for key in ("inertia", "scores", "out_head0_first8"):
+        np.testing.assert_allclose(np.array(now[key]), np.array(stored[key]), rtol=1e-6, atol=1e-9)
