@@ -31,27 +31,45 @@ __device__ inline float dot8(const uint4 &a, const uint4 &b) {
 
 // ------------------------------------------------------------------------------------------------
 // Insertion of one token per unit (Alg. 1 insertion loop; a node that outgrows its page gets a new
-// one, Sec. 4.1).  One workgroup per unit: the four waves scan the bf16 centroids
-// (16 lanes x 16 bytes per row) for the nearest one, lowest id on ties; wave 0 then appends the
-// key/value row to the cluster's tail page and updates, in ordered fp32 (one add per quantity):
-// page sum -> representative, cluster sum -> centroid, its bf16 rounding and squared norm.
-__global__ __launch_bounds__(256) void insert_kernel(Dev d, const bf16_t *__restrict__ k,
-                                                      const bf16_t *__restrict__ v, int cur) {
+// one, Sec. 4.1).  One workgroup per unit: its 16 waves scan the bf16 centroids (16 lanes x 16 bytes
+// per row, four rows per wave and load, four loads in flight) for the nearest one, lowest id on
+// ties; wave 0 then appends the key/value row to the cluster's tail page and updates, in ordered
+// fp32 (one add per quantity): page sum -> representative, cluster sum -> centroid, its bf16
+// rounding and squared norm.
+constexpr int kInsertWaves = 16;
+__global__ __launch_bounds__(kInsertWaves * 64) void insert_kernel(Dev d, const bf16_t *__restrict__ k,
+                                                                    const bf16_t *__restrict__ v, int cur) {
     __shared__ u64 best;
     const int u = blockIdx.x, tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
     const int g = lane >> 4, ch = lane & 15;
     if (tid == 0) best = ~0ull;
     __syncthreads();
     const uint4 kq = ((const uint4 *)(k + (size_t)u * kD))[ch];
+    // what the append needs and does not depend on the chosen cluster is requested before the scan
+    const int np = d.n_pages[u];
+    const int tok = d.n_tokens[u];
+    const uint32_t kw = ((const uint32_t *)(k + (size_t)u * kD))[lane];
+    const uint32_t vw = ((const uint32_t *)(v + (size_t)u * kD))[lane];
     const bf16_t *cb = d.cent_bf16[cur] + (size_t)u * d.Cpad * kD;
     const float *wn = d.cnorm[cur] + (size_t)u * d.Cpad;
     float bv = INFINITY;
     int bi = 0x7FFFFFFF;
-    for (int r = wave * 4 + g; r < d.C; r += 16) {
-        const uint4 row = ((const uint4 *)(cb + (size_t)r * kD))[ch];
-        const float dot = row16_sum(dot8(row, kq));
-        const float val = wn[r] - 2.0f * dot;
-        if (val < bv) { bv = val; bi = r; }
+    constexpr int RS = kInsertWaves * 4;  // rows per pass of the workgroup
+    for (int r0 = wave * 4 + g; r0 < d.C; r0 += 4 * RS) {
+        uint4 row[4];
+        float w[4];
+#pragma unroll
+        for (int x = 0; x < 4; ++x) {
+            const int r = r0 + x * RS;
+            row[x] = r < d.C ? ((const uint4 *)(cb + (size_t)r * kD))[ch] : make_uint4(0, 0, 0, 0);
+            w[x] = r < d.C ? wn[r] : INFINITY;
+        }
+#pragma unroll
+        for (int x = 0; x < 4; ++x) {  // ascending r: a later row wins only when strictly smaller
+            const float dot = row16_sum(dot8(row[x], kq));
+            const float val = w[x] - 2.0f * dot;
+            if (val < bv) { bv = val; bi = r0 + x * RS; }
+        }
     }
     if (ch == 0 && bi != 0x7FFFFFFF) atomicMin(&best, ((u64)f32_ordered(bv) << 32) | (u64)(uint32_t)bi);
     __syncthreads();
@@ -60,16 +78,12 @@ __global__ __launch_bounds__(256) void insert_kernel(Dev d, const bf16_t *__rest
     const size_t cl = (size_t)u * d.C + c;
     int tail = d.cluster_tail[cl];
     int fill = tail >= 0 ? d.page_fill[(size_t)u * d.max_pages + tail] : d.s;
-    const int np = d.n_pages[u];
-    const int tok = d.n_tokens[u];
     const int cnt = d.cluster_cnt[cl] + 1;
     const bool fresh = fill == d.s;
     if (fresh) { tail = np; fill = 0; }
     const size_t pg = (size_t)u * d.max_pages + tail;
     const int slot = fill;
     fill += 1;
-    const uint32_t kw = ((const uint32_t *)(k + (size_t)u * kD))[lane];
-    const uint32_t vw = ((const uint32_t *)(v + (size_t)u * kD))[lane];
     ((uint32_t *)(d.Kp + (pg * d.s + slot) * kD))[lane] = kw;
     ((uint32_t *)(d.Vp + (pg * d.s + slot) * kD))[lane] = vw;
     const float k0 = bf16_lo(kw), k1 = bf16_hi(kw);
@@ -105,7 +119,7 @@ __global__ __launch_bounds__(256) void insert_kernel(Dev d, const bf16_t *__rest
 }
 
 void launch_insert(const Dev &d, const bf16_t *k, const bf16_t *v, int cur, hipStream_t st) {
-    hipLaunchKernelGGL(insert_kernel, dim3(d.U), dim3(256), 0, st, d, k, v, cur);
+    hipLaunchKernelGGL(insert_kernel, dim3(d.U), dim3(kInsertWaves * 64), 0, st, d, k, v, cur);
 }
 
 // ------------------------------------------------------------------------------------------------
