@@ -408,7 +408,11 @@ __global__ __launch_bounds__(NW * 64) void decode_step_kernel(Dev d, const bf16_
         const int p0 = chunk * per, pend = min(np_hint, p0 + per);
         const int nblk = (pend - p0 + 15) >> 4;
         constexpr int UNR = 4;
+        static_assert(NW * UNR == 4 * NW, "sh_rowmax holds one maximum per (wave, unroll slot)");
         int lim = pend;  // the first round of loads does not wait for np (np <= np_hint <= max_pages)
+        float gmax[UNR];  // running maximum of the scores this lane produced in unroll slot x
+#pragma unroll
+        for (int x = 0; x < UNR; ++x) gmax[x] = -INFINITY;
         for (int b0 = wave; b0 < nblk; b0 += NW * UNR) {
             uint4 bb[UNR][4];
 #pragma unroll
@@ -434,7 +438,21 @@ __global__ __launch_bounds__(NW * 64) void decode_step_kernel(Dev d, const bf16_
                 if (g == 0 && page < lim) {
                     if (single) sc_lds[page] = __float_as_uint(sc);
                     else __hip_atomic_store(S + page, __float_as_uint(sc), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                    gmax[x] = fmaxf(gmax[x], sc);
                 }
+            }
+        }
+        // With one workgroup per unit the selection threshold needs the maxima of 4*NW disjoint
+        // groups of scores: group (wave, x) is ready here, for free (the kernel is waiting for HBM).
+        if (single) {
+#pragma unroll
+            for (int x = 0; x < UNR; ++x) {
+                float r = gmax[x];
+                r = fmaxf(r, dpp_f32<0xB1>(r));
+                r = fmaxf(r, dpp_f32<0x4E>(r));
+                r = fmaxf(r, dpp_f32<0x141>(r));
+                r = fmaxf(r, dpp_f32<0x140>(r));
+                if (lane == 0) sh_rowmax[wave * 4 + x] = f32_ordered(r);
             }
         }
     }
@@ -512,13 +530,17 @@ __global__ __launch_bounds__(NW * 64) void decode_step_kernel(Dev d, const bf16_
         ICE_STAMP(2);
         constexpr int NR = 4 * NW;  // 16-lane rows in the workgroup
         if (k <= NR) {
-            // B1: the k-th largest row maximum (rows without keys count as 0, the smallest key)
-            uint32_t lmax = key[0];
+            // B1: the k-th largest of the 4*NW group maxima (groups without keys count as the
+            // smallest key).  With several workgroups per unit the groups are the 16-lane rows of
+            // the key registers; with one they were formed while scoring.
+            if (!single) {
+                uint32_t lmax = key[0];
 #pragma unroll
-            for (int e = 1; e < EMAX; ++e) lmax = max(lmax, key[e]);
-            lmax = row16_max_u32(lmax);
-            if (ch == 0) sh_rowmax[wave * 4 + g] = lmax;
-            __syncthreads();
+                for (int e = 1; e < EMAX; ++e) lmax = max(lmax, key[e]);
+                lmax = row16_max_u32(lmax);
+                if (ch == 0) sh_rowmax[wave * 4 + g] = lmax;
+                __syncthreads();
+            }
             // rank of row maximum i among the NR (equal values: lower row first); 16 lanes share the work
             const int i = tid >> 4, part = tid & 15;
             const uint32_t v = sh_rowmax[i];
