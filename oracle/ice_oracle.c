@@ -372,6 +372,99 @@ void orc_select(const orc_state_t *st, const uint16_t *q, int budget, int32_t *i
     }
 }
 
+/* ---- hierarchical page selection ----------------------------------------------------------------
+ * The two-level form of the paper's top-down search (Sec. 4.3, Alg. 3: descend from the parents
+ * that score best to their children).  Stage 1 scores the C cluster centroids, rounded to bf16
+ * as the index stores them, with the same normalised GQA score as the pages (max over the
+ * group's heads of q_h . mu~_c / ||q_h||, fp64 rounded once to fp32) and keeps the
+ * n_keep = min(n_probe, C) best by (score descending, cluster id ascending); every cluster is
+ * eligible, one without pages simply contributes none.  Stage 2 ranks only the live pages whose
+ * cluster was kept, exactly as orc_select ranks all pages, and returns the best
+ * min(P, number of such pages), ids ascending, padded with -1.  With n_probe >= C every page is
+ * a candidate and the result is orc_select's.
+ * clusters (may be NULL): [U][n_probe] kept cluster ids ascending, -1 padded.
+ * Sc_all (may be NULL): [U][C] fp32 centroid scores. */
+void orc_select_hier(const orc_state_t *st, const uint16_t *q, int budget, int n_probe, int32_t *ids,
+                     int32_t *n_sel, float *scores, int32_t *clusters, float *Sc_all) {
+    const int d = st->d, G = st->G, MP = st->max_pages, C = st->C, P = budget / st->s;
+    const int n_keep = n_probe < C ? n_probe : C;
+#pragma omp parallel for schedule(dynamic, 1)
+    for (int u = 0; u < st->U; ++u) {
+        const int np = st->n_pages[u];
+        double qn[64];
+        for (int h = 0; h < G; ++h) {
+            double acc = 0.0;
+            for (int j = 0; j < d; ++j) {
+                double x = bf16_to_f32(q[((size_t)u * G + h) * d + j]);
+                acc += x * x;
+            }
+            qn[h] = sqrt(acc);
+            if (qn[h] < 1e-20) qn[h] = 1e-20;
+        }
+        /* stage 1: clusters */
+        scored_t *cs = (scored_t *)malloc(sizeof(scored_t) * (size_t)C);
+        for (int c = 0; c < C; ++c) {
+            double best = -INFINITY;
+            for (int h = 0; h < G; ++h) {
+                double dot = 0.0;
+                for (int j = 0; j < d; ++j) {
+                    float mu = bf16_to_f32(f32_to_bf16(st->centroid[((size_t)u * C + c) * d + j]));
+                    dot += (double)bf16_to_f32(q[((size_t)u * G + h) * d + j]) * (double)mu;
+                }
+                double sh = dot / qn[h];
+                if (sh > best) best = sh;
+            }
+            cs[c].s = (float)best;
+            cs[c].id = c;
+            if (Sc_all) Sc_all[(size_t)u * C + c] = (float)best;
+        }
+        qsort(cs, (size_t)C, sizeof(scored_t), cmp_scored);
+        char *kept = (char *)calloc((size_t)C, 1);
+        for (int x = 0; x < n_keep; ++x) kept[cs[x].id] = 1;
+        if (clusters) {
+            int w = 0;
+            for (int c = 0; c < C; ++c)
+                if (kept[c]) clusters[(size_t)u * n_probe + w++] = c;
+            for (; w < n_probe; ++w) clusters[(size_t)u * n_probe + w] = -1;
+        }
+        /* stage 2: the pages of the kept clusters */
+        scored_t *sc = (scored_t *)malloc(sizeof(scored_t) * (size_t)(np > 0 ? np : 1));
+        int nc = 0;
+        for (int p = 0; p < np; ++p) {
+            const int c = st->page_cluster[(size_t)u * MP + p];
+            if (c < 0 || c >= C || !kept[c]) continue;
+            double best = -INFINITY;
+            for (int h = 0; h < G; ++h) {
+                double dot = 0.0;
+                for (int j = 0; j < d; ++j)
+                    dot += (double)bf16_to_f32(q[((size_t)u * G + h) * d + j]) *
+                           (double)bf16_to_f32(st->rep[((size_t)u * MP + p) * d + j]);
+                double sh = dot / qn[h];
+                if (sh > best) best = sh;
+            }
+            sc[nc].s = (float)best;
+            sc[nc].id = p;
+            ++nc;
+        }
+        qsort(sc, (size_t)nc, sizeof(scored_t), cmp_scored);
+        int ns = nc < P ? nc : P;
+        int32_t *out = ids + (size_t)u * P;
+        for (int x = 0; x < ns; ++x) out[x] = sc[x].id;
+        qsort(out, (size_t)ns, sizeof(int32_t), cmp_i32);
+        for (int x = ns; x < P; ++x) out[x] = -1;
+        if (scores) {
+            for (int x = 0; x < P; ++x) scores[(size_t)u * P + x] = 0.0f;
+            for (int x = 0; x < ns; ++x)
+                for (int y = 0; y < ns; ++y)
+                    if (sc[y].id == out[x]) scores[(size_t)u * P + x] = sc[y].s;
+        }
+        n_sel[u] = ns;
+        free(sc);
+        free(kept);
+        free(cs);
+    }
+}
+
 /* ---- sparse attention over the selected pages (Eq. 1 with the mask = selected tokens) ---------
  * For every query head of the group: logits z = q.k / sqrt(d) over every filled slot of every
  * selected page, softmax with the maximum subtracted, output = sum softmax * v.  fp64, output

@@ -499,6 +499,88 @@ def test_bf16_rounding_is_nearest_even():
     assert np.array_equal(widen(narrow(y)), ref)
 
 
+# ----------------------------------------------------------------------------- hierarchical select (Sec. 4.3, Alg. 3)
+def _hier_numpy(ix, q, budget, n_probe):
+    """The staged definition written out with numpy and Python sorting (fp64 scores rounded to fp32)."""
+    qf = widen(q).astype(np.float64)
+    P = budget // ix.s
+    out = []
+    for u in range(ix.U):
+        mu = widen(narrow(ix.centroid[u])).astype(np.float64)                  # bf16-rounded centroids
+        nq = np.linalg.norm(qf[u], axis=1)[None, :]
+        sc = ((mu @ qf[u].T) / nq).max(1).astype(np.float32)
+        kept = sorted(sorted(range(ix.C), key=lambda c: (-sc[c], c))[:min(n_probe, ix.C)])
+        npg = int(ix.n_pages[u])
+        cand = [p for p in range(npg) if ix.page_cluster[u, p] in set(kept)]
+        r = widen(ix.rep[u, :npg]).astype(np.float64)
+        sp = ((r @ qf[u].T) / nq).max(1).astype(np.float32)
+        best = sorted(sorted(cand, key=lambda p: (-sp[p], p))[:min(P, len(cand))])
+        out.append((kept, best, sc))
+    return out
+
+
+@pytest.mark.parametrize("n_probe,budget", [(1, 64), (4, 64), (8, 256), (24, 128)])
+def test_hier_select_is_the_staged_definition(n_probe, budget):
+    w = datagen.small(n_tokens=1500, n_clusters=24, n_kv_heads=3)
+    ix, _, _ = _built(w)
+    q = datagen.queries(w).reshape(ix.U, w.group_size, D)
+    ids, n_sel, scores, clusters, Sc_all = ix.select_hier(q, budget, n_probe)
+    _, _, _, S_all = ix.select(q, budget)
+    for u, (kept, best, sc) in enumerate(_hier_numpy(ix, q, budget, n_probe)):
+        np.testing.assert_allclose(Sc_all[u], sc, rtol=2e-7, atol=1e-7)
+        assert clusters[u, :len(kept)].tolist() == kept and np.all(clusters[u, len(kept):] == -1)
+        assert n_sel[u] == len(best) and ids[u, :len(best)].tolist() == best
+        assert np.all(ids[u, len(best):] == -1)
+        assert np.array_equal(scores[u, :len(best)], S_all[u, best])
+        # every returned page belongs to a kept cluster
+        assert set(ix.page_cluster[u, best].tolist()) <= set(kept)
+
+
+def test_hier_select_with_every_cluster_is_the_flat_select():
+    w = datagen.small(n_tokens=2000, n_clusters=20, n_kv_heads=2)
+    ix, _, _ = _built(w)
+    q = datagen.queries(w).reshape(ix.U, w.group_size, D)
+    for n_probe in (20, 64):                                # == C and > C
+        ids_h, ns_h, sc_h, clusters, _ = ix.select_hier(q, 128, n_probe)
+        ids_f, ns_f, sc_f, _ = ix.select(q, 128)
+        assert np.array_equal(ids_h, ids_f) and np.array_equal(ns_h, ns_f) and np.array_equal(sc_h, sc_f)
+        assert np.array_equal(clusters[:, :20], np.tile(np.arange(20), (ix.U, 1)))
+
+
+def test_hier_select_one_cluster_returns_only_its_pages():
+    """n_probe = 1: the answer is the best pages of the single cluster whose centroid the query likes most;
+    with a budget that covers that cluster, exactly its pages come back."""
+    w = datagen.small(n_tokens=1200, n_clusters=10, n_kv_heads=2)
+    ix, _, _ = _built(w)
+    q = datagen.queries(w).reshape(ix.U, w.group_size, D)
+    ids, n_sel, _, clusters, Sc_all = ix.select_hier(q, 16 * 200, 1)
+    for u in range(ix.U):
+        c = int(clusters[u, 0])
+        assert c == int(np.lexsort((np.arange(ix.C), -Sc_all[u]))[0])
+        mine = [p for p in range(ix.n_pages[u]) if ix.page_cluster[u, p] == c]
+        assert ids[u, :n_sel[u]].tolist() == mine
+
+
+def test_hier_select_sees_pages_appended_by_insertion():
+    """Pages opened by later insertions sit at the end of the page range, not next to their cluster's
+    build-time pages; they must still be candidates of their cluster."""
+    w = datagen.small(n_tokens=640, n_clusters=4, n_kv_heads=1, n_components=4)
+    ix, _, _ = _built(w, max_extra=256)
+    np0 = int(ix.n_pages[0])
+    stream = datagen.DecodeStream(w, seed=3)
+    for _ in range(200):
+        k, v, _ = stream.next()
+        ix.insert(k, v)
+    assert ix.n_pages[0] > np0
+    c = int(ix.page_cluster[0, ix.n_pages[0] - 1])          # a cluster that owns an appended page
+    q = np.tile(narrow(ix.centroid[0, c])[None, None, :], (1, w.group_size, 1))   # a query along its centroid
+    ids, n_sel, _, clusters, _ = ix.select_hier(q, 16 * 400, 1)
+    assert int(clusters[0, 0]) == c
+    mine = [p for p in range(ix.n_pages[0]) if ix.page_cluster[0, p] == c]
+    assert any(p >= np0 for p in mine)                      # the case under test exists
+    assert ids[0, :n_sel[0]].tolist() == mine
+
+
 # ----------------------------------------------------------------------------- change detector
 def test_oracle_still_gives_the_stored_small_case():
     """tests/golden/oracle_small_case.json was written by tests/golden/write_oracle_fixture.py from the
