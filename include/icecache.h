@@ -144,6 +144,23 @@ ice_status_t ice_attend(ice_index_t *idx, const void *q, const int32_t *page_ids
 ice_status_t ice_select_attend(ice_index_t *idx, const void *q, int32_t token_budget,
                                int32_t *page_ids, int32_t *n_selected, float *out, void *stream);
 
+/* Hierarchical selection: the two-level form of the paper's top-down search (Sec. 4.3, Alg. 3).
+ * Stage 1 ranks the n_clusters centroids (as stored, rounded to bf16) by the same normalised GQA
+ * score as pages and keeps the min(n_probe, n_clusters) best, lower id first on ties; every
+ * cluster is eligible, one without pages contributes none.  Stage 2 ranks only the live pages of
+ * the kept clusters and returns the best min(P, number of such pages), P = floor(budget / page_size),
+ * ids ascending, padded with -1; with n_probe >= n_clusters the result is ice_select's.
+ *   q bf16 [B, H_q, d]; page_ids int32 [B, H_kv, P]; n_selected int32 [B, H_kv];
+ *   scores_or_null fp32 [B, H_kv, P] (group scores of the returned pages);
+ *   clusters_or_null int32 [B, H_kv, n_probe] (kept cluster ids ascending, -1 padded);
+ *   out_or_null fp32 [B, H_q, d]: when given, attention over the returned pages (as ice_attend)
+ *   runs in the same launch.
+ * All device pointers, caller-owned; only enqueues.  Errors as ice_select, plus SHAPE for
+ * n_probe < 1 and UNSUPPORTED when the candidate lists do not fit a CU's LDS. */
+ice_status_t ice_select_hier(ice_index_t *idx, const void *q, int32_t token_budget, int32_t n_probe,
+                             int32_t *page_ids, int32_t *n_selected, float *scores_or_null,
+                             int32_t *clusters_or_null, float *out_or_null, void *stream);
+
 /* Test and snapshot surface.  Export fills `view` with pointers INTO the workspace (no copy).
  * Import copies caller arrays (device pointers, same layout; the export-only fields are
  * ignored; n_tokens, page_size, n_clusters, max_pages must fit the workspace) into the index and

@@ -17,7 +17,7 @@ ICE_OK, ICE_ERR_INVALID_ARG, ICE_ERR_SHAPE, ICE_ERR_STATE, ICE_ERR_CAPACITY, ICE
 STATUS_NAMES = ["ICE_OK", "ICE_ERR_INVALID_ARG", "ICE_ERR_SHAPE", "ICE_ERR_STATE", "ICE_ERR_CAPACITY",
                 "ICE_ERR_UNSUPPORTED", "ICE_ERR_DEVICE"]
 SYMBOLS = ["ice_workspace_bytes", "ice_create", "ice_destroy", "ice_build_index", "ice_insert", "ice_select",
-           "ice_attend", "ice_select_attend", "ice_export_index", "ice_import_index", "ice_debug_assign",
+           "ice_attend", "ice_select_attend", "ice_select_hier", "ice_export_index", "ice_import_index", "ice_debug_assign",
            "ice_debug_peak_read", "ice_debug_peak_mfma", "ice_last_error"]
 
 
@@ -63,6 +63,8 @@ def lib() -> C.CDLL:
         L.ice_attend.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32, C.c_void_p, C.c_void_p]
         L.ice_select_attend.argtypes = [C.c_void_p, C.c_void_p, C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p,
                                         C.c_void_p]
+        L.ice_select_hier.argtypes = [C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p,
+                                      C.c_void_p, C.c_void_p, C.c_void_p]
         L.ice_export_index.argtypes = [C.c_void_p, C.POINTER(IceIndexView)]
         L.ice_import_index.argtypes = [C.c_void_p, C.POINTER(IceIndexView), C.c_void_p]
         L.ice_debug_assign.argtypes = [C.c_void_p, C.c_void_p, C.c_int32, C.c_void_p, C.c_int32, C.c_void_p,
@@ -140,6 +142,12 @@ def ice_attend(idx, q, page_ids, n_selected, n_ids_per_unit, out, stream=None) -
 def ice_select_attend(idx, q, token_budget, page_ids, n_selected, out, stream=None) -> None:
     _check(lib().ice_select_attend(idx, _ptr(q), token_budget, _ptr(page_ids), _ptr(n_selected), _ptr(out),
                                    _stream(stream)))
+
+
+def ice_select_hier(idx, q, token_budget, n_probe, page_ids, n_selected, scores=None, clusters=None, out=None,
+                    stream=None) -> None:
+    _check(lib().ice_select_hier(idx, _ptr(q), token_budget, n_probe, _ptr(page_ids), _ptr(n_selected), _ptr(scores),
+                                 _ptr(clusters), _ptr(out), _stream(stream)))
 
 
 def ice_export_index(idx) -> IceIndexView:
@@ -253,6 +261,21 @@ class IceIndex:
                               device=self.device)
         ice_select_attend(self.handle, q, token_budget, ids, n_sel, out, stream)
         return ids, n_sel, out
+
+    def select_hier(self, q, token_budget, n_probe, attend=True, ids=None, n_sel=None, out=None, stream=None):
+        """Two-stage selection (+ attention in the same launch when attend is true).
+        -> (ids, n_sel, scores, clusters, out or None)."""
+        if ids is None:
+            ids, n_sel = self._sel_buffers(token_budget)
+        P = ids.shape[-1]
+        scores = torch.empty((self.batch, self.n_kv_heads, P), dtype=torch.float32, device=self.device)
+        clusters = torch.empty((self.batch, self.n_kv_heads, n_probe), dtype=torch.int32, device=self.device)
+        if attend and out is None:
+            out = torch.empty((self.batch, self.n_kv_heads * self.group_size, 128), dtype=torch.float32,
+                              device=self.device)
+        ice_select_hier(self.handle, q, token_budget, n_probe, ids, n_sel, scores, clusters, out if attend else None,
+                        stream)
+        return ids, n_sel, scores, clusters, (out if attend else None)
 
     def export(self):
         """dict of torch tensors aliasing the workspace (no copy) plus the view itself under 'view'."""

@@ -10,7 +10,7 @@ ROOT = os.path.dirname(PKG)
 CSRC = os.path.join(PKG, "csrc")
 LIB = os.path.join(PKG, "libicecache.so")
 OBJ_DIR = os.path.join(ROOT, "_build")
-SOURCES = ["ice_api.hip", "ice_build.hip", "ice_decode.hip", "ice_peaks.hip"]
+SOURCES = ["ice_api.hip", "ice_build.hip", "ice_decode.hip", "ice_hier.hip", "ice_peaks.hip"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-I" + os.path.join(ROOT, "include"), "-I" + CSRC,
          # packed-fp32 instruction selection is switched off for all device code

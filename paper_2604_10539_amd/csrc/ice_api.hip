@@ -252,6 +252,23 @@ ice_status_t ice_select_attend(ice_index_t *ix, const void *q, int32_t budget, i
     return device_status("ice_select_attend");
 }
 
+ice_status_t ice_select_hier(ice_index_t *ix, const void *q, int32_t budget, int32_t n_probe, int32_t *ids, int32_t *n_sel,
+                             float *scores, int32_t *clusters, float *out, void *stream) {
+    if (!ix) return fail(ICE_ERR_INVALID_ARG, "index is null");
+    if (!ix->built) return fail(ICE_ERR_STATE, "ice_select_hier before ice_build_index");
+    if (!q || !aligned16(q)) return fail(ICE_ERR_INVALID_ARG, "q is null or misaligned");
+    if (!ids || !n_sel) return fail(ICE_ERR_INVALID_ARG, "page_ids or n_selected is null");
+    if (budget < ix->dev.s) return fail(ICE_ERR_SHAPE, "token_budget %d is below page_size %d", budget, ix->dev.s);
+    if (n_probe < 1) return fail(ICE_ERR_SHAPE, "n_probe must be >= 1");
+    const int P = budget / ix->dev.s;
+    if (decode_hier_lds_bytes(ix->dev, P, n_probe) > 160u * 1024u - 1024u)
+        return fail(ICE_ERR_UNSUPPORTED, "%d pages per unit, n_probe %d and token_budget %d need more LDS than a CU has",
+                    ix->dev.max_pages, n_probe, budget);
+    launch_decode_hier(ix->dev, static_cast<const bf16_t *>(q), ix->cur, P, n_probe, ids, n_sel, scores, clusters, out,
+                       static_cast<hipStream_t>(stream));
+    return device_status("ice_select_hier");
+}
+
 ice_status_t ice_export_index(ice_index_t *ix, ice_index_view_t *v) {
     if (!ix || !v) return fail(ICE_ERR_INVALID_ARG, "index or view is null");
     if (!ix->built) return fail(ICE_ERR_STATE, "ice_export_index before ice_build_index");

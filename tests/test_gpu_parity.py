@@ -413,3 +413,138 @@ def test_peak_microbenchmarks_run():
     s = sink.cpu().numpy()
     assert np.isfinite(s).all() and (s > 0).all()
     assert np.array_equal(s[:256], s[256:512])          # every workgroup computes the same sums
+
+
+# ----------------------------------------------------------------------------------------- hierarchical select
+def _check_hier(ix, o, q, budget, n_probe, ids, n_sel, scores, clusters, out):
+    """GPU two-stage selection against the oracle on identical index bits.  Stage 1: the kept clusters
+    must be the oracle's, except for clusters within the tie band of the last kept score.  Stage 2 is
+    checked against the staged definition applied to the GPU's own cluster set (so a stage-1 near-tie
+    does not hide a stage-2 error), with the oracle's fp32 page scores."""
+    U = ix.U
+    oid, ons, osc, ocl, Sc_all = o.select_hier(q, budget, n_probe)
+    _, _, _, S_all = o.select(q, budget)
+    ids, n_sel, clusters = down(ids).reshape(U, -1), down(n_sel).reshape(U), down(clusters).reshape(U, n_probe)
+    scores = down(scores).reshape(U, -1)
+    P = ids.shape[1]
+    n_keep = min(n_probe, o.C)
+    ties = 0
+    for u in range(U):
+        g = clusters[u, :n_keep]
+        assert np.all(np.diff(g) > 0) and np.all(clusters[u, n_keep:] == -1) and g.min() >= 0 and g.max() < o.C
+        if not np.array_equal(g, ocl[u, :n_keep]):
+            thr = np.sort(Sc_all[u])[::-1][n_keep - 1]
+            band = SCORE_TIE * max(1.0, abs(float(thr)))
+            for c in np.setxor1d(g, ocl[u, :n_keep]):
+                assert abs(float(Sc_all[u, c]) - float(thr)) <= band, "kept clusters differ outside the tie band"
+            ties += 1
+        kept = set(g.tolist())
+        npg = int(o.n_pages[u])
+        cand = [p for p in range(npg) if int(o.page_cluster[u, p]) in kept]
+        k = min(P, len(cand))
+        assert n_sel[u] == k
+        got = ids[u, :k]
+        assert np.all(np.diff(got) > 0) and np.all(ids[u, k:] == -1)
+        assert set(got.tolist()) <= set(cand)
+        want = sorted(sorted(cand, key=lambda p: (-S_all[u, p], p))[:k])
+        if got.tolist() != want:
+            thr = sorted((S_all[u, p] for p in cand), reverse=True)[k - 1]
+            band = SCORE_TIE * max(1.0, abs(float(thr)))
+            for p in np.setxor1d(got, want):
+                assert abs(float(S_all[u, p]) - float(thr)) <= band, "pages differ outside the tie band"
+            ties += 1
+        np.testing.assert_allclose(scores[u, :k], S_all[u, got], rtol=2e-6, atol=2e-6)
+    print("[hier] %d near-tie differences" % ties)
+    if out is not None:
+        ref = o.attend(q, ids, n_sel)
+        err = np.abs(down(out).reshape(ref.shape) - ref).max()
+        print("[hier attend] max abs err %.3g" % err)
+        assert err <= ATTN_TOL and err <= ATTN_EXPECTED
+    return ties
+
+
+@pytest.mark.gpu
+@pytest.mark.parametrize("kw,budget,n_probe", [
+    (dict(n_tokens=4096, n_clusters=32, n_kv_heads=2, n_components=32), 256, 4),
+    (dict(n_tokens=4096, n_clusters=32, n_kv_heads=2, n_components=32), 256, 1),
+    (dict(n_tokens=5003, n_clusters=100, n_kv_heads=3, n_components=40), 64, 17),
+    (dict(n_tokens=5003, n_clusters=100, n_kv_heads=3, n_components=40, group_size=1), 512, 100),   # every cluster
+    (dict(n_tokens=5003, n_clusters=100, n_kv_heads=3, n_components=40, group_size=2), 128, 130),   # more than exist
+    (dict(n_tokens=2600, n_clusters=40, n_kv_heads=1, page_size=64, group_size=8), 640, 6),
+    (dict(n_tokens=20000, n_clusters=300, n_kv_heads=2, n_components=128), 256, 70),               # more than 64 kept
+    (dict(n_tokens=300, n_clusters=6, n_kv_heads=2), 16 * 64, 2),                                  # budget covers all candidates
+])
+def test_hier_select_and_attend(kw, budget, n_probe):
+    w = datagen.small(**kw)
+    ix, K, V, _ = _mk(w, T=2)
+    ix.build_index(up(K), up(V))
+    q = datagen.queries(w)
+    ids, n_sel, scores, clusters, out = ix.select_hier(up(q), budget, n_probe)
+    o = oracle_from_export(ix, export_np(ix))
+    _check_hier(ix, o, q, budget, n_probe, ids, n_sel, scores, clusters, out)
+    # selection alone gives the same ids
+    ids2, ns2, _, cl2, none = ix.select_hier(up(q), budget, n_probe, attend=False)
+    assert none is None and torch.equal(ids2, ids) and torch.equal(ns2, n_sel) and torch.equal(cl2, clusters)
+    if n_probe >= w.n_clusters:   # every cluster kept: the flat scan's answer
+        ids_f, ns_f, _ = ix.select(up(q), budget)
+        assert torch.equal(ids_f, ids) and torch.equal(ns_f, n_sel)
+
+
+@pytest.mark.gpu
+def test_hier_select_after_insertions_sees_appended_pages():
+    w = datagen.small(n_tokens=1500, n_clusters=12, n_kv_heads=2, n_components=8, drift=0.01)
+    ix, K, V, _ = _mk(w, T=2, extra=512)
+    ix.build_index(up(K), up(V))
+    np0 = export_np(ix)["n_pages"].copy()
+    stream = datagen.DecodeStream(w, seed=21)
+    for _ in range(400):
+        k, v, qq = stream.next()
+        ix.insert(up(k), up(v))
+    ex = export_np(ix)
+    assert np.all(ex["n_pages"] > np0)
+    o = oracle_from_export(ix, ex)
+    for n_probe in (1, 3, 12):
+        ids, n_sel, scores, clusters, out = ix.select_hier(up(qq), 16 * 40, n_probe)
+        _check_hier(ix, o, qq, 16 * 40, n_probe, ids, n_sel, scores, clusters, out)
+    # the best cluster's appended pages are among the winners when the budget covers the cluster
+    ids, n_sel, _, clusters, _ = ix.select_hier(up(qq), 16 * 400, 1, attend=False)
+    ids, n_sel, clusters = down(ids).reshape(ix.U, -1), down(n_sel).reshape(ix.U), down(clusters).reshape(ix.U, 1)
+    for u in range(ix.U):
+        mine = [p for p in range(ex["n_pages"][u]) if ex["page_cluster"][u, p] == clusters[u, 0]]
+        assert ids[u, :n_sel[u]].tolist() == mine
+
+
+@pytest.mark.gpu
+def test_hier_select_many_exact_ties_takes_the_overflow_path():
+    """Hundreds of identical pages in one kept cluster overflow the short ranking list: the radix
+    path must return the best pages, lowest ids first among exact ties."""
+    from paper_2604_10539_amd import IceIndex
+    rng = np.random.default_rng(19)
+    n = 16 * 700
+    key = narrow(rng.standard_normal(D).astype(np.float32))
+    K = np.tile(key, (1, 1, n, 1))
+    K[0, 0, 16 * 300:16 * 303] = narrow(3.0 * widen(key))
+    V = narrow(rng.standard_normal((1, 1, n, D)).astype(np.float32))
+    ix = IceIndex(1, 1, 1, n, 16, 1, kmeans_iters=1, init_idx=up(np.zeros((1, 1, 1), np.int32)))
+    ix.build_index(up(K), up(V))
+    q = narrow(widen(key)[None, None, :].copy())
+    ids, n_sel, scores, clusters, out = ix.select_hier(up(q), 16 * 8, 1)
+    assert down(ids).ravel().tolist() == [0, 1, 2, 3, 4, 300, 301, 302]
+    o = oracle_from_export(ix, export_np(ix))
+    _check_hier(ix, o, q, 16 * 8, 1, ids, n_sel, scores, clusters, out)
+
+
+@pytest.mark.gpu
+def test_hier_select_argument_errors():
+    from paper_2604_10539_amd import IceError, binding as b
+    w = datagen.small(n_tokens=600, n_clusters=6, n_kv_heads=1)
+    ix, K, V, _ = _mk(w, T=1)
+    q = up(datagen.queries(w))
+    with pytest.raises(IceError) as e:
+        ix.select_hier(q, 64, 2)
+    assert e.value.status == b.ICE_ERR_STATE
+    ix.build_index(up(K), up(V))
+    for budget, n_probe, status in ((8, 2, b.ICE_ERR_SHAPE), (64, 0, b.ICE_ERR_SHAPE)):
+        with pytest.raises(IceError) as e:
+            ix.select_hier(q, budget, n_probe)
+        assert e.value.status == status
