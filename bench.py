@@ -50,6 +50,7 @@ def parse():
     ap.add_argument("--layers", type=int, default=32)
     ap.add_argument("--kmeans-iters", type=int, default=10)
     ap.add_argument("--workload", default="cfg2", choices=["cfg2"])
+    ap.add_argument("--n-probe", type=int, default=64, help="clusters kept by the hierarchical variant")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--warm", action="store_true", help="skip the cache flush between steps")
     return ap.parse_args()
@@ -67,7 +68,7 @@ def main():
               "take disjoint heads or sequences); run with --gpus 1", file=sys.stderr)
         sys.exit(2)
     import torch
-    from paper_2604_10539_amd import IceIndex, ice_debug_peak_mfma, ice_debug_peak_read, ice_select
+    from paper_2604_10539_amd import IceIndex, ice_debug_peak_mfma, ice_debug_peak_read, ice_select, ice_select_hier
 
     assert torch.cuda.is_available(), "bench.py needs the GPU"
     dev = torch.device("cuda:0")
@@ -213,6 +214,38 @@ def main():
     ms_sel = timed(lambda: ice_select(batched.handle, q, budget, ids_b, ns_b, None), args.steps, args.warmup, cold)
     ms_att = timed(lambda: batched.attend(q, ids_b, ns_b, out_b), args.steps, args.warmup, cold)
 
+    # ---------------------------------------------------------------- hierarchical variant (clusters first)
+    # the two-level form of the paper's top-down search: score the 512 centroids, keep the n_probe
+    # best clusters, score only their pages; same launch shape and timing protocol as the headline
+    n_probe = args.n_probe
+    ids_h = torch.empty_like(ids_b)
+    ns_h = torch.empty_like(ns_b)
+    out_h = torch.empty_like(out_b)
+    cl_h = torch.empty((L, H, n_probe), dtype=torch.int32, device=dev)
+    hier = lambda ix: ice_select_hier(ix.handle, q, budget, n_probe, ids_h, ns_h, None, cl_h, out_h)
+    for i in range(max(args.warmup, 3)):
+        hier(rot[i % 3])
+    torch.cuda.synchronize()
+    e0, e1 = ev(), ev()
+    e0.record(st)
+    for i in range(args.steps):
+        hier(rot[i % 3])
+    e1.record(st)
+    torch.cuda.synchronize()
+    ms_hier = e0.elapsed_time(e1) / args.steps
+    hier(batched)
+    torch.cuda.synchronize()
+    pc = exb["page_cluster"].cpu().numpy()
+    cl_np, idh_np, nsh_np = cl_h.cpu().numpy().reshape(L * H, n_probe), ids_h.cpu().numpy().reshape(L * H, P), ns_h.cpu().numpy().reshape(L * H)
+    n_cand = sum(int(np.isin(pc[u, :n_pages[u]], cl_np[u][cl_np[u] >= 0]).sum()) for u in range(L * H))
+    sel_tokens_h = sum(int(fill[u, idh_np[u, :nsh_np[u]]].sum()) for u in range(L * H))
+    cpad = (C + 31) // 32 * 32
+    bytes_hier = (L * H * (cpad * D * 2 + G * D * 2) + float(n_pages.sum()) * 4 + n_cand * D * 2 + float(nsh_np.sum()) * 4
+                  + sel_tokens_h * D * 2 * 2 + L * H * G * D * 4)
+    recall = float(np.mean([len(np.intersect1d(idh_np[u, :nsh_np[u]], ids_np[u, :ns_np[u]])) / max(1, ns_np[u])
+                            for u in range(L * H)]))
+    out_diff = float((out_h - out_b).abs().max().item())
+
     # ---------------------------------------------------------------- one layer at a time, HIP graph of 32
     ids_l = [torch.empty((1, H, P), dtype=torch.int32, device=dev) for _ in range(L)]
     ns_l = [torch.empty((1, H), dtype=torch.int32, device=dev) for _ in range(L)]
@@ -340,6 +373,12 @@ def main():
         "select_only": {"us_per_launch": ms_sel * 1e3, "GBps": sel_gbps, "algorithmic_bytes_per_launch": bytes_select},
         "attend": {"us_per_launch": ms_att * 1e3, "GBps": bytes_attend / (ms_att * 1e-3) / 1e9,
                    "algorithmic_bytes_per_launch": bytes_attend},
+        "hierarchical": {"n_probe": n_probe, "us_per_step": ms_hier * 1e3, "us_per_layer_step": ms_hier * 1e3 / L,
+                         "algorithmic_bytes_per_step": bytes_hier, "GBps": bytes_hier / (ms_hier * 1e-3) / 1e9,
+                         "candidate_pages_per_unit_mean": n_cand / (L * H),
+                         "recall_of_flat_selection": recall, "attend_max_abs_diff_vs_flat": out_diff,
+                         "how": "ice_select_hier (centroids -> kept clusters -> their pages -> top-P -> attention, one "
+                                "launch), same rotation over three index copies as the headline"},
         "sequential": {"us_per_layer_step": ms_seq * 1e3 / L, "GBps": bytes_step / (ms_seq * 1e-3) / 1e9,
                        "how": "HIP graph replay of 32 one-layer select+attend calls (8 units each)",
                        "bitwise_equal_to_batched": same},

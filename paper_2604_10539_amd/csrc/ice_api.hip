@@ -261,11 +261,14 @@ ice_status_t ice_select_hier(ice_index_t *ix, const void *q, int32_t budget, int
     if (budget < ix->dev.s) return fail(ICE_ERR_SHAPE, "token_budget %d is below page_size %d", budget, ix->dev.s);
     if (n_probe < 1) return fail(ICE_ERR_SHAPE, "n_probe must be >= 1");
     const int P = budget / ix->dev.s;
+    if (ix->dev.max_pages > decode_hier_max_pages(ix->dev.G))
+        return fail(ICE_ERR_UNSUPPORTED, "%d pages per unit exceed the selection kernel's limit of %d", ix->dev.max_pages,
+                    decode_hier_max_pages(ix->dev.G));
     if (decode_hier_lds_bytes(ix->dev, P, n_probe) > 160u * 1024u - 1024u)
         return fail(ICE_ERR_UNSUPPORTED, "%d pages per unit, n_probe %d and token_budget %d need more LDS than a CU has",
                     ix->dev.max_pages, n_probe, budget);
-    launch_decode_hier(ix->dev, static_cast<const bf16_t *>(q), ix->cur, P, n_probe, ids, n_sel, scores, clusters, out,
-                       static_cast<hipStream_t>(stream));
+    launch_decode_hier(ix->dev, static_cast<const bf16_t *>(q), ix->cur, P, n_probe, ix->n_tokens / ix->dev.s + ix->dev.C, ids,
+                       n_sel, scores, clusters, out, static_cast<hipStream_t>(stream));
     return device_status("ice_select_hier");
 }
 

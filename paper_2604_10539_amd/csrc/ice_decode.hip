@@ -199,6 +199,26 @@ __global__ __launch_bounds__(NW * 64) void decode_step_kernel(Dev d, const bf16_
     // row group 0 ends up with the dot products of page r with heads 0..3 (group 1: heads 4..7).
     bf16x8 qa[4];
     {
+        const int per = round_up((np_hint + chunks - 1) / chunks, 16 * NW);
+        const int p0 = chunk * per, pend = min(np_hint, p0 + per);
+        const int nblk = (pend - p0 + 15) >> 4;
+        constexpr int UNR = 4;
+        static_assert(NW * UNR == 4 * NW, "sh_rowmax holds one maximum per (wave, unroll slot)");
+        uint4 bb[UNR][4];
+        auto request = [&](int b0, int lim) {
+#pragma unroll
+            for (int x = 0; x < UNR; ++x) {
+                const int page = p0 + 16 * (b0 + NW * x) + ch;
+                const uint4 *src = (const uint4 *)(rep + (size_t)page * kD);
+#pragma unroll
+                for (int ks = 0; ks < 4; ++ks) bb[x][ks] = page < lim ? src[ks * 4 + g] : make_uint4(0, 0, 0, 0);
+            }
+        };
+        // The first round of representative rows is requested together with the query rows, before
+        // anything waits for either (and before np is known: np <= np_hint <= max_pages): the
+        // kernel starts with one memory round trip, not two.
+        int b0 = wave;
+        if (b0 < nblk) request(b0, pend);
         float nn;
         load_query_operand<G>(q, u, lane, qa, &nn);
         nn += __shfl_xor(nn, 16);
@@ -207,25 +227,11 @@ __global__ __launch_bounds__(NW * 64) void decode_step_kernel(Dev d, const bf16_
         float inv[4];
 #pragma unroll
         for (int v = 0; v < 4; ++v) inv[v] = __shfl(invn, (4 * g + v) & 15);
-        const int per = round_up((np_hint + chunks - 1) / chunks, 16 * NW);
-        const int p0 = chunk * per, pend = min(np_hint, p0 + per);
-        const int nblk = (pend - p0 + 15) >> 4;
-        constexpr int UNR = 4;
-        static_assert(NW * UNR == 4 * NW, "sh_rowmax holds one maximum per (wave, unroll slot)");
-        int lim = pend;  // the first round of loads does not wait for np (np <= np_hint <= max_pages)
+        const int lim = min(np, pend);
         float gmax[UNR];  // running maximum of the scores this lane produced in unroll slot x
 #pragma unroll
         for (int x = 0; x < UNR; ++x) gmax[x] = -INFINITY;
-        for (int b0 = wave; b0 < nblk; b0 += NW * UNR) {
-            uint4 bb[UNR][4];
-#pragma unroll
-            for (int x = 0; x < UNR; ++x) {
-                const int page = p0 + 16 * (b0 + NW * x) + ch;
-                const uint4 *src = (const uint4 *)(rep + (size_t)page * kD);
-#pragma unroll
-                for (int ks = 0; ks < 4; ++ks) bb[x][ks] = page < lim ? src[ks * 4 + g] : make_uint4(0, 0, 0, 0);
-            }
-            lim = min(np, pend);
+        while (b0 < nblk) {
 #pragma unroll
             for (int x = 0; x < UNR; ++x) {
                 f32x4 acc = {0.f, 0.f, 0.f, 0.f};
@@ -244,6 +250,8 @@ __global__ __launch_bounds__(NW * 64) void decode_step_kernel(Dev d, const bf16_
                     gmax[x] = fmaxf(gmax[x], sc);
                 }
             }
+            b0 += NW * UNR;
+            if (b0 < nblk) request(b0, lim);
         }
         // With one workgroup per unit the selection threshold needs the maxima of 4*NW disjoint
         // groups of scores: group (wave, x) is ready here, for free (the kernel is waiting for HBM).

@@ -11,6 +11,18 @@
 // Scores are the flat scan's: max over the G heads of (q_h . row) / ||q_h||, fp32 MFMA accumulate.
 #include "ice_decode_common.h"
 
+#ifdef ICE_PROF
+namespace ice {
+__device__ long long ice_prof_h[16];
+}
+#define ICE_HSTAMP(i) do { if (threadIdx.x == 0 && blockIdx.x == 0) ice_prof_h[i] = wall_clock64(); } while (0)
+extern "C" int ice_debug_prof_h(long long *host16) {
+    return (int)hipMemcpyFromSymbol(host16, HIP_SYMBOL(ice::ice_prof_h), sizeof(long long) * 16);
+}
+#else
+#define ICE_HSTAMP(i) do { } while (0)
+#endif
+
 namespace ice {
 
 namespace {
@@ -26,72 +38,111 @@ struct SelShared {
 
 // Exact top-k of n distinct 64-bit composites (ordered score << 32 | ~id) held in LDS, into
 // sel[0..k) (in no particular order when the radix path runs, by rank otherwise); requires
-// 1 <= k < n.  A threshold that at least k composites reach comes from the k-th largest of the
-// 4*NW sixteen-lane row maxima of the per-thread maxima; what passes it goes to a short list that
-// is ranked by counting.  If the list overflows (or k exceeds the row count) an 8-bit-per-pass
-// radix select over LDS histograms runs on the whole array instead.  `nb` = bits of the id field
-// that can be set.  Every thread of the workgroup must call it; it ends with a barrier.
+// 1 <= k < n.  First a 32-bit threshold that at least k keys reach, and few more:
+//   k <= 2*NW  the k-th largest of the 4*NW sixteen-lane row maxima, element j belonging to row
+//              j mod 4*NW (so short arrays still spread over every row);
+//   else       the 16-bit key prefix of the k-th largest key, from two 8-bit LDS histograms.
+// What passes goes to a short list that is ranked by counting.  If the list overflows, an
+// 8-bit-per-pass radix select over LDS histograms runs on the whole array instead.  `nb` = bits of
+// the id field that can be set.  hist: 2 x 272 ints.  Every thread of the workgroup must call it;
+// it ends with a barrier.
 template <int NW>
 __device__ void select_topk_lds(const u64 *comp, int n, int k, int nb, u64 *sel, u64 *list, int *hist, SelShared &sh) {
     constexpr int NT = NW * 64, NR = 4 * NW;
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, g = lane >> 4, ch = lane & 15;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     if (tid == 0) { sh.M = 0; sh.W = 0; sh.pre = 0u; sh.tau = 0ull; }
-    bool listed = false;
-    if (k <= NR) {
+    if (k <= NR / 2) {
+        const int row = tid >> 4, l16 = tid & 15;
         uint32_t lmax = 0u;
-        for (int j = tid; j < n; j += NT) lmax = max(lmax, (uint32_t)(comp[j] >> 32));
+        for (int j = row + NR * l16; j < n; j += NR * 16) lmax = max(lmax, (uint32_t)(comp[j] >> 32));
         lmax = row16_max_u32(lmax);
-        if (ch == 0) sh.rowmax[wave * 4 + g] = lmax;
+        if (l16 == 0) sh.rowmax[row] = lmax;
         __syncthreads();
-        const int i = tid >> 4, part = tid & 15;
-        const uint32_t v = sh.rowmax[i];
+        const uint32_t v = sh.rowmax[row];
         uint32_t c = 0;
 #pragma unroll
         for (int jj = 0; jj < NR / 16; ++jj) {
-            const int j = part * (NR / 16) + jj;
+            const int j = l16 * (NR / 16) + jj;
             const uint32_t o = sh.rowmax[j];
-            c += (o > v || (o == v && j < i)) ? 1u : 0u;
+            c += (o > v || (o == v && j < row)) ? 1u : 0u;
         }
         c = row16_sum_u32(c);
-        if (part == 0 && (int)c == k - 1) sh.pre = v;
-        __syncthreads();
-        const uint32_t pre = sh.pre;
-        // short list of everything at or above the threshold (>= k entries)
-        for (int j0 = 0; j0 < n; j0 += NT) {
-            const int j = j0 + tid;
-            const u64 cc = j < n ? comp[j] : 0ull;
-            const bool is = j < n && (uint32_t)(cc >> 32) >= pre;
-            const u64 bal = __ballot(is);
-            int base = 0;
-            if (lane == 0 && bal) base = atomicAdd(&sh.M, (int)__popcll(bal));
-            base = __shfl(base, 0);
-            const int slot = base + (int)__popcll(bal & ((1ull << lane) - 1ull));
-            if (is && slot < kListCap) list[slot] = cc;
-        }
-        __syncthreads();
-        const int M = sh.M;
-        if (M <= kListCap) {
-            listed = true;
-            // every listed composite counts the listed composites that beat it
-            int lp = 0;
-            while (lp < 6 && (M << (lp + 1)) <= NT) ++lp;
-            const int parts = 1 << lp, len = (M + parts - 1) >> lp;
-            for (int i0 = 0; i0 < M; i0 += NT >> lp) {
-                const int ii = i0 + (tid >> lp), part2 = tid & (parts - 1);
-                const u64 mine = ii < M ? list[ii] : ~0ull;
-                int rank = 0;
-                for (int j = part2 * len; j < min(M, (part2 + 1) * len); ++j) rank += list[j] > mine;
-                if (parts >= 2) rank += (int)dpp_u32<0xB1>((uint32_t)rank);
-                if (parts >= 4) rank += (int)dpp_u32<0x4E>((uint32_t)rank);
-                if (parts >= 8) rank += (int)dpp_u32<0x141>((uint32_t)rank);
-                if (parts >= 16) rank += (int)dpp_u32<0x140>((uint32_t)rank);
-                if (parts >= 32) rank += __shfl_xor(rank, 16);
-                if (parts >= 64) rank += __shfl_xor(rank, 32);
-                if (part2 == 0 && ii < M && rank < k) sel[rank] = mine;
-            }
-        }
+        if (l16 == 0 && (int)c == k - 1) sh.pre = v;
     } else {
-        __syncthreads();  // (sh initialised)
+        // bucket of the k-th largest key by its top byte, then by its second byte inside that bucket
+        int *h0 = hist, *h1 = hist + 272;
+        if (tid < 256) { h0[tid] = 0; h1[tid] = 0; }
+        __syncthreads();
+        auto find_bucket = [&](int *h, int kk, int shift) {  // bins in descending order: thread t owns bin 255 - t
+            int mine = 0, incl = 0;
+            if (tid < 256) {
+                mine = h[255 - tid];
+                incl = mine;
+                for (int off = 1; off < 64; off <<= 1) {
+                    const int t2 = __shfl_up(incl, off);
+                    if (lane >= off) incl += t2;
+                }
+                if (lane == 63) h[256 + wave] = incl;
+            }
+            __syncthreads();
+            if (tid < 256) {
+                for (int w2 = 0; w2 < wave; ++w2) incl += h[256 + w2];
+                const int excl = incl - mine;
+                if (incl >= kk && excl < kk) {  // exactly one bin
+                    sh.pre |= (uint32_t)(255 - tid) << shift;
+                    sh.M2 = kk - excl;
+                }
+            }
+            __syncthreads();
+        };
+        for (int j = tid; j < n; j += NT) atomicAdd(&h0[(int)(comp[j] >> 56)], 1);
+        __syncthreads();
+        find_bucket(h0, k, 24);
+        const uint32_t top = sh.pre >> 24;
+        const int k2 = sh.M2;
+        for (int j = tid; j < n; j += NT) {
+            const uint32_t key = (uint32_t)(comp[j] >> 32);
+            if ((key >> 24) == top) atomicAdd(&h1[(int)((key >> 16) & 255u)], 1);
+        }
+        __syncthreads();
+        find_bucket(h1, k2, 16);
+    }
+    __syncthreads();
+    const uint32_t pre = sh.pre;
+    // short list of everything at or above the threshold (>= k entries)
+    for (int j0 = 0; j0 < n; j0 += NT) {
+        const int j = j0 + tid;
+        const u64 cc = j < n ? comp[j] : 0ull;
+        const bool is = j < n && (uint32_t)(cc >> 32) >= pre;
+        const u64 bal = __ballot(is);
+        int base = 0;
+        if (lane == 0 && bal) base = atomicAdd(&sh.M, (int)__popcll(bal));
+        base = __shfl(base, 0);
+        const int slot = base + (int)__popcll(bal & ((1ull << lane) - 1ull));
+        if (is && slot < kListCap) list[slot] = cc;
+    }
+    __syncthreads();
+    const int M = sh.M;
+    const bool listed = M <= kListCap;
+    if (listed) {
+        // every listed composite counts the listed composites that beat it
+        int lp = 0;
+        while (lp < 6 && (M << (lp + 1)) <= NT) ++lp;
+        const int parts = 1 << lp, len = (M + parts - 1) >> lp;
+        for (int i0 = 0; i0 < M; i0 += NT >> lp) {
+            const int ii = i0 + (tid >> lp), part2 = tid & (parts - 1);
+            const u64 mine = ii < M ? list[ii] : ~0ull;
+            int rank = 0;
+#pragma unroll 8
+            for (int j = part2 * len; j < min(M, (part2 + 1) * len); ++j) rank += list[j] > mine;
+            if (parts >= 2) rank += (int)dpp_u32<0xB1>((uint32_t)rank);
+            if (parts >= 4) rank += (int)dpp_u32<0x4E>((uint32_t)rank);
+            if (parts >= 8) rank += (int)dpp_u32<0x141>((uint32_t)rank);
+            if (parts >= 16) rank += (int)dpp_u32<0x140>((uint32_t)rank);
+            if (parts >= 32) rank += __shfl_xor(rank, 16);
+            if (parts >= 64) rank += __shfl_xor(rank, 32);
+            if (part2 == 0 && ii < M && rank < k) sel[rank] = mine;
+        }
     }
     if (!listed) {  // (workgroup-uniform)
         const u64 idmask = (1ull << nb) - 1ull;
@@ -156,7 +207,7 @@ __host__ __device__ inline HierLds hier_lds(int Cpad, int max_pages, int n_probe
     L.member = off; off += align16((size_t)(Cpad / 32 + 1) * 4);
     L.comp2 = off;  off += align16((size_t)max_pages * 8);
     L.list = off;   off += (size_t)kListCap * 8;
-    L.hist = off;   off += (256 + 16) * 4;
+    L.hist = off;   off += 2 * 272 * 4;
     L.sel1 = off;   off += align16((size_t)n_probe * 8);
     L.sel2 = off;   off += align16((size_t)P * 8);
     L.red = off;    off += align16(sizeof(float) * (size_t)attend_scratch_floats(G, NW));
@@ -164,8 +215,8 @@ __host__ __device__ inline HierLds hier_lds(int Cpad, int max_pages, int n_probe
     return L;
 }
 
-template <int G, int NW>
-__global__ __launch_bounds__(NW * 64) void decode_hier_kernel(Dev d, const bf16_t *__restrict__ q, int cur, int P, int n_probe,
+template <int G, int NW, int EMAX>
+__global__ __launch_bounds__(NW * 64) void decode_hier_kernel(Dev d, const bf16_t *__restrict__ q, int cur, int P, int n_probe, int np_hint,
                                                                int *__restrict__ ids_out, int *__restrict__ n_sel_out,
                                                                float *__restrict__ scores_out, int *__restrict__ clusters_out,
                                                                float *__restrict__ out) {
@@ -185,8 +236,34 @@ __global__ __launch_bounds__(NW * 64) void decode_hier_kernel(Dev d, const bf16_
     u64 *sel2 = (u64 *)(smem + L.sel2);
     float *red = (float *)(smem + L.red);
 
-    const int np = d.n_pages[u];
+    ICE_HSTAMP(0);
+    const int np = d.n_pages[u];  // first needed in stage 2
     const int C = d.C;
+    // the page -> cluster table is requested now and used in stage 2; np_hint is the host's upper
+    // bound of the live pages (entries past the live pages are read and ignored)
+    int pcl[EMAX];
+    {
+        const int *pc = d.page_cluster + (size_t)u * d.max_pages;
+#pragma unroll
+        for (int e = 0; e < EMAX; ++e) pcl[e] = e * NT + tid < np_hint ? pc[e * NT + tid] : -1;
+    }
+    // ---- stage 1 loads: 16 centroids per MFMA chain, four chains' rows in flight per wave (rows of
+    // C..Cpad are padding).  The first round is requested together with the query rows, before
+    // anything waits for either.
+    const bf16_t *cb = d.cent_bf16[cur] + (size_t)u * d.Cpad * kD;
+    const int nblk1 = d.Cpad >> 4;
+    constexpr int UNR1 = 4;
+    uint4 bb1[UNR1][4];
+    auto request1 = [&](int b0) {
+#pragma unroll
+        for (int x = 0; x < UNR1; ++x) {
+            const int c = 16 * (b0 + NW * x) + ch;
+            const uint4 *src = (const uint4 *)(cb + (size_t)c * kD);
+#pragma unroll
+            for (int ks = 0; ks < 4; ++ks) bb1[x][ks] = c < d.Cpad ? src[ks * 4 + g] : make_uint4(0, 0, 0, 0);
+        }
+    };
+    request1(wave);
     // the query operand of every scoring MFMA, and 1/||q_h|| where the scores land
     bf16x8 qa[4];
     float inv[4];
@@ -211,22 +288,23 @@ __global__ __launch_bounds__(NW * 64) void decode_hier_kernel(Dev d, const bf16_
     for (int i = tid; i < d.Cpad / 32 + 1; i += NT) member[i] = 0u;
     if (tid == 0) sh_ncand = 0;
 
-    // ---- stage 1: centroid scores, 16 centroids per MFMA chain (rows of C..Cpad are padding)
-    {
-        const bf16_t *cb = d.cent_bf16[cur] + (size_t)u * d.Cpad * kD;
-        const int nblk = d.Cpad >> 4;
-        for (int b = wave; b < nblk; b += NW) {
-            const int c = 16 * b + ch;
-            const uint4 *src = (const uint4 *)(cb + (size_t)c * kD);
+    // ---- stage 1: centroid scores
+    for (int b0 = wave; b0 < nblk1;) {
+#pragma unroll
+        for (int x = 0; x < UNR1; ++x) {
+            const int c = 16 * (b0 + NW * x) + ch;
             f32x4 acc = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
             for (int ks = 0; ks < 4; ++ks)
-                acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(qa[ks], __builtin_bit_cast(bf16x8, src[ks * 4 + g]), acc, 0, 0, 0);
+                acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(qa[ks], __builtin_bit_cast(bf16x8, bb1[x][ks]), acc, 0, 0, 0);
             const float sc = group_score(acc);
             if (g == 0 && c < C) comp1[c] = ((u64)f32_ordered(sc) << 32) | (u64)(0xFFFFFFFFu - (uint32_t)c);
         }
+        b0 += NW * UNR1;
+        if (b0 < nblk1) request1(b0);
     }
     __syncthreads();
+    ICE_HSTAMP(1);
     const int n_keep = min(n_probe, C);
     if (n_keep == C) {
         for (int c = tid; c < C; c += NT) sel1[c] = comp1[c];
@@ -236,60 +314,69 @@ __global__ __launch_bounds__(NW * 64) void decode_hier_kernel(Dev d, const bf16_
         while ((1 << nb) < C) ++nb;
         select_topk_lds<NW>(comp1, C, n_keep, nb, sel1, list, hist, sh);
     }
-    // kept clusters: bitmask for stage 2, and the optional ascending id list
+    ICE_HSTAMP(2);
+    // kept clusters: bitmask for stage 2 (their ascending id list is written later, off the critical path)
     for (int t = tid; t < n_keep; t += NT) {
         const uint32_t c = 0xFFFFFFFFu - (uint32_t)sel1[t];
         atomicOr(&member[c >> 5], 1u << (c & 31));
     }
-    if (clusters_out) {
-        int *co = clusters_out + (size_t)u * n_probe;
-        for (int t = tid; t < n_probe; t += NT) {
-            if (t < n_keep) {
-                const uint32_t myc = 0xFFFFFFFFu - (uint32_t)sel1[t];
-                int pos = 0;
-                for (int j = 0; j < n_keep; ++j) pos += (0xFFFFFFFFu - (uint32_t)sel1[j]) < myc;
-                co[pos] = (int)myc;
-            } else {
-                co[t] = -1;
-            }
-        }
-    }
     __syncthreads();
 
+    ICE_HSTAMP(3);
     // ---- stage 2a: the live pages of the kept clusters, in any order, ids in the low words of comp2
     {
-        const int *pc = d.page_cluster + (size_t)u * d.max_pages;
-        for (int p0 = 0; p0 < np; p0 += NT) {
-            const int p = p0 + tid;
-            const int c = p < np ? pc[p] : -1;
-            const bool is = c >= 0 && c < C && ((member[c >> 5] >> (c & 31)) & 1u);
-            const u64 bal = __ballot(is);
-            int base = 0;
-            if (lane == 0 && bal) base = atomicAdd(&sh_ncand, (int)__popcll(bal));
-            base = __shfl(base, 0);
-            if (is) comp2[base + (int)__popcll(bal & ((1ull << lane) - 1ull))] = (u64)(uint32_t)p;
+        u64 bal[EMAX];
+        int tot = 0;
+#pragma unroll
+        for (int e = 0; e < EMAX; ++e) {
+            const int p = e * NT + tid, c = pcl[e];
+            bal[e] = __ballot(p < np && c >= 0 && c < C && ((member[c >> 5] >> (c & 31)) & 1u));
+            tot += (int)__popcll(bal[e]);
+        }
+        int base = 0;
+        if (lane == 0 && tot) base = atomicAdd(&sh_ncand, tot);
+        base = __shfl(base, 0);
+#pragma unroll
+        for (int e = 0; e < EMAX; ++e) {
+            if ((bal[e] >> lane) & 1ull) comp2[base + (int)__popcll(bal[e] & ((1ull << lane) - 1ull))] = (u64)(uint32_t)(e * NT + tid);
+            base += (int)__popcll(bal[e]);
         }
     }
     __syncthreads();
     const int ncand = sh_ncand;
-    // ---- stage 2b: their representatives' scores, 16 candidates per MFMA chain (gathered rows)
+    ICE_HSTAMP(4);
+    // ---- stage 2b: their representatives' scores, 16 candidates per MFMA chain (gathered rows),
+    // two chains' rows in flight per wave
     {
         const bf16_t *rep = d.rep + (size_t)u * d.max_pages * kD;
         const int nblk = (ncand + 15) >> 4;
-        for (int b = wave; b < nblk; b += NW) {
-            const int j = 16 * b + ch;
-            const uint32_t p = j < ncand ? (uint32_t)comp2[j] : 0u;  // (page 0 stands in past the end; its score is dropped)
-            const uint4 *src = (const uint4 *)(rep + (size_t)p * kD);
-            f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+        constexpr int UNR = 2;
+        for (int b0 = wave; b0 < nblk; b0 += NW * UNR) {
+            uint4 bb[UNR][4];
+            uint32_t pg[UNR];
 #pragma unroll
-            for (int ks = 0; ks < 4; ++ks)
-                acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(qa[ks], __builtin_bit_cast(bf16x8, src[ks * 4 + g]), acc, 0, 0, 0);
-            const float sc = group_score(acc);
-            __builtin_amdgcn_wave_barrier();  // every lane has read its page id before the entries change
-            if (g == 0 && j < ncand) comp2[j] = ((u64)f32_ordered(sc) << 32) | (u64)(0xFFFFFFFFu - p);
+            for (int x = 0; x < UNR; ++x) {
+                const int j = 16 * (b0 + NW * x) + ch;
+                pg[x] = j < ncand ? (uint32_t)comp2[j] : 0u;  // (page 0 stands in past the end; its score is dropped)
+                const uint4 *src = (const uint4 *)(rep + (size_t)pg[x] * kD);
+#pragma unroll
+                for (int ks = 0; ks < 4; ++ks) bb[x][ks] = src[ks * 4 + g];
+            }
+            __builtin_amdgcn_wave_barrier();  // every lane has read its page ids before the entries change
+#pragma unroll
+            for (int x = 0; x < UNR; ++x) {
+                const int j = 16 * (b0 + NW * x) + ch;
+                f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+                for (int ks = 0; ks < 4; ++ks)
+                    acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(qa[ks], __builtin_bit_cast(bf16x8, bb[x][ks]), acc, 0, 0, 0);
+                const float sc = group_score(acc);
+                if (g == 0 && j < ncand) comp2[j] = ((u64)f32_ordered(sc) << 32) | (u64)(0xFFFFFFFFu - pg[x]);
+            }
         }
     }
     __syncthreads();
+    ICE_HSTAMP(5);
     const int k = min(P, ncand);
     int *ids = ids_out + (size_t)u * P;
     float *sco = scores_out ? scores_out + (size_t)u * P : nullptr;
@@ -306,9 +393,23 @@ __global__ __launch_bounds__(NW * 64) void decode_hier_kernel(Dev d, const bf16_
         while ((1 << nb) < d.max_pages) ++nb;
         select_topk_lds<NW>(comp2, ncand, k, nb, sel2, list, hist, sh);
     }
+    ICE_HSTAMP(6);
     // the winners' places in ascending id order; during the attention it runs where the first
     // waves would wait for the last ones
     auto order_ids = [&] {
+        if (clusters_out) {  // the kept clusters, ascending
+            int *co = clusters_out + (size_t)u * n_probe;
+            for (int t = tid; t < n_probe; t += NT) {
+                if (t < n_keep) {
+                    const uint32_t myc = 0xFFFFFFFFu - (uint32_t)sel1[t];
+                    int pos = 0;
+                    for (int j = 0; j < n_keep; ++j) pos += (0xFFFFFFFFu - (uint32_t)sel1[j]) < myc;
+                    co[pos] = (int)myc;
+                } else {
+                    co[t] = -1;
+                }
+            }
+        }
         for (int t = tid; t < k; t += NT) {
             const u64 mine = sel2[t];
             const uint32_t myid = 0xFFFFFFFFu - (uint32_t)mine;
@@ -320,6 +421,7 @@ __global__ __launch_bounds__(NW * 64) void decode_hier_kernel(Dev d, const bf16_
     };
     if (out) attend_pages<G, NW>(d, u, qa, [=](int x) { return (int)(0xFFFFFFFFu - (uint32_t)sel2[x]); }, k, out, red, order_ids);
     else order_ids();
+    ICE_HSTAMP(7);
 }
 
 size_t decode_hier_lds_bytes(const Dev &d, int P, int n_probe) {
@@ -327,22 +429,26 @@ size_t decode_hier_lds_bytes(const Dev &d, int P, int n_probe) {
     return hier_lds(d.Cpad, d.max_pages, n_probe, P, d.G, NW).total;
 }
 
-void launch_decode_hier(const Dev &d, const bf16_t *q, int cur, int P, int n_probe, int *ids, int *n_sel, float *scores_out,
-                        int *clusters_out, float *out, hipStream_t st) {
+void launch_decode_hier(const Dev &d, const bf16_t *q, int cur, int P, int n_probe, int np_hint, int *ids, int *n_sel,
+                        float *scores_out, int *clusters_out, float *out, hipStream_t st) {
     const size_t lds = decode_hier_lds_bytes(d, P, n_probe);
-#define ICE_HIER(g, nw)                                                                                              \
+    const int NW = d.G == 8 ? 8 : 16;
+    if (np_hint > d.max_pages) np_hint = d.max_pages;
+    const int E = (d.max_pages + NW * 64 - 1) / (NW * 64);
+#define ICE_HIER(g, nw, e)                                                                                           \
     do {                                                                                                             \
-        (void)hipFuncSetAttribute((const void *)decode_hier_kernel<g, nw>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds); \
-        hipLaunchKernelGGL((decode_hier_kernel<g, nw>), dim3(d.U), dim3(nw * 64), lds, st, d, q, cur, P, n_probe, ids, n_sel, \
-                           scores_out, clusters_out, out);                                                           \
+        (void)hipFuncSetAttribute((const void *)decode_hier_kernel<g, nw, e>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds); \
+        hipLaunchKernelGGL((decode_hier_kernel<g, nw, e>), dim3(d.U), dim3(nw * 64), lds, st, d, q, cur, P, n_probe, np_hint, ids, \
+                           n_sel, scores_out, clusters_out, out);                                                    \
     } while (0)
-    switch (d.G) {
-        case 1: ICE_HIER(1, 16); break;
-        case 2: ICE_HIER(2, 16); break;
-        case 4: ICE_HIER(4, 16); break;
-        default: ICE_HIER(8, 8); break;
-    }
+    if (d.G == 8) { if (E <= 8) ICE_HIER(8, 8, 8); else ICE_HIER(8, 8, 32); }
+    else if (d.G == 4) { if (E <= 4) ICE_HIER(4, 16, 4); else ICE_HIER(4, 16, 16); }
+    else if (d.G == 2) { if (E <= 4) ICE_HIER(2, 16, 4); else ICE_HIER(2, 16, 16); }
+    else { if (E <= 4) ICE_HIER(1, 16, 4); else ICE_HIER(1, 16, 16); }
 #undef ICE_HIER
 }
+
+// largest page count per unit the kernel serves (page -> cluster entries held in registers)
+int decode_hier_max_pages(int G) { return G == 8 ? 8 * 64 * 32 : 16 * 64 * 16; }
 
 }  // namespace ice

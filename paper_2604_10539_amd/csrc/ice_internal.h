@@ -69,8 +69,9 @@ void launch_insert(const Dev &d, const bf16_t *k, const bf16_t *v, int cur, hipS
 void launch_decode_step(const Dev &d, const bf16_t *q, int P, int np_hint, int *ids, int *n_sel, float *scores_out,
                         float *out, hipStream_t st);
 // two-stage selection (clusters, then their pages) (+ attention when out != nullptr) in one launch
-void launch_decode_hier(const Dev &d, const bf16_t *q, int cur, int P, int n_probe, int *ids, int *n_sel, float *scores_out,
-                        int *clusters_out, float *out, hipStream_t st);
+void launch_decode_hier(const Dev &d, const bf16_t *q, int cur, int P, int n_probe, int np_hint, int *ids, int *n_sel,
+                        float *scores_out, int *clusters_out, float *out, hipStream_t st);
+int decode_hier_max_pages(int G);
 size_t decode_hier_lds_bytes(const Dev &d, int P, int n_probe);
 int decode_step_max_pages(int G);
 size_t decode_step_lds_bytes(const Dev &d, int P);

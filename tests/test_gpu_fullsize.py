@@ -11,7 +11,7 @@ import torch
 import datagen
 from datagen import bf16_bits_to_f32 as widen, f32_to_bf16_bits as narrow
 from oracle import ice_oracle as orc
-from tests.test_gpu_parity import ATTN_EXPECTED, ATTN_TOL, _assign_band, _compare_select
+from tests.test_gpu_parity import ATTN_EXPECTED, ATTN_TOL, _assign_band, _check_hier, _compare_select
 from tests.util import D, down, up, valid_slot_mask
 
 pytestmark = pytest.mark.gpu
@@ -28,7 +28,15 @@ def _select_attend_vs_oracle(ix, ex, q_np, budget, ids, n_sel, out):
     o.n_pages[...] = down(ex["n_pages"])
     o.page_fill[...] = down(ex["page_fill"])
     _compare_select(o, q_np, budget, down(ids2), down(ns))
-    # compact index: page j of unit u = the j-th selected page
+    _attend_vs_oracle(ix, ex, q_np, budget, ids, n_sel, out)
+
+
+def _attend_vs_oracle(ix, ex, q_np, budget, ids, n_sel, out):
+    """Attention over the GPU's ids against the oracle, which gets only the selected K/V tiles
+    (gathered on the GPU) as a compact index: page j of unit u = the j-th selected page."""
+    U, G, s = ix.U, ix.group_size, ix.page_size
+    P = ids.shape[-1]
+    ids2, ns = ids.reshape(U, P), n_sel.reshape(U)
     gi = ids2.clamp(min=0).long()
     g = orc.OracleIndex(U, G, s, ix.n_clusters, ix.max_tokens, max_pages=P)
     g.Kp[...] = down(torch.gather(ex["Kp"], 1, gi[:, :, None, None].expand(U, P, s, D)))
@@ -42,6 +50,18 @@ def _select_attend_vs_oracle(ix, ex, q_np, budget, ids, n_sel, out):
     fill = down(ex["page_fill"])
     for u in range(U):
         assert fill[u, down(ids2)[u, :down(ns)[u]]].sum() <= budget
+
+
+def _hier_vs_oracle(ix, ex, q_np, budget, n_probe):
+    """Two-stage selection + attention in one launch against the oracle (representatives, page ->
+    cluster table and centroids in full; K/V only for the selected pages)."""
+    ids, n_sel, scores, clusters, out = ix.select_hier(up(q_np), budget, n_probe)
+    torch.cuda.synchronize()
+    o = orc.OracleIndex(ix.U, ix.group_size, ix.page_size, ix.n_clusters, ix.max_tokens, alloc_kv=False)
+    for name in ("rep", "n_pages", "page_fill", "page_cluster", "centroid"):
+        getattr(o, name)[...] = down(ex[name])
+    _check_hier(ix, o, q_np, budget, n_probe, ids, n_sel, scores, clusters, None)
+    _attend_vs_oracle(ix, ex, q_np, budget, ids, n_sel, out)
 
 
 def _check_units(ix, ex, K, V, units, n, rng, n_keys=256):
@@ -105,6 +125,7 @@ def test_config2_all_32_layers_in_the_bench_launch_shape():
     ex = ix.export()
     _select_attend_vs_oracle(ix, ex, q_np, 256, ids, n_sel, out)
     _check_units(ix, ex, K, V, [0, 97, 255], w.n_tokens, np.random.default_rng(0))
+    _hier_vs_oracle(ix, ex, q_np, 256, 64)                   # the benchmark's hierarchical variant
     # one layer at a time (8 units, several workgroups per unit) gives the same ids and output bits
     one = IceIndex(1, 8, 4, w.n_tokens + 64, 16, 512, kmeans_iters=2, init_idx=up(init[5]))
     one.build_index(up(K[40:48]), up(V[40:48]))
@@ -128,6 +149,7 @@ def test_config3_shape_long_context():
     ex = ix.export()
     _select_attend_vs_oracle(ix, ex, q_np, 1024, ids, n_sel, out)
     _check_units(ix, ex, K, V, [1], w.n_tokens, np.random.default_rng(1), n_keys=64)
+    _hier_vs_oracle(ix, ex, q_np, 1024, 256)
 
 
 def test_config4_shape_batched_sequences():
