@@ -1,6 +1,6 @@
 // Device code shared by the decode-step kernels (flat and hierarchical page selection): vector
-// types, packed-bf16 dot products, the query operand of the scoring / logit MFMAs, the exact
-// ranking of a short candidate list, and sparse paged attention over a list of pages.
+// types, packed-bf16 dot products, the query operand of the scoring / logit MFMAs, and sparse
+// paged attention over a list of pages.
 #pragma once
 #include "ice_internal.h"
 
