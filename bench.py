@@ -76,7 +76,7 @@ def main():
     L, H, G, n, s, C, budget = args.layers, w.n_kv_heads, w.group_size, w.n_tokens, w.page_size, w.n_clusters, w.token_budget
     P = budget // s
     T = args.kmeans_iters
-    max_tokens = n + 64
+    max_tokens = n + 128
 
     t0 = time.time()
     with ThreadPoolExecutor(max_workers=min(16, L)) as ex:
@@ -312,6 +312,17 @@ def main():
     e1.record(st)
     torch.cuda.synchronize()
     us_insert = e0.elapsed_time(e1) / n_ins * 1e3
+    # a page of tokens at a time (tokens leaving the recent window): 16 per launch
+    k16 = k1[:, :, None, :].expand(L, H, 16, D).contiguous()
+    v16 = v1[:, :, None, :].expand(L, H, 16, D).contiguous()
+    batched.insert_batch(k16, v16)
+    torch.cuda.synchronize()
+    e0.record(st)
+    batched.insert_batch(k16, v16)
+    batched.insert_batch(k16, v16)
+    e1.record(st)
+    torch.cuda.synchronize()
+    us_insert16 = e0.elapsed_time(e1) / 2 * 1e3
 
     # ---------------------------------------------------------------- CPU oracle on the same step
     cpu = None
@@ -400,7 +411,7 @@ def main():
         "flush_per_step": {"us_per_step": ms_flush * 1e3,
                            "how": "same launch, one event pair per step, 1 GiB read between steps (untimed)"},
         "spread": {"batched_us_per_step": spread_batched, "sequential_us_per_layer_step": spread_seq},
-        "insert": {"us_per_call_256_units": us_insert},
+        "insert": {"us_per_call_256_units": us_insert, "us_per_call_of_16_tokens_256_units": us_insert16},
         "pages_per_unit_mean": float(n_pages.mean()),
         "datagen_s": t_gen,
         "cpu_baseline": cpu,

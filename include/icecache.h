@@ -123,6 +123,13 @@ ice_status_t ice_build_index(ice_index_t *idx, const void *K, const void *V, int
  *   k, v: bf16 [B, H_kv, d].   CAPACITY when n_tokens == max_tokens; STATE before a build. */
 ice_status_t ice_insert(ice_index_t *idx, const void *k, const void *v, void *stream);
 
+/* The same for m tokens per (sequence, KV head), inserted one after the other in the order given
+ * (each sees the centroid the previous one moved): the state afterwards is bit for bit that of m
+ * ice_insert calls.  This is how tokens that leave the recent window enter the index a page at a
+ * time (Alg. 1, insertion loop).  k, v: bf16 [B, H_kv, m, d].  SHAPE for m < 1; CAPACITY when
+ * the index would hold more than max_tokens tokens per unit (nothing is inserted then). */
+ice_status_t ice_insert_batch(ice_index_t *idx, const void *k, const void *v, int32_t m, void *stream);
+
 /* Page selection for one decode query (Sec. 4.3-4.4, Alg. 3): P = floor(token_budget/page_size);
  * score(p) = max over the G query heads of (q_h . rep_p) / ||q_h||; the min(P, n_pages) best
  * pages by (score descending, id ascending) are returned with ids ascending, padded with -1.

@@ -16,7 +16,7 @@ LIB_PATH = os.path.join(_PKG, "libicecache.so")
 ICE_OK, ICE_ERR_INVALID_ARG, ICE_ERR_SHAPE, ICE_ERR_STATE, ICE_ERR_CAPACITY, ICE_ERR_UNSUPPORTED, ICE_ERR_DEVICE = range(7)
 STATUS_NAMES = ["ICE_OK", "ICE_ERR_INVALID_ARG", "ICE_ERR_SHAPE", "ICE_ERR_STATE", "ICE_ERR_CAPACITY",
                 "ICE_ERR_UNSUPPORTED", "ICE_ERR_DEVICE"]
-SYMBOLS = ["ice_workspace_bytes", "ice_create", "ice_destroy", "ice_build_index", "ice_insert", "ice_select",
+SYMBOLS = ["ice_workspace_bytes", "ice_create", "ice_destroy", "ice_build_index", "ice_insert", "ice_insert_batch", "ice_select",
            "ice_attend", "ice_select_attend", "ice_select_hier", "ice_export_index", "ice_import_index", "ice_debug_assign",
            "ice_debug_peak_read", "ice_debug_peak_mfma", "ice_last_error"]
 
@@ -59,6 +59,7 @@ def lib() -> C.CDLL:
         L.ice_destroy.argtypes = [C.c_void_p]
         L.ice_build_index.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.c_int32, C.c_void_p]
         L.ice_insert.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]
+        L.ice_insert_batch.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32, C.c_void_p]
         L.ice_select.argtypes = [C.c_void_p, C.c_void_p, C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]
         L.ice_attend.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32, C.c_void_p, C.c_void_p]
         L.ice_select_attend.argtypes = [C.c_void_p, C.c_void_p, C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p,
@@ -129,6 +130,10 @@ def ice_build_index(idx, K, V, n_tokens, page_size, n_clusters, stream=None) -> 
 
 def ice_insert(idx, k, v, stream=None) -> None:
     _check(lib().ice_insert(idx, _ptr(k), _ptr(v), _stream(stream)))
+
+
+def ice_insert_batch(idx, k, v, m, stream=None) -> None:
+    _check(lib().ice_insert_batch(idx, _ptr(k), _ptr(v), m, _stream(stream)))
 
 
 def ice_select(idx, q, token_budget, page_ids, n_selected, scores=None, stream=None) -> None:
@@ -233,6 +238,10 @@ class IceIndex:
 
     def insert(self, k, v, stream=None):
         ice_insert(self.handle, k, v, stream)
+
+    def insert_batch(self, k, v, stream=None):
+        """k, v: [B, H_kv, m, 128]; the m tokens are inserted in order, as m insert() calls would."""
+        ice_insert_batch(self.handle, k, v, int(k.shape[-2]), stream)
 
     def _sel_buffers(self, token_budget):
         P = max(token_budget // self.page_size, 1)

@@ -192,17 +192,23 @@ ice_status_t ice_build_index(ice_index_t *ix, const void *K, const void *V, int3
     return ICE_OK;
 }
 
-ice_status_t ice_insert(ice_index_t *ix, const void *k, const void *v, void *stream) {
+ice_status_t ice_insert_batch(ice_index_t *ix, const void *k, const void *v, int32_t m, void *stream) {
     if (!ix) return fail(ICE_ERR_INVALID_ARG, "index is null");
     if (!ix->built) return fail(ICE_ERR_STATE, "ice_insert before ice_build_index");
     if (!k || !v || !aligned16(k) || !aligned16(v)) return fail(ICE_ERR_INVALID_ARG, "k or v is null or misaligned");
-    if (ix->n_tokens >= ix->cfg.max_tokens)
-        return fail(ICE_ERR_CAPACITY, "index already holds max_tokens = %d tokens per unit", ix->cfg.max_tokens);
-    launch_insert(ix->dev, static_cast<const bf16_t *>(k), static_cast<const bf16_t *>(v), ix->cur,
+    if (m < 1) return fail(ICE_ERR_SHAPE, "number of tokens to insert must be >= 1");
+    if ((long long)ix->n_tokens + m > ix->cfg.max_tokens)
+        return fail(ICE_ERR_CAPACITY, "index holds %d tokens per unit, %d more exceed max_tokens = %d", ix->n_tokens, m,
+                    ix->cfg.max_tokens);
+    launch_insert(ix->dev, static_cast<const bf16_t *>(k), static_cast<const bf16_t *>(v), m, ix->cur,
                   static_cast<hipStream_t>(stream));
     if (ice_status_t st = device_status("ice_insert")) return st;
-    ix->n_tokens += 1;
+    ix->n_tokens += m;
     return ICE_OK;
+}
+
+ice_status_t ice_insert(ice_index_t *ix, const void *k, const void *v, void *stream) {
+    return ice_insert_batch(ix, k, v, 1, stream);
 }
 
 static ice_status_t check_select(ice_index_t *ix, const void *q, int32_t budget, const int32_t *ids,

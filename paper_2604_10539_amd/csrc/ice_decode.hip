@@ -21,96 +21,104 @@ constexpr uint32_t kScoreEmpty = 0xFFFFFFFFu;  // a NaN pattern no score can tak
 
 
 // ------------------------------------------------------------------------------------------------
-// Insertion of one token per unit (Alg. 1 insertion loop; a node that outgrows its page gets a new
-// one, Sec. 4.1).  One workgroup per unit: its 16 waves scan the bf16 centroids (16 lanes x 16 bytes
-// per row, four rows per wave and load, four loads in flight) for the nearest one, lowest id on
-// ties; wave 0 then appends the key/value row to the cluster's tail page and updates, in ordered
-// fp32 (one add per quantity): page sum -> representative, cluster sum -> centroid, its bf16
-// rounding and squared norm.
+// Insertion of m tokens per unit, one after the other (Alg. 1 insertion loop; a node that outgrows
+// its page gets a new one, Sec. 4.1; m > 1 is the page-at-a-time insertion of tokens that leave the
+// recent window).  One workgroup per unit.  Per token: its 16 waves scan the bf16 centroids
+// (16 lanes x 16 bytes per row, four rows per wave and load, four loads in flight) for the nearest
+// one, lowest id on ties; wave 0 then appends the key/value row to the cluster's tail page and
+// updates, in ordered fp32 (one add per quantity): page sum -> representative, cluster sum ->
+// centroid, its bf16 rounding and squared norm.  The next token sees the moved centroid, exactly
+// as m separate launches would.  k, v: bf16 [U, m, d].
 constexpr int kInsertWaves = 16;
 __global__ __launch_bounds__(kInsertWaves * 64) void insert_kernel(Dev d, const bf16_t *__restrict__ k,
-                                                                    const bf16_t *__restrict__ v, int cur) {
+                                                                    const bf16_t *__restrict__ v, int m, int cur) {
     __shared__ u64 best;
     const int u = blockIdx.x, tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
     const int g = lane >> 4, ch = lane & 15;
-    if (tid == 0) best = ~0ull;
-    __syncthreads();
-    const uint4 kq = ((const uint4 *)(k + (size_t)u * kD))[ch];
     // what the append needs and does not depend on the chosen cluster is requested before the scan
-    const int np = d.n_pages[u];
-    const int tok = d.n_tokens[u];
-    const uint32_t kw = ((const uint32_t *)(k + (size_t)u * kD))[lane];
-    const uint32_t vw = ((const uint32_t *)(v + (size_t)u * kD))[lane];
+    int np = d.n_pages[u];
+    int tok = d.n_tokens[u];
     const bf16_t *cb = d.cent_bf16[cur] + (size_t)u * d.Cpad * kD;
     const float *wn = d.cnorm[cur] + (size_t)u * d.Cpad;
-    float bv = INFINITY;
-    int bi = 0x7FFFFFFF;
     constexpr int RS = kInsertWaves * 4;  // rows per pass of the workgroup
-    for (int r0 = wave * 4 + g; r0 < d.C; r0 += 4 * RS) {
-        uint4 row[4];
-        float w[4];
+    for (int t = 0; t < m; ++t) {
+        const bf16_t *kt = k + ((size_t)u * m + t) * kD, *vt = v + ((size_t)u * m + t) * kD;
+        if (tid == 0) best = ~0ull;
+        __syncthreads();  // also: the previous token's updates are visible to every wave
+        const uint4 kq = ((const uint4 *)kt)[ch];
+        const uint32_t kw = ((const uint32_t *)kt)[lane];
+        const uint32_t vw = ((const uint32_t *)vt)[lane];
+        float bv = INFINITY;
+        int bi = 0x7FFFFFFF;
+        for (int r0 = wave * 4 + g; r0 < d.C; r0 += 4 * RS) {
+            uint4 row[4];
+            float w[4];
 #pragma unroll
-        for (int x = 0; x < 4; ++x) {
-            const int r = r0 + x * RS;
-            row[x] = r < d.C ? ((const uint4 *)(cb + (size_t)r * kD))[ch] : make_uint4(0, 0, 0, 0);
-            w[x] = r < d.C ? wn[r] : INFINITY;
-        }
+            for (int x = 0; x < 4; ++x) {
+                const int r = r0 + x * RS;
+                row[x] = r < d.C ? ((const uint4 *)(cb + (size_t)r * kD))[ch] : make_uint4(0, 0, 0, 0);
+                w[x] = r < d.C ? wn[r] : INFINITY;
+            }
 #pragma unroll
-        for (int x = 0; x < 4; ++x) {  // ascending r: a later row wins only when strictly smaller
-            const float dot = row16_sum(dot8(row[x], kq));
-            const float val = w[x] - 2.0f * dot;
-            if (val < bv) { bv = val; bi = r0 + x * RS; }
+            for (int x = 0; x < 4; ++x) {  // ascending r: a later row wins only when strictly smaller
+                const float dot = row16_sum(dot8(row[x], kq));
+                const float val = w[x] - 2.0f * dot;
+                if (val < bv) { bv = val; bi = r0 + x * RS; }
+            }
         }
-    }
-    if (ch == 0 && bi != 0x7FFFFFFF) atomicMin(&best, ((u64)f32_ordered(bv) << 32) | (u64)(uint32_t)bi);
-    __syncthreads();
-    if (wave != 0) return;
-    const int c = (int)(uint32_t)best;
-    const size_t cl = (size_t)u * d.C + c;
-    int tail = d.cluster_tail[cl];
-    int fill = tail >= 0 ? d.page_fill[(size_t)u * d.max_pages + tail] : d.s;
-    const int cnt = d.cluster_cnt[cl] + 1;
-    const bool fresh = fill == d.s;
-    if (fresh) { tail = np; fill = 0; }
-    const size_t pg = (size_t)u * d.max_pages + tail;
-    const int slot = fill;
-    fill += 1;
-    ((uint32_t *)(d.Kp + (pg * d.s + slot) * kD))[lane] = kw;
-    ((uint32_t *)(d.Vp + (pg * d.s + slot) * kD))[lane] = vw;
-    const float k0 = bf16_lo(kw), k1 = bf16_hi(kw);
-    float2 ps = fresh ? make_float2(0.f, 0.f) : ((const float2 *)(d.page_sum + pg * kD))[lane];
-    ps.x = ps.x + k0;
-    ps.y = ps.y + k1;
-    ((float2 *)(d.page_sum + pg * kD))[lane] = ps;
-    const float ff = (float)fill;
-    ((uint32_t *)(d.rep + pg * kD))[lane] = (uint32_t)f32_to_bf16(ps.x / ff) | ((uint32_t)f32_to_bf16(ps.y / ff) << 16);
-    float2 cs = ((const float2 *)(d.cluster_sum + cl * kD))[lane];
-    cs.x = cs.x + k0;
-    cs.y = cs.y + k1;
-    ((float2 *)(d.cluster_sum + cl * kD))[lane] = cs;
-    const float fc = (float)cnt;
-    const float2 mu = make_float2(cs.x / fc, cs.y / fc);
-    ((float2 *)(d.centroid + cl * kD))[lane] = mu;
-    const bf16_t b0 = f32_to_bf16(mu.x), b1 = f32_to_bf16(mu.y);
-    ((uint32_t *)(d.cent_bf16[cur] + ((size_t)u * d.Cpad + c) * kD))[lane] = (uint32_t)b0 | ((uint32_t)b1 << 16);
-    const float f0 = bf16_to_f32(b0), f1 = bf16_to_f32(b1);
-    const float nn = wave_sum(f0 * f0 + f1 * f1);
-    if (lane == 0) {
-        d.cnorm[cur][(size_t)u * d.Cpad + c] = nn;
-        d.cluster_cnt[cl] = cnt;
-        d.cluster_tail[cl] = tail;
-        d.page_fill[pg] = fill;
-        d.page_pos[pg * d.s + slot] = tok;
-        d.n_tokens[u] = tok + 1;
-        if (fresh) {
-            d.page_cluster[pg] = c;
-            d.n_pages[u] = np + 1;
+        if (ch == 0 && bi != 0x7FFFFFFF) atomicMin(&best, ((u64)f32_ordered(bv) << 32) | (u64)(uint32_t)bi);
+        __syncthreads();
+        if (wave == 0) {
+            const int c = (int)(uint32_t)best;
+            const size_t cl = (size_t)u * d.C + c;
+            int tail = d.cluster_tail[cl];
+            int fill = tail >= 0 ? d.page_fill[(size_t)u * d.max_pages + tail] : d.s;
+            const int cnt = d.cluster_cnt[cl] + 1;
+            const bool fresh = fill == d.s;
+            if (fresh) { tail = np; fill = 0; }
+            const size_t pg = (size_t)u * d.max_pages + tail;
+            const int slot = fill;
+            fill += 1;
+            ((uint32_t *)(d.Kp + (pg * d.s + slot) * kD))[lane] = kw;
+            ((uint32_t *)(d.Vp + (pg * d.s + slot) * kD))[lane] = vw;
+            const float k0 = bf16_lo(kw), k1 = bf16_hi(kw);
+            float2 ps = fresh ? make_float2(0.f, 0.f) : ((const float2 *)(d.page_sum + pg * kD))[lane];
+            ps.x = ps.x + k0;
+            ps.y = ps.y + k1;
+            ((float2 *)(d.page_sum + pg * kD))[lane] = ps;
+            const float ff = (float)fill;
+            ((uint32_t *)(d.rep + pg * kD))[lane] = (uint32_t)f32_to_bf16(ps.x / ff) | ((uint32_t)f32_to_bf16(ps.y / ff) << 16);
+            float2 cs = ((const float2 *)(d.cluster_sum + cl * kD))[lane];
+            cs.x = cs.x + k0;
+            cs.y = cs.y + k1;
+            ((float2 *)(d.cluster_sum + cl * kD))[lane] = cs;
+            const float fc = (float)cnt;
+            const float2 mu = make_float2(cs.x / fc, cs.y / fc);
+            ((float2 *)(d.centroid + cl * kD))[lane] = mu;
+            const bf16_t b0 = f32_to_bf16(mu.x), b1 = f32_to_bf16(mu.y);
+            ((uint32_t *)(d.cent_bf16[cur] + ((size_t)u * d.Cpad + c) * kD))[lane] = (uint32_t)b0 | ((uint32_t)b1 << 16);
+            const float f0 = bf16_to_f32(b0), f1 = bf16_to_f32(b1);
+            const float nn = wave_sum(f0 * f0 + f1 * f1);
+            if (lane == 0) {
+                d.cnorm[cur][(size_t)u * d.Cpad + c] = nn;
+                d.cluster_cnt[cl] = cnt;
+                d.cluster_tail[cl] = tail;
+                d.page_fill[pg] = fill;
+                d.page_pos[pg * d.s + slot] = tok;
+                d.n_tokens[u] = tok + 1;
+                if (fresh) {
+                    d.page_cluster[pg] = c;
+                    d.n_pages[u] = np + 1;
+                }
+            }
+            if (fresh) np += 1;
         }
+        tok += 1;
     }
 }
 
-void launch_insert(const Dev &d, const bf16_t *k, const bf16_t *v, int cur, hipStream_t st) {
-    hipLaunchKernelGGL(insert_kernel, dim3(d.U), dim3(kInsertWaves * 64), 0, st, d, k, v, cur);
+void launch_insert(const Dev &d, const bf16_t *k, const bf16_t *v, int m, int cur, hipStream_t st) {
+    hipLaunchKernelGGL(insert_kernel, dim3(d.U), dim3(kInsertWaves * 64), 0, st, d, k, v, m, cur);
 }
 
 // ------------------------------------------------------------------------------------------------

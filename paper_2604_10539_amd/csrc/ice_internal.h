@@ -63,7 +63,7 @@ void launch_sort(const Dev &d, int n, float *best_out_or_null, int *assign_out_o
 void launch_means(const Dev &d, const bf16_t *K, int n, int cur, hipStream_t st);
 void launch_paginate(const Dev &d, const bf16_t *K, const bf16_t *V, int n, hipStream_t st);
 void launch_refresh_centroids(const Dev &d, int cur, hipStream_t st);
-void launch_insert(const Dev &d, const bf16_t *k, const bf16_t *v, int cur, hipStream_t st);
+void launch_insert(const Dev &d, const bf16_t *k, const bf16_t *v, int m, int cur, hipStream_t st);
 // scores + top-P selection (+ attention when out != nullptr) in one launch
 // np_hint: host-side upper bound of the live pages per unit (tokens / page_size + clusters)
 void launch_decode_step(const Dev &d, const bf16_t *q, int P, int np_hint, int *ids, int *n_sel, float *scores_out,

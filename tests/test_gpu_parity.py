@@ -548,3 +548,55 @@ def test_hier_select_argument_errors():
         with pytest.raises(IceError) as e:
             ix.select_hier(q, budget, n_probe)
         assert e.value.status == status
+
+
+@pytest.mark.gpu
+@pytest.mark.parametrize("kw,m", [
+    (dict(n_tokens=2000, n_clusters=24, n_kv_heads=2, n_components=16, drift=0.01), 16),
+    (dict(n_tokens=600, n_clusters=3, n_kv_heads=3, page_size=32, n_components=2, drift=0.02), 32),   # same cluster again and again
+    (dict(n_tokens=900, n_clusters=40, n_kv_heads=1, group_size=8, n_components=8), 5),
+])
+def test_insert_batch_equals_one_by_one(kw, m):
+    """m tokens in one launch leave the index bit for bit as m single insertions do (each token sees
+    the centroid the previous one moved, pages fill and open in the same order)."""
+    w = datagen.small(**kw)
+    rounds = 4
+    ix_a, K, V, _ = _mk(w, T=2, extra=rounds * m)
+    ix_b, _, _, _ = _mk(w, T=2, extra=rounds * m)
+    ix_a.build_index(up(K), up(V))
+    ix_b.build_index(up(K), up(V))
+    stream = datagen.DecodeStream(w, seed=5)
+    U = ix_a.U
+    for _ in range(rounds):
+        ks, vs = [], []
+        for _ in range(m):
+            k, v, _ = stream.next()
+            ix_a.insert(up(k), up(v))
+            ks.append(k.reshape(U, D))
+            vs.append(v.reshape(U, D))
+        kb = np.stack(ks, 1).reshape(w.batch, w.n_kv_heads, m, D)
+        vb = np.stack(vs, 1).reshape(w.batch, w.n_kv_heads, m, D)
+        ix_b.insert_batch(up(kb), up(vb))
+    ea, eb = export_np(ix_a), export_np(ix_b)
+    assert ea["n_tokens"] == eb["n_tokens"] == w.n_tokens + rounds * m
+    assert np.array_equal(ea["n_pages"], eb["n_pages"]) and np.array_equal(ea["page_fill"], eb["page_fill"])
+    for u in range(U):
+        npg = int(ea["n_pages"][u])
+        live = valid_slot_mask(ea["page_fill"][u, :npg], w.page_size)     # slots past the fill of a page are never written
+        for name in STATE_FIELDS:
+            a, b = ea[name][u], eb[name][u]
+            if name in ("Kp", "Vp", "page_pos"):
+                a, b = a[:npg][live], b[:npg][live]
+            elif name in ("page_cluster", "page_fill", "page_sum", "rep"):
+                a, b = a[:npg], b[:npg]
+            assert np.array_equal(np.ascontiguousarray(a).view(np.uint8), np.ascontiguousarray(b).view(np.uint8)), name
+    # and the selection on top of it is the same
+    q = up(datagen.queries(w))
+    ia, na, _ = ix_a.select(q, 16 * w.page_size)
+    ib, nb, _ = ix_b.select(q, 16 * w.page_size)
+    assert torch.equal(ia, ib) and torch.equal(na, nb)
+    # capacity: one token too many is refused as a whole
+    from paper_2604_10539_amd import IceError, binding as b
+    with pytest.raises(IceError) as e:
+        ix_b.insert_batch(up(kb[:, :, :1]), up(vb[:, :, :1]))
+    assert e.value.status == b.ICE_ERR_CAPACITY
