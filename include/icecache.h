@@ -151,6 +151,21 @@ ice_status_t ice_attend(ice_index_t *idx, const void *q, const int32_t *page_ids
 ice_status_t ice_select_attend(ice_index_t *idx, const void *q, int32_t token_budget,
                                int32_t *page_ids, int32_t *n_selected, float *out, void *stream);
 
+/* Attention with resident tokens: the decode loop of the paper (Alg. 1, App. A) always attends to
+ * the sink tokens at the start of the sequence and to a window of the most recent tokens, which
+ * are not (yet) in the index.  The caller keeps them as one dense run per (sequence, KV head),
+ *   resident_k, resident_v bf16 [B, H_kv, n_resident, d]   (device, caller-owned, 16-byte aligned),
+ * and these calls put them in the same softmax as the tokens of the pages (Eq. 1 with the mask on
+ * the union).  n_resident = 0 gives ice_attend / ice_select_attend exactly (the pointers are then
+ * not read).  SHAPE for n_resident outside [0, 2^20]; otherwise the errors of the plain calls.
+ * Tokens leave the window into the index with ice_insert_batch. */
+ice_status_t ice_attend_resident(ice_index_t *idx, const void *q, const int32_t *page_ids,
+                                 const int32_t *n_selected, int32_t n_ids_per_unit, const void *resident_k,
+                                 const void *resident_v, int32_t n_resident, float *out, void *stream);
+ice_status_t ice_select_attend_resident(ice_index_t *idx, const void *q, int32_t token_budget,
+                                        const void *resident_k, const void *resident_v, int32_t n_resident,
+                                        int32_t *page_ids, int32_t *n_selected, float *out, void *stream);
+
 /* Hierarchical selection: the two-level form of the paper's top-down search (Sec. 4.3, Alg. 3).
  * Stage 1 ranks the n_clusters centroids (as stored, rounded to bf16) by the same normalised GQA
  * score as pages and keeps the min(n_probe, n_clusters) best, lower id first on ties; every

@@ -511,3 +511,62 @@ void orc_attend(const orc_state_t *st, const uint16_t *q, const int32_t *ids, co
         free(o);
     }
 }
+
+/* ---- sparse attention with resident tokens -----------------------------------------------------
+ * The decode loop of the paper (Alg. 1, App. A) always attends to the sink tokens at the start of
+ * the sequence and to a window of the most recent tokens, which are not (yet) in the index; the
+ * selected pages come on top.  Here the resident tokens are one dense run per unit:
+ * rk, rv bf16 [U][n_res][d].  One softmax over the tokens of the listed pages and the resident
+ * tokens together (Eq. 1 with the mask on their union). */
+void orc_attend_resident(const orc_state_t *st, const uint16_t *q, const int32_t *ids, const int32_t *n_sel,
+                         int P, const uint16_t *rk, const uint16_t *rv, int n_res, float *out) {
+    const int d = st->d, s = st->s, G = st->G, MP = st->max_pages;
+    const double scale = 1.0 / sqrt((double)d);
+#pragma omp parallel for schedule(dynamic, 1)
+    for (int u = 0; u < st->U; ++u) {
+        const int ns = n_sel[u];
+        /* rows of every attended token, in any order */
+        size_t cap = (size_t)(ns > 0 ? ns : 0) * s + (size_t)n_res + 1;
+        const uint16_t **kr = (const uint16_t **)malloc(sizeof(void *) * cap);
+        const uint16_t **vr = (const uint16_t **)malloc(sizeof(void *) * cap);
+        int m = 0;
+        for (int x = 0; x < ns; ++x) {
+            size_t pg = (size_t)u * MP + ids[(size_t)u * P + x];
+            for (int t = 0; t < st->page_fill[pg]; ++t) {
+                kr[m] = st->Kp + (pg * s + t) * d;
+                vr[m] = st->Vp + (pg * s + t) * d;
+                ++m;
+            }
+        }
+        for (int t = 0; t < n_res; ++t) {
+            kr[m] = rk + ((size_t)u * n_res + t) * d;
+            vr[m] = rv + ((size_t)u * n_res + t) * d;
+            ++m;
+        }
+        double *z = (double *)malloc(sizeof(double) * (size_t)(m > 0 ? m : 1));
+        for (int h = 0; h < G; ++h) {
+            const uint16_t *qh = q + ((size_t)u * G + h) * d;
+            double zmax = -INFINITY;
+            for (int i = 0; i < m; ++i) {
+                double dot = 0.0;
+                for (int j = 0; j < d; ++j) dot += (double)bf16_to_f32(qh[j]) * (double)bf16_to_f32(kr[i][j]);
+                z[i] = dot * scale;
+                if (z[i] > zmax) zmax = z[i];
+            }
+            double den = 0.0;
+            for (int i = 0; i < m; ++i) {
+                z[i] = exp(z[i] - zmax);
+                den += z[i];
+            }
+            float *oh = out + ((size_t)u * G + h) * d;
+            for (int j = 0; j < d; ++j) {
+                double o = 0.0;
+                for (int i = 0; i < m; ++i) o += z[i] * (double)bf16_to_f32(vr[i][j]);
+                oh[j] = (m > 0) ? (float)(o / den) : 0.0f;
+            }
+        }
+        free(z);
+        free(kr);
+        free(vr);
+    }
+}

@@ -221,3 +221,20 @@ class OracleIndex:
         st = self._state()
         lib().orc_attend(C.byref(st), _p(q), _p(ids), _p(n_sel), C.c_int(P), _p(out))
         return out
+
+    def attend_resident(self, q: np.ndarray, ids: np.ndarray, n_sel: np.ndarray, rk: np.ndarray,
+                        rv: np.ndarray) -> np.ndarray:
+        """Attention over the listed pages and n_res resident tokens per unit (rk, rv uint16
+        [..., n_res, d]) in one softmax: float32 [U, G, d]."""
+        q = self._units(q, (self.G, self.d), np.uint16)
+        P = ids.shape[-1]
+        ids = self._units(ids, (P,), np.int32)
+        n_sel = self._units(n_sel, (), np.int32)
+        n_res = rk.shape[-2]
+        rk = self._units(rk, (n_res, self.d), np.uint16)
+        rv = self._units(rv, (n_res, self.d), np.uint16)
+        out = np.zeros((self.U, self.G, self.d), np.float32)
+        st = self._state()
+        lib().orc_attend_resident(C.byref(st), _p(q), _p(ids), _p(n_sel), C.c_int(P), _p(rk), _p(rv),
+                                  C.c_int(n_res), _p(out))
+        return out

@@ -17,7 +17,7 @@ ICE_OK, ICE_ERR_INVALID_ARG, ICE_ERR_SHAPE, ICE_ERR_STATE, ICE_ERR_CAPACITY, ICE
 STATUS_NAMES = ["ICE_OK", "ICE_ERR_INVALID_ARG", "ICE_ERR_SHAPE", "ICE_ERR_STATE", "ICE_ERR_CAPACITY",
                 "ICE_ERR_UNSUPPORTED", "ICE_ERR_DEVICE"]
 SYMBOLS = ["ice_workspace_bytes", "ice_create", "ice_destroy", "ice_build_index", "ice_insert", "ice_insert_batch", "ice_select",
-           "ice_attend", "ice_select_attend", "ice_select_hier", "ice_export_index", "ice_import_index", "ice_debug_assign",
+           "ice_attend", "ice_select_attend", "ice_attend_resident", "ice_select_attend_resident", "ice_select_hier", "ice_export_index", "ice_import_index", "ice_debug_assign",
            "ice_debug_peak_read", "ice_debug_peak_mfma", "ice_last_error"]
 
 
@@ -64,6 +64,10 @@ def lib() -> C.CDLL:
         L.ice_attend.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32, C.c_void_p, C.c_void_p]
         L.ice_select_attend.argtypes = [C.c_void_p, C.c_void_p, C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p,
                                         C.c_void_p]
+        L.ice_attend_resident.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32, C.c_void_p, C.c_void_p,
+                                          C.c_int32, C.c_void_p, C.c_void_p]
+        L.ice_select_attend_resident.argtypes = [C.c_void_p, C.c_void_p, C.c_int32, C.c_void_p, C.c_void_p, C.c_int32,
+                                                 C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]
         L.ice_select_hier.argtypes = [C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p,
                                       C.c_void_p, C.c_void_p, C.c_void_p]
         L.ice_export_index.argtypes = [C.c_void_p, C.POINTER(IceIndexView)]
@@ -147,6 +151,18 @@ def ice_attend(idx, q, page_ids, n_selected, n_ids_per_unit, out, stream=None) -
 def ice_select_attend(idx, q, token_budget, page_ids, n_selected, out, stream=None) -> None:
     _check(lib().ice_select_attend(idx, _ptr(q), token_budget, _ptr(page_ids), _ptr(n_selected), _ptr(out),
                                    _stream(stream)))
+
+
+def ice_attend_resident(idx, q, page_ids, n_selected, n_ids_per_unit, resident_k, resident_v, n_resident, out,
+                        stream=None) -> None:
+    _check(lib().ice_attend_resident(idx, _ptr(q), _ptr(page_ids), _ptr(n_selected), n_ids_per_unit, _ptr(resident_k),
+                                     _ptr(resident_v), n_resident, _ptr(out), _stream(stream)))
+
+
+def ice_select_attend_resident(idx, q, token_budget, resident_k, resident_v, n_resident, page_ids, n_selected, out,
+                               stream=None) -> None:
+    _check(lib().ice_select_attend_resident(idx, _ptr(q), token_budget, _ptr(resident_k), _ptr(resident_v), n_resident,
+                                            _ptr(page_ids), _ptr(n_selected), _ptr(out), _stream(stream)))
 
 
 def ice_select_hier(idx, q, token_budget, n_probe, page_ids, n_selected, scores=None, clusters=None, out=None,
@@ -269,6 +285,25 @@ class IceIndex:
             out = torch.empty((self.batch, self.n_kv_heads * self.group_size, 128), dtype=torch.float32,
                               device=self.device)
         ice_select_attend(self.handle, q, token_budget, ids, n_sel, out, stream)
+        return ids, n_sel, out
+
+    def attend_resident(self, q, ids, n_sel, resident_k, resident_v, out=None, stream=None):
+        """resident_k, resident_v: [B, H_kv, n_resident, 128], attended together with the listed pages."""
+        if out is None:
+            out = torch.empty((self.batch, self.n_kv_heads * self.group_size, 128), dtype=torch.float32,
+                              device=self.device)
+        ice_attend_resident(self.handle, q, ids, n_sel, int(ids.shape[-1]), resident_k, resident_v,
+                            int(resident_k.shape[-2]), out, stream)
+        return out
+
+    def select_attend_resident(self, q, token_budget, resident_k, resident_v, ids=None, n_sel=None, out=None, stream=None):
+        if ids is None:
+            ids, n_sel = self._sel_buffers(token_budget)
+        if out is None:
+            out = torch.empty((self.batch, self.n_kv_heads * self.group_size, 128), dtype=torch.float32,
+                              device=self.device)
+        ice_select_attend_resident(self.handle, q, token_budget, resident_k, resident_v, int(resident_k.shape[-2]), ids,
+                                   n_sel, out, stream)
         return ids, n_sel, out
 
     def select_hier(self, q, token_budget, n_probe, attend=True, ids=None, n_sel=None, out=None, stream=None):

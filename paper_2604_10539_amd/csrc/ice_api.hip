@@ -231,31 +231,49 @@ ice_status_t ice_select(ice_index_t *ix, const void *q, int32_t budget, int32_t 
                         void *stream) {
     if (ice_status_t st = check_select(ix, q, budget, ids, n_sel, "ice_select")) return st;
     launch_decode_step(ix->dev, static_cast<const bf16_t *>(q), budget / ix->dev.s, ix->n_tokens / ix->dev.s + ix->dev.C,
-                       ids, n_sel, scores, nullptr,
-                       static_cast<hipStream_t>(stream));
+                       ids, n_sel, scores, nullptr, nullptr, 0, nullptr, static_cast<hipStream_t>(stream));
     return device_status("ice_select");
 }
 
-ice_status_t ice_attend(ice_index_t *ix, const void *q, const int32_t *ids, const int32_t *n_sel, int32_t P, float *out,
-                        void *stream) {
+static ice_status_t check_resident(const void *rk, const void *rv, int32_t n_res) {
+    if (n_res < 0 || n_res > (1 << 20)) return fail(ICE_ERR_SHAPE, "n_resident %d is outside [0, 2^20]", n_res);
+    if (n_res > 0 && (!rk || !rv || !aligned16(rk) || !aligned16(rv)))
+        return fail(ICE_ERR_INVALID_ARG, "resident_k or resident_v is null or misaligned");
+    return ICE_OK;
+}
+
+ice_status_t ice_attend_resident(ice_index_t *ix, const void *q, const int32_t *ids, const int32_t *n_sel, int32_t P,
+                                 const void *rk, const void *rv, int32_t n_res, float *out, void *stream) {
     if (!ix) return fail(ICE_ERR_INVALID_ARG, "index is null");
     if (!ix->built) return fail(ICE_ERR_STATE, "ice_attend before ice_build_index");
     if (!q || !aligned16(q)) return fail(ICE_ERR_INVALID_ARG, "q is null or misaligned");
     if (!ids || !n_sel || !out) return fail(ICE_ERR_INVALID_ARG, "page_ids, n_selected or out is null");
     if (P < 1) return fail(ICE_ERR_SHAPE, "n_ids_per_unit must be >= 1");
-    launch_attend(ix->dev, static_cast<const bf16_t *>(q), ids, n_sel, P, out, static_cast<hipStream_t>(stream));
+    if (ice_status_t st = check_resident(rk, rv, n_res)) return st;
+    launch_attend(ix->dev, static_cast<const bf16_t *>(q), ids, n_sel, P, static_cast<const bf16_t *>(rk),
+                  static_cast<const bf16_t *>(rv), n_res, out, static_cast<hipStream_t>(stream));
     return device_status("ice_attend");
+}
+
+ice_status_t ice_attend(ice_index_t *ix, const void *q, const int32_t *ids, const int32_t *n_sel, int32_t P, float *out,
+                        void *stream) {
+    return ice_attend_resident(ix, q, ids, n_sel, P, nullptr, nullptr, 0, out, stream);
+}
+
+ice_status_t ice_select_attend_resident(ice_index_t *ix, const void *q, int32_t budget, const void *rk, const void *rv,
+                                        int32_t n_res, int32_t *ids, int32_t *n_sel, float *out, void *stream) {
+    if (ice_status_t st = check_select(ix, q, budget, ids, n_sel, "ice_select_attend")) return st;
+    if (!out) return fail(ICE_ERR_INVALID_ARG, "out is null");
+    if (ice_status_t st = check_resident(rk, rv, n_res)) return st;
+    launch_decode_step(ix->dev, static_cast<const bf16_t *>(q), budget / ix->dev.s, ix->n_tokens / ix->dev.s + ix->dev.C, ids,
+                       n_sel, nullptr, static_cast<const bf16_t *>(rk), static_cast<const bf16_t *>(rv), n_res, out,
+                       static_cast<hipStream_t>(stream));
+    return device_status("ice_select_attend");
 }
 
 ice_status_t ice_select_attend(ice_index_t *ix, const void *q, int32_t budget, int32_t *ids, int32_t *n_sel, float *out,
                                void *stream) {
-    if (ice_status_t st = check_select(ix, q, budget, ids, n_sel, "ice_select_attend")) return st;
-    if (!out) return fail(ICE_ERR_INVALID_ARG, "out is null");
-    const int P = budget / ix->dev.s;
-    hipStream_t s = static_cast<hipStream_t>(stream);
-    launch_decode_step(ix->dev, static_cast<const bf16_t *>(q), P, ix->n_tokens / ix->dev.s + ix->dev.C, ids, n_sel, nullptr,
-                       out, s);
-    return device_status("ice_select_attend");
+    return ice_select_attend_resident(ix, q, budget, nullptr, nullptr, 0, ids, n_sel, out, stream);
 }
 
 ice_status_t ice_select_hier(ice_index_t *ix, const void *q, int32_t budget, int32_t n_probe, int32_t *ids, int32_t *n_sel,

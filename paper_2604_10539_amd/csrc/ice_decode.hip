@@ -122,23 +122,30 @@ void launch_insert(const Dev &d, const bf16_t *k, const bf16_t *v, int m, int cu
 }
 
 // ------------------------------------------------------------------------------------------------
-template <int G, int NW>
+template <int G, int NW, bool RES>
 __global__ __launch_bounds__(NW * 64) void attend_kernel(Dev d, const bf16_t *__restrict__ q,
                                                           const int *__restrict__ ids, const int *__restrict__ n_sel,
-                                                          int P, float *__restrict__ out) {
+                                                          int P, Resident res, float *__restrict__ out) {
     extern __shared__ __align__(16) char smem[];
     const int u = blockIdx.x;
     bf16x8 qa[4];
     load_query_operand<G>(q, u, threadIdx.x & 63, qa, nullptr);
     const int *list = ids + (size_t)u * P;
-    attend_pages<G, NW>(d, u, qa, [=](int x) { return list[x]; }, min(n_sel[u], P), out, (float *)smem, [] {});
+    attend_pages<G, NW, RES>(d, u, qa, [=](int x) { return list[x]; }, min(n_sel[u], P), res, out, (float *)smem, [] {});
 }
 
-void launch_attend(const Dev &d, const bf16_t *q, const int *ids, const int *n_sel, int P, float *out,
-                   hipStream_t st) {
-#define ICE_ATTEND(g, nw)                                                                              \
-    hipLaunchKernelGGL((attend_kernel<g, nw>), dim3(d.U), dim3(nw * 64), sizeof(float) * attend_scratch_floats(g, nw), st, d, \
-                       q, ids, n_sel, P, out)
+void launch_attend(const Dev &d, const bf16_t *q, const int *ids, const int *n_sel, int P, const bf16_t *res_k,
+                   const bf16_t *res_v, int n_res, float *out, hipStream_t st) {
+    const Resident res = {res_k, res_v, n_res};
+#define ICE_ATTEND(g, nw)                                                                                                  \
+    do {                                                                                                                   \
+        if (n_res > 0)                                                                                                     \
+            hipLaunchKernelGGL((attend_kernel<g, nw, true>), dim3(d.U), dim3(nw * 64),                                     \
+                               sizeof(float) * attend_scratch_floats(g, nw), st, d, q, ids, n_sel, P, res, out);           \
+        else                                                                                                               \
+            hipLaunchKernelGGL((attend_kernel<g, nw, false>), dim3(d.U), dim3(nw * 64),                                    \
+                               sizeof(float) * attend_scratch_floats(g, nw), st, d, q, ids, n_sel, P, res, out);           \
+    } while (0)
     switch (d.G) {
         case 1: ICE_ATTEND(1, 16); break;
         case 2: ICE_ATTEND(2, 16); break;
@@ -169,10 +176,10 @@ void launch_attend(const Dev &d, const bf16_t *q, const int *ids, const int *n_s
 // order.
 //
 // Phase C, same workgroup: attention over the winners (attend_pages), ids never leave the chip.
-template <int G, int NW, int EMAX>
+template <int G, int NW, int EMAX, bool RES>
 __global__ __launch_bounds__(NW * 64) void decode_step_kernel(Dev d, const bf16_t *__restrict__ q, int P, int chunks, int np_hint,
                                                                int lds_scores_off, int *__restrict__ ids_out, int *__restrict__ n_sel_out,
-                                                               float *__restrict__ scores_out, float *__restrict__ out) {
+                                                               float *__restrict__ scores_out, Resident res, float *__restrict__ out) {
     constexpr int NT = NW * 64;
     extern __shared__ __align__(16) char smem[];
     __shared__ int sh_last, sh_M, sh_M2, sh_W;
@@ -514,8 +521,8 @@ __global__ __launch_bounds__(NW * 64) void decode_step_kernel(Dev d, const bf16_
     };
     if (out) {
         ICE_STAMP(6);
-        attend_pages<G, NW>(d, u, qa, [=](int x) { return all_pages ? x : (int)(0xFFFFFFFFu - (uint32_t)sel_comp[x]); }, k,
-                            out, (float *)region, order_ids);
+        attend_pages<G, NW, RES>(d, u, qa, [=](int x) { return all_pages ? x : (int)(0xFFFFFFFFu - (uint32_t)sel_comp[x]); }, k,
+                                 res, out, (float *)region, order_ids);
         ICE_STAMP(7);
     } else {
         order_ids();
@@ -536,7 +543,7 @@ namespace ice {
 size_t decode_step_lds_bytes(const Dev &d, int P);
 
 void launch_decode_step(const Dev &d, const bf16_t *q, int P, int np_hint, int *ids, int *n_sel, float *scores_out,
-                        float *out, hipStream_t st) {
+                        const bf16_t *res_k, const bf16_t *res_v, int n_res, float *out, hipStream_t st) {
     const int NW = d.G == 8 ? 8 : 16;
     // a workgroup pass scores 16*NW pages per load round; few units -> split each unit over many
     // workgroups (one round each), many units -> one workgroup per unit and no cross-workgroup step
@@ -549,17 +556,24 @@ void launch_decode_step(const Dev &d, const bf16_t *q, int P, int np_hint, int *
     const size_t lds = decode_step_lds_bytes(d, P);
     const int grid = round_up(d.U, 8) * chunks;
     const int E = (d.max_pages + NW * 64 - 1) / (NW * 64);
+    const Resident res = {res_k, res_v, out ? n_res : 0};
+#define ICE_STEP_R(g, nw, e, r)                                                                                     \
+    do {                                                                                                            \
+        (void)hipFuncSetAttribute((const void *)decode_step_kernel<g, nw, e, r>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds); \
+        hipLaunchKernelGGL((decode_step_kernel<g, nw, e, r>), dim3(grid), dim3(nw * 64), lds, st, d, q, P, chunks, np_hint, \
+                           (int)(lds - (size_t)d.max_pages * 4), ids, n_sel, scores_out, res, out);                 \
+    } while (0)
 #define ICE_STEP(g, nw, e)                                                                                          \
     do {                                                                                                            \
-        (void)hipFuncSetAttribute((const void *)decode_step_kernel<g, nw, e>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds); \
-        hipLaunchKernelGGL((decode_step_kernel<g, nw, e>), dim3(grid), dim3(nw * 64), lds, st, d, q, P, chunks, np_hint, \
-                           (int)(lds - (size_t)d.max_pages * 4), ids, n_sel, scores_out, out);                                                                 \
+        if (res.n > 0) ICE_STEP_R(g, nw, e, true);                                                                  \
+        else ICE_STEP_R(g, nw, e, false);                                                                           \
     } while (0)
     if (d.G == 8) { if (E <= 8) ICE_STEP(8, 8, 8); else ICE_STEP(8, 8, 32); }
     else if (d.G == 4) { if (E <= 4) ICE_STEP(4, 16, 4); else ICE_STEP(4, 16, 16); }
     else if (d.G == 2) { if (E <= 4) ICE_STEP(2, 16, 4); else ICE_STEP(2, 16, 16); }
     else { if (E <= 4) ICE_STEP(1, 16, 4); else ICE_STEP(1, 16, 16); }
 #undef ICE_STEP
+#undef ICE_STEP_R
 }
 
 // largest page count and page budget launch_decode_step can serve (register-resident keys, LDS lists)

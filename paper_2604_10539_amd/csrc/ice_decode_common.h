@@ -59,8 +59,16 @@ __device__ inline void load_query_operand(const bf16_t *q, int u, int lane, bf16
     if (sumsq) *sumsq = nn;
 }
 
-template <int G, int NW, typename PageOf, typename Aside>
-__device__ inline void attend_pages(const Dev &d, int u, const bf16x8 (&qa)[4], PageOf page_of, int ns,
+// Resident tokens: a dense run of n tokens per unit (k, v bf16 [U][n][d]) that is always attended
+// on top of the listed pages (the sink tokens and the recent window of Alg. 1 / App. A); handled
+// as ceil(n / 16) further 16-token blocks, dealt to the waves after the pages.
+struct Resident {
+    const bf16_t *k, *v;
+    int n;
+};
+
+template <int G, int NW, bool RES, typename PageOf, typename Aside>
+__device__ inline void attend_pages(const Dev &d, int u, const bf16x8 (&qa)[4], PageOf page_of, int ns, Resident res,
                                     float *__restrict__ out, float *red, Aside aside) {
     constexpr int GR = (G + 3) / 4;  // row groups that hold logits and outputs
     float(*wacc)[G][kD] = (float(*)[G][kD])red;                   // [NW][G][128]
@@ -80,12 +88,81 @@ __device__ inline void attend_pages(const Dev &d, int u, const bf16x8 (&qa)[4], 
 #pragma unroll
     for (int j = 0; j < 8; ++j) acc[j] = f32x4{0.f, 0.f, 0.f, 0.f};
     bool first = true;
+    // one 16-token block whose key pieces (kb) and value rows (vt) are in registers; tokens from
+    // nvalid on are masked
+    auto block = [&](int b0, int fill, uint4 (&kb)[4], uint4 (&vt)[4]) {
+        f32x4 z = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int ks = 0; ks < 4; ++ks)
+            z = __builtin_amdgcn_mfma_f32_16x16x32_bf16(qa[ks], __builtin_bit_cast(bf16x8, kb[ks]), z, 0, 0, 0);
+#ifdef ICE_PROF_ATTEND
+        if (threadIdx.x == 0 && u == 0 && z[0] != 12345.f) ice_prof[9] = wall_clock64();
+#endif
+        const bool tok_ok = b0 + ch < fill;  // this lane's logits belong to token b0 + ch
+        float pw[4], alpha[4];
+#pragma unroll
+        for (int v = 0; v < 4; ++v) {
+            const float zz = tok_ok ? z[v] * scale : -INFINITY;
+            float mx = zz;
+            mx = fmaxf(mx, dpp_f32<0xB1>(mx));
+            mx = fmaxf(mx, dpp_f32<0x4E>(mx));
+            mx = fmaxf(mx, dpp_f32<0x141>(mx));
+            mx = fmaxf(mx, dpp_f32<0x140>(mx));   // block maximum of head 4g+v on all 16 lanes of the row
+            const float mn = fmaxf(m[v], mx);     // finite: every live page has at least one token
+            alpha[v] = __expf(m[v] - mn);
+            pw[v] = __expf(zz - mn);
+            l[v] = l[v] * alpha[v] + pw[v];
+            m[v] = mn;
+        }
+        if (g < GR) *(float4 *)(px + ch * 8 + 4 * g) = make_float4(pw[0], pw[1], pw[2], pw[3]);
+        __builtin_amdgcn_wave_barrier();
+        // A operand: lane (g, h) holds p[head h][token 4i+g], i = 0..3, as hi + lo bf16 terms
+        float pa[4];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const float t = px[(4 * i + g) * 8 + (ch & 7)];  // (unconditional read, then select: no branch)
+            pa[i] = ch < G ? t : 0.f;
+        }
+        uint32_t hi[4], lo[4];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            hi[i] = __float_as_uint(pa[i]) & 0xFFFF0000u;
+            lo[i] = __float_as_uint(pa[i] - __uint_as_float(hi[i]));
+        }
+        const v2u ahi = {__builtin_amdgcn_perm(hi[1], hi[0], 0x07060302u), __builtin_amdgcn_perm(hi[3], hi[2], 0x07060302u)};
+        const v2u alo = {__builtin_amdgcn_perm(lo[1], lo[0], 0x07060302u), __builtin_amdgcn_perm(lo[3], lo[2], 0x07060302u)};
+        if (!first) {  // rescale what earlier blocks left (same lanes hold the factors)
+#pragma unroll
+            for (int j = 0; j < 8; ++j)
+#pragma unroll
+                for (int v = 0; v < 4; ++v) acc[j][v] *= alpha[v];
+        }
+        first = false;
+        if (fill - b0 < 16) {  // a partly filled block: rows past the end must not reach the matrix core
+#pragma unroll
+            for (int t = 0; t < 4; ++t)
+                if (b0 + 4 * t + g >= fill) vt[t] = make_uint4(0, 0, 0, 0);
+        }
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+            // column tile j: dims {8c + j}; contraction slot 4g+i = token 4i+g
+            const uint32_t sel = (j & 1) ? 0x07060302u : 0x05040100u;
+            const uint32_t w0 = j < 2 ? vt[0].x : j < 4 ? vt[0].y : j < 6 ? vt[0].z : vt[0].w;
+            const uint32_t w1 = j < 2 ? vt[1].x : j < 4 ? vt[1].y : j < 6 ? vt[1].z : vt[1].w;
+            const uint32_t w2 = j < 2 ? vt[2].x : j < 4 ? vt[2].y : j < 6 ? vt[2].z : vt[2].w;
+            const uint32_t w3 = j < 2 ? vt[3].x : j < 4 ? vt[3].y : j < 6 ? vt[3].z : vt[3].w;
+            const v2u bv = {__builtin_amdgcn_perm(w1, w0, sel), __builtin_amdgcn_perm(w3, w2, sel)};
+            acc[j] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(__builtin_bit_cast(bf16x4s, ahi), __builtin_bit_cast(bf16x4s, bv), acc[j], 0, 0, 0);
+            acc[j] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(__builtin_bit_cast(bf16x4s, alo), __builtin_bit_cast(bf16x4s, bv), acc[j], 0, 0, 0);
+        }
+        __builtin_amdgcn_wave_barrier();  // the next block overwrites px
+    };
+    // the first 16-token block of a page is fetched before its fill count is known (one fewer
+    // dependent round trip); slots >= fill may hold stale bytes and are masked after the load
     for (int x = wave; x < ns; x += NW) {
         const int p = page_of(x);
         if ((unsigned)p >= (unsigned)d.max_pages) continue;  // not a page id: ignored
         const size_t pg = (size_t)u * d.max_pages + p;
-        // the first 16-token block is fetched before the fill count is known (one fewer dependent
-        // round trip); slots >= fill may hold stale bytes and are masked after the load
         uint4 kb[4], vt[4];
 #pragma unroll
         for (int t = 0; t < 4; ++t) {
@@ -102,71 +179,24 @@ __device__ inline void attend_pages(const Dev &d, int u, const bf16x8 (&qa)[4], 
                     vt[t] = ((const uint4 *)(d.Vp + (pg * s + b0 + 4 * t + g) * kD))[ch];
                 }
             }
-            f32x4 z = {0.f, 0.f, 0.f, 0.f};
+            block(b0, fill, kb, vt);
+        }
+    }
+    if constexpr (RES) {
+        // resident tokens, 16 per block, dealt to the waves where the pages left off; rows past the
+        // end of the run are not there to be read
+        const int nrb = (res.n + 15) >> 4;
+        for (int j = ((wave - ns) % NW + NW) % NW; j < nrb; j += NW) {
+            const int r0 = 16 * j, fill = min(16, res.n - r0);
+            const bf16_t *ktile = res.k + ((size_t)u * res.n + r0) * kD;
+            const bf16_t *vtile = res.v + ((size_t)u * res.n + r0) * kD;
+            uint4 kb[4], vt[4];
 #pragma unroll
-            for (int ks = 0; ks < 4; ++ks)
-                z = __builtin_amdgcn_mfma_f32_16x16x32_bf16(qa[ks], __builtin_bit_cast(bf16x8, kb[ks]), z, 0, 0, 0);
-#ifdef ICE_PROF_ATTEND
-            if (threadIdx.x == 0 && u == 0 && z[0] != 12345.f) ice_prof[9] = wall_clock64();
-#endif
-            const bool tok_ok = b0 + ch < fill;  // this lane's logits belong to token b0 + ch
-            float pw[4], alpha[4];
-#pragma unroll
-            for (int v = 0; v < 4; ++v) {
-                const float zz = tok_ok ? z[v] * scale : -INFINITY;
-                float mx = zz;
-                mx = fmaxf(mx, dpp_f32<0xB1>(mx));
-                mx = fmaxf(mx, dpp_f32<0x4E>(mx));
-                mx = fmaxf(mx, dpp_f32<0x141>(mx));
-                mx = fmaxf(mx, dpp_f32<0x140>(mx));   // block maximum of head 4g+v on all 16 lanes of the row
-                const float mn = fmaxf(m[v], mx);     // finite: every live page has at least one token
-                alpha[v] = __expf(m[v] - mn);
-                pw[v] = __expf(zz - mn);
-                l[v] = l[v] * alpha[v] + pw[v];
-                m[v] = mn;
+            for (int t = 0; t < 4; ++t) {
+                kb[t] = ch < fill ? ((const uint4 *)(ktile + (size_t)ch * kD))[t * 4 + g] : make_uint4(0, 0, 0, 0);
+                vt[t] = 4 * t + g < fill ? ((const uint4 *)(vtile + (size_t)(4 * t + g) * kD))[ch] : make_uint4(0, 0, 0, 0);
             }
-            if (g < GR) *(float4 *)(px + ch * 8 + 4 * g) = make_float4(pw[0], pw[1], pw[2], pw[3]);
-            __builtin_amdgcn_wave_barrier();
-            // A operand: lane (g, h) holds p[head h][token 4i+g], i = 0..3, as hi + lo bf16 terms
-            float pa[4];
-#pragma unroll
-            for (int i = 0; i < 4; ++i) {
-                const float t = px[(4 * i + g) * 8 + (ch & 7)];  // (unconditional read, then select: no branch)
-                pa[i] = ch < G ? t : 0.f;
-            }
-            uint32_t hi[4], lo[4];
-#pragma unroll
-            for (int i = 0; i < 4; ++i) {
-                hi[i] = __float_as_uint(pa[i]) & 0xFFFF0000u;
-                lo[i] = __float_as_uint(pa[i] - __uint_as_float(hi[i]));
-            }
-            const v2u ahi = {__builtin_amdgcn_perm(hi[1], hi[0], 0x07060302u), __builtin_amdgcn_perm(hi[3], hi[2], 0x07060302u)};
-            const v2u alo = {__builtin_amdgcn_perm(lo[1], lo[0], 0x07060302u), __builtin_amdgcn_perm(lo[3], lo[2], 0x07060302u)};
-            if (!first) {  // rescale what earlier blocks left (same lanes hold the factors)
-#pragma unroll
-                for (int j = 0; j < 8; ++j)
-#pragma unroll
-                    for (int v = 0; v < 4; ++v) acc[j][v] *= alpha[v];
-            }
-            first = false;
-            if (fill - b0 < 16) {  // a partly filled block: rows past the end must not reach the matrix core
-#pragma unroll
-                for (int t = 0; t < 4; ++t)
-                    if (b0 + 4 * t + g >= fill) vt[t] = make_uint4(0, 0, 0, 0);
-            }
-#pragma unroll
-            for (int j = 0; j < 8; ++j) {
-                // column tile j: dims {8c + j}; contraction slot 4g+i = token 4i+g
-                const uint32_t sel = (j & 1) ? 0x07060302u : 0x05040100u;
-                const uint32_t w0 = j < 2 ? vt[0].x : j < 4 ? vt[0].y : j < 6 ? vt[0].z : vt[0].w;
-                const uint32_t w1 = j < 2 ? vt[1].x : j < 4 ? vt[1].y : j < 6 ? vt[1].z : vt[1].w;
-                const uint32_t w2 = j < 2 ? vt[2].x : j < 4 ? vt[2].y : j < 6 ? vt[2].z : vt[2].w;
-                const uint32_t w3 = j < 2 ? vt[3].x : j < 4 ? vt[3].y : j < 6 ? vt[3].z : vt[3].w;
-                const v2u bv = {__builtin_amdgcn_perm(w1, w0, sel), __builtin_amdgcn_perm(w3, w2, sel)};
-                acc[j] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(__builtin_bit_cast(bf16x4s, ahi), __builtin_bit_cast(bf16x4s, bv), acc[j], 0, 0, 0);
-                acc[j] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(__builtin_bit_cast(bf16x4s, alo), __builtin_bit_cast(bf16x4s, bv), acc[j], 0, 0, 0);
-            }
-            __builtin_amdgcn_wave_barrier();  // the next block overwrites px
+            block(0, fill, kb, vt);
         }
     }
     ICE_STAMP(10);

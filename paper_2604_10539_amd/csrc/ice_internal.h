@@ -66,8 +66,9 @@ void launch_refresh_centroids(const Dev &d, int cur, hipStream_t st);
 void launch_insert(const Dev &d, const bf16_t *k, const bf16_t *v, int m, int cur, hipStream_t st);
 // scores + top-P selection (+ attention when out != nullptr) in one launch
 // np_hint: host-side upper bound of the live pages per unit (tokens / page_size + clusters)
+// res_k, res_v: n_res resident tokens per unit (bf16 [U][n_res][d]) attended on top of the pages; n_res may be 0
 void launch_decode_step(const Dev &d, const bf16_t *q, int P, int np_hint, int *ids, int *n_sel, float *scores_out,
-                        float *out, hipStream_t st);
+                        const bf16_t *res_k, const bf16_t *res_v, int n_res, float *out, hipStream_t st);
 // two-stage selection (clusters, then their pages) (+ attention when out != nullptr) in one launch
 void launch_decode_hier(const Dev &d, const bf16_t *q, int cur, int P, int n_probe, int np_hint, int *ids, int *n_sel,
                         float *scores_out, int *clusters_out, float *out, hipStream_t st);
@@ -75,8 +76,8 @@ int decode_hier_max_pages(int G);
 size_t decode_hier_lds_bytes(const Dev &d, int P, int n_probe);
 int decode_step_max_pages(int G);
 size_t decode_step_lds_bytes(const Dev &d, int P);
-void launch_attend(const Dev &d, const bf16_t *q, const int *ids, const int *n_sel, int P, float *out,
-                   hipStream_t st);
+void launch_attend(const Dev &d, const bf16_t *q, const int *ids, const int *n_sel, int P, const bf16_t *res_k,
+                   const bf16_t *res_v, int n_res, float *out, hipStream_t st);
 
 // ---- device helpers ----
 __device__ inline float bf16_lo(uint32_t w) { return __uint_as_float(w << 16); }

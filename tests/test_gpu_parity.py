@@ -600,3 +600,45 @@ def test_insert_batch_equals_one_by_one(kw, m):
     with pytest.raises(IceError) as e:
         ix_b.insert_batch(up(kb[:, :, :1]), up(vb[:, :, :1]))
     assert e.value.status == b.ICE_ERR_CAPACITY
+
+
+# ----------------------------------------------------------------------------------------- resident tokens
+@pytest.mark.gpu
+@pytest.mark.parametrize("kw,budget,n_res", [
+    (dict(n_tokens=4096, n_clusters=32, n_kv_heads=2, n_components=32), 256, 37),
+    (dict(n_tokens=4096, n_clusters=32, n_kv_heads=2, n_components=32), 256, 1),
+    (dict(n_tokens=5003, n_clusters=100, n_kv_heads=3, n_components=40, group_size=1), 64, 16),
+    (dict(n_tokens=2500, n_clusters=24, n_kv_heads=2, page_size=32, group_size=2), 256, 300),
+    (dict(n_tokens=2600, n_clusters=40, n_kv_heads=1, page_size=64, group_size=8), 640, 129),
+])
+def test_attention_with_resident_tokens(kw, budget, n_res):
+    """Sink / window tokens kept by the caller as a dense run join the pages in one softmax."""
+    w = datagen.small(**kw)
+    ix, K, V, _ = _mk(w, T=2)
+    ix.build_index(up(K), up(V))
+    q = datagen.queries(w)
+    rng = np.random.default_rng(n_res)
+    # resident keys near the query's cluster centres so that they carry real weight
+    rk = narrow((widen(K[:, :n_res]) + 0.1 * rng.standard_normal((ix.U, n_res, D))).astype(np.float32))
+    rv = narrow(rng.standard_normal((ix.U, n_res, D)).astype(np.float32))
+    rk4, rv4 = rk.reshape(w.batch, w.n_kv_heads, n_res, D), rv.reshape(w.batch, w.n_kv_heads, n_res, D)
+    ids, n_sel, _ = ix.select(up(q), budget)
+    out = ix.attend_resident(up(q), ids, n_sel, up(rk4), up(rv4))
+    o = oracle_from_export(ix, export_np(ix))
+    P = ids.shape[-1]
+    ref = o.attend_resident(q, down(ids).reshape(ix.U, P), down(n_sel).reshape(ix.U), rk, rv)
+    err = np.abs(down(out).reshape(ref.shape) - ref).max()
+    plain = o.attend(q, down(ids).reshape(ix.U, P), down(n_sel).reshape(ix.U))
+    print("[resident] max abs err %.3g (resident tokens move the output by %.3g)" % (err, np.abs(ref - plain).max()))
+    assert err <= ATTN_TOL and err <= ATTN_EXPECTED
+    assert np.abs(ref - plain).max() > 1e-3                       # the case is not vacuous
+    # fused call: same ids as the plain selection, same output up to summation order
+    ids2, ns2, out2 = ix.select_attend_resident(up(q), budget, up(rk4), up(rv4))
+    assert torch.equal(ids2, ids) and torch.equal(ns2, n_sel) and (out2 - out).abs().max().item() <= 5e-6
+    # only resident tokens
+    out0 = ix.attend_resident(up(q), ids, torch.zeros_like(n_sel), up(rk4), up(rv4))
+    ref0 = o.attend_resident(q, down(ids).reshape(ix.U, P), np.zeros(ix.U, np.int32), rk, rv)
+    assert np.abs(down(out0).reshape(ref0.shape) - ref0).max() <= ATTN_EXPECTED
+    # none: exactly the plain calls
+    empty = torch.empty((w.batch, w.n_kv_heads, 0, D), dtype=torch.int16, device="cuda")
+    assert torch.equal(ix.attend_resident(up(q), ids, n_sel, empty, empty), ix.attend(up(q), ids, n_sel))

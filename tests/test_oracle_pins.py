@@ -581,6 +581,40 @@ def test_hier_select_sees_pages_appended_by_insertion():
     assert ids[0, :n_sel[0]].tolist() == mine
 
 
+# ----------------------------------------------------------------------------- attention with resident tokens
+def test_attend_resident_is_dense_attention_over_the_union():
+    """Selected pages + resident (sink / window) tokens: one softmax over their union, checked
+    against torch's scaled_dot_product_attention on the gathered rows; with no resident tokens it is
+    attend(); with no pages it is dense attention over the resident tokens alone."""
+    import torch
+    w = datagen.small(n_tokens=800, n_clusters=10, n_kv_heads=2)
+    ix, K, V = _built(w)
+    rng = np.random.default_rng(77)
+    q = datagen.queries(w).reshape(ix.U, w.group_size, D)
+    ids, n_sel, _, _ = ix.select(q, 64)
+    n_res = 37
+    rk, rv = _rand_bits(rng, (ix.U, n_res, D)), _rand_bits(rng, (ix.U, n_res, D))
+    out = ix.attend_resident(q, ids, n_sel, rk, rv)
+    for u in range(ix.U):
+        rows_k, rows_v = [], []
+        for p in ids[u, :n_sel[u]]:
+            f = ix.page_fill[u, p]
+            rows_k.append(ix.Kp[u, p, :f])
+            rows_v.append(ix.Vp[u, p, :f])
+        kk = torch.from_numpy(widen(np.concatenate(rows_k + [rk[u]])).astype(np.float64))
+        vv = torch.from_numpy(widen(np.concatenate(rows_v + [rv[u]])).astype(np.float64))
+        qq = torch.from_numpy(widen(q[u]).astype(np.float64))
+        ref = torch.nn.functional.scaled_dot_product_attention(qq[None], kk[None], vv[None])[0].numpy()
+        np.testing.assert_allclose(out[u], ref, rtol=0, atol=2e-6)
+    none_k = np.zeros((ix.U, 0, D), np.uint16)
+    assert np.array_equal(ix.attend_resident(q, ids, n_sel, none_k, none_k), ix.attend(q, ids, n_sel))
+    only = ix.attend_resident(q, ids, np.zeros_like(n_sel), rk, rv)
+    for u in range(ix.U):
+        z = widen(q[u]).astype(np.float64) @ widen(rk[u]).astype(np.float64).T / math.sqrt(D)
+        p = np.exp(z - z.max(1, keepdims=True))
+        np.testing.assert_allclose(only[u], (p / p.sum(1, keepdims=True)) @ widen(rv[u]).astype(np.float64), atol=2e-6)
+
+
 # ----------------------------------------------------------------------------- change detector
 def test_oracle_still_gives_the_stored_small_case():
     """tests/golden/oracle_small_case.json was written by tests/golden/write_oracle_fixture.py from the
