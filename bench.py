@@ -68,7 +68,7 @@ def main():
               "take disjoint heads or sequences); run with --gpus 1", file=sys.stderr)
         sys.exit(2)
     import torch
-    from paper_2604_10539_amd import IceIndex, ice_debug_peak_mfma, ice_debug_peak_read, ice_select, ice_select_hier
+    from paper_2604_10539_amd import IceIndex, ice_debug_peak_mfma, ice_debug_peak_read, ice_select, ice_select_attend_resident, ice_select_hier
 
     assert torch.cuda.is_available(), "bench.py needs the GPU"
     dev = torch.device("cuda:0")
@@ -246,6 +246,26 @@ def main():
                             for u in range(L * H)]))
     out_diff = float((out_h - out_b).abs().max().item())
 
+    # ---------------------------------------------------------------- with resident (sink + window) tokens
+    # 16 sink + 256 window tokens per (layer, KV head) kept densely by the caller join the softmax
+    n_res = 16 + 256
+    g_res = torch.Generator(device="cpu").manual_seed(7)
+    res_k = torch.randn((L, H, n_res, D), generator=g_res).to(torch.bfloat16).to(dev)
+    res_v = torch.randn((L, H, n_res, D), generator=g_res).to(torch.bfloat16).to(dev)
+    out_r = torch.empty_like(out_b)
+    resident = lambda ix: ice_select_attend_resident(ix.handle, q, budget, res_k, res_v, n_res, ids_h, ns_h, out_r)
+    for i in range(max(args.warmup, 3)):
+        resident(rot[i % 3])
+    torch.cuda.synchronize()
+    e0, e1 = ev(), ev()
+    e0.record(st)
+    for i in range(args.steps):
+        resident(rot[i % 3])
+    e1.record(st)
+    torch.cuda.synchronize()
+    ms_res = e0.elapsed_time(e1) / args.steps
+    bytes_res = bytes_step + L * H * n_res * D * 2 * 2
+
     # ---------------------------------------------------------------- one layer at a time, HIP graph of 32
     ids_l = [torch.empty((1, H, P), dtype=torch.int32, device=dev) for _ in range(L)]
     ns_l = [torch.empty((1, H), dtype=torch.int32, device=dev) for _ in range(L)]
@@ -390,6 +410,10 @@ def main():
                          "recall_of_flat_selection": recall, "attend_max_abs_diff_vs_flat": out_diff,
                          "how": "ice_select_hier (centroids -> kept clusters -> their pages -> top-P -> attention, one "
                                 "launch), same rotation over three index copies as the headline"},
+        "with_resident_tokens": {"n_resident": n_res, "us_per_step": ms_res * 1e3, "us_per_layer_step": ms_res * 1e3 / L,
+                                 "algorithmic_bytes_per_step": bytes_res, "GBps": bytes_res / (ms_res * 1e-3) / 1e9,
+                                 "how": "ice_select_attend_resident: 16 sink + 256 window tokens per unit in the same "
+                                        "softmax as the selected pages; flat selection, same rotation"},
         "sequential": {"us_per_layer_step": ms_seq * 1e3 / L, "GBps": bytes_step / (ms_seq * 1e-3) / 1e9,
                        "how": "HIP graph replay of 32 one-layer select+attend calls (8 units each)",
                        "bitwise_equal_to_batched": same},
