@@ -142,7 +142,6 @@ def main():
         ix.build_index(K, V)
         rot.append(ix)
     torch.cuda.synchronize()
-    del K, V
 
     # ---------------------------------------------------------------- algorithmic bytes of one step
     # select: every live representative row (256 B) + the G query rows + the ids written;
@@ -265,6 +264,14 @@ def main():
     torch.cuda.synchronize()
     ms_res = e0.elapsed_time(e1) / args.steps
     bytes_res = bytes_step + L * H * n_res * D * 2 * 2
+
+    # ---------------------------------------------------------------- a selection reused by the following layers
+    # the anchor layer's pages -> token positions -> attention over (here: the same) dense cache by position
+    pos_t, n_tok_t = batched.selected_tokens(ids_b, ns_b)
+    out_t = torch.empty_like(out_b)
+    ms_tok = timed(lambda: batched.attend_tokens(q, K, V, pos_t, n_tok_t, out_t), args.steps, args.warmup, cold)
+    tok_diff = float((out_t - out_b).abs().max().item())
+    bytes_tok = float(n_tok_t.sum().item()) * D * 2 * 2 + float(n_tok_t.sum().item()) * 4 + L * H * G * D * 4
 
     # ---------------------------------------------------------------- one layer at a time, HIP graph of 32
     ids_l = [torch.empty((1, H, P), dtype=torch.int32, device=dev) for _ in range(L)]
@@ -414,6 +421,13 @@ def main():
                                  "algorithmic_bytes_per_step": bytes_res, "GBps": bytes_res / (ms_res * 1e-3) / 1e9,
                                  "how": "ice_select_attend_resident: 16 sink + 256 window tokens per unit in the same "
                                         "softmax as the selected pages; flat selection, same rotation"},
+        "reuse_by_position": {"attend_tokens_us_per_step": ms_tok * 1e3, "algorithmic_bytes_per_step": bytes_tok,
+                              "GBps": bytes_tok / (ms_tok * 1e-3) / 1e9,
+                              "us_per_layer_step_anchor_every_3_layers": (ms_flush + 2 * ms_tok) * 1e3 / 3 / L,
+                              "max_abs_diff_vs_page_attention": tok_diff,
+                              "how": "ice_selected_tokens once, then ice_attend_tokens over the dense cache by token "
+                                     "position (flush + one event pair per step, like flush_per_step); two of three "
+                                     "layers skip the selection"},
         "sequential": {"us_per_layer_step": ms_seq * 1e3 / L, "GBps": bytes_step / (ms_seq * 1e-3) / 1e9,
                        "how": "HIP graph replay of 32 one-layer select+attend calls (8 units each)",
                        "bitwise_equal_to_batched": same},

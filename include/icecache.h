@@ -166,6 +166,24 @@ ice_status_t ice_select_attend_resident(ice_index_t *idx, const void *q, int32_t
                                         const void *resident_k, const void *resident_v, int32_t n_resident,
                                         int32_t *page_ids, int32_t *n_selected, float *out, void *stream);
 
+/* Reuse of a selection by other layers (App. B: the layers after an anchor layer attend to the
+ * tokens the anchor layer selected).  Page ids are local to one layer's index, token positions
+ * are not:
+ *   ice_selected_tokens  writes the sequence positions of the tokens of the listed pages, in list
+ *       and slot order: token_pos int32 [B, H_kv, n_ids_per_unit * page_size] padded with -1,
+ *       n_tok int32 [B, H_kv].  n_ids_per_unit in [1, 1024].
+ *   ice_attend_tokens    attention (Eq. 1) of q over rows token_pos[b, h, 0 .. n_tok[b, h]) of a
+ *       dense cache K, V bf16 [B, H_kv, n_rows, d] (any layer's; caller-owned device memory);
+ *       max_tok = length of a unit's position list.  The index only supplies B, H_kv and the group
+ *       size.  Positions must lie in [0, n_rows) (others are clamped into the cache, not skipped).
+ * With the cache the index was built from, ice_attend_tokens over ice_selected_tokens' positions
+ * gives ice_attend's result over those pages. */
+ice_status_t ice_selected_tokens(ice_index_t *idx, const int32_t *page_ids, const int32_t *n_selected,
+                                 int32_t n_ids_per_unit, int32_t *token_pos, int32_t *n_tok, void *stream);
+ice_status_t ice_attend_tokens(ice_index_t *idx, const void *q, const void *K, const void *V, int32_t n_rows,
+                               const int32_t *token_pos, const int32_t *n_tok, int32_t max_tok, float *out,
+                               void *stream);
+
 /* Hierarchical selection: the two-level form of the paper's top-down search (Sec. 4.3, Alg. 3).
  * Stage 1 ranks the n_clusters centroids (as stored, rounded to bf16) by the same normalised GQA
  * score as pages and keeps the min(n_probe, n_clusters) best, lower id first on ties; every

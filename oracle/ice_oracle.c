@@ -570,3 +570,56 @@ void orc_attend_resident(const orc_state_t *st, const uint16_t *q, const int32_t
         free(vr);
     }
 }
+
+/* ---- reuse of a selection by other layers (App. B) ---------------------------------------------
+ * Page ids are local to one layer's index; the sequence positions of the tokens in those pages
+ * are not.  orc_selected_tokens lists them (list order, then slot order; -1 padded to P * s);
+ * orc_attend_tokens attends over rows pos[u][0 .. n_tok[u]) of a dense cache K, V [U][n_rows][d]:
+ * one softmax over exactly those rows (Eq. 1 with the mask on them). */
+void orc_selected_tokens(const orc_state_t *st, const int32_t *ids, const int32_t *n_sel, int P,
+                         int32_t *pos, int32_t *n_tok) {
+    const int s = st->s, MP = st->max_pages;
+    for (int u = 0; u < st->U; ++u) {
+        int m = 0;
+        for (int x = 0; x < n_sel[u]; ++x) {
+            size_t pg = (size_t)u * MP + ids[(size_t)u * P + x];
+            for (int t = 0; t < st->page_fill[pg]; ++t) pos[(size_t)u * P * s + m++] = st->page_pos[pg * s + t];
+        }
+        n_tok[u] = m;
+        for (; m < P * s; ++m) pos[(size_t)u * P * s + m] = -1;
+    }
+}
+
+void orc_attend_tokens(const uint16_t *q, const uint16_t *K, const uint16_t *V, int U, int G, int d, int n_rows,
+                       const int32_t *pos, const int32_t *n_tok, int cap, float *out) {
+    const double scale = 1.0 / sqrt((double)d);
+#pragma omp parallel for schedule(dynamic, 1)
+    for (int u = 0; u < U; ++u) {
+        const int m = n_tok[u];
+        double *z = (double *)malloc(sizeof(double) * (size_t)(m > 0 ? m : 1));
+        for (int h = 0; h < G; ++h) {
+            const uint16_t *qh = q + ((size_t)u * G + h) * d;
+            double zmax = -INFINITY;
+            for (int i = 0; i < m; ++i) {
+                const uint16_t *kr = K + ((size_t)u * n_rows + pos[(size_t)u * cap + i]) * d;
+                double dot = 0.0;
+                for (int j = 0; j < d; ++j) dot += (double)bf16_to_f32(qh[j]) * (double)bf16_to_f32(kr[j]);
+                z[i] = dot * scale;
+                if (z[i] > zmax) zmax = z[i];
+            }
+            double den = 0.0;
+            for (int i = 0; i < m; ++i) {
+                z[i] = exp(z[i] - zmax);
+                den += z[i];
+            }
+            float *oh = out + ((size_t)u * G + h) * d;
+            for (int j = 0; j < d; ++j) {
+                double o = 0.0;
+                for (int i = 0; i < m; ++i)
+                    o += z[i] * (double)bf16_to_f32(V[((size_t)u * n_rows + pos[(size_t)u * cap + i]) * d + j]);
+                oh[j] = (m > 0) ? (float)(o / den) : 0.0f;
+            }
+        }
+        free(z);
+    }
+}

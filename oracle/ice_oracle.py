@@ -238,3 +238,27 @@ class OracleIndex:
         lib().orc_attend_resident(C.byref(st), _p(q), _p(ids), _p(n_sel), C.c_int(P), _p(rk), _p(rv),
                                   C.c_int(n_res), _p(out))
         return out
+
+    def selected_tokens(self, ids: np.ndarray, n_sel: np.ndarray):
+        """Sequence positions of the tokens of the listed pages: (pos int32 [U, P*s] -1 padded, n_tok [U])."""
+        P = ids.shape[-1]
+        ids = self._units(ids, (P,), np.int32)
+        n_sel = self._units(n_sel, (), np.int32)
+        pos = np.full((self.U, P * self.s), -1, np.int32)
+        n_tok = np.zeros(self.U, np.int32)
+        st = self._state()
+        lib().orc_selected_tokens(C.byref(st), _p(ids), _p(n_sel), C.c_int(P), _p(pos), _p(n_tok))
+        return pos, n_tok
+
+
+def attend_tokens(q: np.ndarray, K: np.ndarray, V: np.ndarray, pos: np.ndarray, n_tok: np.ndarray) -> np.ndarray:
+    """Attention over rows pos[u, :n_tok[u]] of a dense cache.  q uint16 [U, G, d]; K, V uint16
+    [U, n_rows, d]; pos int32 [U, cap].  -> float32 [U, G, d]."""
+    U, G, d = q.shape
+    n_rows, cap = K.shape[1], pos.shape[1]
+    q, K, V = (np.ascontiguousarray(a, np.uint16) for a in (q, K, V))
+    pos, n_tok = np.ascontiguousarray(pos, np.int32), np.ascontiguousarray(n_tok, np.int32)
+    out = np.zeros((U, G, d), np.float32)
+    lib().orc_attend_tokens(_p(q), _p(K), _p(V), C.c_int(U), C.c_int(G), C.c_int(d), C.c_int(n_rows), _p(pos), _p(n_tok),
+                            C.c_int(cap), _p(out))
+    return out

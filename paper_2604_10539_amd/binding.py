@@ -17,7 +17,7 @@ ICE_OK, ICE_ERR_INVALID_ARG, ICE_ERR_SHAPE, ICE_ERR_STATE, ICE_ERR_CAPACITY, ICE
 STATUS_NAMES = ["ICE_OK", "ICE_ERR_INVALID_ARG", "ICE_ERR_SHAPE", "ICE_ERR_STATE", "ICE_ERR_CAPACITY",
                 "ICE_ERR_UNSUPPORTED", "ICE_ERR_DEVICE"]
 SYMBOLS = ["ice_workspace_bytes", "ice_create", "ice_destroy", "ice_build_index", "ice_insert", "ice_insert_batch", "ice_select",
-           "ice_attend", "ice_select_attend", "ice_attend_resident", "ice_select_attend_resident", "ice_select_hier", "ice_export_index", "ice_import_index", "ice_debug_assign",
+           "ice_attend", "ice_select_attend", "ice_attend_resident", "ice_select_attend_resident", "ice_selected_tokens", "ice_attend_tokens", "ice_select_hier", "ice_export_index", "ice_import_index", "ice_debug_assign",
            "ice_debug_peak_read", "ice_debug_peak_mfma", "ice_last_error"]
 
 
@@ -68,6 +68,9 @@ def lib() -> C.CDLL:
                                           C.c_int32, C.c_void_p, C.c_void_p]
         L.ice_select_attend_resident.argtypes = [C.c_void_p, C.c_void_p, C.c_int32, C.c_void_p, C.c_void_p, C.c_int32,
                                                  C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]
+        L.ice_selected_tokens.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p]
+        L.ice_attend_tokens.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32, C.c_void_p, C.c_void_p,
+                                        C.c_int32, C.c_void_p, C.c_void_p]
         L.ice_select_hier.argtypes = [C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p,
                                       C.c_void_p, C.c_void_p, C.c_void_p]
         L.ice_export_index.argtypes = [C.c_void_p, C.POINTER(IceIndexView)]
@@ -163,6 +166,16 @@ def ice_select_attend_resident(idx, q, token_budget, resident_k, resident_v, n_r
                                stream=None) -> None:
     _check(lib().ice_select_attend_resident(idx, _ptr(q), token_budget, _ptr(resident_k), _ptr(resident_v), n_resident,
                                             _ptr(page_ids), _ptr(n_selected), _ptr(out), _stream(stream)))
+
+
+def ice_selected_tokens(idx, page_ids, n_selected, n_ids_per_unit, token_pos, n_tok, stream=None) -> None:
+    _check(lib().ice_selected_tokens(idx, _ptr(page_ids), _ptr(n_selected), n_ids_per_unit, _ptr(token_pos), _ptr(n_tok),
+                                     _stream(stream)))
+
+
+def ice_attend_tokens(idx, q, K, V, n_rows, token_pos, n_tok, max_tok, out, stream=None) -> None:
+    _check(lib().ice_attend_tokens(idx, _ptr(q), _ptr(K), _ptr(V), n_rows, _ptr(token_pos), _ptr(n_tok), max_tok,
+                                   _ptr(out), _stream(stream)))
 
 
 def ice_select_hier(idx, q, token_budget, n_probe, page_ids, n_selected, scores=None, clusters=None, out=None,
@@ -305,6 +318,22 @@ class IceIndex:
         ice_select_attend_resident(self.handle, q, token_budget, resident_k, resident_v, int(resident_k.shape[-2]), ids,
                                    n_sel, out, stream)
         return ids, n_sel, out
+
+    def selected_tokens(self, ids, n_sel, stream=None):
+        """Sequence positions of the tokens of the listed pages: (token_pos [B, H_kv, P * page_size], n_tok)."""
+        P = int(ids.shape[-1])
+        pos = torch.empty((self.batch, self.n_kv_heads, P * self.page_size), dtype=torch.int32, device=self.device)
+        n_tok = torch.empty((self.batch, self.n_kv_heads), dtype=torch.int32, device=self.device)
+        ice_selected_tokens(self.handle, ids, n_sel, P, pos, n_tok, stream)
+        return pos, n_tok
+
+    def attend_tokens(self, q, K, V, token_pos, n_tok, out=None, stream=None):
+        """Attention over rows token_pos[..., :n_tok] of a dense cache K, V [B, H_kv, n_rows, 128]."""
+        if out is None:
+            out = torch.empty((self.batch, self.n_kv_heads * self.group_size, 128), dtype=torch.float32,
+                              device=self.device)
+        ice_attend_tokens(self.handle, q, K, V, int(K.shape[-2]), token_pos, n_tok, int(token_pos.shape[-1]), out, stream)
+        return out
 
     def select_hier(self, q, token_budget, n_probe, attend=True, ids=None, n_sel=None, out=None, stream=None):
         """Two-stage selection (+ attention in the same launch when attend is true).

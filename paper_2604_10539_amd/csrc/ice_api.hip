@@ -250,8 +250,8 @@ ice_status_t ice_attend_resident(ice_index_t *ix, const void *q, const int32_t *
     if (!ids || !n_sel || !out) return fail(ICE_ERR_INVALID_ARG, "page_ids, n_selected or out is null");
     if (P < 1) return fail(ICE_ERR_SHAPE, "n_ids_per_unit must be >= 1");
     if (ice_status_t st = check_resident(rk, rv, n_res)) return st;
-    launch_attend(ix->dev, static_cast<const bf16_t *>(q), ids, n_sel, P, static_cast<const bf16_t *>(rk),
-                  static_cast<const bf16_t *>(rv), n_res, out, static_cast<hipStream_t>(stream));
+    const Resident res = {static_cast<const bf16_t *>(rk), static_cast<const bf16_t *>(rv), n_res, nullptr, nullptr, 0};
+    launch_attend(ix->dev, static_cast<const bf16_t *>(q), ids, n_sel, P, res, out, static_cast<hipStream_t>(stream));
     return device_status("ice_attend");
 }
 
@@ -274,6 +274,29 @@ ice_status_t ice_select_attend_resident(ice_index_t *ix, const void *q, int32_t 
 ice_status_t ice_select_attend(ice_index_t *ix, const void *q, int32_t budget, int32_t *ids, int32_t *n_sel, float *out,
                                void *stream) {
     return ice_select_attend_resident(ix, q, budget, nullptr, nullptr, 0, ids, n_sel, out, stream);
+}
+
+ice_status_t ice_selected_tokens(ice_index_t *ix, const int32_t *ids, const int32_t *n_sel, int32_t P, int32_t *pos,
+                                 int32_t *n_tok, void *stream) {
+    if (!ix) return fail(ICE_ERR_INVALID_ARG, "index is null");
+    if (!ix->built) return fail(ICE_ERR_STATE, "ice_selected_tokens before ice_build_index");
+    if (!ids || !n_sel || !pos || !n_tok) return fail(ICE_ERR_INVALID_ARG, "a pointer is null");
+    if (P < 1 || P > 1024) return fail(ICE_ERR_SHAPE, "n_ids_per_unit %d is outside [1, 1024]", P);
+    launch_selected_tokens(ix->dev, ids, n_sel, P, pos, n_tok, static_cast<hipStream_t>(stream));
+    return device_status("ice_selected_tokens");
+}
+
+ice_status_t ice_attend_tokens(ice_index_t *ix, const void *q, const void *K, const void *V, int32_t n_rows,
+                               const int32_t *pos, const int32_t *n_tok, int32_t max_tok, float *out, void *stream) {
+    if (!ix) return fail(ICE_ERR_INVALID_ARG, "index is null");
+    if (!ix->laid_out) return fail(ICE_ERR_STATE, "ice_attend_tokens before ice_build_index or ice_import_index");
+    if (!q || !aligned16(q) || !K || !V || !aligned16(K) || !aligned16(V))
+        return fail(ICE_ERR_INVALID_ARG, "q, K or V is null or misaligned");
+    if (!pos || !n_tok || !out) return fail(ICE_ERR_INVALID_ARG, "token_pos, n_tok or out is null");
+    if (n_rows < 1 || max_tok < 1) return fail(ICE_ERR_SHAPE, "n_rows and max_tok must be >= 1");
+    const Resident res = {static_cast<const bf16_t *>(K), static_cast<const bf16_t *>(V), max_tok, pos, n_tok, n_rows};
+    launch_attend(ix->dev, static_cast<const bf16_t *>(q), nullptr, nullptr, 1, res, out, static_cast<hipStream_t>(stream));
+    return device_status("ice_attend_tokens");
 }
 
 ice_status_t ice_select_hier(ice_index_t *ix, const void *q, int32_t budget, int32_t n_probe, int32_t *ids, int32_t *n_sel,

@@ -131,12 +131,48 @@ __global__ __launch_bounds__(NW * 64) void attend_kernel(Dev d, const bf16_t *__
     bf16x8 qa[4];
     load_query_operand<G>(q, u, threadIdx.x & 63, qa, nullptr);
     const int *list = ids + (size_t)u * P;
-    attend_pages<G, NW, RES>(d, u, qa, [=](int x) { return list[x]; }, min(n_sel[u], P), res, out, (float *)smem, [] {});
+    const int ns = ids ? min(n_sel[u], P) : 0;  // (no page list: resident tokens only)
+    attend_pages<G, NW, RES>(d, u, qa, [=](int x) { return list[x]; }, ns, res, out, (float *)smem, [] {});
 }
 
-void launch_attend(const Dev &d, const bf16_t *q, const int *ids, const int *n_sel, int P, const bf16_t *res_k,
-                   const bf16_t *res_v, int n_res, float *out, hipStream_t st) {
-    const Resident res = {res_k, res_v, n_res};
+// the token positions of the listed pages, in list and slot order, padded with -1
+__global__ void selected_tokens_kernel(Dev d, const int *__restrict__ ids, const int *__restrict__ n_sel, int P,
+                                       int *__restrict__ pos_out, int *__restrict__ n_tok_out) {
+    const int u = blockIdx.x, s = d.s;
+    __shared__ int base[1025];
+    const int ns = min(n_sel[u], P);
+    if (threadIdx.x == 0) {
+        int acc = 0;
+        for (int x = 0; x < ns; ++x) {
+            base[x] = acc;
+            const int p = ids[(size_t)u * P + x];
+            acc += (unsigned)p < (unsigned)d.max_pages ? d.page_fill[(size_t)u * d.max_pages + p] : 0;
+        }
+        base[ns] = acc;
+        n_tok_out[u] = acc;
+    }
+    __syncthreads();
+    const int tot = base[ns];
+    for (int i = threadIdx.x; i < P * s; i += blockDim.x) pos_out[(size_t)u * P * s + i] = -1;
+    __syncthreads();
+    for (int i = threadIdx.x; i < ns * s; i += blockDim.x) {
+        const int x = i / s, t = i % s, p = ids[(size_t)u * P + x];
+        if ((unsigned)p >= (unsigned)d.max_pages) continue;
+        const size_t pg = (size_t)u * d.max_pages + p;
+        if (t < d.page_fill[pg]) pos_out[(size_t)u * P * s + base[x] + t] = d.page_pos[pg * s + t];
+    }
+    (void)tot;
+}
+
+void launch_selected_tokens(const Dev &d, const int *ids, const int *n_sel, int P, int *pos_out, int *n_tok_out,
+                            hipStream_t st) {
+    hipLaunchKernelGGL(selected_tokens_kernel, dim3(d.U), dim3(256), 0, st, d, ids, n_sel, P, pos_out, n_tok_out);
+}
+
+void launch_attend(const Dev &d, const bf16_t *q, const int *ids, const int *n_sel, int P, const Resident &res_in,
+                   float *out, hipStream_t st) {
+    const Resident res = res_in;
+    const int n_res = res.n;
 #define ICE_ATTEND(g, nw)                                                                                                  \
     do {                                                                                                                   \
         if (n_res > 0)                                                                                                     \
@@ -556,7 +592,7 @@ void launch_decode_step(const Dev &d, const bf16_t *q, int P, int np_hint, int *
     const size_t lds = decode_step_lds_bytes(d, P);
     const int grid = round_up(d.U, 8) * chunks;
     const int E = (d.max_pages + NW * 64 - 1) / (NW * 64);
-    const Resident res = {res_k, res_v, out ? n_res : 0};
+    const Resident res = {res_k, res_v, out ? n_res : 0, nullptr, nullptr, 0};
 #define ICE_STEP_R(g, nw, e, r)                                                                                     \
     do {                                                                                                            \
         (void)hipFuncSetAttribute((const void *)decode_step_kernel<g, nw, e, r>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds); \

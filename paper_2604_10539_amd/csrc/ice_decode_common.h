@@ -59,14 +59,6 @@ __device__ inline void load_query_operand(const bf16_t *q, int u, int lane, bf16
     if (sumsq) *sumsq = nn;
 }
 
-// Resident tokens: a dense run of n tokens per unit (k, v bf16 [U][n][d]) that is always attended
-// on top of the listed pages (the sink tokens and the recent window of Alg. 1 / App. A); handled
-// as ceil(n / 16) further 16-token blocks, dealt to the waves after the pages.
-struct Resident {
-    const bf16_t *k, *v;
-    int n;
-};
-
 template <int G, int NW, bool RES, typename PageOf, typename Aside>
 __device__ inline void attend_pages(const Dev &d, int u, const bf16x8 (&qa)[4], PageOf page_of, int ns, Resident res,
                                     float *__restrict__ out, float *red, Aside aside) {
@@ -185,16 +177,31 @@ __device__ inline void attend_pages(const Dev &d, int u, const bf16x8 (&qa)[4], 
     if constexpr (RES) {
         // resident tokens, 16 per block, dealt to the waves where the pages left off; rows past the
         // end of the run are not there to be read
-        const int nrb = (res.n + 15) >> 4;
+        const int nres = res.pos ? min(res.cnt[u], res.n) : res.n;
+        const int nrb = (nres + 15) >> 4;
         for (int j = ((wave - ns) % NW + NW) % NW; j < nrb; j += NW) {
-            const int r0 = 16 * j, fill = min(16, res.n - r0);
-            const bf16_t *ktile = res.k + ((size_t)u * res.n + r0) * kD;
-            const bf16_t *vtile = res.v + ((size_t)u * res.n + r0) * kD;
+            const int r0 = 16 * j, fill = min(16, nres - r0);
             uint4 kb[4], vt[4];
+            if (!res.pos) {
+                const bf16_t *ktile = res.k + ((size_t)u * res.n + r0) * kD;
+                const bf16_t *vtile = res.v + ((size_t)u * res.n + r0) * kD;
 #pragma unroll
-            for (int t = 0; t < 4; ++t) {
-                kb[t] = ch < fill ? ((const uint4 *)(ktile + (size_t)ch * kD))[t * 4 + g] : make_uint4(0, 0, 0, 0);
-                vt[t] = 4 * t + g < fill ? ((const uint4 *)(vtile + (size_t)(4 * t + g) * kD))[ch] : make_uint4(0, 0, 0, 0);
+                for (int t = 0; t < 4; ++t) {
+                    kb[t] = ch < fill ? ((const uint4 *)(ktile + (size_t)ch * kD))[t * 4 + g] : make_uint4(0, 0, 0, 0);
+                    vt[t] = 4 * t + g < fill ? ((const uint4 *)(vtile + (size_t)(4 * t + g) * kD))[ch] : make_uint4(0, 0, 0, 0);
+                }
+            } else {
+                const int *pl = res.pos + (size_t)u * res.n + r0;
+                const int krow = ch < fill ? min(max(pl[ch], 0), res.rows - 1) : 0;
+                int vrow[4];
+#pragma unroll
+                for (int t = 0; t < 4; ++t) vrow[t] = 4 * t + g < fill ? min(max(pl[4 * t + g], 0), res.rows - 1) : 0;
+                const bf16_t *kbase = res.k + (size_t)u * res.rows * kD, *vbase = res.v + (size_t)u * res.rows * kD;
+#pragma unroll
+                for (int t = 0; t < 4; ++t) {
+                    kb[t] = ch < fill ? ((const uint4 *)(kbase + (size_t)krow * kD))[t * 4 + g] : make_uint4(0, 0, 0, 0);
+                    vt[t] = 4 * t + g < fill ? ((const uint4 *)(vbase + (size_t)vrow[t] * kD))[ch] : make_uint4(0, 0, 0, 0);
+                }
             }
             block(0, fill, kb, vt);
         }

@@ -419,7 +419,7 @@ __global__ __launch_bounds__(NW * 64) void decode_hier_kernel(Dev d, const bf16_
             if (sco) sco[pos] = ordered_f32((uint32_t)(mine >> 32));
         }
     };
-    if (out) attend_pages<G, NW, false>(d, u, qa, [=](int x) { return (int)(0xFFFFFFFFu - (uint32_t)sel2[x]); }, k, Resident{nullptr, nullptr, 0}, out, red, order_ids);
+    if (out) attend_pages<G, NW, false>(d, u, qa, [=](int x) { return (int)(0xFFFFFFFFu - (uint32_t)sel2[x]); }, k, Resident{nullptr, nullptr, 0, nullptr, nullptr, 0}, out, red, order_ids);
     else order_ids();
     ICE_HSTAMP(7);
 }

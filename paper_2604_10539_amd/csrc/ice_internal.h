@@ -76,8 +76,25 @@ int decode_hier_max_pages(int G);
 size_t decode_hier_lds_bytes(const Dev &d, int P, int n_probe);
 int decode_step_max_pages(int G);
 size_t decode_step_lds_bytes(const Dev &d, int P);
-void launch_attend(const Dev &d, const bf16_t *q, const int *ids, const int *n_sel, int P, const bf16_t *res_k,
-                   const bf16_t *res_v, int n_res, float *out, hipStream_t st);
+// Resident tokens: tokens that are always attended on top of the listed pages, handled as further
+// 16-token blocks dealt to the waves after the pages.  Two forms:
+//   dense     a run of n tokens per unit, k, v bf16 [U][n][d] (the sink tokens and the recent
+//             window of Alg. 1 / App. A), pos == nullptr;
+//   gathered  rows pos[u][0 .. cnt[u]) of a whole cache k, v bf16 [U][rows][d] (token positions
+//             chosen elsewhere, e.g. by another layer's selection, App. B); n is then the length of
+//             a unit's position list.  Positions outside [0, rows) are clamped into the cache.
+struct Resident {
+    const bf16_t *k, *v;
+    int n;
+    const int *pos;
+    const int *cnt;
+    int rows;
+};
+
+void launch_attend(const Dev &d, const bf16_t *q, const int *ids_or_null, const int *n_sel, int P, const Resident &res,
+                   float *out, hipStream_t st);
+void launch_selected_tokens(const Dev &d, const int *ids, const int *n_sel, int P, int *pos_out, int *n_tok_out,
+                            hipStream_t st);
 
 // ---- device helpers ----
 __device__ inline float bf16_lo(uint32_t w) { return __uint_as_float(w << 16); }

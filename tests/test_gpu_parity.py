@@ -642,3 +642,37 @@ def test_attention_with_resident_tokens(kw, budget, n_res):
     # none: exactly the plain calls
     empty = torch.empty((w.batch, w.n_kv_heads, 0, D), dtype=torch.int16, device="cuda")
     assert torch.equal(ix.attend_resident(up(q), ids, n_sel, empty, empty), ix.attend(up(q), ids, n_sel))
+
+
+# ----------------------------------------------------------------------------------------- selection reuse
+@pytest.mark.gpu
+@pytest.mark.parametrize("kw,budget", [
+    (dict(n_tokens=4096, n_clusters=32, n_kv_heads=2, n_components=32), 256),
+    (dict(n_tokens=5003, n_clusters=100, n_kv_heads=3, n_components=40, group_size=1), 64),
+    (dict(n_tokens=2600, n_clusters=40, n_kv_heads=1, page_size=64, group_size=8), 640),
+])
+def test_selection_reused_by_token_position(kw, budget):
+    """An anchor layer's selection, turned into token positions, drives attention over another
+    layer's dense cache; on the anchor layer's own cache it reproduces the page attention."""
+    w = datagen.small(**kw)
+    ix, K, V, _ = _mk(w, T=2)
+    ix.build_index(up(K), up(V))
+    q = datagen.queries(w)
+    ids, n_sel, _ = ix.select(up(q), budget)
+    pos, n_tok = ix.selected_tokens(ids, n_sel)
+    o = oracle_from_export(ix, export_np(ix))
+    P = ids.shape[-1]
+    opos, ont = o.selected_tokens(down(ids).reshape(ix.U, P), down(n_sel).reshape(ix.U))
+    assert np.array_equal(down(pos).reshape(opos.shape), opos) and np.array_equal(down(n_tok).reshape(-1), ont)
+    K4, V4 = K.reshape(w.batch, w.n_kv_heads, -1, D), V.reshape(w.batch, w.n_kv_heads, -1, D)
+    own = ix.attend_tokens(up(q), up(K4), up(V4), pos, n_tok)
+    by_page = ix.attend(up(q), ids, n_sel)
+    assert (own - by_page).abs().max().item() <= 5e-6
+    rng = np.random.default_rng(budget)
+    K2 = narrow((widen(K) + 0.2 * rng.standard_normal(K.shape)).astype(np.float32))
+    V2 = narrow(rng.standard_normal(V.shape).astype(np.float32))
+    other = ix.attend_tokens(up(q), up(K2.reshape(K4.shape)), up(V2.reshape(V4.shape)), pos, n_tok)
+    ref = orc.attend_tokens(q.reshape(ix.U, w.group_size, D), K2, V2, opos, ont)
+    err = np.abs(down(other).reshape(ref.shape) - ref).max()
+    print("[attend by position] max abs err %.3g" % err)
+    assert err <= ATTN_TOL and err <= ATTN_EXPECTED

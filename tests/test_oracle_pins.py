@@ -615,6 +615,35 @@ def test_attend_resident_is_dense_attention_over_the_union():
         np.testing.assert_allclose(only[u], (p / p.sum(1, keepdims=True)) @ widen(rv[u]).astype(np.float64), atol=2e-6)
 
 
+# ----------------------------------------------------------------------------- selection reuse by position
+def test_attending_by_token_position_equals_attending_by_page():
+    """The positions of the selected pages' tokens, applied to the cache the index was built from, give
+    the page attention (the tiles are bit copies of those rows); applied to ANOTHER cache they give
+    dense attention over those rows of that cache (checked with torch SDPA)."""
+    import torch
+    w = datagen.small(n_tokens=1100, n_clusters=14, n_kv_heads=2)
+    ix, K, V = _built(w)
+    q = datagen.queries(w).reshape(ix.U, w.group_size, D)
+    ids, n_sel, _, _ = ix.select(q, 96)
+    pos, n_tok = ix.selected_tokens(ids, n_sel)
+    for u in range(ix.U):
+        want = [int(t) for p in ids[u, :n_sel[u]] for t in ix.page_pos[u, p, :ix.page_fill[u, p]]]
+        assert pos[u, :n_tok[u]].tolist() == want and np.all(pos[u, n_tok[u]:] == -1)
+        assert len(set(want)) == len(want) and min(want) >= 0 and max(want) < w.n_tokens
+    same = orc.attend_tokens(q, K, V, pos, n_tok)
+    np.testing.assert_allclose(same, ix.attend(q, ids, n_sel), rtol=0, atol=1e-7)
+    rng = np.random.default_rng(3)
+    K2, V2 = _rand_bits(rng, K.shape), _rand_bits(rng, V.shape)          # "the next layer's" cache
+    other = orc.attend_tokens(q, K2, V2, pos, n_tok)
+    for u in range(ix.U):
+        rows = pos[u, :n_tok[u]]
+        ref = torch.nn.functional.scaled_dot_product_attention(
+            torch.from_numpy(widen(q[u]).astype(np.float64))[None],
+            torch.from_numpy(widen(K2[u, rows]).astype(np.float64))[None],
+            torch.from_numpy(widen(V2[u, rows]).astype(np.float64))[None])[0].numpy()
+        np.testing.assert_allclose(other[u], ref, rtol=0, atol=2e-6)
+
+
 # ----------------------------------------------------------------------------- change detector
 def test_oracle_still_gives_the_stored_small_case():
     """tests/golden/oracle_small_case.json was written by tests/golden/write_oracle_fixture.py from the
