@@ -676,3 +676,52 @@ def test_selection_reused_by_token_position(kw, budget):
     err = np.abs(down(other).reshape(ref.shape) - ref).max()
     print("[attend by position] max abs err %.3g" % err)
     assert err <= ATTN_TOL and err <= ATTN_EXPECTED
+
+
+# ----------------------------------------------------------------------------------------- random shapes
+@pytest.mark.gpu
+@pytest.mark.parametrize("seed", [11, 12, 13])
+def test_random_shapes_end_to_end(seed):
+    """Ten random configurations per seed (page size, group size, context, clusters, heads, budget,
+    probes, batched insertions, resident tokens): every decode entry point against the oracle."""
+    rng = np.random.default_rng(seed)
+    for case in range(10):
+        s = int(rng.choice([16, 16, 32, 64]))
+        G = int(rng.choice([1, 2, 4, 4, 8]))
+        n = int(rng.integers(s * 4, 9000))
+        C = int(rng.integers(1, min(300, n // 2)))
+        H = int(rng.integers(1, 4))
+        budget, n_probe = s * int(rng.integers(1, 70)), int(rng.integers(1, C + 3))
+        kw = dict(n_tokens=n, n_clusters=C, n_kv_heads=H, page_size=s, group_size=G,
+                  n_components=int(rng.integers(1, 64)), seed=int(rng.integers(1 << 30)))
+        print("case", case, kw, "budget", budget, "n_probe", n_probe, flush=True)
+        w = datagen.small(**kw)
+        ix, K, V, _ = _mk(w, T=2, extra=64)
+        ix.build_index(up(K), up(V))
+        m = int(rng.integers(0, 40))
+        if m:
+            stream = datagen.DecodeStream(w, seed=case)
+            toks = [stream.next()[:2] for _ in range(m)]
+            kb = np.stack([k.reshape(ix.U, D) for k, _ in toks], 1).reshape(1, H, m, D)
+            vb = np.stack([v.reshape(ix.U, D) for _, v in toks], 1).reshape(1, H, m, D)
+            ix.insert_batch(up(kb), up(vb))
+        q = datagen.queries(w)
+        o = oracle_from_export(ix, export_np(ix))
+        ids, n_sel, scores = ix.select(up(q), budget)
+        _compare_select(o, q, budget, down(ids), down(n_sel), down(scores))
+        ids2, ns2, out = ix.select_attend(up(q), budget)
+        assert torch.equal(ids2, ids) and torch.equal(ns2, n_sel)
+        P = ids.shape[-1]
+        idn, nsn = down(ids).reshape(ix.U, P), down(n_sel).reshape(ix.U)
+        assert np.abs(down(out).reshape(ix.U, G, D) - o.attend(q, idn, nsn)).max() <= ATTN_EXPECTED
+        _check_hier(ix, o, q, budget, n_probe, *ix.select_hier(up(q), budget, n_probe))
+        n_res = int(rng.integers(1, 200))
+        rk = narrow((2 * rng.standard_normal((ix.U, n_res, D))).astype(np.float32))
+        rv = narrow(rng.standard_normal((ix.U, n_res, D)).astype(np.float32))
+        _, _, outr = ix.select_attend_resident(up(q), budget, up(rk.reshape(1, H, n_res, D)), up(rv.reshape(1, H, n_res, D)))
+        assert np.abs(down(outr).reshape(ix.U, G, D) - o.attend_resident(q, idn, nsn, rk, rv)).max() <= ATTN_EXPECTED
+        pos, n_tok = ix.selected_tokens(ids, n_sel)
+        by_pos = ix.attend_tokens(up(q), up(K.reshape(1, H, n, D)), up(V.reshape(1, H, n, D)), pos, n_tok) if m == 0 else None
+        if by_pos is not None:   # (without insertions every indexed token is a row of the build cache)
+            assert (by_pos - ix.attend(up(q), ids, n_sel)).abs().max().item() <= 2e-5
+        ix.close()
