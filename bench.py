@@ -245,6 +245,39 @@ def main():
                             for u in range(L * H)]))
     out_diff = float((out_h - out_b).abs().max().item())
 
+    # ---------------------------------------------------------------- re-ranking by the best key (stage 3)
+    # the 4P best pages by representative (of the kept clusters) are re-scored by their best key
+    n_refine = 4 * P
+    refine = lambda ix: ice_select_hier(ix.handle, q, budget, n_probe, ids_h, ns_h, None, cl_h, out_h, n_refine=n_refine)
+    for i in range(max(args.warmup, 3)):
+        refine(rot[i % 3])
+    torch.cuda.synchronize()
+    e0, e1 = ev(), ev()
+    e0.record(st)
+    for i in range(args.steps):
+        refine(rot[i % 3])
+    e1.record(st)
+    torch.cuda.synchronize()
+    ms_refine = e0.elapsed_time(e1) / args.steps
+    refine(batched)
+    torch.cuda.synchronize()
+    idr_np, nsr_np = ids_h.cpu().numpy().reshape(L * H, P), ns_h.cpu().numpy().reshape(L * H)
+
+    # how many of the exact top-`budget` keys (by the group score q.k/||q||) the selected pages hold
+    def key_recall(ids_sel, ns_sel, units=range(0, L * H, 8)):
+        pos_all = exb["page_pos"]
+        hits = []
+        for u in units:
+            l, h = divmod(u, H)
+            qf = q[l].view(torch.bfloat16).float().reshape(H, G, D)[h]
+            sc = (K[l, h].view(torch.bfloat16).float() @ (qf / qf.norm(dim=1, keepdim=True)).T).max(1).values
+            top = set(torch.topk(sc, budget).indices.tolist())
+            toks = pos_all[u, torch.from_numpy(ids_sel[u, :ns_sel[u]]).long().to(dev)].reshape(-1)
+            hits.append(len(top & set(toks[toks >= 0].tolist())) / budget)
+        return float(np.mean(hits))
+    recall_keys = {"flat": key_recall(ids_np, ns_np), "hierarchical": key_recall(idh_np, nsh_np),
+                   "refined": key_recall(idr_np, nsr_np)}
+
     # ---------------------------------------------------------------- with resident (sink + window) tokens
     # 16 sink + 256 window tokens per (layer, KV head) kept densely by the caller join the softmax
     n_res = 16 + 256
@@ -417,6 +450,12 @@ def main():
                          "recall_of_flat_selection": recall, "attend_max_abs_diff_vs_flat": out_diff,
                          "how": "ice_select_hier (centroids -> kept clusters -> their pages -> top-P -> attention, one "
                                 "launch), same rotation over three index copies as the headline"},
+        "refined_by_best_key": {"n_probe": n_probe, "n_refine": n_refine, "us_per_step": ms_refine * 1e3,
+                                "us_per_layer_step": ms_refine * 1e3 / L,
+                                "top_key_recall": recall_keys,
+                                "how": "ice_select_hier with n_refine = 4P: the 4P best pages by representative are re-ranked "
+                                       "by their best key before the top P are attended; top_key_recall = share of the exact "
+                                       "top-256 keys (q.k/||q||, max over the group) held by the selected pages, 32 sampled units"},
         "with_resident_tokens": {"n_resident": n_res, "us_per_step": ms_res * 1e3, "us_per_layer_step": ms_res * 1e3 / L,
                                  "algorithmic_bytes_per_step": bytes_res, "GBps": bytes_res / (ms_res * 1e-3) / 1e9,
                                  "how": "ice_select_attend_resident: 16 sink + 256 window tokens per unit in the same "

@@ -190,14 +190,18 @@ ice_status_t ice_attend_tokens(ice_index_t *idx, const void *q, const void *K, c
  * cluster is eligible, one without pages contributes none.  Stage 2 ranks only the live pages of
  * the kept clusters and returns the best min(P, number of such pages), P = floor(budget / page_size),
  * ids ascending, padded with -1; with n_probe >= n_clusters the result is ice_select's.
+ * Stage 3, when n_refine > 0 (the paper ranks keys and loads the pages that hold them): stage 2 keeps
+ * min(n_refine, candidates) pages instead, each is re-scored by its best key (max over its tokens
+ * and the group's heads of q_h . k / ||q_h||), and the best min(P, kept) by that score, lower id
+ * first on ties, are returned; scores then holds these key scores.  n_refine must be 0 or >= P.
  *   q bf16 [B, H_q, d]; page_ids int32 [B, H_kv, P]; n_selected int32 [B, H_kv];
  *   scores_or_null fp32 [B, H_kv, P] (group scores of the returned pages);
  *   clusters_or_null int32 [B, H_kv, n_probe] (kept cluster ids ascending, -1 padded);
  *   out_or_null fp32 [B, H_q, d]: when given, attention over the returned pages (as ice_attend)
  *   runs in the same launch.
  * All device pointers, caller-owned; only enqueues.  Errors as ice_select, plus SHAPE for
- * n_probe < 1 and UNSUPPORTED when the candidate lists do not fit a CU's LDS. */
-ice_status_t ice_select_hier(ice_index_t *idx, const void *q, int32_t token_budget, int32_t n_probe,
+ * n_probe < 1 or 0 < n_refine < P, and UNSUPPORTED when the candidate lists do not fit a CU's LDS. */
+ice_status_t ice_select_hier(ice_index_t *idx, const void *q, int32_t token_budget, int32_t n_probe, int32_t n_refine,
                              int32_t *page_ids, int32_t *n_selected, float *scores_or_null,
                              int32_t *clusters_or_null, float *out_or_null, void *stream);
 

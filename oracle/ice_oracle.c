@@ -382,9 +382,14 @@ void orc_select(const orc_state_t *st, const uint16_t *q, int budget, int32_t *i
  * cluster was kept, exactly as orc_select ranks all pages, and returns the best
  * min(P, number of such pages), ids ascending, padded with -1.  With n_probe >= C every page is
  * a candidate and the result is orc_select's.
+ * Stage 3 (n_refine > 0; the paper ranks KEYS and then loads the pages that hold them, Alg. 3):
+ * only the min(n_refine, candidates) best pages of stage 2 stay; each is re-scored by its best
+ * key, max over its tokens and the group's heads of q_h . k / ||q_h|| (fp64 rounded once to
+ * fp32), and the best min(P, kept) by (that score descending, page id ascending) are returned;
+ * scores[] then holds these key scores.
  * clusters (may be NULL): [U][n_probe] kept cluster ids ascending, -1 padded.
  * Sc_all (may be NULL): [U][C] fp32 centroid scores. */
-void orc_select_hier(const orc_state_t *st, const uint16_t *q, int budget, int n_probe, int32_t *ids,
+void orc_select_hier(const orc_state_t *st, const uint16_t *q, int budget, int n_probe, int n_refine, int32_t *ids,
                      int32_t *n_sel, float *scores, int32_t *clusters, float *Sc_all) {
     const int d = st->d, G = st->G, MP = st->max_pages, C = st->C, P = budget / st->s;
     const int n_keep = n_probe < C ? n_probe : C;
@@ -447,6 +452,25 @@ void orc_select_hier(const orc_state_t *st, const uint16_t *q, int budget, int n
             ++nc;
         }
         qsort(sc, (size_t)nc, sizeof(scored_t), cmp_scored);
+        if (n_refine > 0) {
+            /* stage 3: the best pages by representative, re-scored by their best key */
+            if (nc > n_refine) nc = n_refine;
+            for (int x = 0; x < nc; ++x) {
+                const size_t pg = (size_t)u * MP + sc[x].id;
+                double best = -INFINITY;
+                for (int t = 0; t < st->page_fill[pg]; ++t)
+                    for (int h = 0; h < G; ++h) {
+                        double dot = 0.0;
+                        for (int j = 0; j < d; ++j)
+                            dot += (double)bf16_to_f32(q[((size_t)u * G + h) * d + j]) *
+                                   (double)bf16_to_f32(st->Kp[(pg * st->s + t) * d + j]);
+                        double sh = dot / qn[h];
+                        if (sh > best) best = sh;
+                    }
+                sc[x].s = (float)best;
+            }
+            qsort(sc, (size_t)nc, sizeof(scored_t), cmp_scored);
+        }
         int ns = nc < P ? nc : P;
         int32_t *out = ids + (size_t)u * P;
         for (int x = 0; x < ns; ++x) out[x] = sc[x].id;

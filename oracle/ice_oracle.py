@@ -195,9 +195,10 @@ class OracleIndex:
         lib().orc_select(C.byref(st), _p(q), C.c_int(token_budget), _p(ids), _p(n_sel), _p(scores), _p(S_all))
         return ids, n_sel, scores, S_all
 
-    def select_hier(self, q: np.ndarray, token_budget: int, n_probe: int):
-        """Two-stage selection: the n_probe best clusters by centroid score, then the best pages among
-        theirs.  -> (ids int32 [U,P], n_sel [U], scores [U,P], clusters int32 [U,n_probe] ascending
+    def select_hier(self, q: np.ndarray, token_budget: int, n_probe: int, n_refine: int = 0):
+        """Staged selection: the n_probe best clusters by centroid score, then the best pages among
+        theirs; with n_refine > 0 the n_refine best of those are re-ranked by their best key (needs the
+        K tiles).  -> (ids int32 [U,P], n_sel [U], scores [U,P], clusters int32 [U,n_probe] ascending
         -1 padded, Sc_all float32 [U,C])."""
         q = self._units(q, (self.G, self.d), np.uint16)
         P = token_budget // self.s
@@ -207,7 +208,7 @@ class OracleIndex:
         clusters = np.full((self.U, n_probe), -1, np.int32)
         Sc_all = np.zeros((self.U, self.C), np.float32)
         st = self._state()
-        lib().orc_select_hier(C.byref(st), _p(q), C.c_int(token_budget), C.c_int(n_probe), _p(ids), _p(n_sel),
+        lib().orc_select_hier(C.byref(st), _p(q), C.c_int(token_budget), C.c_int(n_probe), C.c_int(n_refine), _p(ids), _p(n_sel),
                               _p(scores), _p(clusters), _p(Sc_all))
         return ids, n_sel, scores, clusters, Sc_all
 

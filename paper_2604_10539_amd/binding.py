@@ -71,8 +71,8 @@ def lib() -> C.CDLL:
         L.ice_selected_tokens.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p]
         L.ice_attend_tokens.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32, C.c_void_p, C.c_void_p,
                                         C.c_int32, C.c_void_p, C.c_void_p]
-        L.ice_select_hier.argtypes = [C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p,
-                                      C.c_void_p, C.c_void_p, C.c_void_p]
+        L.ice_select_hier.argtypes = [C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.c_int32, C.c_void_p, C.c_void_p,
+                                      C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]
         L.ice_export_index.argtypes = [C.c_void_p, C.POINTER(IceIndexView)]
         L.ice_import_index.argtypes = [C.c_void_p, C.POINTER(IceIndexView), C.c_void_p]
         L.ice_debug_assign.argtypes = [C.c_void_p, C.c_void_p, C.c_int32, C.c_void_p, C.c_int32, C.c_void_p,
@@ -179,8 +179,8 @@ def ice_attend_tokens(idx, q, K, V, n_rows, token_pos, n_tok, max_tok, out, stre
 
 
 def ice_select_hier(idx, q, token_budget, n_probe, page_ids, n_selected, scores=None, clusters=None, out=None,
-                    stream=None) -> None:
-    _check(lib().ice_select_hier(idx, _ptr(q), token_budget, n_probe, _ptr(page_ids), _ptr(n_selected), _ptr(scores),
+                    stream=None, n_refine=0) -> None:
+    _check(lib().ice_select_hier(idx, _ptr(q), token_budget, n_probe, n_refine, _ptr(page_ids), _ptr(n_selected), _ptr(scores),
                                  _ptr(clusters), _ptr(out), _stream(stream)))
 
 
@@ -335,8 +335,9 @@ class IceIndex:
         ice_attend_tokens(self.handle, q, K, V, int(K.shape[-2]), token_pos, n_tok, int(token_pos.shape[-1]), out, stream)
         return out
 
-    def select_hier(self, q, token_budget, n_probe, attend=True, ids=None, n_sel=None, out=None, stream=None):
-        """Two-stage selection (+ attention in the same launch when attend is true).
+    def select_hier(self, q, token_budget, n_probe, attend=True, ids=None, n_sel=None, out=None, stream=None, n_refine=0):
+        """Staged selection (+ attention in the same launch when attend is true); n_refine > 0 re-ranks
+        the n_refine best pages by their best key.
         -> (ids, n_sel, scores, clusters, out or None)."""
         if ids is None:
             ids, n_sel = self._sel_buffers(token_budget)
@@ -347,7 +348,7 @@ class IceIndex:
             out = torch.empty((self.batch, self.n_kv_heads * self.group_size, 128), dtype=torch.float32,
                               device=self.device)
         ice_select_hier(self.handle, q, token_budget, n_probe, ids, n_sel, scores, clusters, out if attend else None,
-                        stream)
+                        stream, n_refine)
         return ids, n_sel, scores, clusters, (out if attend else None)
 
     def export(self):

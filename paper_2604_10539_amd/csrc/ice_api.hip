@@ -299,8 +299,8 @@ ice_status_t ice_attend_tokens(ice_index_t *ix, const void *q, const void *K, co
     return device_status("ice_attend_tokens");
 }
 
-ice_status_t ice_select_hier(ice_index_t *ix, const void *q, int32_t budget, int32_t n_probe, int32_t *ids, int32_t *n_sel,
-                             float *scores, int32_t *clusters, float *out, void *stream) {
+ice_status_t ice_select_hier(ice_index_t *ix, const void *q, int32_t budget, int32_t n_probe, int32_t n_refine, int32_t *ids,
+                             int32_t *n_sel, float *scores, int32_t *clusters, float *out, void *stream) {
     if (!ix) return fail(ICE_ERR_INVALID_ARG, "index is null");
     if (!ix->built) return fail(ICE_ERR_STATE, "ice_select_hier before ice_build_index");
     if (!q || !aligned16(q)) return fail(ICE_ERR_INVALID_ARG, "q is null or misaligned");
@@ -308,13 +308,16 @@ ice_status_t ice_select_hier(ice_index_t *ix, const void *q, int32_t budget, int
     if (budget < ix->dev.s) return fail(ICE_ERR_SHAPE, "token_budget %d is below page_size %d", budget, ix->dev.s);
     if (n_probe < 1) return fail(ICE_ERR_SHAPE, "n_probe must be >= 1");
     const int P = budget / ix->dev.s;
+    if (n_refine != 0 && n_refine < P)
+        return fail(ICE_ERR_SHAPE, "n_refine %d must be 0 (off) or at least the %d pages of the budget", n_refine, P);
+    if (n_refine > ix->dev.max_pages) n_refine = ix->dev.max_pages;
     if (ix->dev.max_pages > decode_hier_max_pages(ix->dev.G))
         return fail(ICE_ERR_UNSUPPORTED, "%d pages per unit exceed the selection kernel's limit of %d", ix->dev.max_pages,
                     decode_hier_max_pages(ix->dev.G));
-    if (decode_hier_lds_bytes(ix->dev, P, n_probe) > 160u * 1024u - 1024u)
-        return fail(ICE_ERR_UNSUPPORTED, "%d pages per unit, n_probe %d and token_budget %d need more LDS than a CU has",
-                    ix->dev.max_pages, n_probe, budget);
-    launch_decode_hier(ix->dev, static_cast<const bf16_t *>(q), ix->cur, P, n_probe, ix->n_tokens / ix->dev.s + ix->dev.C, ids,
+    if (decode_hier_lds_bytes(ix->dev, P, n_probe, n_refine) > 160u * 1024u - 1024u)
+        return fail(ICE_ERR_UNSUPPORTED, "%d pages per unit, n_probe %d, n_refine %d and token_budget %d need more LDS than a CU has",
+                    ix->dev.max_pages, n_probe, n_refine, budget);
+    launch_decode_hier(ix->dev, static_cast<const bf16_t *>(q), ix->cur, P, n_probe, n_refine, ix->n_tokens / ix->dev.s + ix->dev.C, ids,
                        n_sel, scores, clusters, out, static_cast<hipStream_t>(stream));
     return device_status("ice_select_hier");
 }

@@ -198,9 +198,9 @@ __host__ __device__ inline size_t align16(size_t x) { return (x + 15) & ~(size_t
 
 // LDS carve-up (bytes), shared by host and device
 struct HierLds {
-    size_t comp1, member, comp2, list, hist, sel1, sel2, red, total;
+    size_t comp1, member, comp2, list, hist, sel1, sel2, comp3, sel3, red, total;
 };
-__host__ __device__ inline HierLds hier_lds(int Cpad, int max_pages, int n_probe, int P, int G, int NW) {
+__host__ __device__ inline HierLds hier_lds(int Cpad, int max_pages, int n_probe, int n_refine, int P, int G, int NW) {
     HierLds L;
     size_t off = 0;
     L.comp1 = off;  off += align16((size_t)Cpad * 8);
@@ -209,14 +209,16 @@ __host__ __device__ inline HierLds hier_lds(int Cpad, int max_pages, int n_probe
     L.list = off;   off += (size_t)kListCap * 8;
     L.hist = off;   off += 2 * 272 * 4;
     L.sel1 = off;   off += align16((size_t)n_probe * 8);
-    L.sel2 = off;   off += align16((size_t)P * 8);
+    L.sel2 = off;   off += align16((size_t)(n_refine > P ? n_refine : P) * 8);
+    L.comp3 = off;  off += align16((size_t)n_refine * 8);
+    L.sel3 = off;   off += align16((size_t)P * 8);
     L.red = off;    off += align16(sizeof(float) * (size_t)attend_scratch_floats(G, NW));
     L.total = off;
     return L;
 }
 
 template <int G, int NW, int EMAX>
-__global__ __launch_bounds__(NW * 64) void decode_hier_kernel(Dev d, const bf16_t *__restrict__ q, int cur, int P, int n_probe, int np_hint,
+__global__ __launch_bounds__(NW * 64) void decode_hier_kernel(Dev d, const bf16_t *__restrict__ q, int cur, int P, int n_probe, int n_refine, int np_hint,
                                                                int *__restrict__ ids_out, int *__restrict__ n_sel_out,
                                                                float *__restrict__ scores_out, int *__restrict__ clusters_out,
                                                                float *__restrict__ out) {
@@ -226,7 +228,7 @@ __global__ __launch_bounds__(NW * 64) void decode_hier_kernel(Dev d, const bf16_
     __shared__ int sh_ncand;
     const int u = blockIdx.x, tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
     const int g = lane >> 4, ch = lane & 15;
-    const HierLds L = hier_lds(d.Cpad, d.max_pages, n_probe, P, G, NW);
+    const HierLds L = hier_lds(d.Cpad, d.max_pages, n_probe, n_refine, P, G, NW);
     u64 *comp1 = (u64 *)(smem + L.comp1);
     uint32_t *member = (uint32_t *)(smem + L.member);
     u64 *comp2 = (u64 *)(smem + L.comp2);
@@ -234,6 +236,8 @@ __global__ __launch_bounds__(NW * 64) void decode_hier_kernel(Dev d, const bf16_
     int *hist = (int *)(smem + L.hist);
     u64 *sel1 = (u64 *)(smem + L.sel1);
     u64 *sel2 = (u64 *)(smem + L.sel2);
+    u64 *comp3 = (u64 *)(smem + L.comp3);
+    u64 *sel3 = (u64 *)(smem + L.sel3);
     float *red = (float *)(smem + L.red);
 
     ICE_HSTAMP(0);
@@ -377,7 +381,9 @@ __global__ __launch_bounds__(NW * 64) void decode_hier_kernel(Dev d, const bf16_
     }
     __syncthreads();
     ICE_HSTAMP(5);
-    const int k = min(P, ncand);
+    // how many pages stage 2 keeps: P, or n_refine of which stage 3 then keeps P
+    const int k2 = min(n_refine > 0 ? n_refine : P, ncand);
+    int k = min(P, k2);
     int *ids = ids_out + (size_t)u * P;
     float *sco = scores_out ? scores_out + (size_t)u * P : nullptr;
     for (int x = k + tid; x < P; x += NT) {
@@ -385,13 +391,66 @@ __global__ __launch_bounds__(NW * 64) void decode_hier_kernel(Dev d, const bf16_
         if (sco) sco[x] = 0.f;
     }
     if (tid == 0) n_sel_out[u] = k;
-    if (k == ncand) {
-        for (int x = tid; x < k; x += NT) sel2[x] = comp2[x];
+    int nb = 0;
+    while ((1 << nb) < d.max_pages) ++nb;
+    if (k2 == ncand) {
+        for (int x = tid; x < k2; x += NT) sel2[x] = comp2[x];
         __syncthreads();
     } else {
-        int nb = 0;
-        while ((1 << nb) < d.max_pages) ++nb;
-        select_topk_lds<NW>(comp2, ncand, k, nb, sel2, list, hist, sh);
+        select_topk_lds<NW>(comp2, ncand, k2, nb, sel2, list, hist, sh);
+    }
+    const u64 *win = sel2;  // the winners, as composites
+    if (n_refine > 0) {
+        // ---- stage 3: the kept pages re-scored by their best key (the paper ranks keys and loads the
+        // pages that hold them, Alg. 3): one wave per page, logits of 16 tokens per MFMA chain as in the
+        // attention, normalised like the page scores, maximum over heads and live tokens
+        const int s = d.s;
+        constexpr int UNR3 = 4;  // pages whose first blocks are in flight per wave
+        for (int x0 = wave; x0 < k2; x0 += NW * UNR3) {
+            uint4 kb[UNR3][4];
+            uint32_t pp[UNR3];
+            int fl[UNR3];
+#pragma unroll
+            for (int y = 0; y < UNR3; ++y) {
+                const int x = x0 + NW * y;
+                pp[y] = x < k2 ? 0xFFFFFFFFu - (uint32_t)sel2[x] : 0u;  // (page 0 stands in past the end)
+                const size_t pg = (size_t)u * d.max_pages + pp[y];
+#pragma unroll
+                for (int t = 0; t < 4; ++t) kb[y][t] = ((const uint4 *)(d.Kp + (pg * s + ch) * kD))[t * 4 + g];
+                fl[y] = d.page_fill[pg];
+            }
+#pragma unroll
+            for (int y = 0; y < UNR3; ++y) {
+                const int x = x0 + NW * y;
+                const size_t pg = (size_t)u * d.max_pages + pp[y];
+                float best = -INFINITY;
+                for (int b0 = 0; b0 < fl[y]; b0 += 16) {
+                    if (b0 > 0) {
+#pragma unroll
+                        for (int t = 0; t < 4; ++t) kb[y][t] = ((const uint4 *)(d.Kp + (pg * s + b0 + ch) * kD))[t * 4 + g];
+                    }
+                    f32x4 z = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+                    for (int ks = 0; ks < 4; ++ks)
+                        z = __builtin_amdgcn_mfma_f32_16x16x32_bf16(qa[ks], __builtin_bit_cast(bf16x8, kb[y][ks]), z, 0, 0, 0);
+                    const float sc = group_score(z);       // token b0 + ch, on the lanes of row group 0
+                    if (b0 + ch < fl[y]) best = fmaxf(best, sc);
+                }
+                best = fmaxf(best, dpp_f32<0xB1>(best));
+                best = fmaxf(best, dpp_f32<0x4E>(best));
+                best = fmaxf(best, dpp_f32<0x141>(best));
+                best = fmaxf(best, dpp_f32<0x140>(best));
+                if (lane == 0 && x < k2) comp3[x] = ((u64)f32_ordered(best) << 32) | (u64)(0xFFFFFFFFu - pp[y]);
+            }
+        }
+        __syncthreads();
+        if (k == k2) {
+            for (int x = tid; x < k; x += NT) sel3[x] = comp3[x];
+            __syncthreads();
+        } else {
+            select_topk_lds<NW>(comp3, k2, k, nb, sel3, list, hist, sh);
+        }
+        win = sel3;
     }
     ICE_HSTAMP(6);
     // the winners' places in ascending id order; during the attention it runs where the first
@@ -411,34 +470,34 @@ __global__ __launch_bounds__(NW * 64) void decode_hier_kernel(Dev d, const bf16_
             }
         }
         for (int t = tid; t < k; t += NT) {
-            const u64 mine = sel2[t];
+            const u64 mine = win[t];
             const uint32_t myid = 0xFFFFFFFFu - (uint32_t)mine;
             int pos = 0;
-            for (int j = 0; j < k; ++j) pos += (0xFFFFFFFFu - (uint32_t)sel2[j]) < myid;
+            for (int j = 0; j < k; ++j) pos += (0xFFFFFFFFu - (uint32_t)win[j]) < myid;
             ids[pos] = (int)myid;
             if (sco) sco[pos] = ordered_f32((uint32_t)(mine >> 32));
         }
     };
-    if (out) attend_pages<G, NW, false>(d, u, qa, [=](int x) { return (int)(0xFFFFFFFFu - (uint32_t)sel2[x]); }, k, Resident{nullptr, nullptr, 0, nullptr, nullptr, 0}, out, red, order_ids);
+    if (out) attend_pages<G, NW, false>(d, u, qa, [=](int x) { return (int)(0xFFFFFFFFu - (uint32_t)win[x]); }, k, Resident{nullptr, nullptr, 0, nullptr, nullptr, 0}, out, red, order_ids);
     else order_ids();
     ICE_HSTAMP(7);
 }
 
-size_t decode_hier_lds_bytes(const Dev &d, int P, int n_probe) {
+size_t decode_hier_lds_bytes(const Dev &d, int P, int n_probe, int n_refine) {
     const int NW = d.G == 8 ? 8 : 16;
-    return hier_lds(d.Cpad, d.max_pages, n_probe, P, d.G, NW).total;
+    return hier_lds(d.Cpad, d.max_pages, n_probe, n_refine, P, d.G, NW).total;
 }
 
-void launch_decode_hier(const Dev &d, const bf16_t *q, int cur, int P, int n_probe, int np_hint, int *ids, int *n_sel,
-                        float *scores_out, int *clusters_out, float *out, hipStream_t st) {
-    const size_t lds = decode_hier_lds_bytes(d, P, n_probe);
+void launch_decode_hier(const Dev &d, const bf16_t *q, int cur, int P, int n_probe, int n_refine, int np_hint, int *ids,
+                        int *n_sel, float *scores_out, int *clusters_out, float *out, hipStream_t st) {
+    const size_t lds = decode_hier_lds_bytes(d, P, n_probe, n_refine);
     const int NW = d.G == 8 ? 8 : 16;
     if (np_hint > d.max_pages) np_hint = d.max_pages;
     const int E = (d.max_pages + NW * 64 - 1) / (NW * 64);
 #define ICE_HIER(g, nw, e)                                                                                           \
     do {                                                                                                             \
         (void)hipFuncSetAttribute((const void *)decode_hier_kernel<g, nw, e>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds); \
-        hipLaunchKernelGGL((decode_hier_kernel<g, nw, e>), dim3(d.U), dim3(nw * 64), lds, st, d, q, cur, P, n_probe, np_hint, ids, \
+        hipLaunchKernelGGL((decode_hier_kernel<g, nw, e>), dim3(d.U), dim3(nw * 64), lds, st, d, q, cur, P, n_probe, n_refine, np_hint, ids, \
                            n_sel, scores_out, clusters_out, out);                                                    \
     } while (0)
     if (d.G == 8) { if (E <= 8) ICE_HIER(8, 8, 8); else ICE_HIER(8, 8, 32); }

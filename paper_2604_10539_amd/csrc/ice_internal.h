@@ -70,10 +70,10 @@ void launch_insert(const Dev &d, const bf16_t *k, const bf16_t *v, int m, int cu
 void launch_decode_step(const Dev &d, const bf16_t *q, int P, int np_hint, int *ids, int *n_sel, float *scores_out,
                         const bf16_t *res_k, const bf16_t *res_v, int n_res, float *out, hipStream_t st);
 // two-stage selection (clusters, then their pages) (+ attention when out != nullptr) in one launch
-void launch_decode_hier(const Dev &d, const bf16_t *q, int cur, int P, int n_probe, int np_hint, int *ids, int *n_sel,
-                        float *scores_out, int *clusters_out, float *out, hipStream_t st);
+void launch_decode_hier(const Dev &d, const bf16_t *q, int cur, int P, int n_probe, int n_refine, int np_hint, int *ids,
+                        int *n_sel, float *scores_out, int *clusters_out, float *out, hipStream_t st);
 int decode_hier_max_pages(int G);
-size_t decode_hier_lds_bytes(const Dev &d, int P, int n_probe);
+size_t decode_hier_lds_bytes(const Dev &d, int P, int n_probe, int n_refine);
 int decode_step_max_pages(int G);
 size_t decode_step_lds_bytes(const Dev &d, int P);
 // Resident tokens: tokens that are always attended on top of the listed pages, handled as further

@@ -725,3 +725,60 @@ def test_random_shapes_end_to_end(seed):
         if by_pos is not None:   # (without insertions every indexed token is a row of the build cache)
             assert (by_pos - ix.attend(up(q), ids, n_sel)).abs().max().item() <= 2e-5
         ix.close()
+
+
+# ----------------------------------------------------------------------------------------- refinement by best key
+def _check_refined(ix, o, q, budget, n_probe, n_refine, ids, n_sel, scores, out):
+    """Stage 3 against the oracle; pages may differ from the oracle's only inside the tie band of
+    the stage-2 cut (n_refine-th representative score) or of the final cut (P-th best-key score)."""
+    U = ix.U
+    oid, ons, osc, _, _ = o.select_hier(q, budget, n_probe, n_refine)
+    _, _, _, S_all = o.select(q, budget)
+    ids, n_sel, scores = down(ids).reshape(U, -1), down(n_sel).reshape(U), down(scores).reshape(U, -1)
+    assert np.array_equal(n_sel, ons)
+    qf = widen(q).astype(np.float64).reshape(U, ix.group_size, D)
+    ties = 0
+    for u in range(U):
+        k = int(ons[u])
+        got = ids[u, :k]
+        assert np.all(np.diff(got) > 0) and np.all(ids[u, k:] == -1)
+        nq = np.linalg.norm(qf[u], axis=1)
+
+        def best_key(p):
+            kk = widen(o.Kp[u, p, :o.page_fill[u, p]]).astype(np.float64)
+            return np.float32(((kk @ qf[u].T) / nq[None, :]).max())
+        np.testing.assert_allclose(scores[u, :k], [best_key(p) for p in got], rtol=2e-6, atol=2e-6)
+        if np.array_equal(got, oid[u, :k]):
+            continue
+        ties += 1
+        thr_final = np.sort(osc[u, :k])[0]
+        for p in np.setxor1d(got, oid[u, :k]):
+            near_final = abs(float(best_key(p)) - float(thr_final)) <= SCORE_TIE * max(1.0, abs(float(thr_final)))
+            assert near_final or n_refine < o.n_pages[u], "refined selection differs outside the tie bands"
+    print("[refine] %d units with near-tie differences" % ties)
+    if out is not None:
+        ref = o.attend(q, ids, n_sel)
+        assert np.abs(down(out).reshape(ref.shape) - ref).max() <= ATTN_EXPECTED
+    return ties
+
+
+@pytest.mark.gpu
+@pytest.mark.parametrize("kw,budget,n_probe,n_refine", [
+    (dict(n_tokens=4096, n_clusters=32, n_kv_heads=2, n_components=32), 256, 32, 64),     # flat candidates, 4x
+    (dict(n_tokens=4096, n_clusters=32, n_kv_heads=2, n_components=32), 256, 6, 40),      # hierarchical candidates
+    (dict(n_tokens=5003, n_clusters=100, n_kv_heads=3, n_components=40, group_size=1), 64, 100, 4),   # n_refine == P
+    (dict(n_tokens=2500, n_clusters=24, n_kv_heads=2, page_size=32, group_size=2), 256, 24, 30),
+    (dict(n_tokens=2600, n_clusters=40, n_kv_heads=1, page_size=64, group_size=8), 640, 40, 25),
+    (dict(n_tokens=700, n_clusters=5, n_kv_heads=2), 128, 5, 5000),                        # more than exist
+])
+def test_selection_refined_by_best_key(kw, budget, n_probe, n_refine):
+    w = datagen.small(**kw)
+    ix, K, V, _ = _mk(w, T=2)
+    ix.build_index(up(K), up(V))
+    q = datagen.queries(w)
+    ids, n_sel, scores, clusters, out = ix.select_hier(up(q), budget, n_probe, n_refine=n_refine)
+    o = oracle_from_export(ix, export_np(ix))
+    ties = _check_refined(ix, o, q, budget, n_probe, n_refine, ids, n_sel, scores, out)
+    assert ties == 0
+    with pytest.raises(Exception):
+        ix.select_hier(up(q), budget, n_probe, n_refine=max(1, budget // w.page_size - 1) if budget // w.page_size > 1 else -1)

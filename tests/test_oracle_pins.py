@@ -581,6 +581,38 @@ def test_hier_select_sees_pages_appended_by_insertion():
     assert ids[0, :n_sel[0]].tolist() == mine
 
 
+def test_refined_selection_ranks_pages_by_their_best_key():
+    """Stage 3 written out with numpy: of the n_refine best pages by representative, those holding the
+    best keys win; with n_refine = 0 nothing changes, and with one token per page (representative ==
+    key) refinement cannot change the order."""
+    w = datagen.small(n_tokens=1800, n_clusters=20, n_kv_heads=2)
+    ix, _, _ = _built(w)
+    q = datagen.queries(w).reshape(ix.U, w.group_size, D)
+    budget, n_refine = 64, 24
+    P = budget // 16
+    ids, n_sel, scores, _, _ = ix.select_hier(q, budget, ix.C, n_refine)
+    _, _, _, S_all = ix.select(q, budget)
+    qf = widen(q).astype(np.float64)
+    changed = 0
+    for u in range(ix.U):
+        npg = int(ix.n_pages[u])
+        kept = sorted(range(npg), key=lambda p: (-S_all[u, p], p))[:n_refine]
+        nq = np.linalg.norm(qf[u], axis=1)
+        best = {}
+        for p in kept:
+            kk = widen(ix.Kp[u, p, :ix.page_fill[u, p]]).astype(np.float64)
+            best[p] = np.float32(((kk @ qf[u].T) / nq[None, :]).max())
+        want = sorted(sorted(kept, key=lambda p: (-best[p], p))[:P])
+        assert ids[u, :n_sel[u]].tolist() == want
+        np.testing.assert_allclose(scores[u, :n_sel[u]], [best[p] for p in want], rtol=3e-7)
+        changed += want != sorted(kept[:P])
+        assert all(best[p] >= S_all[u, p] - 0.01 * abs(S_all[u, p]) - 1e-5 for p in kept)   # best key >= mean key (bf16 rep)
+    assert changed > 0                                              # the case is not vacuous
+    a = ix.select_hier(q, budget, ix.C, 0)
+    f = ix.select(q, budget)
+    assert np.array_equal(a[0], f[0]) and np.array_equal(a[2], f[2])
+
+
 # ----------------------------------------------------------------------------- attention with resident tokens
 def test_attend_resident_is_dense_attention_over_the_union():
     """Selected pages + resident (sink / window) tokens: one softmax over their union, checked
