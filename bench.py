@@ -47,10 +47,12 @@ def parse():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=100)
     ap.add_argument("--warmup", type=int, default=10)
-    ap.add_argument("--layers", type=int, default=32)
+    ap.add_argument("--layers", type=int, default=0,
+                    help="independent (layer or sequence) index sets batched in one launch; default 32 / 1 / 16 for cfg2 / 3 / 4")
     ap.add_argument("--kmeans-iters", type=int, default=10)
-    ap.add_argument("--workload", default="cfg2", choices=["cfg2"])
-    ap.add_argument("--n-probe", type=int, default=64, help="clusters kept by the hierarchical variant")
+    ap.add_argument("--workload", default="cfg2", choices=["cfg2", "cfg3", "cfg4"],
+                    help="cfg2 is the headline; cfg3 (131k context, budget 1024) and cfg4 (16 sequences) are extra shapes")
+    ap.add_argument("--n-probe", type=int, default=0, help="clusters kept by the hierarchical variant (default n_clusters / 8)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--warm", action="store_true", help="skip the cache flush between steps")
     return ap.parse_args()
@@ -72,7 +74,12 @@ def main():
 
     assert torch.cuda.is_available(), "bench.py needs the GPU"
     dev = torch.device("cuda:0")
-    w = datagen.WORKLOADS[args.workload]
+    import dataclasses
+    w = dataclasses.replace(datagen.WORKLOADS[args.workload], batch=1)   # sequences of cfg4 are generated like layers
+    if args.layers <= 0:
+        args.layers = {"cfg2": 32, "cfg3": 1, "cfg4": 16}[args.workload]
+    if args.n_probe <= 0:
+        args.n_probe = max(1, w.n_clusters // 8)
     L, H, G, n, s, C, budget = args.layers, w.n_kv_heads, w.group_size, w.n_tokens, w.page_size, w.n_clusters, w.token_budget
     P = budget // s
     T = args.kmeans_iters
@@ -421,12 +428,12 @@ def main():
     gbps = bytes_step / (ms_batched * 1e-3) / 1e9
     sel_gbps = bytes_select / (ms_sel * 1e-3) / 1e9
     line = {
-        "metric": "select+attend us per layer-step (32k ctx, 256-token budget)",
+        "metric": "select+attend us per layer-step (%dk ctx, %d-token budget)" % (n // 1024, budget),
         "value": us_layer, "unit": "us/layer-step",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_batched,
         "higher_is_better": False, "scaling": "weak", "vs_baseline": None,
         "dtype": "bf16", "data": "synthetic",
-        "config": {"workload": "cfg2: %d independent layers x (B=1, %d KV heads, GQA %d, d=128, n=%d, page %d, "
+        "config": {"workload": args.workload + ": %d independent layers x (B=1, %d KV heads, GQA %d, d=128, n=%d, page %d, "
                                "%d clusters, budget %d), batched in one launch set of %d units; %s"
                                % (L, H, G, n, s, C, budget, L * H,
                                   "cold (steps rotate over three copies of the index, 540 MB, so none is cache resident)" if cold else "warm"),
@@ -434,10 +441,11 @@ def main():
         "effective_GBps": gbps,
         "bytes_per_step": bytes_step,
         "hbm_frac": gbps / HBM_PEAK_GBPS,
-        "roofline": {"bound": "hbm", "kernel": "decode_step_kernel<4,16,4> (score + top-P + attention in one launch), "
-                                               "256 workgroups of 1024 threads, one per unit",
+        "roofline": {"bound": "hbm", "kernel": "decode_step_kernel<4,16,%d> (score + top-P + attention in one launch), "
+                                               "%d units, workgroups of 1024 threads (one per unit from 256 units on, "
+                                               "else 256/units per unit)" % (4 if (max_tokens // s + C) <= 4096 else 16, L * H),
                      "achieved": gbps, "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": gbps / HBM_PEAK_GBPS,
-                     "traffic": MEASURED_TRAFFIC_BYTES, "algorithmic_bytes_per_launch": bytes_step,
+                     "traffic": MEASURED_TRAFFIC_BYTES if (args.workload, L) == ("cfg2", 32) else None, "algorithmic_bytes_per_launch": bytes_step,
                      "us_per_launch": ms_batched * 1e3,
                      "traffic_note": "rocprofv3 --pmc FETCH_SIZE x 2.0 (the counter reads half of a plain copy kernel's "
                                      "known bytes) + WRITE_SIZE x 1.0; see profiles/"},
