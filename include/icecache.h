@@ -10,7 +10,8 @@
  * Conventions
  *   Pointers  Every tensor pointer is a DEVICE pointer owned by the caller, 16-byte aligned,
  *             contiguous and row-major as annotated.  bf16 = upper 16 bits of an IEEE fp32.
- *             The only host pointers are ice_config_t*, ice_index_view_t* and ice_index_t**.
+ *             The only host pointers are ice_config_t*, ice_index_view_t*, ice_index_t** and
+ *             the flop count written by ice_debug_peak_mfma.
  *   Memory    The library never allocates device memory.  The caller passes one workspace of
  *             ice_workspace_bytes() bytes (256-byte aligned) to ice_create(); page pools,
  *             tables, representatives, centroids and scratch all live inside it.
@@ -135,7 +136,8 @@ ice_status_t ice_insert_batch(ice_index_t *idx, const void *k, const void *v, in
  * pages by (score descending, id ascending) are returned with ids ascending, padded with -1.
  *   q: bf16 [B, H_q, d];  page_ids: int32 [B, H_kv, P];  n_selected: int32 [B, H_kv];
  *   scores_or_null: fp32 [B, H_kv, P] group score of each returned page (0 in the padding).
- * SHAPE if token_budget < page_size. */
+ * SHAPE if token_budget < page_size; UNSUPPORTED if the index has more than 16384 pages per unit
+ * (the scores of a unit are ranked in one workgroup's registers and LDS). */
 ice_status_t ice_select(ice_index_t *idx, const void *q, int32_t token_budget, int32_t *page_ids,
                         int32_t *n_selected, float *scores_or_null, void *stream);
 
@@ -175,7 +177,8 @@ ice_status_t ice_select_attend_resident(ice_index_t *idx, const void *q, int32_t
  *   ice_attend_tokens    attention (Eq. 1) of q over rows token_pos[b, h, 0 .. n_tok[b, h]) of a
  *       dense cache K, V bf16 [B, H_kv, n_rows, d] (any layer's; caller-owned device memory);
  *       max_tok = length of a unit's position list.  The index only supplies B, H_kv and the group
- *       size.  Positions must lie in [0, n_rows) (others are clamped into the cache, not skipped).
+ *       size (STATE before a build or import).  Positions must lie in [0, n_rows) (others are
+ *       clamped into the cache, not skipped).
  * With the cache the index was built from, ice_attend_tokens over ice_selected_tokens' positions
  * gives ice_attend's result over those pages. */
 ice_status_t ice_selected_tokens(ice_index_t *idx, const int32_t *page_ids, const int32_t *n_selected,
