@@ -320,6 +320,9 @@ def test_imported_oracle_index_select_attend():
     ex = export_np(ix)
     for name in STATE_FIELDS:
         assert np.array_equal(ex[name], getattr(o, name)), name
+    # the staged selection on the imported index (centroid roundings are recomputed at import)
+    _check_hier(ix, o, q, 256, 7, *ix.select_hier(up(q), 256, 7))
+    _check_refined(ix, o, q, 256, 48, 40, *[x for i, x in enumerate(ix.select_hier(up(q), 256, 48, n_refine=40)) if i != 3])
 
 
 # ----------------------------------------------------------------------------------------- insert
