@@ -208,6 +208,28 @@ ice_status_t ice_select_hier(ice_index_t *idx, const void *q, int32_t token_budg
                              int32_t *page_ids, int32_t *n_selected, float *scores_or_null,
                              int32_t *clusters_or_null, float *out_or_null, void *stream);
 
+/* Geometry of the clustering (Sec. 4.2, Eq. 2).  The paper measures key-key distances between
+ * transformed keys T_K(k) = [k / c, sqrt(1 - ||k||^2 / c^2)], c >= the largest key norm.  With
+ * ICE_GEOMETRY_TRANSFORMED the next ice_build_index (and every later insertion) does the same,
+ * kept times c: every key and every centroid carries ONE more coordinate, a(k) = sqrt(c^2 - ||k||^2)
+ * rounded to bf16 resp. the mean of its members' a, c^2 = the largest squared norm among the
+ * unit's prefill keys (a later key with a larger norm gets a = 0).  Page tiles, representatives,
+ * selection and attention are unchanged (the transformed query has 0 in that coordinate, Eq. 3).
+ * ICE_GEOMETRY_RAW (the default) clusters on the keys as they are.  An imported index is raw.
+ * ice_export_geometry gives device pointers into the workspace (null when raw):
+ *   key_extra bf16 [U][max_tokens] by token position; centroid_extra, cluster_sum_extra fp32
+ *   [U][n_clusters]; radius_sq fp32 [U]; assign_centroid_extra_bf16 bf16 [U][cpad], the extra
+ *   coordinate of the centroids that the exported `assign` was computed against. */
+enum { ICE_GEOMETRY_RAW = 0, ICE_GEOMETRY_TRANSFORMED = 1 };
+typedef struct {
+    int32_t geometry, reserved;
+    void *key_extra;
+    float *centroid_extra, *cluster_sum_extra, *radius_sq;
+    void *assign_centroid_extra_bf16;
+} ice_geometry_view_t;
+ice_status_t ice_set_geometry(ice_index_t *idx, int32_t geometry);
+ice_status_t ice_export_geometry(ice_index_t *idx, ice_geometry_view_t *view);
+
 /* Test and snapshot surface.  Export fills `view` with pointers INTO the workspace (no copy).
  * Import copies caller arrays (device pointers, same layout; the export-only fields are
  * ignored; n_tokens, page_size, n_clusters, max_pages must fit the workspace) into the index and

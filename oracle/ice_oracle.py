@@ -263,3 +263,30 @@ def attend_tokens(q: np.ndarray, K: np.ndarray, V: np.ndarray, pos: np.ndarray, 
     lib().orc_attend_tokens(_p(q), _p(K), _p(V), C.c_int(U), C.c_int(G), C.c_int(d), C.c_int(n_rows), _p(pos), _p(n_tok),
                             C.c_int(cap), _p(out))
     return out
+
+
+# ---- transformed keys (Sec. 4.2, Eq. 2) -------------------------------------------------------------
+def _bf16_rne(x: np.ndarray) -> np.ndarray:
+    u = np.ascontiguousarray(x, np.float32).view(np.uint32)
+    return ((u + 0x7FFF + ((u >> 16) & 1)) >> 16).astype(np.uint16)
+
+
+def _bf16_to_f64(b: np.ndarray) -> np.ndarray:
+    return (np.ascontiguousarray(b, np.uint16).astype(np.uint32) << 16).view(np.float32).astype(np.float64)
+
+
+def key_extra_coordinate(K: np.ndarray, c2: np.ndarray | None = None):
+    """The one extra coordinate of c * T_K(k) = [k, sqrt(c^2 - ||k||^2)] for every key.
+    K uint16 [U, n, d]; c2 float64 [U] or None (then c^2 = the largest squared key norm of the unit).
+    Keys with ||k||^2 > c^2 get 0.  -> (extra uint16 [U, n] rounded to bf16, c2 float64 [U])."""
+    n2 = (_bf16_to_f64(K) ** 2).sum(-1)
+    if c2 is None:
+        c2 = n2.max(-1)
+    a = np.sqrt(np.maximum(np.asarray(c2, np.float64)[:, None] - n2, 0.0))
+    return _bf16_rne(a.astype(np.float32)), np.asarray(c2, np.float64)
+
+
+def augment(K: np.ndarray, extra: np.ndarray) -> np.ndarray:
+    """[U, n, d] keys + [U, n] extra coordinate -> [U, n, d+1]: clustering on the transformed keys is
+    clustering on these rows with the functions above (they take any d)."""
+    return np.concatenate([np.ascontiguousarray(K, np.uint16), np.ascontiguousarray(extra, np.uint16)[..., None]], -1)

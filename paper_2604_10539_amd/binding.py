@@ -17,7 +17,7 @@ ICE_OK, ICE_ERR_INVALID_ARG, ICE_ERR_SHAPE, ICE_ERR_STATE, ICE_ERR_CAPACITY, ICE
 STATUS_NAMES = ["ICE_OK", "ICE_ERR_INVALID_ARG", "ICE_ERR_SHAPE", "ICE_ERR_STATE", "ICE_ERR_CAPACITY",
                 "ICE_ERR_UNSUPPORTED", "ICE_ERR_DEVICE"]
 SYMBOLS = ["ice_workspace_bytes", "ice_create", "ice_destroy", "ice_build_index", "ice_insert", "ice_insert_batch", "ice_select",
-           "ice_attend", "ice_select_attend", "ice_attend_resident", "ice_select_attend_resident", "ice_selected_tokens", "ice_attend_tokens", "ice_select_hier", "ice_export_index", "ice_import_index", "ice_debug_assign",
+           "ice_attend", "ice_select_attend", "ice_attend_resident", "ice_select_attend_resident", "ice_selected_tokens", "ice_attend_tokens", "ice_select_hier", "ice_set_geometry", "ice_export_geometry", "ice_export_index", "ice_import_index", "ice_debug_assign",
            "ice_debug_peak_read", "ice_debug_peak_mfma", "ice_last_error"]
 
 
@@ -33,6 +33,15 @@ class IceIndexView(C.Structure):
                [(n, C.c_void_p) for n in ("Kp", "Vp", "page_cluster", "page_fill", "page_pos", "cluster_tail",
                                           "cluster_cnt", "cluster_sum", "centroid", "page_sum", "rep", "n_pages",
                                           "assign", "assign_centroid_bf16", "init_idx")]
+
+
+class IceGeometryView(C.Structure):
+    _fields_ = [("geometry", C.c_int32), ("reserved", C.c_int32), ("key_extra", C.c_void_p),
+                ("centroid_extra", C.c_void_p), ("cluster_sum_extra", C.c_void_p), ("radius_sq", C.c_void_p),
+                ("assign_centroid_extra_bf16", C.c_void_p)]
+
+
+ICE_GEOMETRY_RAW, ICE_GEOMETRY_TRANSFORMED = 0, 1
 
 
 class IceError(RuntimeError):
@@ -73,6 +82,8 @@ def lib() -> C.CDLL:
                                         C.c_int32, C.c_void_p, C.c_void_p]
         L.ice_select_hier.argtypes = [C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.c_int32, C.c_void_p, C.c_void_p,
                                       C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]
+        L.ice_set_geometry.argtypes = [C.c_void_p, C.c_int32]
+        L.ice_export_geometry.argtypes = [C.c_void_p, C.POINTER(IceGeometryView)]
         L.ice_export_index.argtypes = [C.c_void_p, C.POINTER(IceIndexView)]
         L.ice_import_index.argtypes = [C.c_void_p, C.POINTER(IceIndexView), C.c_void_p]
         L.ice_debug_assign.argtypes = [C.c_void_p, C.c_void_p, C.c_int32, C.c_void_p, C.c_int32, C.c_void_p,
@@ -184,6 +195,16 @@ def ice_select_hier(idx, q, token_budget, n_probe, page_ids, n_selected, scores=
                                  _ptr(clusters), _ptr(out), _stream(stream)))
 
 
+def ice_set_geometry(idx, geometry: int) -> None:
+    _check(lib().ice_set_geometry(idx, geometry))
+
+
+def ice_export_geometry(idx) -> IceGeometryView:
+    view = IceGeometryView()
+    _check(lib().ice_export_geometry(idx, C.byref(view)))
+    return view
+
+
 def ice_export_index(idx) -> IceIndexView:
     view = IceIndexView()
     _check(lib().ice_export_index(idx, C.byref(view)))
@@ -237,7 +258,7 @@ class IceIndex:
     bf16 tensors may be torch.bfloat16 or int16 bit patterns."""
 
     def __init__(self, batch, n_kv_heads, group_size, max_tokens, page_size, n_clusters, kmeans_iters=10, seed=0,
-                 init_idx=None, device="cuda"):
+                 init_idx=None, device="cuda", geometry=ICE_GEOMETRY_RAW):
         self.batch, self.n_kv_heads, self.group_size = batch, n_kv_heads, group_size
         self.page_size, self.n_clusters, self.max_tokens = page_size, n_clusters, max_tokens
         self.U = batch * n_kv_heads
@@ -249,6 +270,8 @@ class IceIndex:
             raise IceError(ICE_ERR_INVALID_ARG, "invalid configuration")
         self.workspace = torch.empty(nbytes, dtype=torch.uint8, device=self.device)
         self.handle = ice_create(self.cfg, self.workspace)
+        if geometry != ICE_GEOMETRY_RAW:
+            ice_set_geometry(self.handle, geometry)
 
     def close(self):
         if getattr(self, "handle", None):
@@ -350,6 +373,28 @@ class IceIndex:
         ice_select_hier(self.handle, q, token_budget, n_probe, ids, n_sel, scores, clusters, out if attend else None,
                         stream, n_refine)
         return ids, n_sel, scores, clusters, (out if attend else None)
+
+    def export_geometry(self):
+        """The extra coordinate of the transformed-key geometry as torch tensors aliasing the workspace
+        (None when the index clusters on the raw keys)."""
+        v = ice_export_geometry(self.handle)
+        if v.geometry == ICE_GEOMETRY_RAW:
+            return None
+        iv = ice_export_index(self.handle)
+        base = self.workspace.data_ptr()
+
+        def view(ptr, dtype, shape):
+            nb = int(torch.tensor([], dtype=dtype).element_size())
+            n = 1
+            for x in shape:
+                n *= x
+            return self.workspace[ptr - base: ptr - base + n * nb].view(dtype).view(*shape)
+        U = self.U
+        return {"key_extra": view(v.key_extra, torch.int16, (U, iv.max_tokens)),
+                "centroid_extra": view(v.centroid_extra, torch.float32, (U, iv.n_clusters)),
+                "cluster_sum_extra": view(v.cluster_sum_extra, torch.float32, (U, iv.n_clusters)),
+                "radius_sq": view(v.radius_sq, torch.float32, (U,)),
+                "assign_centroid_extra_bf16": view(v.assign_centroid_extra_bf16, torch.int16, (U, iv.cpad))}
 
     def export(self):
         """dict of torch tensors aliasing the workspace (no copy) plus the view itself under 'view'."""

@@ -79,6 +79,11 @@ size_t lay_out(const ice_config_t &cfg, int s, int C, char *base, Dev *out) {
         d.cent_bf16[b] = (bf16_t *)take(U * CP * kD * 2);
         d.cnorm[b] = (float *)take(U * CP * 4);
     }
+    d.kaug = (bf16_t *)take(U * MT * 2);
+    for (int b = 0; b < 2; ++b) d.caug[b] = (bf16_t *)take(U * CP * 2);
+    d.cent_aug = (float *)take(U * C * 4);
+    d.csum_aug = (float *)take(U * C * 4);
+    d.c2 = (float *)take(U * 4);
     d.init_idx = (int *)take(U * C * 4);
     d.assign = (int *)take(U * MT * 4);
     d.packed = (unsigned long long *)take(U * MT * 8);
@@ -99,6 +104,7 @@ ice_status_t ensure_layout(ice_index *ix, int s, int C) {
         return fail(ICE_ERR_CAPACITY, "workspace has %zu bytes, page_size %d / n_clusters %d need %zu", ix->ws_bytes, s,
                     C, need);
     lay_out(ix->cfg, s, C, ix->ws, &ix->dev);
+    ix->dev.tk = ix->geometry;
     ix->laid_out = true;
     ix->built = false;
     return ICE_OK;
@@ -150,6 +156,7 @@ ice_status_t ice_create(const ice_config_t *cfg, void *workspace, size_t workspa
     ix->built = false;
     ix->n_tokens = 0;
     ix->cur = 0;
+    ix->geometry = 0;
     *out = ix;
     return ICE_OK;
 }
@@ -172,10 +179,12 @@ ice_status_t ice_build_index(ice_index_t *ix, const void *K, const void *V, int3
     if (n > ix->cfg.max_tokens) return fail(ICE_ERR_SHAPE, "n_tokens %d exceeds max_tokens %d", n, ix->cfg.max_tokens);
     if (ice_status_t st = ensure_layout(ix, page_size, n_clusters)) return st;
     hipStream_t s = static_cast<hipStream_t>(stream);
+    ix->dev.tk = ix->geometry;
     const Dev &d = ix->dev;
     const bf16_t *Kb = static_cast<const bf16_t *>(K), *Vb = static_cast<const bf16_t *>(V);
     ix->built = false;
     int cur = 0;
+    if (d.tk) launch_key_aug(d, Kb, n, s);
     launch_init_centroids(d, Kb, n, ix->cfg.init_idx, ix->cfg.seed, cur, s);
     for (int t = 0; t < ix->cfg.kmeans_iters; ++t) {
         launch_assign(d, Kb, n, cur, s);
@@ -322,6 +331,31 @@ ice_status_t ice_select_hier(ice_index_t *ix, const void *q, int32_t budget, int
     return device_status("ice_select_hier");
 }
 
+ice_status_t ice_set_geometry(ice_index_t *ix, int32_t geometry) {
+    if (!ix) return fail(ICE_ERR_INVALID_ARG, "index is null");
+    if (geometry != ICE_GEOMETRY_RAW && geometry != ICE_GEOMETRY_TRANSFORMED)
+        return fail(ICE_ERR_INVALID_ARG, "geometry %d: ICE_GEOMETRY_RAW or ICE_GEOMETRY_TRANSFORMED", geometry);
+    if (geometry != ix->geometry) ix->built = false;  // takes effect with the next build
+    ix->geometry = geometry;
+    return ICE_OK;
+}
+
+ice_status_t ice_export_geometry(ice_index_t *ix, ice_geometry_view_t *v) {
+    if (!ix || !v) return fail(ICE_ERR_INVALID_ARG, "index or view is null");
+    if (!ix->built) return fail(ICE_ERR_STATE, "ice_export_geometry before ice_build_index");
+    const Dev &d = ix->dev;
+    memset(v, 0, sizeof(*v));
+    v->geometry = d.tk;
+    if (d.tk) {
+        v->key_extra = d.kaug;
+        v->centroid_extra = d.cent_aug;
+        v->cluster_sum_extra = d.csum_aug;
+        v->radius_sq = d.c2;
+        v->assign_centroid_extra_bf16 = d.caug[ix->cur ^ 1];
+    }
+    return ICE_OK;
+}
+
 ice_status_t ice_export_index(ice_index_t *ix, ice_index_view_t *v) {
     if (!ix || !v) return fail(ICE_ERR_INVALID_ARG, "index or view is null");
     if (!ix->built) return fail(ICE_ERR_STATE, "ice_export_index before ice_build_index");
@@ -387,6 +421,8 @@ ice_status_t ice_import_index(ice_index_t *ix, const ice_index_view_t *v, void *
     if (e != hipSuccess) return fail(ICE_ERR_DEVICE, "ice_import_index: %s", hipGetErrorString(e));
     reset_decode_state(d, v->n_tokens, s);
     ix->cur = 0;
+    ix->geometry = 0;  // (an imported index carries no extra coordinate)
+    ix->dev.tk = 0;
     launch_refresh_centroids(d, 0, s);
     launch_refresh_centroids(d, 1, s);
     if (ice_status_t st = device_status("ice_import_index")) return st;
@@ -405,6 +441,7 @@ ice_status_t ice_debug_assign(ice_index_t *ix, const void *K, int32_t n, const v
     const int s_cur = ix->laid_out ? ix->dev.s : 16;
     if (ice_status_t st = check_shape(s_cur, n_clusters)) return st;
     if (ice_status_t st = ensure_layout(ix, s_cur, n_clusters)) return st;
+    ix->dev.tk = 0;  // (the debug assignment is always on the raw keys)
     ix->built = false;
     hipStream_t s = static_cast<hipStream_t>(stream);
     const Dev &d = ix->dev;

@@ -19,6 +19,49 @@ __device__ inline uint64_t splitmix64(uint64_t x) {
 }
 
 // ------------------------------------------------------------------------------------------------
+// Transformed keys (Sec. 4.2, Eq. 2): T_K(k) = [k / c, sqrt(1 - ||k||^2 / c^2)] with c >= the largest
+// key norm.  Distances are only compared, so everything is kept times c: the key itself plus ONE
+// more coordinate a(k) = sqrt(c^2 - ||k||^2), stored as bf16 beside the keys; c^2 is the largest
+// squared norm of the unit's prefill keys (a later key with a larger norm gets a(k) = 0).
+// Pass 1: squared norms (16 lanes per key, fixed summation order) and their maximum per unit;
+// pass 2: the extra coordinate.
+__device__ inline float key_sqnorm16(const uint4 &w) {  // this lane's 8 dims; summed over the 16-lane row
+    float t = 0.f;
+    t += bf16_lo(w.x) * bf16_lo(w.x); t += bf16_hi(w.x) * bf16_hi(w.x);
+    t += bf16_lo(w.y) * bf16_lo(w.y); t += bf16_hi(w.y) * bf16_hi(w.y);
+    t += bf16_lo(w.z) * bf16_lo(w.z); t += bf16_hi(w.z) * bf16_hi(w.z);
+    t += bf16_lo(w.w) * bf16_lo(w.w); t += bf16_hi(w.w) * bf16_hi(w.w);
+    return row16_sum(t);
+}
+__device__ inline bf16_t key_extra_coordinate(float c2, float n2) { return f32_to_bf16(sqrtf(fmaxf(c2 - n2, 0.f))); }
+
+__global__ __launch_bounds__(256) void key_norms_kernel(Dev d, const bf16_t *__restrict__ K, int n, float *n2_out) {
+    const int u = blockIdx.y, row = threadIdx.x >> 4, ch = threadIdx.x & 15;
+    const int i = blockIdx.x * 16 + row;
+    float n2 = 0.f;
+    if (i < n) n2 = key_sqnorm16(((const uint4 *)(K + ((size_t)u * n + i) * kD))[ch]);
+    if (i < n && ch == 0) {
+        n2_out[(size_t)u * d.max_tokens + i] = n2;
+        atomicMax((unsigned int *)d.c2 + u, __float_as_uint(n2));  // (non-negative floats order like their bits)
+    }
+}
+__global__ __launch_bounds__(256) void key_aug_kernel(Dev d, int n, const float *n2_in) {
+    const int u = blockIdx.y, i = blockIdx.x * 256 + threadIdx.x;
+    if (i < n) d.kaug[(size_t)u * d.max_tokens + i] = key_extra_coordinate(d.c2[u], n2_in[(size_t)u * d.max_tokens + i]);
+}
+__global__ void fill_f32_kernel(float *p, int n, float v) {
+    const int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n) p[i] = v;
+}
+
+void launch_key_aug(const Dev &d, const bf16_t *K, int n, hipStream_t st) {
+    float *n2 = (float *)d.order;  // (free until the first sort)
+    hipLaunchKernelGGL(fill_f32_kernel, dim3((d.U + 255) / 256), dim3(256), 0, st, d.c2, d.U, 0.f);
+    hipLaunchKernelGGL(key_norms_kernel, dim3((n + 15) / 16, d.U), dim3(256), 0, st, d, K, n, n2);
+    hipLaunchKernelGGL(key_aug_kernel, dim3((n + 255) / 256, d.U), dim3(256), 0, st, d, n, n2);
+}
+
+// ------------------------------------------------------------------------------------------------
 // Initial centroids = the promoted keys (Alg. 2, "random promotion" with an exact count): cluster c
 // of unit u starts at key init_idx[u][c], or, without a list, at a hashed position inside the c-th
 // of C equal strata of the sequence (distinct by construction).  One wave per centroid row; rows
@@ -34,6 +77,7 @@ __global__ __launch_bounds__(64) void init_centroids_kernel(Dev d, const bf16_t 
         if (lane == 0) {
             d.cnorm[cur][(size_t)u * d.Cpad + c] = INFINITY;
             d.cnorm[cur ^ 1][(size_t)u * d.Cpad + c] = INFINITY;
+            if (d.tk) d.caug[cur][(size_t)u * d.Cpad + c] = d.caug[cur ^ 1][(size_t)u * d.Cpad + c] = 0;
         }
         return;
     }
@@ -49,8 +93,15 @@ __global__ __launch_bounds__(64) void init_centroids_kernel(Dev d, const bf16_t 
     const float lo = bf16_lo(w), hi = bf16_hi(w);
     cb0[lane] = w;
     ((float2 *)(d.centroid + ((size_t)u * d.C + c) * kD))[lane] = make_float2(lo, hi);
-    const float nn = wave_sum(lo * lo + hi * hi);
+    float nn = wave_sum(lo * lo + hi * hi);
     if (lane == 0) {
+        if (d.tk) {  // the promoted key's extra coordinate
+            const bf16_t a = d.kaug[(size_t)u * d.max_tokens + idx];
+            const float af = bf16_to_f32(a);
+            d.caug[cur][(size_t)u * d.Cpad + c] = a;
+            d.cent_aug[(size_t)u * d.C + c] = af;
+            nn += af * af;
+        }
         d.cnorm[cur][(size_t)u * d.Cpad + c] = nn;
         d.init_idx[(size_t)u * d.C + c] = idx;
     }
@@ -171,12 +222,17 @@ __device__ long long ice_prof_w[128];
 #define ICE_BSTAMP(i) do { } while (0)
 #define ICE_WSTAMP(t, i) do { } while (0)
 #endif
-constexpr int kKeyStride = 136;  // bf16 elements per LDS key row (128 + 8 padding)
+// bf16 elements per LDS key row: 128 + 8 padding; with the extra coordinate of the transformed keys
+// 144 (one more 16-wide step of the contraction: the coordinate and 15 zeros) + 8 padding.  Both
+// strides keep the 32-row operand reads free of bank conflicts (68 and 76 dwords).
+__host__ __device__ constexpr int key_stride(bool aug) { return aug ? 152 : 136; }
 
-template <int CT, int CW>
+template <int CT, int CW, bool AUG>
 __global__ __launch_bounds__(512) void assign_kernel(Dev d, const bf16_t *__restrict__ K, int n, int cur,
                                                       int keys_per_wg, int zsplit) {
     constexpr int KW = 8 / CW;
+    constexpr int kKeyStride = key_stride(AUG);
+    constexpr int KS = AUG ? 9 : 8;  // 16-wide steps of the contraction
     extern __shared__ __align__(16) char smem[];
     bf16_t *keys = (bf16_t *)smem;                                   // [2][256][kKeyStride]
     u64 *best = (u64 *)(smem + 2 * kAssignTile * kKeyStride * 2);    // [2][256]
@@ -222,6 +278,7 @@ __global__ __launch_bounds__(512) void assign_kernel(Dev d, const bf16_t *__rest
     }
 
     uint4 stage[8];
+    uint32_t stage_aug = 0;  // (AUG) extra coordinate of key `tid` of the tile, threads 0..255
     auto load_tile = [&](int t) {
         const int base = k0 + t * kAssignTile;
 #pragma unroll
@@ -230,12 +287,23 @@ __global__ __launch_bounds__(512) void assign_kernel(Dev d, const bf16_t *__rest
             const int key = base + row;
             stage[i] = key < kend ? ((const uint4 *)(Ku + (size_t)key * kD))[ch] : make_uint4(0, 0, 0, 0);
         }
+        if constexpr (AUG) {
+            const int key = base + tid;
+            stage_aug = tid < kAssignTile && key < kend ? d.kaug[(size_t)u * d.max_tokens + key] : 0u;
+        }
     };
     auto store_tile = [&](int buf) {
 #pragma unroll
         for (int i = 0; i < 8; ++i) {
             const int id = tid + 512 * i, row = id >> 4, ch = id & 15;
             *(uint4 *)(keys + ((size_t)buf * kAssignTile + row) * kKeyStride + ch * 8) = stage[i];
+        }
+        if constexpr (AUG) {
+            if (tid < kAssignTile) {
+                bf16_t *dst = keys + ((size_t)buf * kAssignTile + tid) * kKeyStride + kD;
+                *(uint4 *)dst = make_uint4(stage_aug, 0, 0, 0);
+                *(uint4 *)(dst + 8) = make_uint4(0, 0, 0, 0);
+            }
         }
     };
 
@@ -245,15 +313,23 @@ __global__ __launch_bounds__(512) void assign_kernel(Dev d, const bf16_t *__rest
         const int id = tid + 512 * i, row = id >> 4, ch = id & 15;
         *(uint4 *)(keys + (size_t)row * kKeyStride + ch * 8) = cst[i];
     }
+    if constexpr (AUG) {
+        if (tid < R) {  // the centroids' extra coordinate, then 15 zeros
+            const uint32_t a = crow0 + tid < d.Cpad ? d.caug[cur][(size_t)u * d.Cpad + crow0 + tid] : 0u;
+            bf16_t *dst = keys + (size_t)tid * kKeyStride + kD;
+            *(uint4 *)dst = make_uint4(a, 0, 0, 0);
+            *(uint4 *)(dst + 8) = make_uint4(0, 0, 0, 0);
+        }
+    }
     if (tid < 2 * kAssignTile) best[tid] = 0ull;
     __syncthreads();
     // centroid operand, resident for the whole kernel
-    bf16x8 A[CT][8];
+    bf16x8 A[CT][KS];
 #pragma unroll
     for (int ct = 0; ct < CT; ++ct) {
         const bf16_t *crow = keys + (size_t)((cw * CT + ct) * 32 + col) * kKeyStride + half * 8;
 #pragma unroll
-        for (int ks = 0; ks < 8; ++ks) A[ct][ks] = __builtin_bit_cast(bf16x8, *(const uint4 *)(crow + ks * 16));
+        for (int ks = 0; ks < KS; ++ks) A[ct][ks] = __builtin_bit_cast(bf16x8, *(const uint4 *)(crow + ks * 16));
     }
     __syncthreads();  // every wave holds its fragments before the first key tile overwrites them
     if (ntiles > 0) store_tile(0);
@@ -273,18 +349,18 @@ __global__ __launch_bounds__(512) void assign_kernel(Dev d, const bf16_t *__rest
         // vector operations fit under one MFMA, which is why the index half of the argmax lives
         // in scalar lane masks.  The key operand of a sub-tile is read from LDS one sub-tile ahead.
         constexpr int NSLOT = NSUB * CT;
-        bf16x8 B[2][8];
-        auto load_b = [&](int i, bf16x8 (&dst)[8]) {
+        bf16x8 B[2][KS];
+        auto load_b = [&](int i, bf16x8 (&dst)[KS]) {
             const bf16_t *krow = keys + ((size_t)buf * kAssignTile + (kw + i * KW) * 32 + col) * kKeyStride + half * 8;
 #pragma unroll
-            for (int ks = 0; ks < 8; ++ks) dst[ks] = __builtin_bit_cast(bf16x8, *(const uint4 *)(krow + ks * 16));
+            for (int ks = 0; ks < KS; ++ks) dst[ks] = __builtin_bit_cast(bf16x8, *(const uint4 *)(krow + ks * 16));
         };
         f32x16 acc[2];
         auto chain = [&](int j, f32x16 &dst) {
             const int i = j / CT, ct = j % CT;
             dst = seed[ct];
 #pragma unroll
-            for (int ks = 0; ks < 8; ++ks)
+            for (int ks = 0; ks < KS; ++ks)
                 dst = __builtin_amdgcn_mfma_f32_32x32x16_bf16(A[ct][ks], B[i & 1][ks], dst, 0, 0, 0);
         };
         load_b(0, B[0]);
@@ -376,15 +452,20 @@ void launch_assign(const Dev &d, const bf16_t *K, int n, int cur, hipStream_t st
 #endif
     while ((long long)((n + keys_per_wg - 1) / keys_per_wg) * zsplit * d.U > wg_target && keys_per_wg < kpw_max) keys_per_wg *= 2;
     dim3 grid((n + keys_per_wg - 1) / keys_per_wg, zsplit, d.U);
-    const size_t lds = 2 * kAssignTile * kKeyStride * 2 + 2 * kAssignTile * 8;
+    const size_t lds = 2 * kAssignTile * key_stride(d.tk != 0) * 2 + 2 * kAssignTile * 8;
     if (zsplit > 1) {
         const size_t tot = (size_t)d.U * d.max_tokens;
         hipLaunchKernelGGL(fill_u64_kernel, dim3(1024), dim3(256), 0, st, d.packed, tot, 0ull);
     }
+#define ICE_ASSIGN_A(ct, cw, aug)                                                                   \
+    do {                                                                                            \
+        (void)hipFuncSetAttribute((const void *)assign_kernel<ct, cw, aug>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds); \
+        hipLaunchKernelGGL((assign_kernel<ct, cw, aug>), grid, dim3(512), lds, st, d, K, n, cur, keys_per_wg, zsplit); \
+    } while (0)
 #define ICE_ASSIGN(ct, cw)                                                                          \
     do {                                                                                            \
-        (void)hipFuncSetAttribute((const void *)assign_kernel<ct, cw>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds); \
-        hipLaunchKernelGGL((assign_kernel<ct, cw>), grid, dim3(512), lds, st, d, K, n, cur, keys_per_wg, zsplit);       \
+        if (d.tk) ICE_ASSIGN_A(ct, cw, true);                                                       \
+        else ICE_ASSIGN_A(ct, cw, false);                                                           \
     } while (0)
     if (CT == 1) ICE_ASSIGN(1, 1);
     else if (CW == 1) ICE_ASSIGN(2, 1);
@@ -392,6 +473,7 @@ void launch_assign(const Dev &d, const bf16_t *K, int n, int cur, hipStream_t st
     else if (CW == 4) ICE_ASSIGN(2, 4);
     else ICE_ASSIGN(2, 8);
 #undef ICE_ASSIGN
+#undef ICE_ASSIGN_A
 }
 
 // ------------------------------------------------------------------------------------------------
@@ -593,6 +675,22 @@ __global__ __launch_bounds__(256) void means_kernel(Dev d, const bf16_t *__restr
         nn += f0 * f0 + f1 * f1;
     }
     nn = row16_sum(nn);
+    if (d.tk) {
+        // the centroid's extra coordinate: mean of the members' extra coordinates (lane-strided partial
+        // sums in member order, then the fixed wave reduction)
+        float part = 0.f;
+        for (int r = lane; r < cnt; r += 64) part += bf16_to_f32(d.kaug[(size_t)u * d.max_tokens + ord[r]]);
+        const float asum = wave_sum(part);
+        const float e = cnt > 0 ? asum / (float)cnt : d.cent_aug[(size_t)u * d.C + c];
+        const bf16_t eb = f32_to_bf16(e);
+        const float ef = bf16_to_f32(eb);
+        if (lane == 0) {
+            d.csum_aug[(size_t)u * d.C + c] = asum;
+            d.cent_aug[(size_t)u * d.C + c] = e;
+            d.caug[cur ^ 1][(size_t)u * d.Cpad + c] = eb;
+        }
+        nn += ef * ef;
+    }
     if (g == 0) {
         float *sum = d.cluster_sum + ((size_t)u * d.C + c) * kD + ch * 8;
         ((float4 *)sum)[0] = make_float4(acc[0], acc[1], acc[2], acc[3]);

@@ -28,6 +28,13 @@ struct Dev {
     int *n_tokens;              // [U] device mirror of the token count (page_pos of inserts)
     bf16_t *cent_bf16[2];       // [U][Cpad][128] double buffer: [cur] is live, [cur^1] previous
     float *cnorm[2];            // [U][Cpad] squared norms of cent_bf16 (+inf in the padding)
+    // optional extra coordinate of the clustering geometry (tk != 0): keys and centroids carry one
+    // more dimension, see ice_set_geometry
+    int tk;
+    bf16_t *kaug;               // [U][max_tokens] extra coordinate of every token, by position
+    bf16_t *caug[2];            // [U][Cpad] extra coordinate of the bf16 centroids (double buffer as cent_bf16)
+    float *cent_aug, *csum_aug; // [U][C] its fp32 mean and running sum
+    float *c2;                  // [U] squared radius c^2 of the key transformation
     // build scratch
     int *init_idx;              // [U][C]
     int *assign;                // [U][max_tokens]
@@ -50,6 +57,7 @@ struct Host {
     bool built;
     int n_tokens;    // per unit
     int cur;         // live centroid buffer
+    int geometry;    // 0: distances on the raw keys; 1: on the transformed keys (one more coordinate)
 };
 
 __host__ __device__ inline int round_up(int x, int m) { return (x + m - 1) / m * m; }
@@ -58,6 +66,7 @@ __host__ __device__ inline int round_up(int x, int m) { return (x + m - 1) / m *
 void launch_init_centroids(const Dev &d, const bf16_t *K, int n, const int *init_idx_or_null,
                            uint64_t seed, int cur, hipStream_t st);
 void launch_load_centroids(const Dev &d, const bf16_t *cent, int cur, hipStream_t st);
+void launch_key_aug(const Dev &d, const bf16_t *K, int n, hipStream_t st);
 void launch_assign(const Dev &d, const bf16_t *K, int n, int cur, hipStream_t st);
 void launch_sort(const Dev &d, int n, float *best_out_or_null, int *assign_out_or_null, hipStream_t st);
 void launch_means(const Dev &d, const bf16_t *K, int n, int cur, hipStream_t st);

@@ -785,3 +785,87 @@ def test_selection_refined_by_best_key(kw, budget, n_probe, n_refine):
     assert ties == 0
     with pytest.raises(Exception):
         ix.select_hier(up(q), budget, n_probe, n_refine=max(1, budget // w.page_size - 1) if budget // w.page_size > 1 else -1)
+
+
+# ----------------------------------------------------------------------------------------- transformed keys
+@pytest.mark.gpu
+@pytest.mark.parametrize("kw", [
+    dict(n_tokens=4096, n_clusters=32, n_kv_heads=2, n_components=32),
+    dict(n_tokens=5003, n_clusters=100, n_kv_heads=3, n_components=40),
+    dict(n_tokens=2500, n_clusters=24, n_kv_heads=2, page_size=32, n_components=12),
+    dict(n_tokens=6000, n_clusters=600, n_kv_heads=2, n_components=200),               # two centroid slices
+    dict(n_tokens=700, n_clusters=1, n_kv_heads=1),
+])
+def test_build_on_transformed_keys(kw):
+    """Clustering geometry of Eq. 2: every key carries the extra coordinate sqrt(c^2 - ||k||^2).  The
+    oracle clusters the (d+1)-dimensional rows; each stage is checked on the GPU's own previous stage."""
+    from paper_2604_10539_amd import ICE_GEOMETRY_TRANSFORMED, IceIndex
+    T = 3
+    w = datagen.small(**kw)
+    K, V = datagen.keys_values(w)
+    # mixed norms, so that the extra coordinate matters
+    U, n, C, s = w.batch * w.n_kv_heads, w.n_tokens, w.n_clusters, w.page_size
+    K = K.reshape(U, n, D).copy()
+    K[:, ::3] = narrow((1.7 * widen(K[:, ::3])).astype(np.float32))
+    V = V.reshape(U, n, D)
+    idx = datagen.init_indices(w).reshape(U, C)
+    ix = IceIndex(w.batch, w.n_kv_heads, w.group_size, n, s, C, kmeans_iters=T, init_idx=up(idx.reshape(w.batch, w.n_kv_heads, C)),
+                  geometry=ICE_GEOMETRY_TRANSFORMED)
+    K4 = K.reshape(w.batch, w.n_kv_heads, n, D)
+    ix.build_index(up(K4), up(V.reshape(K4.shape)))
+    ex, geo = export_np(ix), {k: down(v) for k, v in ix.export_geometry().items()}
+    # (a) the extra coordinate itself
+    kf = widen(K).astype(np.float64)
+    n2 = (kf ** 2).sum(-1)
+    np.testing.assert_allclose(geo["radius_sq"], n2.max(-1), rtol=2e-6)
+    a_gpu = widen(geo["key_extra"][:, :n]).astype(np.float64)
+    want2 = np.maximum(geo["radius_sq"].astype(np.float64)[:, None] - n2, 0)
+    assert np.all(np.abs(a_gpu ** 2 - want2) <= 2.0 ** -6 * want2 + 1e-5 * geo["radius_sq"].max())
+    Ka = orc.augment(K, geo["key_extra"][:, :n])                       # [U, n, 129], the GPU's own coordinate
+    assign = ex["assign"][:, :n]
+    differ_from_raw = 0
+    for u in range(U):
+        # (b) last assignment against the augmented bf16 centroids it was computed from
+        mub = np.concatenate([ex["assign_centroid_bf16"][u, :C], geo["assign_centroid_extra_bf16"][u, :C, None]], -1)
+        _check_assign(Ka[u], mub, assign[u], "transformed build u=%d" % u)
+        a_raw, _, _ = orc.assign(K[u], ex["assign_centroid_bf16"][u, :C])
+        differ_from_raw += int((a_raw != assign[u]).sum())
+        # (c) means of the GPU's own assignment, extra coordinate included
+        mu, ssum, cnt = orc.means(Ka[u], assign[u], C, widen(mub))
+        assert np.array_equal(ex["cluster_cnt"][u], cnt)
+        live = cnt > 0
+        np.testing.assert_allclose(ex["cluster_sum"][u], ssum[:, :D], rtol=1e-5, atol=1e-4)
+        np.testing.assert_allclose(ex["centroid"][u][live], mu[live, :D], rtol=1e-5, atol=1e-5)
+        np.testing.assert_allclose(geo["cluster_sum_extra"][u], ssum[:, D], rtol=1e-5, atol=1e-4)
+        np.testing.assert_allclose(geo["centroid_extra"][u][live], mu[live, D], rtol=1e-5, atol=1e-5)
+    if C > 1:
+        assert differ_from_raw > 0, "the extra coordinate never mattered: the case is vacuous"
+    # (d) the page layout is the plain one for that assignment
+    o = orc.OracleIndex(U, w.group_size, s, C, n)
+    o.paginate(K, V, assign)
+    assert np.array_equal(ex["n_pages"], o.n_pages)
+    for name in ("page_cluster", "page_fill", "page_pos", "cluster_tail"):
+        assert np.array_equal(ex[name], getattr(o, name)), name
+    for u in range(U):
+        npg = o.n_pages[u]
+        assert np.array_equal(ex["rep"][u, :npg], o.rep[u, :npg])
+    # (e) the whole iteration: objective close to the oracle's run on the augmented rows
+    for u in range(U):
+        a_o, mu_o, _, _, _ = orc.lloyd(Ka[u], idx[u], T)
+        kaf = widen(Ka[u]).astype(np.float64)
+        cen = np.concatenate([ex["centroid"][u], geo["centroid_extra"][u][:, None]], -1).astype(np.float64)
+        j_gpu = ((kaf - cen[assign[u]]) ** 2).sum()
+        j_orc = ((kaf - mu_o.astype(np.float64)[a_o]) ** 2).sum()
+        assert abs(j_gpu - j_orc) <= 5e-3 * j_orc, (j_gpu, j_orc)
+    # selection and attention work on it as on any index
+    q = datagen.queries(w)
+    ids, n_sel, scores = ix.select(up(q), 128)
+    _compare_select(oracle_from_export(ix, ex), q, 128, down(ids), down(n_sel), down(scores))
+    # a raw rebuild of the same object gives back the raw clustering
+    from paper_2604_10539_amd import ICE_GEOMETRY_RAW, ice_set_geometry
+    ice_set_geometry(ix.handle, ICE_GEOMETRY_RAW)
+    ix.build_index(up(K4), up(V.reshape(K4.shape)))
+    assert ix.export_geometry() is None
+    ex2 = export_np(ix)
+    for u in range(U):
+        _check_assign(K[u], ex2["assign_centroid_bf16"][u, :C], ex2["assign"][u, :n], "raw rebuild u=%d" % u)

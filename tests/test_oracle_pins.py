@@ -676,6 +676,67 @@ def test_attending_by_token_position_equals_attending_by_page():
         np.testing.assert_allclose(other[u], ref, rtol=0, atol=2e-6)
 
 
+# ----------------------------------------------------------------------------- transformed keys (Eq. 2)
+def test_transformed_key_distance_identity_and_unit_sphere():
+    """c T_K(k) = [k, a] lies on the sphere of radius c, and squared distances between transformed keys are
+    2 c^2 - 2 k_i.k_j - 2 a_i a_j (up to the bf16 rounding of a, which the identity is checked without)."""
+    rng = np.random.default_rng(91)
+    K = _rand_bits(rng, (2, 300, D), scale=2.0)
+    extra, c2 = orc.key_extra_coordinate(K)
+    kf = widen(K).astype(np.float64)
+    n2 = (kf ** 2).sum(-1)
+    np.testing.assert_allclose(c2, n2.max(-1))
+    a = np.sqrt(np.maximum(c2[:, None] - n2, 0))
+    np.testing.assert_allclose(widen(extra), a, rtol=2 ** -8, atol=1e-30)          # bf16 RNE of a
+    T = np.concatenate([kf, a[..., None]], -1)
+    np.testing.assert_allclose((T ** 2).sum(-1), np.broadcast_to(c2[:, None], n2.shape), rtol=1e-12)
+    i, j = rng.integers(0, 300, 50), rng.integers(0, 300, 50)
+    d2 = ((T[0, i] - T[0, j]) ** 2).sum(-1)
+    np.testing.assert_allclose(d2, 2 * c2[0] - 2 * (kf[0, i] * kf[0, j]).sum(-1) - 2 * a[0, i] * a[0, j], atol=1e-9)
+    # a key beyond the radius (inserted later) gets 0
+    far = narrow((4.0 * widen(K[:, :1])).astype(np.float32))
+    assert np.all(orc.key_extra_coordinate(far, c2)[0] == 0)
+
+
+def test_transformed_keys_with_equal_norms_cluster_like_raw_keys():
+    """When every key has the same norm the extra coordinate is the same for all keys and centroids'
+    extra coordinates cancel out of every comparison: Lloyd on the transformed keys = Lloyd on the raw keys.
+    (Keys are axis-aligned +-r vectors so that the norms are exactly equal in bf16.)"""
+    rng = np.random.default_rng(92)
+    n, C = 400, 6
+    K = np.zeros((n, D), np.float32)
+    K[np.arange(n), rng.integers(0, D, n)] = 3.0
+    K[np.arange(n), rng.integers(0, D, n)] += 4.0 * (rng.integers(0, 2, n) * 2 - 1)   # |k|^2 in {25, 49, 1}: not equal yet
+    K = K / np.linalg.norm(K, axis=1, keepdims=True)                                 # unit norm in fp32 ...
+    Kb = narrow(K * 8.0)[None]                                                       # ... only nearly in bf16
+    extra, c2 = orc.key_extra_coordinate(Kb)
+    extra[:] = extra.max()                                                           # make the case exact: same a for all
+    init = rng.choice(n, C, replace=False).astype(np.int32)
+    a_raw, mu_raw, _, cnt_raw, _ = orc.lloyd(Kb[0], init, 4)
+    a_tk, mu_tk, _, cnt_tk, _ = orc.lloyd(orc.augment(Kb, extra)[0], init, 4)
+    assert np.array_equal(a_raw, a_tk) and np.array_equal(cnt_raw, cnt_tk)
+    np.testing.assert_allclose(mu_tk[:, :D], mu_raw, rtol=0, atol=0)
+    live = cnt_tk > 0
+    np.testing.assert_allclose(mu_tk[live, D], widen(extra[0, :1])[0], rtol=1e-6)
+
+
+def test_transformed_key_assignment_is_nearest_neighbour_in_d_plus_1():
+    """The oracle's assignment on augmented rows is the exhaustive nearest neighbour between transformed
+    keys and augmented centroids (brute force in d+1 dimensions), and it differs from the raw one when norms vary."""
+    rng = np.random.default_rng(93)
+    K = _rand_bits(rng, (1, 500, D), scale=1.0)
+    K[0, ::3] = narrow(3.0 * widen(K[0, ::3]))                                        # mixed norms
+    extra, _ = orc.key_extra_coordinate(K)
+    Ka = orc.augment(K, extra)[0]
+    mu = Ka[rng.choice(500, 12, replace=False)]
+    a, best, _ = orc.assign(Ka, mu)
+    kf, mf = widen(Ka).astype(np.float64), widen(mu).astype(np.float64)
+    dist = ((kf[:, None, :] - mf[None, :, :]) ** 2).sum(-1)
+    assert np.array_equal(a, dist.argmin(1).astype(np.int32))
+    a_raw, _, _ = orc.assign(K[0], mu[:, :D].copy())
+    assert (a != a_raw).sum() > 0
+
+
 # ----------------------------------------------------------------------------- change detector
 def test_oracle_still_gives_the_stored_small_case():
     """tests/golden/oracle_small_case.json was written by tests/golden/write_oracle_fixture.py from the
