@@ -125,8 +125,8 @@ def main():
     build_ms_batched = e0.elapsed_time(e1)
     assign_flop_round = 2.0 * n * C * D * H * L
 
-    def build_ms(layers_, T_, K_, V_, init_):
-        ix = IceIndex(layers_, H, G, max_tokens, s, C, kmeans_iters=T_, init_idx=init_, device=dev)
+    def build_ms(layers_, T_, K_, V_, init_, geometry=0):
+        ix = IceIndex(layers_, H, G, max_tokens, s, C, kmeans_iters=T_, init_idx=init_, device=dev, geometry=geometry)
         ix.build_index(K_, V_)
         torch.cuda.synchronize()
         a, b = ev(), ev()
@@ -139,6 +139,8 @@ def main():
     # one Lloyd round (assign + sort + means) = (build with 5 rounds - build with 1 round) / 4
     round_ms_layer = (build_ms(1, 5, K[0], V[0], init[0].contiguous()) - build_ms(1, 1, K[0], V[0], init[0].contiguous())) / 4
     round_ms_batched = (build_ms(L, 5, K, V, init.contiguous()) - build_ms(L, 1, K, V, init.contiguous())) / 4
+    # the same on the transformed keys of Eq. 2 (one more coordinate: a ninth MFMA step per chain)
+    round_ms_batched_tk = (build_ms(L, 5, K, V, init.contiguous(), 1) - build_ms(L, 1, K, V, init.contiguous(), 1)) / 4
     n_pages = batched.export()["n_pages"].cpu().numpy().astype(np.int64)              # [256]
     # two more copies of the batched index (same contents, other addresses): the timed loop rotates over
     # the three, 3 x 180 MB of lines touched per round against 256 MB of memory-side cache, so every
@@ -483,6 +485,7 @@ def main():
                        "round_us_one_layer": round_ms_layer * 1e3, "round_us_batched_32_layers": round_ms_batched * 1e3,
                        "round_TFLOPs_one_layer": assign_flop_round / L / (round_ms_layer * 1e-3) / 1e12,
                        "round_TFLOPs_batched": assign_flop_round / (round_ms_batched * 1e-3) / 1e12,
+                       "round_us_batched_transformed_keys": round_ms_batched_tk * 1e3,
                        "note": "a round is assign (MFMA) + counting sort + means; TFLOP/s counts the assign flops only, "
                                "so it is a lower bound on the assign kernel's own rate (see profiles/ for that)",
                        "assign_TFLOPs_lower_bound": assign_flop_round * T / (build_ms_batched * 1e-3) / 1e12,

@@ -25,16 +25,6 @@ __device__ inline uint64_t splitmix64(uint64_t x) {
 // squared norm of the unit's prefill keys (a later key with a larger norm gets a(k) = 0).
 // Pass 1: squared norms (16 lanes per key, fixed summation order) and their maximum per unit;
 // pass 2: the extra coordinate.
-__device__ inline float key_sqnorm16(const uint4 &w) {  // this lane's 8 dims; summed over the 16-lane row
-    float t = 0.f;
-    t += bf16_lo(w.x) * bf16_lo(w.x); t += bf16_hi(w.x) * bf16_hi(w.x);
-    t += bf16_lo(w.y) * bf16_lo(w.y); t += bf16_hi(w.y) * bf16_hi(w.y);
-    t += bf16_lo(w.z) * bf16_lo(w.z); t += bf16_hi(w.z) * bf16_hi(w.z);
-    t += bf16_lo(w.w) * bf16_lo(w.w); t += bf16_hi(w.w) * bf16_hi(w.w);
-    return row16_sum(t);
-}
-__device__ inline bf16_t key_extra_coordinate(float c2, float n2) { return f32_to_bf16(sqrtf(fmaxf(c2 - n2, 0.f))); }
-
 __global__ __launch_bounds__(256) void key_norms_kernel(Dev d, const bf16_t *__restrict__ K, int n, float *n2_out) {
     const int u = blockIdx.y, row = threadIdx.x >> 4, ch = threadIdx.x & 15;
     const int i = blockIdx.x * 16 + row;

@@ -48,20 +48,28 @@ __global__ __launch_bounds__(kInsertWaves * 64) void insert_kernel(Dev d, const 
         const uint4 kq = ((const uint4 *)kt)[ch];
         const uint32_t kw = ((const uint32_t *)kt)[lane];
         const uint32_t vw = ((const uint32_t *)vt)[lane];
+        // transformed keys (Eq. 2): the new key's extra coordinate joins every comparison
+        bf16_t ka = 0;
+        float kaf = 0.f;
+        if (d.tk) {
+            ka = key_extra_coordinate(d.c2[u], key_sqnorm16(kq));
+            kaf = bf16_to_f32(ka);
+        }
         float bv = INFINITY;
         int bi = 0x7FFFFFFF;
         for (int r0 = wave * 4 + g; r0 < d.C; r0 += 4 * RS) {
             uint4 row[4];
-            float w[4];
+            float w[4], ce[4];
 #pragma unroll
             for (int x = 0; x < 4; ++x) {
                 const int r = r0 + x * RS;
                 row[x] = r < d.C ? ((const uint4 *)(cb + (size_t)r * kD))[ch] : make_uint4(0, 0, 0, 0);
                 w[x] = r < d.C ? wn[r] : INFINITY;
+                ce[x] = d.tk && r < d.C ? bf16_to_f32(d.caug[cur][(size_t)u * d.Cpad + r]) : 0.f;
             }
 #pragma unroll
             for (int x = 0; x < 4; ++x) {  // ascending r: a later row wins only when strictly smaller
-                const float dot = row16_sum(dot8(row[x], kq));
+                const float dot = row16_sum(dot8(row[x], kq)) + kaf * ce[x];
                 const float val = w[x] - 2.0f * dot;
                 if (val < bv) { bv = val; bi = r0 + x * RS; }
             }
@@ -98,7 +106,20 @@ __global__ __launch_bounds__(kInsertWaves * 64) void insert_kernel(Dev d, const 
             const bf16_t b0 = f32_to_bf16(mu.x), b1 = f32_to_bf16(mu.y);
             ((uint32_t *)(d.cent_bf16[cur] + ((size_t)u * d.Cpad + c) * kD))[lane] = (uint32_t)b0 | ((uint32_t)b1 << 16);
             const float f0 = bf16_to_f32(b0), f1 = bf16_to_f32(b1);
-            const float nn = wave_sum(f0 * f0 + f1 * f1);
+            float nn = wave_sum(f0 * f0 + f1 * f1);
+            if (d.tk) {  // the cluster's extra coordinate follows its members' running mean as well
+                const float es = d.csum_aug[cl] + kaf;
+                const float e = es / fc;
+                const bf16_t eb = f32_to_bf16(e);
+                const float ef = bf16_to_f32(eb);
+                nn += ef * ef;
+                if (lane == 0) {
+                    d.csum_aug[cl] = es;
+                    d.cent_aug[cl] = e;
+                    d.caug[cur][(size_t)u * d.Cpad + c] = eb;
+                    d.kaug[(size_t)u * d.max_tokens + tok] = ka;
+                }
+            }
             if (lane == 0) {
                 d.cnorm[cur][(size_t)u * d.Cpad + c] = nn;
                 d.cluster_cnt[cl] = cnt;

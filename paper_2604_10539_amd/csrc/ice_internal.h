@@ -163,4 +163,17 @@ __device__ inline float wave_sum(float x) {
     return x;
 }
 
+// squared norm of a key held 8 dims per lane by a 16-lane row (fixed summation order), and the extra
+// coordinate sqrt(c^2 - ||k||^2) of the transformed keys (Eq. 2), rounded to bf16
+__device__ inline float key_sqnorm16(const uint4 &w) {  // this lane's 8 dims; summed over the 16-lane row
+    float t = 0.f;
+    t += bf16_lo(w.x) * bf16_lo(w.x); t += bf16_hi(w.x) * bf16_hi(w.x);
+    t += bf16_lo(w.y) * bf16_lo(w.y); t += bf16_hi(w.y) * bf16_hi(w.y);
+    t += bf16_lo(w.z) * bf16_lo(w.z); t += bf16_hi(w.z) * bf16_hi(w.z);
+    t += bf16_lo(w.w) * bf16_lo(w.w); t += bf16_hi(w.w) * bf16_hi(w.w);
+    return row16_sum(t);
+}
+__device__ inline bf16_t key_extra_coordinate(float c2, float n2) { return f32_to_bf16(sqrtf(fmaxf(c2 - n2, 0.f))); }
+
+
 }  // namespace ice

@@ -869,3 +869,74 @@ def test_build_on_transformed_keys(kw):
     ex2 = export_np(ix)
     for u in range(U):
         _check_assign(K[u], ex2["assign_centroid_bf16"][u, :C], ex2["assign"][u, :n], "raw rebuild u=%d" % u)
+
+
+@pytest.mark.gpu
+def test_insert_on_transformed_keys():
+    """Insertion with the extra coordinate: the new key's coordinate, the nearest augmented centroid (within
+    the fp32 band), and the running means (one ordered fp32 add and one divide per quantity), step by step
+    against numpy on the GPU's own previous state; a key longer than the radius gets coordinate 0."""
+    from paper_2604_10539_amd import ICE_GEOMETRY_TRANSFORMED, IceIndex
+    w = datagen.small(n_tokens=1500, n_clusters=12, n_kv_heads=2, n_components=8, drift=0.01)
+    K, V = datagen.keys_values(w)
+    U, n, C = 2, w.n_tokens, w.n_clusters
+    K = K.reshape(U, n, D).copy()
+    K[:, ::3] = narrow((1.7 * widen(K[:, ::3])).astype(np.float32))
+    idx = datagen.init_indices(w)
+    steps = 24
+    ix = IceIndex(1, 2, w.group_size, n + steps, 16, C, kmeans_iters=2, init_idx=up(idx), geometry=ICE_GEOMETRY_TRANSFORMED)
+    ix.build_index(up(K.reshape(1, 2, n, D)), up(V))
+    stream = datagen.DecodeStream(w, seed=4)
+    f32 = np.float32
+    for step in range(steps):
+        k, v, _ = stream.next()
+        k = k.reshape(U, D).copy()
+        if step == 5:
+            k = narrow((6.0 * widen(k)).astype(np.float32))          # longer than every prefill key
+        ex0, g0 = export_np(ix), {a: down(b).copy() for a, b in ix.export_geometry().items()}
+        ex0 = {a: (b.copy() if isinstance(b, np.ndarray) else b) for a, b in ex0.items()}
+        ix.insert(up(k.reshape(1, 2, D)), up(v))
+        ex1, g1 = export_np(ix), {a: down(b) for a, b in ix.export_geometry().items()}
+        tok = n + step
+        for u in range(U):
+            a_bits = g1["key_extra"][u, tok]
+            n2 = (widen(k[u]).astype(np.float64) ** 2).sum()
+            want2 = max(float(g0["radius_sq"][u]) - n2, 0.0)
+            assert abs(float(widen(np.array([a_bits]))[0]) ** 2 - want2) <= 2.0 ** -6 * want2 + 1e-5 * g0["radius_sq"][u]
+            if step == 5:
+                assert a_bits == 0
+            # where it went
+            pages = np.argwhere(ex1["page_pos"][u] == tok)
+            assert len(pages) == 1
+            c = int(ex1["page_cluster"][u, pages[0][0]])
+            mub = narrow(np.concatenate([ex0["centroid"][u], g0["centroid_extra"][u][:, None]], -1))
+            ka = np.concatenate([k[u], [a_bits]]).astype(np.uint16)[None]
+            _check_assign(ka, mub, np.array([c], np.int32), "transformed insert step %d u=%d" % (step, u))
+            # running means: one ordered fp32 add, one divide
+            af, kf = widen(np.array([a_bits]))[0], widen(k[u])
+            cnt = ex0["cluster_cnt"][u, c] + 1
+            assert ex1["cluster_cnt"][u, c] == cnt
+            s_new = (ex0["cluster_sum"][u, c] + kf).astype(f32)
+            assert np.array_equal(ex1["cluster_sum"][u, c].view(np.uint32), s_new.view(np.uint32))
+            assert np.array_equal(ex1["centroid"][u, c].view(np.uint32), (s_new / f32(cnt)).astype(f32).view(np.uint32))
+            e_new = f32(g0["cluster_sum_extra"][u, c] + af)
+            assert g1["cluster_sum_extra"][u, c] == e_new and g1["centroid_extra"][u, c] == f32(e_new / f32(cnt))
+            others = np.arange(C) != c
+            assert np.array_equal(ex1["centroid"][u][others], ex0["centroid"][u][others])
+            assert np.array_equal(g1["centroid_extra"][u][others], g0["centroid_extra"][u][others])
+    # a page of tokens at once gives the same state as one by one
+    ix_a = IceIndex(1, 2, w.group_size, n + 16, 16, C, kmeans_iters=2, init_idx=up(idx), geometry=ICE_GEOMETRY_TRANSFORMED)
+    ix_b = IceIndex(1, 2, w.group_size, n + 16, 16, C, kmeans_iters=2, init_idx=up(idx), geometry=ICE_GEOMETRY_TRANSFORMED)
+    for x in (ix_a, ix_b):
+        x.build_index(up(K.reshape(1, 2, n, D)), up(V))
+    toks = [stream.next()[:2] for _ in range(16)]
+    for kk, vv in toks:
+        ix_a.insert(up(kk), up(vv))
+    ix_b.insert_batch(up(np.stack([kk.reshape(U, D) for kk, _ in toks], 1).reshape(1, 2, 16, D)),
+                      up(np.stack([vv.reshape(U, D) for _, vv in toks], 1).reshape(1, 2, 16, D)))
+    ga, gb = ix_a.export_geometry(), ix_b.export_geometry()
+    for name in ("key_extra", "centroid_extra", "cluster_sum_extra", "radius_sq"):
+        assert torch.equal(ga[name], gb[name]), name
+    ea, eb = export_np(ix_a), export_np(ix_b)
+    for name in ("cluster_cnt", "cluster_sum", "centroid", "cluster_tail", "n_pages", "page_fill"):
+        assert np.array_equal(ea[name], eb[name]), name
