@@ -26,14 +26,21 @@ __device__ inline uint64_t splitmix64(uint64_t x) {
 // Pass 1: squared norms (16 lanes per key, fixed summation order) and their maximum per unit;
 // pass 2: the extra coordinate.
 __global__ __launch_bounds__(256) void key_norms_kernel(Dev d, const bf16_t *__restrict__ K, int n, float *n2_out) {
+    // 256 keys per workgroup (16 at a time, 16 lanes each); one atomic maximum per wave
     const int u = blockIdx.y, row = threadIdx.x >> 4, ch = threadIdx.x & 15;
-    const int i = blockIdx.x * 16 + row;
-    float n2 = 0.f;
-    if (i < n) n2 = key_sqnorm16(((const uint4 *)(K + ((size_t)u * n + i) * kD))[ch]);
-    if (i < n && ch == 0) {
-        n2_out[(size_t)u * d.max_tokens + i] = n2;
-        atomicMax((unsigned int *)d.c2 + u, __float_as_uint(n2));  // (non-negative floats order like their bits)
+    float mx = 0.f;
+#pragma unroll 4
+    for (int it = 0; it < 16; ++it) {
+        const int i = blockIdx.x * 256 + it * 16 + row;
+        if (i < n) {
+            const float n2 = key_sqnorm16(((const uint4 *)(K + ((size_t)u * n + i) * kD))[ch]);
+            if (ch == 0) n2_out[(size_t)u * d.max_tokens + i] = n2;
+            mx = fmaxf(mx, n2);
+        }
     }
+    mx = fmaxf(mx, __shfl_xor(mx, 16));
+    mx = fmaxf(mx, __shfl_xor(mx, 32));
+    if ((threadIdx.x & 63) == 0) atomicMax((unsigned int *)d.c2 + u, __float_as_uint(mx));  // (non-negative floats order like their bits)
 }
 __global__ __launch_bounds__(256) void key_aug_kernel(Dev d, int n, const float *n2_in) {
     const int u = blockIdx.y, i = blockIdx.x * 256 + threadIdx.x;
@@ -47,7 +54,7 @@ __global__ void fill_f32_kernel(float *p, int n, float v) {
 void launch_key_aug(const Dev &d, const bf16_t *K, int n, hipStream_t st) {
     float *n2 = (float *)d.order;  // (free until the first sort)
     hipLaunchKernelGGL(fill_f32_kernel, dim3((d.U + 255) / 256), dim3(256), 0, st, d.c2, d.U, 0.f);
-    hipLaunchKernelGGL(key_norms_kernel, dim3((n + 15) / 16, d.U), dim3(256), 0, st, d, K, n, n2);
+    hipLaunchKernelGGL(key_norms_kernel, dim3((n + 255) / 256, d.U), dim3(256), 0, st, d, K, n, n2);
     hipLaunchKernelGGL(key_aug_kernel, dim3((n + 255) / 256, d.U), dim3(256), 0, st, d, n, n2);
 }
 
