@@ -264,11 +264,11 @@ __global__ __launch_bounds__(NW * 64) void decode_step_kernel(Dev d, const bf16_
         sh_pre = 0u;
         sh_tau = 0ull;
     }
-    // ---- phase A: scores of this chunk, 16 pages per v_mfma_f32_16x16x32_bf16 chain.
-    // A operand = the G query rows (rows >= G are zero), B operand = 16 representative rows: lane
-    // (g = lane/16, r = lane%16) reads bytes [64*ks + 16*g, +16) of row r for k-step ks, i.e. one
-    // load instruction fetches a 64-byte piece of each of 16 consecutive 256-byte rows.  Lane r of
-    // row group 0 ends up with the dot products of page r with heads 0..3 (group 1: heads 4..7).
+    // ---- phase A: scores of this chunk, 16 pages per four v_mfma_f32_16x16x32_bf16 in the
+    // split-row form (SplitRow: every load instruction reads whole 128-byte lines, 8 rows x 128
+    // bytes; A operand = the G query rows twice).  Lane (.., c) of the owning row group ends up
+    // with the score of page c of the 16.
+    using SR = SplitRow<G>;
     bf16x8 qa[4];
     {
         const int per = round_up((np_hint + chunks - 1) / chunks, 16 * NW);
@@ -277,13 +277,18 @@ __global__ __launch_bounds__(NW * 64) void decode_step_kernel(Dev d, const bf16_
         constexpr int UNR = 4;
         static_assert(NW * UNR == 4 * NW, "sh_rowmax holds one maximum per (wave, unroll slot)");
         uint4 bb[UNR][4];
+        int word[4];
+#pragma unroll
+        for (int j = 0; j < 4; ++j) word[j] = SR::word(lane, j >> 1, j & 1);
+        const int row8 = ch & 7;
         auto request = [&](int b0, int lim) {
 #pragma unroll
             for (int x = 0; x < UNR; ++x) {
-                const int page = p0 + 16 * (b0 + NW * x) + ch;
-                const uint4 *src = (const uint4 *)(rep + (size_t)page * kD);
+                const int pb = p0 + 16 * (b0 + NW * x);
+                const uint4 *src = (const uint4 *)(rep + (size_t)pb * kD);
 #pragma unroll
-                for (int ks = 0; ks < 4; ++ks) bb[x][ks] = page < lim ? src[ks * 4 + g] : make_uint4(0, 0, 0, 0);
+                for (int j = 0; j < 4; ++j)
+                    bb[x][j] = pb + 8 * (j >> 1) + row8 < lim ? load16_stream(src + word[j]) : make_uint4(0, 0, 0, 0);
             }
         };
         // The first round of representative rows is requested together with the query rows, before
@@ -298,7 +303,10 @@ __global__ __launch_bounds__(NW * 64) void decode_step_kernel(Dev d, const bf16_
         const float invn = 1.0f / fmaxf(sqrtf(nn), 1e-20f);
         float inv[4];
 #pragma unroll
-        for (int v = 0; v < 4; ++v) inv[v] = __shfl(invn, (4 * g + v) & 15);
+        for (int v = 0; v < 4; ++v) inv[v] = __shfl(invn, (4 * SR::head_group(lane) + v) & 15);
+        bf16x8 qs[2];
+        SR::from_plain(qa, lane, qs);
+        const bool owner = SR::owner(lane);
         const int lim = min(np, pend);
         float gmax[UNR];  // running maximum of the scores this lane produced in unroll slot x
 #pragma unroll
@@ -306,17 +314,15 @@ __global__ __launch_bounds__(NW * 64) void decode_step_kernel(Dev d, const bf16_
         while (b0 < nblk) {
 #pragma unroll
             for (int x = 0; x < UNR; ++x) {
-                f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+                f32x4 acc0 = {0.f, 0.f, 0.f, 0.f}, acc1 = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-                for (int ks = 0; ks < 4; ++ks)
-                    acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(qa[ks], __builtin_bit_cast(bf16x8, bb[x][ks]), acc, 0, 0, 0);
-                float sc = -INFINITY;
-#pragma unroll
-                for (int v = 0; v < 4; ++v)
-                    if (4 * g + v < G) sc = fmaxf(sc, acc[v] * inv[v]);
-                if (G > 4) sc = fmaxf(sc, __shfl_xor(sc, 16));
+                for (int t = 0; t < 2; ++t) {
+                    acc0 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(qs[t], __builtin_bit_cast(bf16x8, bb[x][t]), acc0, 0, 0, 0);
+                    acc1 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(qs[t], __builtin_bit_cast(bf16x8, bb[x][2 + t]), acc1, 0, 0, 0);
+                }
+                const float sc = SR::score(acc0, acc1, inv, lane);
                 const int page = p0 + 16 * (b0 + NW * x) + ch;
-                if (g == 0 && page < lim) {
+                if (owner && page < lim) {
                     if (single) sc_lds[page] = __float_as_uint(sc);
                     else __hip_atomic_store(S + page, __float_as_uint(sc), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
                     gmax[x] = fmaxf(gmax[x], sc);
@@ -325,6 +331,7 @@ __global__ __launch_bounds__(NW * 64) void decode_step_kernel(Dev d, const bf16_
             b0 += NW * UNR;
             if (b0 < nblk) request(b0, lim);
         }
+        SR::to_plain(qs, lane, qa);  // the attention below takes the plain operand
         // With one workgroup per unit the selection threshold needs the maxima of 4*NW disjoint
         // groups of scores: group (wave, x) is ready here, for free (the kernel is waiting for HBM).
         if (single) {
@@ -335,6 +342,8 @@ __global__ __launch_bounds__(NW * 64) void decode_step_kernel(Dev d, const bf16_
                 r = fmaxf(r, dpp_f32<0x4E>(r));
                 r = fmaxf(r, dpp_f32<0x141>(r));
                 r = fmaxf(r, dpp_f32<0x140>(r));
+                r = fmaxf(r, __shfl_xor(r, 16));  // (the owners sit in two row groups)
+                r = fmaxf(r, __shfl_xor(r, 32));
                 if (lane == 0) sh_rowmax[wave * 4 + x] = f32_ordered(r);
             }
         }

@@ -59,6 +59,82 @@ __device__ inline void load_query_operand(const bf16_t *q, int u, int lane, bf16
     if (sumsq) *sumsq = nn;
 }
 
+// 16-byte load with the non-temporal hint, for data that one call reads exactly once (the
+// representative rows, the tiles of the selected pages).
+typedef unsigned u32x4 __attribute__((ext_vector_type(4)));
+__device__ inline uint4 load16_stream(const uint4 *p) {
+    const u32x4 v = __builtin_nontemporal_load((const u32x4 *)p);
+    return make_uint4(v.x, v.y, v.z, v.w);
+}
+
+// Split-row form of the scoring contraction.  In the plain form lane (g, c) of a B operand reads
+// 16 bytes of row c at 64*ks + 16*g, so one load instruction touches half a 128-byte line of each of
+// 16 rows.  Here a load instruction covers whole lines: lanes c and c+8 read the two 64-byte halves
+// of a line of row c%8, i.e. column c < 8 of the B operand carries dims [64t, 64t+32) of the row and
+// column c+8 dims [64t+32, 64t+64) (t = 0, 1: two MFMAs per 8 rows, as many as before per byte).
+// The A operand holds every query row twice: row h with the dims of the lower halves, row G+h with
+// those of the upper halves.  Output (row h, column c < 8) and (row G+h, column c+8) are then the
+// two halves of q_h . row_c; the other outputs are discarded.  A pair of 8-row blocks shares one
+// exchange: lanes c < 8 keep the first block, lanes c >= 8 the second, each sends the partner
+// (lane xor kXor) the half it does not keep, and lane (.., c) ends with the scores of row c of the
+// 16 for its heads.
+template <int G>
+struct SplitRow {
+    static_assert(G == 1 || G == 2 || G == 4 || G == 8, "2G query rows must fit the 16 operand rows");
+    static constexpr int kDG = G >= 4 ? G / 4 : 0;  // 16-lane row groups between row h and row G+h
+    static constexpr int kDV = G >= 4 ? 0 : G;      // accumulator slots between them
+    static constexpr int kXor = 8 + 16 * kDG;
+    static constexpr int kHV = G < 4 ? G : 4;       // heads per lane
+
+    // from the plain operand (lane (g, h): dims [32ks + 8g, +8) of q_h, zero rows from G on)
+    __device__ static void from_plain(const bf16x8 (&qa)[4], int lane, bf16x8 (&qs)[2]) {
+        const bool low = (lane & 15) < G;
+#pragma unroll
+        for (int t = 0; t < 2; ++t) {
+            uint4 lo = __builtin_bit_cast(uint4, qa[2 * t]), up = __builtin_bit_cast(uint4, qa[2 * t + 1]);
+            const int src = (lane - G) & 63;
+            up.x = __shfl(up.x, src); up.y = __shfl(up.y, src); up.z = __shfl(up.z, src); up.w = __shfl(up.w, src);
+            qs[t] = __builtin_bit_cast(bf16x8, low ? lo : up);  // (rows from 2G on: zeros of the plain operand)
+        }
+    }
+    __device__ static void to_plain(const bf16x8 (&qs)[2], int lane, bf16x8 (&qa)[4]) {
+        const bool low = (lane & 15) < G;
+        const uint4 zero = make_uint4(0, 0, 0, 0);
+#pragma unroll
+        for (int t = 0; t < 2; ++t) {
+            const uint4 w = __builtin_bit_cast(uint4, qs[t]);
+            uint4 up;
+            const int src = (lane + G) & 63;
+            up.x = __shfl(w.x, src); up.y = __shfl(w.y, src); up.z = __shfl(w.z, src); up.w = __shfl(w.w, src);
+            qa[2 * t] = __builtin_bit_cast(bf16x8, low ? w : zero);
+            qa[2 * t + 1] = __builtin_bit_cast(bf16x8, low ? up : zero);
+        }
+    }
+    // uint4 index inside a 16-row block (rows of 16 uint4) of the load that feeds MFMA t of 8-row
+    // block blk
+    __device__ static int word(int lane, int blk, int t) {
+        const int g = lane >> 4, c = lane & 15;
+        return (8 * blk + (c & 7)) * 16 + 8 * t + 4 * (c >> 3) + g;
+    }
+    // lanes whose result is a row's score: row c of the 16, heads 4 * head_group(lane) + v
+    __device__ static bool owner(int lane) { return (lane >> 4) == ((lane & 8) ? kDG : 0); }
+    __device__ static int head_group(int lane) { return (lane >> 4) - ((lane & 8) ? kDG : 0); }
+    // max over the group's heads of (q_h . row) * inv[v]; acc0 / acc1 = accumulators of the two blocks
+    __device__ static float score(const f32x4 &acc0, const f32x4 &acc1, const float (&inv)[4], int lane) {
+        const bool hi = (lane & 8) != 0;
+        float sc = -INFINITY;
+#pragma unroll
+        for (int v = 0; v < kHV; ++v) {
+            const float a0 = (kDV && hi) ? acc0[(v + kDV) & 3] : acc0[v];
+            const float a1 = (kDV && hi) ? acc1[(v + kDV) & 3] : acc1[v];
+            const float tot = (hi ? a1 : a0) + __shfl_xor(hi ? a0 : a1, kXor);
+            sc = fmaxf(sc, tot * inv[v]);
+        }
+        if (G > 4) sc = fmaxf(sc, __shfl_xor(sc, 16));
+        return sc;
+    }
+};
+
 template <int G, int NW, bool RES, typename PageOf, typename Aside>
 __device__ inline void attend_pages(const Dev &d, int u, const bf16x8 (&qa)[4], PageOf page_of, int ns, Resident res,
                                     float *__restrict__ out, float *red, Aside aside) {
