@@ -296,16 +296,12 @@ __global__ __launch_bounds__(NW * 64) void decode_step_kernel(Dev d, const bf16_
         // kernel starts with one memory round trip, not two.
         int b0 = wave;
         if (b0 < nblk) request(b0, pend);
-        float nn;
-        load_query_operand<G>(q, u, lane, qa, &nn);
-        nn += __shfl_xor(nn, 16);
-        nn += __shfl_xor(nn, 32);  // ||q_h||^2 on every lane with lane%16 == h
-        const float invn = 1.0f / fmaxf(sqrtf(nn), 1e-20f);
+        bf16x8 qs[2];
+        float invn;
+        SR::load_query(q, u, lane, qs, &invn);
         float inv[4];
 #pragma unroll
         for (int v = 0; v < 4; ++v) inv[v] = __shfl(invn, (4 * SR::head_group(lane) + v) & 15);
-        bf16x8 qs[2];
-        SR::from_plain(qa, lane, qs);
         const bool owner = SR::owner(lane);
         const int lim = min(np, pend);
         float gmax[UNR];  // running maximum of the scores this lane produced in unroll slot x
@@ -314,6 +310,7 @@ __global__ __launch_bounds__(NW * 64) void decode_step_kernel(Dev d, const bf16_
         while (b0 < nblk) {
 #pragma unroll
             for (int x = 0; x < UNR; ++x) {
+                if (b0 + NW * x >= nblk) break;  // (wave-uniform)
                 f32x4 acc0 = {0.f, 0.f, 0.f, 0.f}, acc1 = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
                 for (int t = 0; t < 2; ++t) {
@@ -331,7 +328,6 @@ __global__ __launch_bounds__(NW * 64) void decode_step_kernel(Dev d, const bf16_
             b0 += NW * UNR;
             if (b0 < nblk) request(b0, lim);
         }
-        SR::to_plain(qs, lane, qa);  // the attention below takes the plain operand
         // With one workgroup per unit the selection threshold needs the maxima of 4*NW disjoint
         // groups of scores: group (wave, x) is ready here, for free (the kernel is waiting for HBM).
         if (single) {
@@ -366,6 +362,8 @@ __global__ __launch_bounds__(NW * 64) void decode_step_kernel(Dev d, const bf16_
     }
     ICE_STAMP(1);
     ICE_USTAMP(1);
+    // the attention takes the plain query operand; it arrives while the selection runs
+    if (out) load_query_operand<G>(q, u, lane, qa, nullptr);
     // all of a thread's score words are requested first, then checked: one round trip, not E
     auto finish_score = [&](int pid, uint32_t v) -> uint32_t {
         if (single) return v;

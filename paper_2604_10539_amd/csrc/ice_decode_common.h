@@ -73,7 +73,7 @@ __device__ inline uint4 load16_stream(const uint4 *p) {
 // of a line of row c%8, i.e. column c < 8 of the B operand carries dims [64t, 64t+32) of the row and
 // column c+8 dims [64t+32, 64t+64) (t = 0, 1: two MFMAs per 8 rows, as many as before per byte).
 // The A operand holds every query row twice: row h with the dims of the lower halves, row G+h with
-// those of the upper halves.  Output (row h, column c < 8) and (row G+h, column c+8) are then the
+// those of the upper halves (load_query).  Output (row h, column c < 8) and (row G+h, column c+8) are then the
 // two halves of q_h . row_c; the other outputs are discarded.  A pair of 8-row blocks shares one
 // exchange: lanes c < 8 keep the first block, lanes c >= 8 the second, each sends the partner
 // (lane xor kXor) the half it does not keep, and lane (.., c) ends with the scores of row c of the
@@ -86,29 +86,24 @@ struct SplitRow {
     static constexpr int kXor = 8 + 16 * kDG;
     static constexpr int kHV = G < 4 ? G : 4;       // heads per lane
 
-    // from the plain operand (lane (g, h): dims [32ks + 8g, +8) of q_h, zero rows from G on)
-    __device__ static void from_plain(const bf16x8 (&qa)[4], int lane, bf16x8 (&qs)[2]) {
-        const bool low = (lane & 15) < G;
+    // The A operand straight from memory: lane (g, c) holds q_c dims [64t + 8g, +8) for c < G and
+    // q_{c-G} dims [64t + 32 + 8g, +8) for G <= c < 2G (t = 0, 1), zeros from row 2G on.  *inv_norm =
+    // 1 / max(||q_h||, 1e-20) on the lanes with c = h and c = G + h.
+    __device__ static void load_query(const bf16_t *q, int u, int lane, bf16x8 (&qs)[2], float *inv_norm) {
+        const int g = lane >> 4, c = lane & 15;
+        const int upper = c >= G ? 1 : 0, h = c - G * upper;
+        const uint4 *row = (const uint4 *)(q + ((size_t)u * G + h) * kD);
+        float nn = 0.f;
 #pragma unroll
         for (int t = 0; t < 2; ++t) {
-            uint4 lo = __builtin_bit_cast(uint4, qa[2 * t]), up = __builtin_bit_cast(uint4, qa[2 * t + 1]);
-            const int src = (lane - G) & 63;
-            up.x = __shfl(up.x, src); up.y = __shfl(up.y, src); up.z = __shfl(up.z, src); up.w = __shfl(up.w, src);
-            qs[t] = __builtin_bit_cast(bf16x8, low ? lo : up);  // (rows from 2G on: zeros of the plain operand)
+            const uint4 w = c < 2 * G ? row[8 * t + 4 * upper + g] : make_uint4(0, 0, 0, 0);
+            qs[t] = __builtin_bit_cast(bf16x8, w);
+            nn += dot8(w, w);
         }
-    }
-    __device__ static void to_plain(const bf16x8 (&qs)[2], int lane, bf16x8 (&qa)[4]) {
-        const bool low = (lane & 15) < G;
-        const uint4 zero = make_uint4(0, 0, 0, 0);
-#pragma unroll
-        for (int t = 0; t < 2; ++t) {
-            const uint4 w = __builtin_bit_cast(uint4, qs[t]);
-            uint4 up;
-            const int src = (lane + G) & 63;
-            up.x = __shfl(w.x, src); up.y = __shfl(w.y, src); up.z = __shfl(w.z, src); up.w = __shfl(w.w, src);
-            qa[2 * t] = __builtin_bit_cast(bf16x8, low ? w : zero);
-            qa[2 * t + 1] = __builtin_bit_cast(bf16x8, low ? up : zero);
-        }
+        nn += __shfl_xor(nn, 16);
+        nn += __shfl_xor(nn, 32);
+        nn += __shfl_xor(nn, G);  // the other half of the row
+        *inv_norm = 1.0f / fmaxf(sqrtf(nn), 1e-20f);
     }
     // uint4 index inside a 16-row block (rows of 16 uint4) of the load that feeds MFMA t of 8-row
     // block blk

@@ -251,43 +251,48 @@ __global__ __launch_bounds__(NW * 64) void decode_hier_kernel(Dev d, const bf16_
 #pragma unroll
         for (int e = 0; e < EMAX; ++e) pcl[e] = e * NT + tid < np_hint ? pc[e * NT + tid] : -1;
     }
-    // ---- stage 1 loads: 16 centroids per MFMA chain, four chains' rows in flight per wave (rows of
-    // C..Cpad are padding).  The first round is requested together with the query rows, before
-    // anything waits for either.
+    // ---- stage 1 loads: 16 centroids per four MFMAs in the split-row form (SplitRow: whole
+    // 128-byte lines per load instruction), four such blocks in flight per wave (rows of C..Cpad
+    // are padding).  The first round is requested together with the query rows, before anything
+    // waits for either.
+    using SR = SplitRow<G>;
     const bf16_t *cb = d.cent_bf16[cur] + (size_t)u * d.Cpad * kD;
     const int nblk1 = d.Cpad >> 4;
     constexpr int UNR1 = 4;
     uint4 bb1[UNR1][4];
+    int word[4];
+#pragma unroll
+    for (int j = 0; j < 4; ++j) word[j] = SR::word(lane, j >> 1, j & 1);
     auto request1 = [&](int b0) {
 #pragma unroll
         for (int x = 0; x < UNR1; ++x) {
-            const int c = 16 * (b0 + NW * x) + ch;
-            const uint4 *src = (const uint4 *)(cb + (size_t)c * kD);
+            const int c0 = 16 * (b0 + NW * x);  // (Cpad is a multiple of 16: a block is there or not)
+            const uint4 *src = (const uint4 *)(cb + (size_t)c0 * kD);
 #pragma unroll
-            for (int ks = 0; ks < 4; ++ks) bb1[x][ks] = c < d.Cpad ? src[ks * 4 + g] : make_uint4(0, 0, 0, 0);
+            for (int j = 0; j < 4; ++j) bb1[x][j] = c0 < d.Cpad ? load16_stream(src + word[j]) : make_uint4(0, 0, 0, 0);
         }
     };
     request1(wave);
     // the query operand of every scoring MFMA, and 1/||q_h|| where the scores land
-    bf16x8 qa[4];
+    bf16x8 qs[2];
     float inv[4];
     {
-        float nn;
-        load_query_operand<G>(q, u, lane, qa, &nn);
-        nn += __shfl_xor(nn, 16);
-        nn += __shfl_xor(nn, 32);  // ||q_h||^2 on every lane with lane%16 == h
-        const float invn = 1.0f / fmaxf(sqrtf(nn), 1e-20f);
+        float invn;
+        SR::load_query(q, u, lane, qs, &invn);
 #pragma unroll
-        for (int v = 0; v < 4; ++v) inv[v] = __shfl(invn, (4 * g + v) & 15);
+        for (int v = 0; v < 4; ++v) inv[v] = __shfl(invn, (4 * SR::head_group(lane) + v) & 15);
     }
-    // group score of the 16 rows a wave just multiplied: valid on the lanes of row group 0
-    auto group_score = [&](const f32x4 &acc) {
-        float sc = -INFINITY;
+    const bool owner = SR::owner(lane);
+    // group scores of 16 rows whose loads are bw[0..3] (SplitRow::word order): valid on the owner
+    // lanes, lane (.., c) for row c
+    auto group_score = [&](const uint4 (&bw)[4]) {
+        f32x4 acc0 = {0.f, 0.f, 0.f, 0.f}, acc1 = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-        for (int v = 0; v < 4; ++v)
-            if (4 * g + v < G) sc = fmaxf(sc, acc[v] * inv[v]);
-        if (G > 4) sc = fmaxf(sc, __shfl_xor(sc, 16));
-        return sc;
+        for (int t = 0; t < 2; ++t) {
+            acc0 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(qs[t], __builtin_bit_cast(bf16x8, bw[t]), acc0, 0, 0, 0);
+            acc1 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(qs[t], __builtin_bit_cast(bf16x8, bw[2 + t]), acc1, 0, 0, 0);
+        }
+        return SR::score(acc0, acc1, inv, lane);
     };
     for (int i = tid; i < d.Cpad / 32 + 1; i += NT) member[i] = 0u;
     if (tid == 0) sh_ncand = 0;
@@ -296,13 +301,10 @@ __global__ __launch_bounds__(NW * 64) void decode_hier_kernel(Dev d, const bf16_
     for (int b0 = wave; b0 < nblk1;) {
 #pragma unroll
         for (int x = 0; x < UNR1; ++x) {
+            if (b0 + NW * x >= nblk1) break;  // (wave-uniform)
             const int c = 16 * (b0 + NW * x) + ch;
-            f32x4 acc = {0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-            for (int ks = 0; ks < 4; ++ks)
-                acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(qa[ks], __builtin_bit_cast(bf16x8, bb1[x][ks]), acc, 0, 0, 0);
-            const float sc = group_score(acc);
-            if (g == 0 && c < C) comp1[c] = ((u64)f32_ordered(sc) << 32) | (u64)(0xFFFFFFFFu - (uint32_t)c);
+            const float sc = group_score(bb1[x]);
+            if (owner && c < C) comp1[c] = ((u64)f32_ordered(sc) << 32) | (u64)(0xFFFFFFFFu - (uint32_t)c);
         }
         b0 += NW * UNR1;
         if (b0 < nblk1) request1(b0);
@@ -349,33 +351,35 @@ __global__ __launch_bounds__(NW * 64) void decode_hier_kernel(Dev d, const bf16_
     __syncthreads();
     const int ncand = sh_ncand;
     ICE_HSTAMP(4);
-    // ---- stage 2b: their representatives' scores, 16 candidates per MFMA chain (gathered rows),
-    // two chains' rows in flight per wave
+    // ---- stage 2b: their representatives' scores, 16 candidates per block (gathered rows: lanes c
+    // and c+8 read the two halves of a line of candidate 8*blk + c%8), two blocks in flight per wave
     {
         const bf16_t *rep = d.rep + (size_t)u * d.max_pages * kD;
         const int nblk = (ncand + 15) >> 4;
         constexpr int UNR = 2;
+        const int piece = 4 * ((ch >> 3) & 1) + g;  // uint4 inside the 128-byte line
         for (int b0 = wave; b0 < nblk; b0 += NW * UNR) {
             uint4 bb[UNR][4];
             uint32_t pg[UNR];
 #pragma unroll
             for (int x = 0; x < UNR; ++x) {
-                const int j = 16 * (b0 + NW * x) + ch;
+                const int j0 = 16 * (b0 + NW * x), j = j0 + ch;
                 pg[x] = j < ncand ? (uint32_t)comp2[j] : 0u;  // (page 0 stands in past the end; its score is dropped)
-                const uint4 *src = (const uint4 *)(rep + (size_t)pg[x] * kD);
 #pragma unroll
-                for (int ks = 0; ks < 4; ++ks) bb[x][ks] = src[ks * 4 + g];
+                for (int blk = 0; blk < 2; ++blk) {
+                    const int jr = j0 + 8 * blk + (ch & 7);
+                    const uint32_t pr = jr < ncand ? (uint32_t)comp2[jr] : 0u;
+                    const uint4 *src = (const uint4 *)(rep + (size_t)pr * kD);
+                    bb[x][2 * blk] = load16_stream(src + piece);
+                    bb[x][2 * blk + 1] = load16_stream(src + 8 + piece);
+                }
             }
             __builtin_amdgcn_wave_barrier();  // every lane has read its page ids before the entries change
 #pragma unroll
             for (int x = 0; x < UNR; ++x) {
                 const int j = 16 * (b0 + NW * x) + ch;
-                f32x4 acc = {0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-                for (int ks = 0; ks < 4; ++ks)
-                    acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(qa[ks], __builtin_bit_cast(bf16x8, bb[x][ks]), acc, 0, 0, 0);
-                const float sc = group_score(acc);
-                if (g == 0 && j < ncand) comp2[j] = ((u64)f32_ordered(sc) << 32) | (u64)(0xFFFFFFFFu - pg[x]);
+                const float sc = group_score(bb[x]);
+                if (owner && j < ncand) comp2[j] = ((u64)f32_ordered(sc) << 32) | (u64)(0xFFFFFFFFu - pg[x]);
             }
         }
     }
@@ -416,7 +420,7 @@ __global__ __launch_bounds__(NW * 64) void decode_hier_kernel(Dev d, const bf16_
                 pp[y] = x < k2 ? 0xFFFFFFFFu - (uint32_t)sel2[x] : 0u;  // (page 0 stands in past the end)
                 const size_t pg = (size_t)u * d.max_pages + pp[y];
 #pragma unroll
-                for (int t = 0; t < 4; ++t) kb[y][t] = ((const uint4 *)(d.Kp + (pg * s + ch) * kD))[t * 4 + g];
+                for (int t = 0; t < 4; ++t) kb[y][t] = ((const uint4 *)(d.Kp + pg * s * kD))[word[t]];
                 fl[y] = d.page_fill[pg];
             }
 #pragma unroll
@@ -427,19 +431,17 @@ __global__ __launch_bounds__(NW * 64) void decode_hier_kernel(Dev d, const bf16_
                 for (int b0 = 0; b0 < fl[y]; b0 += 16) {
                     if (b0 > 0) {
 #pragma unroll
-                        for (int t = 0; t < 4; ++t) kb[y][t] = ((const uint4 *)(d.Kp + (pg * s + b0 + ch) * kD))[t * 4 + g];
+                        for (int t = 0; t < 4; ++t) kb[y][t] = ((const uint4 *)(d.Kp + (pg * s + b0) * kD))[word[t]];
                     }
-                    f32x4 z = {0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-                    for (int ks = 0; ks < 4; ++ks)
-                        z = __builtin_amdgcn_mfma_f32_16x16x32_bf16(qa[ks], __builtin_bit_cast(bf16x8, kb[y][ks]), z, 0, 0, 0);
-                    const float sc = group_score(z);       // token b0 + ch, on the lanes of row group 0
-                    if (b0 + ch < fl[y]) best = fmaxf(best, sc);
+                    const float sc = group_score(kb[y]);   // token b0 + ch, on the owner lanes
+                    if (owner && b0 + ch < fl[y]) best = fmaxf(best, sc);
                 }
                 best = fmaxf(best, dpp_f32<0xB1>(best));
                 best = fmaxf(best, dpp_f32<0x4E>(best));
                 best = fmaxf(best, dpp_f32<0x141>(best));
                 best = fmaxf(best, dpp_f32<0x140>(best));
+                best = fmaxf(best, __shfl_xor(best, 16));  // (the owners sit in two row groups)
+                best = fmaxf(best, __shfl_xor(best, 32));
                 if (lane == 0 && x < k2) comp3[x] = ((u64)f32_ordered(best) << 32) | (u64)(0xFFFFFFFFu - pp[y]);
             }
         }
@@ -478,6 +480,8 @@ __global__ __launch_bounds__(NW * 64) void decode_hier_kernel(Dev d, const bf16_
             if (sco) sco[pos] = ordered_f32((uint32_t)(mine >> 32));
         }
     };
+    bf16x8 qa[4];
+    if (out) load_query_operand<G>(q, u, lane, qa, nullptr);
     if (out) attend_pages<G, NW, false>(d, u, qa, [=](int x) { return (int)(0xFFFFFFFFu - (uint32_t)win[x]); }, k, Resident{nullptr, nullptr, 0, nullptr, nullptr, 0}, out, red, order_ids);
     else order_ids();
     ICE_HSTAMP(7);
