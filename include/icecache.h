@@ -248,7 +248,7 @@ ice_status_t ice_debug_assign(ice_index_t *idx, const void *K, int32_t n, const 
 
 /* Measured-peak microbenchmarks for the benchmark's roofline context (no method arithmetic):
  *   ice_debug_peak_read  streams `bytes` (multiple of 16, 16-byte aligned device pointer) once with
- *                        16-byte loads; achieved bytes/s = bytes / kernel time.
+ *                        16-byte non-temporal loads; achieved bytes/s = bytes / kernel time.
  *   ice_debug_peak_mfma  runs `iters` rounds of four independent v_mfma_f32_32x32x16_bf16 chains per
  *                        wave on register operands and writes the flop count of the launch to the
  *                        HOST double *flops_out (may be null).

@@ -605,6 +605,10 @@ void launch_sort(const Dev &d, int n, float *best_out, int *assign_out, hipStrea
     hipLaunchKernelGGL(sort_scan_kernel, dim3(d.U), dim3(1024), 0, st, d, n_chunks);
     hipLaunchKernelGGL(sort_rank_kernel, dim3(n_chunks, d.U), dim3(64), lds, st, d, n, n_chunks, nbits);
 }
+// The key rows of one clustering pass are read by assign, then by means (and once more by paginate).
+// While they fit the chip's last-level cache (256 MB) the second reader finds them there; beyond
+// that every pass streams from HBM, and the non-temporal hint is what gets the most out of it.
+static bool keys_exceed_cache(const Dev &d, int n) { return (size_t)d.U * (size_t)n * kD * sizeof(bf16_t) >= ((size_t)256 << 20); }
 
 // ------------------------------------------------------------------------------------------------
 // Centroid update: one wave per cluster gathers its members' key rows (256 contiguous bytes each,
@@ -612,6 +616,7 @@ void launch_sort(const Dev &d, int n, float *best_out, int *assign_out, hipStrea
 // so the result is the same on every run (no floating-point atomics).  Writes sum, count, mean,
 // and the bf16 rounding + squared norm of the mean into the OTHER centroid buffer; an empty
 // cluster keeps its centroid.
+template <bool STREAM>
 __global__ __launch_bounds__(256) void means_kernel(Dev d, const bf16_t *__restrict__ K, int n, int cur) {
     const int u = blockIdx.y, wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
     const int c = blockIdx.x * 4 + wave;
@@ -637,7 +642,7 @@ __global__ __launch_bounds__(256) void means_kernel(Dev d, const bf16_t *__restr
 #pragma unroll
             for (int k = 0; k < 8; ++k) {
                 const int tok = __shfl(mine, 4 * (h * 8 + k) + g);
-                w[k] = tok >= 0 ? ((const uint4 *)(Ku + (size_t)tok * kD))[ch] : make_uint4(0, 0, 0, 0);
+                w[k] = tok >= 0 ? load16<STREAM>((const uint4 *)(Ku + (size_t)tok * kD) + ch) : make_uint4(0, 0, 0, 0);
             }
 #pragma unroll
             for (int k = 0; k < 8; ++k) {  // rows past the end add +0
@@ -700,7 +705,8 @@ __global__ __launch_bounds__(256) void means_kernel(Dev d, const bf16_t *__restr
 }
 
 void launch_means(const Dev &d, const bf16_t *K, int n, int cur, hipStream_t st) {
-    hipLaunchKernelGGL(means_kernel, dim3((d.C + 3) / 4, d.U), dim3(256), 0, st, d, K, n, cur);
+    if (keys_exceed_cache(d, n)) hipLaunchKernelGGL(means_kernel<true>, dim3((d.C + 3) / 4, d.U), dim3(256), 0, st, d, K, n, cur);
+    else hipLaunchKernelGGL(means_kernel<false>, dim3((d.C + 3) / 4, d.U), dim3(256), 0, st, d, K, n, cur);
 }
 
 // ------------------------------------------------------------------------------------------------
@@ -708,6 +714,7 @@ void launch_means(const Dev &d, const bf16_t *K, int n, int cur, hipStream_t st)
 // tokens; consecutive page ids.  One wave per page copies the s key rows and s value rows into
 // the page's contiguous tiles, records their positions, and forms the representative: the fp32
 // sum of the page's keys in slot order (one add per slot), divided by the fill, rounded to bf16.
+template <bool STREAM>
 __global__ __launch_bounds__(256) void paginate_kernel(Dev d, const bf16_t *__restrict__ K,
                                                         const bf16_t *__restrict__ V, int n) {
     extern __shared__ __align__(16) char smem[];  // [4][s][128] bf16
@@ -742,11 +749,11 @@ __global__ __launch_bounds__(256) void paginate_kernel(Dev d, const bf16_t *__re
         const int tok = valid ? ord[slot] : -1;
         uint4 kw = make_uint4(0, 0, 0, 0), vw = kw;
         if (valid) {
-            kw = ((const uint4 *)(K + ((size_t)u * n + tok) * kD))[ch];
-            vw = ((const uint4 *)(V + ((size_t)u * n + tok) * kD))[ch];
+            kw = load16<STREAM>((const uint4 *)(K + ((size_t)u * n + tok) * kD) + ch);
+            vw = load16<STREAM>((const uint4 *)(V + ((size_t)u * n + tok) * kD) + ch);
         }
-        ((uint4 *)(d.Kp + (pg * s + slot) * kD))[ch] = kw;
-        ((uint4 *)(d.Vp + (pg * s + slot) * kD))[ch] = vw;
+        store16<STREAM>((uint4 *)(d.Kp + (pg * s + slot) * kD) + ch, kw);
+        store16<STREAM>((uint4 *)(d.Vp + (pg * s + slot) * kD) + ch, vw);
         ((uint4 *)(tile + (size_t)slot * kD))[ch] = kw;
         if (ch == 0) d.page_pos[pg * s + slot] = tok;
     }
@@ -766,7 +773,8 @@ __global__ __launch_bounds__(256) void paginate_kernel(Dev d, const bf16_t *__re
 
 void launch_paginate(const Dev &d, const bf16_t *K, const bf16_t *V, int n, hipStream_t st) {
     const size_t lds = (size_t)4 * d.s * kD * 2;
-    hipLaunchKernelGGL(paginate_kernel, dim3((d.max_pages + 3) / 4, d.U), dim3(256), lds, st, d, K, V, n);
+    if (keys_exceed_cache(d, n)) hipLaunchKernelGGL(paginate_kernel<true>, dim3((d.max_pages + 3) / 4, d.U), dim3(256), lds, st, d, K, V, n);
+    else hipLaunchKernelGGL(paginate_kernel<false>, dim3((d.max_pages + 3) / 4, d.U), dim3(256), lds, st, d, K, V, n);
 }
 
 }  // namespace ice

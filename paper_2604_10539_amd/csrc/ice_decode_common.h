@@ -59,14 +59,6 @@ __device__ inline void load_query_operand(const bf16_t *q, int u, int lane, bf16
     if (sumsq) *sumsq = nn;
 }
 
-// 16-byte load with the non-temporal hint, for data that one call reads exactly once (the
-// representative rows, the tiles of the selected pages).
-typedef unsigned u32x4 __attribute__((ext_vector_type(4)));
-__device__ inline uint4 load16_stream(const uint4 *p) {
-    const u32x4 v = __builtin_nontemporal_load((const u32x4 *)p);
-    return make_uint4(v.x, v.y, v.z, v.w);
-}
-
 // Split-row form of the scoring contraction.  In the plain form lane (g, c) of a B operand reads
 // 16 bytes of row c at 64*ks + 16*g, so one load instruction touches half a 128-byte line of each of
 // 16 rows.  Here a load instruction covers whole lines: lanes c and c+8 read the two 64-byte halves

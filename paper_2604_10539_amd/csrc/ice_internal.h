@@ -165,6 +165,28 @@ __device__ inline float wave_sum(float x) {
 
 // squared norm of a key held 8 dims per lane by a 16-lane row (fixed summation order), and the extra
 // coordinate sqrt(c^2 - ||k||^2) of the transformed keys (Eq. 2), rounded to bf16
+// 16-byte load / store with the non-temporal hint, for data that a launch touches exactly once (the
+// representative rows, key rows of a clustering pass, the page tiles being written)
+typedef unsigned u32x4 __attribute__((ext_vector_type(4)));
+__device__ inline uint4 load16_stream(const uint4 *p) {
+    const u32x4 v = __builtin_nontemporal_load((const u32x4 *)p);
+    return make_uint4(v.x, v.y, v.z, v.w);
+}
+__device__ inline void store16_stream(uint4 *p, const uint4 &w) {
+    const u32x4 v = {w.x, w.y, w.z, w.w};
+    __builtin_nontemporal_store(v, (u32x4 *)p);
+}
+template <bool STREAM>
+__device__ inline uint4 load16(const uint4 *p) {
+    if constexpr (STREAM) return load16_stream(p);
+    else return *p;
+}
+template <bool STREAM>
+__device__ inline void store16(uint4 *p, const uint4 &w) {
+    if constexpr (STREAM) store16_stream(p, w);
+    else *p = w;
+}
+
 __device__ inline float key_sqnorm16(const uint4 &w) {  // this lane's 8 dims; summed over the 16-lane row
     float t = 0.f;
     t += bf16_lo(w.x) * bf16_lo(w.x); t += bf16_hi(w.x) * bf16_hi(w.x);
