@@ -349,7 +349,9 @@ __global__ __launch_bounds__(NW * 64) void decode_step_kernel(Dev d, const bf16_
     // device-scope atomic words, each slot doubles as its own ready flag (kScoreEmpty until written),
     // and the reader re-reads a slot until it is filled.  Writers never wait, so the reader only ever
     // waits for stores that were issued and completed (barrier below) before the counter moved.
-    __syncthreads();
+    // (With one workgroup per unit only LDS is exchanged.)
+    if (single) lds_barrier();
+    else __syncthreads();
     if (!single) {
         if (tid == 0) {
             const int old = __hip_atomic_fetch_add(d.counter + u, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
@@ -466,7 +468,7 @@ __global__ __launch_bounds__(NW * 64) void decode_step_kernel(Dev d, const bf16_
             }
             if (lane == 0) atomicMax(&sh_pre, pre);
         }
-        __syncthreads();
+        lds_barrier();
         const uint32_t pre = sh_pre;
         ICE_STAMP(3);
         // B2: candidates = (score key, ~page id) composites at or above the threshold; all distinct.
@@ -490,7 +492,7 @@ __global__ __launch_bounds__(NW * 64) void decode_step_kernel(Dev d, const bf16_
                 base += (int)__popcll(bal[e]);
             }
         }
-        __syncthreads();
+        lds_barrier();
         const int M = sh_M;  // >= k
         ICE_STAMP(4);
 #ifdef ICE_PROF
@@ -524,13 +526,13 @@ __global__ __launch_bounds__(NW * 64) void decode_step_kernel(Dev d, const bf16_
             int kk = k;
             for (int sft = ((32 + nb - 1) / 8) * 8; sft >= 0; sft -= 8) {
                 if (tid < 256) hist[tid] = 0;
-                __syncthreads();
+                lds_barrier();
                 for (int t = tid; t < M; t += NT) {
                     const u64 cc = cand[t];
                     const u64 pk = ((cc >> 32) << nb) | (cc & idmask);
                     if ((pk & known) == prefix) atomicAdd(&hist[(int)((pk >> sft) & 255ull)], 1);
                 }
-                __syncthreads();
+                lds_barrier();
                 int h = 0, incl = 0;
                 if (tid < 256) {  // bins in descending order: thread t owns bin 255 - t
                     h = hist[255 - tid];
@@ -541,7 +543,7 @@ __global__ __launch_bounds__(NW * 64) void decode_step_kernel(Dev d, const bf16_
                     }
                     if (lane == 63) hist[256 + wave] = incl;
                 }
-                __syncthreads();
+                lds_barrier();
                 if (tid < 256) {
                     for (int w2 = 0; w2 < wave; ++w2) incl += hist[256 + w2];
                     const int excl = incl - h;
@@ -550,11 +552,11 @@ __global__ __launch_bounds__(NW * 64) void decode_step_kernel(Dev d, const bf16_
                         sh_M2 = kk - excl;
                     }
                 }
-                __syncthreads();
+                lds_barrier();
                 prefix = sh_tau;
                 kk = sh_M2;
                 known |= 255ull << sft;
-                __syncthreads();
+                lds_barrier();
             }
             // prefix = packed composite of the k-th largest candidate; everything at or above it wins
             for (int t = tid; t < M; t += NT) {
@@ -564,7 +566,7 @@ __global__ __launch_bounds__(NW * 64) void decode_step_kernel(Dev d, const bf16_
             }
         }
     }
-    __syncthreads();
+    lds_barrier();
     ICE_STAMP(5);
     ICE_USTAMP(2);
     // ---- phase C: attention over the winners, in rank order (the ids' ascending order is only an

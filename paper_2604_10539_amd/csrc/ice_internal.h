@@ -165,6 +165,11 @@ __device__ inline float wave_sum(float x) {
 
 // squared norm of a key held 8 dims per lane by a 16-lane row (fixed summation order), and the extra
 // coordinate sqrt(c^2 - ||k||^2) of the transformed keys (Eq. 2), rounded to bf16
+// Workgroup barrier that orders LDS traffic only: global loads that are still outstanding stay in
+// flight across it (__syncthreads() waits for them as well).  For steps that exchange data through
+// LDS alone.
+__device__ inline void lds_barrier() { asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory"); }
+
 // 16-byte load / store with the non-temporal hint, for data that a launch touches exactly once (the
 // representative rows, key rows of a clustering pass, the page tiles being written)
 typedef unsigned u32x4 __attribute__((ext_vector_type(4)));
