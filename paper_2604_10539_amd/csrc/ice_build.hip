@@ -233,7 +233,7 @@ __global__ __launch_bounds__(512) void assign_kernel(Dev d, const bf16_t *__rest
     extern __shared__ __align__(16) char smem[];
     bf16_t *keys = (bf16_t *)smem;                                   // [2][256][kKeyStride]
     u64 *best = (u64 *)(smem + 2 * kAssignTile * kKeyStride * 2);    // [2][256]
-    float *seeds = (float *)(best + 2 * kAssignTile);                // [CW][CT][2][16] accumulator seeds
+    float *seeds = (float *)(best + 2 * kAssignTile);                // (AUG) [CW][CT][2][16] accumulator seeds
 
     const int u = blockIdx.z, tid = threadIdx.x;
     const int wave = tid >> 6, lane = tid & 63, col = lane & 31, half = lane >> 5;
@@ -260,13 +260,30 @@ __global__ __launch_bounds__(512) void assign_kernel(Dev d, const bf16_t *__rest
             cst[i] = crow0 + row < d.Cpad ? ((const uint4 *)(csrc + (size_t)row * kD))[ch] : make_uint4(0, 0, 0, 0);
         }
     }
-    // Accumulator seeds -||mu~||^2 / 2 (rows past Cpad: -inf) in LDS, in accumulator order: element v of
-    // a lane of half h belongs to local centroid 8 (v / 4) + 4 h + v % 4 of its tile.  A chain starts
-    // from four broadcast 16-byte LDS reads instead of holding 16 registers per centroid tile.
-    if (tid < CW * CT * 32) {
-        const int w = tid / (CT * 32), ct = (tid / 32) % CT, hh = (tid >> 4) & 1, v = tid & 15;
-        const int row = (blockIdx.y * CW + w) * CT * 32 + ct * 32 + 8 * (v >> 2) + 4 * hh + (v & 3);
-        seeds[tid] = row < d.Cpad ? -0.5f * d.cnorm[cur][(size_t)u * d.Cpad + row] : -INFINITY;
+    // Accumulator seeds -||mu~||^2 / 2 (rows past Cpad: -inf): element v of a lane of half h belongs
+    // to local centroid 8 (v / 4) + 4 h + v % 4 of its tile.  They stay in registers for the whole
+    // kernel; with the extra coordinate (operands of 9 steps instead of 8) there is no room for
+    // them, and a chain starts from four broadcast 16-byte LDS reads instead.
+    f32x16 seed[CT];
+    if constexpr (AUG) {
+        if (tid < CW * CT * 32) {
+            const int w = tid / (CT * 32), ct = (tid / 32) % CT, hh = (tid >> 4) & 1, v = tid & 15;
+            const int row = (blockIdx.y * CW + w) * CT * 32 + ct * 32 + 8 * (v >> 2) + 4 * hh + (v & 3);
+            seeds[tid] = row < d.Cpad ? -0.5f * d.cnorm[cur][(size_t)u * d.Cpad + row] : -INFINITY;
+        }
+    } else {
+#pragma unroll
+        for (int ct = 0; ct < CT; ++ct) {
+            const int row0 = cbase + ct * 32;
+            if (row0 < d.Cpad) {
+                const float *wn = d.cnorm[cur] + (size_t)u * d.Cpad + row0;
+#pragma unroll
+                for (int v = 0; v < 16; ++v) seed[ct][v] = -0.5f * wn[8 * (v >> 2) + 4 * half + (v & 3)];
+            } else {
+#pragma unroll
+                for (int v = 0; v < 16; ++v) seed[ct][v] = -INFINITY;
+            }
+        }
     }
 
     uint4 stage[8];
@@ -335,65 +352,66 @@ __global__ __launch_bounds__(512) void assign_kernel(Dev d, const bf16_t *__rest
         u64 *bestt = best + buf * kAssignTile;
         ICE_WSTAMP(t, 0);
         if (t + 1 < ntiles) load_tile(t + 1);
-        // Software pipeline over the 32-key sub-tiles of this wave.  The CT centroid tiles of a
-        // sub-tile are CT independent accumulator chains issued alternately (one chain alone leaves
-        // the matrix core idle for about three of every eleven passes, waiting for its own result),
-        // so one wave keeps the pipe full; meanwhile the vector and scalar units reduce the previous
-        // sub-tile's CT x 16 scores per lane (argmax16).  Only a handful of vector operations fit
-        // under one MFMA, which is why the index half of the argmax lives in scalar lane masks.
-        // The key operand is read from LDS one sub-tile ahead.
+        // Software pipeline over "slots" j = (sub-tile i, centroid tile ct): while the matrix cores
+        // run the 8-MFMA chain of slot j+1 into one accumulator set, the vector and scalar units
+        // reduce slot j's 16 scores per lane from the other set (argmax16).  Only four to five
+        // vector operations fit under one MFMA, which is why the index half of the argmax lives
+        // in scalar lane masks.  The key operand of a sub-tile is read from LDS one sub-tile ahead.
+        constexpr int NSLOT = NSUB * CT;
         bf16x8 B[2][KS];
         auto load_b = [&](int i, bf16x8 (&dst)[KS]) {
             const bf16_t *krow = keys + ((size_t)buf * kAssignTile + (kw + i * KW) * 32 + col) * kKeyStride + half * 8;
 #pragma unroll
             for (int ks = 0; ks < KS; ++ks) dst[ks] = __builtin_bit_cast(bf16x8, *(const uint4 *)(krow + ks * 16));
         };
-        f32x16 acc[2][CT];
-        auto chains = [&](int i, f32x16 (&dst)[CT]) {
-#pragma unroll
-            for (int ct = 0; ct < CT; ++ct) dst[ct] = *(const f32x16 *)(seeds + ((cw * CT + ct) * 2 + half) * 16);
+        f32x16 acc[2];
+        auto chain = [&](int j, f32x16 &dst) {
+            const int i = j / CT, ct = j % CT;
+            if constexpr (AUG) dst = *(const f32x16 *)(seeds + ((cw * CT + ct) * 2 + half) * 16);
+            else dst = seed[ct];
 #pragma unroll
             for (int ks = 0; ks < KS; ++ks)
-#pragma unroll
-                for (int ct = 0; ct < CT; ++ct)
-                    dst[ct] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(A[ct][ks], B[i & 1][ks], dst[ct], 0, 0, 0);
+                dst = __builtin_amdgcn_mfma_f32_32x32x16_bf16(A[ct][ks], B[i & 1][ks], dst, 0, 0, 0);
         };
         load_b(0, B[0]);
-        if (NSUB > 1) load_b(1, B[1]);
-        chains(0, acc[0]);
+        if (CT == 1 && NSUB > 1) load_b(1, B[1]);
+        chain(0, acc[0]);
+        float sv = 0.f;
+        u64 sbit[5] = {0, 0, 0, 0, 0};
 #pragma unroll
-        for (int i = 0; i < NSUB; ++i) {
-            if (i + 1 < NSUB) chains(i + 1, acc[(i + 1) & 1]);
-            if (i + 2 < NSUB) load_b(i + 2, B[i & 1]);
+        for (int j = 0; j < NSLOT; ++j) {
+            const int i = j / CT, ct = j % CT;
+            // LDS reads for the sub-tile whose first chain is issued in the NEXT iteration
+            if ((j + 2) % CT == 0 && (j + 2) / CT < NSUB && (j + 2) / CT >= 1 && !(CT == 1 && j + 2 == 1))
+                load_b((j + 2) / CT, B[((j + 2) / CT) & 1]);
+            if (j + 1 < NSLOT) chain(j + 1, acc[(j + 1) & 1]);
             // element v of this lane has local centroid id ct*32 + 8*(v/4) + v%4 (+ 4*half), ascending in v
-            float sv = 0.f;
-            u64 sbit[5] = {0, 0, 0, 0, 0};
+            float m;
+            u64 bit[4];
+            argmax16(acc[j & 1], m, bit);
+            if (ct == 0) {
+                sv = m;
 #pragma unroll
-            for (int ct = 0; ct < CT; ++ct) {
-                float m;
-                u64 bit[4];
-                argmax16(acc[i & 1][ct], m, bit);
-                if (ct == 0) {
-                    sv = m;
+                for (int b = 0; b < 4; ++b) sbit[b] = bit[b];
+                sbit[4] = 0;
+            } else {
+                const bool gt = m > sv;
+                const u64 e = __builtin_amdgcn_ballot_w64(gt);
+                sv = gt ? m : sv;
 #pragma unroll
-                    for (int b = 0; b < 4; ++b) sbit[b] = bit[b];
-                } else {
-                    const bool gt = m > sv;
-                    const u64 e = __builtin_amdgcn_ballot_w64(gt);
-                    sv = gt ? m : sv;
-#pragma unroll
-                    for (int b = 0; b < 4; ++b) sbit[b] = mask_mux(e, bit[b], sbit[b]);
-                    sbit[4] = e;
-                }
+                for (int b = 0; b < 4; ++b) sbit[b] = mask_mux(e, bit[b], sbit[b]);
+                sbit[4] = e;
             }
-            const uint32_t local = (__builtin_amdgcn_inverse_ballot_w64(sbit[0]) ? 1u : 0u) |
-                                   (__builtin_amdgcn_inverse_ballot_w64(sbit[1]) ? 2u : 0u) |
-                                   (__builtin_amdgcn_inverse_ballot_w64(sbit[2]) ? 8u : 0u) |
-                                   (__builtin_amdgcn_inverse_ballot_w64(sbit[3]) ? 16u : 0u) |
-                                   (__builtin_amdgcn_inverse_ballot_w64(sbit[4]) ? 32u : 0u);
-            // +0.0f: a score of -0 must pack like +0
-            const u64 pk = ((u64)f32_ordered(sv + 0.0f) << 32) | (u64)(inv_cid0 - local);
-            atomicMax(&bestt[(kw + i * KW) * 32 + col], pk);
+            if (ct == CT - 1) {
+                const uint32_t local = (__builtin_amdgcn_inverse_ballot_w64(sbit[0]) ? 1u : 0u) |
+                                       (__builtin_amdgcn_inverse_ballot_w64(sbit[1]) ? 2u : 0u) |
+                                       (__builtin_amdgcn_inverse_ballot_w64(sbit[2]) ? 8u : 0u) |
+                                       (__builtin_amdgcn_inverse_ballot_w64(sbit[3]) ? 16u : 0u) |
+                                       (__builtin_amdgcn_inverse_ballot_w64(sbit[4]) ? 32u : 0u);
+                // +0.0f: a score of -0 must pack like +0
+                const u64 pk = ((u64)f32_ordered(sv + 0.0f) << 32) | (u64)(inv_cid0 - local);
+                atomicMax(&bestt[(kw + i * KW) * 32 + col], pk);
+            }
         }
         ICE_BSTAMP(2 + 2 * (t & 3));
         ICE_WSTAMP(t, 1);
@@ -444,7 +462,7 @@ void launch_assign(const Dev &d, const bf16_t *K, int n, int cur, hipStream_t st
 #endif
     while ((long long)((n + keys_per_wg - 1) / keys_per_wg) * zsplit * d.U > wg_target && keys_per_wg < kpw_max) keys_per_wg *= 2;
     dim3 grid((n + keys_per_wg - 1) / keys_per_wg, zsplit, d.U);
-    const size_t lds = 2 * kAssignTile * key_stride(d.tk != 0) * 2 + 2 * kAssignTile * 8 + 8 * 2 * 2 * 16 * 4;
+    const size_t lds = 2 * kAssignTile * key_stride(d.tk != 0) * 2 + 2 * kAssignTile * 8 + (d.tk ? 8 * 2 * 2 * 16 * 4 : 0);
     if (zsplit > 1) {
         const size_t tot = (size_t)d.U * d.max_tokens;
         hipLaunchKernelGGL(fill_u64_kernel, dim3(1024), dim3(256), 0, st, d.packed, tot, 0ull);
