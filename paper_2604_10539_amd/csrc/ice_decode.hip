@@ -366,20 +366,24 @@ __global__ __launch_bounds__(NW * 64) void decode_step_kernel(Dev d, const bf16_
     ICE_USTAMP(1);
     // the attention takes the plain query operand; it arrives while the selection runs
     if (out) load_query_operand<G>(q, u, lane, qa, nullptr);
-    // all of a thread's score words are requested first, then checked: one round trip, not E
-    auto finish_score = [&](int pid, uint32_t v) -> uint32_t {
-        if (single) return v;
+    // A thread's score words are all requested before any is looked at (clamped addresses, no
+    // branches in between: one round trip, not E), and the slots are re-armed only after the last
+    // one has been read: a store issued between two reads would make the second read wait for it.
+    auto request_score = [&](int pid) -> uint32_t {
+        return single ? sc_lds[pid] : __hip_atomic_load(S + pid, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    };
+    auto finish_score = [&](int pid, uint32_t v) -> uint32_t {  // (several workgroups per unit only)
+        if (v != kScoreEmpty) return v;
         for (int spin = 0; v == kScoreEmpty && spin < (1 << 16); ++spin)
             v = __hip_atomic_load(S + pid, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         if (v == kScoreEmpty) {  // never expected; a fence bounds the wait
             __threadfence();
             v = __hip_atomic_load(S + pid, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         }
-        __hip_atomic_store(S + pid, kScoreEmpty, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);  // re-arm the slot
         return v;
     };
-    auto request_score = [&](int pid) -> uint32_t {
-        return single ? sc_lds[pid] : __hip_atomic_load(S + pid, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    auto rearm_score = [&](int pid) {
+        __hip_atomic_store(S + pid, kScoreEmpty, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     };
 
     // ---- phase B: top-k pages
@@ -398,7 +402,11 @@ __global__ __launch_bounds__(NW * 64) void decode_step_kernel(Dev d, const bf16_
     if (k == np) {
         // budget covers every page
         for (int x = tid; x < k; x += NT) {
-            const uint32_t v = finish_score(x, request_score(x));
+            uint32_t v = request_score(x);
+            if (!single) {
+                v = finish_score(x, v);
+                rearm_score(x);
+            }
             ids[x] = x;
             if (sco) sco[x] = __uint_as_float(v);
         }
@@ -409,13 +417,24 @@ __global__ __launch_bounds__(NW * 64) void decode_step_kernel(Dev d, const bf16_
         uint32_t key[EMAX];
         u64 cm[EMAX];
         int nvalid = 0;
+        if (single) {
 #pragma unroll
-        for (int e = 0; e < EMAX; ++e) key[e] = e * NT + tid < np ? request_score(e * NT + tid) : 0u;
+            for (int e = 0; e < EMAX; ++e) key[e] = sc_lds[min(e * NT + tid, np - 1)];
+        } else {
+#pragma unroll
+            for (int e = 0; e < EMAX; ++e)
+                key[e] = __hip_atomic_load(S + min(e * NT + tid, np - 1), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+#pragma unroll
+            for (int e = 0; e < EMAX; ++e)
+                if (e * NT + tid < np) key[e] = finish_score(e * NT + tid, key[e]);
+#pragma unroll
+            for (int e = 0; e < EMAX; ++e)
+                if (e * NT + tid < np) rearm_score(e * NT + tid);
+        }
 #pragma unroll
         for (int e = 0; e < EMAX; ++e) {
-            const int pid = e * NT + tid;
-            const bool valid = pid < np;
-            key[e] = valid ? f32_ordered(__uint_as_float(finish_score(pid, key[e]))) : 0u;
+            const bool valid = e * NT + tid < np;
+            key[e] = valid ? f32_ordered(__uint_as_float(key[e])) : 0u;
             cm[e] = __ballot(valid);
             nvalid += (int)__popcll(cm[e]);
         }
