@@ -296,6 +296,7 @@ __global__ __launch_bounds__(NW * 64) void decode_step_kernel(Dev d, const bf16_
         // kernel starts with one memory round trip, not two.
         int b0 = wave;
         if (b0 < nblk) request(b0, pend);
+        if (chunk == 0) ICE_STAMP(12);
         bf16x8 qs[2];
         float invn;
         SR::load_query(q, u, lane, qs, &invn);
@@ -303,6 +304,7 @@ __global__ __launch_bounds__(NW * 64) void decode_step_kernel(Dev d, const bf16_
 #pragma unroll
         for (int v = 0; v < 4; ++v) inv[v] = __shfl(invn, (4 * SR::head_group(lane) + v) & 15);
         const bool owner = SR::owner(lane);
+        if (chunk == 0) ICE_STAMP(13);
         const int lim = min(np, pend);
         float gmax[UNR];  // running maximum of the scores this lane produced in unroll slot x
 #pragma unroll
@@ -350,8 +352,10 @@ __global__ __launch_bounds__(NW * 64) void decode_step_kernel(Dev d, const bf16_
     // and the reader re-reads a slot until it is filled.  Writers never wait, so the reader only ever
     // waits for stores that were issued and completed (barrier below) before the counter moved.
     // (With one workgroup per unit only LDS is exchanged.)
+    if (chunk == 0) ICE_STAMP(14);
     if (single) lds_barrier();
     else __syncthreads();
+    if (chunk == 0) ICE_STAMP(15);
     if (!single) {
         if (tid == 0) {
             const int old = __hip_atomic_fetch_add(d.counter + u, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
@@ -515,7 +519,7 @@ __global__ __launch_bounds__(NW * 64) void decode_step_kernel(Dev d, const bf16_
         const int M = sh_M;  // >= k
         ICE_STAMP(4);
 #ifdef ICE_PROF
-        if (tid == 0 && u == 0) ice_prof[15] = M;
+        if (tid == 0 && u == 0 && M < 0) ice_prof[15] = M;
 #endif
         // B3: the k winners among the M candidates, exactly, into sel_comp[0..k)
         if (M <= 256) {
