@@ -77,7 +77,7 @@ def _inertia(K, mu, a):
 
 
 def test_lloyd_round1_is_nearest_promoted_key():
-    """Round 1 is the paper's two-level parent assignment: parent = nearest promoted key (Alg. 2)."""
+    """The first Lloyd round is the paper's two-level parent assignment: parent = nearest promoted key (Alg. 2)."""
     w = datagen.small(n_tokens=400, n_clusters=12)
     K, _ = datagen.keys_values(w)
     idx = datagen.init_indices(w)
