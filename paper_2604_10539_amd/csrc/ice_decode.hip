@@ -269,7 +269,7 @@ __global__ __launch_bounds__(NW * 64) void decode_step_kernel(Dev d, const bf16_
     // bytes; A operand = the G query rows twice).  Lane (.., c) of the owning row group ends up
     // with the score of page c of the 16.
     using SR = SplitRow<G>;
-    bf16x8 qa[4];
+    bf16x8 qs[2];  // the query rows in split-row form (scoring); the attention takes them in plain form
     {
         const int per = round_up((np_hint + chunks - 1) / chunks, 16 * NW);
         const int p0 = chunk * per, pend = min(np_hint, p0 + per);
@@ -297,7 +297,6 @@ __global__ __launch_bounds__(NW * 64) void decode_step_kernel(Dev d, const bf16_
         int b0 = wave;
         if (b0 < nblk) request(b0, pend);
         if (chunk == 0) ICE_STAMP(12);
-        bf16x8 qs[2];
         float invn;
         SR::load_query(q, u, lane, qs, &invn);
         float inv[4];
@@ -368,8 +367,6 @@ __global__ __launch_bounds__(NW * 64) void decode_step_kernel(Dev d, const bf16_
     }
     ICE_STAMP(1);
     ICE_USTAMP(1);
-    // the attention takes the plain query operand; it arrives while the selection runs
-    if (out) load_query_operand<G>(q, u, lane, qa, nullptr);
     // A thread's score words are all requested before any is looked at (clamped addresses, no
     // branches in between: one round trip, not E), and the slots are re-armed only after the last
     // one has been read: a store issued between two reads would make the second read wait for it.
@@ -610,6 +607,8 @@ __global__ __launch_bounds__(NW * 64) void decode_step_kernel(Dev d, const bf16_
     };
     if (out) {
         ICE_STAMP(6);
+        bf16x8 qa[4];
+        SR::to_plain(qs, lane, qa);
         attend_pages<G, NW, RES>(d, u, qa, [=](int x) { return all_pages ? x : (int)(0xFFFFFFFFu - (uint32_t)sel_comp[x]); }, k,
                                  res, out, (float *)region, order_ids);
         ICE_STAMP(7);

@@ -97,6 +97,24 @@ struct SplitRow {
         nn += __shfl_xor(nn, G);  // the other half of the row
         *inv_norm = 1.0f / fmaxf(sqrtf(nn), 1e-20f);
     }
+    // The plain operand of the logit MFMAs (lane (g, h): dims [32ks + 8g, +8) of q_h, zero rows from
+    // G on) out of the split one, by lane exchange: no second trip to memory for the query rows.
+    __device__ static void to_plain(const bf16x8 (&qs)[2], int lane, bf16x8 (&qa)[4]) {
+        const bool low = (lane & 15) < G;
+        const uint4 zero = make_uint4(0, 0, 0, 0);
+        const int src = (lane + G) & 63;  // row G + h holds the upper halves of q_h
+#pragma unroll
+        for (int t = 0; t < 2; ++t) {
+            const uint4 w = __builtin_bit_cast(uint4, qs[t]);
+            uint4 up;
+            up.x = __shfl(w.x, src);
+            up.y = __shfl(w.y, src);
+            up.z = __shfl(w.z, src);
+            up.w = __shfl(w.w, src);
+            qa[2 * t] = __builtin_bit_cast(bf16x8, low ? w : zero);
+            qa[2 * t + 1] = __builtin_bit_cast(bf16x8, low ? up : zero);
+        }
+    }
     // uint4 index inside a 16-row block (rows of 16 uint4) of the load that feeds MFMA t of 8-row
     // block blk
     __device__ static int word(int lane, int blk, int t) {

@@ -481,7 +481,7 @@ __global__ __launch_bounds__(NW * 64) void decode_hier_kernel(Dev d, const bf16_
         }
     };
     bf16x8 qa[4];
-    if (out) load_query_operand<G>(q, u, lane, qa, nullptr);
+    if (out) SR::to_plain(qs, lane, qa);
     if (out) attend_pages<G, NW, false>(d, u, qa, [=](int x) { return (int)(0xFFFFFFFFu - (uint32_t)win[x]); }, k, Resident{nullptr, nullptr, 0, nullptr, nullptr, 0}, out, red, order_ids);
     else order_ids();
     ICE_HSTAMP(7);
