@@ -391,11 +391,6 @@ __global__ __launch_bounds__(NW * 64) void decode_step_kernel(Dev d, const bf16_
     const int k = min(P, np);
     int *ids = ids_out + (size_t)u * P;
     float *sco = scores_out ? scores_out + (size_t)u * P : nullptr;
-    for (int x = k + tid; x < P; x += NT) {
-        ids[x] = -1;
-        if (sco) sco[x] = 0.f;
-    }
-    if (tid == 0) n_sel_out[u] = k;
     const int Pk = min(P, d.max_pages);
     u64 *sel_comp = (u64 *)(smem + round_up(Pk * 4, 16));         // [Pk] winners by rank
     char *region = smem + round_up(Pk * 4, 16) + (size_t)Pk * 8;  // candidates, later attention scratch
@@ -595,6 +590,13 @@ __global__ __launch_bounds__(NW * 64) void decode_step_kernel(Dev d, const bf16_
     // B4: the winners' places in ascending id order; during the attention it runs where the first
     // waves would wait for the last ones
     auto order_ids = [&] {
+        // (every global store of the selection is issued here, after the ranking: a store in flight
+        // makes the next wait of its wave as long as a write to memory)
+        for (int x = k + tid; x < P; x += NT) {
+            ids[x] = -1;
+            if (sco) sco[x] = 0.f;
+        }
+        if (tid == 0) n_sel_out[u] = k;
         if (all_pages) return;
         for (int t = tid; t < k; t += NT) {
             const u64 mine = sel_comp[t];
