@@ -246,8 +246,12 @@ __global__ __launch_bounds__(NW * 64) void decode_step_kernel(Dev d, const bf16_
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
     const int g = lane >> 4, ch = lane & 15;
     const int xcd = blockIdx.x & 7, r = blockIdx.x >> 3;
-    const int chunk = r % chunks, u = xcd + 8 * (r / chunks);
-    if (u >= d.U) return;
+    const int chunk = r % chunks, u_grid = xcd + 8 * (r / chunks);
+    // (the grid is padded to a multiple of 8 units; a workgroup beyond the last unit leaves after the
+    // first loads are issued: an early exit here would split the kernel-argument loads into
+    // dependent round trips for every workgroup)
+    const bool live = u_grid < d.U;
+    const int u = live ? u_grid : d.U - 1;
     const int np = d.n_pages[u];  // first needed after the first loads are in flight
     const bf16_t *rep = d.rep + (size_t)u * d.max_pages * kD;
     uint32_t *S = d.scores + (size_t)u * d.max_pages;  // fp32 bits; kScoreEmpty = not written yet
@@ -299,6 +303,7 @@ __global__ __launch_bounds__(NW * 64) void decode_step_kernel(Dev d, const bf16_
         if (chunk == 0) ICE_STAMP(12);
         float invn;
         SR::load_query(q, u, lane, qs, &invn);
+        if (!live) return;  // (nothing written, no barrier passed yet)
         float inv[4];
 #pragma unroll
         for (int v = 0; v < 4; ++v) inv[v] = __shfl(invn, (4 * SR::head_group(lane) + v) & 15);
