@@ -15,6 +15,8 @@ HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-I" + os.path.join(ROOT, "include"), "-I" + CSRC,
          # packed-fp32 instruction selection is switched off for all device code
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+         # the first 16 dwords of a kernel's arguments are handed over in scalar registers at wave start
+         "-mllvm", "-amdgpu-kernarg-preload-count=16",
          "-Wall", "-Wno-unused-result"]
 
 

@@ -233,10 +233,16 @@ void launch_attend(const Dev &d, const bf16_t *q, const int *ids, const int *n_s
 // order.
 //
 // Phase C, same workgroup: attention over the winners (attend_pages), ids never leave the chip.
+// The leading scalar arguments are what the kernel needs before its first loads can be issued: the
+// first 16 dwords of the kernel arguments are in scalar registers when a wave starts
+// (kernel-argument preload; structures passed by value are not eligible), the rest arrives by
+// scalar loads while the first loads are in flight.
 template <int G, int NW, int EMAX, bool RES>
-__global__ __launch_bounds__(NW * 64) void decode_step_kernel(Dev d, const bf16_t *__restrict__ q, int P, int chunks, int np_hint,
-                                                               int lds_scores_off, int *__restrict__ ids_out, int *__restrict__ n_sel_out,
-                                                               float *__restrict__ scores_out, Resident res, float *__restrict__ out) {
+__global__ __launch_bounds__(NW * 64) void decode_step_kernel(int U, int max_pages, int P, int chunks, int np_hint, int lds_scores_off,
+                                                               const bf16_t *__restrict__ rep_all, const bf16_t *__restrict__ q,
+                                                               const int *__restrict__ n_pages, Dev d, int *__restrict__ ids_out,
+                                                               int *__restrict__ n_sel_out, float *__restrict__ scores_out, Resident res,
+                                                               float *__restrict__ out) {
     constexpr int NT = NW * 64;
     extern __shared__ __align__(16) char smem[];
     __shared__ int sh_last, sh_M, sh_M2, sh_W;
@@ -250,10 +256,10 @@ __global__ __launch_bounds__(NW * 64) void decode_step_kernel(Dev d, const bf16_
     // (the grid is padded to a multiple of 8 units; a workgroup beyond the last unit leaves after the
     // first loads are issued: an early exit here would split the kernel-argument loads into
     // dependent round trips for every workgroup)
-    const bool live = u_grid < d.U;
-    const int u = live ? u_grid : d.U - 1;
-    const int np = d.n_pages[u];  // first needed after the first loads are in flight
-    const bf16_t *rep = d.rep + (size_t)u * d.max_pages * kD;
+    const bool live = u_grid < U;
+    const int u = live ? u_grid : U - 1;
+    const int np = n_pages[u];  // first needed after the first loads are in flight
+    const bf16_t *rep = rep_all + (size_t)u * max_pages * kD;
     uint32_t *S = d.scores + (size_t)u * d.max_pages;  // fp32 bits; kScoreEmpty = not written yet
 
     // one workgroup per unit: the scores never leave LDS and there is nobody to wait for
@@ -655,8 +661,8 @@ void launch_decode_step(const Dev &d, const bf16_t *q, int P, int np_hint, int *
 #define ICE_STEP_R(g, nw, e, r)                                                                                     \
     do {                                                                                                            \
         (void)hipFuncSetAttribute((const void *)decode_step_kernel<g, nw, e, r>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds); \
-        hipLaunchKernelGGL((decode_step_kernel<g, nw, e, r>), dim3(grid), dim3(nw * 64), lds, st, d, q, P, chunks, np_hint, \
-                           (int)(lds - (size_t)d.max_pages * 4), ids, n_sel, scores_out, res, out);                 \
+        hipLaunchKernelGGL((decode_step_kernel<g, nw, e, r>), dim3(grid), dim3(nw * 64), lds, st, d.U, d.max_pages, P, chunks, np_hint, \
+                           (int)(lds - (size_t)d.max_pages * 4), d.rep, q, d.n_pages, d, ids, n_sel, scores_out, res, out); \
     } while (0)
 #define ICE_STEP(g, nw, e)                                                                                          \
     do {                                                                                                            \
