@@ -144,9 +144,9 @@ void launch_insert(const Dev &d, const bf16_t *k, const bf16_t *v, int m, int cu
 
 // ------------------------------------------------------------------------------------------------
 template <int G, int NW, bool RES>
-__global__ __launch_bounds__(NW * 64) void attend_kernel(Dev d, const bf16_t *__restrict__ q,
-                                                          const int *__restrict__ ids, const int *__restrict__ n_sel,
-                                                          int P, Resident res, float *__restrict__ out) {
+__global__ __launch_bounds__(NW * 64) void attend_kernel(const bf16_t *__restrict__ q, const int *__restrict__ ids,
+                                                          const int *__restrict__ n_sel, int P, Dev d, Resident res,
+                                                          float *__restrict__ out) {  // (scalars first: preloaded)
     extern __shared__ __align__(16) char smem[];
     const int u = blockIdx.x;
     bf16x8 qa[4];
@@ -198,10 +198,10 @@ void launch_attend(const Dev &d, const bf16_t *q, const int *ids, const int *n_s
     do {                                                                                                                   \
         if (n_res > 0)                                                                                                     \
             hipLaunchKernelGGL((attend_kernel<g, nw, true>), dim3(d.U), dim3(nw * 64),                                     \
-                               sizeof(float) * attend_scratch_floats(g, nw), st, d, q, ids, n_sel, P, res, out);           \
+                               sizeof(float) * attend_scratch_floats(g, nw), st, q, ids, n_sel, P, d, res, out);           \
         else                                                                                                               \
             hipLaunchKernelGGL((attend_kernel<g, nw, false>), dim3(d.U), dim3(nw * 64),                                    \
-                               sizeof(float) * attend_scratch_floats(g, nw), st, d, q, ids, n_sel, P, res, out);           \
+                               sizeof(float) * attend_scratch_floats(g, nw), st, q, ids, n_sel, P, d, res, out);           \
     } while (0)
     switch (d.G) {
         case 1: ICE_ATTEND(1, 16); break;

@@ -217,8 +217,12 @@ __host__ __device__ inline HierLds hier_lds(int Cpad, int max_pages, int n_probe
     return L;
 }
 
+// (The leading scalar arguments are those needed before the first loads: they are preloaded into
+// scalar registers at wave start; cent_all = the centroid rows in use.)
 template <int G, int NW, int EMAX>
-__global__ __launch_bounds__(NW * 64) void decode_hier_kernel(Dev d, const bf16_t *__restrict__ q, int cur, int P, int n_probe, int n_refine, int np_hint,
+__global__ __launch_bounds__(NW * 64) void decode_hier_kernel(int Cpad, int max_pages, int np_hint, int P, int n_probe, int n_refine,
+                                                               const bf16_t *__restrict__ cent_all, const bf16_t *__restrict__ q,
+                                                               const int *__restrict__ page_cluster, const int *__restrict__ n_pages, Dev d,
                                                                int *__restrict__ ids_out, int *__restrict__ n_sel_out,
                                                                float *__restrict__ scores_out, int *__restrict__ clusters_out,
                                                                float *__restrict__ out) {
@@ -228,7 +232,7 @@ __global__ __launch_bounds__(NW * 64) void decode_hier_kernel(Dev d, const bf16_
     __shared__ int sh_ncand;
     const int u = blockIdx.x, tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
     const int g = lane >> 4, ch = lane & 15;
-    const HierLds L = hier_lds(d.Cpad, d.max_pages, n_probe, n_refine, P, G, NW);
+    const HierLds L = hier_lds(Cpad, max_pages, n_probe, n_refine, P, G, NW);
     u64 *comp1 = (u64 *)(smem + L.comp1);
     uint32_t *member = (uint32_t *)(smem + L.member);
     u64 *comp2 = (u64 *)(smem + L.comp2);
@@ -241,13 +245,13 @@ __global__ __launch_bounds__(NW * 64) void decode_hier_kernel(Dev d, const bf16_
     float *red = (float *)(smem + L.red);
 
     ICE_HSTAMP(0);
-    const int np = d.n_pages[u];  // first needed in stage 2
+    const int np = n_pages[u];  // first needed in stage 2
     const int C = d.C;
     // the page -> cluster table is requested now and used in stage 2; np_hint is the host's upper
     // bound of the live pages (entries past the live pages are read and ignored)
     int pcl[EMAX];
     {
-        const int *pc = d.page_cluster + (size_t)u * d.max_pages;
+        const int *pc = page_cluster + (size_t)u * max_pages;
 #pragma unroll
         for (int e = 0; e < EMAX; ++e) pcl[e] = e * NT + tid < np_hint ? pc[e * NT + tid] : -1;
     }
@@ -256,8 +260,8 @@ __global__ __launch_bounds__(NW * 64) void decode_hier_kernel(Dev d, const bf16_
     // are padding).  The first round is requested together with the query rows, before anything
     // waits for either.
     using SR = SplitRow<G>;
-    const bf16_t *cb = d.cent_bf16[cur] + (size_t)u * d.Cpad * kD;
-    const int nblk1 = d.Cpad >> 4;
+    const bf16_t *cb = cent_all + (size_t)u * Cpad * kD;
+    const int nblk1 = Cpad >> 4;
     constexpr int UNR1 = 4;
     uint4 bb1[UNR1][4];
     int word[4];
@@ -269,7 +273,7 @@ __global__ __launch_bounds__(NW * 64) void decode_hier_kernel(Dev d, const bf16_
             const int c0 = 16 * (b0 + NW * x);  // (Cpad is a multiple of 16: a block is there or not)
             const uint4 *src = (const uint4 *)(cb + (size_t)c0 * kD);
 #pragma unroll
-            for (int j = 0; j < 4; ++j) bb1[x][j] = c0 < d.Cpad ? load16_stream(src + word[j]) : make_uint4(0, 0, 0, 0);
+            for (int j = 0; j < 4; ++j) bb1[x][j] = c0 < Cpad ? load16_stream(src + word[j]) : make_uint4(0, 0, 0, 0);
         }
     };
     request1(wave);
@@ -294,7 +298,7 @@ __global__ __launch_bounds__(NW * 64) void decode_hier_kernel(Dev d, const bf16_
         }
         return SR::score(acc0, acc1, inv, lane);
     };
-    for (int i = tid; i < d.Cpad / 32 + 1; i += NT) member[i] = 0u;
+    for (int i = tid; i < Cpad / 32 + 1; i += NT) member[i] = 0u;
     if (tid == 0) sh_ncand = 0;
 
     // ---- stage 1: centroid scores
@@ -501,8 +505,8 @@ void launch_decode_hier(const Dev &d, const bf16_t *q, int cur, int P, int n_pro
 #define ICE_HIER(g, nw, e)                                                                                           \
     do {                                                                                                             \
         (void)hipFuncSetAttribute((const void *)decode_hier_kernel<g, nw, e>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds); \
-        hipLaunchKernelGGL((decode_hier_kernel<g, nw, e>), dim3(d.U), dim3(nw * 64), lds, st, d, q, cur, P, n_probe, n_refine, np_hint, ids, \
-                           n_sel, scores_out, clusters_out, out);                                                    \
+        hipLaunchKernelGGL((decode_hier_kernel<g, nw, e>), dim3(d.U), dim3(nw * 64), lds, st, d.Cpad, d.max_pages, np_hint, P, n_probe, \
+                           n_refine, d.cent_bf16[cur], q, d.page_cluster, d.n_pages, d, ids, n_sel, scores_out, clusters_out, out);                                                    \
     } while (0)
     if (d.G == 8) { if (E <= 8) ICE_HIER(8, 8, 8); else ICE_HIER(8, 8, 32); }
     else if (d.G == 4) { if (E <= 4) ICE_HIER(4, 16, 4); else ICE_HIER(4, 16, 16); }
