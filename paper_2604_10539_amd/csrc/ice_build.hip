@@ -225,8 +225,9 @@ __device__ long long ice_prof_w[128];
 __host__ __device__ constexpr int key_stride(bool aug) { return aug ? 152 : 136; }
 
 template <int CT, int CW, bool AUG>
-__global__ __launch_bounds__(512) void assign_kernel(Dev d, const bf16_t *__restrict__ K, int n, int cur,
-                                                      int keys_per_wg, int zsplit) {
+__global__ __launch_bounds__(512) void assign_kernel(const bf16_t *__restrict__ K, const bf16_t *__restrict__ cent,
+                                                      const float *__restrict__ cnorm, int n, int keys_per_wg, int zsplit,
+                                                      int Cpad, int cur, Dev d) {  // (scalars first: preloaded at wave start)
     constexpr int KW = 8 / CW;
     constexpr int kKeyStride = key_stride(AUG);
     constexpr int KS = AUG ? 9 : 8;  // 16-wide steps of the contraction
@@ -253,11 +254,11 @@ __global__ __launch_bounds__(512) void assign_kernel(Dev d, const bf16_t *__rest
     const int crow0 = blockIdx.y * R;
     uint4 cst[R / 32];
     {
-        const bf16_t *csrc = d.cent_bf16[cur] + ((size_t)u * d.Cpad + crow0) * kD;
+        const bf16_t *csrc = cent + ((size_t)u * Cpad + crow0) * kD;
 #pragma unroll
         for (int i = 0; i < R / 32; ++i) {
             const int id = tid + 512 * i, row = id >> 4, ch = id & 15;
-            cst[i] = crow0 + row < d.Cpad ? ((const uint4 *)(csrc + (size_t)row * kD))[ch] : make_uint4(0, 0, 0, 0);
+            cst[i] = crow0 + row < Cpad ? ((const uint4 *)(csrc + (size_t)row * kD))[ch] : make_uint4(0, 0, 0, 0);
         }
     }
     // Accumulator seeds -||mu~||^2 / 2 (rows past Cpad: -inf): element v of a lane of half h belongs
@@ -269,14 +270,14 @@ __global__ __launch_bounds__(512) void assign_kernel(Dev d, const bf16_t *__rest
         if (tid < CW * CT * 32) {
             const int w = tid / (CT * 32), ct = (tid / 32) % CT, hh = (tid >> 4) & 1, v = tid & 15;
             const int row = (blockIdx.y * CW + w) * CT * 32 + ct * 32 + 8 * (v >> 2) + 4 * hh + (v & 3);
-            seeds[tid] = row < d.Cpad ? -0.5f * d.cnorm[cur][(size_t)u * d.Cpad + row] : -INFINITY;
+            seeds[tid] = row < Cpad ? -0.5f * cnorm[(size_t)u * Cpad + row] : -INFINITY;
         }
     } else {
 #pragma unroll
         for (int ct = 0; ct < CT; ++ct) {
             const int row0 = cbase + ct * 32;
-            if (row0 < d.Cpad) {
-                const float *wn = d.cnorm[cur] + (size_t)u * d.Cpad + row0;
+            if (row0 < Cpad) {
+                const float *wn = cnorm + (size_t)u * Cpad + row0;
 #pragma unroll
                 for (int v = 0; v < 16; ++v) seed[ct][v] = -0.5f * wn[8 * (v >> 2) + 4 * half + (v & 3)];
             } else {
@@ -324,7 +325,7 @@ __global__ __launch_bounds__(512) void assign_kernel(Dev d, const bf16_t *__rest
     }
     if constexpr (AUG) {
         if (tid < R) {  // the centroids' extra coordinate, then 15 zeros
-            const uint32_t a = crow0 + tid < d.Cpad ? d.caug[cur][(size_t)u * d.Cpad + crow0 + tid] : 0u;
+            const uint32_t a = crow0 + tid < Cpad ? d.caug[cur][(size_t)u * Cpad + crow0 + tid] : 0u;
             bf16_t *dst = keys + (size_t)tid * kKeyStride + kD;
             *(uint4 *)dst = make_uint4(a, 0, 0, 0);
             *(uint4 *)(dst + 8) = make_uint4(0, 0, 0, 0);
@@ -470,7 +471,8 @@ void launch_assign(const Dev &d, const bf16_t *K, int n, int cur, hipStream_t st
 #define ICE_ASSIGN_A(ct, cw, aug)                                                                   \
     do {                                                                                            \
         (void)hipFuncSetAttribute((const void *)assign_kernel<ct, cw, aug>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds); \
-        hipLaunchKernelGGL((assign_kernel<ct, cw, aug>), grid, dim3(512), lds, st, d, K, n, cur, keys_per_wg, zsplit); \
+        hipLaunchKernelGGL((assign_kernel<ct, cw, aug>), grid, dim3(512), lds, st, K, d.cent_bf16[cur], d.cnorm[cur], n, keys_per_wg, \
+                           zsplit, d.Cpad, cur, d);                                                 \
     } while (0)
 #define ICE_ASSIGN(ct, cw)                                                                          \
     do {                                                                                            \
