@@ -30,16 +30,17 @@ constexpr uint32_t kScoreEmpty = 0xFFFFFFFFu;  // a NaN pattern no score can tak
 // centroid, its bf16 rounding and squared norm.  The next token sees the moved centroid, exactly
 // as m separate launches would.  k, v: bf16 [U, m, d].
 constexpr int kInsertWaves = 16;
-__global__ __launch_bounds__(kInsertWaves * 64) void insert_kernel(Dev d, const bf16_t *__restrict__ k,
-                                                                    const bf16_t *__restrict__ v, int m, int cur) {
+__global__ __launch_bounds__(kInsertWaves * 64) void insert_kernel(const bf16_t *__restrict__ k, const bf16_t *__restrict__ v,
+                                                                    const bf16_t *__restrict__ cent, const float *__restrict__ cnorm,
+                                                                    int m, int cur, int C, int Cpad, Dev d) {  // (scalars first: preloaded)
     __shared__ u64 best;
     const int u = blockIdx.x, tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
     const int g = lane >> 4, ch = lane & 15;
     // what the append needs and does not depend on the chosen cluster is requested before the scan
     int np = d.n_pages[u];
     int tok = d.n_tokens[u];
-    const bf16_t *cb = d.cent_bf16[cur] + (size_t)u * d.Cpad * kD;
-    const float *wn = d.cnorm[cur] + (size_t)u * d.Cpad;
+    const bf16_t *cb = cent + (size_t)u * Cpad * kD;
+    const float *wn = cnorm + (size_t)u * Cpad;
     constexpr int RS = kInsertWaves * 4;  // rows per pass of the workgroup
     for (int t = 0; t < m; ++t) {
         const bf16_t *kt = k + ((size_t)u * m + t) * kD, *vt = v + ((size_t)u * m + t) * kD;
@@ -57,15 +58,15 @@ __global__ __launch_bounds__(kInsertWaves * 64) void insert_kernel(Dev d, const 
         }
         float bv = INFINITY;
         int bi = 0x7FFFFFFF;
-        for (int r0 = wave * 4 + g; r0 < d.C; r0 += 4 * RS) {
+        for (int r0 = wave * 4 + g; r0 < C; r0 += 4 * RS) {
             uint4 row[4];
             float w[4], ce[4];
 #pragma unroll
             for (int x = 0; x < 4; ++x) {
                 const int r = r0 + x * RS;
-                row[x] = r < d.C ? ((const uint4 *)(cb + (size_t)r * kD))[ch] : make_uint4(0, 0, 0, 0);
-                w[x] = r < d.C ? wn[r] : INFINITY;
-                ce[x] = d.tk && r < d.C ? bf16_to_f32(d.caug[cur][(size_t)u * d.Cpad + r]) : 0.f;
+                row[x] = r < C ? ((const uint4 *)(cb + (size_t)r * kD))[ch] : make_uint4(0, 0, 0, 0);
+                w[x] = r < C ? wn[r] : INFINITY;
+                ce[x] = d.tk && r < C ? bf16_to_f32(d.caug[cur][(size_t)u * Cpad + r]) : 0.f;
             }
 #pragma unroll
             for (int x = 0; x < 4; ++x) {  // ascending r: a later row wins only when strictly smaller
@@ -139,7 +140,7 @@ __global__ __launch_bounds__(kInsertWaves * 64) void insert_kernel(Dev d, const 
 }
 
 void launch_insert(const Dev &d, const bf16_t *k, const bf16_t *v, int m, int cur, hipStream_t st) {
-    hipLaunchKernelGGL(insert_kernel, dim3(d.U), dim3(kInsertWaves * 64), 0, st, d, k, v, m, cur);
+    hipLaunchKernelGGL(insert_kernel, dim3(d.U), dim3(kInsertWaves * 64), 0, st, k, v, d.cent_bf16[cur], d.cnorm[cur], m, cur, d.C, d.Cpad, d);
 }
 
 // ------------------------------------------------------------------------------------------------
