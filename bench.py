@@ -37,7 +37,7 @@ import datagen  # noqa: E402
 HBM_PEAK_GBPS = 8000.0
 # HBM bytes of one batched decode_step launch (fetch + write), from the counter runs summarised in
 # profiles/decode_step_cfg2_hbm_counters.md; refreshed whenever that profile is.
-MEASURED_TRAFFIC_BYTES = 180166 * 1024
+MEASURED_TRAFFIC_BYTES = 180154 * 1024
 MFMA_BF16_PEAK_TFLOPS = 2500.0
 D = 128
 
