@@ -940,3 +940,71 @@ def test_insert_on_transformed_keys():
     ea, eb = export_np(ix_a), export_np(ix_b)
     for name in ("cluster_cnt", "cluster_sum", "centroid", "cluster_tail", "n_pages", "page_fill"):
         assert np.array_equal(ea[name], eb[name]), name
+
+
+# ------------------------------------------------------------------------------------ HIP graphs
+@pytest.mark.parametrize("kw", [
+    dict(n_tokens=3000, n_clusters=48, n_kv_heads=3, n_components=24),     # few units: several workgroups per unit
+    dict(n_tokens=700, n_clusters=16, n_kv_heads=2, n_components=8),       # one workgroup per unit
+])
+def test_hip_graph_replays_match_eager_calls(kw):
+    """The library only enqueues kernels on the caller's stream (no allocation, no synchronisation, no
+    memset), so build and decode calls can be captured into a HIP graph.  Every replay, with eager
+    work of the same kind in between, must reproduce the eager results bit for bit."""
+    w = datagen.small(**kw)
+    ix, K, V, _ = _mk(w, T=2)
+    Kd, Vd = up(K), up(V)
+    ix.build_index(Kd, Vd)
+    q = up(datagen.queries(w))
+    q_other = up(datagen.queries(w, step=1))
+    ids_e, ns_e, out_e = ix.select_attend(q, 256)
+    hid_e, hns_e, hsc_e, hcl_e, hout_e = ix.select_hier(q, 256, n_probe=8)
+    state_e = export_np(ix)
+    torch.cuda.synchronize()
+
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        ix.select_attend(q, 256)  # (warm-up on the capture stream)
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+
+    g_build, g_step = torch.cuda.CUDAGraph(), torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g_build):
+        ix.build_index(Kd, Vd)
+    with torch.cuda.graph(g_step):
+        ids_g, ns_g, out_g = ix.select_attend(q, 256)
+        hid_g, hns_g, hsc_g, hcl_g, hout_g = ix.select_hier(q, 256, n_probe=8)
+    for replay in range(3):
+        # eager work between the replays: another query, and the outputs of the graph overwritten
+        ix.select_attend(q_other, 256)
+        out_g.fill_(7.0)
+        ids_g.fill_(-5)
+        hout_g.fill_(7.0)
+        torch.cuda.synchronize()
+        if replay == 1:
+            g_build.replay()  # the same prefill again: the same index
+        g_step.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(ids_g, ids_e) and torch.equal(ns_g, ns_e), "replay %d: page ids" % replay
+        assert torch.equal(out_g, out_e), "replay %d: attention output" % replay
+        assert torch.equal(hid_g, hid_e) and torch.equal(hns_g, hns_e) and torch.equal(hcl_g, hcl_e)
+        assert torch.equal(hsc_g, hsc_e) and torch.equal(hout_g, hout_e), "replay %d: hierarchical step" % replay
+    state_g = export_np(ix)
+    for name in STATE_FIELDS:
+        a, b = state_e[name], state_g[name]
+        for u in range(ix.U):
+            npg = int(state_e["n_pages"][u])
+            if name in ("Kp", "Vp"):
+                m = valid_slot_mask(state_e["page_fill"][u, :npg], w.page_size)
+                assert np.array_equal(a[u, :npg][m], b[u, :npg][m]), name
+            elif name in ("page_sum", "rep"):
+                assert np.array_equal(a[u, :npg], b[u, :npg]), name
+            elif name in ("cluster_sum", "centroid"):
+                assert np.array_equal(a[u].view(np.uint32), b[u].view(np.uint32)), name
+            elif name == "n_pages":
+                assert a[u] == b[u], name
+            elif name in ("page_cluster", "page_fill", "page_pos"):
+                assert np.array_equal(a[u, :npg], b[u, :npg]), name
+            else:
+                assert np.array_equal(a[u], b[u]), name
