@@ -17,7 +17,7 @@ FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-I" + os.path.j
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
          # the first 16 dwords of a kernel's arguments are handed over in scalar registers at wave start
          "-mllvm", "-amdgpu-kernarg-preload-count=16",
-         "-Wall", "-Wno-unused-result"]
+         "-Wall", "-Wno-unused-result", "-Wno-inline-asm"]
 
 
 def build_library(verbose: bool = False) -> str:

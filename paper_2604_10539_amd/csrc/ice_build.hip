@@ -222,19 +222,42 @@ __device__ long long ice_prof_w[128];
 // bf16 elements per LDS key row: 128 + 8 padding; with the extra coordinate of the transformed keys
 // 144 (one more 16-wide step of the contraction: the coordinate and 15 zeros) + 8 padding.  Both
 // strides keep the 32-row operand reads free of bank conflicts (68 and 76 dwords).
-__host__ __device__ constexpr int key_stride(bool aug) { return aug ? 152 : 136; }
+// LDS layout of a 256-row tile (keys, or the centroid block while it is staged): rows of 256 bytes
+// without padding, the 16-byte chunk c of row r stored in slot c ^ (r & 15).  A fragment read (lane
+// = row r, chunk 2 ks + half) then hits 16 different 16-byte bank groups per 16 lanes (measured: the
+// full 160 B/clk/CU), and a wave can write four whole rows with ONE direct global -> LDS load (lane
+// l lands at 16 l; it fetches chunk (l & 15) ^ (row & 15) of its row), so a key tile never passes
+// through registers.  With the extra coordinate (transformed keys) each row has a 32-byte
+// companion (the coordinate, then zeros: the two chunks of a ninth contraction step) in a
+// separate array.
+__host__ __device__ constexpr int assign_lds_bytes(bool aug) {
+    return 2 * 256 * 256 + (aug ? 2 * 256 * 32 : 0) + 2 * 256 * 8;
+}
+
+// One direct global -> LDS load of 16 bytes per lane: lane l's bytes land at lds_base + 16 l
+// (lds_base is the same for the whole wave).  Written as inline assembly so that the compiler's wait
+// insertion does not know the load: told about it, it makes the wave wait for the load before the
+// next LDS atomic that might alias its destination, i.e. within the first eighth of the tile that is
+// being computed, and the load is for the NEXT tile.  The caller waits (wait_lds_dma) before the
+// barrier that hands the destination buffer over.
+__device__ inline void lds_dma16(const uint4 *src, char *lds_base) {
+    const uint32_t base = __builtin_amdgcn_readfirstlane((uint32_t)(size_t)(__attribute__((address_space(3))) char *)lds_base);
+    asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off" ::"v"(src), "s"(base) : "memory", "m0");
+}
+__device__ inline void wait_lds_dma() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); }
 
 template <int CT, int CW, bool AUG>
 __global__ __launch_bounds__(512) void assign_kernel(const bf16_t *__restrict__ K, const bf16_t *__restrict__ cent,
                                                       const float *__restrict__ cnorm, int n, int keys_per_wg, int zsplit,
                                                       int Cpad, int cur, Dev d) {  // (scalars first: preloaded at wave start)
     constexpr int KW = 8 / CW;
-    constexpr int kKeyStride = key_stride(AUG);
     constexpr int KS = AUG ? 9 : 8;  // 16-wide steps of the contraction
     extern __shared__ __align__(16) char smem[];
-    bf16_t *keys = (bf16_t *)smem;                                   // [2][256][kKeyStride]
-    u64 *best = (u64 *)(smem + 2 * kAssignTile * kKeyStride * 2);    // [2][256]
-    float *seeds = (float *)(best + 2 * kAssignTile);                // (AUG) [CW][CT][2][16] accumulator seeds
+    char *keys = smem;                                                // [2][256][256 B], chunks swizzled
+    uint4 *kext = (uint4 *)(smem + 2 * kAssignTile * 256);            // (AUG) [2][256][2] companion chunks
+    u64 *best = (u64 *)(smem + 2 * kAssignTile * 256 + (AUG ? 2 * kAssignTile * 32 : 0));  // [2][256]
+    // byte offset of chunk c of row r inside a buffer
+    auto slot = [](int r, int c) { return r * 256 + ((c ^ (r & 15)) << 4); };
 
     const int u = blockIdx.z, tid = threadIdx.x;
     const int wave = tid >> 6, lane = tid & 63, col = lane & 31, half = lane >> 5;
@@ -261,74 +284,70 @@ __global__ __launch_bounds__(512) void assign_kernel(const bf16_t *__restrict__ 
             cst[i] = crow0 + row < Cpad ? ((const uint4 *)(csrc + (size_t)row * kD))[ch] : make_uint4(0, 0, 0, 0);
         }
     }
-    // Accumulator seeds -||mu~||^2 / 2 (rows past Cpad: -inf): element v of a lane of half h belongs
-    // to local centroid 8 (v / 4) + 4 h + v % 4 of its tile.  They stay in registers for the whole
-    // kernel; with the extra coordinate (operands of 9 steps instead of 8) there is no room for
-    // them, and a chain starts from four broadcast 16-byte LDS reads instead.
+    // accumulator seeds -||mu~||^2 / 2 (rows past Cpad: -inf), resident for the whole kernel: element v
+    // of a lane of half h belongs to local centroid 8 (v / 4) + 4 h + v % 4 of its tile
     f32x16 seed[CT];
-    if constexpr (AUG) {
-        if (tid < CW * CT * 32) {
-            const int w = tid / (CT * 32), ct = (tid / 32) % CT, hh = (tid >> 4) & 1, v = tid & 15;
-            const int row = (blockIdx.y * CW + w) * CT * 32 + ct * 32 + 8 * (v >> 2) + 4 * hh + (v & 3);
-            seeds[tid] = row < Cpad ? -0.5f * cnorm[(size_t)u * Cpad + row] : -INFINITY;
-        }
-    } else {
 #pragma unroll
-        for (int ct = 0; ct < CT; ++ct) {
-            const int row0 = cbase + ct * 32;
-            if (row0 < Cpad) {
-                const float *wn = cnorm + (size_t)u * Cpad + row0;
+    for (int ct = 0; ct < CT; ++ct) {
+        const int row0 = cbase + ct * 32;
+        if (row0 < Cpad) {
+            const float *wn = cnorm + (size_t)u * Cpad + row0;
 #pragma unroll
-                for (int v = 0; v < 16; ++v) seed[ct][v] = -0.5f * wn[8 * (v >> 2) + 4 * half + (v & 3)];
-            } else {
+            for (int v = 0; v < 16; ++v) seed[ct][v] = -0.5f * wn[8 * (v >> 2) + 4 * half + (v & 3)];
+        } else {
 #pragma unroll
-                for (int v = 0; v < 16; ++v) seed[ct][v] = -INFINITY;
-            }
+            for (int v = 0; v < 16; ++v) seed[ct][v] = -INFINITY;
         }
     }
 
-    uint4 stage[8];
-    uint32_t stage_aug = 0;  // (AUG) extra coordinate of key `tid` of the tile, threads 0..255
-    auto load_tile = [&](int t) {
-        const int base = k0 + t * kAssignTile;
-#pragma unroll
-        for (int i = 0; i < 8; ++i) {
-            const int id = tid + 512 * i, row = id >> 4, ch = id & 15;
-            const int key = base + row;
-            stage[i] = key < kend ? ((const uint4 *)(Ku + (size_t)key * kD))[ch] : make_uint4(0, 0, 0, 0);
-        }
+    // The first key tile travels through registers (it is requested before the centroid block is
+    // staged in the very buffers it goes to); every later tile goes straight to LDS.
+    uint32_t stage_aug = 0;  // (AUG) extra coordinate of key `tid` of the next tile, threads 0..255
+    auto load_aug = [&](int t) {
         if constexpr (AUG) {
-            const int key = base + tid;
+            const int key = k0 + t * kAssignTile + tid;
             stage_aug = tid < kAssignTile && key < kend ? d.kaug[(size_t)u * d.max_tokens + key] : 0u;
         }
     };
-    auto store_tile = [&](int buf) {
-#pragma unroll
-        for (int i = 0; i < 8; ++i) {
-            const int id = tid + 512 * i, row = id >> 4, ch = id & 15;
-            *(uint4 *)(keys + ((size_t)buf * kAssignTile + row) * kKeyStride + ch * 8) = stage[i];
-        }
+    auto store_aug = [&](int buf) {
         if constexpr (AUG) {
             if (tid < kAssignTile) {
-                bf16_t *dst = keys + ((size_t)buf * kAssignTile + tid) * kKeyStride + kD;
-                *(uint4 *)dst = make_uint4(stage_aug, 0, 0, 0);
-                *(uint4 *)(dst + 8) = make_uint4(0, 0, 0, 0);
+                kext[(buf * kAssignTile + tid) * 2] = make_uint4(stage_aug, 0, 0, 0);
+                kext[(buf * kAssignTile + tid) * 2 + 1] = make_uint4(0, 0, 0, 0);
             }
         }
     };
-
-    if (ntiles > 0) load_tile(0);
+    // rows past the end of the range are never written back: they may hold any valid key
+    auto request_tile = [&](int t, int buf) {
+        const int base = k0 + t * kAssignTile;
+        const int ch = tid & 15, r16 = (tid >> 4) & 15;
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            const int row = (tid >> 4) + 32 * i;
+            const int key = min(base + row, kend - 1);
+            const uint4 *src = (const uint4 *)(Ku + (size_t)key * kD) + (ch ^ r16);
+            char *dst = keys + buf * (kAssignTile * 256) + (4 * wave + 32 * i) * 256;  // this wave's four rows
+            lds_dma16(src, dst);
+        }
+    };
+    u32x4 first[8];  // (the grid leaves no workgroup without keys: ntiles >= 1)
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+        const int id = tid + 512 * i, row = id >> 4, ch = id & 15;
+        const int key = min(k0 + row, kend - 1);
+        first[i] = ((const u32x4 *)(Ku + (size_t)key * kD))[ch];
+    }
+    load_aug(0);
 #pragma unroll
     for (int i = 0; i < R / 32; ++i) {
         const int id = tid + 512 * i, row = id >> 4, ch = id & 15;
-        *(uint4 *)(keys + (size_t)row * kKeyStride + ch * 8) = cst[i];
+        *(uint4 *)(keys + slot(row, ch)) = cst[i];
     }
     if constexpr (AUG) {
         if (tid < R) {  // the centroids' extra coordinate, then 15 zeros
             const uint32_t a = crow0 + tid < Cpad ? d.caug[cur][(size_t)u * Cpad + crow0 + tid] : 0u;
-            bf16_t *dst = keys + (size_t)tid * kKeyStride + kD;
-            *(uint4 *)dst = make_uint4(a, 0, 0, 0);
-            *(uint4 *)(dst + 8) = make_uint4(0, 0, 0, 0);
+            kext[tid * 2] = make_uint4(a, 0, 0, 0);
+            kext[tid * 2 + 1] = make_uint4(0, 0, 0, 0);
         }
     }
     if (tid < 2 * kAssignTile) best[tid] = 0ull;
@@ -337,13 +356,24 @@ __global__ __launch_bounds__(512) void assign_kernel(const bf16_t *__restrict__ 
     bf16x8 A[CT][KS];
 #pragma unroll
     for (int ct = 0; ct < CT; ++ct) {
-        const bf16_t *crow = keys + (size_t)((cw * CT + ct) * 32 + col) * kKeyStride + half * 8;
+        const int r = (cw * CT + ct) * 32 + col;
 #pragma unroll
-        for (int ks = 0; ks < KS; ++ks) A[ct][ks] = __builtin_bit_cast(bf16x8, *(const uint4 *)(crow + ks * 16));
+        for (int ks = 0; ks < 8; ++ks) A[ct][ks] = __builtin_bit_cast(bf16x8, *(const uint4 *)(keys + slot(r, 2 * ks + half)));
+        if constexpr (AUG) A[ct][8] = __builtin_bit_cast(bf16x8, kext[r * 2 + half]);
     }
     __syncthreads();  // every wave holds its fragments before the first key tile overwrites them
-    if (ntiles > 0) store_tile(0);
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+        const int id = tid + 512 * i, row = id >> 4, ch = id & 15;
+        *(u32x4 *)(keys + slot(row, ch)) = first[i];
+    }
+    store_aug(0);
     __syncthreads();
+    // byte address of this lane's fragment chunk ks in row `col` of buffer 0; sub-tiles and the
+    // other buffer are constant offsets from it
+    uint32_t frag[8];
+#pragma unroll
+    for (int ks = 0; ks < 8; ++ks) frag[ks] = (uint32_t)slot(col, 2 * ks + half);
     ICE_BSTAMP(1);
 
     constexpr int NSUB = 8 / KW;  // 32-key sub-tiles of this wave per tile
@@ -352,7 +382,10 @@ __global__ __launch_bounds__(512) void assign_kernel(const bf16_t *__restrict__ 
         const int buf = t & 1;
         u64 *bestt = best + buf * kAssignTile;
         ICE_WSTAMP(t, 0);
-        if (t + 1 < ntiles) load_tile(t + 1);
+        if (t + 1 < ntiles) {
+            request_tile(t + 1, buf ^ 1);
+            load_aug(t + 1);
+        }
         // Software pipeline over "slots" j = (sub-tile i, centroid tile ct): while the matrix cores
         // run the 8-MFMA chain of slot j+1 into one accumulator set, the vector and scalar units
         // reduce slot j's 16 scores per lane from the other set (argmax16).  Only four to five
@@ -361,15 +394,15 @@ __global__ __launch_bounds__(512) void assign_kernel(const bf16_t *__restrict__ 
         constexpr int NSLOT = NSUB * CT;
         bf16x8 B[2][KS];
         auto load_b = [&](int i, bf16x8 (&dst)[KS]) {
-            const bf16_t *krow = keys + ((size_t)buf * kAssignTile + (kw + i * KW) * 32 + col) * kKeyStride + half * 8;
+            const char *sub = keys + buf * (kAssignTile * 256) + (kw + i * KW) * 32 * 256;  // (32 rows: r & 15 is col & 15)
 #pragma unroll
-            for (int ks = 0; ks < KS; ++ks) dst[ks] = __builtin_bit_cast(bf16x8, *(const uint4 *)(krow + ks * 16));
+            for (int ks = 0; ks < 8; ++ks) dst[ks] = __builtin_bit_cast(bf16x8, *(const uint4 *)(sub + frag[ks]));
+            if constexpr (AUG) dst[8] = __builtin_bit_cast(bf16x8, kext[(buf * kAssignTile + (kw + i * KW) * 32 + col) * 2 + half]);
         };
         f32x16 acc[2];
         auto chain = [&](int j, f32x16 &dst) {
             const int i = j / CT, ct = j % CT;
-            if constexpr (AUG) dst = *(const f32x16 *)(seeds + ((cw * CT + ct) * 2 + half) * 16);
-            else dst = seed[ct];
+            dst = seed[ct];
 #pragma unroll
             for (int ks = 0; ks < KS; ++ks)
                 dst = __builtin_amdgcn_mfma_f32_32x32x16_bf16(A[ct][ks], B[i & 1][ks], dst, 0, 0, 0);
@@ -416,7 +449,10 @@ __global__ __launch_bounds__(512) void assign_kernel(const bf16_t *__restrict__ 
         }
         ICE_BSTAMP(2 + 2 * (t & 3));
         ICE_WSTAMP(t, 1);
-        if (t + 1 < ntiles) store_tile(buf ^ 1);
+        if (t + 1 < ntiles) {
+            store_aug(buf ^ 1);
+            wait_lds_dma();  // this wave's share of the next tile is in LDS
+        }
         ICE_WSTAMP(t, 2);
         __syncthreads();
         ICE_WSTAMP(t, 3);
@@ -463,7 +499,7 @@ void launch_assign(const Dev &d, const bf16_t *K, int n, int cur, hipStream_t st
 #endif
     while ((long long)((n + keys_per_wg - 1) / keys_per_wg) * zsplit * d.U > wg_target && keys_per_wg < kpw_max) keys_per_wg *= 2;
     dim3 grid((n + keys_per_wg - 1) / keys_per_wg, zsplit, d.U);
-    const size_t lds = 2 * kAssignTile * key_stride(d.tk != 0) * 2 + 2 * kAssignTile * 8 + (d.tk ? 8 * 2 * 2 * 16 * 4 : 0);
+    const size_t lds = assign_lds_bytes(d.tk != 0);
     if (zsplit > 1) {
         const size_t tot = (size_t)d.U * d.max_tokens;
         hipLaunchKernelGGL(fill_u64_kernel, dim3(1024), dim3(256), 0, st, d.packed, tot, 0ull);
