@@ -164,50 +164,45 @@ __global__ void fill_u64_kernel(u64 *p, size_t n, u64 v) {
 //
 // A workgroup of 8 waves covers CW * CT * 32 centroids (wave w keeps CT tiles of 32 centroids in
 // registers for its whole life) and streams its share of the unit's keys through LDS in tiles of
-// 256 keys (coalesced 16-byte global loads, rows padded to 272 bytes so the 32-row operand reads
-// are bank-conflict free).  When CW < 8 the remaining waves split the key tile instead.  Per key
+// 256 keys (direct global -> LDS loads into unpadded rows whose 16-byte chunks are swizzled by row,
+// so the 32-row operand reads are bank-conflict free).  When CW < 8 the remaining waves split the
+// key tile instead.  Per key
 // the waves' candidates meet in an LDS 64-bit max of (ordered score, ~centroid id): the exact fp32
 // maximum with the lowest centroid id on ties.  More than CW*CT*32 centroids are covered by
 // blockIdx.y slices that meet the same way in global memory.
 //
-// In-lane argmax over the 16 scores of one accumulator tile: a binary tournament in which the
-// right-hand entry wins only when strictly larger (lowest element index on ties).  Each comparison
-// is one v_cmp into a scalar lane mask plus one v_cndmask for the value; the winner's element
-// index is never carried per lane: its four bits are assembled as lane masks on the scalar unit
-// (three scalar operations per 2:1 selection), which runs beside the vector and matrix pipes.
-__device__ inline u64 mask_mux(u64 sel, u64 hi, u64 lo) { return (sel & hi) | (~sel & lo); }
-
-__device__ inline void argmax16(const f32x16 &x, float &m, u64 (&bit)[4]) {
+// In-lane argmax over the 16 scores of one accumulator tile: a binary tournament of (value, index)
+// pairs in which the right-hand entry wins only when strictly larger (lowest element index on
+// ties): one v_cmp and two v_cndmask per comparison, 45 vector operations per tile, and the index
+// comes out as the local centroid id 8 (v / 4) + v % 4 of element v.  (Carrying the index bits as
+// lane masks on the scalar unit instead needs only 30 vector operations but ~40 scalar ones, and
+// measured 3 % slower: what limits the kernel is the number of instructions a wave has to issue
+// per MFMA, not the vector pipe.)
+__device__ inline void argmax16(const f32x16 &x, float &m, uint32_t &idx) {
     float t1[8], t2[4], t3[2];
-    u64 a[8], b[4], c[2], l0[4], h1[2], h0[2];
+    uint32_t i1[8], i2[4], i3[2];
 #pragma unroll
     for (int p = 0; p < 8; ++p) {
-        const bool g = x[2 * p + 1] > x[2 * p];
-        a[p] = __builtin_amdgcn_ballot_w64(g);
-        t1[p] = g ? x[2 * p + 1] : x[2 * p];
+        const int a = 2 * p, b = 2 * p + 1;
+        const bool g = x[b] > x[a];
+        t1[p] = g ? x[b] : x[a];
+        i1[p] = g ? (uint32_t)(8 * (b >> 2) + (b & 3)) : (uint32_t)(8 * (a >> 2) + (a & 3));
     }
 #pragma unroll
     for (int q = 0; q < 4; ++q) {
         const bool g = t1[2 * q + 1] > t1[2 * q];
-        b[q] = __builtin_amdgcn_ballot_w64(g);
         t2[q] = g ? t1[2 * q + 1] : t1[2 * q];
-        l0[q] = mask_mux(b[q], a[2 * q + 1], a[2 * q]);
+        i2[q] = g ? i1[2 * q + 1] : i1[2 * q];
     }
 #pragma unroll
     for (int h = 0; h < 2; ++h) {
         const bool g = t2[2 * h + 1] > t2[2 * h];
-        c[h] = __builtin_amdgcn_ballot_w64(g);
         t3[h] = g ? t2[2 * h + 1] : t2[2 * h];
-        h1[h] = mask_mux(c[h], b[2 * h + 1], b[2 * h]);
-        h0[h] = mask_mux(c[h], l0[2 * h + 1], l0[2 * h]);
+        i3[h] = g ? i2[2 * h + 1] : i2[2 * h];
     }
     const bool g = t3[1] > t3[0];
-    const u64 dm = __builtin_amdgcn_ballot_w64(g);
     m = g ? t3[1] : t3[0];
-    bit[3] = dm;
-    bit[2] = mask_mux(dm, c[1], c[0]);
-    bit[1] = mask_mux(dm, h1[1], h1[0]);
-    bit[0] = mask_mux(dm, h0[1], h0[0]);
+    idx = g ? i3[1] : i3[0];
 }
 
 #ifdef ICE_PROF
@@ -219,9 +214,6 @@ __device__ long long ice_prof_w[128];
 #define ICE_BSTAMP(i) do { } while (0)
 #define ICE_WSTAMP(t, i) do { } while (0)
 #endif
-// bf16 elements per LDS key row: 128 + 8 padding; with the extra coordinate of the transformed keys
-// 144 (one more 16-wide step of the contraction: the coordinate and 15 zeros) + 8 padding.  Both
-// strides keep the 32-row operand reads free of bank conflicts (68 and 76 dwords).
 // LDS layout of a 256-row tile (keys, or the centroid block while it is staged): rows of 256 bytes
 // without padding, the 16-byte chunk c of row r stored in slot c ^ (r & 15).  A fragment read (lane
 // = row r, chunk 2 ks + half) then hits 16 different 16-byte bank groups per 16 lanes (measured: the
@@ -387,10 +379,9 @@ __global__ __launch_bounds__(512) void assign_kernel(const bf16_t *__restrict__ 
             load_aug(t + 1);
         }
         // Software pipeline over "slots" j = (sub-tile i, centroid tile ct): while the matrix cores
-        // run the 8-MFMA chain of slot j+1 into one accumulator set, the vector and scalar units
-        // reduce slot j's 16 scores per lane from the other set (argmax16).  Only four to five
-        // vector operations fit under one MFMA, which is why the index half of the argmax lives
-        // in scalar lane masks.  The key operand of a sub-tile is read from LDS one sub-tile ahead.
+        // run the 8-MFMA chain of slot j+1 into one accumulator set, the vector unit
+        // reduces slot j's 16 scores per lane from the other set (argmax16).  The key operand of a
+        // sub-tile is read from LDS one sub-tile ahead.
         constexpr int NSLOT = NSUB * CT;
         bf16x8 B[2][KS];
         auto load_b = [&](int i, bf16x8 (&dst)[KS]) {
@@ -411,7 +402,7 @@ __global__ __launch_bounds__(512) void assign_kernel(const bf16_t *__restrict__ 
         if (CT == 1 && NSUB > 1) load_b(1, B[1]);
         chain(0, acc[0]);
         float sv = 0.f;
-        u64 sbit[5] = {0, 0, 0, 0, 0};
+        uint32_t sidx = 0;
 #pragma unroll
         for (int j = 0; j < NSLOT; ++j) {
             const int i = j / CT, ct = j % CT;
@@ -421,29 +412,18 @@ __global__ __launch_bounds__(512) void assign_kernel(const bf16_t *__restrict__ 
             if (j + 1 < NSLOT) chain(j + 1, acc[(j + 1) & 1]);
             // element v of this lane has local centroid id ct*32 + 8*(v/4) + v%4 (+ 4*half), ascending in v
             float m;
-            u64 bit[4];
-            argmax16(acc[j & 1], m, bit);
+            uint32_t li;
+            argmax16(acc[j & 1], m, li);
             if (ct == 0) {
                 sv = m;
-#pragma unroll
-                for (int b = 0; b < 4; ++b) sbit[b] = bit[b];
-                sbit[4] = 0;
+                sidx = li;
             } else {
                 const bool gt = m > sv;
-                const u64 e = __builtin_amdgcn_ballot_w64(gt);
                 sv = gt ? m : sv;
-#pragma unroll
-                for (int b = 0; b < 4; ++b) sbit[b] = mask_mux(e, bit[b], sbit[b]);
-                sbit[4] = e;
+                sidx = gt ? li + 32u * ct : sidx;
             }
             if (ct == CT - 1) {
-                const uint32_t local = (__builtin_amdgcn_inverse_ballot_w64(sbit[0]) ? 1u : 0u) |
-                                       (__builtin_amdgcn_inverse_ballot_w64(sbit[1]) ? 2u : 0u) |
-                                       (__builtin_amdgcn_inverse_ballot_w64(sbit[2]) ? 8u : 0u) |
-                                       (__builtin_amdgcn_inverse_ballot_w64(sbit[3]) ? 16u : 0u) |
-                                       (__builtin_amdgcn_inverse_ballot_w64(sbit[4]) ? 32u : 0u);
-                // +0.0f: a score of -0 must pack like +0
-                const u64 pk = ((u64)f32_ordered(sv + 0.0f) << 32) | (u64)(inv_cid0 - local);
+                const u64 pk = ((u64)f32_ordered(sv + 0.0f) << 32) | (u64)(inv_cid0 - sidx);
                 atomicMax(&bestt[(kw + i * KW) * 32 + col], pk);
             }
         }
@@ -489,8 +469,8 @@ void launch_assign(const Dev &d, const bf16_t *K, int n, int cur, hipStream_t st
     while (CW < 8 && CW * CT < tiles) CW *= 2;
     const int cblock = CT * CW * 32;
     const int zsplit = (d.Cpad + cblock - 1) / cblock;
-    // One workgroup per CU when the work allows it (a workgroup fills a CU: 140 KB of LDS, 8 waves
-    // of ~230 registers), each amortising its prologue over as many key tiles as possible.
+    // One workgroup per CU when the work allows it (a workgroup fills a CU: 132-148 KB of LDS, 8 waves
+    // of 226-256 registers), each amortising its prologue over as many key tiles as possible.
     int keys_per_wg = kAssignTile;
     int wg_target = 256, kpw_max = 1 << 30;
 #ifdef ICE_PROF
