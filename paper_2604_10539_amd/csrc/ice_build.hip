@@ -171,40 +171,46 @@ __global__ void fill_u64_kernel(u64 *p, size_t n, u64 v) {
 // maximum with the lowest centroid id on ties.  More than CW*CT*32 centroids are covered by
 // blockIdx.y slices that meet the same way in global memory.
 //
-// In-lane argmax over the 16 scores of one accumulator tile: a binary tournament of (value, index)
-// pairs in which the right-hand entry wins only when strictly larger (lowest element index on
-// ties): one v_cmp and two v_cndmask per comparison, 45 vector operations per tile, and the index
-// comes out as the local centroid id 8 (v / 4) + v % 4 of element v.  (Carrying the index bits as
-// lane masks on the scalar unit instead needs only 30 vector operations but ~40 scalar ones, and
-// measured 3 % slower: what limits the kernel is the number of instructions a wave has to issue
-// per MFMA, not the vector pipe.)
+// In-lane argmax over the 16 scores of one accumulator tile: a tournament with three entries per
+// node.  The value of a node is one v_max3; its index follows by equality with that value, the
+// first of the three entries winning ties (lowest element index), i.e. two v_cmp and two v_cndmask:
+// 5 vector operations for every two entries removed, 38 per tile (a binary tournament of (value,
+// index) pairs needs 45, and measured 2 % slower; carrying the index bits as lane masks on the
+// scalar unit needs 30 vector + ~40 scalar operations and measured 5 % slower: what limits the
+// kernel is the number of instructions a wave has to issue per MFMA).  The index comes out as the
+// local centroid id 8 (v / 4) + v % 4 of element v.  Written level by level (all maxima, then all
+// comparisons, then all selects) so that a comparison and the select that consumes its lane mask
+// need not be adjacent.
+__device__ inline float max3f(float a, float b, float c) { return __builtin_fmaxf(__builtin_fmaxf(a, b), c); }
 __device__ inline void argmax16(const f32x16 &x, float &m, uint32_t &idx) {
-    float t1[8], t2[4], t3[2];
-    uint32_t i1[8], i2[4], i3[2];
+    auto id = [](int v) { return (uint32_t)(8 * (v >> 2) + (v & 3)); };
+    float t1[6], t2[2];
+    uint32_t i1[6], i2[2];
+    bool ea[5], eb[5];
 #pragma unroll
-    for (int p = 0; p < 8; ++p) {
-        const int a = 2 * p, b = 2 * p + 1;
-        const bool g = x[b] > x[a];
-        t1[p] = g ? x[b] : x[a];
-        i1[p] = g ? (uint32_t)(8 * (b >> 2) + (b & 3)) : (uint32_t)(8 * (a >> 2) + (a & 3));
-    }
+    for (int p = 0; p < 5; ++p) t1[p] = max3f(x[3 * p], x[3 * p + 1], x[3 * p + 2]);
+    t1[5] = x[15];
+    t2[0] = max3f(t1[0], t1[1], t1[2]);
+    t2[1] = max3f(t1[3], t1[4], t1[5]);
 #pragma unroll
-    for (int q = 0; q < 4; ++q) {
-        const bool g = t1[2 * q + 1] > t1[2 * q];
-        t2[q] = g ? t1[2 * q + 1] : t1[2 * q];
-        i2[q] = g ? i1[2 * q + 1] : i1[2 * q];
+    for (int p = 0; p < 5; ++p) {
+        ea[p] = x[3 * p] == t1[p];
+        eb[p] = x[3 * p + 1] == t1[p];
     }
+    const bool fa0 = t1[0] == t2[0], fb0 = t1[1] == t2[0], fa1 = t1[3] == t2[1], fb1 = t1[4] == t2[1];
+    const bool g = t2[1] > t2[0];
 #pragma unroll
-    for (int h = 0; h < 2; ++h) {
-        const bool g = t2[2 * h + 1] > t2[2 * h];
-        t3[h] = g ? t2[2 * h + 1] : t2[2 * h];
-        i3[h] = g ? i2[2 * h + 1] : i2[2 * h];
+    for (int p = 0; p < 5; ++p) {
+        const uint32_t t = eb[p] ? id(3 * p + 1) : id(3 * p + 2);
+        i1[p] = ea[p] ? id(3 * p) : t;
     }
-    const bool g = t3[1] > t3[0];
-    m = g ? t3[1] : t3[0];
-    idx = g ? i3[1] : i3[0];
+    i1[5] = id(15);
+    const uint32_t u0 = fb0 ? i1[1] : i1[2], u1 = fb1 ? i1[4] : i1[5];
+    i2[0] = fa0 ? i1[0] : u0;
+    i2[1] = fa1 ? i1[3] : u1;
+    m = g ? t2[1] : t2[0];
+    idx = g ? i2[1] : i2[0];
 }
-
 #ifdef ICE_PROF
 __device__ long long ice_prof_b[16];
 __device__ long long ice_prof_w[128];
