@@ -1,5 +1,6 @@
 // Host side of the C ABI: argument validation, workspace layout, launch sequencing.
 // No call here allocates device memory, synchronises, or reads device memory.
+#include <algorithm>
 #include <cstdarg>
 #include <cstdio>
 #include <cstring>
@@ -55,7 +56,6 @@ size_t lay_out(const ice_config_t &cfg, int s, int C, char *base, Dev *out) {
     d.max_tokens = cfg.max_tokens;
     d.max_pages = cfg.max_tokens / s + C;
     const size_t U = d.U, MP = d.max_pages, MT = d.max_tokens, CP = d.Cpad;
-    const size_t n_chunks = (MT + kSortChunk - 1) / kSortChunk;
     size_t off = 0;
     auto take = [&](size_t bytes) -> char * {
         char *p = base ? base + off : nullptr;
@@ -88,9 +88,9 @@ size_t lay_out(const ice_config_t &cfg, int s, int C, char *base, Dev *out) {
     d.assign = (int *)take(U * MT * 4);
     d.packed = (unsigned long long *)take(U * MT * 8);
     d.order = (int *)take(U * MT * 4);
-    d.chunk_hist = (int *)take(U * n_chunks * CP * 4);
     d.cluster_start = (int *)take(U * (CP + 1) * 4);
     d.page_base = (int *)take(U * (CP + 1) * 4);
+    d.range_tot = (int *)take(std::max<size_t>(U, 256) * CP * 4);
     d.scores = (uint32_t *)take(U * MP * 4);
     d.counter = (int *)take(U * 4);
     if (out) *out = d;

@@ -1,6 +1,7 @@
 // Index build at prefill: promotion of the initial centroids, nearest-centroid assignment on the
 // matrix cores, deterministic per-cluster means, and the node -> page layout (Sec. 4.1-4.2,
 // Alg. 2 of the paper restricted to two levels and iterated as Lloyd rounds).
+#include <algorithm>
 #include <cstdlib>
 
 #include "ice_internal.h"
@@ -512,64 +513,140 @@ void launch_assign(const Dev &d, const bf16_t *K, int n, int cur, hipStream_t st
 
 // ------------------------------------------------------------------------------------------------
 // Stable counting sort of the tokens by cluster (ascending position inside a cluster): the order
-// both the deterministic means and the page layout need.  Three small kernels: per-chunk
-// histograms (which also unpack the assignment), scans, ranks.
-__global__ __launch_bounds__(64) void sort_hist_kernel(Dev d, int n, int n_chunks, float *best_out,
-                                                        int *assign_out) {
-    extern __shared__ int cnt[];  // [Cpad]
-    const int u = blockIdx.y, lane = threadIdx.x, chunk = blockIdx.x;
-    for (int c = lane; c < d.Cpad; c += 64) cnt[c] = 0;
-    constexpr int NG = kSortChunk / 64;
-    const int i0 = chunk * kSortChunk;
-    u64 pk[NG];  // the whole chunk is in flight before the first counter is touched
+// both the deterministic means and the page layout need.  A unit's tokens are cut into R ranges,
+// one workgroup of 16 waves each (R = 1 once there are 256 units; with fewer units more workgroups
+// per unit keep the chip busy), all counters in LDS.  With R > 1 a first kernel leaves every
+// range's member count per cluster in global memory (sort_totals_kernel).  The sorting kernel
+// cuts its range into W segments of `seg` tokens (a multiple of 64), wave w owns segment w:
+//   count  the wave unpacks its tokens' winners (and writes the assignment) and bumps
+//          cnt[w][cluster]; with REG (a segment has at most 32 groups of 64 tokens) the cluster
+//          ids stay in registers for the last phase;
+//   scan   per cluster an exclusive scan over the earlier ranges (their totals) and over the
+//          segments, then over the clusters (member counts and page counts of the whole unit),
+//          which turns cnt[w][c] into the first output slot of segment w's members of cluster c
+//          and yields the cluster and page offsets (written by the workgroup of range 0);
+//   rank   the wave walks its segment in token order, 64 tokens at a time: lanes with the same
+//          cluster find each other through a lane mask per cluster, the first of them moves the
+//          cluster's cursor past all of them.
+// A segment and cluster take 12 bytes of LDS (counter + lane mask): W = min(16, 12288 / Cpad)
+// segments fit in 144 KB.
+__global__ __launch_bounds__(1024) void sort_totals_kernel(Dev d, int n, int range_len) {
+    extern __shared__ int tot[];  // [Cpad]
+    const int r = blockIdx.x, u = blockIdx.y, tid = threadIdx.x;
+    const int Cpad = d.Cpad;
+    const uint32_t *pk = (const uint32_t *)(d.packed + (size_t)u * d.max_tokens);
+    const int rb = r * range_len, re = min(n, rb + range_len);
+    uint32_t v[4];  // (the first 4096 tokens are in flight while the counters are cleared)
 #pragma unroll
-    for (int g = 0; g < NG; ++g) {
-        const int i = i0 + g * 64 + lane;
-        pk[g] = i < n ? d.packed[(size_t)u * d.max_tokens + i] : 0ull;
+    for (int j = 0; j < 4; ++j) v[j] = rb + j * 1024 + tid < re ? pk[2 * (rb + j * 1024 + tid)] : 0u;
+    for (int c = tid; c < Cpad; c += 1024) tot[c] = 0;
+    __syncthreads();
+    for (int i0 = rb; i0 < re; i0 += 4096) {
+        if (i0 > rb) {
+#pragma unroll
+            for (int j = 0; j < 4; ++j) v[j] = i0 + j * 1024 + tid < re ? pk[2 * (i0 + j * 1024 + tid)] : 0u;
+        }
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+            if (i0 + j * 1024 + tid < re) atomicAdd(&tot[(int)min(0xFFFFFFFFu - v[j], (uint32_t)Cpad - 1u)], 1);
     }
     __syncthreads();
+    int *out = d.range_tot + ((size_t)u * gridDim.x + r) * Cpad;
+    for (int c = tid; c < Cpad; c += 1024) out[c] = tot[c];
+}
+
+constexpr int kSortRegGroups = 32;
+
+template <bool REG>
+__global__ __launch_bounds__(1024) void sort_unit_kernel(Dev d, int n, int range_len, int W, int seg, float *best_out,
+                                                         int *assign_out) {
+    extern __shared__ __align__(8) int cnt[];  // [W][Cpad] counters, then [W][Cpad] 64-bit lane masks
+    __shared__ int wsum[2][16];
+    __shared__ int carry[2];
+    const int r = blockIdx.x, R = gridDim.x, u = blockIdx.y, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int Cpad = d.Cpad;
+    const int rb = r * range_len, re = min(n, rb + range_len);  // this workgroup's tokens
+    // low word of a packed winner = ~cluster id (the high word, the score, is read only for best_out)
+    const uint32_t *pk = (const uint32_t *)(d.packed + (size_t)u * d.max_tokens);
+    const int beg = min(re, rb + wave * seg), end = wave < W ? min(re, beg + seg) : beg;  // this wave's tokens
+    // the winners of the first groups are in flight while the counters are cleared
+    constexpr int NB = REG ? kSortRegGroups : 16;  // groups per batch of loads
+    uint32_t v[NB];
 #pragma unroll
-    for (int g = 0; g < NG; ++g) {
-        const int i = i0 + g * 64 + lane;
-        if (i < n) {
-            const int a = (int)(0xFFFFFFFFu - (uint32_t)pk[g]);
-            d.assign[(size_t)u * d.max_tokens + i] = a;
-            if (assign_out) assign_out[(size_t)u * n + i] = a;
-            if (best_out) best_out[(size_t)u * n + i] = -2.0f * ordered_f32((uint32_t)(pk[g] >> 32));
-            atomicAdd(&cnt[a], 1);
+    for (int j = 0; j < NB; ++j) {
+        const int i = beg + j * 64 + lane;
+        v[j] = i < end ? pk[2 * i] : 0u;
+    }
+    u64 *mask_all = (u64 *)(cnt + W * Cpad);  // [W][Cpad] lane masks of the rank phase
+    for (int x = tid; x < W * Cpad; x += 1024) { cnt[x] = 0; mask_all[x] = 0ull; }
+    if (tid < 2) carry[tid] = 0;
+    __syncthreads();
+    int *pos = cnt + (wave < W ? wave : 0) * Cpad;
+    u64 *mask = mask_all + (size_t)(wave < W ? wave : 0) * Cpad;
+    // cluster id of a packed winner (always < Cpad for finite keys; clamped so that no input can
+    // send a counter update or an output slot out of range)
+    auto cluster_of = [&](uint32_t w) { return (int)min(0xFFFFFFFFu - w, (uint32_t)Cpad - 1u); };
+    auto count_one = [&](int i, uint32_t w) {
+        const int a = cluster_of(w);
+        d.assign[(size_t)u * d.max_tokens + i] = a;
+        if (assign_out) assign_out[(size_t)u * n + i] = a;
+        if (best_out) best_out[(size_t)u * n + i] = -2.0f * ordered_f32(pk[2 * i + 1]);
+        atomicAdd(&pos[a], 1);
+        return a;
+    };
+    int areg[REG ? kSortRegGroups : 1];
+    // ---- count
+    if constexpr (REG) {
+#pragma unroll
+        for (int j = 0; j < NB; ++j) {
+            const int i = beg + j * 64 + lane;
+            areg[j] = i < end ? count_one(i, v[j]) : 0;
+        }
+    } else {
+        for (int g0 = beg; g0 < end; g0 += NB * 64) {
+            if (g0 > beg) {
+#pragma unroll
+                for (int j = 0; j < NB; ++j) {
+                    const int i = g0 + j * 64 + lane;
+                    v[j] = i < end ? pk[2 * i] : 0u;
+                }
+            }
+#pragma unroll
+            for (int j = 0; j < NB; ++j) {
+                const int i = g0 + j * 64 + lane;
+                if (i < end) count_one(i, v[j]);
+            }
         }
     }
     __syncthreads();
-    for (int c = lane; c < d.Cpad; c += 64) d.chunk_hist[((size_t)u * n_chunks + chunk) * d.Cpad + c] = cnt[c];
-}
-
-// One workgroup per unit: per cluster, exclusive scan of the chunk histograms over the chunks;
-// then exclusive scans over the clusters of the member counts and of the page counts.
-__global__ __launch_bounds__(1024) void sort_scan_kernel(Dev d, int n_chunks) {
-    __shared__ int wsum[2][16];
-    __shared__ int carry[2];
-    const int u = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    if (tid < 2) carry[tid] = 0;
-    __syncthreads();
-    for (int c0 = 0; c0 < d.Cpad; c0 += 1024) {
+    // ---- scan
+    const int *rtot = d.range_tot + (size_t)u * R * Cpad;
+    for (int c0 = 0; c0 < Cpad; c0 += 1024) {
         const int c = c0 + tid;
-        int tot = 0;
-        if (c < d.Cpad) {
-            int *h = d.chunk_hist + (size_t)u * n_chunks * d.Cpad + c;
-            for (int k0 = 0; k0 < n_chunks; k0 += 16) {  // 16 counts in flight per round trip
-                int v[16];
+        int own = 0, before = 0, tot = 0;
+        if (c < Cpad) {
+            for (int w = 0; w < W; ++w) {
+                const int t = cnt[w * Cpad + c];
+                cnt[w * Cpad + c] = own;
+                own += t;
+            }
+            tot = own;
+            if (R > 1) {
+                tot = 0;
+                for (int q0 = 0; q0 < R; q0 += 16) {  // 16 counts in flight per round trip
+                    int t[16];
 #pragma unroll
-                for (int j = 0; j < 16; ++j) v[j] = k0 + j < n_chunks ? h[(size_t)(k0 + j) * d.Cpad] : 0;
+                    for (int j = 0; j < 16; ++j) t[j] = q0 + j < R ? rtot[(size_t)(q0 + j) * Cpad + c] : 0;
 #pragma unroll
-                for (int j = 0; j < 16; ++j) {
-                    if (k0 + j < n_chunks) h[(size_t)(k0 + j) * d.Cpad] = tot;
-                    tot += v[j];
+                    for (int j = 0; j < 16; ++j) {
+                        if (q0 + j < r) before += t[j];
+                        tot += t[j];
+                    }
                 }
             }
         }
         const int pages = (tot + d.s - 1) / d.s;
-        // inclusive wave scans of (tot, pages)
-        int a = tot, b = pages;
+        int a = tot, b = pages;  // inclusive wave scans of (tot, pages)
         for (int off = 1; off < 64; off <<= 1) {
             const int ta = __shfl_up(a, off), tb = __shfl_up(b, off);
             if (lane >= off) { a += ta; b += tb; }
@@ -579,68 +656,92 @@ __global__ __launch_bounds__(1024) void sort_scan_kernel(Dev d, int n_chunks) {
         int pa = carry[0], pb = carry[1];
         for (int w = 0; w < wave; ++w) { pa += wsum[0][w]; pb += wsum[1][w]; }
         const int ex_a = pa + a - tot, ex_b = pb + b - pages;
-        if (c < d.Cpad) {
-            d.cluster_start[(size_t)u * (d.Cpad + 1) + c] = ex_a;
-            d.page_base[(size_t)u * (d.Cpad + 1) + c] = ex_b;
-            if (c < d.C) {
-                d.cluster_cnt[(size_t)u * d.C + c] = tot;
-                d.cluster_tail[(size_t)u * d.C + c] = tot > 0 ? ex_b + pages - 1 : -1;
+        if (c < Cpad) {
+            for (int w = 0; w < W; ++w) cnt[w * Cpad + c] += ex_a + before;
+            if (r == 0) {
+                d.cluster_start[(size_t)u * (Cpad + 1) + c] = ex_a;
+                d.page_base[(size_t)u * (Cpad + 1) + c] = ex_b;
+                if (c < d.C) {
+                    d.cluster_cnt[(size_t)u * d.C + c] = tot;
+                    d.cluster_tail[(size_t)u * d.C + c] = tot > 0 ? ex_b + pages - 1 : -1;
+                }
             }
         }
         __syncthreads();
         if (tid == 1023) { carry[0] = pa + a; carry[1] = pb + b; }
         __syncthreads();
     }
-    if (tid == 0) {
-        d.cluster_start[(size_t)u * (d.Cpad + 1) + d.Cpad] = carry[0];
-        d.page_base[(size_t)u * (d.Cpad + 1) + d.Cpad] = carry[1];
+    if (tid == 0 && r == 0) {
+        d.cluster_start[(size_t)u * (Cpad + 1) + Cpad] = carry[0];
+        d.page_base[(size_t)u * (Cpad + 1) + Cpad] = carry[1];
         d.n_pages[u] = carry[1];
+    }
+    // ---- rank (row `wave` of the counters is touched by this wave only from here on)
+    int *order = d.order + (size_t)u * d.max_tokens;
+    const u64 lt = (1ull << lane) - 1ull;
+    // Lanes of one group with the same cluster find each other through a 64-bit lane mask per
+    // cluster in LDS (a table of this wave's own): every lane ORs its bit into its cluster's entry,
+    // reads the entry back and clears it.  The LDS unit executes one wave's instructions in order,
+    // so the three steps need no wait between them, only their program order.
+    auto rank_group = [&](int i, int a) {
+        const bool valid = i < end;
+        u64 peers = 0ull;
+        int base = 0;
+        if (valid) atomicOr(&mask[a], 1ull << lane);
+        __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+        if (valid) { peers = mask[a]; base = pos[a]; }
+        __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+        if (valid) {
+            mask[a] = 0ull;
+            if ((peers & lt) == 0ull) pos[a] = base + (int)__popcll(peers);  // the first of them moves the cursor
+            order[base + (int)__popcll(peers & lt)] = i;
+        }
+        __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+    };
+    if constexpr (REG) {
+#pragma unroll
+        for (int j = 0; j < NB; ++j) {
+            if (beg + j * 64 >= end) break;  // (wave-uniform)
+            rank_group(beg + j * 64 + lane, areg[j]);
+        }
+    } else {
+        for (int g0 = beg; g0 < end; g0 += NB * 64) {
+#pragma unroll
+            for (int j = 0; j < NB; ++j) {
+                const int i = g0 + j * 64 + lane;
+                v[j] = i < end ? pk[2 * i] : 0u;  // (read again; nothing written above is read back)
+            }
+#pragma unroll
+            for (int j = 0; j < NB; ++j) {
+                if (g0 + j * 64 >= end) break;  // (wave-uniform)
+                rank_group(g0 + j * 64 + lane, cluster_of(v[j]));
+            }
+        }
     }
 }
 
-__global__ __launch_bounds__(64) void sort_rank_kernel(Dev d, int n, int n_chunks, int nbits) {
-    extern __shared__ int cnt[];  // [Cpad] running write positions
-    const int u = blockIdx.y, lane = threadIdx.x, chunk = blockIdx.x;
-    constexpr int NG = kSortChunk / 64;
-    const int i0 = chunk * kSortChunk;
-    int av[NG];
-#pragma unroll
-    for (int g = 0; g < NG; ++g) {
-        const int i = i0 + g * 64 + lane;
-        av[g] = i < n ? d.assign[(size_t)u * d.max_tokens + i] : 0;
-    }
-    for (int c = lane; c < d.Cpad; c += 64)
-        cnt[c] = d.cluster_start[(size_t)u * (d.Cpad + 1) + c] + d.chunk_hist[((size_t)u * n_chunks + chunk) * d.Cpad + c];
-    __syncthreads();
-    const u64 lt = (1ull << lane) - 1ull;
-#pragma unroll
-    for (int g = 0; g < NG; ++g) {
-        const int i = i0 + g * 64 + lane;
-        const bool valid = i < n;
-        const int a = av[g];
-        u64 peers = __ballot(valid);
-        for (int b = 0; b < nbits; ++b) {
-            const bool bit = (a >> b) & 1;
-            const u64 bal = __ballot(bit);
-            peers &= bit ? bal : ~bal;
-        }
-        if (!valid) peers = 0ull;  // (only trailing lanes of the last group)
-        int base = 0;
-        const int leader = valid ? (int)__builtin_ctzll(peers) : lane;
-        if (valid && lane == leader) base = atomicAdd(&cnt[a], (int)__popcll(peers));
-        base = __shfl(base, leader);
-        if (valid) d.order[(size_t)u * d.max_tokens + base + (int)__popcll(peers & lt)] = i;
-    }
+// ranges per unit of the sort: enough workgroups for the chip, at least 1024 tokens each
+int sort_ranges(int U, int n, int *range_len) {
+    int R = std::max(1, std::min(256 / std::max(U, 1), (n + 1023) / 1024));
+    *range_len = round_up((n + R - 1) / R, 64);
+    return (n + *range_len - 1) / *range_len;
 }
 
 void launch_sort(const Dev &d, int n, float *best_out, int *assign_out, hipStream_t st) {
-    const int n_chunks = (n + kSortChunk - 1) / kSortChunk;
-    int nbits = 0;
-    while ((1 << nbits) < d.Cpad) ++nbits;
-    const size_t lds = (size_t)d.Cpad * sizeof(int);
-    hipLaunchKernelGGL(sort_hist_kernel, dim3(n_chunks, d.U), dim3(64), lds, st, d, n, n_chunks, best_out, assign_out);
-    hipLaunchKernelGGL(sort_scan_kernel, dim3(d.U), dim3(1024), 0, st, d, n_chunks);
-    hipLaunchKernelGGL(sort_rank_kernel, dim3(n_chunks, d.U), dim3(64), lds, st, d, n, n_chunks, nbits);
+    int range_len;
+    const int R = sort_ranges(d.U, n, &range_len);
+    const int W = d.Cpad <= 768 ? 16 : 12288 / d.Cpad;  // (12 bytes per segment and cluster in 144 KB; Cpad <= 8192: W >= 1)
+    const int seg = round_up((range_len + W - 1) / W, 64);
+    const size_t lds = (size_t)W * d.Cpad * 12;
+    if (R > 1)
+        hipLaunchKernelGGL(sort_totals_kernel, dim3(R, d.U), dim3(1024), (size_t)d.Cpad * sizeof(int), st, d, n, range_len);
+    if (seg <= kSortRegGroups * 64) {
+        (void)hipFuncSetAttribute((const void *)sort_unit_kernel<true>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        hipLaunchKernelGGL(sort_unit_kernel<true>, dim3(R, d.U), dim3(1024), lds, st, d, n, range_len, W, seg, best_out, assign_out);
+    } else {
+        (void)hipFuncSetAttribute((const void *)sort_unit_kernel<false>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        hipLaunchKernelGGL(sort_unit_kernel<false>, dim3(R, d.U), dim3(1024), lds, st, d, n, range_len, W, seg, best_out, assign_out);
+    }
 }
 // The key rows of one clustering pass are read by assign, then by means (and once more by paginate).
 // While they fit the chip's last-level cache (256 MB) the second reader finds them there; beyond
@@ -648,30 +749,33 @@ void launch_sort(const Dev &d, int n, float *best_out, int *assign_out, hipStrea
 static bool keys_exceed_cache(const Dev &d, int n) { return (size_t)d.U * (size_t)n * kD * sizeof(bf16_t) >= ((size_t)256 << 20); }
 
 // ------------------------------------------------------------------------------------------------
-// Centroid update: one wave per cluster gathers its members' key rows (256 contiguous bytes each,
-// 16 lanes x 16 bytes, four rows per load) in sorted order and sums them in fp32 in a fixed order,
-// so the result is the same on every run (no floating-point atomics).  Writes sum, count, mean,
-// and the bf16 rounding + squared norm of the mean into the OTHER centroid buffer; an empty
-// cluster keeps its centroid.
+// Centroid update: one workgroup of four waves per cluster.  Wave w gathers the w-th quarter of the
+// cluster's members in sorted order (key rows of 256 contiguous bytes, 16 lanes x 16 bytes, four
+// rows per load) and sums them in fp32 in a fixed order; the four partial sums meet in LDS and are
+// added in wave order, so the result is the same on every run (no floating-point atomics) and a
+// large cluster costs a quarter of the dependent round trips.  Writes sum, count, mean, and the
+// bf16 rounding + squared norm of the mean into the OTHER centroid buffer; an empty cluster keeps
+// its centroid.
 template <bool STREAM>
 __global__ __launch_bounds__(256) void means_kernel(Dev d, const bf16_t *__restrict__ K, int n, int cur) {
-    const int u = blockIdx.y, wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
-    const int c = blockIdx.x * 4 + wave;
-    if (c >= d.C) return;
+    __shared__ float4 part_sum[3][16][2];
+    const int u = blockIdx.y, c = blockIdx.x, wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
     const int g = lane >> 4, ch = lane & 15;
     const int start = d.cluster_start[(size_t)u * (d.Cpad + 1) + c];
     const int cnt = d.cluster_start[(size_t)u * (d.Cpad + 1) + c + 1] - start;
     const int *ord = d.order + (size_t)u * d.max_tokens + start;
     const bf16_t *Ku = K + (size_t)u * n * kD;
+    const int quarter = (cnt + 3) / 4;
+    const int lo = min(cnt, wave * quarter), hi = min(cnt, lo + quarter);
     float acc[8];
 #pragma unroll
     for (int j = 0; j < 8; ++j) acc[j] = 0.f;
-    // Group g sums rows g, g+4, g+8, ... in that order.  The member list is read 64 entries at a
-    // time (one per lane) and the rows are fetched eight per group at once, so a wave keeps 8 KB
-    // of key rows in flight instead of one dependent load pair per step.
-    for (int base = 0; base < cnt; base += 64) {
-        const int mine = base + lane < cnt ? ord[base + lane] : -1;
-        const int rows = min(64, cnt - base);
+    // Group g of a wave sums rows g, g+4, g+8, ... of the wave's range in that order.  The member
+    // list is read 64 entries at a time (one per lane) and the rows are fetched eight per group at
+    // once, so a wave keeps 8 KB of key rows in flight instead of one dependent load pair per step.
+    for (int base = lo; base < hi; base += 64) {
+        const int mine = base + lane < hi ? ord[base + lane] : -1;
+        const int rows = min(64, hi - base);
 #pragma unroll
         for (int h = 0; h < 2; ++h) {
             if (h * 32 >= rows) break;
@@ -695,6 +799,23 @@ __global__ __launch_bounds__(256) void means_kernel(Dev d, const bf16_t *__restr
         acc[j] += __shfl_xor(acc[j], 16);
         acc[j] += __shfl_xor(acc[j], 32);
     }
+    // (transformed keys) sum of the members' extra coordinates: lane-strided partial sums in member
+    // order by the first wave, requested before the waves meet
+    float aug_part = 0.f;
+    if (d.tk && wave == 0)
+        for (int r = lane; r < cnt; r += 64) aug_part += bf16_to_f32(d.kaug[(size_t)u * d.max_tokens + ord[r]]);
+    if (wave > 0 && g == 0) {
+        part_sum[wave - 1][ch][0] = make_float4(acc[0], acc[1], acc[2], acc[3]);
+        part_sum[wave - 1][ch][1] = make_float4(acc[4], acc[5], acc[6], acc[7]);
+    }
+    __syncthreads();
+    if (wave > 0) return;
+#pragma unroll
+    for (int w = 0; w < 3; ++w) {
+        const float4 p0 = part_sum[w][ch][0], p1 = part_sum[w][ch][1];
+        acc[0] += p0.x; acc[1] += p0.y; acc[2] += p0.z; acc[3] += p0.w;
+        acc[4] += p1.x; acc[5] += p1.y; acc[6] += p1.z; acc[7] += p1.w;
+    }
     float mu[8];
     float *cen = d.centroid + ((size_t)u * d.C + c) * kD + ch * 8;
     if (cnt > 0) {
@@ -715,11 +836,9 @@ __global__ __launch_bounds__(256) void means_kernel(Dev d, const bf16_t *__restr
     }
     nn = row16_sum(nn);
     if (d.tk) {
-        // the centroid's extra coordinate: mean of the members' extra coordinates (lane-strided partial
-        // sums in member order, then the fixed wave reduction)
-        float part = 0.f;
-        for (int r = lane; r < cnt; r += 64) part += bf16_to_f32(d.kaug[(size_t)u * d.max_tokens + ord[r]]);
-        const float asum = wave_sum(part);
+        // the centroid's extra coordinate: mean of the members' extra coordinates (the fixed wave
+        // reduction of the partial sums above)
+        const float asum = wave_sum(aug_part);
         const float e = cnt > 0 ? asum / (float)cnt : d.cent_aug[(size_t)u * d.C + c];
         const bf16_t eb = f32_to_bf16(e);
         const float ef = bf16_to_f32(eb);
@@ -742,8 +861,8 @@ __global__ __launch_bounds__(256) void means_kernel(Dev d, const bf16_t *__restr
 }
 
 void launch_means(const Dev &d, const bf16_t *K, int n, int cur, hipStream_t st) {
-    if (keys_exceed_cache(d, n)) hipLaunchKernelGGL(means_kernel<true>, dim3((d.C + 3) / 4, d.U), dim3(256), 0, st, d, K, n, cur);
-    else hipLaunchKernelGGL(means_kernel<false>, dim3((d.C + 3) / 4, d.U), dim3(256), 0, st, d, K, n, cur);
+    if (keys_exceed_cache(d, n)) hipLaunchKernelGGL(means_kernel<true>, dim3(d.C, d.U), dim3(256), 0, st, d, K, n, cur);
+    else hipLaunchKernelGGL(means_kernel<false>, dim3(d.C, d.U), dim3(256), 0, st, d, K, n, cur);
 }
 
 // ------------------------------------------------------------------------------------------------

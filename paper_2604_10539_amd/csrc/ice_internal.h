@@ -8,7 +8,6 @@
 namespace ice {
 
 constexpr int kD = 128;          // head_dim
-constexpr int kSortChunk = 1024; // tokens per wave in the counting sort
 constexpr int kAssignTile = 256; // keys staged in LDS per step of the assign kernel
 
 typedef uint16_t bf16_t;
@@ -40,9 +39,9 @@ struct Dev {
     int *assign;                // [U][max_tokens]
     unsigned long long *packed; // [U][max_tokens] (ordered score << 32) | ~cluster
     int *order;                 // [U][max_tokens] tokens sorted by (cluster, position)
-    int *chunk_hist;            // [U][n_chunks_max][Cpad]
     int *cluster_start;         // [U][Cpad+1] exclusive scan of counts
     int *page_base;             // [U][Cpad+1] exclusive scan of pages per cluster
+    int *range_tot;             // [U][R][Cpad] members per cluster in each of the sort's R token ranges (R = max(1, 256 / U) at most)
     // decode scratch
     uint32_t *scores;           // [U][max_pages] fp32 bits of the page scores; 0xFFFFFFFF = empty slot
     int *counter;               // [U] arrival counters of the decode-step kernel (zero between launches)

@@ -95,6 +95,8 @@ def test_debug_assign_exact_ties_take_lowest_id():
     dict(n_tokens=2500, n_clusters=24, n_kv_heads=2, page_size=32, n_components=12),
     dict(n_tokens=2600, n_clusters=40, n_kv_heads=1, page_size=64, group_size=8, n_components=12),
     dict(n_tokens=6000, n_clusters=600, n_kv_heads=2, n_components=200),               # two centroid slices
+    dict(n_tokens=9000, n_clusters=2500, n_kv_heads=1, n_components=300),              # sort with 12 segments
+    dict(n_tokens=70000, n_clusters=64, n_kv_heads=1, n_components=64),                # sort segments of 69 groups
 ])
 def test_build_stepwise_parity(kw):
     """Per-step protocol: each stage is compared with the oracle on the GPU's own previous stage."""
