@@ -633,12 +633,12 @@ __global__ __launch_bounds__(1024) void sort_unit_kernel(Dev d, int n, int range
             tot = own;
             if (R > 1) {
                 tot = 0;
-                for (int q0 = 0; q0 < R; q0 += 16) {  // 16 counts in flight per round trip
-                    int t[16];
+                for (int q0 = 0; q0 < R; q0 += 32) {  // 32 counts in flight per round trip
+                    int t[32];
 #pragma unroll
-                    for (int j = 0; j < 16; ++j) t[j] = q0 + j < R ? rtot[(size_t)(q0 + j) * Cpad + c] : 0;
+                    for (int j = 0; j < 32; ++j) t[j] = q0 + j < R ? rtot[(size_t)(q0 + j) * Cpad + c] : 0;
 #pragma unroll
-                    for (int j = 0; j < 16; ++j) {
+                    for (int j = 0; j < 32; ++j) {
                         if (q0 + j < r) before += t[j];
                         tot += t[j];
                     }
