@@ -97,6 +97,7 @@ def test_debug_assign_exact_ties_take_lowest_id():
     dict(n_tokens=6000, n_clusters=600, n_kv_heads=2, n_components=200),               # two centroid slices
     dict(n_tokens=9000, n_clusters=2500, n_kv_heads=1, n_components=300),              # sort with 12 segments
     dict(n_tokens=70000, n_clusters=64, n_kv_heads=1, n_components=64),                # sort segments of 69 groups
+    dict(n_tokens=9000, n_clusters=8192, n_kv_heads=1, n_components=300),             # the largest cluster count: 16 centroid slices, one sort segment
 ])
 def test_build_stepwise_parity(kw):
     """Per-step protocol: each stage is compared with the oracle on the GPU's own previous stage."""
