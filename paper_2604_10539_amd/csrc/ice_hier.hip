@@ -30,28 +30,32 @@ namespace {
 constexpr int kListCap = 512;  // entries of the short list that is ranked by all-pairs counting
 
 struct SelShared {
-    int M, W, M2;
+    int M, W, M2, A;
     uint32_t pre;
     u64 tau;
     uint32_t rowmax[64];
 };
 
 // Exact top-k of n distinct 64-bit composites (ordered score << 32 | ~id) held in LDS, into
-// sel[0..k) (in no particular order when the radix path runs, by rank otherwise); requires
+// sel[0..k) (in no particular order); requires
 // 1 <= k < n.  First a 32-bit threshold that at least k keys reach, and few more:
 //   k <= 2*NW  the k-th largest of the 4*NW sixteen-lane row maxima, element j belonging to row
 //              j mod 4*NW (so short arrays still spread over every row);
 //   else       the 16-bit key prefix of the k-th largest key, from two 8-bit LDS histograms.
-// What passes goes to a short list that is ranked by counting.  If the list overflows, an
-// 8-bit-per-pass radix select over LDS histograms runs on the whole array instead.  `nb` = bits of
+// What passes goes to a short list that is ranked by counting; with the prefix threshold only the
+// keys that share the prefix are listed (those above it are winners as they are, and the
+// histograms say how many of the listed ones are still needed), so the list stays a handful of
+// entries however large k is.  If the list overflows, an 8-bit-per-pass radix select over LDS
+// histograms runs on the whole array instead.  `nb` = bits of
 // the id field that can be set.  hist: 2 x 272 ints.  Every thread of the workgroup must call it;
 // it ends with a barrier.
 template <int NW>
 __device__ void select_topk_lds(const u64 *comp, int n, int k, int nb, u64 *sel, u64 *list, int *hist, SelShared &sh) {
     constexpr int NT = NW * 64, NR = 4 * NW;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    if (tid == 0) { sh.M = 0; sh.W = 0; sh.pre = 0u; sh.tau = 0ull; }
-    if (k <= NR / 2) {
+    if (tid == 0) { sh.M = 0; sh.W = 0; sh.A = 0; sh.pre = 0u; sh.tau = 0ull; }
+    const bool by_prefix = k > NR / 2;
+    if (!by_prefix) {
         const int row = tid >> 4, l16 = tid & 15;
         uint32_t lmax = 0u;
         for (int j = row + NR * l16; j < n; j += NR * 16) lmax = max(lmax, (uint32_t)(comp[j] >> 32));
@@ -109,17 +113,26 @@ __device__ void select_topk_lds(const u64 *comp, int n, int k, int nb, u64 *sel,
     }
     __syncthreads();
     const uint32_t pre = sh.pre;
-    // short list of everything at or above the threshold (>= k entries)
+    // With the prefix threshold: keys above the prefix are winners (k - need of them, need = what
+    // the histograms left for the prefix's own bucket) and go straight to sel; the bucket is listed.
+    // With the row-maxima threshold: everything at or above it is listed (>= k entries).
+    const int need = by_prefix ? sh.M2 : k, first = k - need;
     for (int j0 = 0; j0 < n; j0 += NT) {
         const int j = j0 + tid;
         const u64 cc = j < n ? comp[j] : 0ull;
-        const bool is = j < n && (uint32_t)(cc >> 32) >= pre;
-        const u64 bal = __ballot(is);
-        int base = 0;
+        const uint32_t key = (uint32_t)(cc >> 32);
+        const bool above = j < n && by_prefix && (key >> 16) > (pre >> 16);
+        const bool is = j < n && key >= pre && !above;
+        const u64 bal = __ballot(is), bal_a = __ballot(above);
+        int base = 0, base_a = 0;
         if (lane == 0 && bal) base = atomicAdd(&sh.M, (int)__popcll(bal));
+        if (lane == 0 && bal_a) base_a = atomicAdd(&sh.A, (int)__popcll(bal_a));
         base = __shfl(base, 0);
-        const int slot = base + (int)__popcll(bal & ((1ull << lane) - 1ull));
+        base_a = __shfl(base_a, 0);
+        const u64 lower = (1ull << lane) - 1ull;
+        const int slot = base + (int)__popcll(bal & lower);
         if (is && slot < kListCap) list[slot] = cc;
+        if (above) sel[base_a + (int)__popcll(bal_a & lower)] = cc;  // (exactly `first` of them)
     }
     __syncthreads();
     const int M = sh.M;
@@ -141,7 +154,7 @@ __device__ void select_topk_lds(const u64 *comp, int n, int k, int nb, u64 *sel,
             if (parts >= 16) rank += (int)dpp_u32<0x140>((uint32_t)rank);
             if (parts >= 32) rank += __shfl_xor(rank, 16);
             if (parts >= 64) rank += __shfl_xor(rank, 32);
-            if (part2 == 0 && ii < M && rank < k) sel[rank] = mine;
+            if (part2 == 0 && ii < M && rank < need) sel[first + rank] = mine;
         }
     }
     if (!listed) {  // (workgroup-uniform)
