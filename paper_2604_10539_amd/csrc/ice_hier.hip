@@ -99,7 +99,18 @@ __device__ void select_topk_lds(const u64 *comp, int n, int k, int nb, u64 *sel,
             }
             __syncthreads();
         };
-        for (int j = tid; j < n; j += NT) atomicAdd(&h0[(int)(comp[j] >> 56)], 1);
+        // (the top byte is sign and exponent: most keys of a wave share it, so the lanes that agree
+        // with the first active lane are counted with one update)
+        for (int j0 = 0; j0 < n; j0 += NT) {
+            const int j = j0 + tid;
+            const int bin = j < n ? (int)(comp[j] >> 56) : -1;
+            const u64 act = __ballot(bin >= 0);
+            if (act == 0ull) continue;  // (wave-uniform)
+            const int first_bin = __shfl(bin, (int)__builtin_ctzll(act));
+            const u64 same = __ballot(bin == first_bin);
+            if (lane == (int)__builtin_ctzll(act)) atomicAdd(&h0[first_bin], (int)__popcll(same));
+            if (bin >= 0 && bin != first_bin) atomicAdd(&h0[bin], 1);
+        }
         __syncthreads();
         find_bucket(h0, k, 24);
         const uint32_t top = sh.pre >> 24;
