@@ -30,11 +30,17 @@ __global__ __launch_bounds__(256) void key_norms_kernel(Dev d, const bf16_t *__r
     // 256 keys per workgroup (16 at a time, 16 lanes each); one atomic maximum per wave
     const int u = blockIdx.y, row = threadIdx.x >> 4, ch = threadIdx.x & 15;
     float mx = 0.f;
-#pragma unroll 4
+    uint4 w[16];  // the workgroup's 64 KB of key rows are requested at once (read once: streaming loads)
+#pragma unroll
     for (int it = 0; it < 16; ++it) {
         const int i = blockIdx.x * 256 + it * 16 + row;
+        w[it] = i < n ? load16_stream((const uint4 *)(K + ((size_t)u * n + i) * kD) + ch) : make_uint4(0, 0, 0, 0);
+    }
+#pragma unroll
+    for (int it = 0; it < 16; ++it) {
+        const int i = blockIdx.x * 256 + it * 16 + row;
+        const float n2 = key_sqnorm16(w[it]);  // (uniform over the 16 lanes of a key: no divergent reduction)
         if (i < n) {
-            const float n2 = key_sqnorm16(((const uint4 *)(K + ((size_t)u * n + i) * kD))[ch]);
             if (ch == 0) n2_out[(size_t)u * d.max_tokens + i] = n2;
             mx = fmaxf(mx, n2);
         }
