@@ -419,12 +419,7 @@ __global__ __launch_bounds__(NW * 64) void decode_step_kernel(int U, int max_pag
             if (sco) sco[x] = __uint_as_float(v);
         }
     } else {
-        // (budgets above the row count: every wave finds the 16-bit prefix of the k-th largest key it
-        // holds by a bitwise radix descent on wave ballots, the candidate sets in scalar registers;
-        // keys below the largest such prefix cannot be among the k largest of the unit)
         uint32_t key[EMAX];
-        u64 cm[EMAX];
-        int nvalid = 0;
         if (single) {
 #pragma unroll
             for (int e = 0; e < EMAX; ++e) key[e] = sc_lds[min(e * NT + tid, np - 1)];
@@ -443,13 +438,12 @@ __global__ __launch_bounds__(NW * 64) void decode_step_kernel(int U, int max_pag
         for (int e = 0; e < EMAX; ++e) {
             const bool valid = e * NT + tid < np;
             key[e] = valid ? f32_ordered(__uint_as_float(key[e])) : 0u;
-            cm[e] = __ballot(valid);
-            nvalid += (int)__popcll(cm[e]);
         }
         ICE_STAMP(2);
         constexpr int NR = 4 * NW;  // 16-lane rows in the workgroup
-        if (k <= NR) {
-            // B1: the k-th largest of the 4*NW group maxima (groups without keys count as the
+        const bool by_prefix = k > NR / 2;
+        if (!by_prefix) {
+            // B1, small budgets: the k-th largest of the 4*NW group maxima (groups without keys count as the
             // smallest key).  With several workgroups per unit the groups are the 16-lane rows of
             // the key registers; with one they were formed while scoring.
             if (!single) {
@@ -472,60 +466,112 @@ __global__ __launch_bounds__(NW * 64) void decode_step_kernel(int U, int max_pag
             }
             c = row16_sum_u32(c);
             if (part == 0 && (int)c == k - 1) sh_pre = v;
-        } else if (nvalid >= k) {  // (wave-uniform) otherwise every key of this wave stays a candidate
-            int kk = k;
-            uint32_t pre = 0;
-            for (int bit = 31; bit >= 16; --bit) {
-                u64 bm[EMAX];
-                int cnt = 0;
-#pragma unroll
-                for (int e = 0; e < EMAX; ++e) {
-                    bm[e] = __ballot((key[e] >> bit) & 1u) & cm[e];
-                    cnt += (int)__popcll(bm[e]);
+        } else {
+            // B1, large budgets (the row maxima would let through a multiple of k): the 16-bit prefix
+            // of the k-th largest key, from two 8-bit LDS histograms (top byte, then the second byte
+            // inside the top byte's bucket), and how many keys of that prefix are still needed.
+            int *h0 = (int *)region, *h1 = h0 + 272;  // (the candidate list starts here afterwards)
+            if (tid < 256) { h0[tid] = 0; h1[tid] = 0; }
+            lds_barrier();
+            auto find_bucket = [&](int *h, int kk, int shift) {  // bins in descending order: thread t owns bin 255 - t
+                int mine = 0, incl = 0;
+                if (tid < 256) {
+                    mine = h[255 - tid];
+                    incl = mine;
+                    for (int off = 1; off < 64; off <<= 1) {
+                        const int t2 = __shfl_up(incl, off);
+                        if (lane >= off) incl += t2;
+                    }
+                    if (lane == 63) h[256 + wave] = incl;
                 }
-                if (cnt >= kk) {
-                    pre |= 1u << bit;
+                lds_barrier();
+                if (tid < 256) {
+                    for (int w2 = 0; w2 < wave; ++w2) incl += h[256 + w2];
+                    const int excl = incl - mine;
+                    if (incl >= kk && excl < kk) {  // exactly one bin
+                        atomicOr(&sh_pre, (uint32_t)(255 - tid) << shift);
+                        sh_M2 = kk - excl;
+                    }
+                }
+                lds_barrier();
+            };
+            // (the top byte is sign and exponent: most keys of a wave share it, so the lanes that agree
+            // with the first active lane are counted with one update)
 #pragma unroll
-                    for (int e = 0; e < EMAX; ++e) cm[e] = bm[e];
-                } else {
-                    kk -= cnt;
-#pragma unroll
-                    for (int e = 0; e < EMAX; ++e) cm[e] ^= bm[e];
+            for (int e = 0; e < EMAX; ++e) {
+                const int bin = e * NT + tid < np ? (int)(key[e] >> 24) : -1;
+                const u64 act = __ballot(bin >= 0);
+                if (act != 0ull) {  // (wave-uniform)
+                    const int lead = (int)__builtin_ctzll(act);
+                    const int first_bin = __shfl(bin, lead);
+                    const u64 same = __ballot(bin == first_bin);
+                    if (lane == lead) atomicAdd(&h0[first_bin], (int)__popcll(same));
+                    if (bin >= 0 && bin != first_bin) atomicAdd(&h0[bin], 1);
                 }
             }
-            if (lane == 0) atomicMax(&sh_pre, pre);
+            lds_barrier();
+            find_bucket(h0, k, 24);
+            const uint32_t top = sh_pre >> 24;
+            const int k2 = sh_M2;
+#pragma unroll
+            for (int e = 0; e < EMAX; ++e)
+                if (e * NT + tid < np && (key[e] >> 24) == top) atomicAdd(&h1[(int)((key[e] >> 16) & 255u)], 1);
+            lds_barrier();
+            find_bucket(h1, k2, 16);
         }
         lds_barrier();
         const uint32_t pre = sh_pre;
         ICE_STAMP(3);
         // B2: candidates = (score key, ~page id) composites at or above the threshold; all distinct.
-        // One LDS counter bump per wave reserves the slots of all its candidates.
+        // One LDS counter bump per wave reserves the slots of all its candidates.  With the prefix
+        // threshold only the keys that share the prefix are candidates: the keys above it are winners
+        // as they are (k - need of them) and take the first places of the winner list, wave after
+        // wave in a fixed order.
+        const int need = by_prefix ? sh_M2 : k, first = k - need;
         {
-            u64 bal[EMAX];
-            int tot = 0;
+            u64 bal[EMAX], bal_a[EMAX];
+            int tot = 0, tot_a = 0;
 #pragma unroll
             for (int e = 0; e < EMAX; ++e) {
-                bal[e] = __ballot(e * NT + tid < np && key[e] >= pre);
+                const bool valid = e * NT + tid < np;
+                const bool above = valid && by_prefix && (key[e] >> 16) > (pre >> 16);
+                bal[e] = __ballot(valid && key[e] >= pre && !above);
+                bal_a[e] = __ballot(above);
                 tot += (int)__popcll(bal[e]);
+                tot_a += (int)__popcll(bal_a[e]);
             }
             int base = 0;
             if (lane == 0 && tot) base = atomicAdd(&sh_M, tot);
             base = __shfl(base, 0);
+            const u64 lower = (1ull << lane) - 1ull;
 #pragma unroll
             for (int e = 0; e < EMAX; ++e) {
                 const int pid = e * NT + tid;
                 if ((bal[e] >> lane) & 1ull)
-                    cand[base + (int)__popcll(bal[e] & ((1ull << lane) - 1ull))] = ((u64)key[e] << 32) | (u64)(0xFFFFFFFFu - (uint32_t)pid);
+                    cand[base + (int)__popcll(bal[e] & lower)] = ((u64)key[e] << 32) | (u64)(0xFFFFFFFFu - (uint32_t)pid);
                 base += (int)__popcll(bal[e]);
+            }
+            if (by_prefix) {  // (workgroup-uniform)
+                if (lane == 0) sh_rowmax[wave] = (uint32_t)tot_a;  // (the row maxima are not needed on this path)
+                lds_barrier();
+                int base_a = 0;
+                for (int w2 = 0; w2 < wave; ++w2) base_a += (int)sh_rowmax[w2];
+#pragma unroll
+                for (int e = 0; e < EMAX; ++e) {
+                    const int pid = e * NT + tid;
+                    if ((bal_a[e] >> lane) & 1ull)
+                        sel_comp[base_a + (int)__popcll(bal_a[e] & lower)] = ((u64)key[e] << 32) | (u64)(0xFFFFFFFFu - (uint32_t)pid);
+                    base_a += (int)__popcll(bal_a[e]);
+                }
             }
         }
         lds_barrier();
-        const int M = sh_M;  // >= k
+        const int M = sh_M;  // >= need
         ICE_STAMP(4);
 #ifdef ICE_PROF
         if (tid == 0 && u == 0 && M < 0) ice_prof[15] = M;
 #endif
-        // B3: the k winners among the M candidates, exactly, into sel_comp[0..k)
+        // B3: the `need` best of the M candidates, exactly, into sel_comp[first..k)
         if (M <= 256) {
             // every candidate counts the candidates that beat it; `parts` lanes share one candidate
             int lp = 0;
@@ -542,7 +588,7 @@ __global__ __launch_bounds__(NW * 64) void decode_step_kernel(int U, int max_pag
             if (parts >= 16) rank += (int)dpp_u32<0x140>((uint32_t)rank);
             if (parts >= 32) rank += __shfl_xor(rank, 16);
             if (parts >= 64) rank += __shfl_xor(rank, 32);
-            if (part == 0 && i < M && rank < k) sel_comp[rank] = mine;
+            if (part == 0 && i < M && rank < need) sel_comp[first + rank] = mine;
         } else {
             // radix select on LDS histograms, 8 bits a pass, over the (32 + nb)-bit packed composite
             int nb = 0;
@@ -550,7 +596,7 @@ __global__ __launch_bounds__(NW * 64) void decode_step_kernel(int U, int max_pag
             const u64 idmask = (1ull << nb) - 1ull;
             int *hist = (int *)(cand + M);          // 256 bins + 4 wave totals, behind the candidates
             u64 prefix = 0ull, known = 0ull;
-            int kk = k;
+            int kk = need;
             for (int sft = ((32 + nb - 1) / 8) * 8; sft >= 0; sft -= 8) {
                 if (tid < 256) hist[tid] = 0;
                 lds_barrier();
@@ -589,7 +635,7 @@ __global__ __launch_bounds__(NW * 64) void decode_step_kernel(int U, int max_pag
             for (int t = tid; t < M; t += NT) {
                 const u64 cc = cand[t];
                 const u64 pk = ((cc >> 32) << nb) | (cc & idmask);
-                if (pk >= prefix) sel_comp[atomicAdd(&sh_W, 1)] = cc;
+                if (pk >= prefix) sel_comp[first + atomicAdd(&sh_W, 1)] = cc;
             }
         }
     }
