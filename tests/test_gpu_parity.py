@@ -220,6 +220,9 @@ def _compare_select(o, q, budget, ids, n_sel, scores=None):
     (dict(n_tokens=2600, n_clusters=40, n_kv_heads=1, page_size=64, group_size=8), 640),
     (dict(n_tokens=300, n_clusters=6, n_kv_heads=2), 16 * 64),           # budget covers every page
     (dict(n_tokens=20000, n_clusters=300, n_kv_heads=2, n_components=128), 16),   # one page of many
+    (dict(n_tokens=20000, n_clusters=300, n_kv_heads=2, n_components=128), 16 * 48),    # threshold from histograms
+    (dict(n_tokens=30000, n_clusters=500, n_kv_heads=9, n_components=200), 16 * 250),   # 250 of ~2300 pages, several workgroups per unit
+    (dict(n_tokens=4096, n_clusters=32, n_kv_heads=2, n_components=32), 16 * 280),      # all but a few pages
 ])
 def test_select_and_attend_on_gpu_built_index(kw, budget):
     w = datagen.small(**kw)
