@@ -91,6 +91,7 @@ size_t lay_out(const ice_config_t &cfg, int s, int C, char *base, Dev *out) {
     d.cluster_start = (int *)take(U * (CP + 1) * 4);
     d.page_base = (int *)take(U * (CP + 1) * 4);
     d.range_tot = (int *)take(std::max<size_t>(U, 256) * CP * 4);
+    d.attn_part = (float *)take((size_t)256 * d.G * (kD + 2) * 4);
     d.scores = (uint32_t *)take(U * MP * 4);
     d.counter = (int *)take(U * 4);
     if (out) *out = d;

@@ -1,5 +1,7 @@
 // Decode-step kernels: insertion of a new token, scoring of the page representatives, top-P page
 // selection and sparse paged attention (Sec. 4.2-4.4, Alg. 1 and 3, Eq. 1 of the paper).
+#include <algorithm>
+#include <type_traits>
 #include "ice_internal.h"
 
 #ifdef ICE_PROF
@@ -157,6 +159,49 @@ __global__ __launch_bounds__(NW * 64) void attend_kernel(const bf16_t *__restric
     attend_pages<G, NW, RES>(d, u, qa, [=](int x) { return list[x]; }, ns, res, out, (float *)smem, [] {});
 }
 
+// Few units and many pages per unit: one workgroup per unit would pull every tile through a single
+// CU.  The page list of a unit is cut into S shares instead, one workgroup each (grid S x U); every
+// workgroup leaves its partial result (attend_pages, PARTIAL) and a second, small launch merges the
+// shares of a unit: out = sum_s O_s e^(M_s - M) / sum_s L_s e^(M_s - M).
+template <int G, int NW>
+__global__ __launch_bounds__(NW * 64) void attend_split_kernel(const bf16_t *__restrict__ q, const int *__restrict__ ids,
+                                                                const int *__restrict__ n_sel, int P, Dev d,
+                                                                float *__restrict__ part) {
+    extern __shared__ __align__(16) char smem[];
+    const int s = blockIdx.x, S = gridDim.x, u = blockIdx.y;
+    bf16x8 qa[4];
+    load_query_operand<G>(q, u, threadIdx.x & 63, qa, nullptr);
+    const int ns = min(n_sel[u], P), per = (ns + S - 1) / S;
+    const int lo = min(ns, s * per), cnt = min(ns - lo, per);
+    const int *list = ids + (size_t)u * P + lo;
+    attend_pages<G, NW, false, true>(d, u, qa, [=](int x) { return list[x]; }, cnt, Resident{nullptr, nullptr, 0, nullptr, nullptr, 0},
+                                     part + ((size_t)u * S + s) * G * (kD + 2), (float *)smem, [] {});
+}
+__global__ __launch_bounds__(1024) void attend_merge_kernel(const float *__restrict__ part, int S, int G, float *__restrict__ out) {
+    const int u = blockIdx.x, h = threadIdx.x >> 7, j = threadIdx.x & 127;  // G * 128 threads
+    const float *pu = part + ((size_t)u * S * G + h) * (kD + 2);
+    const size_t stride = (size_t)G * (kD + 2);
+    float M = -INFINITY;
+    for (int s = 0; s < S; ++s) M = fmaxf(M, pu[s * stride + kD]);
+    float num = 0.f, den = 0.f;
+    for (int s = 0; s < S; ++s) {
+        const float ms = pu[s * stride + kD];
+        const float w = ms == -INFINITY ? 0.f : __expf(ms - M);  // (a share without tokens: no weight)
+        num += pu[s * stride + j] * w;
+        den += pu[s * stride + kD + 1] * w;
+    }
+    out[((size_t)u * G + h) * kD + j] = den > 0.f ? num / den : 0.f;
+}
+// shares per unit of the split attention: as many workgroups as the chip has CUs, at least one page
+// per wave; below `min_shares` the merge launch costs more than the shares save (measured: 4 when
+// the attention is a call of its own, 8 when it follows the selection of the same call, which
+// otherwise attends in its own launch)
+int attend_shares(const Dev &d, int P, int min_shares) {
+    const int NW = d.G == 8 ? 8 : 16;
+    const int S = std::min(256 / std::max(d.U, 1), (P + NW - 1) / NW);
+    return S >= min_shares ? S : 1;
+}
+
 // the token positions of the listed pages, in list and slot order, padded with -1
 __global__ void selected_tokens_kernel(Dev d, const int *__restrict__ ids, const int *__restrict__ n_sel, int P,
                                        int *__restrict__ pos_out, int *__restrict__ n_tok_out) {
@@ -192,9 +237,24 @@ void launch_selected_tokens(const Dev &d, const int *ids, const int *n_sel, int 
 }
 
 void launch_attend(const Dev &d, const bf16_t *q, const int *ids, const int *n_sel, int P, const Resident &res_in,
-                   float *out, hipStream_t st) {
+                   float *out, hipStream_t st, int min_shares) {
     const Resident res = res_in;
     const int n_res = res.n;
+    const int S = ids && n_res == 0 && !res.pos ? attend_shares(d, P, min_shares) : 1;
+    if (S > 1) {
+#define ICE_ATTEND_SPLIT(g, nw)                                                                                            \
+    hipLaunchKernelGGL((attend_split_kernel<g, nw>), dim3(S, d.U), dim3(nw * 64), sizeof(float) * attend_scratch_floats(g, nw), \
+                       st, q, ids, n_sel, P, d, d.attn_part)
+        switch (d.G) {
+            case 1: ICE_ATTEND_SPLIT(1, 16); break;
+            case 2: ICE_ATTEND_SPLIT(2, 16); break;
+            case 4: ICE_ATTEND_SPLIT(4, 16); break;
+            default: ICE_ATTEND_SPLIT(8, 8); break;
+        }
+#undef ICE_ATTEND_SPLIT
+        hipLaunchKernelGGL(attend_merge_kernel, dim3(d.U), dim3(d.G * 128), 0, st, d.attn_part, S, d.G, out);
+        return;
+    }
 #define ICE_ATTEND(g, nw)                                                                                                  \
     do {                                                                                                                   \
         if (n_res > 0)                                                                                                     \
@@ -441,7 +501,9 @@ __global__ __launch_bounds__(NW * 64) void decode_step_kernel(int U, int max_pag
         }
         ICE_STAMP(2);
         constexpr int NR = 4 * NW;  // 16-lane rows in the workgroup
-        const bool by_prefix = k > NR / 2;
+        // (with up to 4 keys per thread the histograms are cheaper than ranking the longer list the row
+        // maxima leave from k = NR / 2 on; with 16 keys per thread only above NR)
+        const bool by_prefix = k > (EMAX <= 4 ? NR / 2 : NR);
         if (!by_prefix) {
             // B1, small budgets: the k-th largest of the 4*NW group maxima (groups without keys count as the
             // smallest key).  With several workgroups per unit the groups are the 16-lane rows of
@@ -528,17 +590,22 @@ __global__ __launch_bounds__(NW * 64) void decode_step_kernel(int U, int max_pag
         // as they are (k - need of them) and take the first places of the winner list, wave after
         // wave in a fixed order.
         const int need = by_prefix ? sh_M2 : k, first = k - need;
-        {
-            u64 bal[EMAX], bal_a[EMAX];
+        auto list_candidates = [&](auto with_prefix) {
+            constexpr bool PREFIX = decltype(with_prefix)::value;
+            u64 bal[EMAX], bal_a[PREFIX ? EMAX : 1];
             int tot = 0, tot_a = 0;
 #pragma unroll
             for (int e = 0; e < EMAX; ++e) {
                 const bool valid = e * NT + tid < np;
-                const bool above = valid && by_prefix && (key[e] >> 16) > (pre >> 16);
-                bal[e] = __ballot(valid && key[e] >= pre && !above);
-                bal_a[e] = __ballot(above);
+                if constexpr (PREFIX) {
+                    const bool above = valid && (key[e] >> 16) > (pre >> 16);
+                    bal[e] = __ballot(valid && (key[e] >> 16) == (pre >> 16));
+                    bal_a[e] = __ballot(above);
+                    tot_a += (int)__popcll(bal_a[e]);
+                } else {
+                    bal[e] = __ballot(valid && key[e] >= pre);
+                }
                 tot += (int)__popcll(bal[e]);
-                tot_a += (int)__popcll(bal_a[e]);
             }
             int base = 0;
             if (lane == 0 && tot) base = atomicAdd(&sh_M, tot);
@@ -551,7 +618,7 @@ __global__ __launch_bounds__(NW * 64) void decode_step_kernel(int U, int max_pag
                     cand[base + (int)__popcll(bal[e] & lower)] = ((u64)key[e] << 32) | (u64)(0xFFFFFFFFu - (uint32_t)pid);
                 base += (int)__popcll(bal[e]);
             }
-            if (by_prefix) {  // (workgroup-uniform)
+            if constexpr (PREFIX) {
                 if (lane == 0) sh_rowmax[wave] = (uint32_t)tot_a;  // (the row maxima are not needed on this path)
                 lds_barrier();
                 int base_a = 0;
@@ -564,7 +631,9 @@ __global__ __launch_bounds__(NW * 64) void decode_step_kernel(int U, int max_pag
                     base_a += (int)__popcll(bal_a[e]);
                 }
             }
-        }
+        };
+        if (by_prefix) list_candidates(std::true_type{});  // (workgroup-uniform)
+        else list_candidates(std::false_type{});
         lds_barrier();
         const int M = sh_M;  // >= need
         ICE_STAMP(4);
@@ -701,15 +770,19 @@ void launch_decode_step(const Dev &d, const bf16_t *q, int P, int np_hint, int *
     const int max_chunks = (np_hint + 16 * NW - 1) / (16 * NW);
     if (chunks > max_chunks) chunks = max_chunks;
     if (chunks < 1) chunks = 1;
+    // few units and a large budget: select in this launch, attend with the unit's pages spread over
+    // several workgroups (two more launches, see attend_split_kernel)
+    const bool split_attend = out && chunks > 1 && n_res == 0 && attend_shares(d, P, 8) > 1;
+    float *out_fused = split_attend ? nullptr : out;
     const size_t lds = decode_step_lds_bytes(d, P);
     const int grid = round_up(d.U, 8) * chunks;
     const int E = (d.max_pages + NW * 64 - 1) / (NW * 64);
-    const Resident res = {res_k, res_v, out ? n_res : 0, nullptr, nullptr, 0};
+    const Resident res = {res_k, res_v, out_fused ? n_res : 0, nullptr, nullptr, 0};
 #define ICE_STEP_R(g, nw, e, r)                                                                                     \
     do {                                                                                                            \
         (void)hipFuncSetAttribute((const void *)decode_step_kernel<g, nw, e, r>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds); \
         hipLaunchKernelGGL((decode_step_kernel<g, nw, e, r>), dim3(grid), dim3(nw * 64), lds, st, d.U, d.max_pages, P, chunks, np_hint, \
-                           (int)(lds - (size_t)d.max_pages * 4), d.rep, q, d.n_pages, d, ids, n_sel, scores_out, res, out); \
+                           (int)(lds - (size_t)d.max_pages * 4), d.rep, q, d.n_pages, d, ids, n_sel, scores_out, res, out_fused); \
     } while (0)
 #define ICE_STEP(g, nw, e)                                                                                          \
     do {                                                                                                            \
@@ -722,6 +795,7 @@ void launch_decode_step(const Dev &d, const bf16_t *q, int P, int np_hint, int *
     else { if (E <= 4) ICE_STEP(1, 16, 4); else ICE_STEP(1, 16, 16); }
 #undef ICE_STEP
 #undef ICE_STEP_R
+    if (split_attend) launch_attend(d, q, ids, n_sel, P, Resident{nullptr, nullptr, 0, nullptr, nullptr, 0}, out, st, 8);
 }
 
 // largest page count and page budget launch_decode_step can serve (register-resident keys, LDS lists)

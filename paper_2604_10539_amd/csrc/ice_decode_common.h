@@ -140,7 +140,11 @@ struct SplitRow {
     }
 };
 
-template <int G, int NW, bool RES, typename PageOf, typename Aside>
+// With PARTIAL the workgroup attends to a share of a unit's pages and leaves, instead of the output,
+// what a later merge needs: per head h the unnormalised sum at out[h * (kD + 2) + j], the running
+// maximum at [.. + kD] and the denominator at [.. + kD + 1] (`out` then points at the workgroup's own
+// block and `u` only addresses the pages).
+template <int G, int NW, bool RES, bool PARTIAL = false, typename PageOf, typename Aside>
 __device__ inline void attend_pages(const Dev &d, int u, const bf16x8 (&qa)[4], PageOf page_of, int ns, Resident res,
                                     float *__restrict__ out, float *red, Aside aside) {
     constexpr int GR = (G + 3) / 4;  // row groups that hold logits and outputs
@@ -320,7 +324,15 @@ __device__ inline void attend_pages(const Dev &d, int u, const bf16x8 (&qa)[4], 
         M = fmaxf(M, dpp_f32<0x140>(M));
         const float e = M == -INFINITY ? 0.f : __expf(mw - M);
         const float L = row16_sum(lw * e);
-        if (w < NW) wm[w][h] = L > 0.f ? e / L : 0.f;
+        if constexpr (PARTIAL) {
+            if (w < NW) wm[w][h] = e;
+            if (w == 0) {
+                out[h * (kD + 2) + kD] = M;
+                out[h * (kD + 2) + kD + 1] = L;
+            }
+        } else {
+            if (w < NW) wm[w][h] = L > 0.f ? e / L : 0.f;
+        }
     }
     __syncthreads();
     for (int o = tid; o < G * kD; o += NW * 64) {
@@ -328,7 +340,8 @@ __device__ inline void attend_pages(const Dev &d, int u, const bf16x8 (&qa)[4], 
         float O = 0.f;
 #pragma unroll
         for (int w = 0; w < NW; ++w) O += wacc[w][h][j] * wm[w][h];
-        out[((size_t)u * G + h) * kD + j] = O;
+        if constexpr (PARTIAL) out[h * (kD + 2) + j] = O;
+        else out[((size_t)u * G + h) * kD + j] = O;
     }
 }
 

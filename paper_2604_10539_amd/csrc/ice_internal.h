@@ -41,6 +41,7 @@ struct Dev {
     int *order;                 // [U][max_tokens] tokens sorted by (cluster, position)
     int *cluster_start;         // [U][Cpad+1] exclusive scan of counts
     int *page_base;             // [U][Cpad+1] exclusive scan of pages per cluster
+    float *attn_part;           // [256][G][130] partial results of the split attention (shares x units <= 256)
     int *range_tot;             // [U][R][Cpad] members per cluster in each of the sort's R token ranges (R = max(1, 256 / U) at most)
     // decode scratch
     uint32_t *scores;           // [U][max_pages] fp32 bits of the page scores; 0xFFFFFFFF = empty slot
@@ -100,7 +101,7 @@ struct Resident {
 };
 
 void launch_attend(const Dev &d, const bf16_t *q, const int *ids_or_null, const int *n_sel, int P, const Resident &res,
-                   float *out, hipStream_t st);
+                   float *out, hipStream_t st, int min_shares = 4);
 void launch_selected_tokens(const Dev &d, const int *ids, const int *n_sel, int P, int *pos_out, int *n_tok_out,
                             hipStream_t st);
 
