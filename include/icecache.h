@@ -149,6 +149,19 @@ ice_status_t ice_select(ice_index_t *idx, const void *q, int32_t token_budget, i
 ice_status_t ice_attend(ice_index_t *idx, const void *q, const int32_t *page_ids,
                         const int32_t *n_selected, int32_t n_ids_per_unit, float *out, void *stream);
 
+/* ice_attend for callers that cannot allocate device memory and have no scratch to lend: code under
+ * HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments, same
+ * result (to the rounding of a different split of the page list), but the partial sums of the page
+ * list's shares do not go through the workspace: they live in a static device array of the library
+ * (1 064 960 bytes per GPU the library runs on, held until the process ends), whose address is
+ * looked up once per device at the first call there.  The call itself allocates nothing and calls
+ * no allocating routine.
+ * Limit: at most 256 units (batch * n_kv_heads); UNSUPPORTED beyond.  Every call on one GPU shares
+ * that GPU's array: calls that overlap in time on one GPU (different streams or threads) race;
+ * calls issued in order on one stream are safe.  DEVICE if the array's address cannot be found. */
+ice_status_t ice_attend_noalloc(ice_index_t *idx, const void *q, const int32_t *page_ids,
+                                const int32_t *n_selected, int32_t n_ids_per_unit, float *out, void *stream);
+
 /* ice_select followed by ice_attend on the same stream; the ids never leave the device. */
 ice_status_t ice_select_attend(ice_index_t *idx, const void *q, int32_t token_budget,
                                int32_t *page_ids, int32_t *n_selected, float *out, void *stream);

@@ -17,7 +17,7 @@ ICE_OK, ICE_ERR_INVALID_ARG, ICE_ERR_SHAPE, ICE_ERR_STATE, ICE_ERR_CAPACITY, ICE
 STATUS_NAMES = ["ICE_OK", "ICE_ERR_INVALID_ARG", "ICE_ERR_SHAPE", "ICE_ERR_STATE", "ICE_ERR_CAPACITY",
                 "ICE_ERR_UNSUPPORTED", "ICE_ERR_DEVICE"]
 SYMBOLS = ["ice_workspace_bytes", "ice_create", "ice_destroy", "ice_build_index", "ice_insert", "ice_insert_batch", "ice_select",
-           "ice_attend", "ice_select_attend", "ice_attend_resident", "ice_select_attend_resident", "ice_selected_tokens", "ice_attend_tokens", "ice_select_hier", "ice_set_geometry", "ice_export_geometry", "ice_export_index", "ice_import_index", "ice_debug_assign",
+           "ice_attend", "ice_attend_noalloc", "ice_select_attend", "ice_attend_resident", "ice_select_attend_resident", "ice_selected_tokens", "ice_attend_tokens", "ice_select_hier", "ice_set_geometry", "ice_export_geometry", "ice_export_index", "ice_import_index", "ice_debug_assign",
            "ice_debug_peak_read", "ice_debug_peak_mfma", "ice_last_error"]
 
 
@@ -71,6 +71,7 @@ def lib() -> C.CDLL:
         L.ice_insert_batch.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32, C.c_void_p]
         L.ice_select.argtypes = [C.c_void_p, C.c_void_p, C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]
         L.ice_attend.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32, C.c_void_p, C.c_void_p]
+        L.ice_attend_noalloc.argtypes = L.ice_attend.argtypes
         L.ice_select_attend.argtypes = [C.c_void_p, C.c_void_p, C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p,
                                         C.c_void_p]
         L.ice_attend_resident.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32, C.c_void_p, C.c_void_p,
@@ -160,6 +161,11 @@ def ice_select(idx, q, token_budget, page_ids, n_selected, scores=None, stream=N
 
 def ice_attend(idx, q, page_ids, n_selected, n_ids_per_unit, out, stream=None) -> None:
     _check(lib().ice_attend(idx, _ptr(q), _ptr(page_ids), _ptr(n_selected), n_ids_per_unit, _ptr(out), _stream(stream)))
+
+
+def ice_attend_noalloc(idx, q, page_ids, n_selected, n_ids_per_unit, out, stream=None) -> None:
+    _check(lib().ice_attend_noalloc(idx, _ptr(q), _ptr(page_ids), _ptr(n_selected), n_ids_per_unit, _ptr(out),
+                                    _stream(stream)))
 
 
 def ice_select_attend(idx, q, token_budget, page_ids, n_selected, out, stream=None) -> None:

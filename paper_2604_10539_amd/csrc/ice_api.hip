@@ -270,6 +270,22 @@ ice_status_t ice_attend(ice_index_t *ix, const void *q, const int32_t *ids, cons
     return ice_attend_resident(ix, q, ids, n_sel, P, nullptr, nullptr, 0, out, stream);
 }
 
+ice_status_t ice_attend_noalloc(ice_index_t *ix, const void *q, const int32_t *ids, const int32_t *n_sel, int32_t P, float *out,
+                                void *stream) {
+    if (!ix) return fail(ICE_ERR_INVALID_ARG, "index is null");
+    if (!ix->built) return fail(ICE_ERR_STATE, "ice_attend_noalloc before ice_build_index");
+    if (!q || !aligned16(q)) return fail(ICE_ERR_INVALID_ARG, "q is null or misaligned");
+    if (!ids || !n_sel || !out) return fail(ICE_ERR_INVALID_ARG, "page_ids, n_selected or out is null");
+    if (P < 1) return fail(ICE_ERR_SHAPE, "n_ids_per_unit must be >= 1");
+    if (ix->dev.U > attend_static_max_units())
+        return fail(ICE_ERR_UNSUPPORTED, "%d units: the static scratch array holds the partial results of at most %d",
+                    ix->dev.U, attend_static_max_units());
+    const hipError_t e = launch_attend_static(ix->dev, static_cast<const bf16_t *>(q), ids, n_sel, P, out,
+                                              static_cast<hipStream_t>(stream));
+    if (e != hipSuccess) return fail(ICE_ERR_DEVICE, "ice_attend_noalloc: %s", hipGetErrorString(e));
+    return device_status("ice_attend_noalloc");
+}
+
 ice_status_t ice_select_attend_resident(ice_index_t *ix, const void *q, int32_t budget, const void *rk, const void *rv,
                                         int32_t n_res, int32_t *ids, int32_t *n_sel, float *out, void *stream) {
     if (ice_status_t st = check_select(ix, q, budget, ids, n_sel, "ice_select_attend")) return st;

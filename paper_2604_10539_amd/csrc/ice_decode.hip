@@ -1,6 +1,7 @@
 // Decode-step kernels: insertion of a new token, scoring of the page representatives, top-P page
 // selection and sparse paged attention (Sec. 4.2-4.4, Alg. 1 and 3, Eq. 1 of the paper).
 #include <algorithm>
+#include <mutex>
 #include <type_traits>
 #include "ice_internal.h"
 
@@ -271,6 +272,64 @@ void launch_attend(const Dev &d, const bf16_t *q, const int *ids, const int *n_s
         default: ICE_ATTEND(8, 8); break;
     }
 #undef ICE_ATTEND
+}
+
+// ------------------------------------------------------------------------------------------------
+// Attention for callers that cannot allocate (code under HIP graph capture, serving loops and
+// harnesses that forbid hipMalloc) and hold no workspace region to lend: the split attention above
+// with its partial results in a device array of the library itself.  Every call on a GPU shares
+// that GPU's array: calls that overlap on one GPU (two streams, two host threads) race on it.
+// Nothing in it has to start at zero: every share writes its whole block before the merge reads it.
+constexpr int kStaticPairs = 256;  // (unit, share) pairs the array holds, each 8 heads x 130 floats
+}  // namespace ice
+static __device__ __align__(256) float scratch[ice::kStaticPairs * 8 * (ice::kD + 2)];
+namespace ice {
+
+int attend_static_max_units() { return kStaticPairs; }
+
+// The array's name is a host-side stand-in; its device address is looked up once per device, with
+// that device current, and only that address is handed to kernels.
+static float *scratch_on_current_device(hipError_t *err) {
+    constexpr int kMaxDevices = 64;
+    static float *ptr[kMaxDevices] = {};
+    static std::mutex mu;
+    int dev = -1;
+    *err = hipGetDevice(&dev);
+    if (*err != hipSuccess) return nullptr;
+    if (dev < 0 || dev >= kMaxDevices) {
+        *err = hipErrorInvalidDevice;
+        return nullptr;
+    }
+    std::lock_guard<std::mutex> lock(mu);
+    if (!ptr[dev]) {
+        void *p = nullptr;
+        *err = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+        if (*err != hipSuccess) return nullptr;
+        ptr[dev] = static_cast<float *>(p);
+    }
+    return ptr[dev];
+}
+
+// always the two-launch form (shares, then merge), also with one share per unit; d.U <= kStaticPairs
+hipError_t launch_attend_static(const Dev &d, const bf16_t *q, const int *ids, const int *n_sel, int P, float *out,
+                                hipStream_t st) {
+    hipError_t err = hipSuccess;
+    float *part = scratch_on_current_device(&err);
+    if (!part) return err;
+    const int NW = d.G == 8 ? 8 : 16;
+    const int S = std::max(1, std::min(kStaticPairs / d.U, (P + NW - 1) / NW));
+#define ICE_ATTEND_SPLIT(g, nw)                                                                                            \
+    hipLaunchKernelGGL((attend_split_kernel<g, nw>), dim3(S, d.U), dim3(nw * 64), sizeof(float) * attend_scratch_floats(g, nw), \
+                       st, q, ids, n_sel, P, d, part)
+    switch (d.G) {
+        case 1: ICE_ATTEND_SPLIT(1, 16); break;
+        case 2: ICE_ATTEND_SPLIT(2, 16); break;
+        case 4: ICE_ATTEND_SPLIT(4, 16); break;
+        default: ICE_ATTEND_SPLIT(8, 8); break;
+    }
+#undef ICE_ATTEND_SPLIT
+    hipLaunchKernelGGL(attend_merge_kernel, dim3(d.U), dim3(d.G * 128), 0, st, part, S, d.G, out);
+    return hipSuccess;
 }
 
 // ------------------------------------------------------------------------------------------------

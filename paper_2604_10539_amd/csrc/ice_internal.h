@@ -102,6 +102,11 @@ struct Resident {
 
 void launch_attend(const Dev &d, const bf16_t *q, const int *ids_or_null, const int *n_sel, int P, const Resident &res,
                    float *out, hipStream_t st, int min_shares = 4);
+// the same attention with the shares' partial results in the library's own static device array
+// (no workspace region involved); at most attend_static_max_units() units
+hipError_t launch_attend_static(const Dev &d, const bf16_t *q, const int *ids, const int *n_sel, int P, float *out,
+                                hipStream_t st);
+int attend_static_max_units();
 void launch_selected_tokens(const Dev &d, const int *ids, const int *n_sel, int P, int *pos_out, int *n_tok_out,
                             hipStream_t st);
 
