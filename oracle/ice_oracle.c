@@ -8,7 +8,8 @@
  *   - nearest promoted point / nearest centroid = exhaustive argmin        (Sec. 4.2, Alg. 2)
  *   - centroid = arithmetic mean of the members                            (Lloyd step)
  *   - node -> pages: members in token order, cut every page_size tokens    (Sec. 4.1)       
- *   - insertion of a decode token under its nearest parent                 (Sec. 4.2, Alg. 1)
+ *   - insertion of a decode token under its nearest parent, on the raw
+ *     keys or on the transformed ones                                      (Sec. 4.2, Alg. 1, Eq. 2)
  *   - page selection = full sort of all pages by score, take the first P   (Sec. 4.4, Alg. 3)
  *   - attention = masked softmax over the tokens of the selected pages     (Eq. 1)
  *
@@ -237,68 +238,126 @@ void orc_build(orc_state_t *st, const uint16_t *K, const uint16_t *V, int n, con
  * chosen/best/second report the decision and the two smallest objective values.
  * Returns 0, or -1 if a unit is out of token capacity (nothing is modified then).  Pages cannot
  * run out: max_pages = floor(max_tokens / s) + C covers every full page plus one partial page
- * per cluster. */
+ * per cluster.
+ *
+ * With a geometry (orc_insert_transformed) the distances are those between TRANSFORMED keys
+ * (Sec. 4.2 last paragraph: a decode token is inserted under its nearest parent in the same space
+ * the tree was built in; Eq. 2: T_K(k) = [k / c, sqrt(1 - ||k||^2 / c^2)]).  Kept times c, a key is
+ * the row [k, a(k)] with ONE more coordinate a(k) = sqrt(c^2 - ||k||^2), rounded to bf16 like every
+ * stored coordinate; a key beyond the radius (||k|| > c, which Eq. 2 does not cover: c was fixed at
+ * prefill) gets a = 0.  Centroids carry the mean of their members' a.  Everything is the raw
+ * insertion on (d+1)-dimensional rows: the argmin runs over w_c - 2 [k,a].[mu~_c, e~_c] with
+ * w_c = ||mu~_c||^2 + e~_c^2 (e~ = the extra coordinate of the centroid rounded to bf16), and the
+ * extra coordinate's running sum and mean move in ordered fp32 exactly like the other d.
+ * Page tiles, page sums and representatives hold the d raw coordinates only (the transformed query
+ * has 0 in the extra one, Eq. 3).  extra_override[u] >= 0 replaces the oracle's own a(k) bits (to
+ * follow the other side when its fp32 norm lands on the other side of a bf16 rounding boundary);
+ * extra_out reports the oracle's own. */
+typedef struct {
+    float *radius_sq;          /* [U] c^2, fixed at prefill */
+    uint16_t *key_extra;       /* [U][max_tokens] bf16 a(k) by token position */
+    float *centroid_extra;     /* [U][C] mean of the members' a */
+    float *cluster_sum_extra;  /* [U][C] their running sum */
+} orc_geometry_t;
+
+static void insert_one(orc_state_t *st, orc_geometry_t *geo, int u, const uint16_t *ku, const uint16_t *vu,
+                       const int32_t *force, const int32_t *extra_override, int32_t *chosen, double *best,
+                       double *second, uint16_t *extra_out) {
+    const int d = st->d, s = st->s, C = st->C, MP = st->max_pages;
+    /* the new key's extra coordinate (transformed geometry only) */
+    uint16_t a_bits = 0;
+    double a_val = 0.0;
+    if (geo) {
+        double n2 = 0.0;
+        for (int j = 0; j < d; ++j) {
+            double x = bf16_to_f32(ku[j]);
+            n2 += x * x;
+        }
+        double rest = (double)geo->radius_sq[u] - n2;
+        a_bits = f32_to_bf16((float)sqrt(rest > 0.0 ? rest : 0.0));   /* beyond the radius: 0 */
+        if (extra_out) extra_out[u] = a_bits;
+        if (extra_override && extra_override[u] >= 0) a_bits = (uint16_t)extra_override[u];
+        a_val = bf16_to_f32(a_bits);
+    }
+    /* exhaustive search over the bf16-rounded centroids, as orc_assign does for one key */
+    int32_t arg = 0;
+    double b1 = INFINITY, b2 = INFINITY;
+    for (int c = 0; c < C; ++c) {
+        double w = 0.0, dot = 0.0;
+        for (int j = 0; j < d; ++j) {
+            double m = bf16_to_f32(f32_to_bf16(st->centroid[((size_t)u * C + c) * d + j]));
+            w += m * m;
+            dot += (double)bf16_to_f32(ku[j]) * m;
+        }
+        if (geo) {
+            double e = bf16_to_f32(f32_to_bf16(geo->centroid_extra[(size_t)u * C + c]));
+            w += e * e;
+            dot += a_val * e;
+        }
+        double val = w - 2.0 * dot;
+        if (val < b1) { b2 = b1; b1 = val; arg = c; }
+        else if (val < b2) { b2 = val; }
+    }
+    if (force && force[u] >= 0) arg = force[u];
+    if (chosen) chosen[u] = arg;
+    if (best) best[u] = b1;
+    if (second) second[u] = b2;
+
+    int tail = st->cluster_tail[(size_t)u * C + arg];
+    if (tail < 0 || st->page_fill[(size_t)u * MP + tail] == s) {
+        tail = st->n_pages[u]++;
+        st->cluster_tail[(size_t)u * C + arg] = tail;
+        st->page_cluster[(size_t)u * MP + tail] = arg;
+        st->page_fill[(size_t)u * MP + tail] = 0;
+        for (int j = 0; j < d; ++j) st->page_sum[((size_t)u * MP + tail) * d + j] = 0.0f;
+    }
+    size_t pg = (size_t)u * MP + tail;
+    int slot = st->page_fill[pg]++;
+    memcpy(st->Kp + (pg * s + slot) * d, ku, sizeof(uint16_t) * d);
+    memcpy(st->Vp + (pg * s + slot) * d, vu, sizeof(uint16_t) * d);
+    const int tok = st->n_tokens[u]++;
+    st->page_pos[pg * s + slot] = tok;
+    int fill = slot + 1;
+    size_t cl = (size_t)u * C + arg;
+    int cnt = ++st->cluster_cnt[cl];
+    for (int j = 0; j < d; ++j) {
+        float kf = bf16_to_f32(ku[j]);
+        float ps = st->page_sum[pg * d + j] + kf;             /* ordered fp32 */
+        st->page_sum[pg * d + j] = ps;
+        st->rep[pg * d + j] = f32_to_bf16(ps / (float)fill);
+        float cs = st->cluster_sum[cl * d + j] + kf;          /* ordered fp32 */
+        st->cluster_sum[cl * d + j] = cs;
+        st->centroid[cl * d + j] = cs / (float)cnt;
+    }
+    if (geo) {
+        float es = geo->cluster_sum_extra[cl] + bf16_to_f32(a_bits);   /* ordered fp32 */
+        geo->cluster_sum_extra[cl] = es;
+        geo->centroid_extra[cl] = es / (float)cnt;
+        geo->key_extra[(size_t)u * st->max_tokens + tok] = a_bits;
+    }
+}
+
 int orc_insert(orc_state_t *st, const uint16_t *k, const uint16_t *v, const int32_t *force,
                int32_t *chosen, double *best, double *second) {
-    const int d = st->d, s = st->s, C = st->C, MP = st->max_pages;
+    const int d = st->d;
     for (int u = 0; u < st->U; ++u)
         if (st->n_tokens[u] >= st->max_tokens) return -1;
 #pragma omp parallel for schedule(dynamic, 1)
-    for (int u = 0; u < st->U; ++u) {
-        const uint16_t *ku = k + (size_t)u * d, *vu = v + (size_t)u * d;
-        uint16_t *mub = (uint16_t *)malloc(sizeof(uint16_t) * (size_t)C * d);
-        for (size_t x = 0; x < (size_t)C * d; ++x) mub[x] = f32_to_bf16(st->centroid[(size_t)u * C * d + x]);
-        int32_t arg;
-        double b1, b2;
-        {   /* same exhaustive search as orc_assign, for one key */
-            double *w = (double *)malloc(sizeof(double) * (size_t)C);
-            b1 = INFINITY; b2 = INFINITY; arg = 0;
-            for (int c = 0; c < C; ++c) {
-                double acc = 0.0, dot = 0.0;
-                for (int j = 0; j < d; ++j) {
-                    double m = bf16_to_f32(mub[(size_t)c * d + j]);
-                    acc += m * m;
-                    dot += (double)bf16_to_f32(ku[j]) * m;
-                }
-                w[c] = acc;
-                double val = w[c] - 2.0 * dot;
-                if (val < b1) { b2 = b1; b1 = val; arg = c; }
-                else if (val < b2) { b2 = val; }
-            }
-            free(w);
-        }
-        free(mub);
-        if (force && force[u] >= 0) arg = force[u];
-        if (chosen) chosen[u] = arg;
-        if (best) best[u] = b1;
-        if (second) second[u] = b2;
+    for (int u = 0; u < st->U; ++u)
+        insert_one(st, NULL, u, k + (size_t)u * d, v + (size_t)u * d, force, NULL, chosen, best, second, NULL);
+    return 0;
+}
 
-        int tail = st->cluster_tail[(size_t)u * C + arg];
-        if (tail < 0 || st->page_fill[(size_t)u * MP + tail] == s) {
-            tail = st->n_pages[u]++;
-            st->cluster_tail[(size_t)u * C + arg] = tail;
-            st->page_cluster[(size_t)u * MP + tail] = arg;
-            st->page_fill[(size_t)u * MP + tail] = 0;
-            for (int j = 0; j < d; ++j) st->page_sum[((size_t)u * MP + tail) * d + j] = 0.0f;
-        }
-        size_t pg = (size_t)u * MP + tail;
-        int slot = st->page_fill[pg]++;
-        memcpy(st->Kp + (pg * s + slot) * d, ku, sizeof(uint16_t) * d);
-        memcpy(st->Vp + (pg * s + slot) * d, vu, sizeof(uint16_t) * d);
-        st->page_pos[pg * s + slot] = st->n_tokens[u]++;
-        int fill = slot + 1;
-        size_t cl = (size_t)u * C + arg;
-        int cnt = ++st->cluster_cnt[cl];
-        for (int j = 0; j < d; ++j) {
-            float kf = bf16_to_f32(ku[j]);
-            float ps = st->page_sum[pg * d + j] + kf;             /* ordered fp32 */
-            st->page_sum[pg * d + j] = ps;
-            st->rep[pg * d + j] = f32_to_bf16(ps / (float)fill);
-            float cs = st->cluster_sum[cl * d + j] + kf;          /* ordered fp32 */
-            st->cluster_sum[cl * d + j] = cs;
-            st->centroid[cl * d + j] = cs / (float)cnt;
-        }
-    }
+int orc_insert_transformed(orc_state_t *st, orc_geometry_t *geo, const uint16_t *k, const uint16_t *v,
+                           const int32_t *force, const int32_t *extra_override, int32_t *chosen, double *best,
+                           double *second, uint16_t *extra_out) {
+    const int d = st->d;
+    for (int u = 0; u < st->U; ++u)
+        if (st->n_tokens[u] >= st->max_tokens) return -1;
+#pragma omp parallel for schedule(dynamic, 1)
+    for (int u = 0; u < st->U; ++u)
+        insert_one(st, geo, u, k + (size_t)u * d, v + (size_t)u * d, force, extra_override, chosen, best, second,
+                   extra_out);
     return 0;
 }
 

@@ -1,9 +1,11 @@
 """ctypes wrapper around the C oracle (oracle/ice_oracle.c).
 
 TEST INFRASTRUCTURE ONLY.  Imported by tests/, the smoke check and the benchmark's
-cpu_baseline leg; never by the product package.  It holds no arithmetic of its own:
-it allocates numpy arrays, passes their pointers to the C functions and hands the
-arrays back.  All state arrays carry a leading unit dimension U = batch * n_kv_heads.
+cpu_baseline leg; never by the product package.  It allocates numpy arrays, passes their
+pointers to the C functions and hands the arrays back.  The only arithmetic written here is
+key_extra_coordinate (the extra coordinate of the transformed keys at prefill, Eq. 2, in numpy);
+everything else is in the C file.  All state arrays carry a leading unit dimension
+U = batch * n_kv_heads.
 """
 from __future__ import annotations
 
@@ -26,6 +28,10 @@ def build(force: bool = False) -> str:
     return _LIB
 
 
+class _Geometry(C.Structure):
+    _fields_ = [(n, C.c_void_p) for n in ("radius_sq", "key_extra", "centroid_extra", "cluster_sum_extra")]
+
+
 class _State(C.Structure):
     _fields_ = [(n, C.c_int32) for n in ("U", "d", "s", "C", "G", "max_pages", "max_tokens")] + \
                [(n, C.c_void_p) for n in ("n_tokens", "n_pages", "Kp", "Vp", "page_cluster", "page_fill",
@@ -42,6 +48,7 @@ def lib():
         _lib = C.CDLL(build())
         _lib.orc_num_threads.restype = C.c_int
         _lib.orc_insert.restype = C.c_int
+        _lib.orc_insert_transformed.restype = C.c_int
     return _lib
 
 
@@ -129,6 +136,17 @@ class OracleIndex:
         self.page_sum = np.zeros((U, MP, d), np.float32)
         self.rep = np.zeros((U, MP, d), np.uint16)
         self.assign = None
+        self.geometry = None
+
+    def set_geometry(self, radius_sq, key_extra, centroid_extra, cluster_sum_extra):
+        """Switches insertions to the transformed keys of Eq. 2.  radius_sq float32 [U] (c^2, fixed at
+        prefill); key_extra uint16 [U, max_tokens] (a(k) of every token so far, by position);
+        centroid_extra, cluster_sum_extra float32 [U, C] (mean and sum of the members' a).  Copies."""
+        self.geometry = dict(
+            radius_sq=np.array(radius_sq, np.float32, copy=True).reshape(self.U),
+            key_extra=np.array(key_extra, np.uint16, copy=True).reshape(self.U, self.max_tokens),
+            centroid_extra=np.array(centroid_extra, np.float32, copy=True).reshape(self.U, self.C),
+            cluster_sum_extra=np.array(cluster_sum_extra, np.float32, copy=True).reshape(self.U, self.C))
 
     def _state(self) -> _State:
         st = _State()
@@ -167,8 +185,12 @@ class OracleIndex:
         st = self._state()
         lib().orc_paginate(C.byref(st), _p(K), _p(V), _p(assign), C.c_int(n))
 
-    def insert(self, k: np.ndarray, v: np.ndarray, force: np.ndarray | None = None):
-        """k, v uint16 [..., d].  Returns (chosen int32 [U], best float64 [U], second float64 [U])."""
+    def insert(self, k: np.ndarray, v: np.ndarray, force: np.ndarray | None = None,
+               extra_override: np.ndarray | None = None):
+        """k, v uint16 [..., d].  Returns (chosen int32 [U], best float64 [U], second float64 [U]); after
+        set_geometry the insertion is the one on the transformed keys and a fourth value is returned, the
+        oracle's own extra coordinate of the new keys (uint16 [U]); extra_override int32 [U] (bf16 bits,
+        -1 = none) then replaces it in everything that follows."""
         k = self._units(k, (self.d,), np.uint16)
         v = self._units(v, (self.d,), np.uint16)
         if force is not None:
@@ -177,10 +199,23 @@ class OracleIndex:
         best = np.empty(self.U, np.float64)
         second = np.empty(self.U, np.float64)
         st = self._state()
-        rc = lib().orc_insert(C.byref(st), _p(k), _p(v), _p(force), _p(chosen), _p(best), _p(second))
+        if self.geometry is None:
+            assert extra_override is None
+            rc = lib().orc_insert(C.byref(st), _p(k), _p(v), _p(force), _p(chosen), _p(best), _p(second))
+            if rc != 0:
+                raise OverflowError("oracle insert: token capacity exceeded")
+            return chosen, best, second
+        geo = _Geometry()
+        for name, arr in self.geometry.items():
+            setattr(geo, name, arr.ctypes.data)
+        if extra_override is not None:
+            extra_override = self._units(extra_override, (), np.int32)
+        extra = np.zeros(self.U, np.uint16)
+        rc = lib().orc_insert_transformed(C.byref(st), C.byref(geo), _p(k), _p(v), _p(force), _p(extra_override),
+                                          _p(chosen), _p(best), _p(second), _p(extra))
         if rc != 0:
             raise OverflowError("oracle insert: token capacity exceeded")
-        return chosen, best, second
+        return chosen, best, second, extra
 
     def select(self, q: np.ndarray, token_budget: int):
         """q uint16 [..., G, d] -> (ids int32 [U,P] ascending, -1 padded; n_sel [U]; scores [U,P];

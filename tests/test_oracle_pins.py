@@ -737,6 +737,118 @@ def test_transformed_key_assignment_is_nearest_neighbour_in_d_plus_1():
     assert (a != a_raw).sum() > 0
 
 
+# ----------------------------------------------------------------------------- insertion on transformed keys
+def _transformed_index(K, V, C, T, extra_tokens, seed, c2=None):
+    """An oracle index built on the augmented rows [k, a(k)] (Lloyd in d+1 dims, pages of the d raw
+    coordinates), with its geometry set for insertions.  K, V uint16 [U, n, D]."""
+    U, n = K.shape[0], K.shape[1]
+    rng = np.random.default_rng(seed)
+    extra, c2 = orc.key_extra_coordinate(K, c2)
+    Ka = orc.augment(K, extra)
+    ix = orc.OracleIndex(U, 4, 16, C, max_tokens=n + extra_tokens)
+    assign = np.empty((U, n), np.int32)
+    cen_e, sum_e = np.zeros((U, C), np.float32), np.zeros((U, C), np.float32)
+    for u in range(U):
+        init = np.sort(rng.choice(n, C, replace=False)).astype(np.int32)
+        a, mu, ssum, cnt, _ = orc.lloyd(Ka[u], init, T)
+        assign[u] = a
+        ix.centroid[u], ix.cluster_sum[u], ix.cluster_cnt[u] = mu[:, :D], ssum[:, :D], cnt
+        cen_e[u], sum_e[u] = mu[:, D], ssum[:, D]
+    ix.paginate(K, V, assign)
+    key_extra = np.zeros((U, n + extra_tokens), np.uint16)
+    key_extra[:, :n] = extra
+    ix.set_geometry(c2.astype(np.float32), key_extra, cen_e, sum_e)
+    return ix, assign
+
+
+def test_transformed_insert_is_nearest_neighbour_in_d_plus_1_and_keeps_running_means():
+    """Sec. 4.2 (last paragraph) with Eq. 2: the new key goes under its nearest centroid BETWEEN
+    TRANSFORMED rows.  Brute force: direct ||[k, a] - [mu~, e~]||^2 over all clusters in d+1 dims.  The
+    extra coordinate itself against its closed form, the a = 0 rule beyond the radius, and the
+    running mean of the extra coordinate against the true mean of the members' coordinates."""
+    rng = np.random.default_rng(101)
+    U, n, C, steps = 2, 600, 9, 120
+    K = _rand_bits(rng, (U, n + steps, D))
+    K[:, ::3] = narrow(1.8 * widen(K[:, ::3]))                       # mixed norms: the coordinate matters
+    V = _rand_bits(rng, (U, n + steps, D))
+    ix, assign = _transformed_index(K[:, :n], V[:, :n], C, 3, steps, seed=5)
+    members = [[list(np.nonzero(assign[u] == c)[0]) for c in range(C)] for u in range(U)]
+    geo = ix.geometry
+    c2 = geo["radius_sq"].astype(np.float64)
+    differs_from_raw = 0
+    for t in range(n, n + steps):
+        k = K[:, t].copy()
+        if t == n + 7:
+            k = narrow(5.0 * widen(k))                                # longer than every prefill key
+        mub = narrow(ix.centroid)
+        eb = narrow(geo["centroid_extra"])
+        chosen, best, second, extra = ix.insert(k, V[:, t])
+        for u in range(U):
+            kf = widen(k[u]).astype(np.float64)
+            want = math.sqrt(max(c2[u] - (kf ** 2).sum(), 0.0))
+            assert abs(float(widen(extra[u:u + 1])[0]) - want) <= 2.0 ** -8 * want
+            if t == n + 7:
+                assert extra[u] == 0
+            assert geo["key_extra"][u, t] == extra[u]
+            row = np.concatenate([kf, widen(extra[u:u + 1]).astype(np.float64)])
+            cen = np.concatenate([widen(mub[u]).astype(np.float64), widen(eb[u]).astype(np.float64)[:, None]], 1)
+            dist = ((row[None, :] - cen) ** 2).sum(1)
+            assert chosen[u] == dist.argmin()
+            np.testing.assert_allclose(best[u] + (row ** 2).sum(), dist.min(), atol=1e-9)
+            raw = ((kf[None, :] - cen[:, :D]) ** 2).sum(1).argmin()
+            differs_from_raw += int(raw != chosen[u])
+            members[u][int(chosen[u])].append(t if t != n + 7 else -1)
+    assert differs_from_raw > 0, "the extra coordinate never changed a decision: the case is vacuous"
+    # running means = true means of the members, extra coordinate included
+    Kall = K.copy()
+    Kall[:, n + 7] = narrow(5.0 * widen(K[:, n + 7]))
+    for u in range(U):
+        for c in range(C):
+            m = [x if x >= 0 else n + 7 for x in members[u][c]]
+            assert ix.cluster_cnt[u, c] == len(m)
+            if m:
+                np.testing.assert_allclose(ix.centroid[u, c], widen(Kall[u, m]).astype(np.float64).mean(0), rtol=1e-5, atol=1e-5)
+                np.testing.assert_allclose(geo["centroid_extra"][u, c], widen(geo["key_extra"][u, m]).astype(np.float64).mean(),
+                                           rtol=1e-5, atol=1e-6)
+                np.testing.assert_allclose(geo["cluster_sum_extra"][u, c], widen(geo["key_extra"][u, m]).astype(np.float64).sum(),
+                                           rtol=1e-5, atol=1e-5)
+
+
+def test_transformed_insert_with_equal_norms_is_the_raw_insert():
+    """Keys in {+-1}^d all have squared norm d exactly, so with c^2 = d every extra coordinate is 0 and
+    the transformed insertion must leave, bit for bit, the state the raw insertion leaves."""
+    rng = np.random.default_rng(102)
+    U, n, C, steps = 2, 300, 7, 60
+    K = narrow((rng.integers(0, 2, (U, n + steps, D)) * 2 - 1).astype(np.float32))
+    V = _rand_bits(rng, (U, n + steps, D))
+    a_ix, assign = _transformed_index(K[:, :n], V[:, :n], C, 2, steps, seed=6)
+    assert np.all(a_ix.geometry["key_extra"] == 0) and np.all(a_ix.geometry["radius_sq"] == D)
+    b_ix = orc.OracleIndex(U, 4, 16, C, max_tokens=n + steps)
+    b_ix.paginate(K[:, :n], V[:, :n], assign)
+    b_ix.centroid[...], b_ix.cluster_sum[...], b_ix.cluster_cnt[...] = a_ix.centroid, a_ix.cluster_sum, a_ix.cluster_cnt
+    for t in range(n, n + steps):
+        ca = a_ix.insert(K[:, t], V[:, t])
+        cb = b_ix.insert(K[:, t], V[:, t])
+        assert np.array_equal(ca[0], cb[0]) and np.all(ca[3] == 0)
+        np.testing.assert_allclose(ca[1], cb[1], atol=1e-12)
+    for name in orc.OracleIndex.ARRAYS:
+        assert np.array_equal(getattr(a_ix, name), getattr(b_ix, name)), name
+    assert np.all(a_ix.geometry["centroid_extra"] == 0) and np.all(a_ix.geometry["cluster_sum_extra"] == 0)
+
+
+def test_transformed_insert_override_and_force_are_followed():
+    rng = np.random.default_rng(103)
+    K = _rand_bits(rng, (1, 200, D))
+    ix, _ = _transformed_index(K[:, :199], K[:, :199], 4, 1, 1, seed=7)
+    before = ix.geometry["cluster_sum_extra"].copy()
+    bits = int(narrow(np.array([2.5], np.float32))[0])
+    chosen, _, _, own = ix.insert(K[:, 199], K[:, 199], force=np.array([3], np.int32), extra_override=np.array([bits], np.int32))
+    assert chosen[0] == 3 and own[0] != bits
+    assert ix.geometry["key_extra"][0, 199] == bits
+    assert ix.geometry["cluster_sum_extra"][0, 3] == np.float32(before[0, 3] + np.float32(2.5))
+    assert ix.geometry["centroid_extra"][0, 3] == np.float32(ix.geometry["cluster_sum_extra"][0, 3] / np.float32(ix.cluster_cnt[0, 3]))
+
+
 # ----------------------------------------------------------------------------- change detector
 def test_oracle_still_gives_the_stored_small_case():
     """tests/golden/oracle_small_case.json was written by tests/golden/write_oracle_fixture.py from the
