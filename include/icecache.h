@@ -137,7 +137,9 @@ ice_status_t ice_insert_batch(ice_index_t *idx, const void *k, const void *v, in
  *   q: bf16 [B, H_q, d];  page_ids: int32 [B, H_kv, P];  n_selected: int32 [B, H_kv];
  *   scores_or_null: fp32 [B, H_kv, P] group score of each returned page (0 in the padding).
  * SHAPE if token_budget < page_size; UNSUPPORTED if the index has more than 16384 pages per unit
- * (the scores of a unit are ranked in one workgroup's registers and LDS). */
+ * (the scores of a unit are ranked in one workgroup's registers and LDS).
+ * n_selected[u] = -1 (ids -1, zero attention output) reports a unit whose workgroups could not hand
+ * their scores over within the bounded wait (see ice_debug_select_fault); never expected in use. */
 ice_status_t ice_select(ice_index_t *idx, const void *q, int32_t token_budget, int32_t *page_ids,
                         int32_t *n_selected, float *scores_or_null, void *stream);
 
@@ -200,7 +202,8 @@ ice_status_t ice_attend_tokens(ice_index_t *idx, const void *q, const void *K, c
                                const int32_t *token_pos, const int32_t *n_tok, int32_t max_tok, float *out,
                                void *stream);
 
-/* Hierarchical selection: the two-level form of the paper's top-down search (Sec. 4.3, Alg. 3).
+/* Hierarchical selection: the two-level form of the paper's top-down search (Sec. 3.3, Alg. 4: level
+ * by level from the best parents to their children; page selection, Alg. 3, calls it).
  * Stage 1 ranks the n_clusters centroids (as stored, rounded to bf16) by the same normalised GQA
  * score as pages and keeps the min(n_probe, n_clusters) best, lower id first on ties; every
  * cluster is eligible, one without pages contributes none.  Stage 2 ranks only the live pages of
@@ -212,7 +215,8 @@ ice_status_t ice_attend_tokens(ice_index_t *idx, const void *q, const void *K, c
  * first on ties, are returned; scores then holds these key scores.  n_refine must be 0 or >= P.
  *   q bf16 [B, H_q, d]; page_ids int32 [B, H_kv, P]; n_selected int32 [B, H_kv];
  *   scores_or_null fp32 [B, H_kv, P] (group scores of the returned pages);
- *   clusters_or_null int32 [B, H_kv, n_probe] (kept cluster ids ascending, -1 padded);
+ *   clusters_or_null int32 [B, H_kv, n_probe] (kept cluster ids ascending, -1 padded; n_probe may
+ *   exceed n_clusters, the lists inside the kernel are as long as what can be kept);
  *   out_or_null fp32 [B, H_q, d]: when given, attention over the returned pages (as ice_attend)
  *   runs in the same launch.
  * All device pointers, caller-owned; only enqueues.  Errors as ice_select, plus SHAPE for
@@ -251,13 +255,39 @@ ice_status_t ice_export_geometry(ice_index_t *idx, ice_geometry_view_t *view);
 ice_status_t ice_export_index(ice_index_t *idx, ice_index_view_t *view);
 ice_status_t ice_import_index(ice_index_t *idx, const ice_index_view_t *view, void *stream);
 
-/* The assignment step alone (one Lloyd round's first half) on caller data, for parity tests:
+/* The assignment step alone (one Lloyd round's first half, Sec. 4.2: every key gets its nearest
+ * promoted point) on caller data, for parity tests:
  *   K bf16 [n_units, n, d]; centroids_bf16 bf16 [n_units, n_clusters, d] ->
  *   assign_out int32 [n_units, n]; best_out_or_null fp32 [n_units, n] = min_c(||mu_c||^2 - 2 k.mu_c).
- * Uses the index's workspace as scratch and invalidates a built index (STATE afterwards). */
+ * With assign_out NULL only the assignment kernel is enqueued (its packed winners stay in the
+ * workspace): the form the benchmark times.  Uses the index's workspace as scratch and invalidates a
+ * built index (STATE afterwards). */
 ice_status_t ice_debug_assign(ice_index_t *idx, const void *K, int32_t n, const void *centroids_bf16,
-                              int32_t n_clusters, int32_t *assign_out, float *best_out_or_null,
+                              int32_t n_clusters, int32_t *assign_out_or_null, float *best_out_or_null,
                               void *stream);
+
+/* Measurement hook: enqueues ONE stage of the last ice_build_index again, on the state that build
+ * left and the same K, V (bf16 [B, H_kv, n_tokens, d] as given to the build): the assignment of the
+ * last Lloyd round, the counting sort by cluster, the member means, or the page layout (Sec. 4.1-4.2).
+ * Every stage reproduces what it wrote before, so the index is unchanged; the benchmark brackets
+ * such calls with events to time each kernel by itself.  STATE unless the index is fresh from
+ * ice_build_index (no insertion since, not imported). */
+enum { ICE_STAGE_ASSIGN = 0, ICE_STAGE_SORT = 1, ICE_STAGE_MEANS = 2, ICE_STAGE_PAGINATE = 3 };
+ice_status_t ice_debug_rerun_stage(ice_index_t *idx, const void *K, const void *V, int32_t stage, void *stream);
+
+/* Test hook for the failure path of ice_select / ice_select_attend when a unit is served by several
+ * workgroups (fewer than 256 units): those workgroups hand their page scores to the last one of
+ * them through device memory, and that one waits for a missing score only a bounded number of
+ * re-reads.  This call is ice_select_attend (out_or_null: ice_select) with the score stores of
+ * workgroup `muted_chunk` of every unit left out and the wait cut to 2^wait_log2 re-reads, so the
+ * wait expires with every wave running to its end.  What an expired wait does, here and in the
+ * product calls: the unit is not ranked; n_selected[u] = -1, its page ids are -1, its output rows
+ * are 0, and every later selection call reports the same for that unit until ice_build_index or
+ * ice_import_index re-arms it.  UNSUPPORTED when units have one workgroup each (nothing is handed
+ * over); SHAPE for muted_chunk outside the launch's workgroups per unit or wait_log2 outside [0, 20]. */
+ice_status_t ice_debug_select_fault(ice_index_t *idx, const void *q, int32_t token_budget, int32_t *page_ids,
+                                    int32_t *n_selected, float *out_or_null, int32_t muted_chunk, int32_t wait_log2,
+                                    void *stream);
 
 /* Measured-peak microbenchmarks for the benchmark's roofline context (no method arithmetic):
  *   ice_debug_peak_read  streams `bytes` (multiple of 16, 16-byte aligned device pointer) once with

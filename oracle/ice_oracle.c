@@ -432,9 +432,9 @@ void orc_select(const orc_state_t *st, const uint16_t *q, int budget, int32_t *i
 }
 
 /* ---- hierarchical page selection ----------------------------------------------------------------
- * The two-level form of the paper's top-down search (Sec. 4.3, Alg. 3: descend from the parents
- * that score best to their children).  Stage 1 scores the C cluster centroids, rounded to bf16
- * as the index stores them, with the same normalised GQA score as the pages (max over the
+ * The two-level form of the paper's top-down search (Sec. 3.3, Alg. 4: level by level, descend
+ * from the parents that score best to their children; page selection, Alg. 3, calls it).
+ * Stage 1 scores the C cluster centroids, rounded to bf16 as the index stores them, with the same normalised GQA score as the pages (max over the
  * group's heads of q_h . mu~_c / ||q_h||, fp64 rounded once to fp32) and keeps the
  * n_keep = min(n_probe, C) best by (score descending, cluster id ascending); every cluster is
  * eligible, one without pages simply contributes none.  Stage 2 ranks only the live pages whose

@@ -17,7 +17,7 @@ ICE_OK, ICE_ERR_INVALID_ARG, ICE_ERR_SHAPE, ICE_ERR_STATE, ICE_ERR_CAPACITY, ICE
 STATUS_NAMES = ["ICE_OK", "ICE_ERR_INVALID_ARG", "ICE_ERR_SHAPE", "ICE_ERR_STATE", "ICE_ERR_CAPACITY",
                 "ICE_ERR_UNSUPPORTED", "ICE_ERR_DEVICE"]
 SYMBOLS = ["ice_workspace_bytes", "ice_create", "ice_destroy", "ice_build_index", "ice_insert", "ice_insert_batch", "ice_select",
-           "ice_attend", "ice_attend_noalloc", "ice_select_attend", "ice_attend_resident", "ice_select_attend_resident", "ice_selected_tokens", "ice_attend_tokens", "ice_select_hier", "ice_set_geometry", "ice_export_geometry", "ice_export_index", "ice_import_index", "ice_debug_assign",
+           "ice_attend", "ice_attend_noalloc", "ice_select_attend", "ice_attend_resident", "ice_select_attend_resident", "ice_selected_tokens", "ice_attend_tokens", "ice_select_hier", "ice_set_geometry", "ice_export_geometry", "ice_export_index", "ice_import_index", "ice_debug_assign", "ice_debug_rerun_stage", "ice_debug_select_fault",
            "ice_debug_peak_read", "ice_debug_peak_mfma", "ice_last_error"]
 
 
@@ -89,6 +89,9 @@ def lib() -> C.CDLL:
         L.ice_import_index.argtypes = [C.c_void_p, C.POINTER(IceIndexView), C.c_void_p]
         L.ice_debug_assign.argtypes = [C.c_void_p, C.c_void_p, C.c_int32, C.c_void_p, C.c_int32, C.c_void_p,
                                        C.c_void_p, C.c_void_p]
+        L.ice_debug_rerun_stage.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32, C.c_void_p]
+        L.ice_debug_select_fault.argtypes = [C.c_void_p, C.c_void_p, C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32,
+                                             C.c_int32, C.c_void_p]
         L.ice_debug_peak_read.argtypes = [C.c_void_p, C.c_size_t, C.c_void_p, C.c_void_p]
         L.ice_debug_peak_mfma.argtypes = [C.c_void_p, C.c_int32, C.POINTER(C.c_double), C.c_void_p]
         for name in SYMBOLS:
@@ -224,6 +227,18 @@ def ice_import_index(idx, view: IceIndexView, stream=None) -> None:
 def ice_debug_assign(idx, K, n, centroids_bf16, n_clusters, assign_out, best_out=None, stream=None) -> None:
     _check(lib().ice_debug_assign(idx, _ptr(K), n, _ptr(centroids_bf16), n_clusters, _ptr(assign_out),
                                   _ptr(best_out), _stream(stream)))
+
+
+ICE_STAGE_ASSIGN, ICE_STAGE_SORT, ICE_STAGE_MEANS, ICE_STAGE_PAGINATE = range(4)
+
+
+def ice_debug_rerun_stage(idx, K, V, stage, stream=None) -> None:
+    _check(lib().ice_debug_rerun_stage(idx, _ptr(K), _ptr(V), stage, _stream(stream)))
+
+
+def ice_debug_select_fault(idx, q, token_budget, page_ids, n_selected, out, muted_chunk, wait_log2, stream=None) -> None:
+    _check(lib().ice_debug_select_fault(idx, _ptr(q), token_budget, _ptr(page_ids), _ptr(n_selected), _ptr(out), muted_chunk,
+                                        wait_log2, _stream(stream)))
 
 
 def ice_debug_peak_read(buf, nbytes, sink, stream=None) -> None:

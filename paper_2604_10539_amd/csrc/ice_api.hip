@@ -4,7 +4,9 @@
 #include <cstdarg>
 #include <cstdio>
 #include <cstring>
+#include <mutex>
 #include <new>
+#include <unordered_map>
 
 #include "ice_internal.h"
 
@@ -132,6 +134,21 @@ void reset_decode_state(const Dev &d, int n_tokens, hipStream_t s) {
 
 }  // namespace
 
+namespace ice {
+
+void allow_dynamic_lds(const void *kernel, size_t bytes) {
+    static std::mutex mu;
+    static std::unordered_map<uintptr_t, size_t> allowed;  // per (kernel, device): the largest size set so far
+    int dev = 0;
+    (void)hipGetDevice(&dev);
+    std::lock_guard<std::mutex> lock(mu);
+    size_t &have = allowed[reinterpret_cast<uintptr_t>(kernel) * 64u + (uintptr_t)(dev & 63)];
+    if (bytes <= have) return;
+    if (hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes) == hipSuccess) have = bytes;
+}
+
+}  // namespace ice
+
 extern "C" {
 
 const char *ice_last_error(void) { return g_err; }
@@ -156,6 +173,7 @@ ice_status_t ice_create(const ice_config_t *cfg, void *workspace, size_t workspa
     ix->laid_out = false;
     ix->built = false;
     ix->n_tokens = 0;
+    ix->build_n = 0;
     ix->cur = 0;
     ix->geometry = 0;
     *out = ix;
@@ -198,6 +216,7 @@ ice_status_t ice_build_index(ice_index_t *ix, const void *K, const void *V, int3
     if (ice_status_t st = device_status("ice_build_index")) return st;
     ix->cur = cur;
     ix->n_tokens = n;
+    ix->build_n = n;
     ix->built = true;
     return ICE_OK;
 }
@@ -444,6 +463,7 @@ ice_status_t ice_import_index(ice_index_t *ix, const ice_index_view_t *v, void *
     launch_refresh_centroids(d, 1, s);
     if (ice_status_t st = device_status("ice_import_index")) return st;
     ix->n_tokens = v->n_tokens;
+    ix->build_n = 0;  // (not the product of a build here: no stage to re-run)
     ix->built = true;
     return ICE_OK;
 }
@@ -451,8 +471,8 @@ ice_status_t ice_import_index(ice_index_t *ix, const ice_index_view_t *v, void *
 ice_status_t ice_debug_assign(ice_index_t *ix, const void *K, int32_t n, const void *cent, int32_t n_clusters,
                               int32_t *assign_out, float *best_out, void *stream) {
     if (!ix) return fail(ICE_ERR_INVALID_ARG, "index is null");
-    if (!K || !cent || !assign_out || !aligned16(K) || !aligned16(cent))
-        return fail(ICE_ERR_INVALID_ARG, "K, centroids or assign_out is null or misaligned");
+    if (!K || !cent || !aligned16(K) || !aligned16(cent))
+        return fail(ICE_ERR_INVALID_ARG, "K or centroids is null or misaligned");
     if (n < 1) return fail(ICE_ERR_INVALID_ARG, "n must be >= 1");
     if (n > ix->cfg.max_tokens) return fail(ICE_ERR_SHAPE, "n %d exceeds max_tokens %d", n, ix->cfg.max_tokens);
     const int s_cur = ix->laid_out ? ix->dev.s : 16;
@@ -464,8 +484,40 @@ ice_status_t ice_debug_assign(ice_index_t *ix, const void *K, int32_t n, const v
     const Dev &d = ix->dev;
     launch_load_centroids(d, static_cast<const bf16_t *>(cent), 0, s);
     launch_assign(d, static_cast<const bf16_t *>(K), n, 0, s);
-    launch_sort(d, n, best_out, assign_out, s);
+    if (assign_out) launch_sort(d, n, best_out, assign_out, s);  // (unpacks the winners; without it only the kernel is timed)
     return device_status("ice_debug_assign");
+}
+
+ice_status_t ice_debug_rerun_stage(ice_index_t *ix, const void *K, const void *V, int32_t stage, void *stream) {
+    if (!ix) return fail(ICE_ERR_INVALID_ARG, "index is null");
+    if (!ix->built || ix->build_n == 0 || ix->n_tokens != ix->build_n)
+        return fail(ICE_ERR_STATE, "ice_debug_rerun_stage needs an index fresh from ice_build_index (no insertion since)");
+    if (!K || !V || !aligned16(K) || !aligned16(V)) return fail(ICE_ERR_INVALID_ARG, "K or V is null or misaligned");
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    const Dev &d = ix->dev;
+    const bf16_t *Kb = static_cast<const bf16_t *>(K), *Vb = static_cast<const bf16_t *>(V);
+    const int n = ix->build_n, prev = ix->cur ^ 1;  // the last round read buffer `prev` and wrote the live one
+    switch (stage) {
+        case ICE_STAGE_ASSIGN: launch_assign(d, Kb, n, prev, s); break;
+        case ICE_STAGE_SORT: launch_sort(d, n, nullptr, nullptr, s); break;
+        case ICE_STAGE_MEANS: launch_means(d, Kb, n, prev, s); break;
+        case ICE_STAGE_PAGINATE: launch_paginate(d, Kb, Vb, n, s); break;
+        default: return fail(ICE_ERR_INVALID_ARG, "stage %d: one of ICE_STAGE_ASSIGN .. ICE_STAGE_PAGINATE", stage);
+    }
+    return device_status("ice_debug_rerun_stage");
+}
+
+ice_status_t ice_debug_select_fault(ice_index_t *ix, const void *q, int32_t budget, int32_t *ids, int32_t *n_sel, float *out,
+                                    int32_t muted_chunk, int32_t wait_log2, void *stream) {
+    if (ice_status_t st = check_select(ix, q, budget, ids, n_sel, "ice_debug_select_fault")) return st;
+    const int np_hint = ix->n_tokens / ix->dev.s + ix->dev.C;
+    const int chunks = decode_step_chunks(ix->dev, np_hint);
+    if (chunks < 2) return fail(ICE_ERR_UNSUPPORTED, "this index is served by one workgroup per unit: there is no score hand-off to disturb");
+    if (muted_chunk < 0 || muted_chunk >= chunks) return fail(ICE_ERR_SHAPE, "muted_chunk %d is outside [0, %d)", muted_chunk, chunks);
+    if (wait_log2 < 0 || wait_log2 > 20) return fail(ICE_ERR_SHAPE, "wait_log2 %d is outside [0, 20]", wait_log2);
+    launch_decode_step(ix->dev, static_cast<const bf16_t *>(q), budget / ix->dev.s, np_hint, ids, n_sel, nullptr, nullptr, nullptr, 0,
+                       out, static_cast<hipStream_t>(stream), wait_log2 | ((muted_chunk + 1) << 8));
+    return device_status("ice_debug_select_fault");
 }
 
 }  // extern "C"

@@ -2,7 +2,6 @@
 // matrix cores, deterministic per-cluster means, and the node -> page layout (Sec. 4.1-4.2,
 // Alg. 2 of the paper restricted to two levels and iterated as Lloyd rounds).
 #include <algorithm>
-#include <cstdlib>
 
 #include "ice_internal.h"
 
@@ -218,15 +217,6 @@ __device__ inline void argmax16(const f32x16 &x, float &m, uint32_t &idx) {
     m = g ? t2[1] : t2[0];
     idx = g ? i2[1] : i2[0];
 }
-#ifdef ICE_PROF
-__device__ long long ice_prof_b[16];
-__device__ long long ice_prof_w[128];
-#define ICE_BSTAMP(i) do { if (threadIdx.x == 0 && blockIdx.x == 0 && blockIdx.z == 0) ice_prof_b[i] = wall_clock64(); } while (0)
-#define ICE_WSTAMP(t, i) do { if ((t) == 1 && (threadIdx.x & 63) == 0 && blockIdx.x == 0 && blockIdx.z == 0) { ice_prof_w[(threadIdx.x >> 6) * 8 + (i)] = wall_clock64(); ice_prof_w[64 + (threadIdx.x >> 6) * 8 + (i)] = clock64(); } } while (0)
-#else
-#define ICE_BSTAMP(i) do { } while (0)
-#define ICE_WSTAMP(t, i) do { } while (0)
-#endif
 // LDS layout of a 256-row tile (keys, or the centroid block while it is staged): rows of 256 bytes
 // without padding, the 16-byte chunk c of row r stored in slot c ^ (r & 15).  A fragment read (lane
 // = row r, chunk 2 ks + half) then hits 16 different 16-byte bank groups per 16 lanes (measured: the
@@ -465,17 +455,6 @@ __global__ __launch_bounds__(512) void assign_kernel(const bf16_t *__restrict__ 
     }
 }
 
-#ifdef ICE_PROF
-}  // namespace ice
-extern "C" int ice_debug_prof_b(long long *host16) {
-    return (int)hipMemcpyFromSymbol(host16, HIP_SYMBOL(ice::ice_prof_b), sizeof(long long) * 16);
-}
-extern "C" int ice_debug_prof_w(long long *host128) {
-    return (int)hipMemcpyFromSymbol(host128, HIP_SYMBOL(ice::ice_prof_w), sizeof(long long) * 128);
-}
-namespace ice {
-#endif
-
 void launch_assign(const Dev &d, const bf16_t *K, int n, int cur, hipStream_t st) {
     const int tiles = d.Cpad / 32;
     int CT = tiles == 1 ? 1 : 2, CW = 1;
@@ -485,12 +464,8 @@ void launch_assign(const Dev &d, const bf16_t *K, int n, int cur, hipStream_t st
     // One workgroup per CU when the work allows it (a workgroup fills a CU: 132-148 KB of LDS, 8 waves
     // of 226-256 registers), each amortising its prologue over as many key tiles as possible.
     int keys_per_wg = kAssignTile;
-    int wg_target = 256, kpw_max = 1 << 30;
-#ifdef ICE_PROF
-    if (const char *e = getenv("ICE_ASSIGN_WGS")) wg_target = atoi(e);
-    if (const char *e = getenv("ICE_ASSIGN_KPW")) kpw_max = atoi(e);
-#endif
-    while ((long long)((n + keys_per_wg - 1) / keys_per_wg) * zsplit * d.U > wg_target && keys_per_wg < kpw_max) keys_per_wg *= 2;
+    const int wg_target = 256;
+    while ((long long)((n + keys_per_wg - 1) / keys_per_wg) * zsplit * d.U > wg_target && keys_per_wg < n) keys_per_wg *= 2;
     dim3 grid((n + keys_per_wg - 1) / keys_per_wg, zsplit, d.U);
     const size_t lds = assign_lds_bytes(d.tk != 0);
     if (zsplit > 1) {
@@ -499,7 +474,7 @@ void launch_assign(const Dev &d, const bf16_t *K, int n, int cur, hipStream_t st
     }
 #define ICE_ASSIGN_A(ct, cw, aug)                                                                   \
     do {                                                                                            \
-        (void)hipFuncSetAttribute((const void *)assign_kernel<ct, cw, aug>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds); \
+        allow_dynamic_lds((const void *)assign_kernel<ct, cw, aug>, lds);                           \
         hipLaunchKernelGGL((assign_kernel<ct, cw, aug>), grid, dim3(512), lds, st, K, d.cent_bf16[cur], d.cnorm[cur], n, keys_per_wg, \
                            zsplit, d.Cpad, cur, d);                                                 \
     } while (0)
@@ -742,10 +717,10 @@ void launch_sort(const Dev &d, int n, float *best_out, int *assign_out, hipStrea
     if (R > 1)
         hipLaunchKernelGGL(sort_totals_kernel, dim3(R, d.U), dim3(1024), (size_t)d.Cpad * sizeof(int), st, d, n, range_len);
     if (seg <= kSortRegGroups * 64) {
-        (void)hipFuncSetAttribute((const void *)sort_unit_kernel<true>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        allow_dynamic_lds((const void *)sort_unit_kernel<true>, lds);
         hipLaunchKernelGGL(sort_unit_kernel<true>, dim3(R, d.U), dim3(1024), lds, st, d, n, range_len, W, seg, best_out, assign_out);
     } else {
-        (void)hipFuncSetAttribute((const void *)sort_unit_kernel<false>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        allow_dynamic_lds((const void *)sort_unit_kernel<false>, lds);
         hipLaunchKernelGGL(sort_unit_kernel<false>, dim3(R, d.U), dim3(1024), lds, st, d, n, range_len, W, seg, best_out, assign_out);
     }
 }
@@ -940,3 +915,5 @@ void launch_paginate(const Dev &d, const bf16_t *K, const bf16_t *V, int n, hipS
 }
 
 }  // namespace ice
+
+ICE_PROF_EXPORT(ice_debug_prof_build)

@@ -5,22 +5,12 @@
 #include <type_traits>
 #include "ice_internal.h"
 
-#ifdef ICE_PROF
-namespace ice {
-__device__ long long ice_prof[16];
-__device__ long long ice_prof_u[4 * 1024];  // per unit: start, end of scoring, end of selection, end
-}  // namespace ice
-#define ICE_STAMP(i) do { if (threadIdx.x == 0 && u == 0) ice_prof[i] = wall_clock64(); } while (0)
-#define ICE_USTAMP(i) do { if (threadIdx.x == 0 && u < 1024) ice_prof_u[4 * u + (i)] = wall_clock64(); } while (0)
-#define ICE_PROF_ATTEND 1
-#else
-#define ICE_USTAMP(i) do { } while (0)
-#endif
 #include "ice_decode_common.h"
 
 namespace ice {
 
 constexpr uint32_t kScoreEmpty = 0xFFFFFFFFu;  // a NaN pattern no score can take (scores come out of fmaxf)
+constexpr int kUnitFailed = -(1 << 30);        // arrival counter of a unit whose score hand-off gave up
 
 
 // ------------------------------------------------------------------------------------------------
@@ -33,8 +23,10 @@ constexpr uint32_t kScoreEmpty = 0xFFFFFFFFu;  // a NaN pattern no score can tak
 // centroid, its bf16 rounding and squared norm.  The next token sees the moved centroid, exactly
 // as m separate launches would.  k, v: bf16 [U, m, d].
 constexpr int kInsertWaves = 16;
+// (cent, cnorm: the live centroid buffer d.cent_bf16[cur] / d.cnorm[cur], which this kernel also
+// writes, hence neither const nor restrict)
 __global__ __launch_bounds__(kInsertWaves * 64) void insert_kernel(const bf16_t *__restrict__ k, const bf16_t *__restrict__ v,
-                                                                    const bf16_t *__restrict__ cent, const float *__restrict__ cnorm,
+                                                                    bf16_t *cent, float *cnorm,
                                                                     int m, int cur, int C, int Cpad, Dev d) {  // (scalars first: preloaded)
     __shared__ u64 best;
     const int u = blockIdx.x, tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
@@ -81,7 +73,9 @@ __global__ __launch_bounds__(kInsertWaves * 64) void insert_kernel(const bf16_t 
         if (ch == 0 && bi != 0x7FFFFFFF) atomicMin(&best, ((u64)f32_ordered(bv) << 32) | (u64)(uint32_t)bi);
         __syncthreads();
         if (wave == 0) {
-            const int c = (int)(uint32_t)best;
+            // (no lane wins when every distance is NaN, i.e. a key with Inf / NaN coordinates: cluster 0 then,
+            // the choice of an exhaustive search that never sees a smaller value)
+            const int c = best == ~0ull ? 0 : (int)(uint32_t)best;
             const size_t cl = (size_t)u * d.C + c;
             int tail = d.cluster_tail[cl];
             int fill = tail >= 0 ? d.page_fill[(size_t)u * d.max_pages + tail] : d.s;
@@ -108,7 +102,7 @@ __global__ __launch_bounds__(kInsertWaves * 64) void insert_kernel(const bf16_t 
             const float2 mu = make_float2(cs.x / fc, cs.y / fc);
             ((float2 *)(d.centroid + cl * kD))[lane] = mu;
             const bf16_t b0 = f32_to_bf16(mu.x), b1 = f32_to_bf16(mu.y);
-            ((uint32_t *)(d.cent_bf16[cur] + ((size_t)u * d.Cpad + c) * kD))[lane] = (uint32_t)b0 | ((uint32_t)b1 << 16);
+            ((uint32_t *)(cent + ((size_t)u * Cpad + c) * kD))[lane] = (uint32_t)b0 | ((uint32_t)b1 << 16);
             const float f0 = bf16_to_f32(b0), f1 = bf16_to_f32(b1);
             float nn = wave_sum(f0 * f0 + f1 * f1);
             if (d.tk) {  // the cluster's extra coordinate follows its members' running mean as well
@@ -125,7 +119,7 @@ __global__ __launch_bounds__(kInsertWaves * 64) void insert_kernel(const bf16_t 
                 }
             }
             if (lane == 0) {
-                d.cnorm[cur][(size_t)u * d.Cpad + c] = nn;
+                cnorm[(size_t)u * Cpad + c] = nn;
                 d.cluster_cnt[cl] = cnt;
                 d.cluster_tail[cl] = tail;
                 d.page_fill[pg] = fill;
@@ -156,7 +150,7 @@ __global__ __launch_bounds__(NW * 64) void attend_kernel(const bf16_t *__restric
     bf16x8 qa[4];
     load_query_operand<G>(q, u, threadIdx.x & 63, qa, nullptr);
     const int *list = ids + (size_t)u * P;
-    const int ns = ids ? min(n_sel[u], P) : 0;  // (no page list: resident tokens only)
+    const int ns = ids ? max(0, min(n_sel[u], P)) : 0;  // (no page list: resident tokens only; negative count: none)
     attend_pages<G, NW, RES>(d, u, qa, [=](int x) { return list[x]; }, ns, res, out, (float *)smem, [] {});
 }
 
@@ -172,7 +166,7 @@ __global__ __launch_bounds__(NW * 64) void attend_split_kernel(const bf16_t *__r
     const int s = blockIdx.x, S = gridDim.x, u = blockIdx.y;
     bf16x8 qa[4];
     load_query_operand<G>(q, u, threadIdx.x & 63, qa, nullptr);
-    const int ns = min(n_sel[u], P), per = (ns + S - 1) / S;
+    const int ns = max(0, min(n_sel[u], P)), per = (ns + S - 1) / S;
     const int lo = min(ns, s * per), cnt = min(ns - lo, per);
     const int *list = ids + (size_t)u * P + lo;
     attend_pages<G, NW, false, true>(d, u, qa, [=](int x) { return list[x]; }, cnt, Resident{nullptr, nullptr, 0, nullptr, nullptr, 0},
@@ -208,7 +202,7 @@ __global__ void selected_tokens_kernel(Dev d, const int *__restrict__ ids, const
                                        int *__restrict__ pos_out, int *__restrict__ n_tok_out) {
     const int u = blockIdx.x, s = d.s;
     __shared__ int base[1025];
-    const int ns = min(n_sel[u], P);
+    const int ns = max(0, min(n_sel[u], P));
     if (threadIdx.x == 0) {
         int acc = 0;
         for (int x = 0; x < ns; ++x) {
@@ -337,20 +331,22 @@ hipError_t launch_attend_static(const Dev &d, const bf16_t *q, const int *ids, c
 // pages, attend over them (Sec. 4.3-4.4, Alg. 3, Eq. 1).
 //
 // Phase A, every workgroup: a unit's representatives are one contiguous bf16 stream, split over
-// `chunks` workgroups.  A wave reads 1 KiB (four rows) per load instruction, 16 lanes x 16 bytes per
-// row, reduces each row's partial dot products inside its 16-lane DPP row, and stores
+// `chunks` workgroups.  Scores come off the matrix cores, 16 pages per four
+// v_mfma_f32_16x16x32_bf16 in the split-row operand form (SplitRow: every load instruction reads
+// whole 128-byte lines, 8 rows x 128 bytes, with the non-temporal hint):
 //   S[p] = max over the G query heads of (q_h . rep_p) / ||q_h||     (query normalisation of Eq. 3).
 // The workgroup then bumps the unit's arrival counter; the LAST one to arrive carries on alone.
 // Workgroup ids are mapped so that all chunks of a unit share (id mod 8), i.e. the same XCD and L2.
 //
 // Phase B, last workgroup of the unit: exact top-k over the composite key (score, lower id first),
-// all keys distinct.  A threshold that at least k keys reach comes first: the keys sit in registers,
-// every 16-lane row takes the maximum of its keys, and the k-th largest of these row maxima is
-// such a threshold (k different rows hold a key at or above it); with 64 rows and k = 16 it lets
-// through barely more than k keys.  (Budgets above the row count use a bitwise radix descent on
-// wave ballots instead.)  Keys at or above the threshold go to an LDS candidate list, where every
-// candidate counts how many candidates beat it.  Rank < k wins; winners are placed in ascending id
-// order.
+// all keys distinct.  A threshold that at least k keys reach comes first.  Small budgets: the keys
+// sit in registers, every 16-lane row (or, with one workgroup per unit, every (wave, unroll slot)
+// group formed while scoring) takes the maximum of its keys, and the k-th largest of these maxima
+// is such a threshold (k different groups hold a key at or above it); with 64 groups and k = 16 it
+// lets through barely more than k keys.  Large budgets: the 16-bit prefix of the k-th largest key
+// from two 8-bit LDS histograms; keys above the prefix are winners as they are.  What is left goes
+// to an LDS candidate list, ranked exactly by counting (or by an LDS-histogram radix select when
+// the list is long).  Winners are placed in ascending id order.
 //
 // Phase C, same workgroup: attention over the winners (attend_pages), ids never leave the chip.
 // The leading scalar arguments are what the kernel needs before its first loads can be issued: the
@@ -359,13 +355,13 @@ hipError_t launch_attend_static(const Dev &d, const bf16_t *q, const int *ids, c
 // scalar loads while the first loads are in flight.
 template <int G, int NW, int EMAX, bool RES>
 __global__ __launch_bounds__(NW * 64) void decode_step_kernel(int U, int max_pages, int P, int chunks, int np_hint, int lds_scores_off,
-                                                               const bf16_t *__restrict__ rep_all, const bf16_t *__restrict__ q,
+                                                               int wait_cfg, const bf16_t *__restrict__ rep_all, const bf16_t *__restrict__ q,
                                                                const int *__restrict__ n_pages, Dev d, int *__restrict__ ids_out,
                                                                int *__restrict__ n_sel_out, float *__restrict__ scores_out, Resident res,
                                                                float *__restrict__ out) {
     constexpr int NT = NW * 64;
     extern __shared__ __align__(16) char smem[];
-    __shared__ int sh_last, sh_M, sh_M2, sh_W;
+    __shared__ int sh_last, sh_M, sh_M2, sh_W, sh_fail;
     __shared__ uint32_t sh_pre;
     __shared__ uint32_t sh_rowmax[4 * NW];
     __shared__ u64 sh_tau;
@@ -384,6 +380,12 @@ __global__ __launch_bounds__(NW * 64) void decode_step_kernel(int U, int max_pag
 
     // one workgroup per unit: the scores never leave LDS and there is nobody to wait for
     const bool single = chunks == 1;
+    // wait_cfg: bits 0..7 = log2 of the re-reads the last workgroup spends on a score slot that is
+    // still empty; bits 8.. = 1 + the chunk whose score stores are left out (0: none).  The latter
+    // exists for the test of the give-up path only: a hand-off that cannot complete, forced from the
+    // host, with every wave still running to its end.
+    const int spin_limit = 1 << (wait_cfg & 255);
+    const bool muted = (wait_cfg >> 8) == chunk + 1;
     uint32_t *sc_lds = (uint32_t *)(smem + lds_scores_off);
 
     if (chunk == 0) ICE_STAMP(0);
@@ -391,6 +393,7 @@ __global__ __launch_bounds__(NW * 64) void decode_step_kernel(int U, int max_pag
     if (tid == 0) {  // (visible to the workgroup after the barrier that ends phase A)
         sh_M = 0;
         sh_W = 0;
+        sh_fail = 0;
         sh_pre = 0u;
         sh_tau = 0ull;
     }
@@ -453,7 +456,7 @@ __global__ __launch_bounds__(NW * 64) void decode_step_kernel(int U, int max_pag
                 const int page = p0 + 16 * (b0 + NW * x) + ch;
                 if (owner && page < lim) {
                     if (single) sc_lds[page] = __float_as_uint(sc);
-                    else __hip_atomic_store(S + page, __float_as_uint(sc), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                    else if (!muted) __hip_atomic_store(S + page, __float_as_uint(sc), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
                     gmax[x] = fmaxf(gmax[x], sc);
                 }
             }
@@ -489,12 +492,34 @@ __global__ __launch_bounds__(NW * 64) void decode_step_kernel(int U, int max_pag
     if (!single) {
         if (tid == 0) {
             const int old = __hip_atomic_fetch_add(d.counter + u, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            const int last = old == chunks - 1;
-            if (last) __hip_atomic_store(d.counter + u, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);  // next launch
-            sh_last = last;
+            // 1: the last to arrive carries on; 2: the unit was marked failed by an earlier launch (its
+            // counter is negative until the index is rebuilt or imported again): chunk 0 says so again
+            int role = old < 0 ? (chunk == 0 ? 2 : 0) : (old == chunks - 1 ? 1 : 0);
+            if (role == 1) __hip_atomic_store(d.counter + u, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);  // next launch
+            sh_last = role;
         }
         __syncthreads();
         if (!sh_last) return;
+    }
+    // A score hand-off that did not complete (a slot still empty after the bounded wait) is never
+    // ranked: the unit reports n_selected = -1, ids -1 and a zero output, and stays marked (negative
+    // arrival counter, slots left as they are) so that every later launch reports the same until
+    // ice_build_index / ice_import_index re-arm the unit.
+    auto report_failure = [&] {
+        for (int x = tid; x < P; x += NT) {
+            ids_out[(size_t)u * P + x] = -1;
+            if (scores_out) scores_out[(size_t)u * P + x] = 0.f;
+        }
+        if (out)
+            for (int o = tid; o < G * kD; o += NT) out[(size_t)u * G * kD + o] = 0.f;
+        if (tid == 0) {
+            n_sel_out[u] = -1;
+            __hip_atomic_store(d.counter + u, kUnitFailed, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        }
+    };
+    if (!single && sh_last == 2) {  // (workgroup-uniform)
+        report_failure();
+        return;
     }
     ICE_STAMP(1);
     ICE_USTAMP(1);
@@ -506,12 +531,13 @@ __global__ __launch_bounds__(NW * 64) void decode_step_kernel(int U, int max_pag
     };
     auto finish_score = [&](int pid, uint32_t v) -> uint32_t {  // (several workgroups per unit only)
         if (v != kScoreEmpty) return v;
-        for (int spin = 0; v == kScoreEmpty && spin < (1 << 16); ++spin)
+        for (int spin = 0; v == kScoreEmpty && spin < spin_limit; ++spin)
             v = __hip_atomic_load(S + pid, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         if (v == kScoreEmpty) {  // never expected; a fence bounds the wait
             __threadfence();
             v = __hip_atomic_load(S + pid, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         }
+        if (v == kScoreEmpty) sh_fail = 1;  // gave up: the workgroup reports the unit as failed
         return v;
     };
     auto rearm_score = [&](int pid) {
@@ -528,12 +554,17 @@ __global__ __launch_bounds__(NW * 64) void decode_step_kernel(int U, int max_pag
     u64 *cand = (u64 *)region;
     if (k == np) {
         // budget covers every page
-        for (int x = tid; x < k; x += NT) {
-            uint32_t v = request_score(x);
-            if (!single) {
-                v = finish_score(x, v);
-                rearm_score(x);
+        if (!single) {  // all slots filled?  (nothing is written or re-armed before that is known)
+            for (int x = tid; x < k; x += NT) finish_score(x, request_score(x));
+            lds_barrier();
+            if (sh_fail) {
+                report_failure();
+                return;
             }
+        }
+        for (int x = tid; x < k; x += NT) {
+            const uint32_t v = request_score(x);
+            if (!single) rearm_score(x);
             ids[x] = x;
             if (sco) sco[x] = __uint_as_float(v);
         }
@@ -549,6 +580,11 @@ __global__ __launch_bounds__(NW * 64) void decode_step_kernel(int U, int max_pag
 #pragma unroll
             for (int e = 0; e < EMAX; ++e)
                 if (e * NT + tid < np) key[e] = finish_score(e * NT + tid, key[e]);
+            lds_barrier();
+            if (sh_fail) {  // (workgroup-uniform)
+                report_failure();
+                return;
+            }
 #pragma unroll
             for (int e = 0; e < EMAX; ++e)
                 if (e * NT + tid < np) rearm_score(e * NT + tid);
@@ -696,9 +732,6 @@ __global__ __launch_bounds__(NW * 64) void decode_step_kernel(int U, int max_pag
         lds_barrier();
         const int M = sh_M;  // >= need
         ICE_STAMP(4);
-#ifdef ICE_PROF
-        if (tid == 0 && u == 0 && M < 0) ice_prof[15] = M;
-#endif
         // B3: the `need` best of the M candidates, exactly, into sel_comp[first..k)
         if (M <= 256) {
             // every candidate counts the candidates that beat it; `parts` lanes share one candidate
@@ -805,30 +838,25 @@ __global__ __launch_bounds__(NW * 64) void decode_step_kernel(int U, int max_pag
     }
     ICE_USTAMP(3);
 }
-#ifdef ICE_PROF
-}  // namespace ice
-extern "C" int ice_debug_prof_u(long long *host4096) {
-    return (int)hipMemcpyFromSymbol(host4096, HIP_SYMBOL(ice::ice_prof_u), sizeof(long long) * 4096);
-}
-extern "C" int ice_debug_prof(long long *host16) {
-    return (int)hipMemcpyFromSymbol(host16, HIP_SYMBOL(ice::ice_prof), sizeof(long long) * 16);
-}
-namespace ice {
-#endif
-
 size_t decode_step_lds_bytes(const Dev &d, int P);
 
+int decode_step_chunks(const Dev &d, int np_hint) {
+    const int NW = d.G == 8 ? 8 : 16;
+    np_hint = std::max(1, std::min(np_hint, d.max_pages));
+    int chunks = 256 / d.U;
+    const int max_chunks = (np_hint + 16 * NW - 1) / (16 * NW);
+    if (chunks > max_chunks) chunks = max_chunks;
+    return chunks < 1 ? 1 : chunks;
+}
+
 void launch_decode_step(const Dev &d, const bf16_t *q, int P, int np_hint, int *ids, int *n_sel, float *scores_out,
-                        const bf16_t *res_k, const bf16_t *res_v, int n_res, float *out, hipStream_t st) {
+                        const bf16_t *res_k, const bf16_t *res_v, int n_res, float *out, hipStream_t st, int wait_cfg) {
     const int NW = d.G == 8 ? 8 : 16;
     // a workgroup pass scores 16*NW pages per load round; few units -> split each unit over many
     // workgroups (one round each), many units -> one workgroup per unit and no cross-workgroup step
     if (np_hint > d.max_pages) np_hint = d.max_pages;
     if (np_hint < 1) np_hint = 1;
-    int chunks = 256 / d.U;
-    const int max_chunks = (np_hint + 16 * NW - 1) / (16 * NW);
-    if (chunks > max_chunks) chunks = max_chunks;
-    if (chunks < 1) chunks = 1;
+    const int chunks = decode_step_chunks(d, np_hint);
     // few units and a large budget: select in this launch, attend with the unit's pages spread over
     // several workgroups (two more launches, see attend_split_kernel)
     const bool split_attend = out && chunks > 1 && n_res == 0 && attend_shares(d, P, 8) > 1;
@@ -839,9 +867,9 @@ void launch_decode_step(const Dev &d, const bf16_t *q, int P, int np_hint, int *
     const Resident res = {res_k, res_v, out_fused ? n_res : 0, nullptr, nullptr, 0};
 #define ICE_STEP_R(g, nw, e, r)                                                                                     \
     do {                                                                                                            \
-        (void)hipFuncSetAttribute((const void *)decode_step_kernel<g, nw, e, r>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds); \
+        allow_dynamic_lds((const void *)decode_step_kernel<g, nw, e, r>, lds);                                      \
         hipLaunchKernelGGL((decode_step_kernel<g, nw, e, r>), dim3(grid), dim3(nw * 64), lds, st, d.U, d.max_pages, P, chunks, np_hint, \
-                           (int)(lds - (size_t)d.max_pages * 4), d.rep, q, d.n_pages, d, ids, n_sel, scores_out, res, out_fused); \
+                           (int)(lds - (size_t)d.max_pages * 4), wait_cfg, d.rep, q, d.n_pages, d, ids, n_sel, scores_out, res, out_fused); \
     } while (0)
 #define ICE_STEP(g, nw, e)                                                                                          \
     do {                                                                                                            \
@@ -871,3 +899,5 @@ size_t decode_step_lds_bytes(const Dev &d, int P) {
 }
 
 }  // namespace ice
+
+ICE_PROF_EXPORT(ice_debug_prof_decode)

@@ -13,11 +13,6 @@ typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef unsigned v2u __attribute__((ext_vector_type(2)));
 typedef unsigned long long u64;
 
-// profiling builds define these before including this header
-#ifndef ICE_STAMP
-#define ICE_STAMP(i) do { } while (0)
-#endif
-
 // a.lo*b.lo + a.hi*b.hi + c on packed bf16 pairs, fp32 accumulate (v_dot2_f32_bf16)
 __device__ inline float dot2(uint32_t a, uint32_t b, float c) {
     return __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, a), __builtin_bit_cast(bf16x2, b), c, false);
@@ -173,7 +168,7 @@ __device__ inline void attend_pages(const Dev &d, int u, const bf16x8 (&qa)[4], 
         for (int ks = 0; ks < 4; ++ks)
             z = __builtin_amdgcn_mfma_f32_16x16x32_bf16(qa[ks], __builtin_bit_cast(bf16x8, kb[ks]), z, 0, 0, 0);
 #ifdef ICE_PROF_ATTEND
-        if (threadIdx.x == 0 && u == 0 && z[0] != 12345.f) ice_prof[9] = wall_clock64();
+        if (threadIdx.x == 0 && u == 0 && z[0] != 12345.f) ice::prof::stamps[9] = wall_clock64();
 #endif
         const bool tok_ok = b0 + ch < fill;  // this lane's logits belong to token b0 + ch
         float pw[4], alpha[4];

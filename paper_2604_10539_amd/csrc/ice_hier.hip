@@ -1,5 +1,6 @@
-// Hierarchical page selection: the two-level form of the paper's top-down search (Sec. 4.3,
-// Alg. 3: descend from the parents that score best to their children).  One launch, one workgroup
+// Hierarchical page selection: the two-level form of the paper's top-down search (Sec. 3.3,
+// Alg. 4: descend level by level from the parents that score best to their children; Alg. 3,
+// page selection, calls it).  One launch, one workgroup
 // per unit:
 //   stage 1  score the C cluster centroids (their bf16 rounding, the same rows the assignment
 //            uses) against the group's queries, keep the n_probe best by (score, lower id first);
@@ -10,18 +11,6 @@
 // Against the flat scan this reads C + n_probe/C * n_p representative rows instead of n_p.
 // Scores are the flat scan's: max over the G heads of (q_h . row) / ||q_h||, fp32 MFMA accumulate.
 #include "ice_decode_common.h"
-
-#ifdef ICE_PROF
-namespace ice {
-__device__ long long ice_prof_h[16];
-}
-#define ICE_HSTAMP(i) do { if (threadIdx.x == 0 && blockIdx.x == 0) ice_prof_h[i] = wall_clock64(); } while (0)
-extern "C" int ice_debug_prof_h(long long *host16) {
-    return (int)hipMemcpyFromSymbol(host16, HIP_SYMBOL(ice::ice_prof_h), sizeof(long long) * 16);
-}
-#else
-#define ICE_HSTAMP(i) do { } while (0)
-#endif
 
 namespace ice {
 
@@ -232,10 +221,13 @@ __host__ __device__ inline HierLds hier_lds(int Cpad, int max_pages, int n_probe
     L.comp2 = off;  off += align16((size_t)max_pages * 8);
     L.list = off;   off += (size_t)kListCap * 8;
     L.hist = off;   off += 2 * 272 * 4;
-    L.sel1 = off;   off += align16((size_t)n_probe * 8);
-    L.sel2 = off;   off += align16((size_t)(n_refine > P ? n_refine : P) * 8);
-    L.comp3 = off;  off += align16((size_t)n_refine * 8);
-    L.sel3 = off;   off += align16((size_t)P * 8);
+    // (lists are as long as what can be kept: at most every cluster, at most every page)
+    const int n_keep = n_probe < Cpad ? n_probe : Cpad, Pk = P < max_pages ? P : max_pages;
+    const int n_ref = n_refine < max_pages ? n_refine : max_pages;
+    L.sel1 = off;   off += align16((size_t)n_keep * 8);
+    L.sel2 = off;   off += align16((size_t)(n_ref > Pk ? n_ref : Pk) * 8);
+    L.comp3 = off;  off += align16((size_t)n_ref * 8);
+    L.sel3 = off;   off += align16((size_t)Pk * 8);
     L.red = off;    off += align16(sizeof(float) * (size_t)attend_scratch_floats(G, NW));
     L.total = off;
     return L;
@@ -528,7 +520,7 @@ void launch_decode_hier(const Dev &d, const bf16_t *q, int cur, int P, int n_pro
     const int E = (d.max_pages + NW * 64 - 1) / (NW * 64);
 #define ICE_HIER(g, nw, e)                                                                                           \
     do {                                                                                                             \
-        (void)hipFuncSetAttribute((const void *)decode_hier_kernel<g, nw, e>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds); \
+        allow_dynamic_lds((const void *)decode_hier_kernel<g, nw, e>, lds);                                          \
         hipLaunchKernelGGL((decode_hier_kernel<g, nw, e>), dim3(d.U), dim3(nw * 64), lds, st, d.Cpad, d.max_pages, np_hint, P, n_probe, \
                            n_refine, d.cent_bf16[cur], q, d.page_cluster, d.n_pages, d, ids, n_sel, scores_out, clusters_out, out);                                                    \
     } while (0)
@@ -543,3 +535,5 @@ void launch_decode_hier(const Dev &d, const bf16_t *q, int cur, int P, int n_pro
 int decode_hier_max_pages(int G) { return G == 8 ? 8 * 64 * 32 : 16 * 64 * 16; }
 
 }  // namespace ice
+
+ICE_PROF_EXPORT(ice_debug_prof_hier)

@@ -5,6 +5,18 @@
 
 #include "icecache.h"
 
+// time stamps for performance work: empty in the product build
+#ifdef ICE_PROF
+#include "ice_prof.h"
+#else
+#define ICE_STAMP(i) do { } while (0)
+#define ICE_USTAMP(i) do { } while (0)
+#define ICE_BSTAMP(i) do { } while (0)
+#define ICE_WSTAMP(t, i) do { } while (0)
+#define ICE_HSTAMP(i) do { } while (0)
+#define ICE_PROF_EXPORT(symbol)
+#endif
+
 namespace ice {
 
 constexpr int kD = 128;          // head_dim
@@ -56,11 +68,17 @@ struct Host {
     bool laid_out;   // dev pointers valid for (s, C)
     bool built;
     int n_tokens;    // per unit
+    int build_n;     // tokens per unit of the last ice_build_index (0: none, or the index was imported)
     int cur;         // live centroid buffer
     int geometry;    // 0: distances on the raw keys; 1: on the transformed keys (one more coordinate)
 };
 
 __host__ __device__ inline int round_up(int x, int m) { return (x + m - 1) / m * m; }
+
+// Raises a kernel's dynamic-LDS limit when a launch needs more than any launch before it (the
+// attribute is sticky: one runtime call per kernel instantiation and size class, not one per launch).
+// Defined in ice_api.hip.
+void allow_dynamic_lds(const void *kernel, size_t bytes);
 
 // ---- launchers (host functions defined in the kernel files) ----
 void launch_init_centroids(const Dev &d, const bf16_t *K, int n, const int *init_idx_or_null,
@@ -76,8 +94,13 @@ void launch_insert(const Dev &d, const bf16_t *k, const bf16_t *v, int m, int cu
 // scores + top-P selection (+ attention when out != nullptr) in one launch
 // np_hint: host-side upper bound of the live pages per unit (tokens / page_size + clusters)
 // res_k, res_v: n_res resident tokens per unit (bf16 [U][n_res][d]) attended on top of the pages; n_res may be 0
+// wait_cfg: bits 0..7 = log2 of the bounded wait for a missing score, bits 8.. = 1 + the chunk whose
+// score stores a test leaves out (0 in every product call)
+constexpr int kDecodeWaitDefault = 16;
 void launch_decode_step(const Dev &d, const bf16_t *q, int P, int np_hint, int *ids, int *n_sel, float *scores_out,
-                        const bf16_t *res_k, const bf16_t *res_v, int n_res, float *out, hipStream_t st);
+                        const bf16_t *res_k, const bf16_t *res_v, int n_res, float *out, hipStream_t st,
+                        int wait_cfg = kDecodeWaitDefault);
+int decode_step_chunks(const Dev &d, int np_hint);  // workgroups per unit of that launch
 // two-stage selection (clusters, then their pages) (+ attention when out != nullptr) in one launch
 void launch_decode_hier(const Dev &d, const bf16_t *q, int cur, int P, int n_probe, int n_refine, int np_hint, int *ids,
                         int *n_sel, float *scores_out, int *clusters_out, float *out, hipStream_t st);

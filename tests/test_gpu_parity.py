@@ -1021,6 +1021,82 @@ def test_insert_on_transformed_keys():
         assert np.array_equal(ea[name], eb[name]), name
 
 
+# ------------------------------------------------------------------------------------ failure path of the score hand-off
+def test_expired_score_handoff_is_reported_not_ranked():
+    """Few units: a unit's page scores cross from several workgroups to the last of them through device
+    memory, and that one waits for a missing score only a bounded number of re-reads.  The wait is made
+    to expire from the host (one workgroup's score stores left out, a 16-re-read limit; every wave still
+    runs to its end): the unit must come back as n_selected = -1 with ids -1 and a zero output, stay so
+    on later calls, and work again, equal to the oracle, after a rebuild."""
+    from paper_2604_10539_amd import IceError, binding as b
+    w = datagen.small(n_tokens=9000, n_clusters=100, n_kv_heads=2, n_components=40)
+    ix, K, V, _ = _mk(w, T=2)
+    ix.build_index(up(K), up(V))
+    q = datagen.queries(w)
+    ids_ok, ns_ok, out_ok = ix.select_attend(up(q), 256)
+    P = ids_ok.shape[-1]
+    ids = torch.full_like(ids_ok, 5)
+    ns = torch.full_like(ns_ok, 5)
+    out = torch.full_like(out_ok, 5.0)
+    b.ice_debug_select_fault(ix.handle, up(q), 256, ids, ns, out, 1, 4)
+    torch.cuda.synchronize()
+    assert torch.all(ns == -1) and torch.all(ids == -1) and torch.count_nonzero(out).item() == 0
+    # the unit stays marked: the plain calls say so as well, and attention over "-1 pages" is zero
+    ids2, ns2, out2 = ix.select_attend(up(q), 256)
+    ids3, ns3, _ = ix.select(up(q), 256)
+    torch.cuda.synchronize()
+    assert torch.all(ns2 == -1) and torch.all(ids2 == -1) and torch.count_nonzero(out2).item() == 0
+    assert torch.all(ns3 == -1) and torch.all(ids3 == -1)
+    assert torch.count_nonzero(ix.attend(up(q), ids2, ns2)).item() == 0
+    # argument errors of the hook
+    with pytest.raises(IceError) as e:
+        b.ice_debug_select_fault(ix.handle, up(q), 256, ids, ns, out, 99, 4)
+    assert e.value.status == b.ICE_ERR_SHAPE
+    with pytest.raises(IceError) as e:
+        b.ice_debug_select_fault(ix.handle, up(q), 256, ids, ns, out, 0, 21)
+    assert e.value.status == b.ICE_ERR_SHAPE
+    # a rebuild re-arms the unit
+    ix.build_index(up(K), up(V))
+    ids4, ns4, out4 = ix.select_attend(up(q), 256)
+    assert torch.equal(ids4, ids_ok) and torch.equal(ns4, ns_ok) and torch.equal(out4, out_ok)
+    o = oracle_from_export(ix, export_np(ix))
+    _compare_select(o, q, 256, down(ids4), down(ns4))
+    ref = o.attend(q, down(ids4).reshape(ix.U, P), down(ns4).reshape(ix.U))
+    assert np.abs(down(out4).reshape(ref.shape) - ref).max() <= ATTN_EXPECTED
+    # one workgroup per unit: nothing is handed over, the hook says so
+    w1 = datagen.small(n_tokens=700, n_clusters=16, n_kv_heads=2, n_components=8)
+    ix1, K1, V1, _ = _mk(w1, T=1)
+    ix1.build_index(up(K1), up(V1))
+    i1, n1, o1 = ix1.select_attend(up(datagen.queries(w1)), 64)
+    with pytest.raises(IceError) as e:
+        b.ice_debug_select_fault(ix1.handle, up(datagen.queries(w1)), 64, i1, n1, o1, 0, 4)
+    assert e.value.status == b.ICE_ERR_UNSUPPORTED
+
+
+def test_rerunning_a_build_stage_leaves_the_index_as_it_was():
+    """ice_debug_rerun_stage (what the benchmark times kernel by kernel) reproduces what the build wrote."""
+    from paper_2604_10539_amd import IceError, binding as b
+    for kw in (dict(n_tokens=6000, n_clusters=600, n_kv_heads=2, n_components=200), dict(n_tokens=3000, n_clusters=48, n_kv_heads=3)):
+        w = datagen.small(**kw)
+        ix, K, V, _ = _mk(w, T=3, extra=4)
+        Kd, Vd = up(K), up(V)
+        ix.build_index(Kd, Vd)
+        before = {k2: (v2.copy() if isinstance(v2, np.ndarray) else v2) for k2, v2 in export_np(ix).items()}
+        for stage in (b.ICE_STAGE_ASSIGN, b.ICE_STAGE_SORT, b.ICE_STAGE_MEANS, b.ICE_STAGE_PAGINATE, b.ICE_STAGE_ASSIGN):
+            b.ice_debug_rerun_stage(ix.handle, Kd, Vd, stage)
+        after = export_np(ix)
+        for name, a in before.items():
+            if isinstance(a, np.ndarray):
+                assert np.array_equal(a.view(np.uint8), after[name].view(np.uint8)), name
+        with pytest.raises(IceError) as e:
+            b.ice_debug_rerun_stage(ix.handle, Kd, Vd, 7)
+        assert e.value.status == b.ICE_ERR_INVALID_ARG
+        ix.insert(up(K[:, 0]), up(V[:, 0]))
+        with pytest.raises(IceError) as e:
+            b.ice_debug_rerun_stage(ix.handle, Kd, Vd, b.ICE_STAGE_MEANS)
+        assert e.value.status == b.ICE_ERR_STATE
+
+
 # ------------------------------------------------------------------------------------ HIP graphs
 @pytest.mark.parametrize("kw", [
     dict(n_tokens=3000, n_clusters=48, n_kv_heads=3, n_components=24),     # few units: several workgroups per unit

@@ -499,7 +499,7 @@ def test_bf16_rounding_is_nearest_even():
     assert np.array_equal(widen(narrow(y)), ref)
 
 
-# ----------------------------------------------------------------------------- hierarchical select (Sec. 4.3, Alg. 3)
+# ----------------------------------------------------------------------------- hierarchical select (Sec. 3.3, Alg. 4)
 def _hier_numpy(ix, q, budget, n_probe):
     """The staged definition written out with numpy and Python sorting (fp64 scores rounded to fp32)."""
     qf = widen(q).astype(np.float64)
