@@ -90,28 +90,43 @@ def _mixture_rows(rng, cen, n, sigma):
     return x
 
 
-def keys_values(w: Workload, seed: int | None = None, n_tokens: int | None = None):
+def _map_units(fn, w: Workload, workers: int):
+    """fn(b, h) for every (sequence, KV head); with workers > 1 on a thread pool (every unit draws from a
+    generator of its own, so the result does not depend on the schedule)."""
+    units = [(b, h) for b in range(w.batch) for h in range(w.n_kv_heads)]
+    if workers <= 1 or len(units) == 1:
+        for b, h in units:
+            fn(b, h)
+        return
+    from concurrent.futures import ThreadPoolExecutor
+    with ThreadPoolExecutor(max_workers=min(workers, len(units))) as ex:
+        list(ex.map(lambda bh: fn(*bh), units))
+
+
+def keys_values(w: Workload, seed: int | None = None, n_tokens: int | None = None, workers: int = 1):
     """Prefill keys and values as bf16 bits: two uint16 arrays [batch, n_kv_heads, n, D]."""
     seed = w.seed if seed is None else seed
     n = w.n_tokens if n_tokens is None else n_tokens
     cen = centres(w, seed)
     K = np.empty((w.batch, w.n_kv_heads, n, D), dtype=np.uint16)
     V = np.empty_like(K)
-    for b in range(w.batch):
-        for h in range(w.n_kv_heads):
-            rk = _rng(seed, b, h, 1)
-            x = _mixture_rows(rk, cen[b, h], n, w.sigma)
-            if w.outlier_frac > 0.0:
-                m = rk.random(n) < w.outlier_frac
-                x[m] = rk.uniform(-3.0, 3.0, size=(int(m.sum()), D)).astype(np.float32)
-            K[b, h] = f32_to_bf16_bits(x)
-            rv = _rng(seed, b, h, 2)
-            if w.value_kind == "mixture":
-                vc = rv.standard_normal((w.n_components, D), dtype=np.float32)
-                y = _mixture_rows(rv, vc, n, w.sigma)
-            else:
-                y = rv.standard_normal((n, D), dtype=np.float32)
-            V[b, h] = f32_to_bf16_bits(y)
+
+    def one(b, h):
+        rk = _rng(seed, b, h, 1)
+        x = _mixture_rows(rk, cen[b, h], n, w.sigma)
+        if w.outlier_frac > 0.0:
+            m = rk.random(n) < w.outlier_frac
+            x[m] = rk.uniform(-3.0, 3.0, size=(int(m.sum()), D)).astype(np.float32)
+        K[b, h] = f32_to_bf16_bits(x)
+        rv = _rng(seed, b, h, 2)
+        if w.value_kind == "mixture":
+            vc = rv.standard_normal((w.n_components, D), dtype=np.float32)
+            y = _mixture_rows(rv, vc, n, w.sigma)
+        else:
+            y = rv.standard_normal((n, D), dtype=np.float32)
+        V[b, h] = f32_to_bf16_bits(y)
+
+    _map_units(one, w, workers)
     return K, V
 
 
@@ -153,19 +168,61 @@ class DecodeStream:
         self.cen = centres(w, self.seed).copy()
         self.step = 0
 
+    def _unit_step(self, b, h, step, k_out, v_out, q_out):
+        """One step of one (sequence, KV head): drift, new key and value, the group's queries."""
+        w = self.w
+        r = _rng(self.seed, b, h, 5 + 16 * (step + 1))
+        self.cen[b, h] += np.float32(w.drift) * r.standard_normal(self.cen[b, h].shape, dtype=np.float32)
+        k_out[b, h] = f32_to_bf16_bits(_mixture_rows(r, self.cen[b, h], 1, w.sigma)[0])
+        v_out[b, h] = f32_to_bf16_bits(r.standard_normal(D, dtype=np.float32))
+        rq = _rng(self.seed, b, h, 3 + 16 * (step + 2))
+        q_out[b, h * w.group_size:(h + 1) * w.group_size] = f32_to_bf16_bits(_mixture_rows(rq, self.cen[b, h], w.group_size, w.sigma))
+
     def next(self):
         w = self.w
         k = np.empty((w.batch, w.n_kv_heads, D), dtype=np.uint16)
         v = np.empty_like(k)
+        q = np.empty((w.batch, w.n_kv_heads * w.group_size, D), dtype=np.uint16)
         for b in range(w.batch):
             for h in range(w.n_kv_heads):
-                r = _rng(self.seed, b, h, 5 + 16 * (self.step + 1))
-                self.cen[b, h] += np.float32(w.drift) * r.standard_normal(self.cen[b, h].shape, dtype=np.float32)
-                k[b, h] = f32_to_bf16_bits(_mixture_rows(r, self.cen[b, h], 1, w.sigma)[0])
-                v[b, h] = f32_to_bf16_bits(r.standard_normal(D, dtype=np.float32))
-        q = queries(w, self.seed, step=self.step + 1, cen=self.cen)
+                self._unit_step(b, h, self.step, k, v, q)
         self.step += 1
         return k, v, q
+
+    def take(self, m: int, workers: int = 1):
+        """The next m steps at once: k, v uint16 [m, batch, n_kv_heads, D], q uint16 [m, batch, H_q, D]; the
+        same values m calls of next() give.  Units are independent; with workers > 1 they are spread
+        over forked processes (call it before the process initialises a GPU)."""
+        w = self.w
+        k = np.empty((m, w.batch, w.n_kv_heads, D), dtype=np.uint16)
+        v = np.empty_like(k)
+        q = np.empty((m, w.batch, w.n_kv_heads * w.group_size, D), dtype=np.uint16)
+        units = [(b, h) for b in range(w.batch) for h in range(w.n_kv_heads)]
+        if workers > 1 and len(units) > 1:
+            import multiprocessing
+            with multiprocessing.get_context("fork").Pool(min(workers, len(units))) as pool:
+                parts = pool.map(_stream_unit, [(self, b, h, m) for b, h in units])
+        else:
+            parts = [_stream_unit((self, b, h, m)) for b, h in units]
+        G = w.group_size
+        for (b, h), (ku, vu, qu, cen) in zip(units, parts):
+            k[:, b, h], v[:, b, h], q[:, b, h * G:(h + 1) * G] = ku, vu, qu
+            self.cen[b, h] = cen
+        self.step += m
+        return k, v, q
+
+
+def _stream_unit(args):
+    """m steps of one (sequence, KV head) of a DecodeStream: (k [m, D], v [m, D], q [m, G, D], centres after)."""
+    st, b, h, m = args
+    w = st.w
+    k = np.empty((m, w.batch, w.n_kv_heads, D), dtype=np.uint16)
+    v = np.empty_like(k)
+    q = np.empty((m, w.batch, w.n_kv_heads * w.group_size, D), dtype=np.uint16)
+    for t in range(m):
+        st._unit_step(b, h, st.step + t, k[t], v[t], q[t])
+    G = w.group_size
+    return k[:, b, h].copy(), v[:, b, h].copy(), q[:, b, h * G:(h + 1) * G].copy(), st.cen[b, h]
 
 
 def small(name: str = "tiny", **kw) -> Workload:
