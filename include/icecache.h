@@ -155,7 +155,7 @@ ice_status_t ice_attend(ice_index_t *idx, const void *q, const int32_t *page_ids
  * HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments, same
  * result (to the rounding of a different split of the page list), but the partial sums of the page
  * list's shares do not go through the workspace: they live in a static device array of the library
- * (1 064 960 bytes per GPU the library runs on, held until the process ends), whose address is
+ * (1 065 984 bytes per GPU the library runs on, held until the process ends), whose address is
  * looked up once per device at the first call there.  The call itself allocates nothing and calls
  * no allocating routine.
  * Limit: at most 256 units (batch * n_kv_heads); UNSUPPORTED beyond.  Every call on one GPU shares

@@ -94,6 +94,7 @@ size_t lay_out(const ice_config_t &cfg, int s, int C, char *base, Dev *out) {
     d.page_base = (int *)take(U * (CP + 1) * 4);
     d.range_tot = (int *)take(std::max<size_t>(U, 256) * CP * 4);
     d.attn_part = (float *)take((size_t)256 * d.G * (kD + 2) * 4);
+    d.attn_arrive = (int *)take(U * 4);
     d.scores = (uint32_t *)take(U * MP * 4);
     d.counter = (int *)take(U * 4);
     if (out) *out = d;
@@ -128,6 +129,7 @@ __global__ void fill_i32_kernel(int *p, int n, int v) {
 void reset_decode_state(const Dev &d, int n_tokens, hipStream_t s) {
     hipLaunchKernelGGL(fill_i32_kernel, dim3((d.U + 255) / 256), dim3(256), 0, s, d.n_tokens, d.U, n_tokens);
     hipLaunchKernelGGL(fill_i32_kernel, dim3((d.U + 255) / 256), dim3(256), 0, s, d.counter, d.U, 0);
+    hipLaunchKernelGGL(fill_i32_kernel, dim3((d.U + 255) / 256), dim3(256), 0, s, d.attn_arrive, d.U, 0);
     const int ns = d.U * d.max_pages;
     hipLaunchKernelGGL(fill_i32_kernel, dim3((ns + 255) / 256), dim3(256), 0, s, (int *)d.scores, ns, -1);
 }

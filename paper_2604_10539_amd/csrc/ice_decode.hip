@@ -156,45 +156,95 @@ __global__ __launch_bounds__(NW * 64) void attend_kernel(const bf16_t *__restric
 
 // Few units and many pages per unit: one workgroup per unit would pull every tile through a single
 // CU.  The page list of a unit is cut into S shares instead, one workgroup each (grid S x U); every
-// workgroup leaves its partial result (attend_pages, PARTIAL) and a second, small launch merges the
-// shares of a unit: out = sum_s O_s e^(M_s - M) / sum_s L_s e^(M_s - M).
+// workgroup leaves its partial result (attend_pages, PARTIAL) as device-scope words and bumps the
+// unit's arrival counter once those stores have completed; the last one to arrive merges the shares:
+// out = sum_s O_s e^(M_s - M) / sum_s L_s e^(M_s - M).  `arrive` is zero between launches (the last
+// workgroup puts it back).
 template <int G, int NW>
 __global__ __launch_bounds__(NW * 64) void attend_split_kernel(const bf16_t *__restrict__ q, const int *__restrict__ ids,
                                                                 const int *__restrict__ n_sel, int P, Dev d,
-                                                                float *__restrict__ part) {
+                                                                float *__restrict__ part, int *__restrict__ arrive,
+                                                                float *__restrict__ out) {
     extern __shared__ __align__(16) char smem[];
-    const int s = blockIdx.x, S = gridDim.x, u = blockIdx.y;
+    __shared__ int sh_last;
+    const int s = blockIdx.x, S = gridDim.x, u = blockIdx.y, tid = threadIdx.x;
+    if (s == 0) ICE_STAMP(16);
     bf16x8 qa[4];
-    load_query_operand<G>(q, u, threadIdx.x & 63, qa, nullptr);
-    const int ns = max(0, min(n_sel[u], P)), per = (ns + S - 1) / S;
-    const int lo = min(ns, s * per), cnt = min(ns - lo, per);
+    load_query_operand<G>(q, u, tid & 63, qa, nullptr);
+    // shares are cut from the list's capacity P, not from the unit's count, so that every wave can ask
+    // for its first page id together with the count (one round trip less); entries past the count
+    // are dropped below
+    const int per = (P + S - 1) / S, lo = min(P, s * per), wave = tid >> 6;
     const int *list = ids + (size_t)u * P + lo;
-    attend_pages<G, NW, false, true>(d, u, qa, [=](int x) { return list[x]; }, cnt, Resident{nullptr, nullptr, 0, nullptr, nullptr, 0},
-                                     part + ((size_t)u * S + s) * G * (kD + 2), (float *)smem, [] {});
-}
-__global__ __launch_bounds__(1024) void attend_merge_kernel(const float *__restrict__ part, int S, int G, float *__restrict__ out) {
-    const int u = blockIdx.x, h = threadIdx.x >> 7, j = threadIdx.x & 127;  // G * 128 threads
-    const float *pu = part + ((size_t)u * S * G + h) * (kD + 2);
-    const size_t stride = (size_t)G * (kD + 2);
-    float M = -INFINITY;
-    for (int s = 0; s < S; ++s) M = fmaxf(M, pu[s * stride + kD]);
-    float num = 0.f, den = 0.f;
-    for (int s = 0; s < S; ++s) {
-        const float ms = pu[s * stride + kD];
-        const float w = ms == -INFINITY ? 0.f : __expf(ms - M);  // (a share without tokens: no weight)
-        num += pu[s * stride + j] * w;
-        den += pu[s * stride + kD + 1] * w;
+    const int first = lo + wave < P ? list[wave] : -1;
+    const int ns = max(0, min(n_sel[u], P));
+    const int cnt = max(0, min(ns - lo, per));
+    attend_pages<G, NW, false, true>(d, u, qa, [=](int x) { return x == wave ? first : list[x]; }, cnt,
+                                     Resident{nullptr, nullptr, 0, nullptr, nullptr, 0}, part + ((size_t)u * S + s) * G * (kD + 2),
+                                     (float *)smem, [] {});
+    if (s == 0) ICE_STAMP(17);
+    __syncthreads();  // every wave's partial stores have completed
+    if (s == 0) ICE_STAMP(18);
+    if (tid == 0) {
+        const int old = __hip_atomic_fetch_add(arrive + u, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        const int last = old == S - 1;
+        if (last) __hip_atomic_store(arrive + u, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);  // next launch
+        sh_last = last;
     }
-    out[((size_t)u * G + h) * kD + j] = den > 0.f ? num / den : 0.f;
+    __syncthreads();
+    if (!sh_last) return;
+    ICE_STAMP(19);
+    // The merge.  All partial results of the unit come to LDS in batches of independent loads (a
+    // batch costs one round trip; the launch reserves room for S shares), then every output element is
+    // combined from there.
+    const float *pu = part + (size_t)u * S * G * (kD + 2);
+    constexpr int NT = NW * 64, PW = G * (kD + 2);  // words of one share
+    float *lp = (float *)smem;                       // (the attention's scratch is free again)
+    const int words = S * PW;
+    for (int x0 = tid; x0 < words; x0 += 8 * NT) {
+        float v[8];
+#pragma unroll
+        for (int i = 0; i < 8; ++i)
+            v[i] = x0 + i * NT < words ? __hip_atomic_load(pu + x0 + i * NT, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) : 0.f;
+#pragma unroll
+        for (int i = 0; i < 8; ++i)
+            if (x0 + i * NT < words) lp[x0 + i * NT] = v[i];
+    }
+    __syncthreads();
+    ICE_STAMP(20);
+    for (int o = tid; o < G * kD; o += NT) {
+        const int h = o / kD, j = o % kD;
+        const float *ph = lp + h * (kD + 2);
+        float M = -INFINITY;
+        for (int sh = 0; sh < S; ++sh) M = fmaxf(M, ph[sh * PW + kD]);
+        float num = 0.f, den = 0.f;
+        for (int sh = 0; sh < S; ++sh) {
+            const float ms = ph[sh * PW + kD];
+            const float w = ms == -INFINITY ? 0.f : __expf(ms - M);  // (a share without tokens: no weight)
+            num += ph[sh * PW + j] * w;
+            den += ph[sh * PW + kD + 1] * w;
+        }
+        out[((size_t)u * G + h) * kD + j] = den > 0.f ? num / den : 0.f;
+    }
+    ICE_STAMP(21);
 }
+// LDS of a split launch: the attention's scratch, later the S shares' partial results side by side
+static size_t attend_split_lds(int G, int NW, int S) {
+    return sizeof(float) * std::max<size_t>(attend_scratch_floats(G, NW), (size_t)S * G * (kD + 2));
+}
+constexpr int kSplitMaxLdsBytes = 128 * 1024;
 // shares per unit of the split attention: as many workgroups as the chip has CUs, at least one page
-// per wave; below `min_shares` the merge launch costs more than the shares save (measured: 4 when
-// the attention is a call of its own, 8 when it follows the selection of the same call, which
-// otherwise attends in its own launch)
+// per wave; below `min_shares` the exchange of the partial results costs more than the shares save
+constexpr int kPagesPerShare = 4;
+constexpr int kFusedSplitMinShares = 4;  // when the attention follows the selection of the same call (it then takes a launch of its own)
 int attend_shares(const Dev &d, int P, int min_shares) {
     const int NW = d.G == 8 ? 8 : 16;
-    const int S = std::min(256 / std::max(d.U, 1), (P + NW - 1) / NW);
-    return S >= min_shares ? S : 1;
+    // (a CU draws ~30 GB/s from cold HBM however many waves ask: what shortens the attention is the
+    // number of CUs, so a share is kPagesPerShare pages even though a workgroup has a wave per page;
+    // fewer than min_shares workgroups' worth of pages, counted NW to a workgroup, are not split)
+    if ((P + NW - 1) / NW < min_shares) return 1;
+    const int fit = kSplitMaxLdsBytes / (int)(sizeof(float) * d.G * (kD + 2));  // shares whose results fit the merging workgroup's LDS
+    return std::max(1, std::min({256 / std::max(d.U, 1), (P + kPagesPerShare - 1) / kPagesPerShare, fit}));
 }
 
 // the token positions of the listed pages, in list and slot order, padded with -1
@@ -238,8 +288,11 @@ void launch_attend(const Dev &d, const bf16_t *q, const int *ids, const int *n_s
     const int S = ids && n_res == 0 && !res.pos ? attend_shares(d, P, min_shares) : 1;
     if (S > 1) {
 #define ICE_ATTEND_SPLIT(g, nw)                                                                                            \
-    hipLaunchKernelGGL((attend_split_kernel<g, nw>), dim3(S, d.U), dim3(nw * 64), sizeof(float) * attend_scratch_floats(g, nw), \
-                       st, q, ids, n_sel, P, d, d.attn_part)
+    do {                                                                                                                   \
+        allow_dynamic_lds((const void *)attend_split_kernel<g, nw>, attend_split_lds(g, nw, S));                           \
+        hipLaunchKernelGGL((attend_split_kernel<g, nw>), dim3(S, d.U), dim3(nw * 64), attend_split_lds(g, nw, S), st, q, ids, \
+                           n_sel, P, d, d.attn_part, d.attn_arrive, out);                                                  \
+    } while (0)
         switch (d.G) {
             case 1: ICE_ATTEND_SPLIT(1, 16); break;
             case 2: ICE_ATTEND_SPLIT(2, 16); break;
@@ -247,7 +300,6 @@ void launch_attend(const Dev &d, const bf16_t *q, const int *ids, const int *n_s
             default: ICE_ATTEND_SPLIT(8, 8); break;
         }
 #undef ICE_ATTEND_SPLIT
-        hipLaunchKernelGGL(attend_merge_kernel, dim3(d.U), dim3(d.G * 128), 0, st, d.attn_part, S, d.G, out);
         return;
     }
 #define ICE_ATTEND(g, nw)                                                                                                  \
@@ -273,10 +325,13 @@ void launch_attend(const Dev &d, const bf16_t *q, const int *ids, const int *n_s
 // harnesses that forbid hipMalloc) and hold no workspace region to lend: the split attention above
 // with its partial results in a device array of the library itself.  Every call on a GPU shares
 // that GPU's array: calls that overlap on one GPU (two streams, two host threads) race on it.
-// Nothing in it has to start at zero: every share writes its whole block before the merge reads it.
+// The partial results need no initial value (every share writes its whole block before the merge
+// reads it); the arrival counters behind them start at zero (a static array does) and every launch
+// puts them back to zero.
 constexpr int kStaticPairs = 256;  // (unit, share) pairs the array holds, each 8 heads x 130 floats
+constexpr int kStaticPartFloats = kStaticPairs * 8 * (kD + 2);
 }  // namespace ice
-static __device__ __align__(256) float scratch[ice::kStaticPairs * 8 * (ice::kD + 2)];
+static __device__ __align__(256) float scratch[ice::kStaticPartFloats + ice::kStaticPairs];  // partial results, then one counter per unit
 namespace ice {
 
 int attend_static_max_units() { return kStaticPairs; }
@@ -304,17 +359,21 @@ static float *scratch_on_current_device(hipError_t *err) {
     return ptr[dev];
 }
 
-// always the two-launch form (shares, then merge), also with one share per unit; d.U <= kStaticPairs
+// always the split form (shares, the last one to finish merges), also with one share per unit; d.U <= kStaticPairs
 hipError_t launch_attend_static(const Dev &d, const bf16_t *q, const int *ids, const int *n_sel, int P, float *out,
                                 hipStream_t st) {
     hipError_t err = hipSuccess;
     float *part = scratch_on_current_device(&err);
     if (!part) return err;
     const int NW = d.G == 8 ? 8 : 16;
-    const int S = std::max(1, std::min(kStaticPairs / d.U, (P + NW - 1) / NW));
+    const int fit = kSplitMaxLdsBytes / (int)(sizeof(float) * d.G * (kD + 2));
+    const int S = std::max(1, std::min({kStaticPairs / d.U, (P + kPagesPerShare - 1) / kPagesPerShare, fit}));
 #define ICE_ATTEND_SPLIT(g, nw)                                                                                            \
-    hipLaunchKernelGGL((attend_split_kernel<g, nw>), dim3(S, d.U), dim3(nw * 64), sizeof(float) * attend_scratch_floats(g, nw), \
-                       st, q, ids, n_sel, P, d, part)
+    do {                                                                                                                   \
+        allow_dynamic_lds((const void *)attend_split_kernel<g, nw>, attend_split_lds(g, nw, S));                           \
+        hipLaunchKernelGGL((attend_split_kernel<g, nw>), dim3(S, d.U), dim3(nw * 64), attend_split_lds(g, nw, S), st, q, ids, \
+                           n_sel, P, d, part, (int *)(part + kStaticPartFloats), out);                                     \
+    } while (0)
     switch (d.G) {
         case 1: ICE_ATTEND_SPLIT(1, 16); break;
         case 2: ICE_ATTEND_SPLIT(2, 16); break;
@@ -322,7 +381,6 @@ hipError_t launch_attend_static(const Dev &d, const bf16_t *q, const int *ids, c
         default: ICE_ATTEND_SPLIT(8, 8); break;
     }
 #undef ICE_ATTEND_SPLIT
-    hipLaunchKernelGGL(attend_merge_kernel, dim3(d.U), dim3(d.G * 128), 0, st, part, S, d.G, out);
     return hipSuccess;
 }
 
@@ -364,6 +422,7 @@ __global__ __launch_bounds__(NW * 64) void decode_step_kernel(int U, int max_pag
     __shared__ int sh_last, sh_M, sh_M2, sh_W, sh_fail;
     __shared__ uint32_t sh_pre;
     __shared__ uint32_t sh_rowmax[4 * NW];
+    __shared__ uint32_t sh_quadmax[16 * NW];
     __shared__ u64 sh_tau;
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
     const int g = lane >> 4, ch = lane & 15;
@@ -489,16 +548,28 @@ __global__ __launch_bounds__(NW * 64) void decode_step_kernel(int U, int max_pag
     if (single) lds_barrier();
     else __syncthreads();
     if (chunk == 0) ICE_STAMP(15);
+    // The score words a thread would rank are requested by EVERY workgroup right behind its counter
+    // update, before it knows whether it is the last one: the last one then has them (or, for slots
+    // whose writer's store had not landed yet, the empty mark, which finish_score re-reads) one round
+    // trip earlier; the others drop them.  A slot is only ever re-armed by the last workgroup.
+    uint32_t key[EMAX];
+    const bool rank_some = P < np;  // (else every page is returned and nothing is ranked)
     if (!single) {
+        int old = 0;
+        if (tid == 0) old = __hip_atomic_fetch_add(d.counter + u, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        if (rank_some) {
+#pragma unroll
+            for (int e = 0; e < EMAX; ++e)
+                key[e] = __hip_atomic_load(S + min(e * NT + tid, np - 1), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        }
         if (tid == 0) {
-            const int old = __hip_atomic_fetch_add(d.counter + u, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
             // 1: the last to arrive carries on; 2: the unit was marked failed by an earlier launch (its
             // counter is negative until the index is rebuilt or imported again): chunk 0 says so again
             int role = old < 0 ? (chunk == 0 ? 2 : 0) : (old == chunks - 1 ? 1 : 0);
             if (role == 1) __hip_atomic_store(d.counter + u, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);  // next launch
             sh_last = role;
         }
-        __syncthreads();
+        lds_barrier();  // (the score words stay in flight across it)
         if (!sh_last) return;
     }
     // A score hand-off that did not complete (a slot still empty after the bounded wait) is never
@@ -569,14 +640,10 @@ __global__ __launch_bounds__(NW * 64) void decode_step_kernel(int U, int max_pag
             if (sco) sco[x] = __uint_as_float(v);
         }
     } else {
-        uint32_t key[EMAX];
         if (single) {
 #pragma unroll
             for (int e = 0; e < EMAX; ++e) key[e] = sc_lds[min(e * NT + tid, np - 1)];
         } else {
-#pragma unroll
-            for (int e = 0; e < EMAX; ++e)
-                key[e] = __hip_atomic_load(S + min(e * NT + tid, np - 1), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 #pragma unroll
             for (int e = 0; e < EMAX; ++e)
                 if (e * NT + tid < np) key[e] = finish_score(e * NT + tid, key[e]);
@@ -595,11 +662,40 @@ __global__ __launch_bounds__(NW * 64) void decode_step_kernel(int U, int max_pag
             key[e] = valid ? f32_ordered(__uint_as_float(key[e])) : 0u;
         }
         ICE_STAMP(2);
-        constexpr int NR = 4 * NW;  // 16-lane rows in the workgroup
-        // (with up to 4 keys per thread the histograms are cheaper than ranking the longer list the row
-        // maxima leave from k = NR / 2 on; with 16 keys per thread only above NR)
-        const bool by_prefix = k > (EMAX <= 4 ? NR / 2 : NR);
-        if (!by_prefix) {
+        constexpr int NR = 4 * NW;   // 16-lane rows in the workgroup
+        constexpr int NO = 8 * NW;   // 8-lane groups
+        constexpr int NQ = 16 * NW;  // 4-lane groups
+        // The k-th largest of N disjoint groups' maxima is a threshold that k keys reach; it lets through
+        // few more than k keys while k is at most N / 2: the NR rows up to k = NR / 2, then the NO
+        // eight-lane groups, then the NQ four-lane groups; beyond k = NQ / 2 the prefix histograms.
+        const bool by_groups = k > NR / 2 && k <= NQ / 2;
+        const bool by_prefix = k > NQ / 2;
+        if (by_groups) {
+            // B1, medium budgets: group maxima of the key registers, made distinct by the group's number
+            // in their low byte (the threshold need not be a key: any value that k keys reach will do),
+            // so that ranking a maximum among the N is one comparison per pair; the lanes of a group
+            // share its N comparisons.
+            const bool quads = k > NO / 2;  // (workgroup-uniform)
+            const int lg = quads ? 2 : 3, NGr = NT >> lg, gs = 1 << lg;
+            uint32_t lmax = key[0];
+#pragma unroll
+            for (int e = 1; e < EMAX; ++e) lmax = max(lmax, key[e]);
+            lmax = max(lmax, dpp_u32<0xB1>(lmax));  // quad_perm [1,0,3,2]
+            lmax = max(lmax, dpp_u32<0x4E>(lmax));  // quad_perm [2,3,0,1]
+            if (!quads) lmax = max(lmax, dpp_u32<0x141>(lmax));  // row_half_mirror: 8 lanes
+            const int i = tid >> lg, part = tid & (gs - 1);
+            if (part == 0) sh_quadmax[i] = (lmax & 0xFFFFFF00u) | (uint32_t)(255 - i);
+            lds_barrier();
+            const uint32_t v = sh_quadmax[i];
+            const int len = NGr >> lg;  // comparisons per lane
+            uint32_t c = 0;
+#pragma unroll 8
+            for (int jj = 0; jj < len; ++jj) c += sh_quadmax[part * len + jj] > v ? 1u : 0u;
+            c += dpp_u32<0xB1>(c);
+            c += dpp_u32<0x4E>(c);
+            if (!quads) c += dpp_u32<0x141>(c);
+            if (part == 0 && (int)c == k - 1) sh_pre = v & 0xFFFFFF00u;
+        } else if (!by_prefix) {
             // B1, small budgets: the k-th largest of the 4*NW group maxima (groups without keys count as the
             // smallest key).  With several workgroups per unit the groups are the 16-lane rows of
             // the key registers; with one they were formed while scoring.
@@ -733,7 +829,7 @@ __global__ __launch_bounds__(NW * 64) void decode_step_kernel(int U, int max_pag
         const int M = sh_M;  // >= need
         ICE_STAMP(4);
         // B3: the `need` best of the M candidates, exactly, into sel_comp[first..k)
-        if (M <= 256) {
+        if (M <= 512) {
             // every candidate counts the candidates that beat it; `parts` lanes share one candidate
             int lp = 0;
             while (lp < 6 && (M << (lp + 1)) <= NT) ++lp;
@@ -859,7 +955,7 @@ void launch_decode_step(const Dev &d, const bf16_t *q, int P, int np_hint, int *
     const int chunks = decode_step_chunks(d, np_hint);
     // few units and a large budget: select in this launch, attend with the unit's pages spread over
     // several workgroups (two more launches, see attend_split_kernel)
-    const bool split_attend = out && chunks > 1 && n_res == 0 && attend_shares(d, P, 8) > 1;
+    const bool split_attend = out && chunks > 1 && n_res == 0 && attend_shares(d, P, kFusedSplitMinShares) > 1;
     float *out_fused = split_attend ? nullptr : out;
     const size_t lds = decode_step_lds_bytes(d, P);
     const int grid = round_up(d.U, 8) * chunks;
@@ -882,7 +978,7 @@ void launch_decode_step(const Dev &d, const bf16_t *q, int P, int np_hint, int *
     else { if (E <= 4) ICE_STEP(1, 16, 4); else ICE_STEP(1, 16, 16); }
 #undef ICE_STEP
 #undef ICE_STEP_R
-    if (split_attend) launch_attend(d, q, ids, n_sel, P, Resident{nullptr, nullptr, 0, nullptr, nullptr, 0}, out, st, 8);
+    if (split_attend) launch_attend(d, q, ids, n_sel, P, Resident{nullptr, nullptr, 0, nullptr, nullptr, 0}, out, st, kFusedSplitMinShares);
 }
 
 // largest page count and page budget launch_decode_step can serve (register-resident keys, LDS lists)

@@ -319,11 +319,11 @@ __device__ inline void attend_pages(const Dev &d, int u, const bf16x8 (&qa)[4], 
         M = fmaxf(M, dpp_f32<0x140>(M));
         const float e = M == -INFINITY ? 0.f : __expf(mw - M);
         const float L = row16_sum(lw * e);
-        if constexpr (PARTIAL) {
+        if constexpr (PARTIAL) {  // (device-scope words: another workgroup merges them)
             if (w < NW) wm[w][h] = e;
             if (w == 0) {
-                out[h * (kD + 2) + kD] = M;
-                out[h * (kD + 2) + kD + 1] = L;
+                __hip_atomic_store(out + h * (kD + 2) + kD, M, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                __hip_atomic_store(out + h * (kD + 2) + kD + 1, L, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
             }
         } else {
             if (w < NW) wm[w][h] = L > 0.f ? e / L : 0.f;
@@ -335,7 +335,7 @@ __device__ inline void attend_pages(const Dev &d, int u, const bf16x8 (&qa)[4], 
         float O = 0.f;
 #pragma unroll
         for (int w = 0; w < NW; ++w) O += wacc[w][h][j] * wm[w][h];
-        if constexpr (PARTIAL) out[h * (kD + 2) + j] = O;
+        if constexpr (PARTIAL) __hip_atomic_store(out + h * (kD + 2) + j, O, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         else out[((size_t)u * G + h) * kD + j] = O;
     }
 }

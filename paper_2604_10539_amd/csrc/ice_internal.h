@@ -54,6 +54,7 @@ struct Dev {
     int *cluster_start;         // [U][Cpad+1] exclusive scan of counts
     int *page_base;             // [U][Cpad+1] exclusive scan of pages per cluster
     float *attn_part;           // [256][G][130] partial results of the split attention (shares x units <= 256)
+    int *attn_arrive;           // [U] arrival counters of its shares (zero between launches)
     int *range_tot;             // [U][R][Cpad] members per cluster in each of the sort's R token ranges (R = max(1, 256 / U) at most)
     // decode scratch
     uint32_t *scores;           // [U][max_pages] fp32 bits of the page scores; 0xFFFFFFFF = empty slot
