@@ -578,9 +578,10 @@ def main():
     v1 = torch.from_numpy(np.tile(vv.view(np.int16), (L, 1, 1))).to(dev)
     batched.insert(k1, v1)
     us_insert = clock.once(lambda: batched.insert(k1, v1), 32) * 1e3
-    # a page of tokens at a time (tokens leaving the recent window): 16 per launch
-    k16 = k1[:, :, None, :].expand(L, H, 16, D).contiguous()
-    v16 = v1[:, :, None, :].expand(L, H, 16, D).contiguous()
+    # a page of tokens at a time (tokens leaving the recent window): 16 different tokens per launch
+    k16_np, v16_np, _ = stream_in.take(16)                                    # [16, 1, H, D]
+    k16 = torch.from_numpy(np.tile(k16_np.view(np.int16).transpose(1, 2, 0, 3), (L, 1, 1, 1))).contiguous().to(dev)   # [L, H, 16, D]
+    v16 = torch.from_numpy(np.tile(v16_np.view(np.int16).transpose(1, 2, 0, 3), (L, 1, 1, 1))).contiguous().to(dev)
     batched.insert_batch(k16, v16)
     us_insert16 = clock.once(lambda: batched.insert_batch(k16, v16), 2) * 1e3
 

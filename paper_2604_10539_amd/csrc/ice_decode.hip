@@ -16,19 +16,29 @@ constexpr int kUnitFailed = -(1 << 30);        // arrival counter of a unit whos
 // ------------------------------------------------------------------------------------------------
 // Insertion of m tokens per unit, one after the other (Alg. 1 insertion loop; a node that outgrows
 // its page gets a new one, Sec. 4.1; m > 1 is the page-at-a-time insertion of tokens that leave the
-// recent window).  One workgroup per unit.  Per token: its 16 waves scan the bf16 centroids
-// (16 lanes x 16 bytes per row, four rows per wave and load, four loads in flight) for the nearest
-// one, lowest id on ties; wave 0 then appends the key/value row to the cluster's tail page and
-// updates, in ordered fp32 (one add per quantity): page sum -> representative, cluster sum ->
-// centroid, its bf16 rounding and squared norm.  The next token sees the moved centroid, exactly
-// as m separate launches would.  k, v: bf16 [U, m, d].
+// recent window).  One workgroup per unit.  Per token: 15 waves scan the bf16 centroids (16 lanes x
+// 16 bytes per row, four rows per wave and load, four loads in flight) for the nearest one, lowest
+// id on ties; wave 0 then appends the key/value row to the cluster's tail page and updates, in
+// ordered fp32 (one add per quantity): page sum -> representative, cluster sum -> centroid, its bf16
+// rounding and squared norm.  The next token sees the moved centroid, exactly as m separate
+// launches would; yet its scan does not wait for the update: only ONE centroid row changes, so
+// while wave 0 appends token t the other waves scan for token t+1 over every row but that one, and
+// wave 0 adds the moved row's distance (same 16-lane arithmetic, from the row it has just formed)
+// before the barrier that ends the step.  k, v: bf16 [U, m, d].
 constexpr int kInsertWaves = 16;
 // (cent, cnorm: the live centroid buffer d.cent_bf16[cur] / d.cnorm[cur], which this kernel also
 // writes, hence neither const nor restrict)
+// RESIDENT (several tokens and the unit's centroids fit): the bf16 centroid rows, their norms and
+// extra coordinates are copied to LDS once and scanned from there, the moved row patched in place:
+// a token's scan then costs LDS time instead of another 256 C bytes through the CU.
+template <bool RESIDENT>
 __global__ __launch_bounds__(kInsertWaves * 64) void insert_kernel(const bf16_t *__restrict__ k, const bf16_t *__restrict__ v,
                                                                     bf16_t *cent, float *cnorm,
                                                                     int m, int cur, int C, int Cpad, Dev d) {  // (scalars first: preloaded)
-    __shared__ u64 best;
+    extern __shared__ __align__(16) char insert_lds[];  // RESIDENT: [C][128] bf16 rows, [C] fp32 norms, [C] fp32 extra coordinates
+    __shared__ u64 best[3];  // token t's winner meets in best[t % 3]: (ordered distance, cluster id), minimum
+    __shared__ __align__(16) uint32_t moved_row[64];  // the centroid row wave 0 has just moved (bf16 pairs)
+    __shared__ float moved_norm, moved_aug;
     const int u = blockIdx.x, tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
     const int g = lane >> 4, ch = lane & 15;
     // what the append needs and does not depend on the chosen cluster is requested before the scan
@@ -36,65 +46,99 @@ __global__ __launch_bounds__(kInsertWaves * 64) void insert_kernel(const bf16_t 
     int tok = d.n_tokens[u];
     const bf16_t *cb = cent + (size_t)u * Cpad * kD;
     const float *wn = cnorm + (size_t)u * Cpad;
-    constexpr int RS = kInsertWaves * 4;  // rows per pass of the workgroup
-    for (int t = 0; t < m; ++t) {
-        const bf16_t *kt = k + ((size_t)u * m + t) * kD, *vt = v + ((size_t)u * m + t) * kD;
-        if (tid == 0) best = ~0ull;
-        __syncthreads();  // also: the previous token's updates are visible to every wave
-        const uint4 kq = ((const uint4 *)kt)[ch];
-        const uint32_t kw = ((const uint32_t *)kt)[lane];
-        const uint32_t vw = ((const uint32_t *)vt)[lane];
-        // transformed keys (Eq. 2): the new key's extra coordinate joins every comparison
-        bf16_t ka = 0;
-        float kaf = 0.f;
-        if (d.tk) {
-            ka = key_extra_coordinate(d.c2[u], key_sqnorm16(kq));
-            kaf = bf16_to_f32(ka);
+    uint4 *lrow = (uint4 *)insert_lds;
+    float *lnorm = (float *)(insert_lds + (size_t)C * kD * 2), *laug = lnorm + C;
+    if constexpr (RESIDENT) {
+        for (int x = tid; x < C * 16; x += kInsertWaves * 64) lrow[x] = ((const uint4 *)cb)[x];
+        for (int r = tid; r < C; r += kInsertWaves * 64) {
+            lnorm[r] = wn[r];
+            laug[r] = d.tk ? bf16_to_f32(d.caug[cur][(size_t)u * Cpad + r]) : 0.f;
         }
+    }
+    const bf16_t *ku = k + (size_t)u * m * kD, *vu = v + (size_t)u * m * kD;
+    const float c2 = d.tk ? d.c2[u] : 0.f;
+    constexpr int RS = (kInsertWaves - 1) * 4;  // rows per pass of the scanning waves
+    // transformed keys (Eq. 2): the new key's extra coordinate joins every comparison
+    auto extra_of = [&](const uint4 &kq) -> bf16_t { return d.tk ? key_extra_coordinate(c2, key_sqnorm16(kq)) : (bf16_t)0; };
+    // objective of one centroid row for a key: ||mu~||^2 - 2 k . mu~ (extra coordinate included)
+    auto objective = [&](const uint4 &row, float w, float ce, const uint4 &kq, float kaf) {
+        const float dot = row16_sum(dot8(row, kq)) + kaf * ce;
+        return w - 2.0f * dot;
+    };
+    // waves 1..15: nearest row for token t among all rows but `skip`, into best[t % 3]
+    auto scan = [&](int t, int skip) {
+        const uint4 kq = ((const uint4 *)(ku + (size_t)t * kD))[ch];
+        const float kaf = bf16_to_f32(extra_of(kq));
         float bv = INFINITY;
         int bi = 0x7FFFFFFF;
-        for (int r0 = wave * 4 + g; r0 < C; r0 += 4 * RS) {
+        for (int r0 = (wave - 1) * 4 + g; r0 < C; r0 += 4 * RS) {
             uint4 row[4];
             float w[4], ce[4];
 #pragma unroll
             for (int x = 0; x < 4; ++x) {
                 const int r = r0 + x * RS;
-                row[x] = r < C ? ((const uint4 *)(cb + (size_t)r * kD))[ch] : make_uint4(0, 0, 0, 0);
-                w[x] = r < C ? wn[r] : INFINITY;
-                ce[x] = d.tk && r < C ? bf16_to_f32(d.caug[cur][(size_t)u * Cpad + r]) : 0.f;
+                if constexpr (RESIDENT) {
+                    row[x] = r < C ? lrow[r * 16 + ch] : make_uint4(0, 0, 0, 0);
+                    w[x] = r < C ? lnorm[r] : INFINITY;
+                    ce[x] = r < C ? laug[r] : 0.f;
+                } else {
+                    row[x] = r < C ? ((const uint4 *)(cb + (size_t)r * kD))[ch] : make_uint4(0, 0, 0, 0);
+                    w[x] = r < C ? wn[r] : INFINITY;
+                    ce[x] = d.tk && r < C ? bf16_to_f32(d.caug[cur][(size_t)u * Cpad + r]) : 0.f;
+                }
             }
 #pragma unroll
             for (int x = 0; x < 4; ++x) {  // ascending r: a later row wins only when strictly smaller
-                const float dot = row16_sum(dot8(row[x], kq)) + kaf * ce[x];
-                const float val = w[x] - 2.0f * dot;
-                if (val < bv) { bv = val; bi = r0 + x * RS; }
+                const float val = objective(row[x], w[x], ce[x], kq, kaf);
+                if (val < bv && r0 + x * RS != skip) { bv = val; bi = r0 + x * RS; }
             }
         }
-        if (ch == 0 && bi != 0x7FFFFFFF) atomicMin(&best, ((u64)f32_ordered(bv) << 32) | (u64)(uint32_t)bi);
-        __syncthreads();
-        if (wave == 0) {
-            // (no lane wins when every distance is NaN, i.e. a key with Inf / NaN coordinates: cluster 0 then,
-            // the choice of an exhaustive search that never sees a smaller value)
-            const int c = best == ~0ull ? 0 : (int)(uint32_t)best;
+        if (ch == 0 && bi != 0x7FFFFFFF) atomicMin(&best[t % 3], ((u64)f32_ordered(bv) << 32) | (u64)(uint32_t)bi);
+    };
+    if (tid < 3) best[tid] = ~0ull;
+    __syncthreads();
+    if (wave > 0) scan(0, -1);
+    __syncthreads();
+    for (int t = 0; t < m; ++t) {
+        // (no lane wins when every distance is NaN, i.e. a key with Inf / NaN coordinates: cluster 0 then,
+        // the choice of an exhaustive search that never sees a smaller value)
+        const u64 won = best[t % 3];
+        const int c = won == ~0ull ? 0 : (int)(uint32_t)won;
+        if (wave > 0) {
+            if (t + 1 < m) scan(t + 1, c);
+        } else {
+            if (lane == 0) best[(t + 2) % 3] = ~0ull;  // (token t-1's slot, read for the last time before the previous barrier)
+            const uint32_t kw = ((const uint32_t *)(ku + (size_t)t * kD))[lane];
+            const uint32_t vw = ((const uint32_t *)(vu + (size_t)t * kD))[lane];
+            const uint4 kq_now = ((const uint4 *)(ku + (size_t)t * kD))[ch];
+            const int tn = min(t + 1, m - 1);
+            const uint4 kq_next = ((const uint4 *)(ku + (size_t)tn * kD))[ch];
+            const bf16_t ka = extra_of(kq_now);
+            const float kaf = bf16_to_f32(ka);
             const size_t cl = (size_t)u * d.C + c;
+            // two dependent round trips: what hangs on the cluster, then what hangs on its tail page
+            // (fill and page sum together; the sum is dropped when a new page is opened)
             int tail = d.cluster_tail[cl];
-            int fill = tail >= 0 ? d.page_fill[(size_t)u * d.max_pages + tail] : d.s;
             const int cnt = d.cluster_cnt[cl] + 1;
+            float2 cs = ((const float2 *)(d.cluster_sum + cl * kD))[lane];
+            const float es_old = d.tk ? d.csum_aug[cl] : 0.f;
+            const size_t pg_old = (size_t)u * d.max_pages + max(tail, 0);
+            int fill = d.page_fill[pg_old];
+            float2 ps = ((const float2 *)(d.page_sum + pg_old * kD))[lane];
+            if (tail < 0) fill = d.s;
             const bool fresh = fill == d.s;
-            if (fresh) { tail = np; fill = 0; }
+            if (fresh) { tail = np; fill = 0; ps = make_float2(0.f, 0.f); }
             const size_t pg = (size_t)u * d.max_pages + tail;
             const int slot = fill;
             fill += 1;
             ((uint32_t *)(d.Kp + (pg * d.s + slot) * kD))[lane] = kw;
             ((uint32_t *)(d.Vp + (pg * d.s + slot) * kD))[lane] = vw;
             const float k0 = bf16_lo(kw), k1 = bf16_hi(kw);
-            float2 ps = fresh ? make_float2(0.f, 0.f) : ((const float2 *)(d.page_sum + pg * kD))[lane];
             ps.x = ps.x + k0;
             ps.y = ps.y + k1;
             ((float2 *)(d.page_sum + pg * kD))[lane] = ps;
             const float ff = (float)fill;
             ((uint32_t *)(d.rep + pg * kD))[lane] = (uint32_t)f32_to_bf16(ps.x / ff) | ((uint32_t)f32_to_bf16(ps.y / ff) << 16);
-            float2 cs = ((const float2 *)(d.cluster_sum + cl * kD))[lane];
             cs.x = cs.x + k0;
             cs.y = cs.y + k1;
             ((float2 *)(d.cluster_sum + cl * kD))[lane] = cs;
@@ -102,14 +146,16 @@ __global__ __launch_bounds__(kInsertWaves * 64) void insert_kernel(const bf16_t 
             const float2 mu = make_float2(cs.x / fc, cs.y / fc);
             ((float2 *)(d.centroid + cl * kD))[lane] = mu;
             const bf16_t b0 = f32_to_bf16(mu.x), b1 = f32_to_bf16(mu.y);
-            ((uint32_t *)(cent + ((size_t)u * Cpad + c) * kD))[lane] = (uint32_t)b0 | ((uint32_t)b1 << 16);
+            const uint32_t packed = (uint32_t)b0 | ((uint32_t)b1 << 16);
+            ((uint32_t *)(cent + ((size_t)u * Cpad + c) * kD))[lane] = packed;
             const float f0 = bf16_to_f32(b0), f1 = bf16_to_f32(b1);
             float nn = wave_sum(f0 * f0 + f1 * f1);
+            float ef = 0.f;
             if (d.tk) {  // the cluster's extra coordinate follows its members' running mean as well
-                const float es = d.csum_aug[cl] + kaf;
+                const float es = es_old + kaf;
                 const float e = es / fc;
                 const bf16_t eb = f32_to_bf16(e);
-                const float ef = bf16_to_f32(eb);
+                ef = bf16_to_f32(eb);
                 nn += ef * ef;
                 if (lane == 0) {
                     d.csum_aug[cl] = es;
@@ -131,13 +177,40 @@ __global__ __launch_bounds__(kInsertWaves * 64) void insert_kernel(const bf16_t 
                 }
             }
             if (fresh) np += 1;
+            if (t + 1 < m) {
+                // the moved row's distance to the next token, from the bits just stored (every 16-lane
+                // row of the wave computes it, the way a scanning wave would)
+                moved_row[lane] = packed;
+                if (lane == 0) { moved_norm = nn; moved_aug = ef; }
+                __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+                const uint4 row = ((const uint4 *)moved_row)[ch];
+                const float val = objective(row, moved_norm, moved_aug, kq_next, bf16_to_f32(extra_of(kq_next)));
+                if (lane == 0 && !(val != val)) atomicMin(&best[(t + 1) % 3], ((u64)f32_ordered(val) << 32) | (u64)(uint32_t)c);
+                if constexpr (RESIDENT) {  // (the scanning waves skip this row in this step: they may see it half written)
+                    ((uint32_t *)(lrow + c * 16))[lane] = packed;
+                    if (lane == 0) { lnorm[c] = nn; laug[c] = ef; }
+                }
+            }
         }
         tok += 1;
+        // Token t+1's winner is complete.  Token t's updates must be visible to whoever reads them next:
+        // with the centroids in LDS that is wave 0 alone (a wave's loads follow its own earlier stores
+        // to the same address), so the stores may stay in flight; otherwise every wave re-reads the
+        // moved row from memory and the barrier waits for the stores as well.
+        if constexpr (RESIDENT) lds_barrier();
+        else __syncthreads();
     }
 }
 
 void launch_insert(const Dev &d, const bf16_t *k, const bf16_t *v, int m, int cur, hipStream_t st) {
-    hipLaunchKernelGGL(insert_kernel, dim3(d.U), dim3(kInsertWaves * 64), 0, st, k, v, d.cent_bf16[cur], d.cnorm[cur], m, cur, d.C, d.Cpad, d);
+    const size_t lds = (size_t)d.C * (kD * 2 + 8);
+    if (m >= 2 && lds <= 150u * 1024u) {
+        allow_dynamic_lds((const void *)insert_kernel<true>, lds);
+        hipLaunchKernelGGL(insert_kernel<true>, dim3(d.U), dim3(kInsertWaves * 64), lds, st, k, v, d.cent_bf16[cur], d.cnorm[cur], m, cur,
+                           d.C, d.Cpad, d);
+        return;
+    }
+    hipLaunchKernelGGL(insert_kernel<false>, dim3(d.U), dim3(kInsertWaves * 64), 0, st, k, v, d.cent_bf16[cur], d.cnorm[cur], m, cur, d.C, d.Cpad, d);
 }
 
 // ------------------------------------------------------------------------------------------------
@@ -463,7 +536,7 @@ __global__ __launch_bounds__(NW * 64) void decode_step_kernel(int U, int max_pag
     using SR = SplitRow<G>;
     bf16x8 qs[2];  // the query rows in split-row form (scoring); the attention takes them in plain form
     {
-        const int per = round_up((np_hint + chunks - 1) / chunks, 16 * NW);
+        const int per = round_up((np_hint + chunks - 1) / chunks, 16);  // (whole 16-page blocks)
         const int p0 = chunk * per, pend = min(np_hint, p0 + per);
         const int nblk = (pend - p0 + 15) >> 4;
         constexpr int UNR = 4;
@@ -936,6 +1009,9 @@ __global__ __launch_bounds__(NW * 64) void decode_step_kernel(int U, int max_pag
 }
 size_t decode_step_lds_bytes(const Dev &d, int P);
 
+// Workgroups per unit: enough for every CU when units are few, but at least one 16-page block per
+// wave each (smaller pieces were measured slower: 64 pages per workgroup 15.8 us per one-layer
+// step, 128 pages 14.95, 256 pages 14.85: more arrivals per counter, no shorter scoring).
 int decode_step_chunks(const Dev &d, int np_hint) {
     const int NW = d.G == 8 ? 8 : 16;
     np_hint = std::max(1, std::min(np_hint, d.max_pages));
