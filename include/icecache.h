@@ -136,8 +136,10 @@ ice_status_t ice_insert_batch(ice_index_t *idx, const void *k, const void *v, in
  * pages by (score descending, id ascending) are returned with ids ascending, padded with -1.
  *   q: bf16 [B, H_q, d];  page_ids: int32 [B, H_kv, P];  n_selected: int32 [B, H_kv];
  *   scores_or_null: fp32 [B, H_kv, P] group score of each returned page (0 in the padding).
- * SHAPE if token_budget < page_size; UNSUPPORTED if the index has more than 16384 pages per unit
- * (the scores of a unit are ranked in one workgroup's registers and LDS).
+ * SHAPE if token_budget < page_size; UNSUPPORTED if the index can hold more than 32768 pages per
+ * unit (the scores of a unit are ranked from one workgroup's registers: 524 288 tokens per KV head
+ * at page size 16 less one page per cluster), or if the budget's winner lists (12 bytes per page
+ * of the budget) do not fit a CU's LDS; a budget that covers every page is always accepted.
  * n_selected[u] = -1 (ids -1, zero attention output) reports a unit whose workgroups could not hand
  * their scores over within the bounded wait (see ice_debug_select_fault); never expected in use. */
 ice_status_t ice_select(ice_index_t *idx, const void *q, int32_t token_budget, int32_t *page_ids,
@@ -220,7 +222,8 @@ ice_status_t ice_attend_tokens(ice_index_t *idx, const void *q, const void *K, c
  *   out_or_null fp32 [B, H_q, d]: when given, attention over the returned pages (as ice_attend)
  *   runs in the same launch.
  * All device pointers, caller-owned; only enqueues.  Errors as ice_select, plus SHAPE for
- * n_probe < 1 or 0 < n_refine < P, and UNSUPPORTED when the candidate lists do not fit a CU's LDS. */
+ * n_probe < 1 or 0 < n_refine < P, and UNSUPPORTED for more than 16384 pages per unit or when the
+ * candidate lists (8 bytes per page the index can hold) do not fit a CU's LDS. */
 ice_status_t ice_select_hier(ice_index_t *idx, const void *q, int32_t token_budget, int32_t n_probe, int32_t n_refine,
                              int32_t *page_ids, int32_t *n_selected, float *scores_or_null,
                              int32_t *clusters_or_null, float *out_or_null, void *stream);

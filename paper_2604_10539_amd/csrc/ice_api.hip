@@ -252,9 +252,9 @@ static ice_status_t check_select(ice_index_t *ix, const void *q, int32_t budget,
     if (ix->dev.max_pages > decode_step_max_pages(ix->dev.G))
         return fail(ICE_ERR_UNSUPPORTED, "%d pages per unit exceed the selection kernel's limit of %d", ix->dev.max_pages,
                     decode_step_max_pages(ix->dev.G));
-    if (decode_step_lds_bytes(ix->dev, budget / ix->dev.s) > 160u * 1024u - 64u)
-        return fail(ICE_ERR_UNSUPPORTED, "token_budget %d needs more LDS than a CU has for the candidate list "
-                    "(a budget that covers max_pages is always accepted)", budget);
+    if (!decode_step_plan(ix->dev, budget / ix->dev.s, ix->n_tokens / ix->dev.s + ix->dev.C).fits)
+        return fail(ICE_ERR_UNSUPPORTED, "token_budget %d (%d pages) and %d pages per unit need more LDS than a CU has for the "
+                    "winner lists", budget, budget / ix->dev.s, ix->dev.max_pages);
     return ICE_OK;
 }
 

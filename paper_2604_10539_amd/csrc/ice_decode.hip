@@ -486,7 +486,8 @@ hipError_t launch_attend_static(const Dev &d, const bf16_t *q, const int *ids, c
 // scalar loads while the first loads are in flight.
 template <int G, int NW, int EMAX, bool RES>
 __global__ __launch_bounds__(NW * 64) void decode_step_kernel(int U, int max_pages, int P, int chunks, int np_hint, int lds_scores_off,
-                                                               int wait_cfg, const bf16_t *__restrict__ rep_all, const bf16_t *__restrict__ q,
+                                                               int wait_cfg, int cand_cap, const bf16_t *__restrict__ rep_all,
+                                                               const bf16_t *__restrict__ q,
                                                                const int *__restrict__ n_pages, Dev d, int *__restrict__ ids_out,
                                                                int *__restrict__ n_sel_out, float *__restrict__ scores_out, Resident res,
                                                                float *__restrict__ out) {
@@ -856,20 +857,19 @@ __global__ __launch_bounds__(NW * 64) void decode_step_kernel(int U, int max_pag
         const int need = by_prefix ? sh_M2 : k, first = k - need;
         auto list_candidates = [&](auto with_prefix) {
             constexpr bool PREFIX = decltype(with_prefix)::value;
-            u64 bal[EMAX], bal_a[PREFIX ? EMAX : 1];
+            // (the lane masks are formed twice, once to count and once to place: keeping EMAX of them
+            // would not fit the scalar registers of the instantiations with many keys per thread)
+            auto listed = [&](int e) {
+                const bool valid = e * NT + tid < np;
+                if constexpr (PREFIX) return __ballot(valid && (key[e] >> 16) == (pre >> 16));
+                else return __ballot(valid && key[e] >= pre);
+            };
+            auto is_above = [&](int e) { return __ballot(e * NT + tid < np && (key[e] >> 16) > (pre >> 16)); };
             int tot = 0, tot_a = 0;
 #pragma unroll
             for (int e = 0; e < EMAX; ++e) {
-                const bool valid = e * NT + tid < np;
-                if constexpr (PREFIX) {
-                    const bool above = valid && (key[e] >> 16) > (pre >> 16);
-                    bal[e] = __ballot(valid && (key[e] >> 16) == (pre >> 16));
-                    bal_a[e] = __ballot(above);
-                    tot_a += (int)__popcll(bal_a[e]);
-                } else {
-                    bal[e] = __ballot(valid && key[e] >= pre);
-                }
-                tot += (int)__popcll(bal[e]);
+                tot += (int)__popcll(listed(e));
+                if constexpr (PREFIX) tot_a += (int)__popcll(is_above(e));
             }
             int base = 0;
             if (lane == 0 && tot) base = atomicAdd(&sh_M, tot);
@@ -878,9 +878,11 @@ __global__ __launch_bounds__(NW * 64) void decode_step_kernel(int U, int max_pag
 #pragma unroll
             for (int e = 0; e < EMAX; ++e) {
                 const int pid = e * NT + tid;
-                if ((bal[e] >> lane) & 1ull)
-                    cand[base + (int)__popcll(bal[e] & lower)] = ((u64)key[e] << 32) | (u64)(0xFFFFFFFFu - (uint32_t)pid);
-                base += (int)__popcll(bal[e]);
+                const u64 bal = listed(e);
+                const int slot = base + (int)__popcll(bal & lower);
+                if (((bal >> lane) & 1ull) && slot < cand_cap)  // (a list that overflows is not used: see B3)
+                    cand[slot] = ((u64)key[e] << 32) | (u64)(0xFFFFFFFFu - (uint32_t)pid);
+                base += (int)__popcll(bal);
             }
             if constexpr (PREFIX) {
                 if (lane == 0) sh_rowmax[wave] = (uint32_t)tot_a;  // (the row maxima are not needed on this path)
@@ -890,9 +892,10 @@ __global__ __launch_bounds__(NW * 64) void decode_step_kernel(int U, int max_pag
 #pragma unroll
                 for (int e = 0; e < EMAX; ++e) {
                     const int pid = e * NT + tid;
-                    if ((bal_a[e] >> lane) & 1ull)
-                        sel_comp[base_a + (int)__popcll(bal_a[e] & lower)] = ((u64)key[e] << 32) | (u64)(0xFFFFFFFFu - (uint32_t)pid);
-                    base_a += (int)__popcll(bal_a[e]);
+                    const u64 bal_a = is_above(e);
+                    if ((bal_a >> lane) & 1ull)
+                        sel_comp[base_a + (int)__popcll(bal_a & lower)] = ((u64)key[e] << 32) | (u64)(0xFFFFFFFFu - (uint32_t)pid);
+                    base_a += (int)__popcll(bal_a);
                 }
             }
         };
@@ -902,7 +905,80 @@ __global__ __launch_bounds__(NW * 64) void decode_step_kernel(int U, int max_pag
         const int M = sh_M;  // >= need
         ICE_STAMP(4);
         // B3: the `need` best of the M candidates, exactly, into sel_comp[first..k)
-        if (M <= 512) {
+        if (M > cand_cap) {
+            // More candidates than the list holds (many equal scores, or a threshold that cut little):
+            // radix select straight from the key registers over ALL keys of the unit, 8 bits a pass over
+            // the (32 + nb)-bit packed composite (score key, lower id first); it fills sel_comp[0..k) as
+            // a whole, waves in a fixed order.
+            int nb = 0;
+            while ((1 << nb) < np) ++nb;
+            const u64 idmask = (1ull << nb) - 1ull;
+            auto packed = [&](int e) { return ((u64)key[e] << nb) | (idmask - (u64)(uint32_t)(e * NT + tid)); };
+            int *hist = (int *)region;  // 256 bins + wave totals (the overflowed list is dead)
+            u64 prefix = 0ull, known = 0ull;
+            int kk = k;
+            for (int sft = ((32 + nb - 1) / 8) * 8; sft >= 0; sft -= 8) {
+                lds_barrier();
+                if (tid < 256) hist[tid] = 0;
+                lds_barrier();
+#pragma unroll
+                for (int e = 0; e < EMAX; ++e) {
+                    // (keys that share the prefix mostly share the next byte as well: the lanes that agree
+                    // with the first such lane are counted with one update)
+                    const u64 pk = packed(e);
+                    const int bin = e * NT + tid < np && (pk & known) == prefix ? (int)((pk >> sft) & 255ull) : -1;
+                    const u64 act = __ballot(bin >= 0);
+                    if (act != 0ull) {  // (wave-uniform)
+                        const int lead = (int)__builtin_ctzll(act);
+                        const int first_bin = __shfl(bin, lead);
+                        const u64 same = __ballot(bin == first_bin);
+                        if (lane == lead) atomicAdd(&hist[first_bin], (int)__popcll(same));
+                        if (bin >= 0 && bin != first_bin) atomicAdd(&hist[bin], 1);
+                    }
+                }
+                lds_barrier();
+                int h = 0, incl = 0;
+                if (tid < 256) {  // bins in descending order: thread t owns bin 255 - t
+                    h = hist[255 - tid];
+                    incl = h;
+                    for (int off = 1; off < 64; off <<= 1) {
+                        const int t2 = __shfl_up(incl, off);
+                        if (lane >= off) incl += t2;
+                    }
+                    if (lane == 63) hist[256 + wave] = incl;
+                }
+                lds_barrier();
+                if (tid < 256) {
+                    for (int w2 = 0; w2 < wave; ++w2) incl += hist[256 + w2];
+                    const int excl = incl - h;
+                    if (incl >= kk && excl < kk) {
+                        sh_tau = prefix | ((u64)(255 - tid) << sft);
+                        sh_M2 = kk - excl;
+                    }
+                }
+                lds_barrier();
+                prefix = sh_tau;
+                kk = sh_M2;
+                known |= 255ull << sft;
+            }
+            // prefix = packed composite of the k-th largest key; everything at or above it wins
+            const u64 lower = (1ull << lane) - 1ull;
+            int tot = 0;
+#pragma unroll
+            for (int e = 0; e < EMAX; ++e) tot += (int)__popcll(__ballot(e * NT + tid < np && packed(e) >= prefix));
+            lds_barrier();
+            if (lane == 0) sh_rowmax[wave] = (uint32_t)tot;
+            lds_barrier();
+            int base = 0;
+            for (int w2 = 0; w2 < wave; ++w2) base += (int)sh_rowmax[w2];
+#pragma unroll
+            for (int e = 0; e < EMAX; ++e) {
+                const int pid = e * NT + tid;
+                const u64 bal = __ballot(pid < np && packed(e) >= prefix);
+                if ((bal >> lane) & 1ull) sel_comp[base + (int)__popcll(bal & lower)] = ((u64)key[e] << 32) | (u64)(0xFFFFFFFFu - (uint32_t)pid);
+                base += (int)__popcll(bal);
+            }
+        } else if (M <= 512) {
             // every candidate counts the candidates that beat it; `parts` lanes share one candidate
             int lp = 0;
             while (lp < 6 && (M << (lp + 1)) <= NT) ++lp;
@@ -1007,7 +1083,6 @@ __global__ __launch_bounds__(NW * 64) void decode_step_kernel(int U, int max_pag
     }
     ICE_USTAMP(3);
 }
-size_t decode_step_lds_bytes(const Dev &d, int P);
 
 // Workgroups per unit: enough for every CU when units are few, but at least one 16-page block per
 // wave each (smaller pieces were measured slower: 64 pages per workgroup 15.8 us per one-layer
@@ -1021,19 +1096,47 @@ int decode_step_chunks(const Dev &d, int np_hint) {
     return chunks < 1 ? 1 : chunks;
 }
 
+// Launch shape and LDS of a decode step.  LDS: the winner lists ([Pk] ids, [Pk] composites), then
+// one region used first for the candidate list (cand_cap entries + histograms) and later as the
+// attention's scratch, then, with one workgroup per unit only, the unit's scores.  The candidate
+// list is as long as the pages the index can hold, up to kCandCapMax entries (a longer list is
+// never needed unless thousands of scores tie: then the selection runs from the key registers).
+constexpr int kCandCapMax = 4096;
+DecodePlan decode_step_plan(const Dev &d, int P, int np_hint) {
+    const int NW = d.G == 8 ? 8 : 16;
+    DecodePlan p;
+    p.np_hint = std::max(1, std::min(np_hint, d.max_pages));
+    p.chunks = decode_step_chunks(d, p.np_hint);
+    const int Pk = P < d.max_pages ? P : d.max_pages;
+    const size_t red_bytes = sizeof(float) * attend_scratch_floats(d.G, NW);
+    const size_t fixed = round_up(Pk * 4, 16) + (size_t)Pk * 8 + (p.chunks == 1 ? (size_t)d.max_pages * 4 : 0);
+    const size_t limit = 160u * 1024u - 2048u;  // (static LDS of the kernel: 1.7 KB)
+    // no candidate list is needed when the budget covers every page the index can hold
+    p.cand_cap = P >= d.max_pages ? 0 : std::min(d.max_pages, kCandCapMax);
+    auto total = [&](int cap) {
+        const size_t cand_bytes = cap ? (size_t)cap * 8 + 272 * 4 : 0;
+        return fixed + round_up((int)std::max(cand_bytes, std::max(red_bytes, (size_t)272 * 4)), 16);
+    };
+    if (total(p.cand_cap) > limit && p.cand_cap > 1024) p.cand_cap = 1024;
+    p.lds = total(p.cand_cap);
+    p.scores_off = p.chunks == 1 ? (int)(p.lds - (size_t)d.max_pages * 4) : 0;
+    p.fits = p.lds <= limit;
+    return p;
+}
+
 void launch_decode_step(const Dev &d, const bf16_t *q, int P, int np_hint, int *ids, int *n_sel, float *scores_out,
                         const bf16_t *res_k, const bf16_t *res_v, int n_res, float *out, hipStream_t st, int wait_cfg) {
     const int NW = d.G == 8 ? 8 : 16;
     // a workgroup pass scores 16*NW pages per load round; few units -> split each unit over many
     // workgroups (one round each), many units -> one workgroup per unit and no cross-workgroup step
-    if (np_hint > d.max_pages) np_hint = d.max_pages;
-    if (np_hint < 1) np_hint = 1;
-    const int chunks = decode_step_chunks(d, np_hint);
+    const DecodePlan plan = decode_step_plan(d, P, np_hint);
+    np_hint = plan.np_hint;
+    const int chunks = plan.chunks;
     // few units and a large budget: select in this launch, attend with the unit's pages spread over
-    // several workgroups (two more launches, see attend_split_kernel)
+    // several workgroups (one more launch, see attend_split_kernel)
     const bool split_attend = out && chunks > 1 && n_res == 0 && attend_shares(d, P, kFusedSplitMinShares) > 1;
     float *out_fused = split_attend ? nullptr : out;
-    const size_t lds = decode_step_lds_bytes(d, P);
+    const size_t lds = plan.lds;
     const int grid = round_up(d.U, 8) * chunks;
     const int E = (d.max_pages + NW * 64 - 1) / (NW * 64);
     const Resident res = {res_k, res_v, out_fused ? n_res : 0, nullptr, nullptr, 0};
@@ -1041,34 +1144,24 @@ void launch_decode_step(const Dev &d, const bf16_t *q, int P, int np_hint, int *
     do {                                                                                                            \
         allow_dynamic_lds((const void *)decode_step_kernel<g, nw, e, r>, lds);                                      \
         hipLaunchKernelGGL((decode_step_kernel<g, nw, e, r>), dim3(grid), dim3(nw * 64), lds, st, d.U, d.max_pages, P, chunks, np_hint, \
-                           (int)(lds - (size_t)d.max_pages * 4), wait_cfg, d.rep, q, d.n_pages, d, ids, n_sel, scores_out, res, out_fused); \
+                           plan.scores_off, wait_cfg, plan.cand_cap, d.rep, q, d.n_pages, d, ids, n_sel, scores_out, res, out_fused); \
     } while (0)
 #define ICE_STEP(g, nw, e)                                                                                          \
     do {                                                                                                            \
         if (res.n > 0) ICE_STEP_R(g, nw, e, true);                                                                  \
         else ICE_STEP_R(g, nw, e, false);                                                                           \
     } while (0)
-    if (d.G == 8) { if (E <= 8) ICE_STEP(8, 8, 8); else ICE_STEP(8, 8, 32); }
-    else if (d.G == 4) { if (E <= 4) ICE_STEP(4, 16, 4); else ICE_STEP(4, 16, 16); }
-    else if (d.G == 2) { if (E <= 4) ICE_STEP(2, 16, 4); else ICE_STEP(2, 16, 16); }
-    else { if (E <= 4) ICE_STEP(1, 16, 4); else ICE_STEP(1, 16, 16); }
+    if (d.G == 8) { if (E <= 8) ICE_STEP(8, 8, 8); else if (E <= 32) ICE_STEP(8, 8, 32); else ICE_STEP(8, 8, 64); }
+    else if (d.G == 4) { if (E <= 4) ICE_STEP(4, 16, 4); else if (E <= 16) ICE_STEP(4, 16, 16); else ICE_STEP(4, 16, 32); }
+    else if (d.G == 2) { if (E <= 4) ICE_STEP(2, 16, 4); else if (E <= 16) ICE_STEP(2, 16, 16); else ICE_STEP(2, 16, 32); }
+    else { if (E <= 4) ICE_STEP(1, 16, 4); else if (E <= 16) ICE_STEP(1, 16, 16); else ICE_STEP(1, 16, 32); }
 #undef ICE_STEP
 #undef ICE_STEP_R
     if (split_attend) launch_attend(d, q, ids, n_sel, P, Resident{nullptr, nullptr, 0, nullptr, nullptr, 0}, out, st, kFusedSplitMinShares);
 }
 
-// largest page count and page budget launch_decode_step can serve (register-resident keys, LDS lists)
-int decode_step_max_pages(int G) { return (G == 8 ? 8 * 64 * 32 : 16 * 64 * 16); }
-size_t decode_step_lds_bytes(const Dev &d, int P) {
-    const int NW = d.G == 8 ? 8 : 16;
-    const int Pk = P < d.max_pages ? P : d.max_pages;
-    // no candidate list is needed when the budget covers every page the index can hold
-    const size_t cand_bytes = P >= d.max_pages ? 0 : (size_t)d.max_pages * 8 + 260 * 4;
-    const size_t red_bytes = sizeof(float) * attend_scratch_floats(d.G, NW);
-    // winner lists, candidate list / attention scratch (used one after the other), LDS copy of the scores
-    return round_up(Pk * 4, 16) + (size_t)Pk * 8 + round_up((int)(cand_bytes > red_bytes ? cand_bytes : red_bytes), 16) +
-           (size_t)d.max_pages * 4;
-}
+// largest page count launch_decode_step can serve (a unit's scores are ranked from one workgroup's registers)
+int decode_step_max_pages(int G) { return (G == 8 ? 8 * 64 * 64 : 16 * 64 * 32); }
 
 }  // namespace ice
 

@@ -108,7 +108,15 @@ void launch_decode_hier(const Dev &d, const bf16_t *q, int cur, int P, int n_pro
 int decode_hier_max_pages(int G);
 size_t decode_hier_lds_bytes(const Dev &d, int P, int n_probe, int n_refine);
 int decode_step_max_pages(int G);
-size_t decode_step_lds_bytes(const Dev &d, int P);
+struct DecodePlan {
+    int chunks;      // workgroups per unit
+    int np_hint;     // clamped upper bound of the live pages per unit
+    int cand_cap;    // entries of the LDS candidate list
+    int scores_off;  // byte offset of the LDS copy of the scores (one workgroup per unit only)
+    size_t lds;      // dynamic LDS of the launch
+    bool fits;       // ... within a CU's LDS
+};
+DecodePlan decode_step_plan(const Dev &d, int P, int np_hint);
 // Resident tokens: tokens that are always attended on top of the listed pages, handled as further
 // 16-token blocks dealt to the waves after the pages.  Two forms:
 //   dense     a run of n tokens per unit, k, v bf16 [U][n][d] (the sink tokens and the recent

@@ -238,3 +238,48 @@ def test_config5_long_generation_loop():
             print("[config 5] step %d: state equal, %d pages opened so far" % (t + 1, int((o.n_pages - pages0).sum())), flush=True)
     assert flips <= steps * 8 // 500
     print("[config 5] %d steps, %d nearest-centroid decisions inside the tie band" % (steps, flips))
+
+
+def test_context_of_300k_tokens_on_the_flat_path():
+    """The paper's longest latency point (300k tokens): 20 798 pages per unit at page size 16, more than one
+    workgroup's 16 keys per thread hold, so the 32-keys-per-thread instantiation ranks them.  One KV
+    head; selection over every page and attention against the oracle, for a small and a large budget."""
+    from paper_2604_10539_amd import IceIndex
+    w = datagen.small("ctx300k", n_kv_heads=1, n_tokens=300000, n_clusters=2048, token_budget=1024, n_components=1024,
+                      outlier_frac=0.05, seed=3300)
+    K, V = datagen.keys_values(w)
+    K, V = K.reshape(1, w.n_tokens, D), V.reshape(1, w.n_tokens, D)
+    init, q_np = datagen.init_indices(w), datagen.queries(w)
+    ix = IceIndex(1, 1, 4, w.n_tokens, 16, w.n_clusters, kmeans_iters=1, init_idx=up(init))
+    ix.build_index(up(K), up(V))
+    ex = ix.export()
+    assert int(ex["n_pages"][0]) > 16384
+    for budget in (1024, 256, 16 * 300):
+        ids, n_sel, out = ix.select_attend(up(q_np), budget)
+        torch.cuda.synchronize()
+        _select_attend_vs_oracle(ix, ex, q_np, budget, ids, n_sel, out)
+    _check_units(ix, ex, K, V, [0], w.n_tokens, np.random.default_rng(3), n_keys=32)
+
+
+def test_thousands_of_tied_pages_are_ranked_from_the_registers():
+    """More exactly tied candidates than the LDS candidate list holds (5000 identical pages, a few better
+    and a few worse ones): the selection falls back to the radix select over the key registers and
+    must still return the best pages, lowest ids first among the ties."""
+    from paper_2604_10539_amd import IceIndex
+    from tests.util import export_np, oracle_from_export
+    rng = np.random.default_rng(19)
+    n = 16 * 5000
+    key = narrow(rng.standard_normal(D).astype(np.float32))
+    K = np.tile(key, (1, 1, n, 1))
+    K[0, 0, 16 * 4100:16 * 4103] = narrow(3.0 * widen(key))         # three pages that beat the rest
+    K[0, 0, 16 * 10:16 * 12] = narrow(-1.0 * widen(key))            # two pages that lose
+    V = narrow(rng.standard_normal((1, 1, n, D)).astype(np.float32))
+    ix = IceIndex(1, 1, 1, n, 16, 1, kmeans_iters=1, init_idx=up(np.zeros((1, 1, 1), np.int32)))
+    ix.build_index(up(K), up(V))
+    q = narrow(widen(key)[None, None, :].copy())
+    o = oracle_from_export(ix, export_np(ix))
+    for pages in (8, 40, 200):
+        ids, n_sel, scores = ix.select(up(q), 16 * pages)
+        want = sorted([4100, 4101, 4102] + [p for p in range(pages) if p not in (10, 11)][:pages - 3])
+        assert down(ids).ravel().tolist() == want, pages
+        _compare_select(o, q, 16 * pages, down(ids), down(n_sel), down(scores))
