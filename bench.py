@@ -244,6 +244,30 @@ def compact_config(name, torch, dev, clock, args, stream_data=None):
     ms_warm = clock.back_to_back([lambda: first.select_attend(q, budget, ids, ns, out)], args.steps, args.warmup)
     res["warm_us_per_step"] = ms_warm * 1e3
     res["clustering"] = clustering
+    # ---- the staged searches on the same index (cold: flush + one event pair per step)
+    from paper_2604_10539_amd import binding
+    n_probe = max(1, C // 8)
+    ids_h, ns_h, out_h = torch.empty_like(ids), torch.empty_like(ns), torch.empty_like(out)
+    try:
+        ms_h = clock.per_step(lambda: binding.ice_select_hier(first.handle, q, budget, n_probe, ids_h, ns_h, None, None, out_h),
+                              args.steps, args.warmup, True)
+        rec2 = float(np.mean([len(np.intersect1d(ids_h.cpu().numpy().reshape(U, P)[u2, :ns_np[u2]], ids_np[u2, :ns_np[u2]])) / max(1, ns_np[u2])
+                              for u2 in range(U)]))
+        staged = {"two_levels": {"n_probe": n_probe, "us_per_step": ms_h * 1e3, "recall_of_flat_selection": rec2}}
+        if C >= 64:
+            n_top = min(256, max(8, int(round(np.sqrt(C) * 1.5))))
+            n_probe_top = max(2, n_top // 4)
+            t_top = clock.once(lambda: first.build_top_level(n_top, 3))
+            ms_3 = clock.per_step(lambda: binding.ice_select_hier3(first.handle, q, budget, n_probe_top, n_probe, ids_h, ns_h, None, None,
+                                                                    None, out_h), args.steps, args.warmup, True)
+            rec3 = float(np.mean([len(np.intersect1d(ids_h.cpu().numpy().reshape(U, P)[u2, :ns_np[u2]], ids_np[u2, :ns_np[u2]])) / max(1, ns_np[u2])
+                                  for u2 in range(U)]))
+            staged["three_levels"] = {"n_top": n_top, "n_probe_top": n_probe_top, "n_probe": n_probe, "us_per_step": ms_3 * 1e3,
+                                      "recall_of_flat_selection": rec3, "build_top_level_us": t_top * 1e3}
+        staged["flat_flush_per_step_us"] = ms_flush * 1e3
+        res["staged_search"] = staged
+    except binding.IceError as e:
+        res["staged_search"] = {"unsupported": str(e)}
 
     # ---- cfg5: the decode loop itself (Alg. 1 decode phase: insert -> select -> attend, one token per step)
     loop = None

@@ -228,6 +228,38 @@ ice_status_t ice_select_hier(ice_index_t *idx, const void *q, int32_t token_budg
                              int32_t *page_ids, int32_t *n_selected, float *scores_or_null,
                              int32_t *clusters_or_null, float *out_or_null, void *stream);
 
+/* A third level (Sec. 3.3: the tree has levels L..1, every point's parent is a point one level up;
+ * Alg. 4 searches it top-down).  ice_build_top_level puts n_top nodes per unit above the clusters:
+ * n_top clusters are promoted (evenly spaced cluster ids), then `iters` rounds of (every cluster goes
+ * to the nearest top node by squared Euclidean distance between its bf16 centroid and the node's bf16
+ * rounding, lowest id on ties -> every node moves to the mean of its clusters' bf16 centroids); the
+ * state kept is the last assignment and the means of that assignment.  Built from the centroids as
+ * they are at the call (after ice_build_index, or after insertions); it does not follow later
+ * insertions (a new key gets a parent, the levels above stay as they are, Sec. 4.2), and
+ * ice_build_index / ice_import_index drop it.  n_top in [1, min(256, n_clusters)]; 0 drops it.
+ *
+ * ice_select_hier3 is ice_select_hier with one stage in front: the n_top nodes are ranked by the
+ * same normalised GQA score, the min(n_probe_top, n_top) best are kept (lower id first on ties), and
+ * stage 1 ranks only the clusters hanging under them (it keeps min(n_probe, their number)).  With
+ * n_probe_top >= n_top the result is ice_select_hier's.
+ *   tops_or_null int32 [B, H_kv, n_probe_top]: kept top nodes ascending, -1 padded.
+ * STATE before ice_build_top_level; SHAPE for n_probe_top < 1; otherwise as ice_select_hier.
+ * ice_export_top_level gives device pointers into the workspace:
+ *   top_centroid fp32 [U][n_top_max][d], top_centroid_bf16 bf16 [U][n_top_max][d] (rows >= n_top zero),
+ *   top_of int32 [U][n_clusters], top_count int32 [U][n_top_max], top_init int32 [U][n_top_max] (the
+ *   cluster each node was promoted from). */
+typedef struct {
+    int32_t n_top, n_top_max;
+    float *top_centroid;
+    void *top_centroid_bf16;
+    int32_t *top_of, *top_count, *top_init;
+} ice_top_view_t;
+ice_status_t ice_build_top_level(ice_index_t *idx, int32_t n_top, int32_t iters, void *stream);
+ice_status_t ice_export_top_level(ice_index_t *idx, ice_top_view_t *view);
+ice_status_t ice_select_hier3(ice_index_t *idx, const void *q, int32_t token_budget, int32_t n_probe_top, int32_t n_probe,
+                              int32_t n_refine, int32_t *page_ids, int32_t *n_selected, float *scores_or_null,
+                              int32_t *clusters_or_null, int32_t *tops_or_null, float *out_or_null, void *stream);
+
 /* Geometry of the clustering (Sec. 4.2, Eq. 2).  The paper measures key-key distances between
  * transformed keys T_K(k) = [k / c, sqrt(1 - ||k||^2 / c^2)], c >= the largest key norm.  With
  * ICE_GEOMETRY_TRANSFORMED the next ice_build_index (and every later insertion) does the same,

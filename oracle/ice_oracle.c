@@ -448,10 +448,10 @@ void orc_select(const orc_state_t *st, const uint16_t *q, int budget, int32_t *i
  * scores[] then holds these key scores.
  * clusters (may be NULL): [U][n_probe] kept cluster ids ascending, -1 padded.
  * Sc_all (may be NULL): [U][C] fp32 centroid scores. */
-void orc_select_hier(const orc_state_t *st, const uint16_t *q, int budget, int n_probe, int n_refine, int32_t *ids,
-                     int32_t *n_sel, float *scores, int32_t *clusters, float *Sc_all) {
+static void select_hier_impl(const orc_state_t *st, const uint16_t *q, int budget, int n_probe, int n_refine,
+                             const char *eligible /* [U][C] or NULL: clusters that may be kept */, int32_t *ids,
+                             int32_t *n_sel, float *scores, int32_t *clusters, float *Sc_all) {
     const int d = st->d, G = st->G, MP = st->max_pages, C = st->C, P = budget / st->s;
-    const int n_keep = n_probe < C ? n_probe : C;
 #pragma omp parallel for schedule(dynamic, 1)
     for (int u = 0; u < st->U; ++u) {
         const int np = st->n_pages[u];
@@ -482,7 +482,12 @@ void orc_select_hier(const orc_state_t *st, const uint16_t *q, int budget, int n
             cs[c].id = c;
             if (Sc_all) Sc_all[(size_t)u * C + c] = (float)best;
         }
-        qsort(cs, (size_t)C, sizeof(scored_t), cmp_scored);
+        /* the eligible clusters first (all of them without a level above), best first */
+        int n_el = 0;
+        for (int c = 0; c < C; ++c)
+            if (!eligible || eligible[(size_t)u * C + c]) cs[n_el++] = cs[c];
+        qsort(cs, (size_t)n_el, sizeof(scored_t), cmp_scored);
+        const int n_keep = n_probe < n_el ? n_probe : n_el;
         char *kept = (char *)calloc((size_t)C, 1);
         for (int x = 0; x < n_keep; ++x) kept[cs[x].id] = 1;
         if (clusters) {
@@ -546,6 +551,77 @@ void orc_select_hier(const orc_state_t *st, const uint16_t *q, int budget, int n
         free(kept);
         free(cs);
     }
+}
+
+void orc_select_hier(const orc_state_t *st, const uint16_t *q, int budget, int n_probe, int n_refine, int32_t *ids,
+                     int32_t *n_sel, float *scores, int32_t *clusters, float *Sc_all) {
+    select_hier_impl(st, q, budget, n_probe, n_refine, NULL, ids, n_sel, scores, clusters, Sc_all);
+}
+
+/* ---- three levels ---------------------------------------------------------------------------------
+ * One more level of the tree above the clusters (Sec. 3.3: levels L..1, every point's parent is a
+ * point of the level above; Alg. 4 descends from the top level, keeping the best nodes of a level
+ * and searching only their children on the next).  The top level is given as state: top_centroid
+ * fp32 [U][C2][d] (a top node's position) and top_of int32 [U][C] (the top node each cluster
+ * hangs under).  Stage 0 scores the C2 top nodes, rounded to bf16, with the same normalised GQA
+ * score as everything below (max over the group's heads of q_h . t / ||q_h||, fp64 rounded once to
+ * fp32) and keeps the min(n_probe_top, C2) best by (score descending, id ascending).  Stage 1 is
+ * orc_select_hier's, restricted to the clusters whose top node was kept (the best
+ * min(n_probe, number of such clusters) of them); stages 2 and 3 follow unchanged.  With
+ * n_probe_top >= C2 every cluster is eligible and the result is orc_select_hier's.
+ * tops (may be NULL): [U][n_probe_top] kept top nodes ascending, -1 padded; St_all (may be NULL):
+ * [U][C2] fp32 top-node scores. */
+void orc_select_hier3(const orc_state_t *st, const float *top_centroid, const int32_t *top_of, int C2,
+                      const uint16_t *q, int budget, int n_probe_top, int n_probe, int n_refine, int32_t *ids,
+                      int32_t *n_sel, float *scores, int32_t *clusters, int32_t *tops, float *Sc_all, float *St_all) {
+    const int d = st->d, G = st->G, C = st->C;
+    const int n_keep0 = n_probe_top < C2 ? n_probe_top : C2;
+    char *eligible = (char *)calloc((size_t)st->U * C, 1);
+    for (int u = 0; u < st->U; ++u) {
+        double qn[64];
+        for (int h = 0; h < G; ++h) {
+            double acc = 0.0;
+            for (int j = 0; j < d; ++j) {
+                double x = bf16_to_f32(q[((size_t)u * G + h) * d + j]);
+                acc += x * x;
+            }
+            qn[h] = sqrt(acc);
+            if (qn[h] < 1e-20) qn[h] = 1e-20;
+        }
+        scored_t *ts = (scored_t *)malloc(sizeof(scored_t) * (size_t)C2);
+        for (int t = 0; t < C2; ++t) {
+            double best = -INFINITY;
+            for (int h = 0; h < G; ++h) {
+                double dot = 0.0;
+                for (int j = 0; j < d; ++j) {
+                    float tc = bf16_to_f32(f32_to_bf16(top_centroid[((size_t)u * C2 + t) * d + j]));
+                    dot += (double)bf16_to_f32(q[((size_t)u * G + h) * d + j]) * (double)tc;
+                }
+                double sh = dot / qn[h];
+                if (sh > best) best = sh;
+            }
+            ts[t].s = (float)best;
+            ts[t].id = t;
+            if (St_all) St_all[(size_t)u * C2 + t] = (float)best;
+        }
+        qsort(ts, (size_t)C2, sizeof(scored_t), cmp_scored);
+        char *kept0 = (char *)calloc((size_t)C2, 1);
+        for (int x = 0; x < n_keep0; ++x) kept0[ts[x].id] = 1;
+        if (tops) {
+            int w = 0;
+            for (int t = 0; t < C2; ++t)
+                if (kept0[t]) tops[(size_t)u * n_probe_top + w++] = t;
+            for (; w < n_probe_top; ++w) tops[(size_t)u * n_probe_top + w] = -1;
+        }
+        for (int c = 0; c < C; ++c) {
+            const int t = top_of[(size_t)u * C + c];
+            eligible[(size_t)u * C + c] = (t >= 0 && t < C2 && kept0[t]) ? 1 : 0;
+        }
+        free(kept0);
+        free(ts);
+    }
+    select_hier_impl(st, q, budget, n_probe, n_refine, eligible, ids, n_sel, scores, clusters, Sc_all);
+    free(eligible);
 }
 
 /* ---- sparse attention over the selected pages (Eq. 1 with the mask = selected tokens) ---------

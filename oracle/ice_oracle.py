@@ -247,6 +247,30 @@ class OracleIndex:
                               _p(scores), _p(clusters), _p(Sc_all))
         return ids, n_sel, scores, clusters, Sc_all
 
+    def select_hier3(self, q: np.ndarray, token_budget: int, n_probe_top: int, n_probe: int, top_centroid: np.ndarray,
+                     top_of: np.ndarray, n_refine: int = 0):
+        """Three-level selection: the n_probe_top best top nodes (top_centroid float32 [U, C2, d]), then the
+        n_probe best clusters among those hanging under them (top_of int32 [U, C]), then pages as
+        select_hier.  -> (ids, n_sel, scores, clusters [U, n_probe], tops [U, n_probe_top], Sc_all [U, C],
+        St_all [U, C2])."""
+        q = self._units(q, (self.G, self.d), np.uint16)
+        C2 = top_centroid.shape[-2]
+        top_centroid = np.ascontiguousarray(top_centroid, np.float32).reshape(self.U, C2, self.d)
+        top_of = np.ascontiguousarray(top_of, np.int32).reshape(self.U, self.C)
+        P = token_budget // self.s
+        ids = np.full((self.U, P), -1, np.int32)
+        n_sel = np.zeros(self.U, np.int32)
+        scores = np.zeros((self.U, P), np.float32)
+        clusters = np.full((self.U, n_probe), -1, np.int32)
+        tops = np.full((self.U, n_probe_top), -1, np.int32)
+        Sc_all = np.zeros((self.U, self.C), np.float32)
+        St_all = np.zeros((self.U, C2), np.float32)
+        st = self._state()
+        lib().orc_select_hier3(C.byref(st), _p(top_centroid), _p(top_of), C.c_int(C2), _p(q), C.c_int(token_budget),
+                               C.c_int(n_probe_top), C.c_int(n_probe), C.c_int(n_refine), _p(ids), _p(n_sel), _p(scores),
+                               _p(clusters), _p(tops), _p(Sc_all), _p(St_all))
+        return ids, n_sel, scores, clusters, tops, Sc_all, St_all
+
     def attend(self, q: np.ndarray, ids: np.ndarray, n_sel: np.ndarray) -> np.ndarray:
         """Sparse attention over the listed pages: float32 [U, G, d]."""
         q = self._units(q, (self.G, self.d), np.uint16)

@@ -6,5 +6,5 @@ from .binding import (ICE_GEOMETRY_RAW, ICE_GEOMETRY_TRANSFORMED, ICE_STAGE_ASSI
                       ice_debug_assign, ice_debug_peak_mfma, ice_debug_peak_read, ice_debug_rerun_stage,
                       ice_debug_select_fault, ice_destroy, ice_export_geometry, ice_export_index, ice_import_index,
                       ice_insert, ice_insert_batch, ice_last_error, ice_select, ice_select_attend,
-                      ice_select_attend_resident, ice_select_hier, ice_selected_tokens, ice_set_geometry,
+                      ice_select_attend_resident, ice_select_hier, ice_select_hier3, ice_build_top_level, ice_export_top_level, ice_selected_tokens, ice_set_geometry,
                       ice_workspace_bytes, lib, make_config)

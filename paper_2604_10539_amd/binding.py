@@ -17,7 +17,7 @@ ICE_OK, ICE_ERR_INVALID_ARG, ICE_ERR_SHAPE, ICE_ERR_STATE, ICE_ERR_CAPACITY, ICE
 STATUS_NAMES = ["ICE_OK", "ICE_ERR_INVALID_ARG", "ICE_ERR_SHAPE", "ICE_ERR_STATE", "ICE_ERR_CAPACITY",
                 "ICE_ERR_UNSUPPORTED", "ICE_ERR_DEVICE"]
 SYMBOLS = ["ice_workspace_bytes", "ice_create", "ice_destroy", "ice_build_index", "ice_insert", "ice_insert_batch", "ice_select",
-           "ice_attend", "ice_attend_noalloc", "ice_select_attend", "ice_attend_resident", "ice_select_attend_resident", "ice_selected_tokens", "ice_attend_tokens", "ice_select_hier", "ice_set_geometry", "ice_export_geometry", "ice_export_index", "ice_import_index", "ice_debug_assign", "ice_debug_rerun_stage", "ice_debug_select_fault",
+           "ice_attend", "ice_attend_noalloc", "ice_select_attend", "ice_attend_resident", "ice_select_attend_resident", "ice_selected_tokens", "ice_attend_tokens", "ice_select_hier", "ice_select_hier3", "ice_build_top_level", "ice_export_top_level", "ice_set_geometry", "ice_export_geometry", "ice_export_index", "ice_import_index", "ice_debug_assign", "ice_debug_rerun_stage", "ice_debug_select_fault",
            "ice_debug_peak_read", "ice_debug_peak_mfma", "ice_last_error"]
 
 
@@ -33,6 +33,11 @@ class IceIndexView(C.Structure):
                [(n, C.c_void_p) for n in ("Kp", "Vp", "page_cluster", "page_fill", "page_pos", "cluster_tail",
                                           "cluster_cnt", "cluster_sum", "centroid", "page_sum", "rep", "n_pages",
                                           "assign", "assign_centroid_bf16", "init_idx")]
+
+
+class IceTopView(C.Structure):
+    _fields_ = [("n_top", C.c_int32), ("n_top_max", C.c_int32), ("top_centroid", C.c_void_p), ("top_centroid_bf16", C.c_void_p),
+                ("top_of", C.c_void_p), ("top_count", C.c_void_p), ("top_init", C.c_void_p)]
 
 
 class IceGeometryView(C.Structure):
@@ -83,6 +88,10 @@ def lib() -> C.CDLL:
                                         C.c_int32, C.c_void_p, C.c_void_p]
         L.ice_select_hier.argtypes = [C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.c_int32, C.c_void_p, C.c_void_p,
                                       C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]
+        L.ice_select_hier3.argtypes = [C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.c_int32, C.c_int32, C.c_void_p, C.c_void_p,
+                                       C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]
+        L.ice_build_top_level.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.c_void_p]
+        L.ice_export_top_level.argtypes = [C.c_void_p, C.POINTER(IceTopView)]
         L.ice_set_geometry.argtypes = [C.c_void_p, C.c_int32]
         L.ice_export_geometry.argtypes = [C.c_void_p, C.POINTER(IceGeometryView)]
         L.ice_export_index.argtypes = [C.c_void_p, C.POINTER(IceIndexView)]
@@ -202,6 +211,22 @@ def ice_select_hier(idx, q, token_budget, n_probe, page_ids, n_selected, scores=
                     stream=None, n_refine=0) -> None:
     _check(lib().ice_select_hier(idx, _ptr(q), token_budget, n_probe, n_refine, _ptr(page_ids), _ptr(n_selected), _ptr(scores),
                                  _ptr(clusters), _ptr(out), _stream(stream)))
+
+
+def ice_select_hier3(idx, q, token_budget, n_probe_top, n_probe, page_ids, n_selected, scores=None, clusters=None, tops=None,
+                     out=None, stream=None, n_refine=0) -> None:
+    _check(lib().ice_select_hier3(idx, _ptr(q), token_budget, n_probe_top, n_probe, n_refine, _ptr(page_ids), _ptr(n_selected),
+                                  _ptr(scores), _ptr(clusters), _ptr(tops), _ptr(out), _stream(stream)))
+
+
+def ice_build_top_level(idx, n_top: int, iters: int, stream=None) -> None:
+    _check(lib().ice_build_top_level(idx, n_top, iters, _stream(stream)))
+
+
+def ice_export_top_level(idx) -> IceTopView:
+    view = IceTopView()
+    _check(lib().ice_export_top_level(idx, C.byref(view)))
+    return view
 
 
 def ice_set_geometry(idx, geometry: int) -> None:
@@ -394,6 +419,42 @@ class IceIndex:
         ice_select_hier(self.handle, q, token_budget, n_probe, ids, n_sel, scores, clusters, out if attend else None,
                         stream, n_refine)
         return ids, n_sel, scores, clusters, (out if attend else None)
+
+    def build_top_level(self, n_top, iters=3, stream=None):
+        """A level of n_top nodes above the clusters (dropped again by the next build_index)."""
+        ice_build_top_level(self.handle, n_top, iters, stream)
+
+    def select_hier3(self, q, token_budget, n_probe_top, n_probe, attend=True, stream=None, n_refine=0):
+        """Three-level selection (+ attention).  -> (ids, n_sel, scores, clusters, tops, out or None)."""
+        ids, n_sel = self._sel_buffers(token_budget)
+        P = ids.shape[-1]
+        scores = torch.empty((self.batch, self.n_kv_heads, P), dtype=torch.float32, device=self.device)
+        clusters = torch.empty((self.batch, self.n_kv_heads, n_probe), dtype=torch.int32, device=self.device)
+        tops = torch.empty((self.batch, self.n_kv_heads, n_probe_top), dtype=torch.int32, device=self.device)
+        out = torch.empty((self.batch, self.n_kv_heads * self.group_size, 128), dtype=torch.float32,
+                          device=self.device) if attend else None
+        ice_select_hier3(self.handle, q, token_budget, n_probe_top, n_probe, ids, n_sel, scores, clusters, tops, out, stream,
+                         n_refine)
+        return ids, n_sel, scores, clusters, tops, out
+
+    def export_top_level(self):
+        """The level above the clusters as torch tensors aliasing the workspace."""
+        v = ice_export_top_level(self.handle)
+        base = self.workspace.data_ptr()
+
+        def view(ptr, dtype, shape):
+            nb = int(torch.tensor([], dtype=dtype).element_size())
+            n = 1
+            for x in shape:
+                n *= x
+            return self.workspace[ptr - base: ptr - base + n * nb].view(dtype).view(*shape)
+        U, T = self.U, v.n_top_max
+        return {"n_top": v.n_top,
+                "top_centroid": view(v.top_centroid, torch.float32, (U, T, 128))[:, :v.n_top],
+                "top_centroid_bf16": view(v.top_centroid_bf16, torch.int16, (U, T, 128)),
+                "top_of": view(v.top_of, torch.int32, (U, self.n_clusters)),
+                "top_count": view(v.top_count, torch.int32, (U, T))[:, :v.n_top],
+                "top_init": view(v.top_init, torch.int32, (U, T))[:, :v.n_top]}
 
     def export_geometry(self):
         """The extra coordinate of the transformed-key geometry as torch tensors aliasing the workspace

@@ -86,6 +86,11 @@ size_t lay_out(const ice_config_t &cfg, int s, int C, char *base, Dev *out) {
     d.cent_aug = (float *)take(U * C * 4);
     d.csum_aug = (float *)take(U * C * 4);
     d.c2 = (float *)take(U * 4);
+    d.top_cent = (float *)take(U * kTopMax * kD * 4);
+    d.top_bf16 = (bf16_t *)take(U * kTopMax * kD * 2);
+    d.top_of = (int *)take(U * C * 4);
+    d.top_cnt = (int *)take(U * kTopMax * 4);
+    d.top_init = (int *)take(U * kTopMax * 4);
     d.init_idx = (int *)take(U * C * 4);
     d.assign = (int *)take(U * MT * 4);
     d.packed = (unsigned long long *)take(U * MT * 8);
@@ -176,6 +181,7 @@ ice_status_t ice_create(const ice_config_t *cfg, void *workspace, size_t workspa
     ix->built = false;
     ix->n_tokens = 0;
     ix->build_n = 0;
+    ix->n_top = 0;
     ix->cur = 0;
     ix->geometry = 0;
     *out = ix;
@@ -219,6 +225,7 @@ ice_status_t ice_build_index(ice_index_t *ix, const void *K, const void *V, int3
     ix->cur = cur;
     ix->n_tokens = n;
     ix->build_n = n;
+    ix->n_top = 0;
     ix->built = true;
     return ICE_OK;
 }
@@ -346,10 +353,9 @@ ice_status_t ice_attend_tokens(ice_index_t *ix, const void *q, const void *K, co
     return device_status("ice_attend_tokens");
 }
 
-ice_status_t ice_select_hier(ice_index_t *ix, const void *q, int32_t budget, int32_t n_probe, int32_t n_refine, int32_t *ids,
-                             int32_t *n_sel, float *scores, int32_t *clusters, float *out, void *stream) {
-    if (!ix) return fail(ICE_ERR_INVALID_ARG, "index is null");
-    if (!ix->built) return fail(ICE_ERR_STATE, "ice_select_hier before ice_build_index");
+static ice_status_t select_hier_common(ice_index_t *ix, const void *q, int32_t budget, int32_t n_top, int32_t n_probe_top,
+                                       int32_t n_probe, int32_t n_refine, int32_t *ids, int32_t *n_sel, float *scores,
+                                       int32_t *clusters, int32_t *tops, float *out, void *stream, const char *who) {
     if (!q || !aligned16(q)) return fail(ICE_ERR_INVALID_ARG, "q is null or misaligned");
     if (!ids || !n_sel) return fail(ICE_ERR_INVALID_ARG, "page_ids or n_selected is null");
     if (budget < ix->dev.s) return fail(ICE_ERR_SHAPE, "token_budget %d is below page_size %d", budget, ix->dev.s);
@@ -361,12 +367,61 @@ ice_status_t ice_select_hier(ice_index_t *ix, const void *q, int32_t budget, int
     if (ix->dev.max_pages > decode_hier_max_pages(ix->dev.G))
         return fail(ICE_ERR_UNSUPPORTED, "%d pages per unit exceed the selection kernel's limit of %d", ix->dev.max_pages,
                     decode_hier_max_pages(ix->dev.G));
-    if (decode_hier_lds_bytes(ix->dev, P, n_probe, n_refine) > 160u * 1024u - 1024u)
+    if (decode_hier_lds_bytes(ix->dev, P, n_probe, n_refine) > 160u * 1024u - 6144u)
         return fail(ICE_ERR_UNSUPPORTED, "%d pages per unit, n_probe %d, n_refine %d and token_budget %d need more LDS than a CU has",
                     ix->dev.max_pages, n_probe, n_refine, budget);
-    launch_decode_hier(ix->dev, static_cast<const bf16_t *>(q), ix->cur, P, n_probe, n_refine, ix->n_tokens / ix->dev.s + ix->dev.C, ids,
-                       n_sel, scores, clusters, out, static_cast<hipStream_t>(stream));
-    return device_status("ice_select_hier");
+    launch_decode_hier(ix->dev, static_cast<const bf16_t *>(q), ix->cur, P, n_top, n_probe_top, n_probe, n_refine,
+                       ix->n_tokens / ix->dev.s + ix->dev.C, ids, n_sel, scores, clusters, tops, out, static_cast<hipStream_t>(stream));
+    return device_status(who);
+}
+
+ice_status_t ice_select_hier(ice_index_t *ix, const void *q, int32_t budget, int32_t n_probe, int32_t n_refine, int32_t *ids,
+                             int32_t *n_sel, float *scores, int32_t *clusters, float *out, void *stream) {
+    if (!ix) return fail(ICE_ERR_INVALID_ARG, "index is null");
+    if (!ix->built) return fail(ICE_ERR_STATE, "ice_select_hier before ice_build_index");
+    return select_hier_common(ix, q, budget, 0, 0, n_probe, n_refine, ids, n_sel, scores, clusters, nullptr, out, stream,
+                              "ice_select_hier");
+}
+
+ice_status_t ice_select_hier3(ice_index_t *ix, const void *q, int32_t budget, int32_t n_probe_top, int32_t n_probe,
+                              int32_t n_refine, int32_t *ids, int32_t *n_sel, float *scores, int32_t *clusters, int32_t *tops,
+                              float *out, void *stream) {
+    if (!ix) return fail(ICE_ERR_INVALID_ARG, "index is null");
+    if (!ix->built) return fail(ICE_ERR_STATE, "ice_select_hier3 before ice_build_index");
+    if (ix->n_top == 0) return fail(ICE_ERR_STATE, "ice_select_hier3 before ice_build_top_level");
+    if (n_probe_top < 1) return fail(ICE_ERR_SHAPE, "n_probe_top must be >= 1");
+    return select_hier_common(ix, q, budget, ix->n_top, n_probe_top, n_probe, n_refine, ids, n_sel, scores, clusters, tops, out,
+                              stream, "ice_select_hier3");
+}
+
+ice_status_t ice_build_top_level(ice_index_t *ix, int32_t n_top, int32_t iters, void *stream) {
+    if (!ix) return fail(ICE_ERR_INVALID_ARG, "index is null");
+    if (!ix->built) return fail(ICE_ERR_STATE, "ice_build_top_level before ice_build_index");
+    if (n_top == 0) {  // (drops the level)
+        ix->n_top = 0;
+        return ICE_OK;
+    }
+    if (n_top < 1 || n_top > kTopMax || n_top > ix->dev.C)
+        return fail(ICE_ERR_SHAPE, "n_top %d is outside [1, min(%d, n_clusters = %d)]", n_top, kTopMax, ix->dev.C);
+    if (iters < 1) return fail(ICE_ERR_INVALID_ARG, "iters must be >= 1");
+    launch_top_level(ix->dev, ix->cur, n_top, iters, static_cast<hipStream_t>(stream));
+    if (ice_status_t st = device_status("ice_build_top_level")) return st;
+    ix->n_top = n_top;
+    return ICE_OK;
+}
+
+ice_status_t ice_export_top_level(ice_index_t *ix, ice_top_view_t *v) {
+    if (!ix || !v) return fail(ICE_ERR_INVALID_ARG, "index or view is null");
+    if (!ix->built || ix->n_top == 0) return fail(ICE_ERR_STATE, "ice_export_top_level before ice_build_top_level");
+    memset(v, 0, sizeof(*v));
+    v->n_top = ix->n_top;
+    v->n_top_max = kTopMax;
+    v->top_centroid = ix->dev.top_cent;
+    v->top_centroid_bf16 = ix->dev.top_bf16;
+    v->top_of = ix->dev.top_of;
+    v->top_count = ix->dev.top_cnt;
+    v->top_init = ix->dev.top_init;
+    return ICE_OK;
 }
 
 ice_status_t ice_set_geometry(ice_index_t *ix, int32_t geometry) {
@@ -466,6 +521,7 @@ ice_status_t ice_import_index(ice_index_t *ix, const ice_index_view_t *v, void *
     if (ice_status_t st = device_status("ice_import_index")) return st;
     ix->n_tokens = v->n_tokens;
     ix->build_n = 0;  // (not the product of a build here: no stage to re-run)
+    ix->n_top = 0;
     ix->built = true;
     return ICE_OK;
 }

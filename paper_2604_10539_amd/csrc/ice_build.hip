@@ -10,6 +10,11 @@ namespace ice {
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 typedef unsigned long long u64;
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+// a.lo*b.lo + a.hi*b.hi + c on packed bf16 pairs, fp32 accumulate (v_dot2_f32_bf16)
+__device__ inline float dot2(uint32_t a, uint32_t b, float c) {
+    return __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, a), __builtin_bit_cast(bf16x2, b), c, false);
+}
 
 __device__ inline uint64_t splitmix64(uint64_t x) {
     x += 0x9E3779B97F4A7C15ull;
@@ -912,6 +917,129 @@ void launch_paginate(const Dev &d, const bf16_t *K, const bf16_t *V, int n, hipS
     const size_t lds = (size_t)4 * d.s * kD * 2;
     if (keys_exceed_cache(d, n)) hipLaunchKernelGGL(paginate_kernel<true>, dim3((d.max_pages + 3) / 4, d.U), dim3(256), lds, st, d, K, V, n);
     else hipLaunchKernelGGL(paginate_kernel<false>, dim3((d.max_pages + 3) / 4, d.U), dim3(256), lds, st, d, K, V, n);
+}
+
+// ------------------------------------------------------------------------------------------------
+// The level above the clusters (Sec. 3.3: every point's parent is a point one level up).  A small
+// Lloyd iteration over the unit's C bf16 centroids as points, one workgroup per unit:
+//   promote  top node t starts at the centroid in the middle of the t-th of n_top equal strata of the
+//            cluster ids;
+//   assign   every cluster to the nearest top node: ||t~||^2 - 2 c . t~ in fp32 against the nodes'
+//            bf16 rounding held in LDS, lowest id on ties;
+//   means    the clusters of a node are listed in ascending id (one wave per node walks the
+//            assignment with lane masks) and summed in that order in fp32, four dimensions per thread;
+//            an empty node keeps its position.
+// The state left is the last assignment and the means of that assignment, as for the clusters.
+// LDS: [n_top][128] bf16 rows, [n_top] norms, [n_top + 1] list starts, [C] assignment, [C] member list.
+__global__ __launch_bounds__(1024) void top_level_kernel(Dev d, const bf16_t *__restrict__ cent, int n_top, int iters) {
+    extern __shared__ __align__(16) char smem[];
+    const int u = blockIdx.x, tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+    const int C = d.C;
+    uint4 *rows = (uint4 *)smem;                                   // [n_top][16]
+    float *norm = (float *)(smem + (size_t)n_top * 256);           // [n_top]
+    int *start = (int *)(norm + n_top);                            // [n_top + 1]
+    int *asg = start + n_top + 1;                                  // [C]
+    int *members = asg + C;                                        // [C]
+    const bf16_t *pts = cent + (size_t)u * d.Cpad * kD;            // the clusters' bf16 centroids: the points
+    float *tc = d.top_cent + (size_t)u * kTopMax * kD;
+    // promote
+    for (int x = tid; x < n_top * 16; x += 1024) {
+        const int t = x >> 4, ch = x & 15;
+        const int c = (int)(((long long)(2 * t + 1) * C) / (2 * n_top));
+        const uint4 w = ((const uint4 *)(pts + (size_t)c * kD))[ch];
+        rows[x] = w;
+        float *dst = tc + (size_t)t * kD + ch * 8;
+        dst[0] = bf16_lo(w.x); dst[1] = bf16_hi(w.x); dst[2] = bf16_lo(w.y); dst[3] = bf16_hi(w.y);
+        dst[4] = bf16_lo(w.z); dst[5] = bf16_hi(w.z); dst[6] = bf16_lo(w.w); dst[7] = bf16_hi(w.w);
+        if (ch == 0) d.top_init[(size_t)u * kTopMax + t] = c;
+    }
+    __syncthreads();
+    for (int it = 0; it < iters; ++it) {
+        for (int t = tid; t < n_top; t += 1024) {
+            float nn = 0.f;
+            for (int ch = 0; ch < 16; ++ch) {
+                const uint4 w = rows[t * 16 + ch];
+                nn += bf16_lo(w.x) * bf16_lo(w.x) + bf16_hi(w.x) * bf16_hi(w.x) + bf16_lo(w.y) * bf16_lo(w.y) + bf16_hi(w.y) * bf16_hi(w.y) +
+                      bf16_lo(w.z) * bf16_lo(w.z) + bf16_hi(w.z) * bf16_hi(w.z) + bf16_lo(w.w) * bf16_lo(w.w) + bf16_hi(w.w) * bf16_hi(w.w);
+            }
+            norm[t] = nn;
+        }
+        __syncthreads();
+        // assign: a thread per cluster, the node rows broadcast from LDS
+        for (int c = tid; c < C; c += 1024) {
+            uint4 pt[16];
+#pragma unroll
+            for (int ch = 0; ch < 16; ++ch) pt[ch] = ((const uint4 *)(pts + (size_t)c * kD))[ch];
+            float bv = INFINITY;
+            int bi = 0;
+            for (int t = 0; t < n_top; ++t) {
+                float dot = 0.f;
+#pragma unroll
+                for (int ch = 0; ch < 16; ++ch) {
+                    const uint4 w = rows[t * 16 + ch];
+                    dot = dot2(pt[ch].w, w.w, dot2(pt[ch].z, w.z, dot2(pt[ch].y, w.y, dot2(pt[ch].x, w.x, dot))));
+                }
+                const float val = norm[t] - 2.0f * dot;
+                if (val < bv) { bv = val; bi = t; }
+            }
+            asg[c] = bi;
+            d.top_of[(size_t)u * C + c] = bi;
+        }
+        __syncthreads();
+        // list the clusters of every node in ascending id: counts, starts, then placement
+        for (int t = wave; t < n_top; t += 16) {
+            int cnt = 0;
+            for (int c0 = 0; c0 < C; c0 += 64) cnt += (int)__popcll(__ballot(c0 + lane < C && asg[c0 + lane] == t));
+            if (lane == 0) start[t + 1] = cnt;
+        }
+        __syncthreads();
+        if (tid == 0) {
+            start[0] = 0;
+            for (int t = 0; t < n_top; ++t) start[t + 1] += start[t];
+        }
+        __syncthreads();
+        for (int t = wave; t < n_top; t += 16) {
+            int base = start[t];
+            for (int c0 = 0; c0 < C; c0 += 64) {
+                const bool is = c0 + lane < C && asg[c0 + lane] == t;
+                const u64 bal = __ballot(is);
+                if (is) members[base + (int)__popcll(bal & ((1ull << lane) - 1ull))] = c0 + lane;
+                base += (int)__popcll(bal);
+            }
+        }
+        __syncthreads();
+        // means: (node, four dimensions) per thread, members in list order
+        for (int x = tid; x < n_top * 32; x += 1024) {
+            const int t = x >> 5, qd = x & 31;
+            const int lo = start[t], cnt = start[t + 1] - lo;
+            float a0 = 0.f, a1 = 0.f, a2 = 0.f, a3 = 0.f;
+            for (int i = 0; i < cnt; ++i) {
+                const uint2 w = ((const uint2 *)(pts + (size_t)members[lo + i] * kD))[qd];
+                a0 += bf16_lo(w.x); a1 += bf16_hi(w.x); a2 += bf16_lo(w.y); a3 += bf16_hi(w.y);
+            }
+            float *dst = tc + (size_t)t * kD + qd * 4;
+            if (cnt > 0) {
+                const float f = (float)cnt;
+                a0 /= f; a1 /= f; a2 /= f; a3 /= f;
+                dst[0] = a0; dst[1] = a1; dst[2] = a2; dst[3] = a3;
+            } else {
+                a0 = dst[0]; a1 = dst[1]; a2 = dst[2]; a3 = dst[3];
+            }
+            ((uint2 *)rows)[t * 32 + qd] = make_uint2((uint32_t)f32_to_bf16(a0) | ((uint32_t)f32_to_bf16(a1) << 16),
+                                                      (uint32_t)f32_to_bf16(a2) | ((uint32_t)f32_to_bf16(a3) << 16));
+            if (qd == 0) d.top_cnt[(size_t)u * kTopMax + t] = cnt;
+        }
+        __syncthreads();
+    }
+    // the nodes' bf16 rows for the search (rows from n_top on: zero)
+    uint4 *dst = (uint4 *)(d.top_bf16 + (size_t)u * kTopMax * kD);
+    for (int x = tid; x < kTopMax * 16; x += 1024) dst[x] = x < n_top * 16 ? rows[x] : make_uint4(0, 0, 0, 0);
+}
+
+void launch_top_level(const Dev &d, int cur, int n_top, int iters, hipStream_t st) {
+    const size_t lds = (size_t)n_top * 256 + (size_t)(2 * n_top + 1) * 4 + (size_t)d.C * 8;
+    allow_dynamic_lds((const void *)top_level_kernel, lds);
+    hipLaunchKernelGGL(top_level_kernel, dim3(d.U), dim3(1024), lds, st, d, d.cent_bf16[cur], n_top, iters);
 }
 
 }  // namespace ice

@@ -241,11 +241,14 @@ __global__ __launch_bounds__(NW * 64) void decode_hier_kernel(int Cpad, int max_
                                                                const int *__restrict__ page_cluster, const int *__restrict__ n_pages, Dev d,
                                                                int *__restrict__ ids_out, int *__restrict__ n_sel_out,
                                                                float *__restrict__ scores_out, int *__restrict__ clusters_out,
-                                                               float *__restrict__ out) {
+                                                               float *__restrict__ out, int n_top, int n_probe_top,
+                                                               int *__restrict__ tops_out) {
     constexpr int NT = NW * 64;
     extern __shared__ __align__(16) char smem[];
     __shared__ SelShared sh;
     __shared__ int sh_ncand;
+    __shared__ u64 comp0[kTopMax], sel0[kTopMax];  // three levels: the top nodes' composites, the kept ones
+    __shared__ uint32_t member0[kTopMax / 32];
     const int u = blockIdx.x, tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
     const int g = lane >> 4, ch = lane & 15;
     const HierLds L = hier_lds(Cpad, max_pages, n_probe, n_refine, P, G, NW);
@@ -292,7 +295,7 @@ __global__ __launch_bounds__(NW * 64) void decode_hier_kernel(int Cpad, int max_
             for (int j = 0; j < 4; ++j) bb1[x][j] = c0 < Cpad ? load16_stream(src + word[j]) : make_uint4(0, 0, 0, 0);
         }
     };
-    request1(wave);
+    if (n_top == 0) request1(wave);
     // the query operand of every scoring MFMA, and 1/||q_h|| where the scores land
     bf16x8 qs[2];
     float inv[4];
@@ -315,30 +318,121 @@ __global__ __launch_bounds__(NW * 64) void decode_hier_kernel(int Cpad, int max_
         return SR::score(acc0, acc1, inv, lane);
     };
     for (int i = tid; i < Cpad / 32 + 1; i += NT) member[i] = 0u;
+    if (tid < kTopMax / 32) member0[tid] = 0u;
     if (tid == 0) sh_ncand = 0;
-
-    // ---- stage 1: centroid scores
-    for (int b0 = wave; b0 < nblk1;) {
+    // Scores of `cnt` rows gathered through a list (16 per block: lanes c and c+8 read the two halves
+    // of a line of row 8*blk + c%8; two blocks in flight per wave).  lst[j] holds row id j in its low
+    // word and is overwritten by the row's composite (ordered score, lower id first).
+    auto score_listed = [&](const bf16_t *rows, u64 *lst, int cnt) {
+        const int nblk = (cnt + 15) >> 4;
+        constexpr int UNR = 2;
+        const int piece = 4 * ((ch >> 3) & 1) + g;  // uint4 inside the 128-byte line
+        for (int b0 = wave; b0 < nblk; b0 += NW * UNR) {
+            uint4 bb[UNR][4];
+            uint32_t rid[UNR];
 #pragma unroll
-        for (int x = 0; x < UNR1; ++x) {
-            if (b0 + NW * x >= nblk1) break;  // (wave-uniform)
-            const int c = 16 * (b0 + NW * x) + ch;
-            const float sc = group_score(bb1[x]);
-            if (owner && c < C) comp1[c] = ((u64)f32_ordered(sc) << 32) | (u64)(0xFFFFFFFFu - (uint32_t)c);
+            for (int x = 0; x < UNR; ++x) {
+                const int j0 = 16 * (b0 + NW * x), j = j0 + ch;
+                rid[x] = j < cnt ? (uint32_t)lst[j] : 0u;  // (row 0 stands in past the end; its score is dropped)
+#pragma unroll
+                for (int blk = 0; blk < 2; ++blk) {
+                    const int jr = j0 + 8 * blk + (ch & 7);
+                    const uint32_t rr = jr < cnt ? (uint32_t)lst[jr] : 0u;
+                    const uint4 *src = (const uint4 *)(rows + (size_t)rr * kD);
+                    bb[x][2 * blk] = load16_stream(src + piece);
+                    bb[x][2 * blk + 1] = load16_stream(src + 8 + piece);
+                }
+            }
+            __builtin_amdgcn_wave_barrier();  // every lane has read its row ids before the entries change
+#pragma unroll
+            for (int x = 0; x < UNR; ++x) {
+                const int j = 16 * (b0 + NW * x) + ch;
+                const float sc = group_score(bb[x]);
+                if (owner && j < cnt) lst[j] = ((u64)f32_ordered(sc) << 32) | (u64)(0xFFFFFFFFu - rid[x]);
+            }
         }
-        b0 += NW * UNR1;
-        if (b0 < nblk1) request1(b0);
-    }
-    __syncthreads();
-    ICE_HSTAMP(1);
-    const int n_keep = min(n_probe, C);
-    if (n_keep == C) {
-        for (int c = tid; c < C; c += NT) sel1[c] = comp1[c];
+    };
+
+    int n_keep, n_keep0 = 0;
+    if (n_top == 0) {
+        // ---- stage 1: centroid scores
+        for (int b0 = wave; b0 < nblk1;) {
+#pragma unroll
+            for (int x = 0; x < UNR1; ++x) {
+                if (b0 + NW * x >= nblk1) break;  // (wave-uniform)
+                const int c = 16 * (b0 + NW * x) + ch;
+                const float sc = group_score(bb1[x]);
+                if (owner && c < C) comp1[c] = ((u64)f32_ordered(sc) << 32) | (u64)(0xFFFFFFFFu - (uint32_t)c);
+            }
+            b0 += NW * UNR1;
+            if (b0 < nblk1) request1(b0);
+        }
         __syncthreads();
+        ICE_HSTAMP(1);
+        n_keep = min(n_probe, C);
+        if (n_keep == C) {
+            for (int c = tid; c < C; c += NT) sel1[c] = comp1[c];
+            __syncthreads();
+        } else {
+            int nb = 0;
+            while ((1 << nb) < C) ++nb;
+            select_topk_lds<NW>(comp1, C, n_keep, nb, sel1, list, hist, sh);
+        }
     } else {
-        int nb = 0;
-        while ((1 << nb) < C) ++nb;
-        select_topk_lds<NW>(comp1, C, n_keep, nb, sel1, list, hist, sh);
+        // ---- stage 0 (three levels): scores of the top nodes, 16 rows per block as in stage 1
+        const bf16_t *tb = d.top_bf16 + (size_t)u * kTopMax * kD;
+        for (int b0 = wave; 16 * b0 < n_top; b0 += NW) {
+            uint4 bw[4];
+#pragma unroll
+            for (int j = 0; j < 4; ++j) bw[j] = load16_stream((const uint4 *)(tb + (size_t)16 * b0 * kD) + word[j]);
+            const int t = 16 * b0 + ch;
+            const float sc = group_score(bw);
+            if (owner && t < n_top) comp0[t] = ((u64)f32_ordered(sc) << 32) | (u64)(0xFFFFFFFFu - (uint32_t)t);
+        }
+        __syncthreads();
+        n_keep0 = min(n_probe_top, n_top);
+        if (n_keep0 == n_top) {
+            for (int t = tid; t < n_top; t += NT) sel0[t] = comp0[t];
+            __syncthreads();
+        } else {
+            int nb0 = 0;
+            while ((1 << nb0) < n_top) ++nb0;
+            select_topk_lds<NW>(comp0, n_top, n_keep0, nb0, sel0, list, hist, sh);
+        }
+        for (int t = tid; t < n_keep0; t += NT) {
+            const uint32_t tn = 0xFFFFFFFFu - (uint32_t)sel0[t];
+            atomicOr(&member0[tn >> 5], 1u << (tn & 31));
+        }
+        __syncthreads();
+        // the clusters hanging under the kept nodes, in any order, ids in the low words of comp1
+        const int *tof = d.top_of + (size_t)u * C;
+        for (int c0 = 0; c0 < C; c0 += NT) {
+            const int c = c0 + tid;
+            const int tn = c < C ? tof[c] : -1;
+            const bool is = tn >= 0 && tn < n_top && ((member0[tn >> 5] >> (tn & 31)) & 1u);
+            const u64 bal = __ballot(is);
+            int base = 0;
+            if (lane == 0 && bal) base = atomicAdd(&sh_ncand, (int)__popcll(bal));
+            base = __shfl(base, 0);
+            if (is) comp1[base + (int)__popcll(bal & ((1ull << lane) - 1ull))] = (u64)(uint32_t)c;
+        }
+        __syncthreads();
+        const int ncl = sh_ncand;
+        __syncthreads();
+        if (tid == 0) sh_ncand = 0;  // (counts the candidate pages next)
+        // ---- stage 1: scores of those clusters' centroids
+        score_listed(cb, comp1, ncl);
+        __syncthreads();
+        ICE_HSTAMP(1);
+        n_keep = min(n_probe, ncl);
+        if (n_keep == ncl) {
+            for (int c = tid; c < ncl; c += NT) sel1[c] = comp1[c];
+            __syncthreads();
+        } else {
+            int nb = 0;
+            while ((1 << nb) < C) ++nb;
+            select_topk_lds<NW>(comp1, ncl, n_keep, nb, sel1, list, hist, sh);
+        }
     }
     ICE_HSTAMP(2);
     // kept clusters: bitmask for stage 2 (their ascending id list is written later, off the critical path)
@@ -371,38 +465,8 @@ __global__ __launch_bounds__(NW * 64) void decode_hier_kernel(int Cpad, int max_
     __syncthreads();
     const int ncand = sh_ncand;
     ICE_HSTAMP(4);
-    // ---- stage 2b: their representatives' scores, 16 candidates per block (gathered rows: lanes c
-    // and c+8 read the two halves of a line of candidate 8*blk + c%8), two blocks in flight per wave
-    {
-        const bf16_t *rep = d.rep + (size_t)u * d.max_pages * kD;
-        const int nblk = (ncand + 15) >> 4;
-        constexpr int UNR = 2;
-        const int piece = 4 * ((ch >> 3) & 1) + g;  // uint4 inside the 128-byte line
-        for (int b0 = wave; b0 < nblk; b0 += NW * UNR) {
-            uint4 bb[UNR][4];
-            uint32_t pg[UNR];
-#pragma unroll
-            for (int x = 0; x < UNR; ++x) {
-                const int j0 = 16 * (b0 + NW * x), j = j0 + ch;
-                pg[x] = j < ncand ? (uint32_t)comp2[j] : 0u;  // (page 0 stands in past the end; its score is dropped)
-#pragma unroll
-                for (int blk = 0; blk < 2; ++blk) {
-                    const int jr = j0 + 8 * blk + (ch & 7);
-                    const uint32_t pr = jr < ncand ? (uint32_t)comp2[jr] : 0u;
-                    const uint4 *src = (const uint4 *)(rep + (size_t)pr * kD);
-                    bb[x][2 * blk] = load16_stream(src + piece);
-                    bb[x][2 * blk + 1] = load16_stream(src + 8 + piece);
-                }
-            }
-            __builtin_amdgcn_wave_barrier();  // every lane has read its page ids before the entries change
-#pragma unroll
-            for (int x = 0; x < UNR; ++x) {
-                const int j = 16 * (b0 + NW * x) + ch;
-                const float sc = group_score(bb[x]);
-                if (owner && j < ncand) comp2[j] = ((u64)f32_ordered(sc) << 32) | (u64)(0xFFFFFFFFu - pg[x]);
-            }
-        }
-    }
+    // ---- stage 2b: their representatives' scores
+    score_listed(d.rep + (size_t)u * d.max_pages * kD, comp2, ncand);
     __syncthreads();
     ICE_HSTAMP(5);
     // how many pages stage 2 keeps: P, or n_refine of which stage 3 then keeps P
@@ -478,6 +542,19 @@ __global__ __launch_bounds__(NW * 64) void decode_hier_kernel(int Cpad, int max_
     // the winners' places in ascending id order; during the attention it runs where the first
     // waves would wait for the last ones
     auto order_ids = [&] {
+        if (tops_out && n_top > 0) {  // the kept top nodes, ascending
+            int *to = tops_out + (size_t)u * n_probe_top;
+            for (int t = tid; t < n_probe_top; t += NT) {
+                if (t < n_keep0) {
+                    const uint32_t mine = 0xFFFFFFFFu - (uint32_t)sel0[t];
+                    int pos = 0;
+                    for (int j = 0; j < n_keep0; ++j) pos += (0xFFFFFFFFu - (uint32_t)sel0[j]) < mine;
+                    to[pos] = (int)mine;
+                } else {
+                    to[t] = -1;
+                }
+            }
+        }
         if (clusters_out) {  // the kept clusters, ascending
             int *co = clusters_out + (size_t)u * n_probe;
             for (int t = tid; t < n_probe; t += NT) {
@@ -512,8 +589,9 @@ size_t decode_hier_lds_bytes(const Dev &d, int P, int n_probe, int n_refine) {
     return hier_lds(d.Cpad, d.max_pages, n_probe, n_refine, P, d.G, NW).total;
 }
 
-void launch_decode_hier(const Dev &d, const bf16_t *q, int cur, int P, int n_probe, int n_refine, int np_hint, int *ids,
-                        int *n_sel, float *scores_out, int *clusters_out, float *out, hipStream_t st) {
+void launch_decode_hier(const Dev &d, const bf16_t *q, int cur, int P, int n_top, int n_probe_top, int n_probe, int n_refine,
+                        int np_hint, int *ids, int *n_sel, float *scores_out, int *clusters_out, int *tops_out, float *out,
+                        hipStream_t st) {
     const size_t lds = decode_hier_lds_bytes(d, P, n_probe, n_refine);
     const int NW = d.G == 8 ? 8 : 16;
     if (np_hint > d.max_pages) np_hint = d.max_pages;
@@ -522,7 +600,8 @@ void launch_decode_hier(const Dev &d, const bf16_t *q, int cur, int P, int n_pro
     do {                                                                                                             \
         allow_dynamic_lds((const void *)decode_hier_kernel<g, nw, e>, lds);                                          \
         hipLaunchKernelGGL((decode_hier_kernel<g, nw, e>), dim3(d.U), dim3(nw * 64), lds, st, d.Cpad, d.max_pages, np_hint, P, n_probe, \
-                           n_refine, d.cent_bf16[cur], q, d.page_cluster, d.n_pages, d, ids, n_sel, scores_out, clusters_out, out);                                                    \
+                           n_refine, d.cent_bf16[cur], q, d.page_cluster, d.n_pages, d, ids, n_sel, scores_out, clusters_out, out, \
+                           n_top, n_probe_top, tops_out);                                                            \
     } while (0)
     if (d.G == 8) { if (E <= 8) ICE_HIER(8, 8, 8); else ICE_HIER(8, 8, 32); }
     else if (d.G == 4) { if (E <= 4) ICE_HIER(4, 16, 4); else ICE_HIER(4, 16, 16); }

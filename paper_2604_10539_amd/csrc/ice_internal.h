@@ -21,6 +21,7 @@ namespace ice {
 
 constexpr int kD = 128;          // head_dim
 constexpr int kAssignTile = 256; // keys staged in LDS per step of the assign kernel
+constexpr int kTopMax = 256;     // nodes of the optional level above the clusters, per unit
 
 typedef uint16_t bf16_t;
 
@@ -46,6 +47,13 @@ struct Dev {
     bf16_t *caug[2];            // [U][Cpad] extra coordinate of the bf16 centroids (double buffer as cent_bf16)
     float *cent_aug, *csum_aug; // [U][C] its fp32 mean and running sum
     float *c2;                  // [U] squared radius c^2 of the key transformation
+    // optional level above the clusters (ice_build_top_level): n_top nodes per unit, each the parent of
+    // a group of clusters; fixed once built (insertions move centroids, not the level above them)
+    float *top_cent;            // [U][kTopMax][128] position of a top node (mean of its clusters' bf16 centroids)
+    bf16_t *top_bf16;           // [U][kTopMax][128] its bf16 rounding (rows >= n_top: zero)
+    int *top_of;                // [U][C] top node of every cluster
+    int *top_cnt;               // [U][kTopMax] clusters per top node
+    int *top_init;              // [U][kTopMax] cluster each top node was promoted from
     // build scratch
     int *init_idx;              // [U][C]
     int *assign;                // [U][max_tokens]
@@ -70,6 +78,7 @@ struct Host {
     bool built;
     int n_tokens;    // per unit
     int build_n;     // tokens per unit of the last ice_build_index (0: none, or the index was imported)
+    int n_top;       // nodes of the level above the clusters (0: not built)
     int cur;         // live centroid buffer
     int geometry;    // 0: distances on the raw keys; 1: on the transformed keys (one more coordinate)
 };
@@ -103,8 +112,11 @@ void launch_decode_step(const Dev &d, const bf16_t *q, int P, int np_hint, int *
                         int wait_cfg = kDecodeWaitDefault);
 int decode_step_chunks(const Dev &d, int np_hint);  // workgroups per unit of that launch
 // two-stage selection (clusters, then their pages) (+ attention when out != nullptr) in one launch
-void launch_decode_hier(const Dev &d, const bf16_t *q, int cur, int P, int n_probe, int n_refine, int np_hint, int *ids,
-                        int *n_sel, float *scores_out, int *clusters_out, float *out, hipStream_t st);
+// n_top > 0: three levels (the n_probe_top best top nodes first, only their clusters are scored)
+void launch_decode_hier(const Dev &d, const bf16_t *q, int cur, int P, int n_top, int n_probe_top, int n_probe, int n_refine,
+                        int np_hint, int *ids, int *n_sel, float *scores_out, int *clusters_out, int *tops_out, float *out,
+                        hipStream_t st);
+void launch_top_level(const Dev &d, int cur, int n_top, int iters, hipStream_t st);
 int decode_hier_max_pages(int G);
 size_t decode_hier_lds_bytes(const Dev &d, int P, int n_probe, int n_refine);
 int decode_step_max_pages(int G);

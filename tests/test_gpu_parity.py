@@ -736,6 +736,144 @@ def test_random_shapes_end_to_end(seed):
         ix.close()
 
 
+# ----------------------------------------------------------------------------------------- three levels
+def _check_hier3(ix, o, q, budget, n_probe_top, n_probe, top_c, top_of, ids, n_sel, scores, clusters, tops, out):
+    """GPU three-level selection against the oracle on identical index and top-level bits, stage by stage
+    (each stage on the GPU's own previous stage, with the oracle's fp32 scores and the 1e-5 tie band)."""
+    U = ix.U
+    C2 = top_c.shape[1]
+    _, _, _, _, _, Sc_all, St_all = o.select_hier3(q, budget, n_probe_top, n_probe, top_c, top_of)
+    oid, ons, osc, ocl, otp, _, _ = o.select_hier3(q, budget, n_probe_top, n_probe, top_c, top_of)
+    _, _, _, S_all = o.select(q, budget)
+    ids, n_sel, scores = down(ids).reshape(U, -1), down(n_sel).reshape(U), down(scores).reshape(U, -1)
+    clusters, tops = down(clusters).reshape(U, n_probe), down(tops).reshape(U, n_probe_top)
+    P = ids.shape[1]
+    ties = 0
+
+    def same_or_tied(got, want, score_of, pool, k, what):
+        if list(got) == list(want):
+            return 0
+        thr = sorted((score_of(x) for x in pool), reverse=True)[k - 1]
+        for x in np.setxor1d(got, want):
+            assert abs(float(score_of(x)) - float(thr)) <= SCORE_TIE * max(1.0, abs(float(thr))), what + " differ outside the tie band"
+        return 1
+
+    for u in range(U):
+        k0 = min(n_probe_top, C2)
+        g0 = tops[u, :k0]
+        assert np.all(np.diff(g0) > 0) and np.all(tops[u, k0:] == -1) and g0.min() >= 0 and g0.max() < C2
+        want0 = sorted(sorted(range(C2), key=lambda t: (-St_all[u, t], t))[:k0])
+        ties += same_or_tied(g0, want0, lambda t: St_all[u, t], range(C2), k0, "kept top nodes")
+        children = [c for c in range(o.C) if int(top_of[u, c]) in set(g0.tolist())]
+        k1 = min(n_probe, len(children))
+        g1 = clusters[u, :k1]
+        assert np.all(np.diff(g1) > 0) and np.all(clusters[u, k1:] == -1) and set(g1.tolist()) <= set(children)
+        want1 = sorted(sorted(children, key=lambda c: (-Sc_all[u, c], c))[:k1])
+        if k1:
+            ties += same_or_tied(g1, want1, lambda c: Sc_all[u, c], children, k1, "kept clusters")
+        kept = set(g1.tolist())
+        cand = [p for p in range(int(o.n_pages[u])) if int(o.page_cluster[u, p]) in kept]
+        k = min(P, len(cand))
+        assert n_sel[u] == k
+        got = ids[u, :k]
+        assert np.all(np.diff(got) > 0) and np.all(ids[u, k:] == -1) and set(got.tolist()) <= set(cand)
+        want = sorted(sorted(cand, key=lambda p: (-S_all[u, p], p))[:k])
+        if k:
+            ties += same_or_tied(got, want, lambda p: S_all[u, p], cand, k, "pages")
+        np.testing.assert_allclose(scores[u, :k], S_all[u, got], rtol=2e-6, atol=2e-6)
+        if list(g0) == want0 and list(g1) == want1 and list(got) == want:   # then it IS the oracle's answer
+            assert otp[u, :k0].tolist() == want0 and ocl[u, :k1].tolist() == want1 and ons[u] == k and oid[u, :k].tolist() == want
+    print("[hier3] %d near-tie differences" % ties)
+    if out is not None:
+        ref = o.attend(q, ids, n_sel)
+        assert np.abs(down(out).reshape(ref.shape) - ref).max() <= ATTN_EXPECTED
+    return ties
+
+
+@pytest.mark.gpu
+@pytest.mark.parametrize("kw,n_top,iters", [
+    (dict(n_tokens=4096, n_clusters=32, n_kv_heads=2, n_components=32), 6, 1),
+    (dict(n_tokens=6000, n_clusters=600, n_kv_heads=2, n_components=200), 24, 3),
+    (dict(n_tokens=9000, n_clusters=2500, n_kv_heads=1, n_components=300), 256, 2),
+    (dict(n_tokens=700, n_clusters=5, n_kv_heads=2), 5, 2),
+])
+def test_top_level_build_stepwise_parity(kw, n_top, iters):
+    """The level above the clusters: promoted clusters, nearest-node assignment of the bf16 centroids,
+    node means; each stage against the oracle's routines on the GPU's own previous stage."""
+    w = datagen.small(**kw)
+    ix, K, V, _ = _mk(w, T=2)
+    ix.build_index(up(K), up(V))
+    ix.build_top_level(n_top, iters)
+    ex = export_np(ix)
+    tl = {k2: (down(v2) if torch.is_tensor(v2) else v2) for k2, v2 in ix.export_top_level().items()}
+    C = w.n_clusters
+    assert tl["n_top"] == n_top
+    want_init = [((2 * t + 1) * C) // (2 * n_top) for t in range(n_top)]
+    for u in range(ix.U):
+        pts = narrow(ex["centroid"][u])                                     # the clusters' bf16 centroids: the points
+        assert tl["top_init"][u].tolist() == want_init
+        top_of = tl["top_of"][u]
+        assert top_of.min() >= 0 and top_of.max() < n_top
+        if iters == 1:   # the only assignment was computed against the promoted rows
+            _check_assign(pts, pts[want_init], top_of, "top level u=%d" % u)
+        # node = mean of its clusters' points (fp32 sums in ascending cluster id); an empty node keeps its place
+        mu, ssum, cnt = orc.means(pts, top_of, n_top, tl["top_centroid"][u])
+        assert np.array_equal(tl["top_count"][u], cnt)
+        live = cnt > 0
+        np.testing.assert_allclose(tl["top_centroid"][u][live], mu[live], rtol=1e-5, atol=1e-5)
+        assert np.array_equal(tl["top_centroid_bf16"][u, :n_top], narrow(tl["top_centroid"][u]))
+        assert not tl["top_centroid_bf16"][u, n_top:].any()
+        # the whole iteration: objective close to the oracle's run from the same promoted clusters
+        a_o, mu_o, _, _, _ = orc.lloyd(pts, np.array(want_init, np.int32), iters)
+        pf = widen(pts).astype(np.float64)
+        j_gpu = ((pf - tl["top_centroid"][u].astype(np.float64)[top_of]) ** 2).sum()
+        j_orc = ((pf - mu_o.astype(np.float64)[a_o]) ** 2).sum()
+        assert abs(j_gpu - j_orc) <= 5e-3 * max(j_orc, 1e-9), (j_gpu, j_orc)
+    # a rebuild of the index drops the level
+    from paper_2604_10539_amd import IceError, binding as b
+    ix.build_index(up(K), up(V))
+    with pytest.raises(IceError) as e:
+        ix.select_hier3(up(datagen.queries(w)), 64, 2, 2)
+    assert e.value.status == b.ICE_ERR_STATE
+
+
+@pytest.mark.gpu
+@pytest.mark.parametrize("kw,budget,n_top,n_probe_top,n_probe", [
+    (dict(n_tokens=4096, n_clusters=32, n_kv_heads=2, n_components=32), 256, 6, 2, 8),
+    (dict(n_tokens=4096, n_clusters=32, n_kv_heads=2, n_components=32), 256, 6, 1, 32),
+    (dict(n_tokens=5003, n_clusters=100, n_kv_heads=3, n_components=40), 64, 10, 3, 17),
+    (dict(n_tokens=6000, n_clusters=600, n_kv_heads=2, n_components=200), 128, 24, 5, 60),
+    (dict(n_tokens=2500, n_clusters=24, n_kv_heads=2, page_size=32, group_size=2), 256, 4, 2, 6),
+    (dict(n_tokens=2600, n_clusters=40, n_kv_heads=1, page_size=64, group_size=8), 640, 8, 3, 12),
+    (dict(n_tokens=9000, n_clusters=2500, n_kv_heads=1, n_components=300), 512, 256, 40, 200),
+])
+def test_three_level_selection_on_gpu_built_index(kw, budget, n_top, n_probe_top, n_probe):
+    w = datagen.small(**kw)
+    ix, K, V, _ = _mk(w, T=2, extra=40)
+    ix.build_index(up(K), up(V))
+    ix.build_top_level(n_top, 2)
+    # insertions afterwards move centroids and open pages; the level above stays as built
+    stream = datagen.DecodeStream(w, seed=9)
+    for _ in range(40):
+        k, v, _ = stream.next()
+        ix.insert(up(k), up(v))
+    tl = ix.export_top_level()
+    top_c, top_of = down(tl["top_centroid"]), down(tl["top_of"])
+    q = datagen.queries(w)
+    o = oracle_from_export(ix, export_np(ix))
+    res = ix.select_hier3(up(q), budget, n_probe_top, n_probe)
+    assert _check_hier3(ix, o, q, budget, n_probe_top, n_probe, top_c, top_of, *res) == 0
+    # every top node kept: exactly the two-level call
+    a = ix.select_hier3(up(q), budget, n_top + 3, n_probe)
+    b2 = ix.select_hier(up(q), budget, n_probe)
+    assert torch.equal(a[0], b2[0]) and torch.equal(a[1], b2[1]) and torch.equal(a[2], b2[2]) and torch.equal(a[3], b2[3])
+    assert torch.equal(a[5], b2[4])
+    # with the best-key stage on top
+    r = ix.select_hier3(up(q), budget, n_probe_top, n_probe, n_refine=2 * (budget // w.page_size))
+    oid, ons, _, _, _, _, _ = o.select_hier3(q, budget, n_probe_top, n_probe, top_c, top_of, n_refine=2 * (budget // w.page_size))
+    assert np.array_equal(down(r[0]).reshape(oid.shape), oid) and np.array_equal(down(r[1]).reshape(ons.shape), ons)
+
+
 # ----------------------------------------------------------------------------------------- refinement by best key
 def _check_refined(ix, o, q, budget, n_probe, n_refine, ids, n_sel, scores, clusters, out):
     """Stage 3 against the staged definition with the oracle's fp32 scores, on the GPU's own kept

@@ -849,6 +849,70 @@ def test_transformed_insert_override_and_force_are_followed():
     assert ix.geometry["centroid_extra"][0, 3] == np.float32(ix.geometry["cluster_sum_extra"][0, 3] / np.float32(ix.cluster_cnt[0, 3]))
 
 
+# ----------------------------------------------------------------------------- three levels (Sec. 3.3, Alg. 4)
+def _top_level(ix, C2, seed):
+    """A top level over the clusters of an oracle index: Lloyd on the bf16-rounded centroids (the pinned
+    routine), from C2 promoted clusters."""
+    rng = np.random.default_rng(seed)
+    top_c = np.zeros((ix.U, C2, D), np.float32)
+    top_of = np.zeros((ix.U, ix.C), np.int32)
+    for u in range(ix.U):
+        init = np.sort(rng.choice(ix.C, C2, replace=False)).astype(np.int32)
+        a, mu, _, _, _ = orc.lloyd(narrow(ix.centroid[u]), init, 3)
+        top_c[u], top_of[u] = mu, a
+    return top_c, top_of
+
+
+@pytest.mark.parametrize("n_probe_top,n_probe,budget", [(3, 6, 128), (1, 4, 64), (5, 40, 256), (2, 2, 16)])
+def test_three_level_select_is_the_staged_definition(n_probe_top, n_probe, budget):
+    """numpy, stage by stage: best top nodes by the normalised GQA score of their bf16 rounding, best
+    clusters among their children, best pages among those clusters' pages."""
+    w = datagen.small(n_tokens=3000, n_clusters=40, n_kv_heads=3, n_components=24)
+    ix, _, _ = _built(w)
+    C2 = 8
+    top_c, top_of = _top_level(ix, C2, 1)
+    q = datagen.queries(w).reshape(ix.U, ix.G, D)
+    ids, n_sel, scores, clusters, tops, Sc_all, St_all = ix.select_hier3(q, budget, n_probe_top, n_probe, top_c, top_of)
+    qf = widen(q).astype(np.float64)
+    S = _scores_numpy(ix, q)
+    P = budget // ix.s
+    for u in range(ix.U):
+        nq = np.linalg.norm(qf[u], axis=1)
+        st = np.float32(((widen(narrow(top_c[u])).astype(np.float64) @ qf[u].T) / nq[None]).max(1))
+        np.testing.assert_allclose(St_all[u], st, rtol=1e-6)
+        keep0 = sorted(sorted(range(C2), key=lambda t: (-St_all[u, t], t))[:n_probe_top])
+        assert tops[u, :len(keep0)].tolist() == keep0 and np.all(tops[u, len(keep0):] == -1)
+        sc = np.float32(((widen(narrow(ix.centroid[u])).astype(np.float64) @ qf[u].T) / nq[None]).max(1))
+        np.testing.assert_allclose(Sc_all[u], sc, rtol=1e-6)
+        children = [c for c in range(ix.C) if top_of[u, c] in keep0]
+        keep1 = sorted(sorted(children, key=lambda c: (-Sc_all[u, c], c))[:n_probe])
+        assert clusters[u, :len(keep1)].tolist() == keep1 and np.all(clusters[u, len(keep1):] == -1)
+        cand = [p for p in range(ix.n_pages[u]) if ix.page_cluster[u, p] in keep1]
+        want = sorted(sorted(cand, key=lambda p: (-S[u][p], p))[:P])
+        assert n_sel[u] == len(want) and ids[u, :len(want)].tolist() == want
+
+
+def test_three_level_select_with_every_top_node_is_the_two_level_select():
+    w = datagen.small(n_tokens=3000, n_clusters=40, n_kv_heads=2, n_components=24)
+    ix, _, _ = _built(w)
+    top_c, top_of = _top_level(ix, 6, 2)
+    q = datagen.queries(w).reshape(ix.U, ix.G, D)
+    for n_refine in (0, 20):
+        a = ix.select_hier3(q, 128, 6, 7, top_c, top_of, n_refine=n_refine)
+        b = ix.select_hier(q, 128, 7, n_refine=n_refine)
+        for x, y in zip(a[:4], b[:4]):
+            assert np.array_equal(x, y)
+    # one top node: only clusters hanging under it can be kept, only their pages returned
+    ids, n_sel, _, clusters, tops, _, _ = ix.select_hier3(q, 16 * 500, 1, 40, top_c, top_of)
+    for u in range(ix.U):
+        t = tops[u, 0]
+        kept = clusters[u][clusters[u] >= 0]
+        assert set(kept.tolist()) == set(np.nonzero(top_of[u] == t)[0].tolist())
+        got = ids[u, :n_sel[u]]
+        assert set(ix.page_cluster[u, got].tolist()) <= set(kept.tolist())
+        assert n_sel[u] == int(np.isin(ix.page_cluster[u, :ix.n_pages[u]], kept).sum())
+
+
 # ----------------------------------------------------------------------------- change detector
 def test_oracle_still_gives_the_stored_small_case():
     """tests/golden/oracle_small_case.json was written by tests/golden/write_oracle_fixture.py from the
