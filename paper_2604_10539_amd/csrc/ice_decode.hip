@@ -1096,6 +1096,12 @@ int decode_step_chunks(const Dev &d, int np_hint) {
     return chunks < 1 ? 1 : chunks;
 }
 
+// the attention of a selection call as a launch of its own (few units, many pages per unit)
+bool launch_attend_would_split(const Dev &d, int P) { return attend_shares(d, P, kFusedSplitMinShares) > 1; }
+void launch_attend_split_after_select(const Dev &d, const bf16_t *q, const int *ids, const int *n_sel, int P, float *out, hipStream_t st) {
+    launch_attend(d, q, ids, n_sel, P, Resident{nullptr, nullptr, 0, nullptr, nullptr, 0}, out, st, kFusedSplitMinShares);
+}
+
 // Launch shape and LDS of a decode step.  LDS: the winner lists ([Pk] ids, [Pk] composites), then
 // one region used first for the candidate list (cand_cap entries + histograms) and later as the
 // attention's scratch, then, with one workgroup per unit only, the unit's scores.  The candidate
@@ -1134,7 +1140,7 @@ void launch_decode_step(const Dev &d, const bf16_t *q, int P, int np_hint, int *
     const int chunks = plan.chunks;
     // few units and a large budget: select in this launch, attend with the unit's pages spread over
     // several workgroups (one more launch, see attend_split_kernel)
-    const bool split_attend = out && chunks > 1 && n_res == 0 && attend_shares(d, P, kFusedSplitMinShares) > 1;
+    const bool split_attend = out && chunks > 1 && n_res == 0 && launch_attend_would_split(d, P);
     float *out_fused = split_attend ? nullptr : out;
     const size_t lds = plan.lds;
     const int grid = round_up(d.U, 8) * chunks;
@@ -1157,7 +1163,7 @@ void launch_decode_step(const Dev &d, const bf16_t *q, int P, int np_hint, int *
     else { if (E <= 4) ICE_STEP(1, 16, 4); else if (E <= 16) ICE_STEP(1, 16, 16); else ICE_STEP(1, 16, 32); }
 #undef ICE_STEP
 #undef ICE_STEP_R
-    if (split_attend) launch_attend(d, q, ids, n_sel, P, Resident{nullptr, nullptr, 0, nullptr, nullptr, 0}, out, st, kFusedSplitMinShares);
+    if (split_attend) launch_attend_split_after_select(d, q, ids, n_sel, P, out, st);
 }
 
 // largest page count launch_decode_step can serve (a unit's scores are ranked from one workgroup's registers)

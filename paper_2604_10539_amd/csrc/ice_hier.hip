@@ -235,7 +235,9 @@ __host__ __device__ inline HierLds hier_lds(int Cpad, int max_pages, int n_probe
 
 // (The leading scalar arguments are those needed before the first loads: they are preloaded into
 // scalar registers at wave start; cent_all = the centroid rows in use.)
-template <int G, int NW, int EMAX>
+// TOP: three levels (a stage in front that ranks the top nodes; compiled apart so that the two-level
+// instantiations keep their register budget).
+template <int G, int NW, int EMAX, bool TOP>
 __global__ __launch_bounds__(NW * 64) void decode_hier_kernel(int Cpad, int max_pages, int np_hint, int P, int n_probe, int n_refine,
                                                                const bf16_t *__restrict__ cent_all, const bf16_t *__restrict__ q,
                                                                const int *__restrict__ page_cluster, const int *__restrict__ n_pages, Dev d,
@@ -247,7 +249,7 @@ __global__ __launch_bounds__(NW * 64) void decode_hier_kernel(int Cpad, int max_
     extern __shared__ __align__(16) char smem[];
     __shared__ SelShared sh;
     __shared__ int sh_ncand;
-    __shared__ u64 comp0[kTopMax], sel0[kTopMax];  // three levels: the top nodes' composites, the kept ones
+    __shared__ u64 comp0[TOP ? kTopMax : 1], sel0[TOP ? kTopMax : 1];  // three levels: the top nodes' composites, the kept ones
     __shared__ uint32_t member0[kTopMax / 32];
     const int u = blockIdx.x, tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
     const int g = lane >> 4, ch = lane & 15;
@@ -295,7 +297,7 @@ __global__ __launch_bounds__(NW * 64) void decode_hier_kernel(int Cpad, int max_
             for (int j = 0; j < 4; ++j) bb1[x][j] = c0 < Cpad ? load16_stream(src + word[j]) : make_uint4(0, 0, 0, 0);
         }
     };
-    if (n_top == 0) request1(wave);
+    if constexpr (!TOP) request1(wave);
     // the query operand of every scoring MFMA, and 1/||q_h|| where the scores land
     bf16x8 qs[2];
     float inv[4];
@@ -354,7 +356,7 @@ __global__ __launch_bounds__(NW * 64) void decode_hier_kernel(int Cpad, int max_
     };
 
     int n_keep, n_keep0 = 0;
-    if (n_top == 0) {
+    if constexpr (!TOP) {
         // ---- stage 1: centroid scores
         for (int b0 = wave; b0 < nblk1;) {
 #pragma unroll
@@ -542,7 +544,7 @@ __global__ __launch_bounds__(NW * 64) void decode_hier_kernel(int Cpad, int max_
     // the winners' places in ascending id order; during the attention it runs where the first
     // waves would wait for the last ones
     auto order_ids = [&] {
-        if (tops_out && n_top > 0) {  // the kept top nodes, ascending
+        if (TOP && tops_out) {  // the kept top nodes, ascending
             int *to = tops_out + (size_t)u * n_probe_top;
             for (int t = tid; t < n_probe_top; t += NT) {
                 if (t < n_keep0) {
@@ -594,20 +596,34 @@ void launch_decode_hier(const Dev &d, const bf16_t *q, int cur, int P, int n_top
                         hipStream_t st) {
     const size_t lds = decode_hier_lds_bytes(d, P, n_probe, n_refine);
     const int NW = d.G == 8 ? 8 : 16;
+    // few units and many pages: the attention moves to a launch of its own that spreads a unit's pages
+    // over several workgroups (see attend_split_kernel)
+    float *out_split = nullptr;
+    if (out && launch_attend_would_split(d, P)) {
+        out_split = out;
+        out = nullptr;
+    }
     if (np_hint > d.max_pages) np_hint = d.max_pages;
     const int E = (d.max_pages + NW * 64 - 1) / (NW * 64);
+#define ICE_HIER_T(g, nw, e, top)                                                                                    \
+    do {                                                                                                             \
+        allow_dynamic_lds((const void *)decode_hier_kernel<g, nw, e, top>, lds);                                     \
+        hipLaunchKernelGGL((decode_hier_kernel<g, nw, e, top>), dim3(d.U), dim3(nw * 64), lds, st, d.Cpad, d.max_pages, np_hint, P, \
+                           n_probe, n_refine, d.cent_bf16[cur], q, d.page_cluster, d.n_pages, d, ids, n_sel, scores_out,   \
+                           clusters_out, out, n_top, n_probe_top, tops_out);                                         \
+    } while (0)
 #define ICE_HIER(g, nw, e)                                                                                           \
     do {                                                                                                             \
-        allow_dynamic_lds((const void *)decode_hier_kernel<g, nw, e>, lds);                                          \
-        hipLaunchKernelGGL((decode_hier_kernel<g, nw, e>), dim3(d.U), dim3(nw * 64), lds, st, d.Cpad, d.max_pages, np_hint, P, n_probe, \
-                           n_refine, d.cent_bf16[cur], q, d.page_cluster, d.n_pages, d, ids, n_sel, scores_out, clusters_out, out, \
-                           n_top, n_probe_top, tops_out);                                                            \
+        if (n_top > 0) ICE_HIER_T(g, nw, e, true);                                                                   \
+        else ICE_HIER_T(g, nw, e, false);                                                                            \
     } while (0)
     if (d.G == 8) { if (E <= 8) ICE_HIER(8, 8, 8); else ICE_HIER(8, 8, 32); }
     else if (d.G == 4) { if (E <= 4) ICE_HIER(4, 16, 4); else ICE_HIER(4, 16, 16); }
     else if (d.G == 2) { if (E <= 4) ICE_HIER(2, 16, 4); else ICE_HIER(2, 16, 16); }
     else { if (E <= 4) ICE_HIER(1, 16, 4); else ICE_HIER(1, 16, 16); }
 #undef ICE_HIER
+#undef ICE_HIER_T
+    if (out_split) launch_attend_split_after_select(d, q, ids, n_sel, P, out_split, st);
 }
 
 // largest page count per unit the kernel serves (page -> cluster entries held in registers)

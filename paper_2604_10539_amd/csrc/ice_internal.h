@@ -151,6 +151,9 @@ void launch_attend(const Dev &d, const bf16_t *q, const int *ids_or_null, const 
 hipError_t launch_attend_static(const Dev &d, const bf16_t *q, const int *ids, const int *n_sel, int P, float *out,
                                 hipStream_t st);
 int attend_static_max_units();
+bool launch_attend_would_split(const Dev &d, int P);  // few units, many pages: a selection call attends in a launch of its own
+void launch_attend_split_after_select(const Dev &d, const bf16_t *q, const int *ids, const int *n_sel, int P, float *out,
+                                      hipStream_t st);
 void launch_selected_tokens(const Dev &d, const int *ids, const int *n_sel, int P, int *pos_out, int *n_tok_out,
                             hipStream_t st);
 
