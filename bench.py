@@ -595,19 +595,44 @@ def main():
     gemm_tflops = 2.0 * 8192 ** 3 / (clock.once(lambda: torch.matmul(ga, gb, out=gc), 5) * 1e-3) / 1e12
     del ga, gb, gc
 
-    # ---------------------------------------------------------------- insertion (one token per unit)
-    stream_in = datagen.DecodeStream(w, seed=w.seed)
-    kk, vv, _ = stream_in.next()
-    k1 = torch.from_numpy(np.tile(kk.view(np.int16), (L, 1, 1))).to(dev)
-    v1 = torch.from_numpy(np.tile(vv.view(np.int16), (L, 1, 1))).to(dev)
-    batched.insert(k1, v1)
-    us_insert = clock.once(lambda: batched.insert(k1, v1), 32) * 1e3
-    # a page of tokens at a time (tokens leaving the recent window): 16 different tokens per launch
-    k16_np, v16_np, _ = stream_in.take(16)                                    # [16, 1, H, D]
-    k16 = torch.from_numpy(np.tile(k16_np.view(np.int16).transpose(1, 2, 0, 3), (L, 1, 1, 1))).contiguous().to(dev)   # [L, H, 16, D]
-    v16 = torch.from_numpy(np.tile(v16_np.view(np.int16).transpose(1, 2, 0, 3), (L, 1, 1, 1))).contiguous().to(dev)
-    batched.insert_batch(k16, v16)
-    us_insert16 = clock.once(lambda: batched.insert_batch(k16, v16), 2) * 1e3
+    # ---------------------------------------------------------------- insertion
+    # 32 + 3 x 16 consecutive tokens of every layer's own decode stream (seeded like the layer's keys, so
+    # the tokens come from the distribution the layer was clustered on), one per launch and a page of 16 per
+    # launch; the C ABI is called with raw addresses so that the host is not what the launches wait for
+    from paper_2604_10539_amd import binding
+    with ThreadPoolExecutor(max_workers=min(16, L)) as ex:
+        taken = list(ex.map(lambda l: datagen.DecodeStream(w, seed=w.seed + l).take(32 + 3 * 16)[:2], range(L)))
+    k_np = np.stack([t[0][:, 0] for t in taken], 1)                             # [80, L, H, D]
+    v_np = np.stack([t[1][:, 0] for t in taken], 1)
+    tile = lambda a: torch.from_numpy(np.ascontiguousarray(a.view(np.int16).transpose(1, 2, 0, 3))).to(dev)   # -> [L, H, m, D]
+    k1, v1 = tile(k_np[:32]), tile(v_np[:32])                                   # token t at [:, :, t]
+    k1 = k1.permute(2, 0, 1, 3).contiguous()                                    # [32, L, H, D]: one launch's keys contiguous
+    v1 = v1.permute(2, 0, 1, 3).contiguous()
+    k16 = [tile(k_np[32 + 16 * r:48 + 16 * r]) for r in range(3)]               # [L, H, 16, D] each
+    v16 = [tile(v_np[32 + 16 * r:48 + 16 * r]) for r in range(3)]
+    lib_raw, hs = binding.lib(), clock.st.cuda_stream
+    step1 = L * H * D * 2
+
+    def insert_singles(lo, hi):
+        r = 0
+        for t in range(lo, hi):
+            r |= lib_raw.ice_insert(batched.handle, k1.data_ptr() + t * step1, v1.data_ptr() + t * step1, hs)
+        assert r == 0, binding.ice_last_error()
+    insert_singles(0, 8)
+    us_insert = clock.once(lambda: insert_singles(8, 32)) / 24 * 1e3
+    batched.insert_batch(k16[0], v16[0])
+
+    def insert_pages():
+        r = 0
+        for i in (1, 2):
+            r |= lib_raw.ice_insert_batch(batched.handle, k16[i].data_ptr(), v16[i].data_ptr(), 16, hs)
+        assert r == 0, binding.ice_last_error()
+    us_insert16 = clock.once(insert_pages) / 2 * 1e3
+    # the unfavourable case: every layer is given layer 0's tokens, which for the other 31 layers come from a
+    # foreign distribution and crowd into a few clusters (most tokens of a launch then depend on each other)
+    kf = torch.from_numpy(np.ascontiguousarray(np.tile(k_np[32:48, :1].view(np.int16), (1, L, 1, 1)).transpose(1, 2, 0, 3))).to(dev)
+    vf = torch.from_numpy(np.ascontiguousarray(np.tile(v_np[32:48, :1].view(np.int16), (1, L, 1, 1)).transpose(1, 2, 0, 3))).to(dev)
+    us_insert16_foreign = clock.once(lambda: batched.insert_batch(kf, vf)) * 1e3
 
     # ---------------------------------------------------------------- CPU oracle on the same step
     cpu = None
@@ -725,7 +750,11 @@ def main():
         "flush_per_step": {"us_per_step": ms_flush * 1e3,
                            "how": "same launch, one event pair per step, 1 GiB read between steps (untimed)"},
         "spread": {"batched_us_per_step": spread_batched, "sequential_us_per_layer_step": spread_seq},
-        "insert": {"us_per_call_256_units": us_insert, "us_per_call_of_16_tokens_256_units": us_insert16},
+        "insert": {"us_per_call_256_units": us_insert, "us_per_call_of_16_tokens_256_units": us_insert16,
+                   "us_per_call_of_16_crowding_tokens_256_units": us_insert16_foreign,
+                   "how": "tokens of each layer's own decode stream, 24 single-token launches and 2 launches of 16 tokens "
+                          "issued back to back between two events; crowding: layer 0's tokens given to every layer (foreign to "
+                          "31 of them: most tokens of a launch land in the same few clusters and are settled one after the other)"},
         "pages_per_unit_mean": float(n_pages.mean()),
         "datagen_s": t_gen,
         "cpu_baseline": cpu,

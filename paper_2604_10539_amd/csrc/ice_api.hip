@@ -71,6 +71,8 @@ size_t lay_out(const ice_config_t &cfg, int s, int C, char *base, Dev *out) {
     d.page_pos = (int *)take(U * MP * s * 4);
     d.cluster_tail = (int *)take(U * C * 4);
     d.cluster_cnt = (int *)take(U * C * 4);
+    d.tail_fill = (int *)take(U * C * 4);
+    d.tail_sum = (float *)take(U * C * kD * 4);
     d.cluster_sum = (float *)take(U * C * kD * 4);
     d.centroid = (float *)take(U * C * kD * 4);
     d.page_sum = (float *)take(U * MP * kD * 4);
@@ -518,6 +520,7 @@ ice_status_t ice_import_index(ice_index_t *ix, const ice_index_view_t *v, void *
     ix->dev.tk = 0;
     launch_refresh_centroids(d, 0, s);
     launch_refresh_centroids(d, 1, s);
+    launch_refresh_tails(d, s);
     if (ice_status_t st = device_status("ice_import_index")) return st;
     ix->n_tokens = v->n_tokens;
     ix->build_n = 0;  // (not the product of a build here: no stage to re-run)

@@ -161,6 +161,26 @@ void launch_refresh_centroids(const Dev &d, int cur, hipStream_t st) {
     hipLaunchKernelGGL(refresh_centroids_kernel, dim3(d.Cpad, d.U), dim3(64), 0, st, d, cur);
 }
 
+// The copy of every cluster's tail-page state that the insertions work on (fill and key sum).
+__global__ __launch_bounds__(256) void refresh_tails_kernel(Dev d) {
+    const int c = blockIdx.x * 4 + (threadIdx.x >> 6), u = blockIdx.y, lane = threadIdx.x & 63;
+    if (c >= d.C) return;
+    const size_t cl = (size_t)u * d.C + c;
+    const int tail = d.cluster_tail[cl];
+    float2 ps = make_float2(0.f, 0.f);
+    int fill = d.s;
+    if (tail >= 0) {
+        const size_t pg = (size_t)u * d.max_pages + tail;
+        fill = d.page_fill[pg];
+        ps = ((const float2 *)(d.page_sum + pg * kD))[lane];
+    }
+    ((float2 *)(d.tail_sum + cl * kD))[lane] = ps;
+    if (lane == 0) d.tail_fill[cl] = fill;
+}
+void launch_refresh_tails(const Dev &d, hipStream_t st) {
+    hipLaunchKernelGGL(refresh_tails_kernel, dim3((d.C + 3) / 4, d.U), dim3(256), 0, st, d);
+}
+
 __global__ void fill_u64_kernel(u64 *p, size_t n, u64 v) {
     for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += (size_t)gridDim.x * blockDim.x) p[i] = v;
 }
@@ -233,18 +253,6 @@ __device__ inline void argmax16(const f32x16 &x, float &m, uint32_t &idx) {
 __host__ __device__ constexpr int assign_lds_bytes(bool aug) {
     return 2 * 256 * 256 + (aug ? 2 * 256 * 32 : 0) + 2 * 256 * 8;
 }
-
-// One direct global -> LDS load of 16 bytes per lane: lane l's bytes land at lds_base + 16 l
-// (lds_base is the same for the whole wave).  Written as inline assembly so that the compiler's wait
-// insertion does not know the load: told about it, it makes the wave wait for the load before the
-// next LDS atomic that might alias its destination, i.e. within the first eighth of the tile that is
-// being computed, and the load is for the NEXT tile.  The caller waits (wait_lds_dma) before the
-// barrier that hands the destination buffer over.
-__device__ inline void lds_dma16(const uint4 *src, char *lds_base) {
-    const uint32_t base = __builtin_amdgcn_readfirstlane((uint32_t)(size_t)(__attribute__((address_space(3))) char *)lds_base);
-    asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off" ::"v"(src), "s"(base) : "memory", "m0");
-}
-__device__ inline void wait_lds_dma() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); }
 
 template <int CT, int CW, bool AUG>
 __global__ __launch_bounds__(512) void assign_kernel(const bf16_t *__restrict__ K, const bf16_t *__restrict__ cent,
@@ -917,6 +925,7 @@ void launch_paginate(const Dev &d, const bf16_t *K, const bf16_t *V, int n, hipS
     const size_t lds = (size_t)4 * d.s * kD * 2;
     if (keys_exceed_cache(d, n)) hipLaunchKernelGGL(paginate_kernel<true>, dim3((d.max_pages + 3) / 4, d.U), dim3(256), lds, st, d, K, V, n);
     else hipLaunchKernelGGL(paginate_kernel<false>, dim3((d.max_pages + 3) / 4, d.U), dim3(256), lds, st, d, K, V, n);
+    launch_refresh_tails(d, st);
 }
 
 // ------------------------------------------------------------------------------------------------

@@ -14,203 +14,722 @@ constexpr int kUnitFailed = -(1 << 30);        // arrival counter of a unit whos
 
 
 // ------------------------------------------------------------------------------------------------
-// Insertion of m tokens per unit, one after the other (Alg. 1 insertion loop; a node that outgrows
-// its page gets a new one, Sec. 4.1; m > 1 is the page-at-a-time insertion of tokens that leave the
-// recent window).  One workgroup per unit.  Per token: 15 waves scan the bf16 centroids (16 lanes x
-// 16 bytes per row, four rows per wave and load, four loads in flight) for the nearest one, lowest
-// id on ties; wave 0 then appends the key/value row to the cluster's tail page and updates, in
-// ordered fp32 (one add per quantity): page sum -> representative, cluster sum -> centroid, its bf16
-// rounding and squared norm.  The next token sees the moved centroid, exactly as m separate
-// launches would; yet its scan does not wait for the update: only ONE centroid row changes, so
-// while wave 0 appends token t the other waves scan for token t+1 over every row but that one, and
-// wave 0 adds the moved row's distance (same 16-lane arithmetic, from the row it has just formed)
-// before the barrier that ends the step.  k, v: bf16 [U, m, d].
+// Insertion (Alg. 1 insertion loop; a node that outgrows its page gets a new one, Sec. 4.1).  One
+// workgroup of 16 waves per unit.  A token goes to the nearest bf16 centroid, objective
+// ||mu~||^2 - 2 k . mu~ (with the extra coordinate when the keys are transformed, Eq. 2), lowest id
+// on ties; the dot products come off the matrix cores (v_mfma_f32_16x16x32_bf16: A = the tokens'
+// keys, one per row; B = 16 centroid rows), and every one of them comes out of the same instruction
+// sequence whichever row or column slot it sits in, so inserting m tokens in one launch and in m
+// launches leaves the same bits.  The cluster then moves (ordered fp32: sum -> centroid -> bf16 row
+// and squared norm) and the row is appended to the cluster's tail page (page sum -> representative).
 constexpr int kInsertWaves = 16;
-// (cent, cnorm: the live centroid buffer d.cent_bf16[cur] / d.cnorm[cur], which this kernel also
-// writes, hence neither const nor restrict)
-// RESIDENT (several tokens and the unit's centroids fit): the bf16 centroid rows, their norms and
-// extra coordinates are copied to LDS once and scanned from there, the moved row patched in place:
-// a token's scan then costs LDS time instead of another 256 C bytes through the CU.
-template <bool RESIDENT>
-__global__ __launch_bounds__(kInsertWaves * 64) void insert_kernel(const bf16_t *__restrict__ k, const bf16_t *__restrict__ v,
-                                                                    bf16_t *cent, float *cnorm,
-                                                                    int m, int cur, int C, int Cpad, Dev d) {  // (scalars first: preloaded)
-    extern __shared__ __align__(16) char insert_lds[];  // RESIDENT: [C][128] bf16 rows, [C] fp32 norms, [C] fp32 extra coordinates
-    __shared__ u64 best[3];  // token t's winner meets in best[t % 3]: (ordered distance, cluster id), minimum
-    __shared__ __align__(16) uint32_t moved_row[64];  // the centroid row wave 0 has just moved (bf16 pairs)
-    __shared__ float moved_norm, moved_aug;
-    const int u = blockIdx.x, tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
-    const int g = lane >> 4, ch = lane & 15;
-    // what the append needs and does not depend on the chosen cluster is requested before the scan
-    int np = d.n_pages[u];
-    int tok = d.n_tokens[u];
-    const bf16_t *cb = cent + (size_t)u * Cpad * kD;
-    const float *wn = cnorm + (size_t)u * Cpad;
-    uint4 *lrow = (uint4 *)insert_lds;
-    float *lnorm = (float *)(insert_lds + (size_t)C * kD * 2), *laug = lnorm + C;
-    if constexpr (RESIDENT) {
-        for (int x = tid; x < C * 16; x += kInsertWaves * 64) lrow[x] = ((const uint4 *)cb)[x];
-        for (int r = tid; r < C; r += kInsertWaves * 64) {
-            lnorm[r] = wn[r];
-            laug[r] = d.tk ? bf16_to_f32(d.caug[cur][(size_t)u * Cpad + r]) : 0.f;
-        }
+constexpr int kInsertTokens = 16;  // tokens per launch of the batched kernel at most (one per wave)
+
+__device__ inline float insert_objective(float w, float dot, float kaf, float ce) {
+    return __builtin_fmaf(-2.0f, __builtin_fmaf(kaf, ce, dot), w);
+}
+__device__ inline u64 insert_pack(float val, int c) { return ((u64)f32_ordered(val) << 32) | (u64)(uint32_t)c; }
+__device__ inline int insert_winner(u64 b) { return b == ~0ull ? 0 : (int)(uint32_t)b; }  // (every objective NaN: cluster 0, as an exhaustive search that never sees a smaller value)
+__device__ inline u64 readlane_u64(u64 x, int l) {
+    const uint32_t lo = (uint32_t)__builtin_amdgcn_readlane((int)(uint32_t)x, l);
+    const uint32_t hi = (uint32_t)__builtin_amdgcn_readlane((int)(uint32_t)(x >> 32), l);
+    return ((u64)hi << 32) | lo;
+}
+// minimum over the 16 lanes of a DPP row / over the wave (vector unit only, no trip through LDS)
+__device__ inline u64 row16_min_u64(u64 x) {
+#define ICE_MIN_STEP(CTRL)                                                                         \
+    do {                                                                                           \
+        const u64 y = ((u64)dpp_u32<CTRL>((uint32_t)(x >> 32)) << 32) | dpp_u32<CTRL>((uint32_t)x); \
+        x = y < x ? y : x;                                                                         \
+    } while (0)
+    ICE_MIN_STEP(0xB1);
+    ICE_MIN_STEP(0x4E);
+    ICE_MIN_STEP(0x141);
+    ICE_MIN_STEP(0x140);
+#undef ICE_MIN_STEP
+    return x;
+}
+__device__ inline u64 wave_min_u64(u64 x) {
+    x = row16_min_u64(x);
+    const u64 a = readlane_u64(x, 0), b = readlane_u64(x, 16), c = readlane_u64(x, 32), e = readlane_u64(x, 48);
+    const u64 ab = a < b ? a : b, ce = c < e ? c : e;
+    return ab < ce ? ab : ce;
+}
+// the two smallest of the wave's values (each lane brings its own two smallest, a <= b)
+__device__ inline void merge_min2(u64 &a, u64 &b, u64 pa, u64 pb) {
+    const u64 hi = a < pa ? pa : a, lo2 = b < pb ? b : pb;
+    a = a < pa ? a : pa;
+    b = hi < lo2 ? hi : lo2;
+}
+__device__ inline void wave_min2_u64(u64 &a, u64 &b) {
+#define ICE_MIN2_STEP(CTRL)                                                                          \
+    do {                                                                                             \
+        const u64 pa = ((u64)dpp_u32<CTRL>((uint32_t)(a >> 32)) << 32) | dpp_u32<CTRL>((uint32_t)a);  \
+        const u64 pb = ((u64)dpp_u32<CTRL>((uint32_t)(b >> 32)) << 32) | dpp_u32<CTRL>((uint32_t)b);  \
+        merge_min2(a, b, pa, pb);                                                                    \
+    } while (0)
+    ICE_MIN2_STEP(0xB1);
+    ICE_MIN2_STEP(0x4E);
+    ICE_MIN2_STEP(0x141);
+    ICE_MIN2_STEP(0x140);
+#undef ICE_MIN2_STEP
+    u64 ra = readlane_u64(a, 0), rb = readlane_u64(b, 0);
+    merge_min2(ra, rb, readlane_u64(a, 16), readlane_u64(b, 16));
+    merge_min2(ra, rb, readlane_u64(a, 32), readlane_u64(b, 32));
+    merge_min2(ra, rb, readlane_u64(a, 48), readlane_u64(b, 48));
+    a = ra;
+    b = rb;
+}
+// sum over the wave in a fixed order: the four row sums, then ((r0 + r1) + r2) + r3
+__device__ inline float wave_sum_rows(float x) {
+    x = row16_sum(x);
+    const float r0 = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(x), 0));
+    const float r1 = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(x), 16));
+    const float r2 = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(x), 32));
+    const float r3 = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(x), 48));
+    return ((r0 + r1) + r2) + r3;
+}
+// the four MFMAs of one 16-row tile: lane (g, n) ends with tokens 4g .. 4g+3 against column n
+__device__ inline f32x4 insert_dots(const bf16x8 (&ka)[4], const uint4 (&b)[4]) {
+    f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int ks = 0; ks < 4; ++ks)
+        acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ka[ks], __builtin_bit_cast(bf16x8, b[ks]), acc, 0, 0, 0);
+    return acc;
+}
+// what a token does to its cluster: ordered-fp32 running sums, the mean, its bf16 rounding and squared norm
+struct ClusterMove {
+    int cnt;
+    float2 cs, mu;
+    uint32_t packed;  // this lane's two bf16 coordinates of the moved row
+    float nn, es, e, ef;
+    bf16_t eb;
+};
+__device__ inline ClusterMove insert_move(int cnt_old, float2 cs, float es_old, uint32_t kw, float kaf, bool tk) {
+    ClusterMove r;
+    r.cnt = cnt_old + 1;
+    cs.x = cs.x + bf16_lo(kw);
+    cs.y = cs.y + bf16_hi(kw);
+    r.cs = cs;
+    const float fc = (float)r.cnt;
+    r.mu = make_float2(cs.x / fc, cs.y / fc);
+    const bf16_t b0 = f32_to_bf16(r.mu.x), b1 = f32_to_bf16(r.mu.y);
+    r.packed = (uint32_t)b0 | ((uint32_t)b1 << 16);
+    const float f0 = bf16_to_f32(b0), f1 = bf16_to_f32(b1);
+    r.nn = wave_sum_rows(f0 * f0 + f1 * f1);
+    r.es = 0.f; r.e = 0.f; r.ef = 0.f; r.eb = 0;
+    if (tk) {  // the cluster's extra coordinate follows its members' running mean as well
+        r.es = es_old + kaf;
+        r.e = r.es / fc;
+        r.eb = f32_to_bf16(r.e);
+        r.ef = bf16_to_f32(r.eb);
+        r.nn += r.ef * r.ef;
     }
-    const bf16_t *ku = k + (size_t)u * m * kD, *vu = v + (size_t)u * m * kD;
-    const float c2 = d.tk ? d.c2[u] : 0.f;
-    constexpr int RS = (kInsertWaves - 1) * 4;  // rows per pass of the scanning waves
-    // transformed keys (Eq. 2): the new key's extra coordinate joins every comparison
-    auto extra_of = [&](const uint4 &kq) -> bf16_t { return d.tk ? key_extra_coordinate(c2, key_sqnorm16(kq)) : (bf16_t)0; };
-    // objective of one centroid row for a key: ||mu~||^2 - 2 k . mu~ (extra coordinate included)
-    auto objective = [&](const uint4 &row, float w, float ce, const uint4 &kq, float kaf) {
-        const float dot = row16_sum(dot8(row, kq)) + kaf * ce;
-        return w - 2.0f * dot;
-    };
-    // waves 1..15: nearest row for token t among all rows but `skip`, into best[t % 3]
-    auto scan = [&](int t, int skip) {
-        const uint4 kq = ((const uint4 *)(ku + (size_t)t * kD))[ch];
-        const float kaf = bf16_to_f32(extra_of(kq));
-        float bv = INFINITY;
-        int bi = 0x7FFFFFFF;
-        for (int r0 = (wave - 1) * 4 + g; r0 < C; r0 += 4 * RS) {
-            uint4 row[4];
-            float w[4], ce[4];
-#pragma unroll
-            for (int x = 0; x < 4; ++x) {
-                const int r = r0 + x * RS;
-                if constexpr (RESIDENT) {
-                    row[x] = r < C ? lrow[r * 16 + ch] : make_uint4(0, 0, 0, 0);
-                    w[x] = r < C ? lnorm[r] : INFINITY;
-                    ce[x] = r < C ? laug[r] : 0.f;
-                } else {
-                    row[x] = r < C ? ((const uint4 *)(cb + (size_t)r * kD))[ch] : make_uint4(0, 0, 0, 0);
-                    w[x] = r < C ? wn[r] : INFINITY;
-                    ce[x] = d.tk && r < C ? bf16_to_f32(d.caug[cur][(size_t)u * Cpad + r]) : 0.f;
-                }
-            }
-#pragma unroll
-            for (int x = 0; x < 4; ++x) {  // ascending r: a later row wins only when strictly smaller
-                const float val = objective(row[x], w[x], ce[x], kq, kaf);
-                if (val < bv && r0 + x * RS != skip) { bv = val; bi = r0 + x * RS; }
-            }
+    return r;
+}
+__device__ inline void insert_store_move(const Dev &d, bf16_t *cent, float *cnorm, int u, int c, int cur, int Cpad, int lane,
+                                         const ClusterMove &mv, bool tk) {
+    const size_t cl = (size_t)u * d.C + c;
+    ((float2 *)(d.cluster_sum + cl * kD))[lane] = mv.cs;
+    ((float2 *)(d.centroid + cl * kD))[lane] = mv.mu;
+    ((uint32_t *)(cent + ((size_t)u * Cpad + c) * kD))[lane] = mv.packed;
+    if (lane == 0) {
+        cnorm[(size_t)u * Cpad + c] = mv.nn;
+        d.cluster_cnt[cl] = mv.cnt;
+        if (tk) {
+            d.csum_aug[cl] = mv.es;
+            d.cent_aug[cl] = mv.e;
+            d.caug[cur][(size_t)u * Cpad + c] = mv.eb;
         }
-        if (ch == 0 && bi != 0x7FFFFFFF) atomicMin(&best[t % 3], ((u64)f32_ordered(bv) << 32) | (u64)(uint32_t)bi);
-    };
-    if (tid < 3) best[tid] = ~0ull;
-    __syncthreads();
-    if (wave > 0) scan(0, -1);
-    __syncthreads();
-    for (int t = 0; t < m; ++t) {
-        // (no lane wins when every distance is NaN, i.e. a key with Inf / NaN coordinates: cluster 0 then,
-        // the choice of an exhaustive search that never sees a smaller value)
-        const u64 won = best[t % 3];
-        const int c = won == ~0ull ? 0 : (int)(uint32_t)won;
-        if (wave > 0) {
-            if (t + 1 < m) scan(t + 1, c);
-        } else {
-            if (lane == 0) best[(t + 2) % 3] = ~0ull;  // (token t-1's slot, read for the last time before the previous barrier)
-            const uint32_t kw = ((const uint32_t *)(ku + (size_t)t * kD))[lane];
-            const uint32_t vw = ((const uint32_t *)(vu + (size_t)t * kD))[lane];
-            const uint4 kq_now = ((const uint4 *)(ku + (size_t)t * kD))[ch];
-            const int tn = min(t + 1, m - 1);
-            const uint4 kq_next = ((const uint4 *)(ku + (size_t)tn * kD))[ch];
-            const bf16_t ka = extra_of(kq_now);
-            const float kaf = bf16_to_f32(ka);
-            const size_t cl = (size_t)u * d.C + c;
-            // two dependent round trips: what hangs on the cluster, then what hangs on its tail page
-            // (fill and page sum together; the sum is dropped when a new page is opened)
-            int tail = d.cluster_tail[cl];
-            const int cnt = d.cluster_cnt[cl] + 1;
-            float2 cs = ((const float2 *)(d.cluster_sum + cl * kD))[lane];
-            const float es_old = d.tk ? d.csum_aug[cl] : 0.f;
-            const size_t pg_old = (size_t)u * d.max_pages + max(tail, 0);
-            int fill = d.page_fill[pg_old];
-            float2 ps = ((const float2 *)(d.page_sum + pg_old * kD))[lane];
-            if (tail < 0) fill = d.s;
-            const bool fresh = fill == d.s;
-            if (fresh) { tail = np; fill = 0; ps = make_float2(0.f, 0.f); }
-            const size_t pg = (size_t)u * d.max_pages + tail;
-            const int slot = fill;
-            fill += 1;
-            ((uint32_t *)(d.Kp + (pg * d.s + slot) * kD))[lane] = kw;
-            ((uint32_t *)(d.Vp + (pg * d.s + slot) * kD))[lane] = vw;
-            const float k0 = bf16_lo(kw), k1 = bf16_hi(kw);
-            ps.x = ps.x + k0;
-            ps.y = ps.y + k1;
-            ((float2 *)(d.page_sum + pg * kD))[lane] = ps;
-            const float ff = (float)fill;
-            ((uint32_t *)(d.rep + pg * kD))[lane] = (uint32_t)f32_to_bf16(ps.x / ff) | ((uint32_t)f32_to_bf16(ps.y / ff) << 16);
-            cs.x = cs.x + k0;
-            cs.y = cs.y + k1;
-            ((float2 *)(d.cluster_sum + cl * kD))[lane] = cs;
-            const float fc = (float)cnt;
-            const float2 mu = make_float2(cs.x / fc, cs.y / fc);
-            ((float2 *)(d.centroid + cl * kD))[lane] = mu;
-            const bf16_t b0 = f32_to_bf16(mu.x), b1 = f32_to_bf16(mu.y);
-            const uint32_t packed = (uint32_t)b0 | ((uint32_t)b1 << 16);
-            ((uint32_t *)(cent + ((size_t)u * Cpad + c) * kD))[lane] = packed;
-            const float f0 = bf16_to_f32(b0), f1 = bf16_to_f32(b1);
-            float nn = wave_sum(f0 * f0 + f1 * f1);
-            float ef = 0.f;
-            if (d.tk) {  // the cluster's extra coordinate follows its members' running mean as well
-                const float es = es_old + kaf;
-                const float e = es / fc;
-                const bf16_t eb = f32_to_bf16(e);
-                ef = bf16_to_f32(eb);
-                nn += ef * ef;
-                if (lane == 0) {
-                    d.csum_aug[cl] = es;
-                    d.cent_aug[cl] = e;
-                    d.caug[cur][(size_t)u * d.Cpad + c] = eb;
-                    d.kaug[(size_t)u * d.max_tokens + tok] = ka;
-                }
-            }
-            if (lane == 0) {
-                cnorm[(size_t)u * Cpad + c] = nn;
-                d.cluster_cnt[cl] = cnt;
-                d.cluster_tail[cl] = tail;
-                d.page_fill[pg] = fill;
-                d.page_pos[pg * d.s + slot] = tok;
-                d.n_tokens[u] = tok + 1;
-                if (fresh) {
-                    d.page_cluster[pg] = c;
-                    d.n_pages[u] = np + 1;
-                }
-            }
-            if (fresh) np += 1;
-            if (t + 1 < m) {
-                // the moved row's distance to the next token, from the bits just stored (every 16-lane
-                // row of the wave computes it, the way a scanning wave would)
-                moved_row[lane] = packed;
-                if (lane == 0) { moved_norm = nn; moved_aug = ef; }
-                __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
-                const uint4 row = ((const uint4 *)moved_row)[ch];
-                const float val = objective(row, moved_norm, moved_aug, kq_next, bf16_to_f32(extra_of(kq_next)));
-                if (lane == 0 && !(val != val)) atomicMin(&best[(t + 1) % 3], ((u64)f32_ordered(val) << 32) | (u64)(uint32_t)c);
-                if constexpr (RESIDENT) {  // (the scanning waves skip this row in this step: they may see it half written)
-                    ((uint32_t *)(lrow + c * 16))[lane] = packed;
-                    if (lane == 0) { lnorm[c] = nn; laug[c] = ef; }
-                }
-            }
-        }
-        tok += 1;
-        // Token t+1's winner is complete.  Token t's updates must be visible to whoever reads them next:
-        // with the centroids in LDS that is wave 0 alone (a wave's loads follow its own earlier stores
-        // to the same address), so the stores may stay in flight; otherwise every wave re-reads the
-        // moved row from memory and the barrier waits for the stores as well.
-        if constexpr (RESIDENT) lds_barrier();
-        else __syncthreads();
     }
 }
 
-void launch_insert(const Dev &d, const bf16_t *k, const bf16_t *v, int m, int cur, hipStream_t st) {
-    const size_t lds = (size_t)d.C * (kD * 2 + 8);
-    if (m >= 2 && lds <= 150u * 1024u) {
-        allow_dynamic_lds((const void *)insert_kernel<true>, lds);
-        hipLaunchKernelGGL(insert_kernel<true>, dim3(d.U), dim3(kInsertWaves * 64), lds, st, k, v, d.cent_bf16[cur], d.cnorm[cur], m, cur,
-                           d.C, d.Cpad, d);
-        return;
+// A wave's own staging area for centroid tiles (16 rows x 256 bytes each): direct global -> LDS loads
+// of four whole rows per instruction (a quad of lanes reads 64 contiguous bytes; loading the MFMA
+// operand straight from memory would spread every quad over four rows), the 16-byte chunk c of row r
+// in slot c ^ r so that the operand reads (lane (g, n): chunk 4 ks + g of row n) are conflict-free.
+constexpr int kInsertTileBytes = 16 * kD * 2;
+__device__ inline void insert_stage_tile(const bf16_t *cb, int tile, char *stg, int lane) {
+    const int g = lane >> 4, i = lane & 15;
+#pragma unroll
+    for (int x = 0; x < 4; ++x) {
+        const int rr = 4 * x + g;
+        lds_dma16((const uint4 *)(cb + (size_t)(tile * 16 + rr) * kD) + (i ^ rr), stg + x * 1024);
     }
-    hipLaunchKernelGGL(insert_kernel<false>, dim3(d.U), dim3(kInsertWaves * 64), 0, st, k, v, d.cent_bf16[cur], d.cnorm[cur], m, cur, d.C, d.Cpad, d);
+}
+__device__ inline void insert_read_tile(const char *stg, int lane, uint4 (&b)[4]) {
+    const int g = lane >> 4, n = lane & 15;
+#pragma unroll
+    for (int ks = 0; ks < 4; ++ks) b[ks] = *(const uint4 *)(stg + n * 256 + (((4 * ks + g) ^ n) << 4));
+}
+
+// One token per unit.  Every wave scans its share of the centroid tiles (both tiles of a round
+// requested at once) and keeps its best row in registers; it then requests what hangs on THAT row
+// (count and sum of the cluster, its tail page with fill and sum: all kept beside the cluster, one
+// round trip) before the waves meet in one LDS word, so that for the wave whose row wins these loads
+// have been in flight while it waited for the others.  That wave alone carries on, with nothing
+// left to fetch: it moves the cluster and appends the row.
+// (cent, cnorm: the live centroid buffer d.cent_bf16[cur] / d.cnorm[cur], which this kernel also
+// writes, hence neither const nor restrict)
+__global__ __launch_bounds__(kInsertWaves * 64) void insert_one_kernel(const bf16_t *__restrict__ k, const bf16_t *__restrict__ v,
+                                                                        bf16_t *cent, float *cnorm, int m_total, int t0, int cur,
+                                                                        int C, int Cpad, Dev d) {  // (scalars first: preloaded)
+    extern __shared__ __align__(16) char insert_stage[];  // [16 waves][2 tiles]
+    __shared__ u64 s_best;
+    const int u = blockIdx.x, tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+    const int g = lane >> 4, i = lane & 15;
+    const bool tk = d.tk != 0;
+    char *stg = insert_stage + wave * 2 * kInsertTileBytes;
+    const bf16_t *cb = cent + (size_t)u * Cpad * kD;
+    const float *wn = cnorm + (size_t)u * Cpad;
+    const bf16_t *ku = k + ((size_t)u * m_total + t0) * kD, *vu = v + ((size_t)u * m_total + t0) * kD;
+    ICE_STAMP(40);
+    if (tid == 0) s_best = ~0ull;
+    const int tiles = (C + 15) / 16;
+    if (wave < tiles) {  // (the first round's tiles go out before anything else is asked of memory)
+        insert_stage_tile(cb, wave, stg, lane);
+        if (wave + kInsertWaves < tiles) insert_stage_tile(cb, wave + kInsertWaves, stg + kInsertTileBytes, lane);
+    }
+    bf16x8 ka[4];  // A operand: the key in row 0
+#pragma unroll
+    for (int ks = 0; ks < 4; ++ks) {  // (a load under a condition, not a choice between two addresses: no zero constant in memory)
+        uint4 w = make_uint4(0, 0, 0, 0);
+        if (i == 0) w = ((const uint4 *)ku)[ks * 4 + g];
+        ka[ks] = __builtin_bit_cast(bf16x8, w);
+    }
+    bf16_t kab = 0;
+    if (tk) kab = key_extra_coordinate(d.c2[u], key_sqnorm16(((const uint4 *)ku)[i]));
+    const float kaf = bf16_to_f32(kab);
+    u64 best = ~0ull;
+    lds_barrier();  // (s_best is set before any wave's minimum can reach it)
+    ICE_STAMP(41);
+    for (int tile = wave; tile < tiles; tile += 2 * kInsertWaves) {
+        const int tb = tile + kInsertWaves;
+        const int ra = tile * 16 + i, rb = tb * 16 + i;
+        if (tile != wave) {
+            insert_stage_tile(cb, tile, stg, lane);
+            if (tb < tiles) insert_stage_tile(cb, tb, stg + kInsertTileBytes, lane);
+        }
+        const float wa = ra < C ? wn[ra] : INFINITY, wb = tb < tiles && rb < C ? wn[rb] : INFINITY;
+        const float ea = tk && ra < C ? bf16_to_f32(d.caug[cur][(size_t)u * Cpad + ra]) : 0.f;
+        const float eb = tk && tb < tiles && rb < C ? bf16_to_f32(d.caug[cur][(size_t)u * Cpad + rb]) : 0.f;
+        wait_lds_dma();
+        ICE_STAMP(45);
+        uint4 b0[4], b1[4];
+        insert_read_tile(stg, lane, b0);
+        insert_read_tile(stg + kInsertTileBytes, lane, b1);  // (no second tile: stale rows, results unused)
+        const f32x4 a0 = insert_dots(ka, b0), a1 = insert_dots(ka, b1);
+        ICE_STAMP(46);
+        if (g == 0) {  // (row 0 of the output: the token against columns 0..15)
+            const float va = insert_objective(wa, a0[0], kaf, ea), vb = insert_objective(wb, a1[0], kaf, eb);
+            if (ra < C && !(va != va)) { const u64 key = insert_pack(va, ra); best = key < best ? key : best; }
+            if (tb < tiles && rb < C && !(vb != vb)) { const u64 key = insert_pack(vb, rb); best = key < best ? key : best; }
+        }
+    }
+    const u64 mine = readlane_u64(row16_min_u64(best), 0);  // (only row 0 of the wave holds candidates)
+    ICE_STAMP(47);
+    // what hangs on this wave's best row, requested before the waves meet
+    const int c = insert_winner(mine);
+    const size_t cl = (size_t)u * d.C + c;
+    const int cnt = d.cluster_cnt[cl];
+    const float2 cs = ((const float2 *)(d.cluster_sum + cl * kD))[lane];
+    const float es_old = tk ? d.csum_aug[cl] : 0.f;
+    int tail = d.cluster_tail[cl];
+    int fill = d.tail_fill[cl];  // (page_size when the cluster has no page)
+    float2 ps = ((const float2 *)(d.tail_sum + cl * kD))[lane];
+    const int np = d.n_pages[u], tok = d.n_tokens[u];
+    const uint32_t kw = ((const uint32_t *)ku)[lane], vw = ((const uint32_t *)vu)[lane];
+    if (lane == 0 && mine != ~0ull) atomicMin(&s_best, mine);
+    ICE_STAMP(42);
+    lds_barrier();
+    ICE_STAMP(43);
+    const u64 won = s_best;
+    if (won == ~0ull ? wave != 0 : mine != won) return;  // (every objective NaN: wave 0 carries on with cluster 0)
+    ICE_STAMP(48);
+    const ClusterMove mv = insert_move(cnt, cs, es_old, kw, kaf, tk);
+    insert_store_move(d, cent, cnorm, u, c, cur, Cpad, lane, mv, tk);
+    if (tk && lane == 0) d.kaug[(size_t)u * d.max_tokens + tok] = kab;
+    ICE_STAMP(49);
+    // the row goes to the cluster's tail page, or to a new page when that one is full or the cluster
+    // has none (the sum is dropped when a page is opened)
+    const bool fresh = fill == d.s;
+    if (fresh) { tail = np; fill = 0; ps = make_float2(0.f, 0.f); }
+    const size_t pg = (size_t)u * d.max_pages + tail;
+    ((uint32_t *)(d.Kp + (pg * d.s + fill) * kD))[lane] = kw;
+    ((uint32_t *)(d.Vp + (pg * d.s + fill) * kD))[lane] = vw;
+    ps.x = ps.x + bf16_lo(kw);
+    ps.y = ps.y + bf16_hi(kw);
+    ((float2 *)(d.page_sum + pg * kD))[lane] = ps;
+    ((float2 *)(d.tail_sum + cl * kD))[lane] = ps;
+    const float ff = (float)(fill + 1);
+    ((uint32_t *)(d.rep + pg * kD))[lane] = (uint32_t)f32_to_bf16(ps.x / ff) | ((uint32_t)f32_to_bf16(ps.y / ff) << 16);
+    if (lane == 0) {
+        d.cluster_tail[cl] = tail;
+        d.tail_fill[cl] = fill + 1;
+        d.page_fill[pg] = fill + 1;
+        d.page_pos[pg * d.s + fill] = tok;
+        d.n_tokens[u] = tok + 1;
+        if (fresh) {
+            d.page_cluster[pg] = c;
+            d.n_pages[u] = np + 1;
+        }
+    }
+    ICE_STAMP(44);
+}
+
+// Up to 16 tokens per unit, with the result of inserting them one after the other (the
+// page-at-a-time insertion of tokens that leave the recent window).  What makes the tokens depend on
+// each other is small: token t moves ONE centroid row and touches one page.  Steps:
+//   scan     all waves: D[t][c], the dot product of every token with every centroid row, into LDS.
+//            The centroids cross the CU once for all tokens.
+//   guess    wave t: token t's nearest centroid (and the runner-up) as if no token before it had
+//            moved anything, the loads that hang on that cluster (count, sum, tail page with its
+//            fill and sum: one round trip, all tokens' side by side), the cluster's move worked out
+//            on that assumption, and the moved row's dot products with all tokens (one more MFMA
+//            chain, the row in column 0).
+//   check    wave t, the earlier tokens on its lanes: against which of the earlier guessed moves
+//            token t's guess fails (same cluster guessed, or the moved row nearer than the guess).
+//   settle   wave 0, everything in registers and LDS.  Tokens whose guess fails against no move that
+//            stands are settled as guessed, whole runs at once; the others one by one: the nearest
+//            centroid given the rows moved so far is the guess, or the runner-up when the guessed
+//            row has moved, or one of the moved rows (their fresh objectives come from the dot
+//            products the movers left); only when guess and runner-up have both moved a full pass
+//            over D, which is then brought in step with the moves.  Such a token's move is worked out
+//            from the cluster's current state (in LDS for every cluster some token guessed, read
+//            from memory otherwise) and stored by wave 0, and the later guesses are checked
+//            against it.  Meanwhile wave 1 works out the page table for the case that every token
+//            goes where it guessed.
+//   commit   wave t stores its own move if it stood.
+//   append   wave t: token t's row into its cluster's tail page, or into a page opened by the
+//            first token that finds the page full (page ids in the order single insertions hand
+//            them out); the last token of a page adds the page's new keys to its sum in token
+//            order and writes the representative; the tables follow.
+// Worst case: all tokens of a launch crowd into a few clusters, and the settle step handles them one
+// after the other (about 3 us each on one wave).
+// k, v: bf16 [U, m_total, d], tokens t0 .. t0 + mt of them in this launch.
+__host__ __device__ inline int insert_row_stride(int C) { return round_up(C, 16) + 4; }  // (+4: the four token groups of a store hit different banks)
+// dynamic LDS: D [mt][stride], norms [Cr] (+ extras [Cr]), the tokens' keys and moved rows [16][64] words each,
+// per slot the cluster sum before and after the guessed move and the tail page's sum [16][64] float2 each
+__host__ __device__ inline size_t insert_fixed_lds(int C, bool tk) {
+    return (size_t)round_up(C, 16) * 4 * (tk ? 2 : 1) + 2 * kInsertTokens * 64 * 4 + 3 * kInsertTokens * 64 * 8;
+}
+
+__global__ __launch_bounds__(kInsertWaves * 64) void insert_batch_kernel(const bf16_t *__restrict__ k, const bf16_t *__restrict__ v,
+                                                                          bf16_t *cent, float *cnorm, int m_total, int t0, int mt,
+                                                                          int cur, int C, int Cpad, int stage_tiles, Dev d) {  // (scalars first: preloaded)
+    extern __shared__ __align__(16) char insert_lds[];
+    __shared__ u64 s_best[kInsertTokens];        // the guess: (ordered objective, cluster), ~0 when every objective is NaN
+    __shared__ int s_cluster[kInsertTokens];     // slot t caches the state of token t's guessed cluster
+    __shared__ int s_cnt[kInsertTokens], s_tail[kInsertTokens], s_fill[kInsertTokens];
+    __shared__ float s_es[kInsertTokens], s_es1[kInsertTokens], s_kaf[kInsertTokens];
+    __shared__ float s_nn[kInsertTokens], s_ef[kInsertTokens];  // squared norm and extra coordinate of the row token t's move forms
+    __shared__ float s_dm[kInsertTokens][kInsertTokens];        // [t'][t]: token t against the row token t' moved
+    __shared__ bf16_t s_ka[kInsertTokens];
+    __shared__ u64 s_best2[kInsertTokens];                      // the runner-up of the guess
+    __shared__ int s_fail[kInsertTokens];                       // bit t': token t's guess fails if token t' < t moves as it guessed
+    __shared__ int s_stood;                                     // bit t: token t's guessed move stands (wave t stores it); bit 16: every token went where it guessed
+    __shared__ int t_cluster[2][kInsertTokens], t_page[2][kInsertTokens], t_slot[2][kInsertTokens], t_src[2][kInsertTokens], t_pages[2];  // page_table
+    const int u = blockIdx.x, tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+    const int g = lane >> 4, i = lane & 15;
+    const bool tk = d.tk != 0;
+    const int Cr = round_up(C, 16), Cs = insert_row_stride(C);
+    float *Dl = (float *)insert_lds;
+    float *lw = Dl + (size_t)mt * Cs;
+    float *lce = lw + Cr;
+    uint32_t *lkey = (uint32_t *)(lce + (tk ? Cr : 0));
+    uint32_t *lrow = lkey + kInsertTokens * 64;  // [t][64]: the bf16 row token t's move forms (a B operand is read back from it)
+    float2 *s_cs = (float2 *)(lrow + kInsertTokens * 64);  // slot t: the guessed cluster's sum as it stands
+    float2 *s_cs1 = s_cs + kInsertTokens * 64;             // ... and after token t's guessed move
+    float2 *s_ps = s_cs1 + kInsertTokens * 64;             // ... and its tail page's sum before this launch
+    char *stg = (char *)(s_ps + kInsertTokens * 64) + wave * stage_tiles * kInsertTileBytes;  // this wave's staging area
+    const bf16_t *cb = cent + (size_t)u * Cpad * kD;
+    const float *wn = cnorm + (size_t)u * Cpad;
+    const bf16_t *ku = k + ((size_t)u * m_total + t0) * kD, *vu = v + ((size_t)u * m_total + t0) * kD;
+
+    // ---- scan (the tile loads go out first; the small tables are staged while they are in flight)
+    ICE_STAMP(32);
+    const int tiles = Cr / 16;
+    if (wave < tiles) {
+        insert_stage_tile(cb, wave, stg, lane);
+        if (stage_tiles == 2 && wave + kInsertWaves < tiles) insert_stage_tile(cb, wave + kInsertWaves, stg + kInsertTileBytes, lane);
+    }
+    bf16x8 ka[4];  // A operand: row i = token i, lane (g, i) holds its dims [32 ks + 8 g, +8)
+#pragma unroll
+    for (int ks = 0; ks < 4; ++ks) {  // (a load under a condition, not a choice between two addresses: no zero constant in memory)
+        uint4 w = make_uint4(0, 0, 0, 0);
+        if (i < mt) w = ((const uint4 *)(ku + (size_t)i * kD))[ks * 4 + g];
+        ka[ks] = __builtin_bit_cast(bf16x8, w);
+    }
+    uint32_t vw = 0;
+    if (wave < mt) {
+        lkey[wave * 64 + lane] = ((const uint32_t *)(ku + (size_t)wave * kD))[lane];
+        vw = ((const uint32_t *)(vu + (size_t)wave * kD))[lane];
+    }
+    for (int r = tid; r < Cr; r += kInsertWaves * 64) {
+        lw[r] = r < C ? wn[r] : INFINITY;
+        if (tk) lce[r] = r < C ? bf16_to_f32(d.caug[cur][(size_t)u * Cpad + r]) : 0.f;
+    }
+    auto store_dots = [&](const f32x4 &acc, int tile) {
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+            if (4 * g + j < mt) Dl[(size_t)(4 * g + j) * Cs + tile * 16 + i] = acc[j];
+    };
+    for (int tile = wave; tile < tiles; tile += stage_tiles * kInsertWaves) {
+        const int tb = tile + kInsertWaves;
+        const bool two = stage_tiles == 2 && tb < tiles;
+        if (tile != wave) {
+            insert_stage_tile(cb, tile, stg, lane);
+            if (two) insert_stage_tile(cb, tb, stg + kInsertTileBytes, lane);
+        }
+        wait_lds_dma();
+        uint4 b0[4];
+        insert_read_tile(stg, lane, b0);
+        store_dots(insert_dots(ka, b0), tile);
+        if (two) {
+            uint4 b1[4];
+            insert_read_tile(stg + kInsertTileBytes, lane, b1);
+            store_dots(insert_dots(ka, b1), tb);
+        }
+    }
+    const int np0 = d.n_pages[u], tok0 = d.n_tokens[u];
+    ICE_STAMP(33);
+    __syncthreads();
+    ICE_STAMP(34);
+
+    // nearest row for token t over all rows, from LDS
+    auto nearest = [&](int t, float kaf) {
+        u64 b = ~0ull;
+        for (int c = lane; c < C; c += 64) {
+            const float val = insert_objective(lw[c], Dl[(size_t)t * Cs + c], kaf, tk ? lce[c] : 0.f);
+            if (!(val != val)) {
+                const u64 key = insert_pack(val, c);
+                b = key < b ? key : b;
+            }
+        }
+        return wave_min_u64(b);
+    };
+    // the row a move forms against every token: lanes (g, 0) end with tokens 4g .. 4g+3
+    auto row_dots = [&](const uint32_t *row) {
+        uint4 bm[4];
+#pragma unroll
+        for (int ks = 0; ks < 4; ++ks) {
+            bm[ks] = make_uint4(0, 0, 0, 0);
+            if (i == 0) bm[ks] = ((const uint4 *)row)[ks * 4 + g];
+        }
+        return insert_dots(ka, bm);
+    };
+
+    // ---- guess
+    ClusterMove mine = {};
+    if (wave < mt) {
+        const int t = wave;
+        bf16_t kab = 0;
+        if (tk) kab = key_extra_coordinate(d.c2[u], key_sqnorm16(((const uint4 *)(ku + (size_t)t * kD))[i]));
+        const float kaf = bf16_to_f32(kab);
+        u64 b = ~0ull, b2 = ~0ull;  // the nearest row and the runner-up
+        for (int c = lane; c < C; c += 64) {
+            const float val = insert_objective(lw[c], Dl[(size_t)t * Cs + c], kaf, tk ? lce[c] : 0.f);
+            if (!(val != val)) merge_min2(b, b2, insert_pack(val, c), ~0ull);
+        }
+        wave_min2_u64(b, b2);
+        const int p = insert_winner(b);
+        const size_t cl = (size_t)u * d.C + p;
+        const int cnt = d.cluster_cnt[cl];
+        const float2 cs = ((const float2 *)(d.cluster_sum + cl * kD))[lane];
+        const float es = tk ? d.csum_aug[cl] : 0.f;
+        const int tail = d.cluster_tail[cl];
+        const int fill = d.tail_fill[cl];
+        const float2 ps = ((const float2 *)(d.tail_sum + cl * kD))[lane];
+        mine = insert_move(cnt, cs, es, lkey[t * 64 + lane], kaf, tk);
+        lrow[t * 64 + lane] = mine.packed;
+        if (lane == 0) {
+            s_best[t] = b;
+            s_best2[t] = b2;
+            s_cluster[t] = p;
+            s_cnt[t] = cnt;
+            s_es[t] = es;
+            s_es1[t] = mine.es;
+            s_tail[t] = tail;
+            s_fill[t] = fill;
+            s_kaf[t] = kaf;
+            s_ka[t] = kab;
+            s_nn[t] = mine.nn;
+            s_ef[t] = mine.ef;
+        }
+        s_cs[t * 64 + lane] = cs;
+        s_cs1[t * 64 + lane] = mine.cs;
+        s_ps[t * 64 + lane] = ps;
+        __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+        const f32x4 acc = row_dots(lrow + t * 64);
+        if (i == 0) {
+#pragma unroll
+            for (int j = 0; j < 4; ++j) s_dm[t][4 * g + j] = acc[j];
+        }
+    }
+    ICE_STAMP(35);
+    __syncthreads();
+    ICE_STAMP(36);
+
+    // ---- check, all pairs at once (wave t, the earlier tokens on its lanes): token t's guess fails against an
+    // earlier token t' that moves as IT guessed if both guessed the same cluster or the row t' moves comes
+    // out nearer to t than t's guess.  A token whose guess fails against no earlier move goes where it
+    // guessed, with the move its wave worked out.
+    if (wave < mt) {
+        const int t = wave, lt = lane < mt ? lane : 0;
+        const int p_l = s_cluster[lt];
+        const float val = insert_objective(s_nn[lt], s_dm[lt][t], s_kaf[t], s_ef[lt]);
+        const bool bad = lane < t && (p_l == s_cluster[t] || (!(val != val) && insert_pack(val, p_l) < s_best[t]));
+        const u64 bads = __ballot(bad);
+        if (lane == 0) s_fail[t] = (int)bads;
+    }
+    lds_barrier();
+
+    // Where every token goes, token j on lane j: cj = its cluster, gj / tail_s / fill_s = what slot j
+    // caches (the guessed cluster, its tail page and that page's fill before this launch).  Written to
+    // table `buf` in LDS; one wave works it out.
+    auto page_table = [&](int buf, int cj, int gj, int tail_s, int fill_s) {
+        const int s = d.s;
+        int src = -1;  // lowest slot that caches this token's cluster (-1: nobody guessed it)
+        u64 equal = 0; // tokens of the same cluster
+        for (int jj = 0; jj < mt; ++jj) {
+            const int gjj = __builtin_amdgcn_readlane(gj, jj), cjj = __builtin_amdgcn_readlane(cj, jj);
+            if (src < 0 && gjj == cj) src = jj;
+            const u64 eq = __ballot(cjj == cj);
+            if (lane == jj) equal = eq;
+        }
+        int tail0 = __shfl(tail_s, max(src, 0)), fill0 = __shfl(fill_s, max(src, 0));
+        if (lane < mt && src < 0) {
+            tail0 = d.cluster_tail[(size_t)u * d.C + cj];
+            fill0 = d.tail_fill[(size_t)u * d.C + cj];
+        }
+        const int r = __popcll(equal & ((1ull << lane) - 1ull));  // tokens of the same cluster before this one
+        const int q = fill0 + r;
+        const bool onold = q < s;
+        const int slot = onold ? q : (q - s) % s;
+        const u64 openers = __ballot(lane < mt && !onold && slot == 0);
+        u64 mm = equal;  // the token that opened this token's page: the (r - slot)-th of its cluster
+        for (int x = 0; x < r - slot; ++x) mm &= mm - 1;
+        const int opener = mm ? __ffsll((long long)mm) - 1 : lane;
+        const int page = onold ? tail0 : np0 + __popcll(openers & ((1ull << opener) - 1ull));
+        if (lane < mt) {
+            t_cluster[buf][lane] = cj;
+            t_page[buf][lane] = page;
+            t_slot[buf][lane] = slot | (onold ? 1 << 30 : 0);
+            t_src[buf][lane] = src;
+        }
+        if (lane == 0) t_pages[buf] = __popcll(openers);
+    };
+
+    if (wave == 1) {
+        // while wave 0 settles: the table as it is if every token goes where it guessed
+        const int lt = lane < mt ? lane : 0;
+        const int gj = lane < mt ? s_cluster[lt] : -1 - lane;
+        page_table(0, gj, gj, s_tail[lt], s_fill[lt]);
+    }
+    // ---- settle (wave 0; token j's entry lives on lane j)
+    if (wave == 0) {
+        const int lt = lane < mt ? lane : 0;
+        const int r_guess = lane < mt ? s_cluster[lt] : -1 - lane;  // the cluster slot `lane` caches
+        const int r_tail = s_tail[lt], r_fill = s_fill[lt];
+        const u64 r_best = s_best[lt];
+        const float r_kaf = s_kaf[lt];
+        float r_nn = s_nn[lt], r_ef = s_ef[lt];  // of the row token `lane` moves (the guessed move until settled otherwise)
+        int r_row = -1 - lane;                   // cluster token `lane` went to (set when it is settled)
+        u64 live = 0;     // the latest move of its row
+        u64 stood = 0;    // the guessed move stands (and no later token moved the cluster again): wave t stores it
+        u64 post = 0;     // slot t's cluster is in the state AFTER token t's guessed move (s_cnt + 1, s_cs1, s_es1)
+        u64 patched = 0;  // D and the norms hold this move
+        bool all_guessed = true;
+        const u64 r_best2 = s_best2[lt];
+        const int r_fail = lane < mt ? s_fail[lt] : 0;  // against the guessed moves of earlier tokens
+        u64 dfail = 0;                                  // tokens whose guess fails against a move settled here
+        const u64 all = mt >= 64 ? ~0ull : (1ull << mt) - 1ull;
+        int t = -1;
+        for (;;) {
+            // the next token whose guess does not stand, taking every token up to it as standing
+            const u64 done = t < 0 ? 0ull : (2ull << t) - 1ull;  // tokens 0 .. t
+            const u64 assumed = stood | (all & ~done);
+            const bool bad = lane > t && lane < mt &&
+                             ((((u64)(uint32_t)r_fail & assumed & ((1ull << lane) - 1ull)) != 0ull) || ((dfail >> lane) & 1ull));
+            const u64 bads = __ballot(bad);
+            const int next = bads ? __ffsll((long long)bads) - 1 : mt;
+            const u64 run = ((1ull << next) - 1ull) & ~done;  // tokens t+1 .. next-1: settled as guessed
+            stood |= run;
+            post |= run;
+            live |= run;
+            if ((run >> lane) & 1ull) r_row = r_guess;
+            if (next >= mt) break;
+            t = next;
+            const float kaf = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(r_kaf), t));
+            const u64 b1 = readlane_u64(r_best, t), b2 = readlane_u64(r_best2, t);
+            const int p = insert_winner(b1);
+            const bool is_live = (live >> lane) & 1ull;
+            // fresh objectives of the rows moved so far
+            u64 cand = ~0ull;
+            if (is_live) {
+                const float val = insert_objective(r_nn, s_dm[lt][t], kaf, r_ef);
+                if (!(val != val)) cand = insert_pack(val, r_row);
+            }
+            cand = readlane_u64(row16_min_u64(cand), 0);
+            const bool p_moved = __ballot(is_live && r_row == p) != 0ull;
+            const bool p2_moved = b2 != ~0ull && __ballot(is_live && r_row == insert_winner(b2)) != 0ull;
+            u64 b;
+            if (!p_moved) {
+                b = cand < b1 ? cand : b1;  // the guess still stands among the rows that have not moved
+            } else if (!p2_moved) {
+                b = cand < b2 ? cand : b2;  // ... or the runner-up does
+            } else {
+                // a full pass: D and the norms first catch up with the moves that are live
+                for (u64 need = live & ~patched; need; need &= need - 1) {
+                    const int j = __ffsll((long long)need) - 1;
+                    const int row = __builtin_amdgcn_readlane(r_row, j);
+                    if (lane >= t && lane < mt) Dl[(size_t)lane * Cs + row] = s_dm[j][lane];
+                    if (lane == 0) {
+                        lw[row] = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(r_nn), j));
+                        if (tk) lce[row] = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(r_ef), j));
+                    }
+                }
+                patched |= live;
+                __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+                b = nearest(t, kaf);
+            }
+            const int c = insert_winner(b);
+            all_guessed = all_guessed && c == p;
+            const u64 same_slot = __ballot(r_guess == c);  // slots that cache this cluster
+            if (c == p && !p_moved) {
+                // the guessed move stands after all: wave t stores it; slot t now stands for the state after it
+                stood |= 1ull << t;
+                post |= 1ull << t;
+            } else {
+                // (a move of this cluster that stood is superseded: everything it would store is stored here)
+                stood &= ~__ballot(lane < t && r_row == c);
+                const size_t cl = (size_t)u * d.C + c;
+                int cnt;
+                float2 cs;
+                float es_old;
+                if (same_slot & post) {
+                    const int j = __ffsll((long long)(same_slot & post)) - 1;
+                    cnt = s_cnt[j] + 1;
+                    cs = s_cs1[j * 64 + lane];
+                    es_old = s_es1[j];
+                } else if (same_slot) {
+                    const int j = __ffsll((long long)same_slot) - 1;
+                    cnt = s_cnt[j];
+                    cs = s_cs[j * 64 + lane];
+                    es_old = s_es[j];
+                } else {
+                    cnt = d.cluster_cnt[cl];
+                    cs = ((const float2 *)(d.cluster_sum + cl * kD))[lane];
+                    es_old = tk ? d.csum_aug[cl] : 0.f;
+                }
+                const ClusterMove mv = insert_move(cnt, cs, es_old, lkey[t * 64 + lane], kaf, tk);
+                insert_store_move(d, cent, cnorm, u, c, cur, Cpad, lane, mv, tk);
+                if (same_slot) {  // the lowest slot that caches this cluster holds its state from now on
+                    const int j = __ffsll((long long)same_slot) - 1;
+                    s_cs[j * 64 + lane] = mv.cs;
+                    if (lane == 0) { s_cnt[j] = mv.cnt; s_es[j] = mv.es; }
+                }
+                post &= ~same_slot;
+                if (lane == t) { r_nn = mv.nn; r_ef = mv.ef; }
+                if (t + 1 < mt) {
+                    lrow[t * 64 + lane] = mv.packed;
+                    __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+                    const f32x4 acc = row_dots(lrow + t * 64);
+                    if (i == 0) {
+#pragma unroll
+                        for (int j = 0; j < 4; ++j) s_dm[t][4 * g + j] = acc[j];
+                    }
+                    __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+                    // the later tokens against this move: same cluster guessed, or the moved row nearer than their guess
+                    const float val = insert_objective(mv.nn, s_dm[t][lt], r_kaf, mv.ef);
+                    dfail |= __ballot(lane > t && lane < mt && (r_guess == c || (!(val != val) && insert_pack(val, c) < r_best)));
+                }
+            }
+            live &= ~__ballot(is_live && r_row == c);
+            live |= 1ull << t;
+            if (lane == t) r_row = c;
+        }
+        if (lane == 0) s_stood = (int)stood | (all_guessed ? 1 << 16 : 0);
+        if (!all_guessed) page_table(1, r_row, r_guess, r_tail, r_fill);
+    }
+    ICE_STAMP(37);
+    __syncthreads();
+    ICE_STAMP(38);
+
+    // ---- commit
+    const int stood_all = s_stood;
+    if (wave < mt && ((stood_all >> wave) & 1)) insert_store_move(d, cent, cnorm, u, s_cluster[wave], cur, Cpad, lane, mine, tk);
+
+    // ---- append
+    ICE_STAMP(53);
+    if (wave < mt) {
+        const int s = d.s, t = wave, buf = (stood_all >> 16) & 1 ? 0 : 1;
+        const int lt = lane < mt ? lane : 0;
+        const int cj = lane < mt ? t_cluster[buf][lt] : -1 - lane, page = lane < mt ? t_page[buf][lt] : -1 - lane;
+        const int c = t_cluster[buf][t], pg_t = t_page[buf][t], slot_t = t_slot[buf][t] & ~(1 << 30), src_t = t_src[buf][t];
+        const bool onold_t = (t_slot[buf][t] >> 30) & 1;
+        const size_t cl = (size_t)u * d.C + c;
+        const size_t pg = (size_t)u * d.max_pages + pg_t;
+        ((uint32_t *)(d.Kp + (pg * s + slot_t) * kD))[lane] = lkey[t * 64 + lane];
+        ((uint32_t *)(d.Vp + (pg * s + slot_t) * kD))[lane] = vw;
+        if (lane == 0) {
+            d.page_pos[pg * s + slot_t] = tok0 + t;
+            if (tk) d.kaug[(size_t)u * d.max_tokens + tok0 + t] = s_ka[t];
+        }
+        const u64 members = __ballot(page == pg_t);
+        if ((members >> t) == 1ull) {  // the page's last token of this launch: its sum and representative
+            float2 ps = make_float2(0.f, 0.f);
+            // (the page's own sum when nobody cached it: the cluster's copy may already belong to a later page)
+            if (onold_t) ps = src_t >= 0 ? s_ps[src_t * 64 + lane] : ((const float2 *)(d.page_sum + pg * kD))[lane];
+            for (u64 hm = members; hm; hm &= hm - 1) {  // ascending token order, one add per key
+                const uint32_t kwj = lkey[(__ffsll((long long)hm) - 1) * 64 + lane];
+                ps.x = ps.x + bf16_lo(kwj);
+                ps.y = ps.y + bf16_hi(kwj);
+            }
+            ((float2 *)(d.page_sum + pg * kD))[lane] = ps;
+            const float ff = (float)(slot_t + 1);
+            ((uint32_t *)(d.rep + pg * kD))[lane] = (uint32_t)f32_to_bf16(ps.x / ff) | ((uint32_t)f32_to_bf16(ps.y / ff) << 16);
+            if (lane == 0) {
+                d.page_fill[pg] = slot_t + 1;
+                if (!onold_t) d.page_cluster[pg] = c;
+            }
+            const u64 same_cluster = __ballot(cj == c);
+            if ((same_cluster >> t) == 1ull) {  // ... and the cluster's last: this page is its tail from now on
+                ((float2 *)(d.tail_sum + cl * kD))[lane] = ps;
+                if (lane == 0) {
+                    d.cluster_tail[cl] = pg_t;
+                    d.tail_fill[cl] = slot_t + 1;
+                }
+            }
+        }
+        if (t == 0 && lane == 0) {
+            d.n_pages[u] = np0 + t_pages[buf];
+            d.n_tokens[u] = tok0 + mt;
+        }
+    }
+    ICE_STAMP(55);
+}
+
+void launch_insert(const Dev &d, const bf16_t *k, const bf16_t *v, int m, int cur, hipStream_t st) {
+    // LDS of the batched kernel: the fixed tables, one staging tile per wave at least, a row of D per token
+    const size_t budget = 156u * 1024u, stage1 = (size_t)kInsertWaves * kInsertTileBytes;
+    const size_t fixed = insert_fixed_lds(d.C, d.tk != 0), row = (size_t)insert_row_stride(d.C) * 4;
+    const int cap = (int)std::min<size_t>(kInsertTokens, (budget - fixed - stage1) / row);  // >= 1 up to 8192 clusters
+    const size_t one_lds = 2 * stage1;
+    for (int t0 = 0; t0 < m; t0 += std::max(cap, 1)) {
+        const int mt = std::min(std::max(cap, 1), m - t0);
+        if (mt == 1) {
+            allow_dynamic_lds((const void *)insert_one_kernel, one_lds);
+            hipLaunchKernelGGL(insert_one_kernel, dim3(d.U), dim3(kInsertWaves * 64), one_lds, st, k, v, d.cent_bf16[cur], d.cnorm[cur], m,
+                               t0, cur, d.C, d.Cpad, d);
+            continue;
+        }
+        const int stage_tiles = fixed + mt * row + 2 * stage1 <= budget ? 2 : 1;
+        const size_t lds = fixed + mt * row + stage_tiles * stage1;
+        allow_dynamic_lds((const void *)insert_batch_kernel, lds);
+        hipLaunchKernelGGL(insert_batch_kernel, dim3(d.U), dim3(kInsertWaves * 64), lds, st, k, v, d.cent_bf16[cur], d.cnorm[cur], m, t0,
+                           mt, cur, d.C, d.Cpad, stage_tiles, d);
+    }
 }
 
 // ------------------------------------------------------------------------------------------------

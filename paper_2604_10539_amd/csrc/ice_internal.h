@@ -33,6 +33,10 @@ struct Dev {
     int *page_cluster, *page_fill; // [U][max_pages]
     int *page_pos;              // [U][max_pages][s]
     int *cluster_tail, *cluster_cnt; // [U][C]
+    // what an insertion needs of a cluster's tail page, kept beside the cluster so that one round trip
+    // fetches it (derived from the page tables by launch_refresh_tails; kept in step by the insertions)
+    int *tail_fill;             // [U][C] tokens in the tail page; page_size when the cluster has no page
+    float *tail_sum;            // [U][C][128] the tail page's fp32 key sum (page_sum of that page)
     float *cluster_sum, *centroid;   // [U][C][128]
     float *page_sum;            // [U][max_pages][128]
     bf16_t *rep;                // [U][max_pages][128]
@@ -100,6 +104,7 @@ void launch_sort(const Dev &d, int n, float *best_out_or_null, int *assign_out_o
 void launch_means(const Dev &d, const bf16_t *K, int n, int cur, hipStream_t st);
 void launch_paginate(const Dev &d, const bf16_t *K, const bf16_t *V, int n, hipStream_t st);
 void launch_refresh_centroids(const Dev &d, int cur, hipStream_t st);
+void launch_refresh_tails(const Dev &d, hipStream_t st);  // tail_fill / tail_sum from the page tables (after a build or an import)
 void launch_insert(const Dev &d, const bf16_t *k, const bf16_t *v, int m, int cur, hipStream_t st);
 // scores + top-P selection (+ attention when out != nullptr) in one launch
 // np_hint: host-side upper bound of the live pages per unit (tokens / page_size + clusters)
@@ -243,6 +248,19 @@ __device__ inline void store16(uint4 *p, const uint4 &w) {
     if constexpr (STREAM) store16_stream(p, w);
     else *p = w;
 }
+
+// One direct global -> LDS load of 16 bytes per lane: lane l's bytes land at lds_base + 16 l
+// (lds_base is the same for the whole wave).  Written as inline assembly so that the compiler's wait
+// insertion does not know the load: told about it, it makes the wave wait for the load before the
+// next LDS access that might alias its destination, which for a double-buffered tile is far too
+// early.  The caller waits (wait_lds_dma) before the data is read, and before any barrier that
+// hands the destination buffer over.
+__device__ inline void lds_dma16(const uint4 *src, char *lds_base) {
+    const uint32_t base = __builtin_amdgcn_readfirstlane((uint32_t)(size_t)(__attribute__((address_space(3))) char *)lds_base);
+    asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off" ::"v"(src), "s"(base) : "memory", "m0");
+}
+__device__ inline void wait_lds_dma() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); }
+
 
 __device__ inline float key_sqnorm16(const uint4 &w) {  // this lane's 8 dims; summed over the 16-lane row
     float t = 0.f;

@@ -560,26 +560,33 @@ def test_hier_select_argument_errors():
 
 
 @pytest.mark.gpu
-@pytest.mark.parametrize("kw,m", [
-    (dict(n_tokens=2000, n_clusters=24, n_kv_heads=2, n_components=16, drift=0.01), 16),
-    (dict(n_tokens=600, n_clusters=3, n_kv_heads=3, page_size=32, n_components=2, drift=0.02), 32),   # same cluster again and again
-    (dict(n_tokens=900, n_clusters=40, n_kv_heads=1, group_size=8, n_components=8), 5),
+@pytest.mark.parametrize("kw,m,mode", [
+    (dict(n_tokens=2000, n_clusters=24, n_kv_heads=2, n_components=16, drift=0.01), 16, "foreign"),
+    (dict(n_tokens=600, n_clusters=3, n_kv_heads=3, page_size=32, n_components=2, drift=0.02), 32, "foreign"),   # same cluster again and again
+    (dict(n_tokens=900, n_clusters=40, n_kv_heads=1, group_size=8, n_components=8), 5, "foreign"),
+    (dict(n_tokens=4000, n_clusters=200, n_kv_heads=2, n_components=100, drift=0.01), 16, "own"),      # mostly one token per cluster: the guesses stand
+    (dict(n_tokens=6000, n_clusters=1500, n_kv_heads=1, n_components=64), 16, "own"),                  # many clusters: fewer tokens per launch, one staging tile per wave
+    (dict(n_tokens=1500, n_clusters=20, n_kv_heads=2, n_components=10), 16, "same"),                   # 16 copies of one key: one cluster, pages overflow inside a launch
 ])
-def test_insert_batch_equals_one_by_one(kw, m):
+def test_insert_batch_equals_one_by_one(kw, m, mode):
     """m tokens in one launch leave the index bit for bit as m single insertions do (each token sees
-    the centroid the previous one moved, pages fill and open in the same order)."""
+    the centroid the previous one moved, pages fill and open in the same order).  foreign: the tokens
+    come from other centres than the index was built on and crowd into few clusters; own: from the
+    index's own stream; same: every launch repeats one key."""
     w = datagen.small(**kw)
     rounds = 4
     ix_a, K, V, _ = _mk(w, T=2, extra=rounds * m)
     ix_b, _, _, _ = _mk(w, T=2, extra=rounds * m)
     ix_a.build_index(up(K), up(V))
     ix_b.build_index(up(K), up(V))
-    stream = datagen.DecodeStream(w, seed=5)
+    stream = datagen.DecodeStream(w, seed=5 if mode == "foreign" else None)
     U = ix_a.U
     for _ in range(rounds):
         ks, vs = [], []
-        for _ in range(m):
+        for j in range(m):
             k, v, _ = stream.next()
+            if mode == "same" and j > 0:
+                k = ks[0].reshape(k.shape).copy()
             ix_a.insert(up(k), up(v))
             ks.append(k.reshape(U, D))
             vs.append(v.reshape(U, D))
@@ -609,6 +616,45 @@ def test_insert_batch_equals_one_by_one(kw, m):
     with pytest.raises(IceError) as e:
         ix_b.insert_batch(up(kb[:, :, :1]), up(vb[:, :, :1]))
     assert e.value.status == b.ICE_ERR_CAPACITY
+
+
+@pytest.mark.gpu
+def test_insert_after_import_equals_insert_after_build():
+    """What the insertions keep beside every cluster (its tail page's fill and key sum) is rebuilt from
+    the page tables when an index is imported: the same tokens inserted into the built index and into
+    an import of its exported state leave the same bits, one at a time and a page at a time."""
+    from paper_2604_10539_amd import IceIndex
+    w = datagen.small(n_tokens=3000, n_clusters=50, n_kv_heads=2, n_components=30, drift=0.01)
+    extra = 48
+    ix_a, K, V, _ = _mk(w, T=2, extra=extra)
+    ix_a.build_index(up(K), up(V))
+    ix_b = IceIndex(w.batch, w.n_kv_heads, w.group_size, w.n_tokens + extra, w.page_size, w.n_clusters, kmeans_iters=2)
+    from paper_2604_10539_amd.binding import IMPORT_FIELDS
+    exa = ix_a.export()
+    ix_b.import_arrays({name: exa[name].clone() for name in IMPORT_FIELDS}, w.n_tokens)
+    stream = datagen.DecodeStream(w)
+    U = ix_a.U
+    ks, vs, _ = stream.take(extra)
+    for t in range(16):
+        for ix in (ix_a, ix_b):
+            ix.insert(up(ks[t]), up(vs[t]))
+    for r in (1, 2):
+        kb = up(np.ascontiguousarray(ks[16 * r:16 * r + 16].transpose(1, 2, 0, 3)))
+        vb = up(np.ascontiguousarray(vs[16 * r:16 * r + 16].transpose(1, 2, 0, 3)))
+        for ix in (ix_a, ix_b):
+            ix.insert_batch(kb, vb)
+    ea, eb = export_np(ix_a), export_np(ix_b)
+    assert np.array_equal(ea["n_pages"], eb["n_pages"])
+    for u in range(U):
+        npg = int(ea["n_pages"][u])
+        live = valid_slot_mask(ea["page_fill"][u, :npg], w.page_size)
+        for name in STATE_FIELDS:
+            a, b = ea[name][u], eb[name][u]
+            if name in ("Kp", "Vp", "page_pos"):
+                a, b = a[:npg][live], b[:npg][live]
+            elif name in ("page_cluster", "page_fill", "page_sum", "rep"):
+                a, b = a[:npg], b[:npg]
+            assert np.array_equal(np.ascontiguousarray(a).view(np.uint8), np.ascontiguousarray(b).view(np.uint8)), name
 
 
 # ----------------------------------------------------------------------------------------- resident tokens
