@@ -20,13 +20,15 @@ FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-I" + os.path.j
          "-Wall", "-Wno-unused-result", "-Wno-inline-asm"]
 
 
-def build_library(verbose: bool = False) -> str:
-    """Compile every source (always, also when a library is already there) and link."""
-    os.makedirs(OBJ_DIR, exist_ok=True)
+def build_library(verbose: bool = False, extra_flags=(), lib_path: str = LIB, obj_dir: str = OBJ_DIR) -> str:
+    """Compile every source (always, also when a library is already there) and link.  extra_flags,
+    lib_path and obj_dir are for variants that must not replace the product library (the build with
+    in-kernel time stamps of phase_stamps.py)."""
+    os.makedirs(obj_dir, exist_ok=True)
 
     def compile_one(src: str) -> str:
-        obj = os.path.join(OBJ_DIR, src.replace(".hip", ".o"))
-        cmd = [HIPCC, *FLAGS, "-c", os.path.join(CSRC, src), "-o", obj]
+        obj = os.path.join(obj_dir, src.replace(".hip", ".o"))
+        cmd = [HIPCC, *FLAGS, *extra_flags, "-c", os.path.join(CSRC, src), "-o", obj]
         r = subprocess.run(cmd, capture_output=True, text=True)
         if r.returncode != 0:
             raise RuntimeError("hipcc failed for %s:\n%s" % (src, r.stderr))
@@ -36,11 +38,11 @@ def build_library(verbose: bool = False) -> str:
 
     with ThreadPoolExecutor(max_workers=len(SOURCES)) as ex:
         objs = list(ex.map(compile_one, SOURCES))
-    r = subprocess.run([HIPCC, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", LIB, *objs],
+    r = subprocess.run([HIPCC, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", lib_path, *objs],
                        capture_output=True, text=True)
     if r.returncode != 0:
         raise RuntimeError("link failed:\n" + r.stderr)
-    return LIB
+    return lib_path
 
 
 if __name__ == "__main__":

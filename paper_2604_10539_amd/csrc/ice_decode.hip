@@ -127,7 +127,7 @@ __device__ inline ClusterMove insert_move(int cnt_old, float2 cs, float es_old, 
     }
     return r;
 }
-__device__ inline void insert_store_move(const Dev &d, bf16_t *cent, float *cnorm, int u, int c, int cur, int Cpad, int lane,
+__device__ inline void insert_store_move(const Dev &d, bf16_t *cent, float *cnorm, bf16_t *caug_cur, int u, int c, int Cpad, int lane,
                                          const ClusterMove &mv, bool tk) {
     const size_t cl = (size_t)u * d.C + c;
     ((float2 *)(d.cluster_sum + cl * kD))[lane] = mv.cs;
@@ -139,7 +139,7 @@ __device__ inline void insert_store_move(const Dev &d, bf16_t *cent, float *cnor
         if (tk) {
             d.csum_aug[cl] = mv.es;
             d.cent_aug[cl] = mv.e;
-            d.caug[cur][(size_t)u * Cpad + c] = mv.eb;
+            caug_cur[(size_t)u * Cpad + c] = mv.eb;
         }
     }
 }
@@ -173,12 +173,11 @@ __device__ inline void insert_read_tile(const char *stg, int lane, uint4 (&b)[4]
 // writes, hence neither const nor restrict)
 __global__ __launch_bounds__(kInsertWaves * 64) void insert_one_kernel(const bf16_t *__restrict__ k, const bf16_t *__restrict__ v,
                                                                         bf16_t *cent, float *cnorm, int m_total, int t0, int cur,
-                                                                        int C, int Cpad, Dev d) {  // (scalars first: preloaded)
+                                                                        int C, int Cpad, int tk_arg, Dev d_arg) {  // (scalars first: preloaded)
     extern __shared__ __align__(16) char insert_stage[];  // [16 waves][2 tiles]
     __shared__ u64 s_best;
     const int u = blockIdx.x, tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
     const int g = lane >> 4, i = lane & 15;
-    const bool tk = d.tk != 0;
     char *stg = insert_stage + wave * 2 * kInsertTileBytes;
     const bf16_t *cb = cent + (size_t)u * Cpad * kD;
     const float *wn = cnorm + (size_t)u * Cpad;
@@ -197,6 +196,12 @@ __global__ __launch_bounds__(kInsertWaves * 64) void insert_one_kernel(const bf1
         if (i == 0) w = ((const uint4 *)ku)[ks * 4 + g];
         ka[ks] = __builtin_bit_cast(bf16x8, w);
     }
+    // The other arguments are fetched here, once, while tiles and key are on their way (waiting for them
+    // only after the scan measured slower: their loads are then issued there as well).
+    const bool tk = tk_arg != 0;
+    Dev d;
+    bf16_t *caug_cur;
+    pin_insert_fields(d, d_arg, cur, caug_cur);
     bf16_t kab = 0;
     if (tk) kab = key_extra_coordinate(d.c2[u], key_sqnorm16(((const uint4 *)ku)[i]));
     const float kaf = bf16_to_f32(kab);
@@ -211,8 +216,8 @@ __global__ __launch_bounds__(kInsertWaves * 64) void insert_one_kernel(const bf1
             if (tb < tiles) insert_stage_tile(cb, tb, stg + kInsertTileBytes, lane);
         }
         const float wa = ra < C ? wn[ra] : INFINITY, wb = tb < tiles && rb < C ? wn[rb] : INFINITY;
-        const float ea = tk && ra < C ? bf16_to_f32(d.caug[cur][(size_t)u * Cpad + ra]) : 0.f;
-        const float eb = tk && tb < tiles && rb < C ? bf16_to_f32(d.caug[cur][(size_t)u * Cpad + rb]) : 0.f;
+        const float ea = tk && ra < C ? bf16_to_f32(caug_cur[(size_t)u * Cpad + ra]) : 0.f;
+        const float eb = tk && tb < tiles && rb < C ? bf16_to_f32(caug_cur[(size_t)u * Cpad + rb]) : 0.f;
         wait_lds_dma();
         ICE_STAMP(45);
         uint4 b0[4], b1[4];
@@ -247,7 +252,7 @@ __global__ __launch_bounds__(kInsertWaves * 64) void insert_one_kernel(const bf1
     if (won == ~0ull ? wave != 0 : mine != won) return;  // (every objective NaN: wave 0 carries on with cluster 0)
     ICE_STAMP(48);
     const ClusterMove mv = insert_move(cnt, cs, es_old, kw, kaf, tk);
-    insert_store_move(d, cent, cnorm, u, c, cur, Cpad, lane, mv, tk);
+    insert_store_move(d, cent, cnorm, caug_cur, u, c, Cpad, lane, mv, tk);
     if (tk && lane == 0) d.kaug[(size_t)u * d.max_tokens + tok] = kab;
     ICE_STAMP(49);
     // the row goes to the cluster's tail page, or to a new page when that one is full or the cluster
@@ -316,7 +321,8 @@ __host__ __device__ inline size_t insert_fixed_lds(int C, bool tk) {
 
 __global__ __launch_bounds__(kInsertWaves * 64) void insert_batch_kernel(const bf16_t *__restrict__ k, const bf16_t *__restrict__ v,
                                                                           bf16_t *cent, float *cnorm, int m_total, int t0, int mt,
-                                                                          int cur, int C, int Cpad, int stage_tiles, Dev d) {  // (scalars first: preloaded)
+                                                                          int cur, int C, int Cpad, int stage_tiles, int tk_arg,
+                                                                          Dev d_arg) {  // (scalars first: preloaded)
     extern __shared__ __align__(16) char insert_lds[];
     __shared__ u64 s_best[kInsertTokens];        // the guess: (ordered objective, cluster), ~0 when every objective is NaN
     __shared__ int s_cluster[kInsertTokens];     // slot t caches the state of token t's guessed cluster
@@ -331,17 +337,8 @@ __global__ __launch_bounds__(kInsertWaves * 64) void insert_batch_kernel(const b
     __shared__ int t_cluster[2][kInsertTokens], t_page[2][kInsertTokens], t_slot[2][kInsertTokens], t_src[2][kInsertTokens], t_pages[2];  // page_table
     const int u = blockIdx.x, tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
     const int g = lane >> 4, i = lane & 15;
-    const bool tk = d.tk != 0;
     const int Cr = round_up(C, 16), Cs = insert_row_stride(C);
-    float *Dl = (float *)insert_lds;
-    float *lw = Dl + (size_t)mt * Cs;
-    float *lce = lw + Cr;
-    uint32_t *lkey = (uint32_t *)(lce + (tk ? Cr : 0));
-    uint32_t *lrow = lkey + kInsertTokens * 64;  // [t][64]: the bf16 row token t's move forms (a B operand is read back from it)
-    float2 *s_cs = (float2 *)(lrow + kInsertTokens * 64);  // slot t: the guessed cluster's sum as it stands
-    float2 *s_cs1 = s_cs + kInsertTokens * 64;             // ... and after token t's guessed move
-    float2 *s_ps = s_cs1 + kInsertTokens * 64;             // ... and its tail page's sum before this launch
-    char *stg = (char *)(s_ps + kInsertTokens * 64) + wave * stage_tiles * kInsertTileBytes;  // this wave's staging area
+    char *stg = insert_lds + wave * stage_tiles * kInsertTileBytes;  // this wave's staging area (first in LDS: placed by preloaded arguments alone)
     const bf16_t *cb = cent + (size_t)u * Cpad * kD;
     const float *wn = cnorm + (size_t)u * Cpad;
     const bf16_t *ku = k + ((size_t)u * m_total + t0) * kD, *vu = v + ((size_t)u * m_total + t0) * kD;
@@ -360,6 +357,19 @@ __global__ __launch_bounds__(kInsertWaves * 64) void insert_batch_kernel(const b
         if (i < mt) w = ((const uint4 *)(ku + (size_t)i * kD))[ks * 4 + g];
         ka[ks] = __builtin_bit_cast(bf16x8, w);
     }
+    // The other arguments are fetched here, once, while tiles and keys are on their way.
+    const bool tk = tk_arg != 0;
+    Dev d;
+    bf16_t *caug_cur;
+    pin_insert_fields(d, d_arg, cur, caug_cur);
+    float *Dl = (float *)(insert_lds + kInsertWaves * stage_tiles * kInsertTileBytes);
+    float *lw = Dl + (size_t)mt * Cs;
+    float *lce = lw + Cr;
+    uint32_t *lkey = (uint32_t *)(lce + (tk ? Cr : 0));
+    uint32_t *lrow = lkey + kInsertTokens * 64;  // [t][64]: the bf16 row token t's move forms (a B operand is read back from it)
+    float2 *s_cs = (float2 *)(lrow + kInsertTokens * 64);  // slot t: the guessed cluster's sum as it stands
+    float2 *s_cs1 = s_cs + kInsertTokens * 64;             // ... and after token t's guessed move
+    float2 *s_ps = s_cs1 + kInsertTokens * 64;             // ... and its tail page's sum before this launch
     uint32_t vw = 0;
     if (wave < mt) {
         lkey[wave * 64 + lane] = ((const uint32_t *)(ku + (size_t)wave * kD))[lane];
@@ -367,7 +377,7 @@ __global__ __launch_bounds__(kInsertWaves * 64) void insert_batch_kernel(const b
     }
     for (int r = tid; r < Cr; r += kInsertWaves * 64) {
         lw[r] = r < C ? wn[r] : INFINITY;
-        if (tk) lce[r] = r < C ? bf16_to_f32(d.caug[cur][(size_t)u * Cpad + r]) : 0.f;
+        if (tk) lce[r] = r < C ? bf16_to_f32(caug_cur[(size_t)u * Cpad + r]) : 0.f;
     }
     auto store_dots = [&](const f32x4 &acc, int tile) {
 #pragma unroll
@@ -623,7 +633,7 @@ __global__ __launch_bounds__(kInsertWaves * 64) void insert_batch_kernel(const b
                     es_old = tk ? d.csum_aug[cl] : 0.f;
                 }
                 const ClusterMove mv = insert_move(cnt, cs, es_old, lkey[t * 64 + lane], kaf, tk);
-                insert_store_move(d, cent, cnorm, u, c, cur, Cpad, lane, mv, tk);
+                insert_store_move(d, cent, cnorm, caug_cur, u, c, Cpad, lane, mv, tk);
                 if (same_slot) {  // the lowest slot that caches this cluster holds its state from now on
                     const int j = __ffsll((long long)same_slot) - 1;
                     s_cs[j * 64 + lane] = mv.cs;
@@ -658,7 +668,7 @@ __global__ __launch_bounds__(kInsertWaves * 64) void insert_batch_kernel(const b
 
     // ---- commit
     const int stood_all = s_stood;
-    if (wave < mt && ((stood_all >> wave) & 1)) insert_store_move(d, cent, cnorm, u, s_cluster[wave], cur, Cpad, lane, mine, tk);
+    if (wave < mt && ((stood_all >> wave) & 1)) insert_store_move(d, cent, cnorm, caug_cur, u, s_cluster[wave], Cpad, lane, mine, tk);
 
     // ---- append
     ICE_STAMP(53);
@@ -721,14 +731,14 @@ void launch_insert(const Dev &d, const bf16_t *k, const bf16_t *v, int m, int cu
         if (mt == 1) {
             allow_dynamic_lds((const void *)insert_one_kernel, one_lds);
             hipLaunchKernelGGL(insert_one_kernel, dim3(d.U), dim3(kInsertWaves * 64), one_lds, st, k, v, d.cent_bf16[cur], d.cnorm[cur], m,
-                               t0, cur, d.C, d.Cpad, d);
+                               t0, cur, d.C, d.Cpad, d.tk, d);
             continue;
         }
         const int stage_tiles = fixed + mt * row + 2 * stage1 <= budget ? 2 : 1;
         const size_t lds = fixed + mt * row + stage_tiles * stage1;
         allow_dynamic_lds((const void *)insert_batch_kernel, lds);
         hipLaunchKernelGGL(insert_batch_kernel, dim3(d.U), dim3(kInsertWaves * 64), lds, st, k, v, d.cent_bf16[cur], d.cnorm[cur], m, t0,
-                           mt, cur, d.C, d.Cpad, stage_tiles, d);
+                           mt, cur, d.C, d.Cpad, stage_tiles, d.tk, d);
     }
 }
 

@@ -262,6 +262,27 @@ __device__ inline void lds_dma16(const uint4 *src, char *lds_base) {
 __device__ inline void wait_lds_dma() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); }
 
 
+// Kernel arguments beyond the preloaded dwords are fetched from memory where the compiler places the
+// scalar load, which by default is next to each use: a load (and its wait) per use site, several of them
+// on the critical path of a latency-bound kernel.  Pinning a value makes it opaque from here on, so it
+// is fetched once, before this point, and then lives in a scalar register.
+#define ICE_PIN(x) asm volatile("" : "+s"(x) : : "memory")
+#define ICE_PIN_FIELD(dst, src, f) do { auto pinned_ = (src).f; ICE_PIN(pinned_); (dst).f = pinned_; } while (0)
+// the fields of Dev that the insertion kernels use (the others stay unset)
+__device__ inline void pin_insert_fields(Dev &d, const Dev &a, int cur, bf16_t *&caug_cur) {
+    caug_cur = cur ? a.caug[1] : a.caug[0];
+    ICE_PIN(caug_cur);
+    ICE_PIN_FIELD(d, a, s); ICE_PIN_FIELD(d, a, C); ICE_PIN_FIELD(d, a, Cpad); ICE_PIN_FIELD(d, a, max_pages);
+    ICE_PIN_FIELD(d, a, max_tokens); ICE_PIN_FIELD(d, a, tk);
+    ICE_PIN_FIELD(d, a, Kp); ICE_PIN_FIELD(d, a, Vp); ICE_PIN_FIELD(d, a, page_cluster); ICE_PIN_FIELD(d, a, page_fill);
+    ICE_PIN_FIELD(d, a, page_pos); ICE_PIN_FIELD(d, a, cluster_tail); ICE_PIN_FIELD(d, a, cluster_cnt);
+    ICE_PIN_FIELD(d, a, tail_fill); ICE_PIN_FIELD(d, a, tail_sum); ICE_PIN_FIELD(d, a, cluster_sum);
+    ICE_PIN_FIELD(d, a, centroid); ICE_PIN_FIELD(d, a, page_sum); ICE_PIN_FIELD(d, a, rep);
+    ICE_PIN_FIELD(d, a, n_pages); ICE_PIN_FIELD(d, a, n_tokens);
+    ICE_PIN_FIELD(d, a, kaug); ICE_PIN_FIELD(d, a, cent_aug); ICE_PIN_FIELD(d, a, csum_aug); ICE_PIN_FIELD(d, a, c2);
+    // (caug is picked by the live buffer index at the call: an array indexed at run time would put the copy into scratch memory)
+}
+
 __device__ inline float key_sqnorm16(const uint4 &w) {  // this lane's 8 dims; summed over the 16-lane row
     float t = 0.f;
     t += bf16_lo(w.x) * bf16_lo(w.x); t += bf16_hi(w.x) * bf16_hi(w.x);
