@@ -600,6 +600,7 @@ def main():
     # the tokens come from the distribution the layer was clustered on), one per launch and a page of 16 per
     # launch; the C ABI is called with raw addresses so that the host is not what the launches wait for
     from paper_2604_10539_amd import binding
+    ins_ix = rot[2]          # (a copy of the index: the one the oracle is compared with stays as built)
     with ThreadPoolExecutor(max_workers=min(16, L)) as ex:
         taken = list(ex.map(lambda l: datagen.DecodeStream(w, seed=w.seed + l).take(32 + 3 * 16)[:2], range(L)))
     k_np = np.stack([t[0][:, 0] for t in taken], 1)                             # [80, L, H, D]
@@ -616,23 +617,23 @@ def main():
     def insert_singles(lo, hi):
         r = 0
         for t in range(lo, hi):
-            r |= lib_raw.ice_insert(batched.handle, k1.data_ptr() + t * step1, v1.data_ptr() + t * step1, hs)
+            r |= lib_raw.ice_insert(ins_ix.handle, k1.data_ptr() + t * step1, v1.data_ptr() + t * step1, hs)
         assert r == 0, binding.ice_last_error()
     insert_singles(0, 8)
     us_insert = clock.once(lambda: insert_singles(8, 32)) / 24 * 1e3
-    batched.insert_batch(k16[0], v16[0])
+    ins_ix.insert_batch(k16[0], v16[0])
 
     def insert_pages():
         r = 0
         for i in (1, 2):
-            r |= lib_raw.ice_insert_batch(batched.handle, k16[i].data_ptr(), v16[i].data_ptr(), 16, hs)
+            r |= lib_raw.ice_insert_batch(ins_ix.handle, k16[i].data_ptr(), v16[i].data_ptr(), 16, hs)
         assert r == 0, binding.ice_last_error()
     us_insert16 = clock.once(insert_pages) / 2 * 1e3
     # the unfavourable case: every layer is given layer 0's tokens, which for the other 31 layers come from a
     # foreign distribution and crowd into a few clusters (most tokens of a launch then depend on each other)
     kf = torch.from_numpy(np.ascontiguousarray(np.tile(k_np[32:48, :1].view(np.int16), (1, L, 1, 1)).transpose(1, 2, 0, 3))).to(dev)
     vf = torch.from_numpy(np.ascontiguousarray(np.tile(v_np[32:48, :1].view(np.int16), (1, L, 1, 1)).transpose(1, 2, 0, 3))).to(dev)
-    us_insert16_foreign = clock.once(lambda: batched.insert_batch(kf, vf)) * 1e3
+    us_insert16_foreign = clock.once(lambda: ins_ix.insert_batch(kf, vf)) * 1e3
 
     # ---------------------------------------------------------------- CPU oracle on the same step
     cpu = None
@@ -642,7 +643,7 @@ def main():
         for name in ("n_pages", "Kp", "Vp", "page_fill", "rep"):
             arr = exb[name].cpu().numpy()
             getattr(o, name)[...] = arr.view(np.uint16) if arr.dtype == np.int16 else arr
-        o.n_pages[...] = n_pages               # (the state before the insertions above)
+        o.n_pages[...] = n_pages
         o.page_fill[...] = fill
         qn = q_np.reshape(L * H, G, D)
         threads = orc.num_threads()
