@@ -265,6 +265,30 @@ def compact_config(name, torch, dev, clock, args, stream_data=None):
             staged["three_levels"] = {"n_top": n_top, "n_probe_top": n_probe_top, "n_probe": n_probe, "us_per_step": ms_3 * 1e3,
                                       "recall_of_flat_selection": rec3, "build_top_level_us": t_top * 1e3}
         staged["flat_flush_per_step_us"] = ms_flush * 1e3
+        if name == "cfg3":
+            # The same shapes on a nested mixture (the centres gather around 64 points): data with structure
+            # above the clusters, which is what a third level can summarise; the plain mixture has none.
+            wn = dataclasses.replace(w, n_super=64, super_spread=0.4, outlier_frac=0.0, seed=w.seed + 7)
+            Kn_np, Vn_np = datagen.keys_values(wn, workers=16)
+            Kn, Vn = torch.from_numpy(Kn_np.view(np.int16)).to(dev), torch.from_numpy(Vn_np.view(np.int16)).to(dev)
+            qn = torch.from_numpy(datagen.queries(wn).view(np.int16)).to(dev)
+            nix = IceIndex(B, H, G, max_tokens, s, C, kmeans_iters=T, init_idx=torch.from_numpy(datagen.init_indices(wn)).to(dev), device=dev)
+            nix.build_index(Kn, Vn)
+            nix.build_top_level(n_top, 3)
+            ids_f, ns_f = torch.empty_like(ids), torch.empty_like(ns)
+            ms_nf = clock.per_step(lambda: nix.select_attend(qn, budget, ids_f, ns_f, out_h), args.steps, args.warmup, True)
+            ms_n2 = clock.per_step(lambda: binding.ice_select_hier(nix.handle, qn, budget, n_probe, ids_h, ns_h, None, None, out_h),
+                                   args.steps, args.warmup, True)
+            ids_2 = ids_h.cpu().numpy().reshape(U, P).copy()
+            ms_n3 = clock.per_step(lambda: binding.ice_select_hier3(nix.handle, qn, budget, n_probe_top, n_probe, ids_h, ns_h, None, None,
+                                                                     None, out_h), args.steps, args.warmup, True)
+            idf, nsf = ids_f.cpu().numpy().reshape(U, P), ns_f.cpu().numpy().reshape(U)
+            recall = lambda got: float(np.mean([len(np.intersect1d(got[u2, :nsf[u2]], idf[u2, :nsf[u2]])) / max(1, nsf[u2]) for u2 in range(U)]))
+            staged["on_nested_mixture"] = {
+                "data": "the same shapes, centres ~ one of 64 points + 0.4 N(0, I) instead of N(0, I)",
+                "flat_us_per_step": ms_nf * 1e3, "two_levels_us_per_step": ms_n2 * 1e3, "two_levels_recall": recall(ids_2),
+                "three_levels_us_per_step": ms_n3 * 1e3, "three_levels_recall": recall(ids_h.cpu().numpy().reshape(U, P))}
+            del nix, Kn, Vn
         res["staged_search"] = staged
     except binding.IceError as e:
         res["staged_search"] = {"unsupported": str(e)}

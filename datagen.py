@@ -41,6 +41,8 @@ class Workload:
     decode_steps: int = 0    # > 0: long-generation loop
     drift: float = 0.0       # per-step, per-coordinate std of the centre drift
     seed: int = 1
+    n_super: int = 0         # > 0: nested mixture, the centres themselves gather around n_super points
+    super_spread: float = 0.0  # per-coordinate std of a centre around its point
 
 
 # The five workloads of the benchmark definition.  n_clusters of configs 4 and 5
@@ -78,7 +80,13 @@ def centres(w: Workload, seed: int | None = None) -> np.ndarray:
     out = np.empty((w.batch, w.n_kv_heads, w.n_components, D), dtype=np.float32)
     for b in range(w.batch):
         for h in range(w.n_kv_heads):
-            out[b, h] = _rng(seed, b, h, 0).standard_normal((w.n_components, D), dtype=np.float32)
+            r = _rng(seed, b, h, 0)
+            if w.n_super > 0:   # structure above the centres: what a level above the clusters can summarise
+                sup = r.standard_normal((w.n_super, D), dtype=np.float32)
+                out[b, h] = sup[r.integers(0, w.n_super, size=w.n_components)] + np.float32(w.super_spread) * r.standard_normal(
+                    (w.n_components, D), dtype=np.float32)
+            else:
+                out[b, h] = r.standard_normal((w.n_components, D), dtype=np.float32)
     return out
 
 

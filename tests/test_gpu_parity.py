@@ -567,6 +567,7 @@ def test_hier_select_argument_errors():
     (dict(n_tokens=4000, n_clusters=200, n_kv_heads=2, n_components=100, drift=0.01), 16, "own"),      # mostly one token per cluster: the guesses stand
     (dict(n_tokens=6000, n_clusters=1500, n_kv_heads=1, n_components=64), 16, "own"),                  # many clusters: fewer tokens per launch, one staging tile per wave
     (dict(n_tokens=1500, n_clusters=20, n_kv_heads=2, n_components=10), 16, "same"),                   # 16 copies of one key: one cluster, pages overflow inside a launch
+    (dict(n_tokens=2500, n_clusters=64, n_kv_heads=2, n_components=32, drift=0.01), 17, "own"),         # a launch of 16 and a launch of one
 ])
 def test_insert_batch_equals_one_by_one(kw, m, mode):
     """m tokens in one launch leave the index bit for bit as m single insertions do (each token sees
