@@ -335,6 +335,7 @@ def test_imported_oracle_index_select_attend():
 @pytest.mark.parametrize("kw,steps", [
     (dict(n_tokens=2000, n_clusters=24, n_kv_heads=2, n_components=16, drift=0.01), 300),
     (dict(n_tokens=600, n_clusters=5, n_kv_heads=3, page_size=32, n_components=4, drift=0.02), 200),
+    (dict(n_tokens=6000, n_clusters=700, n_kv_heads=1, n_components=64, drift=0.01), 60),   # the scan takes two rounds of tiles per wave
 ])
 def test_insert_replay_is_bit_exact(kw, steps):
     """The oracle starts from the exported post-build state and replays every insertion; all tables
@@ -568,6 +569,7 @@ def test_hier_select_argument_errors():
     (dict(n_tokens=6000, n_clusters=1500, n_kv_heads=1, n_components=64), 16, "own"),                  # many clusters: fewer tokens per launch, one staging tile per wave
     (dict(n_tokens=1500, n_clusters=20, n_kv_heads=2, n_components=10), 16, "same"),                   # 16 copies of one key: one cluster, pages overflow inside a launch
     (dict(n_tokens=2500, n_clusters=64, n_kv_heads=2, n_components=32, drift=0.01), 17, "own"),         # a launch of 16 and a launch of one
+    (dict(n_tokens=9000, n_clusters=4500, n_kv_heads=1, n_components=64), 6, "own"),                   # two tokens per launch; the one-token scan takes nine rounds of tiles
 ])
 def test_insert_batch_equals_one_by_one(kw, m, mode):
     """m tokens in one launch leave the index bit for bit as m single insertions do (each token sees
