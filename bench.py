@@ -175,6 +175,9 @@ def clustering_block(torch, clock, ix, K, V, T, build_ms, n, C, U):
         "means_GBps": kv_bytes / (st["means_us"] * 1e-6) / 1e9,
         "paginate_GBps": 4.0 * kv_bytes / (st["paginate_us"] * 1e-6) / 1e9,
         "paginate_frac_of_hbm_peak": 4.0 * kv_bytes / (st["paginate_us"] * 1e-6) / 1e9 / HBM_PEAK_GBPS,
+        # what the build spends outside the timed stages: promotion of the initial centroids, the tail copies kept for
+        # the insertions, resets, and the gaps between the launches (build time minus rounds and paginate)
+        "init_and_rest_us": build_ms * 1e3 - T * round_us - st["paginate_us"],
         "how": "every stage re-run by itself on the built index (ice_debug_rerun_stage) between two events; assign counts "
                "2 n C d flop per unit; a round = assign + sort + means; means reads the keys once more (n d 2 B per unit), "
                "paginate reads K and V and writes both page tiles (4 n d 2 B per unit)",
