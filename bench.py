@@ -180,7 +180,8 @@ def clustering_block(torch, clock, ix, K, V, T, build_ms, n, C, U):
         "init_and_rest_us": build_ms * 1e3 - T * round_us - st["paginate_us"],
         "how": "every stage re-run by itself on the built index (ice_debug_rerun_stage) between two events; assign counts "
                "2 n C d flop per unit; a round = assign + sort + means; means reads the keys once more (n d 2 B per unit), "
-               "paginate reads K and V and writes both page tiles (4 n d 2 B per unit)",
+               "paginate reads K and V and writes both page tiles (4 n d 2 B per unit); init_and_rest_us = build - rounds - "
+               "paginate (negative where the stages run faster inside the build, with the keys still cached, than alone)",
     }
 
 
