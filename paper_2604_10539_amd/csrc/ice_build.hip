@@ -9,6 +9,7 @@ namespace ice {
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef unsigned long long u64;
 typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
 // a.lo*b.lo + a.hi*b.hi + c on packed bf16 pairs, fp32 accumulate (v_dot2_f32_bf16)
@@ -933,8 +934,9 @@ void launch_paginate(const Dev &d, const bf16_t *K, const bf16_t *V, int n, hipS
 // Lloyd iteration over the unit's C bf16 centroids as points, one workgroup per unit:
 //   promote  top node t starts at the centroid in the middle of the t-th of n_top equal strata of the
 //            cluster ids;
-//   assign   every cluster to the nearest top node: ||t~||^2 - 2 c . t~ in fp32 against the nodes'
-//            bf16 rounding held in LDS, lowest id on ties;
+//   assign   every cluster to the nearest top node: ||t~||^2 - 2 c . t~, fp32 accumulate on the matrix cores
+//            (16 clusters x 16 nodes per v_mfma_f32_16x16x32_bf16 chain) against the nodes' bf16 rounding held
+//            in LDS, lowest id on ties;
 //   means    the clusters of a node are listed in ascending id (one wave per node walks the
 //            assignment with lane masks) and summed in that order in fp32, four dimensions per thread;
 //            an empty node keeps its position.
@@ -974,25 +976,58 @@ __global__ __launch_bounds__(1024) void top_level_kernel(Dev d, const bf16_t *__
             norm[t] = nn;
         }
         __syncthreads();
-        // assign: a thread per cluster, the node rows broadcast from LDS
-        for (int c = tid; c < C; c += 1024) {
-            uint4 pt[16];
+        // assign on the matrix cores: a wave takes 16 clusters at a time as the columns of the B operand (lane
+        // (g, n): dims [32 ks + 8 g, +8) of cluster n) and walks the nodes 16 at a time as the rows of A, read from
+        // LDS; lane (g, n) ends with nodes 4g .. 4g+3 of the tile against cluster n and keeps the best, lowest node
+        // id on ties; the four row groups meet by lane exchange
+        {
+            const int g = lane >> 4, i16 = lane & 15;
+            const int ptiles = (C + 15) >> 4, ntiles = (n_top + 15) >> 4;
+            auto cluster_rows = [&](int pt, uint4 (&b)[4]) {
+                const int c = pt * 16 + i16;
 #pragma unroll
-            for (int ch = 0; ch < 16; ++ch) pt[ch] = ((const uint4 *)(pts + (size_t)c * kD))[ch];
-            float bv = INFINITY;
-            int bi = 0;
-            for (int t = 0; t < n_top; ++t) {
-                float dot = 0.f;
-#pragma unroll
-                for (int ch = 0; ch < 16; ++ch) {
-                    const uint4 w = rows[t * 16 + ch];
-                    dot = dot2(pt[ch].w, w.w, dot2(pt[ch].z, w.z, dot2(pt[ch].y, w.y, dot2(pt[ch].x, w.x, dot))));
+                for (int ks = 0; ks < 4; ++ks) {
+                    b[ks] = make_uint4(0, 0, 0, 0);
+                    if (c < C) b[ks] = ((const uint4 *)(pts + (size_t)c * kD))[ks * 4 + g];
                 }
-                const float val = norm[t] - 2.0f * dot;
-                if (val < bv) { bv = val; bi = t; }
+            };
+            uint4 b[4], bn[4];
+            if (wave < ptiles) cluster_rows(wave, b);
+            for (int pt = wave; pt < ptiles; pt += 16) {
+                const int c = pt * 16 + i16;
+                if (pt + 16 < ptiles) cluster_rows(pt + 16, bn);  // (the next tile's rows are on their way during this one)
+                u64 best = ~0ull;
+                for (int nt = 0; nt < ntiles; ++nt) {
+                    const int node_a = nt * 16 + i16;
+                    f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+                    for (int ks = 0; ks < 4; ++ks) {
+                        uint4 a = make_uint4(0, 0, 0, 0);
+                        if (node_a < n_top) a = rows[node_a * 16 + ks * 4 + g];
+                        acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, a), __builtin_bit_cast(bf16x8, b[ks]), acc, 0, 0, 0);
+                    }
+#pragma unroll
+                    for (int j = 0; j < 4; ++j) {
+                        const int node = nt * 16 + 4 * g + j;
+                        const float val = __builtin_fmaf(-2.0f, acc[j], node < n_top ? norm[node] : INFINITY);
+                        if (node < n_top && !(val != val)) {
+                            const u64 key = ((u64)f32_ordered(val) << 32) | (u64)(uint32_t)node;
+                            best = key < best ? key : best;
+                        }
+                    }
+                }
+                u64 o = __shfl_xor(best, 16);
+                best = o < best ? o : best;
+                o = __shfl_xor(best, 32);
+                best = o < best ? o : best;
+                if (g == 0 && c < C) {
+                    const int bi = best == ~0ull ? 0 : (int)(uint32_t)best;
+                    asg[c] = bi;
+                    d.top_of[(size_t)u * C + c] = bi;
+                }
+#pragma unroll
+                for (int ks = 0; ks < 4; ++ks) b[ks] = bn[ks];
             }
-            asg[c] = bi;
-            d.top_of[(size_t)u * C + c] = bi;
         }
         __syncthreads();
         // list the clusters of every node in ascending id: counts, starts, then placement
@@ -1022,9 +1057,17 @@ __global__ __launch_bounds__(1024) void top_level_kernel(Dev d, const bf16_t *__
             const int t = x >> 5, qd = x & 31;
             const int lo = start[t], cnt = start[t + 1] - lo;
             float a0 = 0.f, a1 = 0.f, a2 = 0.f, a3 = 0.f;
-            for (int i = 0; i < cnt; ++i) {
-                const uint2 w = ((const uint2 *)(pts + (size_t)members[lo + i] * kD))[qd];
-                a0 += bf16_lo(w.x); a1 += bf16_hi(w.x); a2 += bf16_lo(w.y); a3 += bf16_hi(w.y);
+            constexpr int MB = 32;  // rows requested at once (the sum itself stays in list order)
+            for (int i0 = 0; i0 < cnt; i0 += MB) {
+                uint2 w[MB];
+#pragma unroll
+                for (int x = 0; x < MB; ++x) {
+                    w[x] = make_uint2(0u, 0u);
+                    if (i0 + x < cnt) w[x] = ((const uint2 *)(pts + (size_t)members[lo + i0 + x] * kD))[qd];
+                }
+#pragma unroll
+                for (int x = 0; x < MB; ++x)
+                    if (i0 + x < cnt) { a0 += bf16_lo(w[x].x); a1 += bf16_hi(w[x].x); a2 += bf16_lo(w[x].y); a3 += bf16_hi(w[x].y); }
             }
             float *dst = tc + (size_t)t * kD + qd * 4;
             if (cnt > 0) {
